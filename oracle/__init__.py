@@ -1,0 +1,209 @@
+"""fp64 CPU oracle of the structured-tensor kernels -- TEST INFRASTRUCTURE.
+
+Thin ctypes wrapper over ``st_oracle.c`` (plain C, dense definitions, its own
+index enumeration by counting loops).  Only tests, the smoke check and the
+benchmark's CPU-baseline leg may import this package; the product never does.
+It imports nothing from the GPU package.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+from .build import LIB, build
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB):
+            build()
+        _lib = C.CDLL(LIB)
+        i64, p = C.c_int64, C.c_void_p
+        sig = {
+            "so_enum_sym2": (i64, [i64, p]),
+            "so_enum_sym3": (i64, [i64, p]),
+            "so_count_sym4": (i64, [i64]),
+            "so_enum_band": (i64, [i64, i64, p]),
+            "so_list_sym2": (i64, [i64, p]),
+            "so_list_sym3": (i64, [i64, p]),
+            "so_list_band": (i64, [i64, i64, p]),
+            "so_dense_sym3": (None, [p, i64, p]),
+            "so_dense_utri": (None, [p, i64, p]),
+            "so_dense_band": (None, [p, i64, i64, i64, p]),
+            "so_mttkrp_sym3": (None, [p, p, i64, i64, p, i64, p]),
+            "so_batax_utri": (None, [p, p, i64, C.c_double, p]),
+            "so_ttm_dense": (None, [p, p, i64, i64, i64, i64, p]),
+            "so_ttm_band": (None, [p, p, i64, i64, i64, i64, p]),
+            "so_moment3_dense": (None, [p, i64, i64, p]),
+            "so_moment3_entries": (None, [p, i64, i64, p, i64, p]),
+            "so_expand_sym": (C.c_int, [p, i64, C.c_int, p]),
+        }
+        for name, (res, args) in sig.items():
+            f = getattr(_lib, name)
+            f.restype, f.argtypes = res, args
+    return _lib
+
+
+def _f32(a):
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    return a, a.ctypes.data
+
+
+# ---- enumeration ---------------------------------------------------------
+def count_sym2(n):
+    return int(lib().so_enum_sym2(n, None))
+
+
+def count_sym3(n):
+    return int(lib().so_enum_sym3(n, None))
+
+
+def count_sym4(n):
+    return int(lib().so_count_sym4(n))
+
+
+def count_band(n, w):
+    return int(lib().so_enum_band(n, w, None))
+
+
+def table_sym2(n):
+    tab = np.empty((n, n), dtype=np.int64)
+    lib().so_enum_sym2(n, tab.ctypes.data)
+    return tab
+
+
+def table_sym3(n):
+    tab = np.empty((n, n, n), dtype=np.int64)
+    lib().so_enum_sym3(n, tab.ctypes.data)
+    return tab
+
+
+def table_band(n, w):
+    tab = np.empty((n, n), dtype=np.int64)
+    lib().so_enum_band(n, w, tab.ctypes.data)
+    return tab
+
+
+def list_sym2(n):
+    out = np.empty((count_sym2(n), 2), dtype=np.int32)
+    lib().so_list_sym2(n, out.ctypes.data)
+    return out
+
+
+def list_sym3(n):
+    out = np.empty((count_sym3(n), 3), dtype=np.int16)
+    lib().so_list_sym3(n, out.ctypes.data)
+    return out
+
+
+def list_band(n, w):
+    out = np.empty((count_band(n, w), 2), dtype=np.int32)
+    lib().so_list_band(n, w, out.ctypes.data)
+    return out
+
+
+# ---- dense materialisation -------------------------------------------------
+def dense_sym3(Tc, n):
+    Tc, pT = _f32(Tc)
+    assert Tc.size == count_sym3(n)
+    T = np.empty((n, n, n), dtype=np.float64)
+    lib().so_dense_sym3(pT, n, T.ctypes.data)
+    return T
+
+
+def dense_utri(Ap, n):
+    Ap, pA = _f32(Ap)
+    assert Ap.size == count_sym2(n)
+    A = np.empty((n, n), dtype=np.float64)
+    lib().so_dense_utri(pA, n, A.ctypes.data)
+    return A
+
+
+def dense_band(Tc, n, w, nl):
+    Tc, pT = _f32(Tc)
+    assert Tc.size == count_band(n, w) * nl
+    T = np.empty((n, n, nl), dtype=np.float64)
+    lib().so_dense_band(pT, n, w, nl, T.ctypes.data)
+    return T
+
+
+# ---- the five operations -----------------------------------------------------
+def mttkrp_sym3(Tc, B, rows=None):
+    """M(i,r) = sum_jk T(i,j,k) B(j,r) B(k,r); optional subset of rows."""
+    B, pB = _f32(B)
+    n, R = B.shape
+    Tc, pT = _f32(Tc)
+    assert Tc.size == count_sym3(n)
+    if rows is None:
+        M = np.empty((n, R), dtype=np.float64)
+        lib().so_mttkrp_sym3(pT, pB, n, R, None, n, M.ctypes.data)
+    else:
+        rows = np.ascontiguousarray(rows, dtype=np.int64)
+        assert rows.size == 0 or (rows.min() >= 0 and rows.max() < n)
+        M = np.empty((rows.size, R), dtype=np.float64)
+        lib().so_mttkrp_sym3(pT, pB, n, R, rows.ctypes.data, rows.size, M.ctypes.data)
+    return M
+
+
+def batax_utri(Ap, x, beta):
+    x, px = _f32(x)
+    n = x.size
+    Ap, pA = _f32(Ap)
+    assert Ap.size == count_sym2(n)
+    y = np.empty(n, dtype=np.float64)
+    lib().so_batax_utri(pA, px, n, float(beta), y.ctypes.data)
+    return y
+
+
+def ttm_dense(Tc, U, n, w):
+    U, pU = _f32(U)
+    nl, R = U.shape
+    Tc, pT = _f32(Tc)
+    assert Tc.size == count_band(n, w) * nl
+    Y = np.empty((n, n, R), dtype=np.float64)
+    lib().so_ttm_dense(pT, pU, n, w, nl, R, Y.ctypes.data)
+    return Y
+
+
+def ttm_band(Tc, U, n, w):
+    U, pU = _f32(U)
+    nl, R = U.shape
+    Tc, pT = _f32(Tc)
+    nb = count_band(n, w)
+    assert Tc.size == nb * nl
+    Yc = np.empty((nb, R), dtype=np.float64)
+    lib().so_ttm_band(pT, pU, n, w, nl, R, Yc.ctypes.data)
+    return Yc
+
+
+def moment3_dense(X):
+    X, pX = _f32(X)
+    N, n = X.shape
+    S = np.empty((n, n, n), dtype=np.float64)
+    lib().so_moment3_dense(pX, N, n, S.ctypes.data)
+    return S
+
+
+def moment3_entries(X, ijk):
+    X, pX = _f32(X)
+    N, n = X.shape
+    ijk = np.ascontiguousarray(ijk, dtype=np.int32).reshape(-1, 3)
+    assert ijk.size == 0 or (ijk.min() >= 0 and ijk.max() < n)
+    out = np.empty(ijk.shape[0], dtype=np.float64)
+    lib().so_moment3_entries(pX, N, n, ijk.ctypes.data, ijk.shape[0], out.ctypes.data)
+    return out
+
+
+def expand_sym(Sc, n, order):
+    Sc, pS = _f32(Sc)
+    assert order in (2, 3)
+    assert Sc.size == (count_sym2(n) if order == 2 else count_sym3(n))
+    S = np.empty((n,) * order, dtype=np.float32)
+    rc = lib().so_expand_sym(pS, n, order, S.ctypes.data)
+    assert rc == 0
+    return S

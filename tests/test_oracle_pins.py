@@ -1,0 +1,281 @@
+"""Pins for the CPU oracle: every oracle function is checked against something
+other than itself -- values the paper prints, closed forms, library routines on
+independently built dense tensors, special cases and invariants."""
+import itertools
+import math
+import os
+
+import numpy as np
+import pytest
+
+import st_workloads as W
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden", "paper_counts.txt")
+
+
+def golden():
+    out = {}
+    with open(GOLD) as f:
+        for line in f:
+            line = line.split("#")[0].split()
+            if len(line) == 2:
+                out[line[0]] = int(line[1])
+    return out
+
+
+# ------------------------------------------------------------------ counts
+def test_counts_closed_forms(oracle):
+    for n in list(range(0, 41)) + [64, 100]:
+        assert oracle.count_sym2(n) == math.comb(n + 1, 2)
+        assert oracle.count_sym3(n) == math.comb(n + 2, 3)
+    for n in range(0, 25):
+        assert oracle.count_sym4(n) == math.comb(n + 3, 4)
+    assert oracle.count_sym3(512) == 22_500_864
+    assert oracle.count_sym3(64) == 45_760
+    assert oracle.count_sym2(8192) == 33_558_528
+    assert oracle.count_sym2(64) == 2_080
+
+
+def test_counts_paper_values(oracle):
+    g = golden()
+    n = 4
+    assert n + n * n == g["pr2_matrix_dim_n4"]
+    assert (oracle.count_sym2(n) + oracle.count_sym3(n) + oracle.count_sym4(n)
+            == g["pr2_distinct_elements_n4"])
+    n = 400
+    r3 = (n ** 3 - oracle.count_sym3(n)) / oracle.count_sym3(n)
+    assert abs(r3 - g["m2_redundant_over_unique"]) < 0.05
+    n = 120
+    r4 = (n ** 4 - oracle.count_sym4(n)) / oracle.count_sym4(n)
+    assert abs(r4 - g["m3_redundant_over_unique"]) < 1.2 and r4 < 23
+    n = 2000
+    assert abs(n * n / oracle.count_sym2(n) - g["utri_fraction_inverse"]) < 0.01
+
+
+def test_band_counts(oracle):
+    for n in (1, 2, 5, 9, 33):
+        assert oracle.count_band(n, 0) == n
+        assert oracle.count_band(n, n - 1) == n * n
+        assert oracle.count_band(n, n + 7) == n * n
+        for w in range(0, n):
+            i, j = np.indices((n, n))
+            assert oracle.count_band(n, w) == int((np.abs(i - j) <= w).sum())
+    assert oracle.count_band(512, 8) == 8_632
+
+
+# -------------------------------------------------------------- enumeration
+@pytest.mark.parametrize("n", [1, 2, 3, 7, 16, 21])
+def test_sym_tables_are_lexicographic(oracle, n):
+    combos3 = list(itertools.combinations_with_replacement(range(n), 3))
+    tab3 = oracle.table_sym3(n)
+    lst3 = oracle.list_sym3(n)
+    assert lst3.shape == (len(combos3), 3)
+    assert [tuple(int(v) for v in t) for t in lst3] == combos3
+    for p, (i, j, k) in enumerate(combos3):
+        assert tab3[i, j, k] == p
+    assert int((tab3 >= 0).sum()) == len(combos3)
+    combos2 = list(itertools.combinations_with_replacement(range(n), 2))
+    tab2 = oracle.table_sym2(n)
+    assert [tuple(int(v) for v in t) for t in oracle.list_sym2(n)] == combos2
+    for p, (i, j) in enumerate(combos2):
+        assert tab2[i, j] == p
+    assert int((tab2 >= 0).sum()) == len(combos2)
+    # numpy's own row-major upper-triangle order is the same packing
+    iu = np.triu_indices(n)
+    assert np.array_equal(tab2[iu], np.arange(len(combos2)))
+
+
+@pytest.mark.parametrize("n,w", [(1, 0), (4, 0), (4, 1), (7, 2), (7, 6), (12, 3), (12, 20)])
+def test_band_table(oracle, n, w):
+    i, j = np.indices((n, n))
+    mask = np.abs(i - j) <= w
+    expect = np.argwhere(mask)              # row-major order
+    got = oracle.list_band(n, w)
+    assert np.array_equal(got, expect)
+    tab = oracle.table_band(n, w)
+    assert np.array_equal(tab[mask], np.arange(expect.shape[0]))
+    assert np.all(tab[~mask] == -1)
+
+
+# ---------------------------------------------------------- materialisation
+def _dense_sym3_numpy(Tc, n):
+    T = np.zeros((n, n, n))
+    for p, (i, j, k) in enumerate(itertools.combinations_with_replacement(range(n), 3)):
+        for a, b, c in set(itertools.permutations((i, j, k))):
+            T[a, b, c] = float(Tc[p])
+    return T
+
+
+@pytest.mark.parametrize("n", [1, 3, 6, 9])
+def test_dense_sym3(oracle, n):
+    Tc = W.uniform(11, math.comb(n + 2, 3))
+    T = oracle.dense_sym3(Tc, n)
+    assert np.array_equal(T, _dense_sym3_numpy(Tc, n))
+    for perm in itertools.permutations(range(3)):
+        assert np.array_equal(T, np.transpose(T, perm))
+
+
+# --------------------------------------------------------------------- mttkrp
+@pytest.mark.parametrize("n,R", [(1, 1), (2, 3), (5, 4), (8, 16), (13, 5)])
+def test_mttkrp_against_einsum(oracle, n, R):
+    Tc = W.uniform(21, math.comb(n + 2, 3))
+    B = W.uniform(22, n * R).reshape(n, R)
+    T = _dense_sym3_numpy(Tc, n)
+    ref = np.einsum("ijk,jr,kr->ir", T, B.astype(np.float64), B.astype(np.float64))
+    got = oracle.mttkrp_sym3(Tc, B)
+    assert np.allclose(got, ref, rtol=1e-13, atol=1e-13)
+    # mode invariance: contracting modes (1,3) or (1,2) gives the same M
+    ref2 = np.einsum("jik,jr,kr->ir", T, B.astype(np.float64), B.astype(np.float64))
+    assert np.allclose(got, ref2, rtol=1e-13, atol=1e-13)
+    rows = np.array([n - 1, 0, n // 2])
+    assert np.array_equal(oracle.mttkrp_sym3(Tc, B, rows=rows), got[rows])
+
+
+def test_mttkrp_special_cases(oracle):
+    n, R = 9, 4
+    B = W.uniform(31, n * R).reshape(n, R).astype(np.float64)
+    ones = np.ones(math.comb(n + 2, 3), dtype=np.float32)
+    M = oracle.mttkrp_sym3(ones, B)
+    assert np.allclose(M, np.tile(B.sum(axis=0) ** 2, (n, 1)), rtol=1e-13)
+    # rank one: T = a (x) a (x) a  =>  M(i,r) = a_i (a^T b_r)^2, with a exact in fp32
+    a = np.array([1, -2, 0.5, 3, 0, -1, 2, 0.25, -4], dtype=np.float64)
+    lst = oracle.list_sym3(n)
+    Tc = (a[lst[:, 0]] * a[lst[:, 1]] * a[lst[:, 2]]).astype(np.float32)
+    M = oracle.mttkrp_sym3(Tc, B)
+    assert np.allclose(M, np.outer(a, (a @ B) ** 2), rtol=1e-12, atol=1e-12)
+
+
+def test_mttkrp_weight_sum(oracle):
+    # multiplicities of the packed entries (1, 3 or 6 index permutations) add up to n^3:
+    # with B = ones(n,1), sum_i M(i,0) = sum over the full tensor.
+    n = 10
+    Tc = W.uniform(41, math.comb(n + 2, 3))
+    B = np.ones((n, 1), dtype=np.float32)
+    M = oracle.mttkrp_sym3(Tc, B)
+    mult = np.array([len(set(itertools.permutations(t)))
+                     for t in itertools.combinations_with_replacement(range(n), 3)])
+    assert mult.sum() == n ** 3
+    assert np.isclose(M.sum(), float((mult * Tc.astype(np.float64)).sum()), rtol=1e-12)
+
+
+# ---------------------------------------------------------------------- batax
+@pytest.mark.parametrize("n", [1, 2, 5, 33, 100])
+def test_batax_against_numpy(oracle, n):
+    Ap = W.uniform(51, math.comb(n + 1, 2))
+    x = W.uniform(52, n)
+    A = np.zeros((n, n))
+    A[np.triu_indices(n)] = Ap
+    assert np.array_equal(oracle.dense_utri(Ap, n), A)
+    beta = 0.5
+    ref = beta * (A.T @ (A @ x.astype(np.float64)))
+    got = oracle.batax_utri(Ap, x, beta)
+    assert np.allclose(got, ref, rtol=1e-13, atol=1e-13)
+    assert np.isclose(x.astype(np.float64) @ got, beta * np.sum((A @ x.astype(np.float64)) ** 2))
+
+
+def test_batax_special_cases(oracle):
+    n = 17
+    x = W.uniform(53, n)
+    eye = np.zeros((n, n))
+    eye[np.diag_indices(n)] = 1
+    Ap = eye[np.triu_indices(n)].astype(np.float32)
+    assert np.allclose(oracle.batax_utri(Ap, x, 0.75), 0.75 * x.astype(np.float64), rtol=1e-15)
+    ones = np.ones(math.comb(n + 1, 2), dtype=np.float32)
+    t = np.cumsum(x.astype(np.float64)[::-1])[::-1]        # suffix sums
+    y = 2.0 * np.cumsum(t)                                 # prefix sums of t
+    assert np.allclose(oracle.batax_utri(ones, x, 2.0), y, rtol=1e-13, atol=1e-13)
+
+
+# ------------------------------------------------------------------------ ttm
+@pytest.mark.parametrize("n,w,nl,R", [(1, 0, 1, 1), (4, 1, 3, 2), (7, 2, 5, 4), (9, 8, 6, 3), (6, 0, 8, 5)])
+def test_ttm_against_numpy(oracle, n, w, nl, R):
+    i, j = np.indices((n, n))
+    mask = np.abs(i - j) <= w
+    nb = int(mask.sum())
+    Tc = W.uniform(61, nb * nl).reshape(nb, nl)
+    U = W.uniform(62, nl * R).reshape(nl, R)
+    T = np.zeros((n, n, nl))
+    T[mask] = Tc                               # row-major band order
+    assert np.array_equal(oracle.dense_band(Tc, n, w, nl), T)
+    ref = T @ U.astype(np.float64)
+    Y = oracle.ttm_dense(Tc, U, n, w)
+    assert np.allclose(Y, ref, rtol=1e-13, atol=1e-13)
+    assert np.all(Y[~mask] == 0.0)             # output keeps the input's band
+    Yc = oracle.ttm_band(Tc, U, n, w)
+    assert np.array_equal(Yc, Y[mask])
+    if w >= n - 1:                             # no structure left: a plain GEMM
+        assert np.allclose(Yc, Tc.astype(np.float64) @ U.astype(np.float64), rtol=1e-13)
+
+
+def test_ttm_identity_factor(oracle):
+    n, w, nl = 8, 2, 6
+    nb = oracle.count_band(n, w)
+    Tc = W.uniform(63, nb * nl).reshape(nb, nl)
+    Yc = oracle.ttm_band(Tc, np.eye(nl, dtype=np.float32), n, w)
+    assert np.array_equal(Yc, Tc.astype(np.float64))
+
+
+# -------------------------------------------------------------------- moment3
+@pytest.mark.parametrize("N,n", [(1, 1), (1, 5), (7, 4), (50, 9)])
+def test_moment3_against_einsum(oracle, N, n):
+    X = W.normal(71, N * n).reshape(N, n)
+    X64 = X.astype(np.float64)
+    ref = np.einsum("si,sj,sk->ijk", X64, X64, X64)
+    S = oracle.moment3_dense(X)
+    assert np.allclose(S, ref, rtol=1e-13, atol=1e-13)
+    for perm in itertools.permutations(range(3)):
+        assert np.allclose(S, np.transpose(S, perm), rtol=1e-14, atol=1e-14)
+    trip = np.array(list(itertools.product(range(n), repeat=3)), dtype=np.int32)
+    assert np.array_equal(oracle.moment3_entries(X, trip), S.reshape(-1))
+
+
+def test_moment3_special_cases(oracle):
+    n, N = 6, 11
+    X = np.zeros((N, n), dtype=np.float32)
+    X[:, 2] = 1.0
+    S = oracle.moment3_dense(X)
+    assert S[2, 2, 2] == N and np.count_nonzero(S) == 1
+    # N = 1 is the paper's M2 nest: S(i,j,k) = f_i f_j f_k, in dense position [i][j*n+k]
+    f = W.normal(72, n)
+    S = oracle.moment3_dense(f.reshape(1, n))
+    f64 = f.astype(np.float64)
+    M2 = np.outer(f64, np.outer(f64, f64).reshape(-1))
+    assert np.allclose(S.reshape(n, n * n), M2, rtol=1e-15)
+    # sum_p mult(p) * S_C(p) = sum_s (1^T x_s)^3
+    X = W.normal(73, 40 * n).reshape(40, n)
+    lst = oracle.list_sym3(n)
+    Sc = oracle.moment3_entries(X, lst)
+    mult = np.array([len(set(itertools.permutations(tuple(t)))) for t in lst.tolist()])
+    assert np.isclose((mult * Sc).sum(), (X.astype(np.float64).sum(axis=1) ** 3).sum(), rtol=1e-12)
+
+
+def test_cross_kernel_identity(oracle):
+    # mttkrp(moment3(X), B)(i,r) = sum_s x_s(i) (x_s^T b_r)^2, with X small integers so that
+    # the third moments are exact in fp32.
+    n, N, R = 7, 5, 3
+    X = np.round(W.uniform(81, N * n) * 4).reshape(N, n).astype(np.float32)
+    B = W.uniform(82, n * R).reshape(n, R)
+    Sc = oracle.moment3_entries(X, oracle.list_sym3(n)).astype(np.float32)
+    M = oracle.mttkrp_sym3(Sc, B)
+    X64, B64 = X.astype(np.float64), B.astype(np.float64)
+    ref = np.einsum("si,sr->ir", X64, (X64 @ B64) ** 2)
+    assert np.allclose(M, ref, rtol=1e-12, atol=1e-12)
+
+
+# --------------------------------------------------------------------- expand
+@pytest.mark.parametrize("n", [1, 2, 5, 12])
+def test_expand(oracle, n):
+    Sc3 = W.uniform(91, math.comb(n + 2, 3))
+    S = oracle.expand_sym(Sc3, n, 3)
+    assert S.dtype == np.float32
+    idx = np.sort(np.indices((n, n, n)).reshape(3, -1), axis=0)
+    pos = {t: p for p, t in enumerate(itertools.combinations_with_replacement(range(n), 3))}
+    ref = np.array([Sc3[pos[tuple(int(v) for v in idx[:, q])]] for q in range(n ** 3)],
+                   dtype=np.float32).reshape(n, n, n)
+    assert np.array_equal(S.view(np.uint32), ref.view(np.uint32))
+    for perm in itertools.permutations(range(3)):
+        assert np.array_equal(S, np.transpose(S, perm))
+    Sc2 = W.uniform(92, math.comb(n + 1, 2))
+    S2 = oracle.expand_sym(Sc2, n, 2)
+    assert np.array_equal(S2, S2.T)                      # y[i][j] = y[j][i] for j < i
+    assert np.array_equal(S2[np.triu_indices(n)], Sc2)   # unique half is the packed data
