@@ -1,0 +1,152 @@
+/*
+ * structtensor.h -- C ABI of the structured-tensor kernel library for
+ * AMD CDNA4 (gfx950), libstructtensor_hip.so.
+ *
+ * The library evaluates tensor kernels over only the unique, non-zero
+ * iteration space fixed by a tensor's sparsity structure (unique set T_U)
+ * and redundancy structure (redundancy map T_R), and reconstructs redundant
+ * outputs afterwards, as in "Compiling Structured Tensor Algebra"
+ * (StructTensor).  Where the paper leaves a compressed tensor inside a full
+ * n-d array (code generation section), this library stores it PACKED.
+ *
+ * Packed layouts (part of the ABI; 0-based, last index fastest, i.e. the
+ * visiting order of the paper's loop nests, code generation section):
+ *   sym2 : pairs   0<=i<=j<n      (class S / upper-triangular unique set),
+ *          n(n+1)/2 entries, row i holds columns i..n-1.
+ *   sym3 : triples 0<=i<=j<=k<n   ("Tensor Structures": unique elements of a
+ *          degree-3 interaction tensor), n(n+1)(n+2)/6 entries.
+ *   band : pairs |i-j|<=w, 0<=i,j<n, row-major; a band 3-tensor stores one
+ *          contiguous fibre of length nl per in-band pair.
+ *
+ * Conventions for every kernel entry point:
+ *   - all data pointers are DEVICE pointers to contiguous fp32, 16-byte
+ *     aligned (ST_ERR_ALIGN otherwise); dense matrices are row-major;
+ *   - the caller owns every buffer, including the workspace `ws` of at least
+ *     st_<kernel>_workspace(...) bytes (may be NULL when that is 0);
+ *     the library allocates no device memory and keeps no state between calls;
+ *   - inputs and outputs must not overlap;
+ *   - work is enqueued on `stream` (a hipStream_t passed as void*, NULL =
+ *     the default stream) and the call returns without synchronising;
+ *   - arguments are validated on the host before anything is launched: on
+ *     any status other than ST_OK nothing was launched and outputs are
+ *     untouched;
+ *   - results are deterministic: same inputs, same bits (no float atomics).
+ */
+#ifndef STRUCTTENSOR_H
+#define STRUCTTENSOR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int st_status;
+enum {
+    ST_OK = 0,
+    ST_ERR_NULL = 1,        /* a required pointer is NULL                       */
+    ST_ERR_SHAPE = 2,       /* a size is out of range, or buffers alias         */
+    ST_ERR_ALIGN = 3,       /* a device pointer is not 16-byte aligned          */
+    ST_ERR_WORKSPACE = 4,   /* ws is NULL or ws_bytes is below the query        */
+    ST_ERR_LAUNCH = 5,      /* the HIP runtime reported an error at launch      */
+    ST_ERR_UNSUPPORTED = 6  /* valid arguments outside what is implemented      */
+};
+
+/* Static, NUL-terminated description of a status code. */
+const char *st_status_string(st_status s);
+
+/* ---- host-side integer utilities (pure functions, no GPU needed) -------- */
+
+/* Sizes of the unique sets.  n(n+1)/2 is what remains of n^2 for an
+ * upper-triangular / symmetric matrix ("half of the elements", compressed
+ * tensor example); n(n+1)(n+2)/6 is the number of i<=j<=k triples.  w is
+ * clamped to n-1.  Return -1 for n < 0 or w < 0. */
+int64_t st_count_sym2(int64_t n);
+int64_t st_count_sym3(int64_t n);
+int64_t st_count_band(int64_t n, int64_t w);
+
+/* Position of an index tuple in packed storage (closed forms, no tables).
+ * Return -1 if the tuple is outside the unique set. */
+int64_t st_rank_sym2(int64_t n, int64_t i, int64_t j);
+int64_t st_rank_sym3(int64_t n, int64_t i, int64_t j, int64_t k);
+int64_t st_rank_band(int64_t n, int64_t w, int64_t i, int64_t j);
+
+/* Inverse maps.  ST_ERR_SHAPE if p is outside [0, count); ST_ERR_NULL for a
+ * NULL result pointer. */
+st_status st_unrank_sym2(int64_t n, int64_t p, int64_t *i, int64_t *j);
+st_status st_unrank_sym3(int64_t n, int64_t p, int64_t *i, int64_t *j, int64_t *k);
+st_status st_unrank_band(int64_t n, int64_t w, int64_t p, int64_t *i, int64_t *j);
+
+/* Batched inverse maps on the host: tuples of positions p0 .. p0+count-1
+ * written to HOST memory `out` as int32, 2 (sym2, band) or 3 (sym3) per
+ * position. */
+st_status st_unrank_sym2_batch(int64_t n, int64_t p0, int64_t count, int32_t *out);
+st_status st_unrank_sym3_batch(int64_t n, int64_t p0, int64_t count, int32_t *out);
+st_status st_unrank_band_batch(int64_t n, int64_t w, int64_t p0, int64_t count, int32_t *out);
+
+/* The same inverse maps evaluated by the DEVICE code the kernels use (the
+ * kernels turn a flat position into indices with these, instead of masks).
+ * `out` is a DEVICE pointer to 2*count (kind 2: sym2, kind 4: band, with
+ * w) or 3*count (kind 3: sym3) int32.  For checking the device index maps. */
+st_status st_unrank_device(int kind, int64_t n, int64_t w, int64_t p0, int64_t count,
+                           int32_t *out, void *stream);
+
+/* ---- workspace queries (bytes; 0 means ws may be NULL) -------------------- */
+size_t st_mttkrp_sym3_workspace(int n, int R);
+size_t st_batax_utri_workspace(int n);
+size_t st_ttm_band_workspace(int n, int w, int nl, int R);
+size_t st_moment3_sym_workspace(int64_t N, int n);
+
+/* ---- kernels -------------------------------------------------------------- */
+
+/* MTTKRP with a fully symmetric order-3 tensor and equal factors:
+ *     M(i,r) = sum_{j,k} T(i,j,k) * B(j,r) * B(k,r)        0<=i<n, 0<=r<R
+ * (kernel table, MTTKRP row  A(i,j) := B(i,k,l) * C(k,j) * D(l,j)  with
+ * C = D; structure from "Tensor Structures").  Only the unique entries are
+ * read: Tc holds the n(n+1)(n+2)/6 sym3-packed values of T; the sum still
+ * ranges over the FULL symmetric tensor (each stored entry stands for its 1,
+ * 3 or 6 index permutations).  B is n x R, M is n x R, overwritten.
+ * n >= 1, R >= 1. */
+st_status st_mttkrp_sym3(const float *Tc, const float *B, float *M, int n, int R,
+                         void *ws, size_t ws_bytes, void *stream);
+
+/* y = beta * A^T (A x) for an upper-triangular A, A(i,j) = 0 for i > j
+ * (unique set 0<=i<=j<n of the upper-triangular compressed-tensor example;
+ * matrix-vector products as sum-of-products rules).  Ap holds the n(n+1)/2
+ * sym2-packed entries of A, x and y have n entries, y is overwritten.  A is
+ * streamed from memory once.  n >= 1. */
+st_status st_batax_utri(const float *Ap, const float *x, float *y, int n, float beta,
+                        void *ws, size_t ws_bytes, void *stream);
+
+/* Tensor-times-matrix along mode 3 of a band tensor:
+ *     Y(i,j,r) = sum_l T(i,j,l) * U(l,r)   for |i-j| <= w, zero elsewhere
+ * (kernel table, TTM row  A(i,j,k) := B(i,j,l) * C(k,l)  with U(l,r) =
+ * C(r,l); w = 0 is the table's "diagonal plane" structure; the output keeps
+ * the input's unique set by the product and projection inference rules).
+ * Tc is [st_count_band(n,w)][nl], U is nl x R, Yc is
+ * [st_count_band(n,w)][R] in the same band order, overwritten.
+ * n >= 1, w >= 0 (clamped to n-1), nl >= 1, R >= 1. */
+st_status st_ttm_band(const float *Tc, const float *U, float *Yc, int n, int w, int nl,
+                      int R, void *ws, size_t ws_bytes, void *stream);
+
+/* Third-moment (degree-3 interaction) accumulation over N samples:
+ *     Sc(rank3(i,j,k)) (+)= sum_s X(s,i) * X(s,j) * X(s,k)    for i<=j<=k
+ * (the M2 = f (x) vec(f (x) f) term of the degree-2 polynomial-regression
+ * covariance, summed over the data: "creation and addition of covariance
+ * matrices").  X is N x n row-major.  accumulate = 0 overwrites Sc, 1 adds to
+ * it.  Raw sums: no 1/N, no centring.  N >= 0 (N = 0 zero-fills when
+ * accumulate = 0), n >= 1. */
+st_status st_moment3_sym(const float *X, int64_t N, int n, float *Sc, int accumulate,
+                         void *ws, size_t ws_bytes, void *stream);
+
+/* Reconstruction through the redundancy map (Property 5:
+ * T(x) = T_C(x) + T_R(x,x') * T_C(x')).  order 2: S(i,j) = Sc[rank2(min,max)]
+ * (class S: i' = j, j' = i for j < i); order 3: S(i,j,k) = Sc[rank3(sorted
+ * triple)].  S is the dense n^order array, overwritten.  A bit-exact copy. */
+st_status st_expand_sym(const float *Sc, float *S, int n, int order, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* STRUCTTENSOR_H */

@@ -1,0 +1,31 @@
+"""MI355X-native structured-tensor kernels (StructTensor hot path).
+
+Thin Python binding over the C ABI of ``libstructtensor_hip.so`` (see
+``include/structtensor.h``): argument marshalling only.  PyTorch is used for
+device memory and streams; every step of the computation runs in the HIP
+kernels.  There is no CPU fallback: if the library cannot be loaded, importing
+the binding's functions raises.
+"""
+from .binding import (  # noqa: F401
+    StructTensorError,
+    count_band,
+    count_sym2,
+    count_sym3,
+    expand_sym,
+    batax_utri,
+    lib,
+    moment3_sym,
+    mttkrp_sym3,
+    rank_band,
+    rank_sym2,
+    rank_sym3,
+    ttm_band,
+    unrank_band,
+    unrank_band_batch,
+    unrank_device,
+    unrank_sym2,
+    unrank_sym2_batch,
+    unrank_sym3,
+    unrank_sym3_batch,
+    workspace_bytes,
+)

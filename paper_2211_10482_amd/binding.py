@@ -1,0 +1,222 @@
+"""ctypes binding of libstructtensor_hip.so: same names as the C ABI, argument
+marshalling only (pointers, sizes, the current torch stream, a torch-allocated
+workspace)."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libstructtensor_hip.so")
+
+_lib = None
+
+
+class StructTensorError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__("%s failed: status %d (%s)" % (what, status, _status_string(status)))
+
+
+# names and signatures of include/structtensor.h
+_I64, _I32, _P, _SZ, _F = C.c_int64, C.c_int, C.c_void_p, C.c_size_t, C.c_float
+SIGNATURES = {
+    "st_status_string": (C.c_char_p, [_I32]),
+    "st_count_sym2": (_I64, [_I64]),
+    "st_count_sym3": (_I64, [_I64]),
+    "st_count_band": (_I64, [_I64, _I64]),
+    "st_rank_sym2": (_I64, [_I64, _I64, _I64]),
+    "st_rank_sym3": (_I64, [_I64, _I64, _I64, _I64]),
+    "st_rank_band": (_I64, [_I64, _I64, _I64, _I64]),
+    "st_unrank_sym2": (_I32, [_I64, _I64, _P, _P]),
+    "st_unrank_sym3": (_I32, [_I64, _I64, _P, _P, _P]),
+    "st_unrank_band": (_I32, [_I64, _I64, _I64, _P, _P]),
+    "st_unrank_sym2_batch": (_I32, [_I64, _I64, _I64, _P]),
+    "st_unrank_sym3_batch": (_I32, [_I64, _I64, _I64, _P]),
+    "st_unrank_band_batch": (_I32, [_I64, _I64, _I64, _I64, _P]),
+    "st_unrank_device": (_I32, [_I32, _I64, _I64, _I64, _I64, _P, _P]),
+    "st_mttkrp_sym3_workspace": (_SZ, [_I32, _I32]),
+    "st_batax_utri_workspace": (_SZ, [_I32]),
+    "st_ttm_band_workspace": (_SZ, [_I32, _I32, _I32, _I32]),
+    "st_moment3_sym_workspace": (_SZ, [_I64, _I32]),
+    "st_mttkrp_sym3": (_I32, [_P, _P, _P, _I32, _I32, _P, _SZ, _P]),
+    "st_batax_utri": (_I32, [_P, _P, _P, _I32, _F, _P, _SZ, _P]),
+    "st_ttm_band": (_I32, [_P, _P, _P, _I32, _I32, _I32, _I32, _P, _SZ, _P]),
+    "st_moment3_sym": (_I32, [_P, _I64, _I32, _P, _I32, _P, _SZ, _P]),
+    "st_expand_sym": (_I32, [_P, _P, _I32, _I32, _P]),
+}
+
+
+def lib():
+    """Load the HIP library (built in-tree by ``build.py``).  No fallback."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(
+                "libstructtensor_hip.so is not built: run `python -m paper_2211_10482_amd.build` "
+                "(there is no CPU fallback)")
+        _lib = C.CDLL(LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            f = getattr(_lib, name)
+            f.restype, f.argtypes = res, args
+    return _lib
+
+
+def _status_string(status: int) -> str:
+    return lib().st_status_string(status).decode()
+
+
+def _check(status: int, what: str):
+    if status != 0:
+        raise StructTensorError(status, what)
+
+
+# ---- host index utilities --------------------------------------------------------
+def count_sym2(n): return int(lib().st_count_sym2(n))
+def count_sym3(n): return int(lib().st_count_sym3(n))
+def count_band(n, w): return int(lib().st_count_band(n, w))
+def rank_sym2(n, i, j): return int(lib().st_rank_sym2(n, i, j))
+def rank_sym3(n, i, j, k): return int(lib().st_rank_sym3(n, i, j, k))
+def rank_band(n, w, i, j): return int(lib().st_rank_band(n, w, i, j))
+
+
+def unrank_sym2(n, p):
+    i, j = _I64(), _I64()
+    _check(lib().st_unrank_sym2(n, p, C.byref(i), C.byref(j)), "st_unrank_sym2")
+    return i.value, j.value
+
+
+def unrank_sym3(n, p):
+    i, j, k = _I64(), _I64(), _I64()
+    _check(lib().st_unrank_sym3(n, p, C.byref(i), C.byref(j), C.byref(k)), "st_unrank_sym3")
+    return i.value, j.value, k.value
+
+
+def unrank_band(n, w, p):
+    i, j = _I64(), _I64()
+    _check(lib().st_unrank_band(n, w, p, C.byref(i), C.byref(j)), "st_unrank_band")
+    return i.value, j.value
+
+
+def unrank_sym2_batch(n, p0, count):
+    out = np.empty((count, 2), dtype=np.int32)
+    _check(lib().st_unrank_sym2_batch(n, p0, count, out.ctypes.data), "st_unrank_sym2_batch")
+    return out
+
+
+def unrank_sym3_batch(n, p0, count):
+    out = np.empty((count, 3), dtype=np.int32)
+    _check(lib().st_unrank_sym3_batch(n, p0, count, out.ctypes.data), "st_unrank_sym3_batch")
+    return out
+
+
+def unrank_band_batch(n, w, p0, count):
+    out = np.empty((count, 2), dtype=np.int32)
+    _check(lib().st_unrank_band_batch(n, w, p0, count, out.ctypes.data), "st_unrank_band_batch")
+    return out
+
+
+# ---- device entry points -----------------------------------------------------------
+def _torch():
+    import torch
+    return torch
+
+
+def _stream():
+    return C.c_void_p(_torch().cuda.current_stream().cuda_stream)
+
+
+def _dev_f32(t, what):
+    torch = _torch()
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.float32 and t.is_contiguous()):
+        raise TypeError("%s must be a contiguous float32 CUDA tensor" % what)
+    return C.c_void_p(t.data_ptr())
+
+
+def _workspace(nbytes, like, ws):
+    torch = _torch()
+    if ws is None:
+        ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=like.device)
+    if not (ws.is_cuda and ws.is_contiguous()):
+        raise TypeError("workspace must be a contiguous CUDA tensor")
+    return ws, C.c_void_p(ws.data_ptr()), ws.numel() * ws.element_size()
+
+
+def workspace_bytes(kernel: str, **kw) -> int:
+    L = lib()
+    if kernel == "mttkrp_sym3":
+        return int(L.st_mttkrp_sym3_workspace(kw["n"], kw["R"]))
+    if kernel == "batax_utri":
+        return int(L.st_batax_utri_workspace(kw["n"]))
+    if kernel == "ttm_band":
+        return int(L.st_ttm_band_workspace(kw["n"], kw["w"], kw["nl"], kw["R"]))
+    if kernel == "moment3_sym":
+        return int(L.st_moment3_sym_workspace(kw["N"], kw["n"]))
+    raise KeyError(kernel)
+
+
+def unrank_device(kind, n, w, p0, count):
+    torch = _torch()
+    width = 3 if kind == 3 else 2
+    out = torch.empty((max(count, 1), width), dtype=torch.int32, device="cuda")
+    _check(lib().st_unrank_device(kind, n, w, p0, count, C.c_void_p(out.data_ptr()), _stream()),
+           "st_unrank_device")
+    return out[:count]
+
+
+def mttkrp_sym3(Tc, B, M=None, ws=None):
+    torch = _torch()
+    n, R = B.shape
+    if M is None:
+        M = torch.empty((n, R), dtype=torch.float32, device=B.device)
+    ws, pws, wsb = _workspace(workspace_bytes("mttkrp_sym3", n=n, R=R), B, ws)
+    _check(lib().st_mttkrp_sym3(_dev_f32(Tc, "Tc"), _dev_f32(B, "B"), _dev_f32(M, "M"), n, R, pws, wsb,
+                                _stream()), "st_mttkrp_sym3")
+    return M
+
+
+def batax_utri(Ap, x, beta, y=None, ws=None):
+    torch = _torch()
+    n = x.numel()
+    if y is None:
+        y = torch.empty(n, dtype=torch.float32, device=x.device)
+    ws, pws, wsb = _workspace(workspace_bytes("batax_utri", n=n), x, ws)
+    _check(lib().st_batax_utri(_dev_f32(Ap, "Ap"), _dev_f32(x, "x"), _dev_f32(y, "y"), n, float(beta), pws,
+                               wsb, _stream()), "st_batax_utri")
+    return y
+
+
+def ttm_band(Tc, U, n, w, Yc=None, ws=None):
+    torch = _torch()
+    nl, R = U.shape
+    rows = count_band(n, w)
+    if Yc is None:
+        Yc = torch.empty((rows, R), dtype=torch.float32, device=U.device)
+    ws, pws, wsb = _workspace(workspace_bytes("ttm_band", n=n, w=w, nl=nl, R=R), U, ws)
+    _check(lib().st_ttm_band(_dev_f32(Tc, "Tc"), _dev_f32(U, "U"), _dev_f32(Yc, "Yc"), n, w, nl, R, pws, wsb,
+                             _stream()), "st_ttm_band")
+    return Yc
+
+
+def moment3_sym(X, Sc=None, accumulate=False, ws=None):
+    torch = _torch()
+    N, n = X.shape
+    if Sc is None:
+        if accumulate:
+            raise ValueError("accumulate needs an existing Sc")
+        Sc = torch.empty(count_sym3(n), dtype=torch.float32, device=X.device)
+    ws, pws, wsb = _workspace(workspace_bytes("moment3_sym", N=N, n=n), X, ws)
+    px = _dev_f32(X, "X") if N > 0 else C.c_void_p(X.data_ptr() if X.numel() else 0)
+    _check(lib().st_moment3_sym(px, N, n, _dev_f32(Sc, "Sc"), 1 if accumulate else 0, pws, wsb, _stream()),
+           "st_moment3_sym")
+    return Sc
+
+
+def expand_sym(Sc, n, order, S=None):
+    torch = _torch()
+    if S is None:
+        S = torch.empty((n,) * order, dtype=torch.float32, device=Sc.device)
+    _check(lib().st_expand_sym(_dev_f32(Sc, "Sc"), _dev_f32(S, "S"), n, order, _stream()), "st_expand_sym")
+    return S

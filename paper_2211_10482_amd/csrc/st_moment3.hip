@@ -1,0 +1,344 @@
+// Third-moment accumulation over the unique set i<=j<=k,
+//     Sc(rank3(i,j,k)) (+)= sum_s X(s,i) X(s,j) X(s,k).
+//
+// The sum over samples is a dense contraction  S(i,(j,k)) = sum_s X(s,i) P(s,(j,k))
+// with P = x_j x_k formed on the fly, so it runs on the fp32 matrix cores
+// (v_mfma_f32_16x16x4_f32: a 16 x 16 tile of outputs, four samples per
+// instruction).  What keeps it in the unique space is the choice of tiles.
+//
+// MFMA path (n <= 64, indices padded to 64).  The 64 indices are split into
+// four groups of 16, group g = {4m+g}; one 16-byte load per lane then delivers
+// the A operand of all four groups at once (lane = (m, sample slot)).  An
+// unordered index triple is classified by the groups it touches:
+//   * three different groups a<b<c : rows = group a, columns = (fixed element
+//     of b) x (16 elements of c).  P = xa[c] * broadcast_m(xa[b]) is ONE VALU
+//     multiply with a DPP row broadcast.  4 * 16 tiles, all outputs unique.
+//   * a pair inside one group g, third index anywhere (group r): columns = the
+//     16 pairs (m, m-d mod 16) of g at cyclic distance d = 0..8, rows = group r.
+//     P = xa[g] * rotate_d(xa[g]) is one VALU multiply with a DPP row rotate
+//     and is shared by the four row groups.  4 * 9 * 4 tiles.
+// 208 tiles cover every unordered triple (53,248 accumulators for the 45,760
+// unique entries, against 64^3 = 262,144 dense ones), 84 pair products per four
+// samples feed 208 MFMAs.  A workgroup (8 waves, 26 tiles = 104 accumulator
+// registers per wave) owns ALL accumulators and streams a contiguous slice of
+// the samples; X is read from HBM exactly once.  Workgroup partials go to the
+// workspace in raw tile layout (coalesced) and a second kernel adds them in a
+// fixed order, drops the padding / duplicate positions and scatters through
+// rank3.  No float atomics.
+//
+// General path (n > 64): one thread per unique entry and sample slice.
+#include <type_traits>
+#include <utility>
+
+#include "st_common.h"
+#include "st_index.h"
+
+namespace st {
+
+typedef uint32_t u32;
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+template <int... Is, typename F>
+__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, Is...>, F &&f)
+{
+    (f(std::integral_constant<int, Is>{}), ...);
+}
+template <int N, typename F> __device__ __forceinline__ void static_for(F &&f)
+{
+    static_for_impl(std::make_integer_sequence<int, N>{}, static_cast<F &&>(f));
+}
+
+constexpr int M3_WAVES = 8;
+constexpr int M3_TPW = 26;                         // tiles per wave
+constexpr int M3_TILES = M3_WAVES * M3_TPW;        // 208
+constexpr int M3_ACC = M3_TILES * 256;             // accumulators per workgroup
+constexpr int M3_GMAX = 256;
+
+// lane m of each 16-lane row reads lane (m - D) mod 16 of the same row
+template <int D> __device__ __forceinline__ float row_ror(float v)
+{
+    if constexpr (D == 0) return v;
+    else
+        return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v),
+                                                                     0x120 + D, 0xf, 0xf, false));
+}
+// every lane of a 16-lane row reads lane M of that row
+template <int M> __device__ __forceinline__ float row_bcast(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v),
+                                                                 0x150 + M, 0xf, 0xf, false));
+}
+
+// Tile descriptor shared by the accumulation kernel (compile time) and the
+// reduction kernel (run time).  Tile `local` of wave `w`:
+//   local 0..17 : pair-in-group tiles; half unit h = 9 w + local/2 = (g*9 + d)*2 + half,
+//                 row group r = 2*half + local%2
+//   local 18,19 : groups (r=0, 1, 2), fixed element m = 2w + local-18 of group 1
+//   local 20,21 : groups (r=0, 1, 3), fixed element m = 2w + local-20 of group 1
+//   local 22..25: groups (r, 2, 3), fixed element m = 2w + (local-22)/2 of group 2, r = (local-22)%2
+struct TileDesc {
+    int kind;   // 0: pair inside group gb at distance d; 1: (element m of gb) x (group gc)
+    int r;      // row group
+    int gb, gc; // column groups (gc unused for kind 0)
+    int d;      // cyclic distance (kind 0) or fixed element m (kind 1)
+};
+__host__ __device__ constexpr TileDesc tile_desc(int w, int local)
+{
+    if (local < 18) {
+        int h = 9 * w + local / 2;
+        int gd = h / 2, half = h % 2;
+        return TileDesc{0, 2 * half + local % 2, gd / 9, 0, gd % 9};
+    }
+    if (local < 20) return TileDesc{1, 0, 1, 2, 2 * w + (local - 18)};
+    if (local < 22) return TileDesc{1, 0, 1, 3, 2 * w + (local - 20)};
+    return TileDesc{1, (local - 22) % 2, 2, 3, 2 * w + (local - 22) / 2};
+}
+
+// Row s of X as the A operands of the four groups (component g = X(s, 4m+g)).
+// Branch free so that the loads can stay in flight across K-steps: load_raw
+// clamps the row index into the slice, mask_x (applied where the value is first
+// needed) zeroes the rows past its end.
+template <bool FULL>
+__device__ __forceinline__ f32x4 load_raw(const float *__restrict__ X, int64_t s, int64_t s_end, u32 n,
+                                          u32 m)
+{
+    const int64_t sc = s < s_end ? s : s_end - 1;
+    f32x4 v;
+    if constexpr (FULL) {
+        float4 t = *reinterpret_cast<const float4 *>(X + sc * 64 + 4 * m);
+        v = (f32x4){t.x, t.y, t.z, t.w};
+    } else {
+        const float *row = X + sc * (int64_t)n;
+#pragma unroll
+        for (u32 g = 0; g < 4; ++g) {
+            u32 c = 4 * m + g;
+            v[g] = row[c < n ? c : n - 1];
+        }
+    }
+    return v;
+}
+template <bool FULL>
+__device__ __forceinline__ f32x4 mask_x(f32x4 v, int64_t s, int64_t s_end, u32 n, u32 m)
+{
+#pragma unroll
+    for (u32 g = 0; g < 4; ++g) {
+        bool ok = s < s_end && (FULL || 4 * m + g < n);
+        v[g] = ok ? v[g] : 0.f;
+    }
+    return v;
+}
+
+template <int W>
+__device__ __forceinline__ void m3_step(f32x4 (&acc)[M3_TPW], const f32x4 &xa)
+{
+    // pair-in-group half units
+    static_for<9>([&](auto HU) {
+        constexpr int h = 9 * W + HU;
+        constexpr int gd = h / 2, half = h % 2, g = gd / 9, d = gd % 9;
+        const float p = xa[g] * row_ror<d>(xa[g]);
+        acc[2 * HU] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[2 * half], p, acc[2 * HU], 0, 0, 0);
+        acc[2 * HU + 1] =
+            __builtin_amdgcn_mfma_f32_16x16x4f32(xa[2 * half + 1], p, acc[2 * HU + 1], 0, 0, 0);
+    });
+    // three different groups
+    static_for<2>([&](auto E) {
+        constexpr int m = 2 * W + E;
+        const float b1 = row_bcast<m>(xa[1]);
+        const float b2 = row_bcast<m>(xa[2]);
+        const float p12 = xa[2] * b1, p13 = xa[3] * b1, p23 = xa[3] * b2;
+        acc[18 + E] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[0], p12, acc[18 + E], 0, 0, 0);
+        acc[20 + E] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[0], p13, acc[20 + E], 0, 0, 0);
+        acc[22 + 2 * E] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[0], p23, acc[22 + 2 * E], 0, 0, 0);
+        acc[23 + 2 * E] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[1], p23, acc[23 + 2 * E], 0, 0, 0);
+    });
+}
+
+template <int W, bool FULL>
+__device__ __forceinline__ void m3_wave(const float *__restrict__ X, int64_t s_begin, int64_t s_end,
+                                        u32 n, float *__restrict__ part, u32 lane)
+{
+    const u32 m = lane & 15u, q = lane >> 4;
+    f32x4 acc[M3_TPW];
+#pragma unroll
+    for (int t = 0; t < M3_TPW; ++t) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+    // Four K-steps (of four samples each) per iteration; the loads of the next
+    // iteration are issued before the MFMAs of the current one and are only
+    // waited for at its end.
+    f32x4 x0 = mask_x<FULL>(load_raw<FULL>(X, s_begin + 0 + q, s_end, n, m), s_begin + 0 + q, s_end, n, m);
+    f32x4 x1 = mask_x<FULL>(load_raw<FULL>(X, s_begin + 4 + q, s_end, n, m), s_begin + 4 + q, s_end, n, m);
+    f32x4 x2 = mask_x<FULL>(load_raw<FULL>(X, s_begin + 8 + q, s_end, n, m), s_begin + 8 + q, s_end, n, m);
+    f32x4 x3 = mask_x<FULL>(load_raw<FULL>(X, s_begin + 12 + q, s_end, n, m), s_begin + 12 + q, s_end, n, m);
+    for (int64_t s = s_begin; s < s_end; s += 16) {
+        f32x4 y0 = load_raw<FULL>(X, s + 16 + q, s_end, n, m);
+        f32x4 y1 = load_raw<FULL>(X, s + 20 + q, s_end, n, m);
+        f32x4 y2 = load_raw<FULL>(X, s + 24 + q, s_end, n, m);
+        f32x4 y3 = load_raw<FULL>(X, s + 28 + q, s_end, n, m);
+        __builtin_amdgcn_sched_barrier(0);
+        m3_step<W>(acc, x0);
+        m3_step<W>(acc, x1);
+        m3_step<W>(acc, x2);
+        m3_step<W>(acc, x3);
+        __builtin_amdgcn_sched_barrier(0);
+        x0 = mask_x<FULL>(y0, s + 16 + q, s_end, n, m);
+        x1 = mask_x<FULL>(y1, s + 20 + q, s_end, n, m);
+        x2 = mask_x<FULL>(y2, s + 24 + q, s_end, n, m);
+        x3 = mask_x<FULL>(y3, s + 28 + q, s_end, n, m);
+    }
+
+    float *dst = part + (size_t)W * M3_TPW * 256 + lane;
+#pragma unroll
+    for (int t = 0; t < M3_TPW; ++t)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) dst[(t * 4 + v) * 64] = acc[t][v];
+}
+
+template <bool FULL>
+__global__ __launch_bounds__(M3_WAVES * 64) void moment3_mfma_kernel(const float *__restrict__ X,
+                                                                   int64_t N, u32 n, int64_t chunk,
+                                                                   float *__restrict__ ws)
+{
+    const u32 lane = threadIdx.x & 63u;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    int64_t s_begin = (int64_t)blockIdx.x * chunk;
+    int64_t s_end = s_begin + chunk < N ? s_begin + chunk : N;
+    float *part = ws + (size_t)blockIdx.x * M3_ACC;
+    switch (wave) {
+    case 0: m3_wave<0, FULL>(X, s_begin, s_end, n, part, lane); break;
+    case 1: m3_wave<1, FULL>(X, s_begin, s_end, n, part, lane); break;
+    case 2: m3_wave<2, FULL>(X, s_begin, s_end, n, part, lane); break;
+    case 3: m3_wave<3, FULL>(X, s_begin, s_end, n, part, lane); break;
+    case 4: m3_wave<4, FULL>(X, s_begin, s_end, n, part, lane); break;
+    case 5: m3_wave<5, FULL>(X, s_begin, s_end, n, part, lane); break;
+    case 6: m3_wave<6, FULL>(X, s_begin, s_end, n, part, lane); break;
+    default: m3_wave<7, FULL>(X, s_begin, s_end, n, part, lane); break;
+    }
+}
+
+__device__ __forceinline__ void sort3u(u32 &a, u32 &b, u32 &c)
+{
+    u32 lo = min(a, b), hi = max(a, b);
+    u32 mn = min(lo, c), mx = max(hi, c), md = max(lo, min(hi, c));
+    a = mn; b = md; c = mx;
+}
+
+// Adds the G workgroup partials (g ascending) and scatters the unique ones.
+__global__ __launch_bounds__(256) void moment3_reduce_kernel(const float *__restrict__ ws, u32 G, u32 n,
+                                                            float *__restrict__ Sc, int accumulate)
+{
+    u32 e = blockIdx.x * 256u + threadIdx.x;      // raw accumulator id, < M3_ACC
+    u32 tile = e >> 8, v = (e >> 6) & 3u, lane = e & 63u;
+    TileDesc td = tile_desc((int)(tile / M3_TPW), (int)(tile % M3_TPW));
+    // D layout of the 16x16 MFMA: lane holds column lane%16 of rows 4*(lane/16) + v
+    u32 rowel = 4u * (lane >> 4) + v, col = lane & 15u;
+    u32 i = 4u * rowel + (u32)td.r, j, k;
+    bool keep;
+    if (td.kind == 0) {
+        u32 other = (col - (u32)td.d) & 15u;
+        j = 4u * col + (u32)td.gb;
+        k = 4u * other + (u32)td.gb;
+        keep = (td.d < 8) || (col < 8u);                       // distance 8 lists each pair twice
+        if (td.r == td.gb) keep = keep && rowel <= min(col, other);   // row is the smallest of the three
+    } else {
+        j = 4u * (u32)td.d + (u32)td.gb;
+        k = 4u * col + (u32)td.gc;
+        keep = true;
+    }
+    keep = keep && i < n && j < n && k < n;
+    if (!keep) return;
+    float s = 0.f;
+    for (u32 g = 0; g < G; ++g) s += ws[(size_t)g * M3_ACC + e];
+    sort3u(i, j, k);
+    u32 p = rank_sym3<u32>(n, i, j, k);
+    Sc[p] = accumulate ? Sc[p] + s : s;
+}
+
+// ---- general path -----------------------------------------------------------------
+__global__ __launch_bounds__(256) void moment3_plain_kernel(const float *__restrict__ X, int64_t N, u32 n,
+                                                           u32 count, int64_t slice,
+                                                           float *__restrict__ part)
+{
+    u32 p = blockIdx.x * 256u + threadIdx.x;
+    if (p >= count) return;
+    u32 i, j, k;
+    unrank_sym3<u32>(n, p, i, j, k);
+    int64_t s0 = (int64_t)blockIdx.y * slice, s1 = s0 + slice < N ? s0 + slice : N;
+    float s = 0.f;
+    for (int64_t q = s0; q < s1; ++q) {
+        const float *row = X + q * (int64_t)n;
+        s += row[i] * row[j] * row[k];
+    }
+    part[(size_t)blockIdx.y * count + p] = s;
+}
+
+__global__ __launch_bounds__(256) void moment3_plain_reduce_kernel(const float *__restrict__ part, u32 SY,
+                                                                  u32 count, float *__restrict__ Sc,
+                                                                  int accumulate)
+{
+    u32 p = blockIdx.x * 256u + threadIdx.x;
+    if (p >= count) return;
+    float s = 0.f;
+    for (u32 y = 0; y < SY; ++y) s += part[(size_t)y * count + p];
+    Sc[p] = accumulate ? Sc[p] + s : s;
+}
+
+__global__ __launch_bounds__(256) void zero_kernel(float *__restrict__ p, u32 count)
+{
+    u32 t = blockIdx.x * 256u + threadIdx.x;
+    if (t < count) p[t] = 0.f;
+}
+
+static inline int64_t m3_chunk(int64_t N)
+{
+    int64_t c = (N + M3_GMAX - 1) / M3_GMAX;
+    c = (c + 15) / 16 * 16;
+    return c < 64 ? 64 : c;
+}
+static inline u32 m3_groups(int64_t N) { return N == 0 ? 0u : (u32)((N + m3_chunk(N) - 1) / m3_chunk(N)); }
+static inline u32 plain_slices(int64_t N)
+{
+    int64_t s = (N + 1023) / 1024;
+    return (u32)(s < 1 ? 1 : s > 16 ? 16 : s);
+}
+
+size_t moment3_workspace(int64_t N, int n)
+{
+    if (N == 0) return 0;
+    if (n <= 64) return (size_t)m3_groups(N) * M3_ACC * sizeof(float);
+    return (size_t)plain_slices(N) * (size_t)count_sym3<int64_t>(n) * sizeof(float);
+}
+
+st_status launch_moment3(const float *X, int64_t N, int n, float *Sc, int accumulate, void *ws,
+                         hipStream_t s)
+{
+    u32 count = (u32)count_sym3<int64_t>(n);
+    if (N == 0) {
+        if (!accumulate) hipLaunchKernelGGL(zero_kernel, dim3((count + 255u) / 256u), dim3(256), 0, s, Sc, count);
+        return launch_status();
+    }
+    float *wsf = static_cast<float *>(ws);
+    if (n <= 64) {
+        int64_t chunk = m3_chunk(N);
+        u32 G = m3_groups(N);
+        if (n == 64)
+            hipLaunchKernelGGL(moment3_mfma_kernel<true>, dim3(G), dim3(M3_WAVES * 64), 0, s, X, N, (u32)n,
+                               chunk, wsf);
+        else
+            hipLaunchKernelGGL(moment3_mfma_kernel<false>, dim3(G), dim3(M3_WAVES * 64), 0, s, X, N, (u32)n,
+                               chunk, wsf);
+        if (hipGetLastError() != hipSuccess) return ST_ERR_LAUNCH;
+        hipLaunchKernelGGL(moment3_reduce_kernel, dim3(M3_ACC / 256), dim3(256), 0, s, wsf, G, (u32)n, Sc,
+                           accumulate);
+        return launch_status();
+    }
+    u32 SY = plain_slices(N);
+    int64_t slice = (N + SY - 1) / SY;
+    hipLaunchKernelGGL(moment3_plain_kernel, dim3((count + 255u) / 256u, SY), dim3(256), 0, s, X, N, (u32)n,
+                       count, slice, wsf);
+    if (hipGetLastError() != hipSuccess) return ST_ERR_LAUNCH;
+    hipLaunchKernelGGL(moment3_plain_reduce_kernel, dim3((count + 255u) / 256u), dim3(256), 0, s, wsf, SY,
+                       count, Sc, accumulate);
+    return launch_status();
+}
+
+}  // namespace st

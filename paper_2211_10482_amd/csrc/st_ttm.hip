@@ -1,0 +1,182 @@
+// Tensor-times-matrix along mode 3 of a band tensor,
+//     Y(i,j,r) = sum_l T(i,j,l) U(l,r)   for the in-band pairs (i,j) only.
+//
+// In packed band storage the in-band fibres T(i,j,:) are the rows of a plain
+// row-major matrix [band_pairs][nl], and the output keeps the same unique set,
+// so the kernel is a dense contraction [rows x nl] . [nl x R] and runs on the
+// fp32 matrix cores (v_mfma_f32_16x16x4_f32).  The band itself only decides
+// which rows exist (rank/unrank of the row id is the caller's business).
+//
+// MFMA path (nl % 16 == 0, R % 16 == 0, R <= 256): persistent workgroups of 16
+// waves, one per CU.  U is staged once into LDS, already permuted into MFMA
+// B-operand order, so that the hot loop issues per 16 values of l: one 16-byte
+// global load of T per lane (lane = (row, l-quad); the four components feed
+// four MFMAs whose K slots are permuted consistently on the U side), one
+// ds_read_b128 of U and four MFMAs.  A work unit is a 16-row x 16-column
+// output tile; the units of one row tile sit on waves of the same workgroup so
+// its rows are fetched from HBM once and shared through the CU's L1.
+//
+// Algorithmic traffic per output row: 4*nl bytes read + 4*R written (+ U once).
+#include "st_common.h"
+
+namespace st {
+
+typedef uint32_t u32;
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int TW = 16;        // waves per workgroup
+constexpr int MAXR = 4;       // row tiles a wave keeps accumulators for at once
+
+// Stage rows [k0, k0+kc) of U (nl x R, row-major) into LDS in B-operand order:
+// value U(k0 + 16 s + 4 q + t, 16 ct + c) goes to ((s*CT + ct)*64 + 16 q + c)*4 + t.
+__device__ __forceinline__ void stage_u(float *lds, const float *__restrict__ U, u32 k0, u32 kc, u32 R,
+                                        u32 CT, u32 tid, u32 nthreads)
+{
+    u32 rq = R / 4u;
+    for (u32 e = tid; e < kc * rq; e += nthreads) {
+        u32 k = e / rq, c4 = (e - k * rq) * 4u;
+        float4 v = *reinterpret_cast<const float4 *>(U + (size_t)(k0 + k) * R + c4);
+        u32 s = k >> 4, q = (k >> 2) & 3u, t = k & 3u, ct = c4 >> 4, c = c4 & 15u;
+        float *d = lds + ((size_t)((s * CT + ct) * 64u + 16u * q + c)) * 4u + t;
+        d[0] = v.x; d[4] = v.y; d[8] = v.z; d[12] = v.w;
+    }
+}
+
+__global__ __launch_bounds__(TW * 64) void ttm_mfma_kernel(const float *__restrict__ Tc,
+                                                         const float *__restrict__ U, float *__restrict__ Yc,
+                                                         u32 rows, u32 nl, u32 R, u32 KC)
+{
+    extern __shared__ float lds[];
+    const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const u32 CT = R / 16u;
+    const u32 SLOTS = TW / CT;                 // row tiles in flight per workgroup
+    const u32 slot = wave / CT, ct = wave - slot * CT;
+    const bool active = slot < SLOTS;
+    const u32 rtiles = (rows + 15u) / 16u;
+    const u32 per_super = gridDim.x * SLOTS * MAXR;
+    const u32 nsuper = (rtiles + per_super - 1u) / per_super;
+    const u32 nchunks = (nl + KC - 1u) / KC;
+    const u32 lrow = lane & 15u, lq = lane >> 4;
+
+    for (u32 sr = 0; sr < nsuper; ++sr) {
+        f32x4 acc[MAXR];
+#pragma unroll
+        for (int r = 0; r < MAXR; ++r) acc[r] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+        for (u32 ch = 0; ch < nchunks; ++ch) {
+            const u32 k0 = ch * KC, kc = min(KC, nl - k0);
+            if (!(nchunks == 1u && sr > 0u)) {
+                __syncthreads();
+                stage_u(lds, U, k0, kc, R, CT, tid, TW * 64u);
+                __syncthreads();
+            }
+            if (!active) continue;
+            const u32 steps = kc / 16u;
+#pragma unroll
+            for (int r = 0; r < MAXR; ++r) {
+                u32 rt = blockIdx.x + gridDim.x * (slot + SLOTS * ((u32)r + MAXR * sr));
+                if (rt >= rtiles) continue;
+                u32 row = min(rt * 16u + lrow, rows - 1u);          // clamp: tail rows are discarded
+                const float4 *ap = reinterpret_cast<const float4 *>(Tc + (size_t)row * nl + k0) + lq;
+                const f32x4 *bp = reinterpret_cast<const f32x4 *>(lds) + (size_t)ct * 64u + lane;
+                f32x4 c = acc[r];
+                u32 s = 0;
+                for (; s + 4u <= steps; s += 4u) {
+                    float4 a0 = ap[(s + 0u) * 4u], a1 = ap[(s + 1u) * 4u];
+                    float4 a2 = ap[(s + 2u) * 4u], a3 = ap[(s + 3u) * 4u];
+                    f32x4 b0 = bp[(size_t)(s + 0u) * CT * 64u], b1 = bp[(size_t)(s + 1u) * CT * 64u];
+                    f32x4 b2 = bp[(size_t)(s + 2u) * CT * 64u], b3 = bp[(size_t)(s + 3u) * CT * 64u];
+                    c = __builtin_amdgcn_mfma_f32_16x16x4f32(a0.x, b0[0], c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_16x16x4f32(a0.y, b0[1], c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_16x16x4f32(a0.z, b0[2], c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_16x16x4f32(a0.w, b0[3], c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_16x16x4f32(a1.x, b1[0], c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_16x16x4f32(a1.y, b1[1], c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_16x16x4f32(a1.z, b1[2], c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_16x16x4f32(a1.w, b1[3], c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_16x16x4f32(a2.x, b2[0], c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_16x16x4f32(a2.y, b2[1], c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_16x16x4f32(a2.z, b2[2], c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_16x16x4f32(a2.w, b2[3], c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_16x16x4f32(a3.x, b3[0], c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_16x16x4f32(a3.y, b3[1], c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_16x16x4f32(a3.z, b3[2], c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_16x16x4f32(a3.w, b3[3], c, 0, 0, 0);
+                }
+                for (; s < steps; ++s) {
+                    float4 a0 = ap[s * 4u];
+                    f32x4 b0 = bp[(size_t)s * CT * 64u];
+                    c = __builtin_amdgcn_mfma_f32_16x16x4f32(a0.x, b0[0], c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_16x16x4f32(a0.y, b0[1], c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_16x16x4f32(a0.z, b0[2], c, 0, 0, 0);
+                    c = __builtin_amdgcn_mfma_f32_16x16x4f32(a0.w, b0[3], c, 0, 0, 0);
+                }
+                acc[r] = c;
+            }
+        }
+
+        if (active) {
+#pragma unroll
+            for (int r = 0; r < MAXR; ++r) {
+                u32 rt = blockIdx.x + gridDim.x * (slot + SLOTS * ((u32)r + MAXR * sr));
+                if (rt >= rtiles) continue;
+                // D layout: lane holds column lane%16 of rows 4*(lane/16) + v
+#pragma unroll
+                for (u32 v = 0; v < 4; ++v) {
+                    u32 row = rt * 16u + 4u * lq + v;
+                    if (row < rows) Yc[(size_t)row * R + ct * 16u + lrow] = acc[r][v];
+                }
+            }
+        }
+    }
+}
+
+// Any shape: one thread per output value.
+__global__ __launch_bounds__(256) void ttm_plain_kernel(const float *__restrict__ Tc,
+                                                       const float *__restrict__ U, float *__restrict__ Yc,
+                                                       uint64_t rows, u32 nl, u32 R)
+{
+    uint64_t t = (uint64_t)blockIdx.x * 256u + threadIdx.x;
+    if (t >= rows * R) return;
+    uint64_t row = t / R;
+    u32 r = (u32)(t - row * R);
+    const float *a = Tc + row * nl;
+    float s = 0.f;
+    for (u32 l = 0; l < nl; ++l) s += a[l] * U[(size_t)l * R + r];
+    Yc[t] = s;
+}
+
+size_t ttm_workspace(int, int, int, int) { return 0; }
+
+st_status launch_ttm(const float *Tc, const float *U, float *Yc, int64_t rows, int nl, int R, void *,
+                     hipStream_t s)
+{
+    if (rows == 0) return ST_OK;
+    bool mfma = (nl % 16 == 0) && (R % 16 == 0) && R <= 256 && rows < ((int64_t)1 << 31);
+    if (mfma) {
+        const u32 lds_budget = 128u * 1024u;
+        u32 KC = (lds_budget / ((u32)R * 4u)) & ~15u;      // rows of U per LDS chunk, multiple of 16
+        if (KC > (u32)nl) KC = (u32)nl;
+        size_t lds_bytes = (size_t)KC * R * 4u;
+        static bool attr_set = false;
+        if (!attr_set) {
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(ttm_mfma_kernel),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_budget) != hipSuccess)
+                return ST_ERR_LAUNCH;
+            attr_set = true;
+        }
+        u32 rtiles = (u32)((rows + 15) / 16);
+        u32 grid = (u32)num_cus();
+        if (grid > rtiles) grid = rtiles;
+        hipLaunchKernelGGL(ttm_mfma_kernel, dim3(grid), dim3(TW * 64), lds_bytes, s, Tc, U, Yc, (u32)rows,
+                           (u32)nl, (u32)R, KC);
+        return launch_status();
+    }
+    uint64_t total = (uint64_t)rows * R;
+    if ((total + 255) / 256 > 0x7fffffffull) return ST_ERR_UNSUPPORTED;
+    hipLaunchKernelGGL(ttm_plain_kernel, dim3((u32)((total + 255) / 256)), dim3(256), 0, s, Tc, U, Yc,
+                       (uint64_t)rows, (u32)nl, (u32)R);
+    return launch_status();
+}
+
+}  // namespace st

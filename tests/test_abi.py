@@ -1,0 +1,92 @@
+"""The C-ABI library loads without a GPU, exports every symbol the header
+declares, and turns invalid arguments into status codes on the host (nothing is
+launched on any of these paths)."""
+import ctypes as C
+import os
+import re
+
+import paper_2211_10482_amd as st
+from paper_2211_10482_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "structtensor.h")
+
+OK, NULL, SHAPE, ALIGN, WORKSPACE, LAUNCH, UNSUPPORTED = range(7)
+P = 0x7F0000001000      # an aligned, never dereferenced, fake device address
+
+
+def declared_symbols():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(st_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported():
+    names = declared_symbols()
+    assert "st_mttkrp_sym3" in names and "st_expand_sym" in names and len(names) >= 20
+    lib = st.lib()
+    for name in names:
+        assert hasattr(lib, name), name
+    assert set(names) == set(binding.SIGNATURES)
+
+
+def test_status_strings():
+    lib = st.lib()
+    for s in range(0, 7):
+        assert len(lib.st_status_string(s)) > 0
+    assert lib.st_status_string(0) == b"ok"
+
+
+def test_null_and_shape_errors():
+    L = st.lib()
+    assert L.st_mttkrp_sym3(None, P, P + 0x100000, 4, 2, None, 0, None) == NULL
+    assert L.st_mttkrp_sym3(P, P + 0x10000, P + 0x20000, 0, 2, None, 0, None) == SHAPE
+    assert L.st_mttkrp_sym3(P, P + 0x10000, P + 0x20000, 4, 0, None, 0, None) == SHAPE
+    assert L.st_mttkrp_sym3(P, P + 0x10000, P + 0x20000, 5000, 4, None, 0, None) == UNSUPPORTED
+    assert L.st_batax_utri(P, None, P + 0x10000, 4, 0.5, None, 0, None) == NULL
+    assert L.st_batax_utri(P, P + 0x10000, P + 0x20000, -1, 0.5, None, 0, None) == SHAPE
+    assert L.st_ttm_band(P, P + 0x100000, None, 4, 1, 4, 4, None, 0, None) == NULL
+    assert L.st_ttm_band(P, P + 0x100000, P + 0x200000, 4, -1, 4, 4, None, 0, None) == SHAPE
+    assert L.st_ttm_band(P, P + 0x100000, P + 0x200000, 4, 1, 0, 4, None, 0, None) == SHAPE
+    assert L.st_moment3_sym(P, 10, 4, None, 0, None, 0, None) == NULL
+    assert L.st_moment3_sym(None, 10, 4, P, 0, None, 0, None) == NULL
+    assert L.st_moment3_sym(P, -1, 4, P + 0x100000, 0, None, 0, None) == SHAPE
+    assert L.st_moment3_sym(P, 10, 4, P + 0x100000, 2, None, 0, None) == SHAPE
+    assert L.st_expand_sym(None, P, 4, 3, None) == NULL
+    assert L.st_expand_sym(P, P + 0x100000, 4, 4, None) == SHAPE
+    assert L.st_expand_sym(P, P + 0x100000, 0, 3, None) == SHAPE
+    assert L.st_unrank_device(5, 4, 0, 0, 1, P, None) == SHAPE
+    assert L.st_unrank_device(3, 4, 0, 19, 2, P, None) == SHAPE
+
+
+def test_alignment_overlap_workspace_errors():
+    L = st.lib()
+    assert L.st_batax_utri(P + 4, P + 0x10000, P + 0x20000, 8, 0.5, None, 0, None) == ALIGN
+    assert L.st_expand_sym(P, P + 0x100008, 4, 3, None) == ALIGN
+    # output aliases an input
+    assert L.st_batax_utri(P, P + 0x10000, P + 0x10000, 8, 0.5, None, 0, None) == SHAPE
+    assert L.st_expand_sym(P, P + 16, 4, 3, None) == SHAPE
+    assert L.st_mttkrp_sym3(P, P + 0x10000, P, 4, 2, None, 0, None) == SHAPE
+    # workspace missing / too small / misaligned
+    need = L.st_batax_utri_workspace(100)
+    assert need > 0
+    assert L.st_batax_utri(P, P + 0x100000, P + 0x200000, 100, 0.5, None, 0, None) == WORKSPACE
+    assert L.st_batax_utri(P, P + 0x100000, P + 0x200000, 100, 0.5, P + 0x300000, need - 1, None) == WORKSPACE
+    assert L.st_batax_utri(P, P + 0x100000, P + 0x200000, 100, 0.5, P + 0x300004, need, None) == ALIGN
+    need = L.st_moment3_sym_workspace(1000, 8)
+    assert need > 0
+    assert L.st_moment3_sym(P, 1000, 8, P + 0x100000, 0, None, 0, None) == WORKSPACE
+    need = L.st_mttkrp_sym3_workspace(20, 4)
+    assert need > 0
+    assert L.st_mttkrp_sym3(P, P + 0x100000, P + 0x200000, 20, 4, P + 0x300000, need - 4, None) == WORKSPACE
+    assert L.st_moment3_sym_workspace(0, 8) == 0 and L.st_ttm_band_workspace(8, 1, 8, 8) == 0
+
+
+def test_binding_refuses_host_tensors():
+    import numpy as np
+    import pytest
+    import torch
+    with pytest.raises(TypeError):
+        st.expand_sym(torch.zeros(20), 4, 3, S=torch.zeros(4, 4, 4))
+    with pytest.raises(TypeError):
+        st.expand_sym(np.zeros(20, dtype=np.float32), 4, 3, S=torch.zeros(4, 4, 4))
