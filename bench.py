@@ -1,0 +1,235 @@
+#!/usr/bin/env python3
+"""Benchmark of the structured-tensor hot path on one MI355X.
+
+One *step* is one pass of the whole hot path over the five synthetic
+workloads: symmetric MTTKRP (n=64, R=16), upper-triangular BATAX (n=8192),
+band TTM (512^3, w=8, R=64), symmetric MTTKRP (n=512, R=64), third-moment
+accumulation (N=2e6, n=64) followed by the expansion of its result.  Inputs are
+resident in HBM before the timed region.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import st_workloads as W  # noqa: E402
+
+# published MI355X peaks
+HBM_PEAK_GBS = 8000.0
+MFMA_FP32_PEAK_TFLOPS = 157.3
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def tri(n):
+    return n * (n + 1) // 2
+
+
+def tet(n):
+    return n * (n + 1) * (n + 2) // 6
+
+
+def workloads():
+    """Algorithmic flops (unique-element convention) and bytes per launch."""
+    c1, c2, c3, c4, c5 = (W.CONFIGS[i] for i in range(1, 6))
+    out = {}
+    n, R = c1["n"], c1["R"]
+    out["mttkrp_sym3_n64_R16"] = dict(flops=6 * R * tet(n), bytes=4 * (tet(n) + 2 * n * R), bound="mfma")
+    n = c2["n"]
+    out["batax_utri_n8192"] = dict(flops=4 * tri(n), bytes=4 * (tri(n) + 2 * n), bound="hbm")
+    rows, nl, R = c3["band_pairs"], c3["nl"], c3["R"]
+    out["ttm_band_n512_w8_R64"] = dict(flops=2 * rows * nl * R, bytes=4 * (rows * nl + nl * R + rows * R),
+                                       bound="mfma")
+    n, R = c4["n"], c4["R"]
+    out["mttkrp_sym3_n512_R64"] = dict(flops=6 * R * tet(n), bytes=4 * (tet(n) + 2 * n * R), bound="mfma")
+    N, n = c5["N"], c5["n"]
+    out["moment3_sym_N2e6_n64"] = dict(flops=N * (2 * tet(n) + tri(n)), bytes=4 * (N * n + tet(n)), bound="mfma")
+    out["expand_sym_n64"] = dict(flops=0, bytes=4 * (tet(n) + n ** 3), bound="hbm")
+    return out
+
+
+def cpu_baseline(inputs):
+    """The oracle as it stands, timed on a bounded sample of the same step."""
+    import oracle
+    t_est = 0.0
+    parts = []
+
+    def timed(f):
+        t0 = time.perf_counter()
+        f()
+        return time.perf_counter() - t0
+
+    Tc1, B1 = inputs["c1"]
+    t = timed(lambda: oracle.mttkrp_sym3(Tc1, B1))
+    t_est += t
+    parts.append("mttkrp n=64 full %.2fs" % t)
+    Ap, x = inputs["c2"]
+    t = timed(lambda: oracle.batax_utri(Ap, x, 0.5))
+    t_est += t
+    parts.append("batax n=8192 full %.2fs" % t)
+    Tc3, U = inputs["c3"]
+    t = timed(lambda: oracle.ttm_band(Tc3, U, 512, 8))
+    t_est += t
+    parts.append("ttm full %.2fs" % t)
+    Tc4, B4 = inputs["c4"]
+    rows = np.arange(0, 512, 32, dtype=np.int64)
+    t = timed(lambda: oracle.mttkrp_sym3(Tc4, B4, rows=rows))
+    t_est += t * (512 / rows.size)
+    parts.append("mttkrp n=512: %d of 512 rows %.2fs" % (rows.size, t))
+    X = inputs["c5"]
+    ns = 4000
+    t = timed(lambda: oracle.moment3_dense(X[:ns]))
+    t_est += t * (X.shape[0] / ns)
+    parts.append("moment3: %d of %d samples %.2fs" % (ns, X.shape[0], t))
+    Sc = W.uniform(7, tet(64))
+    t = timed(lambda: oracle.expand_sym(Sc, 64, 3))
+    t_est += t
+    parts.append("expand full %.3fs" % t)
+    total_flops = sum(w["flops"] for w in workloads().values())
+    return dict(value=total_flops / t_est / 1e9, unit="GFLOP/s", cores=oracle.num_threads(), kind="oracle",
+                sample="; ".join(parts) + "; scaled to one full step = %.1fs" % t_est)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (--gpus 1); nothing here uses a second GPU")
+
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible (there is no CPU fallback)")
+    import paper_2211_10482_amd as st
+    st.lib()
+    dev = torch.device("cuda:0")
+
+    log("generating inputs ...")
+    c1, c2, c3, c4, c5 = (W.CONFIGS[i] for i in range(1, 6))
+    host = {
+        "c1": W.mttkrp_inputs(c1["n"], c1["R"], c1["entries"], c1["b_dist"], 1),
+        "c2": W.batax_inputs(c2["n"], c2["entries"]),
+        "c3": W.ttm_inputs(c3["band_pairs"], c3["nl"], c3["R"]),
+        "c4": W.mttkrp_inputs(c4["n"], c4["R"], c4["entries"], c4["b_dist"], 4),
+        "c5": W.moment_inputs(c5["N"], c5["n"]),
+    }
+    up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+    Tc1, B1 = map(up, host["c1"])
+    Ap, x = map(up, host["c2"])
+    Tc3, U = map(up, host["c3"])
+    Tc4, B4 = map(up, host["c4"])
+    X = up(host["c5"])
+
+    # outputs and workspaces are allocated once, outside the timed region
+    f32 = dict(dtype=torch.float32, device=dev)
+    M1 = torch.empty((c1["n"], c1["R"]), **f32)
+    y = torch.empty(c2["n"], **f32)
+    Yc = torch.empty((c3["band_pairs"], c3["R"]), **f32)
+    M4 = torch.empty((c4["n"], c4["R"]), **f32)
+    Sc = torch.empty(c5["entries"], **f32)
+    S = torch.empty((c5["n"],) * 3, **f32)
+    wsb = max(st.workspace_bytes("mttkrp_sym3", n=c1["n"], R=c1["R"]),
+              st.workspace_bytes("batax_utri", n=c2["n"]),
+              st.workspace_bytes("ttm_band", n=c3["n"], w=c3["w"], nl=c3["nl"], R=c3["R"]),
+              st.workspace_bytes("mttkrp_sym3", n=c4["n"], R=c4["R"]),
+              st.workspace_bytes("moment3_sym", N=c5["N"], n=c5["n"]))
+    ws = torch.empty(wsb, dtype=torch.uint8, device=dev)
+
+    calls = [
+        ("mttkrp_sym3_n64_R16", lambda: st.mttkrp_sym3(Tc1, B1, M=M1, ws=ws)),
+        ("batax_utri_n8192", lambda: st.batax_utri(Ap, x, c2["beta"], y=y, ws=ws)),
+        ("ttm_band_n512_w8_R64", lambda: st.ttm_band(Tc3, U, c3["n"], c3["w"], Yc=Yc, ws=ws)),
+        ("mttkrp_sym3_n512_R64", lambda: st.mttkrp_sym3(Tc4, B4, M=M4, ws=ws)),
+        ("moment3_sym_N2e6_n64", lambda: st.moment3_sym(X, Sc=Sc, ws=ws)),
+        ("expand_sym_n64", lambda: st.expand_sym(Sc, c5["n"], 3, S=S)),
+    ]
+
+    def step(events=None):
+        for name, f in calls:
+            if events is not None:
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                f()
+                e1.record()
+                events[name].append((e0, e1))
+            else:
+                f()
+
+    log("warmup ...")
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    events = {name: [] for name, _ in calls}
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(events)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    wl = workloads()
+    kernels = {}
+    for name, _ in calls:
+        ms = float(np.mean([a.elapsed_time(b) for a, b in events[name]]))
+        w = wl[name]
+        gflops = w["flops"] / (ms * 1e-3) / 1e9
+        gbs = w["bytes"] / (ms * 1e-3) / 1e9
+        frac = gbs / HBM_PEAK_GBS if w["bound"] == "hbm" else gflops / 1e3 / MFMA_FP32_PEAK_TFLOPS
+        kernels[name] = dict(ms=round(ms, 5), unique_gflops=round(gflops, 2), alg_gbs=round(gbs, 2),
+                             bound=w["bound"], frac=round(frac, 4))
+    total_flops = sum(w["flops"] for w in wl.values())
+    value = total_flops / (ms_per_step * 1e-3) / 1e9
+
+    dom = "moment3_sym_N2e6_n64"
+    dom_ms = kernels[dom]["ms"]
+    achieved = wl[dom]["flops"] / (dom_ms * 1e-3) / 1e12
+    roofline = dict(kernel=dom, bound="mfma", achieved=round(achieved, 3), peak=MFMA_FP32_PEAK_TFLOPS,
+                    unit="TFLOP/s", frac=round(achieved / MFMA_FP32_PEAK_TFLOPS, 4), traffic=None)
+
+    result = {
+        "metric": "unique-element GFLOP/s over the five structured kernels, 1xMI355X",
+        "value": round(value, 2),
+        "unit": "GFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "all five configs per step: mttkrp_sym3 n=64 R=16; batax_utri n=8192; "
+                               "ttm_band n=512 w=8 nl=512 R=64; mttkrp_sym3 n=512 R=64; "
+                               "moment3_sym N=2e6 n=64 + expand_sym n=64"},
+        "roofline": roofline,
+        "kernels": kernels,
+    }
+    if not args.no_cpu_baseline:
+        log("cpu baseline (oracle on a bounded sample) ...")
+        result["cpu_baseline"] = cpu_baseline(host)
+    else:
+        result["cpu_baseline"] = None
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -42,6 +42,7 @@ def lib():
             "so_moment3_dense": (None, [p, i64, i64, p]),
             "so_moment3_entries": (None, [p, i64, i64, p, i64, p]),
             "so_expand_sym": (C.c_int, [p, i64, C.c_int, p]),
+            "so_num_threads": (C.c_int, []),
         }
         for name, (res, args) in sig.items():
             f = getattr(_lib, name)
@@ -52,6 +53,10 @@ def lib():
 def _f32(a):
     a = np.ascontiguousarray(a, dtype=np.float32)
     return a, a.ctypes.data
+
+
+def num_threads():
+    return int(lib().so_num_threads())
 
 
 # ---- enumeration ---------------------------------------------------------

@@ -30,7 +30,21 @@
 #include <stdlib.h>
 #include <string.h>
 
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
 #define SO_API __attribute__((visibility("default")))
+
+/* Threads the parallel loops below will use (for reporting timings). */
+SO_API int so_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
 
 /* ------------------------------------------------------------------ */
 /* enumeration by counting                                             */

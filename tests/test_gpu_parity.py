@@ -1,0 +1,279 @@
+"""Parity of the HIP kernels (through the C ABI) against the fp64 CPU oracle, on
+the same seeded inputs.
+
+Bar: bit-exact for index maps and expand; for fp32 results the norm-wise error
+max|got - ref| / max|ref| <= 1e-4 per output tensor (the outputs are sums of
+zero-mean terms, so element-wise relative error is meaningless near zero).
+"""
+import itertools
+import sys
+
+import numpy as np
+import pytest
+
+import st_workloads as W
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-4
+
+
+@pytest.fixture(scope="module")
+def st():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    import paper_2211_10482_amd as lib
+    lib.lib()
+    return lib
+
+
+def dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+def rel_err(got, ref):
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    scale = np.abs(ref).max()
+    if scale == 0.0:
+        return float(np.abs(got).max())
+    return float(np.abs(got - ref).max() / scale)
+
+
+# ------------------------------------------------------------ device index maps
+@pytest.mark.parametrize("n", [1, 2, 7, 40, 64])
+def test_device_unrank_small(st, oracle, n):
+    say("device unrank n=%d" % n)
+    got3 = st.unrank_device(3, n, 0, 0, oracle.count_sym3(n)).cpu().numpy()
+    assert np.array_equal(got3, oracle.list_sym3(n))
+    got2 = st.unrank_device(2, n, 0, 0, oracle.count_sym2(n)).cpu().numpy()
+    assert np.array_equal(got2, oracle.list_sym2(n))
+    for w in (0, 1, n // 2, n - 1, n + 3):
+        gotb = st.unrank_device(4, n, w, 0, oracle.count_band(n, w)).cpu().numpy()
+        assert np.array_equal(gotb, oracle.list_band(n, w))
+
+
+def test_device_unrank_full_sizes(st, oracle):
+    say("device unrank sym3 n=512 (22.5M), sym2 n=8192 (33.6M), band (512,8)")
+    lst = oracle.list_sym3(512)
+    got = st.unrank_device(3, 512, 0, 0, lst.shape[0]).cpu().numpy()
+    assert np.array_equal(got, lst)
+    del got, lst
+    lst = oracle.list_sym2(8192)
+    got = st.unrank_device(2, 8192, 0, 0, lst.shape[0]).cpu().numpy()
+    assert np.array_equal(got, lst)
+    del got, lst
+    got = st.unrank_device(4, 512, 8, 0, 8632).cpu().numpy()
+    assert np.array_equal(got, oracle.list_band(512, 8))
+    # 64-bit device path (n above the 32-bit range of the kernels' arithmetic)
+    n = 1100
+    lst = oracle.list_sym3(n)
+    p0 = lst.shape[0] - 300_000
+    got = st.unrank_device(3, n, 0, p0, 300_000).cpu().numpy()
+    assert np.array_equal(got, lst[p0:])
+
+
+# ---------------------------------------------------------------------- expand
+@pytest.mark.parametrize("n", [1, 2, 5, 12, 33, 64])
+def test_expand_order3(st, oracle, n):
+    say("expand order 3 n=%d" % n)
+    Sc = W.uniform(101, oracle.count_sym3(n))
+    ref = oracle.expand_sym(Sc, n, 3)
+    got = st.expand_sym(dev(Sc), n, 3).cpu().numpy()
+    assert np.array_equal(got.view(np.uint32), ref.view(np.uint32))
+    for perm in itertools.permutations(range(3)):
+        assert np.array_equal(got, np.transpose(got, perm))
+    idx = oracle.list_sym3(n).astype(np.int64)
+    assert np.array_equal(got[idx[:, 0], idx[:, 1], idx[:, 2]], Sc)
+
+
+@pytest.mark.parametrize("n", [1, 7, 64, 100, 1001])
+def test_expand_order2(st, oracle, n):
+    say("expand order 2 n=%d" % n)
+    Sc = W.uniform(102, oracle.count_sym2(n))
+    ref = oracle.expand_sym(Sc, n, 2)
+    got = st.expand_sym(dev(Sc), n, 2).cpu().numpy()
+    assert np.array_equal(got.view(np.uint32), ref.view(np.uint32))
+
+
+# ----------------------------------------------------------------------- batax
+@pytest.mark.parametrize("n", [1, 2, 5, 33, 100, 257, 1000, 4096, 4100, 8200])
+def test_batax_small(st, oracle, n):
+    say("batax n=%d" % n)
+    Ap = W.uniform(201, oracle.count_sym2(n))
+    x = W.uniform(202, n)
+    ref = oracle.batax_utri(Ap, x, 0.5)
+    got = st.batax_utri(dev(Ap), dev(x), 0.5).cpu().numpy()
+    assert rel_err(got, ref) <= TOL
+    got2 = st.batax_utri(dev(Ap), dev(x), 0.5).cpu().numpy()
+    assert np.array_equal(got, got2)                      # deterministic
+
+
+def test_batax_identity(st, oracle):
+    n = 300
+    eye = np.eye(n, dtype=np.float32)[np.triu_indices(n)]
+    x = W.uniform(203, n)
+    got = st.batax_utri(dev(eye), dev(x), 0.75).cpu().numpy()
+    assert np.array_equal(got, (np.float32(0.75) * x))
+
+
+def test_batax_full(st, oracle):
+    cfg = W.CONFIGS[2]
+    say("batax full n=%d" % cfg["n"])
+    Ap, x = W.batax_inputs(cfg["n"], cfg["entries"])
+    ref = oracle.batax_utri(Ap, x, cfg["beta"])
+    got = st.batax_utri(dev(Ap), dev(x), cfg["beta"]).cpu().numpy()
+    err = rel_err(got, ref)
+    say("  norm-wise error %.3e" % err)
+    assert err <= TOL
+
+
+# ------------------------------------------------------------------------- ttm
+@pytest.mark.parametrize("n,w,nl,R", [(1, 0, 1, 1), (7, 2, 5, 4), (9, 0, 16, 16), (40, 3, 32, 16),
+                                      (64, 8, 48, 32), (33, 40, 64, 64), (50, 4, 80, 48),
+                                      (30, 2, 1040, 256), (20, 3, 16, 272)])
+def test_ttm_small(st, oracle, n, w, nl, R):
+    say("ttm n=%d w=%d nl=%d R=%d" % (n, w, nl, R))
+    nb = oracle.count_band(n, w)
+    Tc = W.uniform(301, nb * nl).reshape(nb, nl)
+    U = W.uniform(302, nl * R).reshape(nl, R)
+    ref = oracle.ttm_band(Tc, U, n, w)
+    got = st.ttm_band(dev(Tc), dev(U), n, w).cpu().numpy()
+    assert got.shape == ref.shape
+    assert rel_err(got, ref) <= TOL
+
+
+def test_ttm_identity_factor(st, oracle):
+    n, w, nl = 24, 3, 32
+    nb = oracle.count_band(n, w)
+    Tc = W.uniform(303, nb * nl).reshape(nb, nl)
+    got = st.ttm_band(dev(Tc), dev(np.eye(nl, dtype=np.float32)), n, w).cpu().numpy()
+    assert np.array_equal(got, Tc)
+
+
+def test_ttm_full(st, oracle):
+    cfg = W.CONFIGS[3]
+    say("ttm full", cfg)
+    Tc, U = W.ttm_inputs(cfg["band_pairs"], cfg["nl"], cfg["R"])
+    ref = oracle.ttm_band(Tc, U, cfg["n"], cfg["w"])
+    got = st.ttm_band(dev(Tc), dev(U), cfg["n"], cfg["w"]).cpu().numpy()
+    err = rel_err(got, ref)
+    say("  norm-wise error %.3e" % err)
+    assert err <= TOL
+
+
+# --------------------------------------------------------------------- moment3
+@pytest.mark.parametrize("N,n", [(1, 5), (7, 4), (50, 9), (300, 17), (1000, 33), (100, 64), (5000, 64),
+                                 (70, 1), (200, 70)])
+def test_moment3_small(st, oracle, N, n):
+    say("moment3 N=%d n=%d" % (N, n))
+    X = W.normal(401, N * n).reshape(N, n)
+    lst = oracle.list_sym3(n)
+    ref = oracle.moment3_entries(X, lst)
+    got = st.moment3_sym(dev(X)).cpu().numpy()
+    assert got.shape == ref.shape
+    assert rel_err(got, ref) <= TOL
+    got2 = st.moment3_sym(dev(X)).cpu().numpy()
+    assert np.array_equal(got, got2)                      # deterministic
+
+
+def test_moment3_accumulate_and_empty(st, oracle):
+    import torch
+    N, n = 600, 20
+    X = W.normal(402, N * n).reshape(N, n)
+    ref = oracle.moment3_entries(X, oracle.list_sym3(n))
+    Sc = st.moment3_sym(dev(X[:250]))
+    Sc = st.moment3_sym(dev(X[250:]), Sc=Sc, accumulate=True)
+    assert rel_err(Sc.cpu().numpy(), ref) <= TOL
+    # N = 0: overwrite gives zeros, accumulate leaves Sc alone
+    empty = torch.empty((0, n), dtype=torch.float32, device="cuda")
+    keep = Sc.clone()
+    st.moment3_sym(empty, Sc=Sc, accumulate=True)
+    assert torch.equal(Sc, keep)
+    st.moment3_sym(empty, Sc=Sc, accumulate=False)
+    assert float(Sc.abs().max()) == 0.0
+
+
+def test_moment3_unit_vectors(st):
+    n, N = 64, 777
+    X = np.zeros((N, n), dtype=np.float32)
+    X[:, 37] = 1.0
+    got = st.moment3_sym(dev(X)).cpu().numpy()
+    p = st.rank_sym3(n, 37, 37, 37)
+    assert got[p] == N and np.count_nonzero(got) == 1
+
+
+def test_moment3_full(st, oracle):
+    cfg = W.CONFIGS[5]
+    N, n = cfg["N"], cfg["n"]
+    say("moment3 full N=%d n=%d: generating" % (N, n))
+    X = W.moment_inputs(N, n)
+    say("  running")
+    Sc = st.moment3_sym(dev(X))
+    got = Sc.cpu().numpy()
+    rng = np.random.default_rng(5)
+    lst = oracle.list_sym3(n)
+    pick = np.unique(np.concatenate([rng.integers(0, lst.shape[0], 700),
+                                     [0, lst.shape[0] - 1, st.rank_sym3(n, 0, 0, 63), st.rank_sym3(n, 15, 16, 17),
+                                      st.rank_sym3(n, 3, 3, 3), st.rank_sym3(n, 0, 63, 63)]]))
+    say("  oracle on %d sampled entries" % pick.size)
+    ref = oracle.moment3_entries(X, lst[pick])
+    scale = np.abs(ref).max()
+    err = float(np.abs(got[pick] - ref).max() / scale)
+    say("  norm-wise error on the sample %.3e" % err)
+    assert err <= TOL
+    # property that holds at any size: sum_p mult(p) Sc(p) = sum_s (1^T x_s)^3
+    i, j, k = lst[:, 0], lst[:, 1], lst[:, 2]
+    mult = np.where((i == j) & (j == k), 1, np.where((i == j) | (j == k), 3, 6)).astype(np.float64)
+    lhs = float((mult * got.astype(np.float64)).sum())
+    rhs = float((X.astype(np.float64).sum(axis=1) ** 3).sum())
+    bound = TOL * float((mult * np.abs(got.astype(np.float64))).sum())
+    assert abs(lhs - rhs) <= bound
+    # expand the result (the second half of this workload) and check it bit-exactly
+    S = st.expand_sym(Sc, n, 3).cpu().numpy()
+    ref_S = oracle.expand_sym(got, n, 3)
+    assert np.array_equal(S.view(np.uint32), ref_S.view(np.uint32))
+
+
+# ---------------------------------------------------------------------- mttkrp
+@pytest.mark.parametrize("n,R", [(1, 1), (5, 4), (16, 16), (17, 3), (40, 16), (64, 16), (100, 20), (130, 64),
+                                 (48, 80)])
+def test_mttkrp_small(st, oracle, n, R):
+    say("mttkrp n=%d R=%d" % (n, R))
+    Tc, B = W.mttkrp_inputs(n, R, oracle.count_sym3(n), "uniform", config_index=1)
+    ref = oracle.mttkrp_sym3(Tc, B)
+    got = st.mttkrp_sym3(dev(Tc), dev(B)).cpu().numpy()
+    assert rel_err(got, ref) <= TOL
+    got2 = st.mttkrp_sym3(dev(Tc), dev(B)).cpu().numpy()
+    assert np.array_equal(got, got2)                      # deterministic
+
+
+def test_mttkrp_all_ones(st):
+    n, R = 70, 8
+    B = W.uniform(501, n * R).reshape(n, R)
+    ones = np.ones(st.count_sym3(n), dtype=np.float32)
+    got = st.mttkrp_sym3(dev(ones), dev(B)).cpu().numpy()
+    ref = np.tile(B.astype(np.float64).sum(axis=0) ** 2, (n, 1))
+    assert rel_err(got, ref) <= TOL
+
+
+def test_mttkrp_full(st, oracle):
+    cfg = W.CONFIGS[4]
+    n, R = cfg["n"], cfg["R"]
+    say("mttkrp full n=%d R=%d: generating" % (n, R))
+    Tc, B = W.mttkrp_inputs(n, R, cfg["entries"], cfg["b_dist"], config_index=4)
+    got = st.mttkrp_sym3(dev(Tc), dev(B)).cpu().numpy()
+    rows = np.array([0, 1, 15, 16, 17, 100, 255, 256, 300, 400, 495, 496, 510, 511], dtype=np.int64)
+    say("  oracle on %d sampled rows" % rows.size)
+    ref = oracle.mttkrp_sym3(Tc, B, rows=rows)
+    scale = np.abs(ref).max()
+    err = float(np.abs(got[rows] - ref).max() / scale)
+    say("  norm-wise error on the sampled rows %.3e" % err)
+    assert err <= TOL
+    assert np.all(np.isfinite(got))
