@@ -3,7 +3,7 @@
 // One-pass kernel (n <= 8192).  The packed matrix is streamed from HBM once:
 // a row has to stay on chip between its use in t_i = A(i,:) x and its use in
 // y += t_i A(i,:), so a workgroup of 1024 threads holds whole rows in
-// registers.  Thread `tid` owns the fixed columns 4*(tid + 1024 v) .. +3, keeps
+// registers.  Thread `tid` owns the fixed columns 4*(tid + 1024 v) .. +3, v < 2, keeps
 // x and its partial y for those columns in registers for the whole kernel, and
 // rows are dealt to workgroups round-robin (row i -> workgroup i mod G), which
 // balances the triangular row lengths.  Per batch of RB rows: every thread
@@ -24,8 +24,14 @@ namespace st {
 
 typedef uint32_t u32;
 
-constexpr int BT = 1024;   // threads per workgroup (16 waves)
-constexpr int RB = 4;      // rows per batch
+#ifndef ST_BATAX_BT
+#define ST_BATAX_BT 1024
+#endif
+#ifndef ST_BATAX_RB
+#define ST_BATAX_RB 4
+#endif
+constexpr int BT = ST_BATAX_BT;   // threads per workgroup
+constexpr int RB = ST_BATAX_RB;   // rows per batch
 constexpr int GMAX = 256;  // workgroups of the one-pass kernel (one per CU)
 
 struct __attribute__((packed, aligned(4))) f4u { float x, y, z, w; };
@@ -50,7 +56,13 @@ __device__ __forceinline__ float wave_sum(float v)
     return (r0 + r1) + (r2 + r3);
 }
 
-template <int V>
+// Raw (unmasked) pieces of RB rows.  FAST (n % 4 == 0, n >= 4): branch free, so
+// that all loads of a batch are in flight together -- a group of four columns
+// that starts left of the diagonal is read from up to three entries before the
+// row start (the tail of the previous row, always inside the array for i >= 1),
+// groups entirely outside the row read position 0; mask_batch zeroes what does
+// not belong to the row.  Otherwise: guarded element loads.
+template <int V, bool FAST>
 __device__ __forceinline__ void load_batch(float4 (&a)[RB][V], const float *__restrict__ Ap, u32 n,
                                            u32 row0, u32 rstride, u32 tid)
 {
@@ -60,23 +72,43 @@ __device__ __forceinline__ void load_batch(float4 (&a)[RB][V], const float *__re
 #pragma unroll
         for (int v = 0; v < V; ++v) {
             u32 c0 = 4u * (tid + (u32)BT * v);
-            float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (i < n && c0 + 3u >= i && c0 < n) {
-                const float *rowp = Ap + row_sym2<u32>(n, i);   // address of A(i,i)
-                if (c0 >= i && c0 + 3u < n) {
-                    f4u t = *reinterpret_cast<const f4u *>(rowp + (c0 - i));
-                    val = make_float4(t.x, t.y, t.z, t.w);
-                } else {
-                    float e[4];
+            if constexpr (FAST) {
+                bool touch = i < n && c0 + 3u >= i && c0 < n;
+                u32 pos = touch ? row_sym2<u32>(n, i) + c0 - i : 0u;   // c0 - i may wrap: sum is exact mod 2^32
+                // byte offset in 32 bits (n <= 8192: the array is below 2^28 bytes): scalar base + vector offset
+                f4u t = *reinterpret_cast<const f4u *>(reinterpret_cast<const char *>(Ap) + (pos << 2));
+                a[r][v] = make_float4(t.x, t.y, t.z, t.w);
+            } else {
+                float e[4] = {0.f, 0.f, 0.f, 0.f};
+                if (i < n) {
+                    const float *rowp = Ap + row_sym2<u32>(n, i);
 #pragma unroll
                     for (u32 q = 0; q < 4; ++q) {
                         u32 c = c0 + q;
-                        e[q] = (c >= i && c < n) ? rowp[c - i] : 0.f;
+                        if (c >= i && c < n) e[q] = rowp[c - i];
                     }
-                    val = make_float4(e[0], e[1], e[2], e[3]);
                 }
+                a[r][v] = make_float4(e[0], e[1], e[2], e[3]);
             }
-            a[r][v] = val;
+        }
+    }
+}
+
+template <int V>
+__device__ __forceinline__ void mask_batch(float4 (&a)[RB][V], u32 n, u32 row0, u32 rstride, u32 tid)
+{
+#pragma unroll
+    for (int r = 0; r < RB; ++r) {
+        u32 i = row0 + (u32)r * rstride;
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            u32 c0 = 4u * (tid + (u32)BT * v);
+            // element q of the group is in the row iff q >= i - c0 (and the row / group exist)
+            int d = (i < n && c0 < n) ? (int)i - (int)c0 : 4;
+            a[r][v].x = (0 >= d) ? a[r][v].x : 0.f;
+            a[r][v].y = (1 >= d) ? a[r][v].y : 0.f;
+            a[r][v].z = (2 >= d) ? a[r][v].z : 0.f;
+            a[r][v].w = (3 >= d) ? a[r][v].w : 0.f;
         }
     }
 }
@@ -86,6 +118,8 @@ __device__ __forceinline__ void process_batch(const float4 (&a)[RB][V], const fl
                                               float4 (&ya)[V], float (*red)[RB][BT / 64], int pb,
                                               u32 lane, u32 wave)
 {
+    constexpr int NW = BT / 64;
+    static_assert(NW * RB <= 64 && (NW == 4 || NW == 8 || NW == 16), "cross-wave reduction layout");
     float p[RB];
 #pragma unroll
     for (int r = 0; r < RB; ++r) {
@@ -100,11 +134,17 @@ __device__ __forceinline__ void process_batch(const float4 (&a)[RB][V], const fl
         for (int r = 0; r < RB; ++r) red[pb][r][wave] = p[r];
     }
     __syncthreads();
+    // Every wave adds the NW wave partials of each row in the same fixed tree:
+    // lane l holds partial (row l / NW, wave l % NW); DPP adds inside aligned
+    // groups of NW lanes; the row sums are then read as wave-uniform scalars.
+    float c = (lane < (u32)(NW * RB)) ? (&red[pb][0][0])[lane] : 0.f;
+    c += dpp_f<0xB1>(c);
+    c += dpp_f<0x4E>(c);
+    if constexpr (NW >= 8) c += dpp_f<0x141>(c);
+    if constexpr (NW >= 16) c += dpp_f<0x140>(c);
 #pragma unroll
     for (int r = 0; r < RB; ++r) {
-        float t = 0.f;
-#pragma unroll
-        for (int w = 0; w < BT / 64; ++w) t += red[pb][r][w];   // same order in every thread
+        const float t = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, c), r * NW));
 #pragma unroll
         for (int v = 0; v < V; ++v) {
             ya[v].x += t * a[r][v].x; ya[v].y += t * a[r][v].y;
@@ -113,7 +153,7 @@ __device__ __forceinline__ void process_batch(const float4 (&a)[RB][V], const fl
     }
 }
 
-template <int V>
+template <int V, bool FAST>
 __global__ __launch_bounds__(BT) void batax_onepass_kernel(const float *__restrict__ Ap,
                                                           const float *__restrict__ x,
                                                           float *__restrict__ part, u32 n, u32 npad,
@@ -137,12 +177,18 @@ __global__ __launch_bounds__(BT) void batax_onepass_kernel(const float *__restri
     const u32 nrows = (n > g) ? (n - g + G - 1) / G : 0;
     const u32 nb = (nrows + RB - 1) / RB;
     float4 a0[RB][V], a1[RB][V];
-    load_batch<V>(a0, Ap, n, g, G, tid);
+    load_batch<V, FAST>(a0, Ap, n, g, G, tid);
     for (u32 b = 0; b < nb; b += 2) {
-        load_batch<V>(a1, Ap, n, g + G * RB * (b + 1), G, tid);
+        load_batch<V, FAST>(a1, Ap, n, g + G * RB * (b + 1), G, tid);
+        __builtin_amdgcn_sched_barrier(0);
+        mask_batch<V>(a0, n, g + G * RB * b, G, tid);
         process_batch<V>(a0, xs, ya, red, 0, lane, wave);
-        load_batch<V>(a0, Ap, n, g + G * RB * (b + 2), G, tid);
+        __builtin_amdgcn_sched_barrier(0);
+        load_batch<V, FAST>(a0, Ap, n, g + G * RB * (b + 2), G, tid);
+        __builtin_amdgcn_sched_barrier(0);
+        mask_batch<V>(a1, n, g + G * RB * (b + 1), G, tid);
         process_batch<V>(a1, xs, ya, red, 1, lane, wave);
+        __builtin_amdgcn_sched_barrier(0);
     }
 
     float *dst = part + (size_t)g * npad;
@@ -153,26 +199,39 @@ __global__ __launch_bounds__(BT) void batax_onepass_kernel(const float *__restri
     }
 }
 
-// y[j] = beta * sum_g part[g][j], g ascending inside 8 slices, slices ascending.
+// y[j] = beta * sum_g part[g][j]: a block owns 8 groups of four columns and cuts
+// the G partials into 32 slices (g ascending inside a slice, slices ascending).
 __global__ __launch_bounds__(256) void batax_reduce_kernel(const float *__restrict__ part,
                                                           float *__restrict__ y, u32 n, u32 npad, u32 G,
                                                           float beta)
 {
-    __shared__ float acc[8][32];
-    u32 cx = threadIdx.x & 31u, sl = threadIdx.x >> 5;
-    u32 j = blockIdx.x * 32u + cx;
-    u32 per = (G + 7u) / 8u;
-    u32 g0 = sl * per, g1 = min(G, g0 + per);
-    float s = 0.f;
-    if (j < n)
-        for (u32 g = g0; g < g1; ++g) s += part[(size_t)g * npad + j];
-    acc[sl][cx] = s;
+    __shared__ float4 acc[32][8];
+    const u32 cq = threadIdx.x & 7u, sl = threadIdx.x >> 3;
+    const u32 c0 = (blockIdx.x * 8u + cq) * 4u;
+    const u32 per = (G + 31u) / 32u;
+    const u32 g0 = min(G, sl * per), g1 = min(G, g0 + per);
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (c0 < npad) {
+        const float *src = part + c0;
+#pragma unroll 8
+        for (u32 g = g0; g < g1; ++g) {
+            float4 v = *reinterpret_cast<const float4 *>(src + (size_t)g * npad);
+            s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+        }
+    }
+    acc[sl][cq] = s;
     __syncthreads();
-    if (sl == 0 && j < n) {
-        float t = 0.f;
+    if (sl == 0 && c0 < npad) {
+        float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-        for (int q = 0; q < 8; ++q) t += acc[q][cx];
-        y[j] = beta * t;
+        for (int q = 0; q < 32; ++q) {
+            float4 v = acc[q][cq];
+            t.x += v.x; t.y += v.y; t.z += v.z; t.w += v.w;
+        }
+        float e[4] = {beta * t.x, beta * t.y, beta * t.z, beta * t.w};
+#pragma unroll
+        for (u32 q = 0; q < 4; ++q)
+            if (c0 + q < n) y[c0 + q] = e[q];
     }
 }
 
@@ -202,13 +261,26 @@ __global__ __launch_bounds__(256) void batax_aty_kernel(const float *__restrict_
     y[j] = beta * s;
 }
 
+constexpr int NMAX_ONEPASS = 8192;          // rows of up to 32 KB stay in one workgroup's registers
+constexpr int VMAX = NMAX_ONEPASS / (4 * BT);
+
 static inline u32 onepass_grid(int n) { return (u32)(n < GMAX ? n : GMAX); }
 static inline u32 pad4(int n) { return ((u32)n + 3u) & ~3u; }
 
 size_t batax_workspace(int n)
 {
-    if (n <= 2 * 4 * BT) return (size_t)onepass_grid(n) * pad4(n) * sizeof(float);
+    if (n <= NMAX_ONEPASS) return (size_t)onepass_grid(n) * pad4(n) * sizeof(float);
     return (size_t)pad4(n) * sizeof(float);
+}
+
+template <int V>
+static void launch_onepass(bool fast, u32 G, hipStream_t s, const float *Ap, const float *x, float *wsf, u32 un,
+                           u32 npad)
+{
+    if (fast)
+        hipLaunchKernelGGL((batax_onepass_kernel<V, true>), dim3(G), dim3(BT), 0, s, Ap, x, wsf, un, npad, G);
+    else
+        hipLaunchKernelGGL((batax_onepass_kernel<V, false>), dim3(G), dim3(BT), 0, s, Ap, x, wsf, un, npad, G);
 }
 
 st_status launch_batax(const float *Ap, const float *x, float *y, int n, float beta, void *ws,
@@ -216,14 +288,16 @@ st_status launch_batax(const float *Ap, const float *x, float *y, int n, float b
 {
     u32 un = (u32)n;
     float *wsf = static_cast<float *>(ws);
-    if (n <= 2 * 4 * BT) {
+    if (n <= NMAX_ONEPASS) {
         u32 G = onepass_grid(n), npad = pad4(n);
-        if (n <= 4 * BT)
-            hipLaunchKernelGGL(batax_onepass_kernel<1>, dim3(G), dim3(BT), 0, s, Ap, x, wsf, un, npad, G);
-        else
-            hipLaunchKernelGGL(batax_onepass_kernel<2>, dim3(G), dim3(BT), 0, s, Ap, x, wsf, un, npad, G);
+        const bool fast = (n % 4 == 0) && n >= 4;
+        int V = (n + 4 * BT - 1) / (4 * BT);
+        if (V <= 1) launch_onepass<1>(fast, G, s, Ap, x, wsf, un, npad);
+        else if (V == 2) launch_onepass<2>(fast, G, s, Ap, x, wsf, un, npad);
+        else if (V <= 4) launch_onepass<(VMAX >= 4 ? 4 : VMAX)>(fast, G, s, Ap, x, wsf, un, npad);
+        else launch_onepass<VMAX>(fast, G, s, Ap, x, wsf, un, npad);
         if (hipGetLastError() != hipSuccess) return ST_ERR_LAUNCH;
-        hipLaunchKernelGGL(batax_reduce_kernel, dim3((un + 31u) / 32u), dim3(256), 0, s, wsf, y, un, npad,
+        hipLaunchKernelGGL(batax_reduce_kernel, dim3((npad / 4u + 7u) / 8u), dim3(256), 0, s, wsf, y, un, npad,
                            G, beta);
         return launch_status();
     }

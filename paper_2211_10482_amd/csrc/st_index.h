@@ -20,11 +20,9 @@ namespace st {
 template <typename I> ST_HD I tri(I m) { return m * (m + 1) / 2; }            // 1+2+..+m
 template <typename I> ST_HD I tet(I m)                                       // tri(1)+..+tri(m)
 {
-    // one of m, m+1 is even; one of m, m+1, m+2 is a multiple of 3
-    I a = m, b = m + 1, c = m + 2;
-    if (a % 2 == 0) a /= 2; else b /= 2;
-    if (a % 3 == 0) a /= 3; else if (b % 3 == 0) b /= 3; else c /= 3;
-    return a * b * c;
+    // tri(m) is exact and tri(m)*(m+2) = 3*tet(m): one division by a constant, no
+    // branches.  The intermediate is 3*tet(m), so 32-bit use is valid to m = 2047.
+    return tri<I>(m) * (m + 2) / 3;
 }
 
 template <typename I> ST_HD I count_sym2(I n) { return tri<I>(n); }

@@ -19,10 +19,14 @@
 //     16-byte loads, transposed into the tile by the LDS writes;
 //   * any two blocks equal (or a ragged last block): per element sort + closed
 //     form rank3 gather.
-// Each of the 4 waves then owns 16 columns r: per p one ds_read_b128 of D (lane =
-// (x, q-quad); the four components feed four MFMAs with consistently permuted K
-// slots), four VALU multiplies for the Khatri-Rao operand, four MFMAs.
-// Workgroup partials go to the workspace; a second kernel adds them in order.
+// The 16 x 64 blocks of B for P (pre-scaled by w) and Q are staged beside it.
+// Staging is software pipelined: while visit v is multiplied, visit v+1 sits in
+// the second LDS buffer and the loads of visit v+2 are in flight in registers;
+// one barrier per visit.  Each of the 4 waves owns 16 columns r: per p one
+// ds_read_b128 of D (lane = (x, q-quad); the four components feed four MFMAs
+// with consistently permuted K slots and separate accumulators), four VALU
+// multiplies for the Khatri-Rao operand, four MFMAs.  Workgroup partials go to
+// the workspace; a second kernel adds them in a fixed order.
 //
 // Algorithmic traffic: 4 bytes per stored entry (each read by three owners,
 // two of them out of cache) + B + M.
@@ -36,6 +40,8 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 constexpr u32 XS = 260;            // LDS stride between x-planes of the tile (16*16 + 4 pad)
 constexpr u32 TILE_F = 16 * XS;    // floats per staged tile
+constexpr u32 BS = 68;             // LDS row stride of a staged 16 x 64 block of B (bank spread)
+constexpr u32 BBLK_F = 16 * BS;
 
 struct __attribute__((packed, aligned(4))) f4u { float x, y, z, w; };
 
@@ -46,93 +52,200 @@ __device__ __forceinline__ void sort3u(u32 &a, u32 &b, u32 &c)
     a = mn; b = md; c = mx;
 }
 
+// One visit = (row block X, block pair P <= Q).  kind: 0 runs along q, 1 runs
+// along x (transposed into the tile), 2 per-element gather.
+struct Visit {
+    u32 p0, q0;
+    int kind;
+    float wgt;
+};
+
+__device__ __forceinline__ Visit decode_visit(u32 NB, u32 pi, u32 X, u32 n)
+{
+    u32 P, Q;
+    unrank_sym2<u32>(NB, pi, P, Q);
+    Visit v;
+    v.p0 = P * 16u;
+    v.q0 = Q * 16u;
+    const bool full = max(X, Q) * 16u + 16u <= n;
+    v.kind = (full && Q > X && Q > P && X != P) ? 0 : (full && X > Q && Q > P) ? 1 : 2;
+    v.wgt = (P < Q) ? 2.f : 1.f;
+    return v;
+}
+
+// Global -> registers for one visit: 16 tile values and one float4 of each staged
+// B block per thread.  All loads are unconditional (addresses clamped) and their
+// results are not touched here, so that they stay in flight while the previous
+// visit is being multiplied; `mask` records which of them are real (bits 0..15
+// tile values, 16..19 P-block, 20..23 Q-block) for store_visit to apply.
+__device__ __forceinline__ void load_visit(const Visit &v, const float *__restrict__ Tc,
+                                           const float *__restrict__ B, u32 n, u32 R, u32 x0, u32 rbase,
+                                           u32 tid, float (&pf)[16], float4 &pb, float4 &qb, u32 &mask)
+{
+    mask = 0xffffu;
+    if (v.kind == 0) {
+        // D[x][p][q] = Tc[run(min, max) + (q0 + q - max)], 16 consecutive q per (x, p)
+#pragma unroll
+        for (u32 it = 0; it < 4; ++it) {
+            u32 e = tid + 256u * it, row = e >> 2, qr = e & 3u;
+            u32 a = min(x0 + (row >> 4), v.p0 + (row & 15u)), b = max(x0 + (row >> 4), v.p0 + (row & 15u));
+            f4u t = *reinterpret_cast<const f4u *>(Tc + run_sym3<u32>(n, a, b) + (v.q0 - b) + 4u * qr);
+            pf[4 * it] = t.x; pf[4 * it + 1] = t.y; pf[4 * it + 2] = t.z; pf[4 * it + 3] = t.w;
+        }
+    } else if (v.kind == 1) {
+        // D[x][p][q] = Tc[run(p, q) + (x0 + x - q)], 16 consecutive x per (p, q)
+#pragma unroll
+        for (u32 it = 0; it < 4; ++it) {
+            u32 e = tid + 256u * it, row = e >> 2, xr = e & 3u;
+            u32 pp = v.p0 + (row >> 4), qq = v.q0 + (row & 15u);
+            f4u t = *reinterpret_cast<const f4u *>(Tc + run_sym3<u32>(n, pp, qq) + (x0 - qq) + 4u * xr);
+            pf[4 * it] = t.x; pf[4 * it + 1] = t.y; pf[4 * it + 2] = t.z; pf[4 * it + 3] = t.w;
+        }
+    } else {
+        mask = 0;
+#pragma unroll
+        for (u32 it = 0; it < 16; ++it) {
+            u32 e = tid + 256u * it;
+            u32 a = x0 + (e >> 8), b = v.p0 + ((e >> 4) & 15u), c = v.q0 + (e & 15u);
+            sort3u(a, b, c);
+            const bool ok = c < n;
+            pf[it] = Tc[ok ? rank_sym3<u32>(n, a, b, c) : 0u];
+            mask |= ok ? (1u << it) : 0u;
+        }
+    }
+    // rows p0 + tid/16 and q0 + tid/16 of B, columns rbase + 4*(tid%16) .. +3
+    const u32 row = tid >> 4, col = rbase + 4u * (tid & 15u);
+    float e[2][4];
+#pragma unroll
+    for (u32 h = 0; h < 2; ++h) {
+        const u32 gr = (h == 0 ? v.p0 : v.q0) + row;
+        if ((R & 3u) == 0) {
+            const bool ok = gr < n && col < R;
+            float4 t = *reinterpret_cast<const float4 *>(B + (ok ? (size_t)gr * R + col : 0));
+            e[h][0] = t.x; e[h][1] = t.y; e[h][2] = t.z; e[h][3] = t.w;
+            mask |= ok ? (0xfu << (16u + 4u * h)) : 0u;
+        } else {
+#pragma unroll
+            for (u32 q = 0; q < 4; ++q) {
+                const bool ok = gr < n && col + q < R;
+                e[h][q] = B[ok ? (size_t)gr * R + col + q : 0];
+                mask |= ok ? (1u << (16u + 4u * h + q)) : 0u;
+            }
+        }
+    }
+    pb = make_float4(e[0][0], e[0][1], e[0][2], e[0][3]);
+    qb = make_float4(e[1][0], e[1][1], e[1][2], e[1][3]);
+}
+
+// Registers -> LDS (dense tile D[x][p][q] with x-stride XS, and the two B blocks;
+// the P block is pre-scaled by the pair weight).
+__device__ __forceinline__ void store_visit(int kind, float wgt, float *__restrict__ tile,
+                                            float *__restrict__ bp, float *__restrict__ bq, u32 tid,
+                                            const float (&pf)[16], const float4 &pb, const float4 &qb, u32 mask)
+{
+    if (kind == 0) {
+#pragma unroll
+        for (u32 it = 0; it < 4; ++it) {
+            u32 e = tid + 256u * it, row = e >> 2, qr = e & 3u;
+            *reinterpret_cast<float4 *>(&tile[(row >> 4) * XS + (row & 15u) * 16u + 4u * qr]) =
+                make_float4(pf[4 * it], pf[4 * it + 1], pf[4 * it + 2], pf[4 * it + 3]);
+        }
+    } else if (kind == 1) {
+#pragma unroll
+        for (u32 it = 0; it < 4; ++it) {
+            u32 e = tid + 256u * it, row = e >> 2, xr = e & 3u;
+            float *d = &tile[(4u * xr) * XS + (row >> 4) * 16u + (row & 15u)];
+            d[0] = pf[4 * it]; d[XS] = pf[4 * it + 1]; d[2 * XS] = pf[4 * it + 2]; d[3 * XS] = pf[4 * it + 3];
+        }
+    } else {
+#pragma unroll
+        for (u32 it = 0; it < 16; ++it) {
+            u32 e = tid + 256u * it;
+            tile[(e >> 8) * XS + ((e >> 4) & 15u) * 16u + (e & 15u)] = ((mask >> it) & 1u) ? pf[it] : 0.f;
+        }
+    }
+    const u32 o = (tid >> 4) * BS + 4u * (tid & 15u);
+    *reinterpret_cast<float4 *>(&bp[o]) =
+        make_float4(((mask >> 16) & 1u) ? wgt * pb.x : 0.f, ((mask >> 17) & 1u) ? wgt * pb.y : 0.f,
+                    ((mask >> 18) & 1u) ? wgt * pb.z : 0.f, ((mask >> 19) & 1u) ? wgt * pb.w : 0.f);
+    *reinterpret_cast<float4 *>(&bq[o]) =
+        make_float4(((mask >> 20) & 1u) ? qb.x : 0.f, ((mask >> 21) & 1u) ? qb.y : 0.f,
+                    ((mask >> 22) & 1u) ? qb.z : 0.f, ((mask >> 23) & 1u) ? qb.w : 0.f);
+}
+
 __global__ __launch_bounds__(256) void mttkrp_mfma_kernel(const float *__restrict__ Tc,
                                                         const float *__restrict__ B,
                                                         float *__restrict__ part, u32 n, u32 R, u32 NB,
                                                         u32 npairs, u32 PPC, u32 NCH, u32 Rpad)
 {
-    __shared__ __attribute__((aligned(16))) float tile[TILE_F];
+    __shared__ __attribute__((aligned(16))) float tile[2][TILE_F];
+    __shared__ __attribute__((aligned(16))) float bpb[2][BBLK_F];
+    __shared__ __attribute__((aligned(16))) float bqb[2][BBLK_F];
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const u32 X = blockIdx.y, ch = blockIdx.x;
-    const u32 rt = blockIdx.z * 4u + wave;           // this wave's block of 16 columns of R
+    const u32 rbase = blockIdx.z * 64u;               // this workgroup's 64 columns of R
+    const u32 rt = blockIdx.z * 4u + wave;            // this wave's block of 16 columns
     const bool has_rt = rt * 16u < R;
     const u32 x0 = X * 16u;
     const u32 lrow = lane & 15u, lq = lane >> 4;
-    const u32 r = rt * 16u + lrow;                    // column of B / M handled as MFMA column
-    const bool r_ok = has_rt && r < R;
 
-    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    f32x4 acc[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
     const u32 pi0 = ch * PPC, pi1 = min(npairs, pi0 + PPC);
-    for (u32 pi = pi0; pi < pi1; ++pi) {
-        u32 P, Q;
-        unrank_sym2<u32>(NB, pi, P, Q);
-        const u32 p0 = P * 16u, q0 = Q * 16u;
-        const bool full = (max(x0, q0) + 16u <= n);
+    const u32 nv = pi1 - pi0;
 
-        __syncthreads();                              // previous visit's readers are done
-        if (full && Q > X && Q > P && X != P) {
-            // runs along q: D[x][p][q] = Tc[run(min, max) + (q0 + q - max)]
-#pragma unroll
-            for (u32 it = 0; it < 4; ++it) {
-                u32 e = tid + 256u * it, row = e >> 2, qr = e & 3u;
-                u32 x = row >> 4, p = row & 15u;
-                u32 a = min(x0 + x, p0 + p), b = max(x0 + x, p0 + p);
-                const float *src = Tc + run_sym3<u32>(n, a, b) + (q0 - b) + 4u * qr;
-                f4u v = *reinterpret_cast<const f4u *>(src);
-                *reinterpret_cast<float4 *>(&tile[x * XS + p * 16u + 4u * qr]) = make_float4(v.x, v.y, v.z, v.w);
-            }
-        } else if (full && X > Q && Q > P) {
-            // runs along x: D[x][p][q] = Tc[run(p, q) + (x0 + x - q)]
-#pragma unroll
-            for (u32 it = 0; it < 4; ++it) {
-                u32 e = tid + 256u * it, row = e >> 2, xr = e & 3u;
-                u32 p = row >> 4, q = row & 15u;
-                const float *src = Tc + run_sym3<u32>(n, p0 + p, q0 + q) + (x0 - (q0 + q)) + 4u * xr;
-                f4u v = *reinterpret_cast<const f4u *>(src);
-                float *d = &tile[(4u * xr) * XS + p * 16u + q];
-                d[0] = v.x; d[XS] = v.y; d[2 * XS] = v.z; d[3 * XS] = v.w;
-            }
-        } else {
-#pragma unroll 4
-            for (u32 it = 0; it < 16; ++it) {
-                u32 e = tid + 256u * it;
-                u32 x = e >> 8, p = (e >> 4) & 15u, q = e & 15u;
-                u32 a = x0 + x, b = p0 + p, c = q0 + q;
-                sort3u(a, b, c);
-                float v = 0.f;
-                if (c < n) v = Tc[rank_sym3<u32>(n, a, b, c)];
-                tile[x * XS + p * 16u + q] = v;
-            }
+    float pf[16];
+    float4 pb, qb;
+    u32 mask;
+    Visit cur = decode_visit(NB, pi0, X, n);
+    load_visit(cur, Tc, B, n, R, x0, rbase, tid, pf, pb, qb, mask);
+    store_visit(cur.kind, cur.wgt, tile[0], bpb[0], bqb[0], tid, pf, pb, qb, mask);
+    Visit nxt = cur;
+    if (nv > 1) {
+        nxt = decode_visit(NB, pi0 + 1, X, n);
+        load_visit(nxt, Tc, B, n, R, x0, rbase, tid, pf, pb, qb, mask);
+    }
+    __syncthreads();
+
+    for (u32 v = 0; v < nv; ++v) {
+        const u32 cb = v & 1u;
+        // registers hold visit v+1: park it in the other buffer (its last readers
+        // finished before the barrier that ended iteration v-1) ...
+        if (v + 1 < nv)
+            store_visit(nxt.kind, nxt.wgt, tile[cb ^ 1u], bpb[cb ^ 1u], bqb[cb ^ 1u], tid, pf, pb, qb, mask);
+        // ... and put visit v+2 in flight
+        if (v + 2 < nv) {
+            nxt = decode_visit(NB, pi0 + v + 2, X, n);
+            load_visit(nxt, Tc, B, n, R, x0, rbase, tid, pf, pb, qb, mask);
         }
-        __syncthreads();
-
+        __builtin_amdgcn_sched_barrier(0);
         if (has_rt) {
-            const float wgt = (P < Q) ? 2.f : 1.f;
-            float bq[4];
+            const float *bqp = &bqb[cb][(4u * lq) * BS + wave * 16u + lrow];
+            const float bq0 = bqp[0], bq1 = bqp[BS], bq2 = bqp[2 * BS], bq3 = bqp[3 * BS];
+            const float *bpp = &bpb[cb][wave * 16u + lrow];
+            const float *arow = &tile[cb][lrow * XS + 4u * lq];
 #pragma unroll
-            for (u32 t = 0; t < 4; ++t) {
-                u32 q = q0 + 4u * lq + t;
-                bq[t] = (r_ok && q < n) ? B[(size_t)q * R + r] : 0.f;
-            }
-            const float *arow = &tile[lrow * XS + 4u * lq];
-#pragma unroll 4
             for (u32 p = 0; p < 16; ++p) {
-                u32 pg = p0 + p;
-                float bp = (r_ok && pg < n) ? wgt * B[(size_t)pg * R + r] : 0.f;
-                f32x4 a = *reinterpret_cast<const f32x4 *>(arow + p * 16u);
-                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[0], bp * bq[0], acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[1], bp * bq[1], acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[2], bp * bq[2], acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[3], bp * bq[3], acc, 0, 0, 0);
+                const float bp = bpp[p * BS];
+                const f32x4 a = *reinterpret_cast<const f32x4 *>(arow + p * 16u);
+                acc[0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[0], bp * bq0, acc[0], 0, 0, 0);
+                acc[1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[1], bp * bq1, acc[1], 0, 0, 0);
+                acc[2] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[2], bp * bq2, acc[2], 0, 0, 0);
+                acc[3] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[3], bp * bq3, acc[3], 0, 0, 0);
             }
         }
+        __builtin_amdgcn_sched_barrier(0);
+        __syncthreads();
     }
 
     if (has_rt) {
         // D layout: lane holds column lane%16 of rows 4*(lane/16) + v
         float *dst = part + ((size_t)(X * NCH + ch) * 16u) * Rpad + rt * 16u + lrow;
 #pragma unroll
-        for (u32 v = 0; v < 4; ++v) dst[(size_t)(4u * lq + v) * Rpad] = acc[v];
+        for (u32 v = 0; v < 4; ++v)
+            dst[(size_t)(4u * lq + v) * Rpad] = (acc[0][v] + acc[1][v]) + (acc[2][v] + acc[3][v]);
     }
 }
 
@@ -159,7 +272,7 @@ static inline MttkrpPlan plan(int n, int R)
     p.NB = ((u32)n + 15u) / 16u;
     p.npairs = p.NB * (p.NB + 1u) / 2u;
     uint64_t visits = (uint64_t)p.NB * p.npairs;
-    p.PPC = (u32)((visits + 2047u) / 2048u);
+    p.PPC = (u32)((visits + 1535u) / 1536u);   // about 1536 workgroups: two rounds of three per CU
     if (p.PPC < 1u) p.PPC = 1u;
     p.NCH = (p.npairs + p.PPC - 1u) / p.PPC;
     p.RT = ((u32)R + 15u) / 16u;

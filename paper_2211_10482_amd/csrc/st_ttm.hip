@@ -29,16 +29,19 @@ constexpr int MAXR = 4;       // row tiles a wave keeps accumulators for at once
 
 // Stage rows [k0, k0+kc) of U (nl x R, row-major) into LDS in B-operand order:
 // value U(k0 + 16 s + 4 q + t, 16 ct + c) goes to ((s*CT + ct)*64 + 16 q + c)*4 + t.
+// A thread gathers the four rows t = 0..3 of one column (each of its loads is
+// coalesced along the column index across the wave) and writes them with one
+// conflict-free 16-byte LDS store.
 __device__ __forceinline__ void stage_u(float *lds, const float *__restrict__ U, u32 k0, u32 kc, u32 R,
                                         u32 CT, u32 tid, u32 nthreads)
 {
-    u32 rq = R / 4u;
-    for (u32 e = tid; e < kc * rq; e += nthreads) {
-        u32 k = e / rq, c4 = (e - k * rq) * 4u;
-        float4 v = *reinterpret_cast<const float4 *>(U + (size_t)(k0 + k) * R + c4);
-        u32 s = k >> 4, q = (k >> 2) & 3u, t = k & 3u, ct = c4 >> 4, c = c4 & 15u;
-        float *d = lds + ((size_t)((s * CT + ct) * 64u + 16u * q + c)) * 4u + t;
-        d[0] = v.x; d[4] = v.y; d[8] = v.z; d[12] = v.w;
+    const u32 kq = kc / 4u;
+    for (u32 e = tid; e < kq * R; e += nthreads) {
+        u32 k4 = e / R, col = e - k4 * R;
+        const float *src = U + (size_t)(k0 + 4u * k4) * R + col;
+        float4 v = make_float4(src[0], src[R], src[2 * (size_t)R], src[3 * (size_t)R]);
+        u32 s = k4 >> 2, q = k4 & 3u, ct = col >> 4, c = col & 15u;
+        *reinterpret_cast<float4 *>(lds + ((size_t)((s * CT + ct) * 64u + 16u * q + c)) * 4u) = v;
     }
 }
 
