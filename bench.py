@@ -90,7 +90,7 @@ def cpu_baseline(inputs):
     t_est += t * (512 / rows.size)
     parts.append("mttkrp n=512: %d of 512 rows %.2fs" % (rows.size, t))
     X = inputs["c5"]
-    ns = 500_000
+    ns = 100_000
     t = timed(lambda: oracle.moment3_dense(X[:ns]))
     t_est += t * (X.shape[0] / ns)
     parts.append("moment3: %d of %d samples %.2fs" % (ns, X.shape[0], t))
@@ -109,6 +109,9 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="after the timed region, run one plain 256 MiB device copy (a kernel of known "
+                         "traffic for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (--gpus 1); nothing here uses a second GPU")
@@ -184,6 +187,15 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    if args.copy_probe:
+        src = torch.empty(64 * 1024 * 1024, **f32)
+        src.fill_(1.0)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     wl = workloads()
     kernels = {}

@@ -21,7 +21,9 @@
 // unique entries, against 64^3 = 262,144 dense ones), 84 pair products per four
 // samples feed 208 MFMAs.  A workgroup (8 waves, 26 tiles = 104 accumulator
 // registers per wave) owns ALL accumulators and streams a contiguous slice of
-// the samples; X is read from HBM exactly once.  Workgroup partials go to the
+// the samples through a double-buffered LDS chunk of 64 samples that the whole
+// workgroup loads once (X is read from HBM exactly once; the loads of chunk c+2
+// are in flight while chunk c is multiplied).  Workgroup partials go to the
 // workspace in raw tile layout (coalesced) and a second kernel adds them in a
 // fixed order, drops the padding / duplicate positions and scatters through
 // rank3.  No float atomics.
@@ -94,96 +96,136 @@ __host__ __device__ constexpr TileDesc tile_desc(int w, int local)
     return TileDesc{1, (local - 22) % 2, 2, 3, 2 * w + (local - 22) / 2};
 }
 
-// Row s of X as the A operands of the four groups (component g = X(s, 4m+g)).
-// Branch free so that the loads can stay in flight across K-steps: load_raw
-// clamps the row index into the slice, mask_x (applied where the value is first
-// needed) zeroes the rows past its end.
+constexpr int M3_CH = 64;                          // samples per staged chunk (16 K-steps)
+constexpr int M3_THREADS = M3_WAVES * 64;
+constexpr int M3_LPT = M3_CH * 16 / M3_THREADS;    // 16-byte pieces of a chunk per thread (2)
+
+// A chunk of 64 samples is staged in LDS as [sample][64 columns] by the whole
+// workgroup (each row of X is fetched from HBM exactly once), columns >= n and
+// samples past the end of the slice as zeros.  load_chunk only issues the loads
+// (row clamped into the slice, nothing touches the results) so that they stay in
+// flight under the MFMAs of the previous chunks; store_chunk masks and writes.
 template <bool FULL>
-__device__ __forceinline__ f32x4 load_raw(const float *__restrict__ X, int64_t s, int64_t s_end, u32 n,
-                                          u32 m)
+__device__ __forceinline__ void load_chunk(f32x4 (&r)[M3_LPT], const float *__restrict__ X, int64_t s0,
+                                           int64_t s_end, u32 n, u32 tid)
 {
-    const int64_t sc = s < s_end ? s : s_end - 1;
-    f32x4 v;
-    if constexpr (FULL) {
-        float4 t = *reinterpret_cast<const float4 *>(X + sc * 64 + 4 * m);
-        v = (f32x4){t.x, t.y, t.z, t.w};
-    } else {
-        const float *row = X + sc * (int64_t)n;
 #pragma unroll
-        for (u32 g = 0; g < 4; ++g) {
-            u32 c = 4 * m + g;
-            v[g] = row[c < n ? c : n - 1];
+    for (int k = 0; k < M3_LPT; ++k) {
+        const u32 j = tid + (u32)M3_THREADS * k, smp = j >> 4, c0 = 4u * (j & 15u);
+        const int64_t s = s0 + smp, sc = s < s_end ? s : s_end - 1;
+        if constexpr (FULL) {
+            float4 t = *reinterpret_cast<const float4 *>(X + sc * 64 + c0);
+            r[k] = (f32x4){t.x, t.y, t.z, t.w};
+        } else {
+            const float *row = X + sc * (int64_t)n;
+#pragma unroll
+            for (u32 g = 0; g < 4; ++g) r[k][g] = row[c0 + g < n ? c0 + g : n - 1];
         }
     }
-    return v;
 }
 template <bool FULL>
-__device__ __forceinline__ f32x4 mask_x(f32x4 v, int64_t s, int64_t s_end, u32 n, u32 m)
+__device__ __forceinline__ void store_chunk(const f32x4 (&r)[M3_LPT], float *__restrict__ buf, int64_t s0,
+                                            int64_t s_end, u32 n, u32 tid)
 {
 #pragma unroll
-    for (u32 g = 0; g < 4; ++g) {
-        bool ok = s < s_end && (FULL || 4 * m + g < n);
-        v[g] = ok ? v[g] : 0.f;
+    for (int k = 0; k < M3_LPT; ++k) {
+        const u32 j = tid + (u32)M3_THREADS * k, smp = j >> 4, c0 = 4u * (j & 15u);
+        const bool live = s0 + smp < s_end;
+        f32x4 v;
+#pragma unroll
+        for (u32 g = 0; g < 4; ++g) v[g] = (live && (FULL || c0 + g < n)) ? r[k][g] : 0.f;
+        *reinterpret_cast<f32x4 *>(buf + smp * 64u + c0) = v;
     }
-    return v;
 }
 
 template <int W>
 __device__ __forceinline__ void m3_step(f32x4 (&acc)[M3_TPW], const f32x4 &xa)
 {
-    // pair-in-group half units
+    // All pair products of the step first, each in a register of its own, then the
+    // 26 MFMAs back to back: a product that is formed right in front of its MFMA in
+    // a recycled register has to wait for the previous MFMA to release it.
+    float pw[9], p12[2], p13[2], p23[2];
     static_for<9>([&](auto HU) {
         constexpr int h = 9 * W + HU;
-        constexpr int gd = h / 2, half = h % 2, g = gd / 9, d = gd % 9;
-        const float p = xa[g] * row_ror<d>(xa[g]);
-        acc[2 * HU] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[2 * half], p, acc[2 * HU], 0, 0, 0);
-        acc[2 * HU + 1] =
-            __builtin_amdgcn_mfma_f32_16x16x4f32(xa[2 * half + 1], p, acc[2 * HU + 1], 0, 0, 0);
+        constexpr int gd = h / 2, g = gd / 9, d = gd % 9;
+        pw[HU] = xa[g] * row_ror<d>(xa[g]);
     });
-    // three different groups
     static_for<2>([&](auto E) {
         constexpr int m = 2 * W + E;
         const float b1 = row_bcast<m>(xa[1]);
         const float b2 = row_bcast<m>(xa[2]);
-        const float p12 = xa[2] * b1, p13 = xa[3] * b1, p23 = xa[3] * b2;
-        acc[18 + E] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[0], p12, acc[18 + E], 0, 0, 0);
-        acc[20 + E] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[0], p13, acc[20 + E], 0, 0, 0);
-        acc[22 + 2 * E] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[0], p23, acc[22 + 2 * E], 0, 0, 0);
-        acc[23 + 2 * E] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[1], p23, acc[23 + 2 * E], 0, 0, 0);
+        p12[E] = xa[2] * b1; p13[E] = xa[3] * b1; p23[E] = xa[3] * b2;
     });
+    __builtin_amdgcn_sched_barrier(0);
+    // pair-in-group half units
+    static_for<9>([&](auto HU) {
+        constexpr int h = 9 * W + HU;
+        constexpr int half = h % 2;
+        acc[2 * HU] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[2 * half], pw[HU], acc[2 * HU], 0, 0, 0);
+        acc[2 * HU + 1] =
+            __builtin_amdgcn_mfma_f32_16x16x4f32(xa[2 * half + 1], pw[HU], acc[2 * HU + 1], 0, 0, 0);
+    });
+    // three different groups
+    static_for<2>([&](auto E) {
+        acc[18 + E] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[0], p12[E], acc[18 + E], 0, 0, 0);
+        acc[20 + E] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[0], p13[E], acc[20 + E], 0, 0, 0);
+        acc[22 + 2 * E] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[0], p23[E], acc[22 + 2 * E], 0, 0, 0);
+        acc[23 + 2 * E] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[1], p23[E], acc[23 + 2 * E], 0, 0, 0);
+    });
+    __builtin_amdgcn_sched_barrier(0);
 }
 
 template <int W, bool FULL>
 __device__ __forceinline__ void m3_wave(const float *__restrict__ X, int64_t s_begin, int64_t s_end,
-                                        u32 n, float *__restrict__ part, u32 lane)
+                                        u32 n, float *__restrict__ part, float (*xs)[M3_CH * 64], u32 tid)
 {
-    const u32 m = lane & 15u, q = lane >> 4;
+    const u32 lane = tid & 63u;
     f32x4 acc[M3_TPW];
 #pragma unroll
     for (int t = 0; t < M3_TPW; ++t) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-    // Four K-steps (of four samples each) per iteration; the loads of the next
-    // iteration are issued before the MFMAs of the current one and are only
-    // waited for at its end.
-    f32x4 x0 = mask_x<FULL>(load_raw<FULL>(X, s_begin + 0 + q, s_end, n, m), s_begin + 0 + q, s_end, n, m);
-    f32x4 x1 = mask_x<FULL>(load_raw<FULL>(X, s_begin + 4 + q, s_end, n, m), s_begin + 4 + q, s_end, n, m);
-    f32x4 x2 = mask_x<FULL>(load_raw<FULL>(X, s_begin + 8 + q, s_end, n, m), s_begin + 8 + q, s_end, n, m);
-    f32x4 x3 = mask_x<FULL>(load_raw<FULL>(X, s_begin + 12 + q, s_end, n, m), s_begin + 12 + q, s_end, n, m);
-    for (int64_t s = s_begin; s < s_end; s += 16) {
-        f32x4 y0 = load_raw<FULL>(X, s + 16 + q, s_end, n, m);
-        f32x4 y1 = load_raw<FULL>(X, s + 20 + q, s_end, n, m);
-        f32x4 y2 = load_raw<FULL>(X, s + 24 + q, s_end, n, m);
-        f32x4 y3 = load_raw<FULL>(X, s + 28 + q, s_end, n, m);
+    const int64_t nchunks = (s_end - s_begin + M3_CH - 1) / M3_CH;
+    f32x4 r[M3_LPT];
+    load_chunk<FULL>(r, X, s_begin, s_end, n, tid);
+    store_chunk<FULL>(r, xs[0], s_begin, s_end, n, tid);
+    if (nchunks > 1) load_chunk<FULL>(r, X, s_begin + M3_CH, s_end, n, tid);
+    __syncthreads();
+
+    // lane (m, q) reads X(s + q, 4m .. 4m+3): component g is the A operand of group g
+    const float *mine = &xs[0][0] + lane * 4u;
+    for (int64_t c = 0; c < nchunks; ++c) {
+        const u32 cb = (u32)(c & 1);
+        // registers hold chunk c+1: park it in the other buffer (its readers finished
+        // before the barrier that ended the previous iteration), then put chunk c+2
+        // in flight
+        if (c + 1 < nchunks) store_chunk<FULL>(r, xs[cb ^ 1u], s_begin + (c + 1) * M3_CH, s_end, n, tid);
+        if (c + 2 < nchunks) load_chunk<FULL>(r, X, s_begin + (c + 2) * M3_CH, s_end, n, tid);
         __builtin_amdgcn_sched_barrier(0);
-        m3_step<W>(acc, x0);
-        m3_step<W>(acc, x1);
-        m3_step<W>(acc, x2);
-        m3_step<W>(acc, x3);
+        const float *src = mine + cb * (M3_CH * 64);
+        f32x4 xa[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) xa[k] = *reinterpret_cast<const f32x4 *>(src + k * 256);
+        // four groups of four K-steps; kept as a real loop so that the eight per-wave
+        // code streams stay small enough for the instruction cache
+#pragma unroll 1
+        for (int g = 0; g < 4; ++g) {
+            // the next four K-steps are read while these four are multiplied (the last
+            // group re-reads itself, which is harmless)
+            const float *nsrc = src + (g < 3 ? g + 1 : 3) * 1024;
+            f32x4 xb[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) xb[k] = *reinterpret_cast<const f32x4 *>(nsrc + k * 256);
+            __builtin_amdgcn_sched_barrier(0);
+            m3_step<W>(acc, xa[0]);
+            m3_step<W>(acc, xa[1]);
+            m3_step<W>(acc, xa[2]);
+            m3_step<W>(acc, xa[3]);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) xa[k] = xb[k];
+        }
         __builtin_amdgcn_sched_barrier(0);
-        x0 = mask_x<FULL>(y0, s + 16 + q, s_end, n, m);
-        x1 = mask_x<FULL>(y1, s + 20 + q, s_end, n, m);
-        x2 = mask_x<FULL>(y2, s + 24 + q, s_end, n, m);
-        x3 = mask_x<FULL>(y3, s + 28 + q, s_end, n, m);
+        __syncthreads();
     }
 
     float *dst = part + (size_t)W * M3_TPW * 256 + lane;
@@ -194,24 +236,25 @@ __device__ __forceinline__ void m3_wave(const float *__restrict__ X, int64_t s_b
 }
 
 template <bool FULL>
-__global__ __launch_bounds__(M3_WAVES * 64) void moment3_mfma_kernel(const float *__restrict__ X,
-                                                                   int64_t N, u32 n, int64_t chunk,
-                                                                   float *__restrict__ ws)
+__global__ __launch_bounds__(M3_THREADS) void moment3_mfma_kernel(const float *__restrict__ X, int64_t N, u32 n,
+                                                                int64_t chunk, float *__restrict__ ws)
 {
-    const u32 lane = threadIdx.x & 63u;
-    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    __shared__ __attribute__((aligned(16))) float xs[2][M3_CH * 64];
+    const u32 tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(tid >> 6));
     int64_t s_begin = (int64_t)blockIdx.x * chunk;
     int64_t s_end = s_begin + chunk < N ? s_begin + chunk : N;
     float *part = ws + (size_t)blockIdx.x * M3_ACC;
+    // every wave runs the same chunk loop (same number of barriers) over its own tiles
     switch (wave) {
-    case 0: m3_wave<0, FULL>(X, s_begin, s_end, n, part, lane); break;
-    case 1: m3_wave<1, FULL>(X, s_begin, s_end, n, part, lane); break;
-    case 2: m3_wave<2, FULL>(X, s_begin, s_end, n, part, lane); break;
-    case 3: m3_wave<3, FULL>(X, s_begin, s_end, n, part, lane); break;
-    case 4: m3_wave<4, FULL>(X, s_begin, s_end, n, part, lane); break;
-    case 5: m3_wave<5, FULL>(X, s_begin, s_end, n, part, lane); break;
-    case 6: m3_wave<6, FULL>(X, s_begin, s_end, n, part, lane); break;
-    default: m3_wave<7, FULL>(X, s_begin, s_end, n, part, lane); break;
+    case 0: m3_wave<0, FULL>(X, s_begin, s_end, n, part, xs, tid); break;
+    case 1: m3_wave<1, FULL>(X, s_begin, s_end, n, part, xs, tid); break;
+    case 2: m3_wave<2, FULL>(X, s_begin, s_end, n, part, xs, tid); break;
+    case 3: m3_wave<3, FULL>(X, s_begin, s_end, n, part, xs, tid); break;
+    case 4: m3_wave<4, FULL>(X, s_begin, s_end, n, part, xs, tid); break;
+    case 5: m3_wave<5, FULL>(X, s_begin, s_end, n, part, xs, tid); break;
+    case 6: m3_wave<6, FULL>(X, s_begin, s_end, n, part, xs, tid); break;
+    default: m3_wave<7, FULL>(X, s_begin, s_end, n, part, xs, tid); break;
     }
 }
 
@@ -222,12 +265,16 @@ __device__ __forceinline__ void sort3u(u32 &a, u32 &b, u32 &c)
     a = mn; b = md; c = mx;
 }
 
-// Adds the G workgroup partials (g ascending) and scatters the unique ones.
+// Adds the G workgroup partials and scatters the unique ones.  A block owns 64 raw
+// accumulators and cuts the partials into 4 slices (g ascending inside a slice,
+// slices ascending).
 __global__ __launch_bounds__(256) void moment3_reduce_kernel(const float *__restrict__ ws, u32 G, u32 n,
                                                             float *__restrict__ Sc, int accumulate)
 {
-    u32 e = blockIdx.x * 256u + threadIdx.x;      // raw accumulator id, < M3_ACC
-    u32 tile = e >> 8, v = (e >> 6) & 3u, lane = e & 63u;
+    __shared__ float accs[4][64];
+    const u32 lane = threadIdx.x & 63u, sl = threadIdx.x >> 6;
+    const u32 e = blockIdx.x * 64u + lane;        // raw accumulator id, < M3_ACC
+    const u32 tile = e >> 8, v = (e >> 6) & 3u;
     TileDesc td = tile_desc((int)(tile / M3_TPW), (int)(tile % M3_TPW));
     // D layout of the 16x16 MFMA: lane holds column lane%16 of rows 4*(lane/16) + v
     u32 rowel = 4u * (lane >> 4) + v, col = lane & 15u;
@@ -245,12 +292,21 @@ __global__ __launch_bounds__(256) void moment3_reduce_kernel(const float *__rest
         keep = true;
     }
     keep = keep && i < n && j < n && k < n;
-    if (!keep) return;
     float s = 0.f;
-    for (u32 g = 0; g < G; ++g) s += ws[(size_t)g * M3_ACC + e];
-    sort3u(i, j, k);
-    u32 p = rank_sym3<u32>(n, i, j, k);
-    Sc[p] = accumulate ? Sc[p] + s : s;
+    if (keep) {
+        const u32 per = (G + 3u) / 4u, g0 = min(G, sl * per), g1 = min(G, g0 + per);
+        const float *src = ws + e;
+#pragma unroll 8
+        for (u32 g = g0; g < g1; ++g) s += src[(size_t)g * M3_ACC];
+    }
+    accs[sl][lane] = s;
+    __syncthreads();
+    if (sl == 0 && keep) {
+        s = (accs[0][lane] + accs[1][lane]) + (accs[2][lane] + accs[3][lane]);
+        sort3u(i, j, k);
+        u32 p = rank_sym3<u32>(n, i, j, k);
+        Sc[p] = accumulate ? Sc[p] + s : s;
+    }
 }
 
 // ---- general path -----------------------------------------------------------------
@@ -291,8 +347,8 @@ __global__ __launch_bounds__(256) void zero_kernel(float *__restrict__ p, u32 co
 static inline int64_t m3_chunk(int64_t N)
 {
     int64_t c = (N + M3_GMAX - 1) / M3_GMAX;
-    c = (c + 15) / 16 * 16;
-    return c < 64 ? 64 : c;
+    c = (c + M3_CH - 1) / M3_CH * M3_CH;
+    return c;
 }
 static inline u32 m3_groups(int64_t N) { return N == 0 ? 0u : (u32)((N + m3_chunk(N) - 1) / m3_chunk(N)); }
 static inline u32 plain_slices(int64_t N)
@@ -327,7 +383,7 @@ st_status launch_moment3(const float *X, int64_t N, int n, float *Sc, int accumu
             hipLaunchKernelGGL(moment3_mfma_kernel<false>, dim3(G), dim3(M3_WAVES * 64), 0, s, X, N, (u32)n,
                                chunk, wsf);
         if (hipGetLastError() != hipSuccess) return ST_ERR_LAUNCH;
-        hipLaunchKernelGGL(moment3_reduce_kernel, dim3(M3_ACC / 256), dim3(256), 0, s, wsf, G, (u32)n, Sc,
+        hipLaunchKernelGGL(moment3_reduce_kernel, dim3(M3_ACC / 64), dim3(256), 0, s, wsf, G, (u32)n, Sc,
                            accumulate);
         return launch_status();
     }
