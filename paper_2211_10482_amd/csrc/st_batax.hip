@@ -162,22 +162,28 @@ __global__ __launch_bounds__(BT) void batax_onepass_kernel(const float *__restri
     __shared__ float red[2][RB][BT / 64];
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6, g = blockIdx.x;
 
+    // rows g, g+G, g+2G, ...; batch b holds rows g + G*(RB*b + r)
+    const u32 nrows = (n > g) ? (n - g + G - 1) / G : 0;
+    const u32 nb = (nrows + RB - 1) / RB;
+    float4 a0[RB][V], a1[RB][V];
+    load_batch<V, FAST>(a0, Ap, n, g, G, tid);     // first rows go out before anything else
+
+    // x for the owned columns: branch-free (index clamped, value selected), so these
+    // loads overlap the first batch instead of serialising in front of it
     float4 xs[V], ya[V];
 #pragma unroll
     for (int v = 0; v < V; ++v) {
         u32 c0 = 4u * (tid + (u32)BT * v);
         float e[4];
 #pragma unroll
-        for (u32 q = 0; q < 4; ++q) e[q] = (c0 + q < n) ? x[c0 + q] : 0.f;
+        for (u32 q = 0; q < 4; ++q) {
+            float t = x[min(c0 + q, n - 1u)];
+            e[q] = (c0 + q < n) ? t : 0.f;
+        }
         xs[v] = make_float4(e[0], e[1], e[2], e[3]);
         ya[v] = make_float4(0.f, 0.f, 0.f, 0.f);
     }
 
-    // rows g, g+G, g+2G, ...; batch b holds rows g + G*(RB*b + r)
-    const u32 nrows = (n > g) ? (n - g + G - 1) / G : 0;
-    const u32 nb = (nrows + RB - 1) / RB;
-    float4 a0[RB][V], a1[RB][V];
-    load_batch<V, FAST>(a0, Ap, n, g, G, tid);
     for (u32 b = 0; b < nb; b += 2) {
         load_batch<V, FAST>(a1, Ap, n, g + G * RB * (b + 1), G, tid);
         __builtin_amdgcn_sched_barrier(0);
