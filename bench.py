@@ -61,6 +61,28 @@ def workloads():
     return out
 
 
+def recorded_traffic():
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter summary, or None when
+    the kernel source has changed since the counters were taken."""
+    import hashlib
+    rec = os.path.join(ROOT, "profiles", "moment3_sym_N2e6_n64_traffic.txt")
+    src = os.path.join(ROOT, "paper_2211_10482_amd", "csrc", "st_moment3.hip")
+    try:
+        kv = {}
+        with open(rec) as f:
+            for line in f:
+                parts = line.split()
+                if len(parts) == 2 and not line.startswith("#"):
+                    kv[parts[0]] = parts[1]
+        with open(src, "rb") as f:
+            sha = hashlib.sha256(f.read()).hexdigest()
+        if kv.get("kernel_source_sha256") != sha:
+            return None
+        return float(kv["traffic_bytes"])
+    except (OSError, KeyError, ValueError):
+        return None
+
+
 def cpu_baseline(inputs):
     """The oracle as it stands, timed on a bounded sample of the same step."""
     import oracle
@@ -214,7 +236,7 @@ def main():
     dom_ms = kernels[dom]["ms"]
     achieved = wl[dom]["flops"] / (dom_ms * 1e-3) / 1e12
     roofline = dict(kernel=dom, bound="mfma", achieved=round(achieved, 3), peak=MFMA_FP32_PEAK_TFLOPS,
-                    unit="TFLOP/s", frac=round(achieved / MFMA_FP32_PEAK_TFLOPS, 4), traffic=None)
+                    unit="TFLOP/s", frac=round(achieved / MFMA_FP32_PEAK_TFLOPS, 4), traffic=recorded_traffic())
 
     result = {
         "metric": "unique-element GFLOP/s over the five structured kernels, 1xMI355X",
