@@ -359,17 +359,26 @@ __device__ __forceinline__ void pair_loop(LdsPair &L, const float *__restrict__ 
             const float *bxp = &L.bx[cb][(4u * lq) * BS + cw * 16u + lrow];
             const float bx0 = bxp[0], bx1 = bxp[BS], bx2 = bxp[2 * BS], bx3 = bxp[3 * BS];
             const float *ap = &L.tile[cb][(half * 8u) * PS + lrow * QS + 4u * lq];
-            f32x4 a[8];
+            // two groups of four p: 16 independent MFMAs per group keep the matrix pipe
+            // busy with half the operand registers
 #pragma unroll
-            for (int j = 0; j < 8; ++j) a[j] = *reinterpret_cast<const f32x4 *>(ap + j * PS);
+            for (int g = 0; g < 2; ++g) {
+                f32x4 a[4];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[j][0], bx0, acc[j], 0, 0, 0);
+                for (int j = 0; j < 4; ++j) a[j] = *reinterpret_cast<const f32x4 *>(ap + (4 * g + j) * PS);
 #pragma unroll
-            for (int j = 0; j < 8; ++j) acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[j][1], bx1, acc[j], 0, 0, 0);
+                for (int j = 0; j < 4; ++j)
+                    acc[4 * g + j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[j][0], bx0, acc[4 * g + j], 0, 0, 0);
 #pragma unroll
-            for (int j = 0; j < 8; ++j) acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[j][2], bx2, acc[j], 0, 0, 0);
+                for (int j = 0; j < 4; ++j)
+                    acc[4 * g + j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[j][1], bx1, acc[4 * g + j], 0, 0, 0);
 #pragma unroll
-            for (int j = 0; j < 8; ++j) acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[j][3], bx3, acc[j], 0, 0, 0);
+                for (int j = 0; j < 4; ++j)
+                    acc[4 * g + j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[j][2], bx2, acc[4 * g + j], 0, 0, 0);
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc[4 * g + j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[j][3], bx3, acc[4 * g + j], 0, 0, 0);
+            }
         }
         __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
