@@ -4,34 +4,47 @@
 //
 // The index range is cut into blocks of 16, so the packed tensor is a set of
 // 16^3 sub-tensors, one per block triple A <= B <= C.  Every contraction below is
-// dense and runs on the fp32 matrix cores (v_mfma_f32_16x16x4_f32).  Three kinds
-// of work item, each a workgroup of 8 waves with its own branch-free,
-// software-pipelined loop over "visits" (one staged sub-tensor each):
+// dense and runs on the fp32 matrix cores (v_mfma_f32_16x16x4_f32).  When n is a
+// multiple of 16 all work is done by two kinds of pair item, each a workgroup of
+// 8 waves with a branch-free, software-pipelined loop over "visits" (one staged
+// 16^3 tile each) that uses plain rows of B as the second MFMA operand (no
+// Khatri-Rao products are ever formed):
 //
-//   * row items (row block X, a range of block pairs X < P < Q):
-//         M(x,r) += 2 * sum_{p,q} T(x,p,q) B(p,r) B(q,r)
-//     a [16 x 256] . [256 x R] contraction against Khatri-Rao rows formed on the
-//     fly (one VALU multiply per MFMA); the sub-tensor is made of contiguous runs
-//     along q -> 16-byte loads, 16-byte LDS writes.
-//   * pair items (block pair P < Q, a range of row blocks X < P):
-//         U(p,q;r) = sum_X sum_x T(x,p,q) B(x,r)        (accumulated over the visits)
+//   * (P,Q) items (block pair P <= Q, a range of row blocks X <= P):
+//         U(p,q;r) = sum_X w_X sum_x T(x,p,q) B(x,r)     (accumulated over the visits)
 //         M(p,r) += 2 * sum_q B(q,r) U(p,q;r),   M(q,r) += 2 * sum_p B(p,r) U(p,q;r)
-//     a [256 x 16] . [16 x R] contraction per visit with plain rows of B as the
-//     second operand (no products at all); the two outputs come from ONE
-//     accumulator, so a sub-tensor with three different blocks is multiplied
-//     twice, not three times, for its three output blocks.
-//   * gather items (row block X, the 2*NB-1 block pairs that repeat a block, or
-//     every pair when n is not a multiple of 16): owner-computes with a per-element
-//     sort + closed-form rank3 gather,
+//     two output blocks from ONE accumulator (P = Q: one, the two are the same);
+//   * (X,P) items (block pair X <= P, a range of blocks Q >= P):
+//         V(x,p;r) = sum_Q w_Q sum_q T(x,p,q) B(q,r),    M(x,r) += 2 * sum_p B(p,r) V(x,p;r)
+//     consecutive visits read consecutive 64-byte runs.
+//
+// A block triple X < P < Q is visited once by each kind (weight 1), which gives its
+// three output blocks from two contractions.  Triples that repeat a block use the
+// symmetry of the tile instead of a gather: the staged tile is completed from the
+// stored half (canonical min/max addressing, or a mirrored LDS write when the
+// stored runs are ragged), and the visits X = P, Q = P and all visits of an (X,X)
+// item carry weight 1/2, so that every ordered pair (j,k) of
+// M(i,r) = sum_{j,k} T(i,j,k) B(j,r) B(k,r) is counted exactly once:
+//     {A,A,C}: M[A] from item (P=A,Q=C) visit X=A (1/2) and item (X=A,P=A) visit Q=C (1/2),
+//              M[C] from item (P=A,Q=C) visit X=A (1/2);
+//     {A,C,C}: M[C] from item (P=C,Q=C) visit X=A,  M[A] from item (X=A,P=C) visit Q=C (1/2);
+//     {A,A,A}: item (X=A,P=A) visit Q=A (1/2), the only tile that needs a per-element sort.
+//
+// When n is not a multiple of 16 gather items do all the work instead (row block X,
+// every block pair P <= Q): owner-computes with a per-element sort + closed-form
+// rank3 gather and Khatri-Rao rows formed on the fly,
 //         M(x,r) += w * sum_{p,q} T(sort(x,p,q)) B(p,r) B(q,r),  w = 2 for P < Q.
+//
+// Both pair kinds run the same [256 x 16] . [16 x R] MFMA loop on a staged tile
+// D[i1][i2][k] (k fastest): (P,Q) items stage it transposed (i1 = p, i2 = q, k = x),
+// (X,P) items as it lies in memory (i1 = x, i2 = p, k = q; 16-byte LDS writes).
 //
 // No two workgroups add into the same output: each item writes its own partial
 // block(s) and a second kernel adds them in a fixed order (deterministic, no
 // float atomics).  Staging is double buffered in LDS with the loads of visit v+2
-// in flight in registers while visit v is multiplied; one barrier per visit.  In
-// the row/gather loops lane = (x, q-quad): one ds_read_b128 of the sub-tensor
-// feeds four MFMAs whose K slots are permuted consistently on the B side; in the
-// pair loop lane = (q, x-quad) on a transposed staging layout.
+// in flight in registers while visit v is multiplied; one barrier per visit.  One
+// ds_read_b128 of the tile feeds four MFMAs whose K slots are permuted
+// consistently on the B side.
 //
 // Algorithmic traffic: 4 bytes per stored entry (read by two or three items) + B + M.
 #include "st_common.h"
@@ -42,6 +55,12 @@ namespace st {
 typedef uint32_t u32;
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
+#ifndef ST_MTTKRP_WPE
+#define ST_MTTKRP_WPE 4
+#endif
+#ifndef ST_MTTKRP_ITEMS
+#define ST_MTTKRP_ITEMS 350u
+#endif
 constexpr u32 NT = 512;            // threads per workgroup: 4 column waves x 2 halves
 constexpr u32 XS = 260;            // row/gather tile D[x][p][q]: stride between x-planes (16*16 + 4 pad)
 constexpr u32 TILE_F = 16 * XS;
@@ -62,78 +81,42 @@ __device__ __forceinline__ void sort3u(u32 &a, u32 &b, u32 &c)
 
 struct MttkrpPlan {
     u32 NB, RT, Rpad;
-    u32 all_pairs;          // ragged n: every visit is a gather visit, no row/pair items
+    u32 all_pairs;          // ragged n: gather items only, no pair items
     u32 ngat;               // gather visits per row block
-    u32 PPR, PPG, PPB;      // visits per row / gather / pair item
-    u32 NCHR, NCHG, NCHA;   // row chunks (of row block 0, the longest), gather chunks, NCHA = NCHR + NCHG
-    u32 CHB;                // chunk slots per block pair
-    u32 nitemsA;            // NB * NCHA row+gather items (unused row slots exit at once)
-    u32 npairs_strict;      // block pairs P < Q
+    u32 PPG, PPB;           // visits per gather / pair item
+    u32 NCHG;               // gather chunks per row block
+    u32 CHB;                // chunk slots per block pair (either pair kind)
+    u32 nitemsG;            // NB * NCHG gather items
+    u32 npairs;             // block pairs P <= Q that have pair items
 };
 
-__host__ __device__ inline u32 strict_pairs(u32 m) { return m >= 2u ? m * (m - 1u) / 2u : 0u; }
-__host__ __device__ inline u32 row_chunks(const MttkrpPlan &pl, u32 X)       // row items of row block X
-{
-    return pl.all_pairs ? 0u : (strict_pairs(pl.NB - 1u - X) + pl.PPR - 1u) / pl.PPR;
-}
-__host__ __device__ inline u32 pair_chunks(const MttkrpPlan &pl, u32 P)      // pair items of a pair (P, .)
-{
-    return pl.all_pairs ? 0u : (P + pl.PPB - 1u) / pl.PPB;
-}
-__host__ __device__ inline u32 pair_index(u32 NB, u32 P, u32 Q)              // P < Q  ->  0 .. C(NB,2)-1
-{
-    return P * (NB - 1u) - (P * (P - 1u)) / 2u + (Q - 1u - P);
-}
+// visits of a (P,Q) item: row blocks X <= P (P = Q: X < P, the tile of three equal
+// blocks belongs to the (X,P) kind); of an (X,P) item: blocks Q >= P
+__host__ __device__ inline u32 visits_pq(u32 P, u32 Q) { return P < Q ? P + 1u : P; }
+__host__ __device__ inline u32 visits_xp(u32 NB, u32 P) { return NB - P; }
+__host__ __device__ inline u32 chunks_of(const MttkrpPlan &pl, u32 visits) { return (visits + pl.PPB - 1u) / pl.PPB; }
 
-// ---- row and gather items ----------------------------------------------------------
+// ---- gather items (n not a multiple of 16) ---------------------------------------------------
 struct Visit {
     u32 p0, q0;   // first index of blocks P and Q
     float wgt;    // 2 for P < Q, 1 for P = Q
 };
 
-// Cursor over the visits of a row or gather item.  Only the first position is
-// unranked; after that the cursor steps (wave-uniform scalar work).
-//   row    : u-th strict pair P < Q of the m = NB-1-X blocks above X, kept as (a, b)
-//            with a <= b < m-1 in sym2 order: P = X+1+a, Q = X+2+b
-//   gather : ragged n -> every pair P <= Q in sym2 order (a, b); otherwise the 2*NB-1
-//            pairs with two equal blocks: (g,g) for g < NB, then (g',X) for g' < X,
-//            then (X,g'+1)   (a = g)
-template <bool GATHER> struct Cursor {
-    u32 NB, X, a, b;
-    bool all_pairs;
+// Cursor over the visits of a gather item: every block pair P <= Q in sym2 order.
+// Only the first position is unranked; after that the cursor steps (wave-uniform
+// scalar work).
+struct Cursor {
+    u32 NB, a, b;
 
-    __device__ __forceinline__ Cursor(u32 NB_, u32 X_, bool all_pairs_, u32 u) : NB(NB_), X(X_), all_pairs(all_pairs_)
-    {
-        if (!GATHER) unrank_sym2<u32>(NB - 2u - X, u, a, b);
-        else if (all_pairs) unrank_sym2<u32>(NB, u, a, b);
-        else { a = u; b = 0; }
-    }
+    __device__ __forceinline__ Cursor(u32 NB_, u32 u) : NB(NB_) { unrank_sym2<u32>(NB, u, a, b); }
     __device__ __forceinline__ void step()
     {
-        if (!GATHER || all_pairs) {
-            const u32 last = (GATHER ? NB : NB - 2u - X) - 1u;
-            if (b < last) ++b; else { ++a; b = a; }
-        } else {
-            ++a;
-        }
+        if (b < NB - 1u) ++b; else { ++a; b = a; }
     }
     __device__ __forceinline__ Visit get() const
     {
-        u32 P, Q;
-        if (!GATHER) {
-            P = X + 1u + a;
-            Q = X + 2u + b;
-        } else if (all_pairs) {
-            P = a; Q = b;
-        } else if (a < NB) {
-            P = Q = a;
-        } else {
-            const u32 h = a - NB;
-            P = h < X ? h : X;
-            Q = h < X ? X : h + 1u;
-        }
         Visit v;
-        v.p0 = P * 16u; v.q0 = Q * 16u; v.wgt = (P < Q) ? 2.f : 1.f;
+        v.p0 = a * 16u; v.q0 = b * 16u; v.wgt = (a < b) ? 2.f : 1.f;
         return v;
     }
 };
@@ -142,28 +125,17 @@ template <bool GATHER> struct Cursor {
 // the two staged blocks of B per thread.  Every load is unconditional (addresses
 // clamped) and the results are not touched here, so they stay in flight while
 // the previous visit is multiplied; store_visit zeroes what lies outside.
-template <bool GATHER, bool R4>
+template <bool R4>
 __device__ __forceinline__ void load_visit(const Visit &v, const float *__restrict__ Tc,
                                            const float *__restrict__ B, u32 n, u32 R, u32 x0, u32 rbase,
                                            u32 tid, float (&pf)[8], float (&bb)[4])
 {
-    if constexpr (!GATHER) {
-        // X < P < Q: D[x][p][q] = Tc[run(x, p) + (q0 + q - p)], 16 consecutive q per (x, p)
 #pragma unroll
-        for (u32 it = 0; it < 2; ++it) {
-            const u32 e = tid + NT * it, row = e >> 2, qr = e & 3u;
-            const u32 xi = x0 + (row >> 4), pi = v.p0 + (row & 15u);
-            f4u t = *reinterpret_cast<const f4u *>(Tc + run_sym3<u32>(n, xi, pi) + (v.q0 - pi) + 4u * qr);
-            pf[4 * it] = t.x; pf[4 * it + 1] = t.y; pf[4 * it + 2] = t.z; pf[4 * it + 3] = t.w;
-        }
-    } else {
-#pragma unroll
-        for (u32 it = 0; it < 8; ++it) {
-            const u32 e = tid + NT * it;
-            u32 a = x0 + (e >> 8), b = v.p0 + ((e >> 4) & 15u), c = v.q0 + (e & 15u);
-            sort3u(a, b, c);
-            pf[it] = Tc[c < n ? rank_sym3<u32>(n, a, b, c) : 0u];
-        }
+    for (u32 it = 0; it < 8; ++it) {
+        const u32 e = tid + NT * it;
+        u32 a = x0 + (e >> 8), b = v.p0 + ((e >> 4) & 15u), c = v.q0 + (e & 15u);
+        sort3u(a, b, c);
+        pf[it] = Tc[c < n ? rank_sym3<u32>(n, a, b, c) : 0u];
     }
     // piece tid of the two 16 x 64 blocks of B: block tid/256 (P, then Q), row
     // (tid%256)/16, columns rbase + 4*(tid%16) .. +3
@@ -181,27 +153,17 @@ __device__ __forceinline__ void load_visit(const Visit &v, const float *__restri
 
 // Registers -> LDS: dense tile D[x][p][q] (x-stride XS) and the two B blocks, the
 // P block scaled by the pair weight; positions outside the tensor become zero.
-template <bool GATHER>
 __device__ __forceinline__ void store_visit(const Visit &v, u32 n, u32 R, u32 x0, u32 rbase,
                                             float *__restrict__ tile, float *__restrict__ bp,
                                             float *__restrict__ bq, u32 tid, const float (&pf)[8],
                                             const float (&bb)[4])
 {
-    if constexpr (!GATHER) {
 #pragma unroll
-        for (u32 it = 0; it < 2; ++it) {
-            const u32 e = tid + NT * it, row = e >> 2, qr = e & 3u;
-            *reinterpret_cast<float4 *>(&tile[(row >> 4) * XS + (row & 15u) * 16u + 4u * qr]) =
-                make_float4(pf[4 * it], pf[4 * it + 1], pf[4 * it + 2], pf[4 * it + 3]);
-        }
-    } else {
-#pragma unroll
-        for (u32 it = 0; it < 8; ++it) {
-            const u32 e = tid + NT * it;
-            const u32 x = e >> 8, p = (e >> 4) & 15u, q = e & 15u;
-            const bool ok = max(x0 + x, max(v.p0 + p, v.q0 + q)) < n;
-            tile[x * XS + p * 16u + q] = ok ? pf[it] : 0.f;
-        }
+    for (u32 it = 0; it < 8; ++it) {
+        const u32 e = tid + NT * it;
+        const u32 x = e >> 8, p = (e >> 4) & 15u, q = e & 15u;
+        const bool ok = max(x0 + x, max(v.p0 + p, v.q0 + q)) < n;
+        tile[x * XS + p * 16u + q] = ok ? pf[it] : 0.f;
     }
     const u32 h = tid >> 8, row = (tid & 255u) >> 4, col = rbase + 4u * (tid & 15u);
     const bool rok = (h == 0 ? v.p0 : v.q0) + row < n;
@@ -212,39 +174,39 @@ __device__ __forceinline__ void store_visit(const Visit &v, u32 n, u32 R, u32 x0
                     (rok && col + 2u < R) ? w * bb[2] : 0.f, (rok && col + 3u < R) ? w * bb[3] : 0.f);
 }
 
-struct LdsRow {
+struct LdsGather {
     float tile[2][TILE_F];
     float bp[2][BBLK_F];
     float bq[2][BBLK_F];
 };
 struct LdsPair {
     float tile[2][TILEB_F];
-    float bx[2][BBLK_F];
+    float bk[2][BBLK_F];
 };
-constexpr size_t LDS_BYTES = sizeof(LdsRow) > sizeof(LdsPair) ? sizeof(LdsRow) : sizeof(LdsPair);
 
-// Visits [v0, v1) of a row (GATHER = false) or gather item of row block X.
-// Wave (cw, half) accumulates columns 16*cw.. of its half of the p range.
-template <bool GATHER, bool R4>
-__device__ __forceinline__ void visit_loop(LdsRow &L, const float *__restrict__ Tc,
-                                           const float *__restrict__ B, u32 n, u32 R, u32 NB, u32 X,
-                                           bool all_pairs, u32 v0, u32 v1, u32 rbase, bool has_rt,
-                                           f32x4 (&acc)[4])
+// Visits [v0, v1) of a gather item of row block X: a [16 x 256] . [256 x R]
+// contraction per visit against Khatri-Rao rows formed on the fly (one VALU multiply
+// per MFMA).  Lane = (x, q-quad); wave (cw, half) accumulates columns 16*cw.. of its
+// half of the p range.
+template <bool R4>
+__device__ __forceinline__ void gather_loop(LdsGather &L, const float *__restrict__ Tc,
+                                            const float *__restrict__ B, u32 n, u32 R, u32 NB, u32 X,
+                                            u32 v0, u32 v1, u32 rbase, bool has_rt, f32x4 (&acc)[4])
 {
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const u32 x0 = X * 16u, lrow = lane & 15u, lq = lane >> 4;
     if (v0 >= v1) return;
     const u32 nv = v1 - v0;
-    Cursor<GATHER> cur(NB, X, all_pairs, v0);
+    Cursor cur(NB, v0);
 
     float pf[8], bb[4];
     Visit nxt = cur.get();
-    load_visit<GATHER, R4>(nxt, Tc, B, n, R, x0, rbase, tid, pf, bb);
-    store_visit<GATHER>(nxt, n, R, x0, rbase, L.tile[0], L.bp[0], L.bq[0], tid, pf, bb);
+    load_visit<R4>(nxt, Tc, B, n, R, x0, rbase, tid, pf, bb);
+    store_visit(nxt, n, R, x0, rbase, L.tile[0], L.bp[0], L.bq[0], tid, pf, bb);
     if (nv > 1) {
         cur.step();
         nxt = cur.get();
-        load_visit<GATHER, R4>(nxt, Tc, B, n, R, x0, rbase, tid, pf, bb);
+        load_visit<R4>(nxt, Tc, B, n, R, x0, rbase, tid, pf, bb);
     }
     __syncthreads();
 
@@ -253,12 +215,12 @@ __device__ __forceinline__ void visit_loop(LdsRow &L, const float *__restrict__ 
         // registers hold visit v+1: park it in the other buffer (its last readers
         // finished before the barrier that ended iteration v-1) ...
         if (v + 1 < nv)
-            store_visit<GATHER>(nxt, n, R, x0, rbase, L.tile[cb ^ 1u], L.bp[cb ^ 1u], L.bq[cb ^ 1u], tid, pf, bb);
+            store_visit(nxt, n, R, x0, rbase, L.tile[cb ^ 1u], L.bp[cb ^ 1u], L.bq[cb ^ 1u], tid, pf, bb);
         // ... and put visit v+2 in flight
         if (v + 2 < nv) {
             cur.step();
             nxt = cur.get();
-            load_visit<GATHER, R4>(nxt, Tc, B, n, R, x0, rbase, tid, pf, bb);
+            load_visit<R4>(nxt, Tc, B, n, R, x0, rbase, tid, pf, bb);
         }
         __builtin_amdgcn_sched_barrier(0);
         if (has_rt) {
@@ -283,83 +245,170 @@ __device__ __forceinline__ void visit_loop(LdsRow &L, const float *__restrict__ 
 }
 
 // ---- pair items -----------------------------------------------------------------------
-// Global -> registers for the visit (X, P, Q), X < P < Q: thread (qr, x, p) takes
-// T(x, p, q0 + 4qr .. +3); threads below 256 also take one 16-byte piece of the 16 x 64
-// block of B for the rows of X.
-template <bool R4>
-__device__ __forceinline__ void load_pair_visit(u32 x0, u32 p0, u32 q0, const float *__restrict__ Tc,
+// The staged tile is D[i1][i2][k] with k fastest (i2-stride QS, i1-stride PS); block b1
+// supplies i1, block b2 supplies i2 and the visit supplies the block of k:
+//   KIND 0: item (P, Q), visits X <= P:  i1 = p, i2 = q, k = x
+//   KIND 1: item (X, P), visits Q >= P:  i1 = x, i2 = p, k = q
+// Global -> registers for one visit: thread (qr, ., .) takes the four values
+// T(min(x,p), max(x,p), q0 + 4qr .. +3) of one stored run (x and p only meet in the same
+// block when X = P, where the tile is symmetric in them); threads below 256 also take
+// one 16-byte piece of the 16 x 64 block of B for the rows of the k block.  Where the q
+// block equals the p block the values with q < p are not part of the run (they are
+// whatever precedes it in memory, p >= 16 there) and store_pair_visit<MIRROR> drops them.
+template <int KIND, bool R4>
+__device__ __forceinline__ void load_pair_visit(u32 b1_0, u32 b2_0, u32 k0, const float *__restrict__ Tc,
                                                 const float *__restrict__ B, u32 n, u32 R, u32 rbase, u32 tid,
                                                 float (&pf)[8], float (&bb)[4])
 {
 #pragma unroll
     for (u32 it = 0; it < 2; ++it) {
-        const u32 e = tid + NT * it, qr = e & 3u, xi = x0 + ((e >> 2) & 15u), pi = p0 + (e >> 6);
-        f4u t = *reinterpret_cast<const f4u *>(Tc + run_sym3<u32>(n, xi, pi) + (q0 - pi) + 4u * qr);
+        const u32 e = tid + NT * it, qr = e & 3u, mid = (e >> 2) & 15u, hi = e >> 6;
+        const u32 x = (KIND == 0) ? k0 + mid : b1_0 + hi;
+        const u32 pp = (KIND == 0) ? b1_0 + hi : b2_0 + mid;
+        const u32 q0 = (KIND == 0) ? b2_0 : k0;
+        const u32 lo = min(x, pp), up = max(x, pp);
+        // one 32-bit sum: q0 - up is negative (wraps) where the q block is the p block
+        const u32 pos = run_sym3<u32>(n, lo, up) + (q0 - up) + 4u * qr;
+        f4u t = *reinterpret_cast<const f4u *>(Tc + pos);
         pf[4 * it] = t.x; pf[4 * it + 1] = t.y; pf[4 * it + 2] = t.z; pf[4 * it + 3] = t.w;
     }
     const u32 row = (tid & 255u) >> 4, col = rbase + 4u * (tid & 15u);
     if constexpr (R4) {
         const bool ok = col < R;
-        float4 t = *reinterpret_cast<const float4 *>(B + (ok ? (size_t)(x0 + row) * R + col : 0));
+        float4 t = *reinterpret_cast<const float4 *>(B + (ok ? (size_t)(k0 + row) * R + col : 0));
         bb[0] = t.x; bb[1] = t.y; bb[2] = t.z; bb[3] = t.w;
     } else {
 #pragma unroll
-        for (u32 q = 0; q < 4; ++q) bb[q] = B[(col + q < R) ? (size_t)(x0 + row) * R + col + q : 0];
+        for (u32 q = 0; q < 4; ++q) bb[q] = B[(col + q < R) ? (size_t)(k0 + row) * R + col + q : 0];
     }
 }
 
-// Registers -> LDS, transposed: D[p][q][x] with x fastest (q-stride QS, p-stride PS).
-__device__ __forceinline__ void store_pair_visit(u32 R, u32 rbase, float *__restrict__ tile,
-                                                 float *__restrict__ bx, u32 tid, const float (&pf)[8],
+// The tile of three equal blocks (item (X,X), visit Q = X): one sorted gather per value.
+template <bool R4>
+__device__ __forceinline__ void load_diag_visit(u32 b0, const float *__restrict__ Tc, const float *__restrict__ B,
+                                                u32 n, u32 R, u32 rbase, u32 tid, float (&pf)[8], float (&bb)[4])
+{
+#pragma unroll
+    for (u32 it = 0; it < 2; ++it) {
+        const u32 e = tid + NT * it, qr = e & 3u, mid = (e >> 2) & 15u, hi = e >> 6;
+#pragma unroll
+        for (u32 t = 0; t < 4; ++t) {
+            u32 a = b0 + hi, b = b0 + mid, c = b0 + 4u * qr + t;
+            sort3u(a, b, c);
+            pf[4 * it + t] = Tc[rank_sym3<u32>(n, a, b, c)];
+        }
+    }
+    const u32 row = (tid & 255u) >> 4, col = rbase + 4u * (tid & 15u);
+    if constexpr (R4) {
+        const bool ok = col < R;
+        float4 t = *reinterpret_cast<const float4 *>(B + (ok ? (size_t)(b0 + row) * R + col : 0));
+        bb[0] = t.x; bb[1] = t.y; bb[2] = t.z; bb[3] = t.w;
+    } else {
+#pragma unroll
+        for (u32 q = 0; q < 4; ++q) bb[q] = B[(col + q < R) ? (size_t)(b0 + row) * R + col + q : 0];
+    }
+}
+
+// Registers -> LDS, the block of B scaled by the weight w of the visit.  KIND 0
+// transposes (the loaded run lies along i2), KIND 1 keeps the run as one 16-byte write
+// along k.  MIRROR (the q block is the p block): the loaded values with q >= p are
+// written to (p, q) and to (q, p), the others dropped.
+template <int KIND, bool MIRROR>
+__device__ __forceinline__ void store_pair_visit(u32 R, u32 rbase, float w, float *__restrict__ tile,
+                                                 float *__restrict__ bk, u32 tid, const float (&pf)[8],
                                                  const float (&bb)[4])
 {
 #pragma unroll
     for (u32 it = 0; it < 2; ++it) {
-        const u32 e = tid + NT * it, qr = e & 3u, x = (e >> 2) & 15u, p = e >> 6;
-        float *d = &tile[p * PS + (4u * qr) * QS + x];
-        d[0] = pf[4 * it]; d[QS] = pf[4 * it + 1]; d[2 * QS] = pf[4 * it + 2]; d[3 * QS] = pf[4 * it + 3];
+        const u32 e = tid + NT * it, qr = e & 3u, mid = (e >> 2) & 15u, hi = e >> 6;
+        if constexpr (!MIRROR) {
+            if constexpr (KIND == 0) {
+                float *d = &tile[hi * PS + (4u * qr) * QS + mid];
+                d[0] = pf[4 * it]; d[QS] = pf[4 * it + 1]; d[2 * QS] = pf[4 * it + 2]; d[3 * QS] = pf[4 * it + 3];
+            } else {
+                *reinterpret_cast<float4 *>(&tile[hi * PS + mid * QS + 4u * qr]) =
+                    make_float4(pf[4 * it], pf[4 * it + 1], pf[4 * it + 2], pf[4 * it + 3]);
+            }
+        } else {
+            // KIND 0: (p, q, x) = (hi, 4qr+t, mid) at [p][q][x];  KIND 1: (x, p, q) = (hi, mid, 4qr+t) at [x][p][q]
+            const u32 pl = (KIND == 0) ? hi : mid;
+#pragma unroll
+            for (u32 t = 0; t < 4; ++t) {
+                const u32 ql = 4u * qr + t;
+                const float v = pf[4 * it + t];
+                if constexpr (KIND == 0) {
+                    if (ql >= pl) tile[pl * PS + ql * QS + mid] = v;
+                    if (ql > pl) tile[ql * PS + pl * QS + mid] = v;
+                } else {
+                    if (ql >= pl) tile[hi * PS + pl * QS + ql] = v;
+                    if (ql > pl) tile[hi * PS + ql * QS + pl] = v;
+                }
+            }
+        }
     }
     if (tid < 256u) {
         const u32 row = tid >> 4, col = rbase + 4u * (tid & 15u);
-        *reinterpret_cast<float4 *>(&bx[row * BS + 4u * (tid & 15u)]) =
-            make_float4(col + 0u < R ? bb[0] : 0.f, col + 1u < R ? bb[1] : 0.f, col + 2u < R ? bb[2] : 0.f,
-                        col + 3u < R ? bb[3] : 0.f);
+        *reinterpret_cast<float4 *>(&bk[row * BS + 4u * (tid & 15u)]) =
+            make_float4(col + 0u < R ? w * bb[0] : 0.f, col + 1u < R ? w * bb[1] : 0.f,
+                        col + 2u < R ? w * bb[2] : 0.f, col + 3u < R ? w * bb[3] : 0.f);
     }
 }
 
-// Pair item (P, Q), row blocks X in [xa, xb): accumulates U(p,q;r) over the visits,
-// then writes the two output blocks (rows of P, rows of Q) to out[2][16][Rpad].
-template <bool R4>
+// Weight of the visit with k block kb (see the table at the top of the file).
+template <int KIND> __device__ __forceinline__ float visit_weight(u32 b1, u32 b2, u32 kb)
+{
+    if (KIND == 0) return (kb == b1 && b1 != b2) ? 0.5f : 1.f;
+    return (b1 == b2 || kb == b2) ? 0.5f : 1.f;
+}
+
+// Pair item of blocks (b1, b2), k blocks [va, vb): accumulates U(i1,i2;r) over the
+// visits, then writes the rows of b1 (sums over i2) to out[0][16][Rpad] and, for
+// KIND 0 with b1 < b2, the rows of b2 (sums over i1) to out[1][16][Rpad].
+// SYM: a (P,P) item, every tile is completed by mirroring.
+template <int KIND, bool SYM, bool R4>
 __device__ __forceinline__ void pair_loop(LdsPair &L, const float *__restrict__ Tc, const float *__restrict__ B,
-                                          u32 n, u32 R, u32 P, u32 Q, u32 xa, u32 xb, u32 rbase, u32 rt,
+                                          u32 n, u32 R, u32 b1, u32 b2, u32 va, u32 vb, u32 rbase, u32 rt,
                                           bool has_rt, float *__restrict__ out, u32 Rpad)
 {
+    static_assert(!(SYM && KIND == 1), "only (P,P) items mirror every visit");
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const u32 cw = wave & 3u, half = wave >> 2, lrow = lane & 15u, lq = lane >> 4;
-    const u32 p0 = P * 16u, q0 = Q * 16u;
-    const u32 nv = xb - xa;
+    const u32 b1_0 = b1 * 16u, b2_0 = b2 * 16u;
+    const u32 nv = vb - va;
 
-    f32x4 acc[8];                                         // U(p = 8*half + j, q = 4*(lane/16) + v; r)
+    f32x4 acc[8];                                         // U(i1 = 8*half + j, i2 = 4*(lane/16) + v; r)
 #pragma unroll
     for (int j = 0; j < 8; ++j) acc[j] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
     float pf[8], bb[4];
-    load_pair_visit<R4>(xa * 16u, p0, q0, Tc, B, n, R, rbase, tid, pf, bb);
-    store_pair_visit(R, rbase, L.tile[0], L.bx[0], tid, pf, bb);
-    if (nv > 1) load_pair_visit<R4>((xa + 1u) * 16u, p0, q0, Tc, B, n, R, rbase, tid, pf, bb);
+    // first visit: for an (X,P) item that starts at Q = P the q block is the p block
+    if (KIND == 1 && va == b2) {
+        if (b1 == b2) {
+            load_diag_visit<R4>(b1_0, Tc, B, n, R, rbase, tid, pf, bb);
+            store_pair_visit<KIND, false>(R, rbase, 0.5f, L.tile[0], L.bk[0], tid, pf, bb);
+        } else {
+            load_pair_visit<KIND, R4>(b1_0, b2_0, va * 16u, Tc, B, n, R, rbase, tid, pf, bb);
+            store_pair_visit<KIND, true>(R, rbase, 0.5f, L.tile[0], L.bk[0], tid, pf, bb);
+        }
+    } else {
+        load_pair_visit<KIND, R4>(b1_0, b2_0, va * 16u, Tc, B, n, R, rbase, tid, pf, bb);
+        store_pair_visit<KIND, SYM>(R, rbase, visit_weight<KIND>(b1, b2, va), L.tile[0], L.bk[0], tid, pf, bb);
+    }
+    if (nv > 1) load_pair_visit<KIND, R4>(b1_0, b2_0, (va + 1u) * 16u, Tc, B, n, R, rbase, tid, pf, bb);
     __syncthreads();
 
     for (u32 v = 0; v < nv; ++v) {
         const u32 cb = v & 1u;
-        if (v + 1 < nv) store_pair_visit(R, rbase, L.tile[cb ^ 1u], L.bx[cb ^ 1u], tid, pf, bb);
-        if (v + 2 < nv) load_pair_visit<R4>((xa + v + 2u) * 16u, p0, q0, Tc, B, n, R, rbase, tid, pf, bb);
-        __builtin_amdgcn_sched_barrier(0);
+        // The MFMAs of visit v are issued first: they run on the matrix pipe while this
+        // wave waits for the loads of visit v+1, parks them in the other buffer (its last
+        // readers finished before the barrier that ended iteration v-1) and puts visit
+        // v+2 in flight.
         if (has_rt) {
-            // lane = (q, x-quad): component t of the 16-byte read is x = 4*(lane/16) + t
-            const float *bxp = &L.bx[cb][(4u * lq) * BS + cw * 16u + lrow];
-            const float bx0 = bxp[0], bx1 = bxp[BS], bx2 = bxp[2 * BS], bx3 = bxp[3 * BS];
+            // lane = (i2, k-quad): component t of the 16-byte read is k = 4*(lane/16) + t
+            const float *bkp = &L.bk[cb][(4u * lq) * BS + cw * 16u + lrow];
+            const float bk0 = bkp[0], bk1 = bkp[BS], bk2 = bkp[2 * BS], bk3 = bkp[3 * BS];
             const float *ap = &L.tile[cb][(half * 8u) * PS + lrow * QS + 4u * lq];
-            // two groups of four p: 16 independent MFMAs per group keep the matrix pipe
+            // two groups of four i1: 16 independent MFMAs per group keep the matrix pipe
             // busy with half the operand registers
 #pragma unroll
             for (int g = 0; g < 2; ++g) {
@@ -368,55 +417,62 @@ __device__ __forceinline__ void pair_loop(LdsPair &L, const float *__restrict__ 
                 for (int j = 0; j < 4; ++j) a[j] = *reinterpret_cast<const f32x4 *>(ap + (4 * g + j) * PS);
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    acc[4 * g + j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[j][0], bx0, acc[4 * g + j], 0, 0, 0);
+                    acc[4 * g + j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[j][0], bk0, acc[4 * g + j], 0, 0, 0);
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    acc[4 * g + j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[j][1], bx1, acc[4 * g + j], 0, 0, 0);
+                    acc[4 * g + j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[j][1], bk1, acc[4 * g + j], 0, 0, 0);
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    acc[4 * g + j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[j][2], bx2, acc[4 * g + j], 0, 0, 0);
+                    acc[4 * g + j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[j][2], bk2, acc[4 * g + j], 0, 0, 0);
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
-                    acc[4 * g + j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[j][3], bx3, acc[4 * g + j], 0, 0, 0);
+                    acc[4 * g + j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[j][3], bk3, acc[4 * g + j], 0, 0, 0);
             }
         }
+        __builtin_amdgcn_sched_barrier(0);
+        if (v + 1 < nv)
+            store_pair_visit<KIND, SYM>(R, rbase, visit_weight<KIND>(b1, b2, va + v + 1u), L.tile[cb ^ 1u],
+                                        L.bk[cb ^ 1u], tid, pf, bb);
+        if (v + 2 < nv) load_pair_visit<KIND, R4>(b1_0, b2_0, (va + v + 2u) * 16u, Tc, B, n, R, rbase, tid, pf, bb);
         __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
     }
 
-    // outputs: rows of P from sums over q, rows of Q from sums over p
+    // outputs: rows of b1 from sums over i2, rows of b2 from sums over i1
+    constexpr bool TWO = (KIND == 0) && !SYM;
     const u32 r = rt * 16u + lrow;
     const bool r_ok = has_rt && r < R;
     float mk[4] = {0.f, 0.f, 0.f, 0.f};
     float mj[8];
-    float bqv[4];
+    float b2v[4];
 #pragma unroll
-    for (u32 v = 0; v < 4; ++v) bqv[v] = r_ok ? B[(size_t)(q0 + 4u * lq + v) * R + r] : 0.f;
+    for (u32 v = 0; v < 4; ++v) b2v[v] = r_ok ? B[(size_t)(b2_0 + 4u * lq + v) * R + r] : 0.f;
 #pragma unroll
     for (u32 j = 0; j < 8; ++j) {
-        const float bpv = r_ok ? B[(size_t)(p0 + half * 8u + j) * R + r] : 0.f;
         float s = 0.f;
+        if constexpr (TWO) {
+            const float b1v = r_ok ? B[(size_t)(b1_0 + half * 8u + j) * R + r] : 0.f;
 #pragma unroll
-        for (u32 v = 0; v < 4; ++v) {
-            mk[v] += bpv * acc[j][v];
-            s += bqv[v] * acc[j][v];
+            for (u32 v = 0; v < 4; ++v) mk[v] += b1v * acc[j][v];
         }
-        // add the four q-quads (lanes l, l^16, l^32, l^48); every lane ends with the same sum
+#pragma unroll
+        for (u32 v = 0; v < 4; ++v) s += b2v[v] * acc[j][v];
+        // add the four i2-quads (lanes l, l^16, l^32, l^48); every lane ends with the same sum
         s += __shfl_xor(s, 16);
         s += __shfl_xor(s, 32);
         mj[j] = s;
     }
-    // the two halves of the p range meet in LDS for the rows of Q (the loop ended
-    // with a barrier, so the tile buffer is free)
-    f32x4 *xch = reinterpret_cast<f32x4 *>(&L.tile[0][0]);
-    if (half == 1u) xch[cw * 64u + lane] = (f32x4){mk[0], mk[1], mk[2], mk[3]};
-    __syncthreads();
-    if (has_rt) {
-        if (lq == 0u) {
+    if (has_rt && lq == 0u) {
 #pragma unroll
-            for (u32 j = 0; j < 8; ++j) out[(size_t)(half * 8u + j) * Rpad + rt * 16u + lrow] = 2.f * mj[j];
-        }
-        if (half == 0u) {
+        for (u32 j = 0; j < 8; ++j) out[(size_t)(half * 8u + j) * Rpad + rt * 16u + lrow] = 2.f * mj[j];
+    }
+    if constexpr (TWO) {
+        // the two halves of the i1 range meet in LDS for the rows of b2 (the loop ended
+        // with a barrier, so the tile buffer is free)
+        f32x4 *xch = reinterpret_cast<f32x4 *>(&L.tile[0][0]);
+        if (half == 1u) xch[cw * 64u + lane] = (f32x4){mk[0], mk[1], mk[2], mk[3]};
+        __syncthreads();
+        if (has_rt && half == 0u) {
             const f32x4 o = xch[cw * 64u + lane];
             // D layout: lane holds column lane%16 of rows 4*(lane/16) + v
 #pragma unroll
@@ -426,55 +482,76 @@ __device__ __forceinline__ void pair_loop(LdsPair &L, const float *__restrict__ 
     }
 }
 
-// ---- the kernel ----------------------------------------------------------------------------
-// items [0, nitemsA): row block X = item / NCHA, chunk ch = item % NCHA (ch < NCHR: row
-// item, else gather item);  items [nitemsA, ..): block pair (P, Q) and chunk c.
+// ---- the kernels --------------------------------------------------------------------------
+// n a multiple of 16: 2*npairs*CHB pair items (block pair and chunk slot; slots beyond
+// the pair's own number of chunks exit at once).
 template <bool R4>
-__global__ __launch_bounds__(NT) void mttkrp_mfma_kernel(const float *__restrict__ Tc,
+__global__ __launch_bounds__(NT, ST_MTTKRP_WPE) void mttkrp_pair_kernel(const float *__restrict__ Tc,
                                                        const float *__restrict__ B,
-                                                       float *__restrict__ partA, float *__restrict__ partB,
+                                                       float *__restrict__ partPQ, float *__restrict__ partXP,
                                                        u32 n, u32 R, MttkrpPlan pl)
 {
-    __shared__ __attribute__((aligned(16))) unsigned char lds_raw[LDS_BYTES];
-    const u32 lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    __shared__ __attribute__((aligned(16))) LdsPair L;
+    const u32 wave = threadIdx.x >> 6;
     const u32 rbase = blockIdx.y * 64u;                  // this workgroup's 64 columns of R
     const u32 rt = blockIdx.y * 4u + (wave & 3u);        // this wave's block of 16 columns
     const bool has_rt = rt * 16u < R;
-    const u32 item = blockIdx.x;
 
-    if (item >= pl.nitemsA) {
-        const u32 it = item - pl.nitemsA, pidx = it / pl.CHB, c = it - pidx * pl.CHB;
-        u32 P, Qm;
-        unrank_sym2<u32>(pl.NB - 1u, pidx, P, Qm);      // inverse of pair_index: (P, Q-1)
-        if (c >= pair_chunks(pl, P)) return;
-        const u32 xa = c * pl.PPB, xb = min(P, xa + pl.PPB);
-        pair_loop<R4>(*reinterpret_cast<LdsPair *>(lds_raw), Tc, B, n, R, P, Qm + 1u, xa, xb, rbase, rt, has_rt,
-                      partB + (size_t)it * 32u * pl.Rpad, pl.Rpad);
-        return;
+    // Launch order: pair after pair, longest pairs first ((P,Q) items have about P visits
+    // per pair, (X,P) items NB-P), the 2*CHB slots of a pair (kind, chunk) next to each
+    // other, so that the long items start early.  Workgroups go to the XCDs round-robin
+    // by index: the slots of a pair are rotated by a hash of the pair, or the empty
+    // slots of the short pairs would all land on the same XCDs.
+    const u32 g = 2u * pl.CHB;
+    const u32 kp = blockIdx.x / g, pos = blockIdx.x - kp * g;
+    const u32 slot = (pos + ((kp * 0x9E3779B1u) >> 16)) % g;
+    const bool xp = (slot & 1u) != 0u;
+    const u32 c = slot >> 1;
+    u32 a, b;
+    unrank_sym2<u32>(pl.NB, pl.npairs - 1u - kp, a, b);          // a <= b, a descending
+    if (!xp) {
+        const u32 P = a, Q = b, nvis = visits_pq(P, Q);
+        const u32 nc = chunks_of(pl, nvis);
+        if (c >= nc) return;
+        const u32 va = c * nvis / nc, vb = (c + 1u) * nvis / nc;                  // row blocks X, even chunks
+        float *out = partPQ + ((size_t)rank_sym2<u32>(pl.NB, P, Q) * pl.CHB + c) * 32u * pl.Rpad;
+        if (P < Q) pair_loop<0, false, R4>(L, Tc, B, n, R, P, Q, va, vb, rbase, rt, has_rt, out, pl.Rpad);
+        else pair_loop<0, true, R4>(L, Tc, B, n, R, P, Q, va, vb, rbase, rt, has_rt, out, pl.Rpad);
+    } else {
+        const u32 X = pl.NB - 1u - b, P = pl.NB - 1u - a;         // mirrored: X <= P, P ascending
+        const u32 nvis = visits_xp(pl.NB, P), nc = chunks_of(pl, nvis);
+        if (c >= nc) return;
+        const u32 va = P + c * nvis / nc, vb = P + (c + 1u) * nvis / nc;          // blocks Q, even chunks
+        float *out = partXP + ((size_t)rank_sym2<u32>(pl.NB, X, P) * pl.CHB + c) * 16u * pl.Rpad;
+        pair_loop<1, false, R4>(L, Tc, B, n, R, X, P, va, vb, rbase, rt, has_rt, out, pl.Rpad);
     }
+}
 
-    const u32 X = item / pl.NCHA, ch = item - X * pl.NCHA;
-    if (ch < pl.NCHR && ch >= row_chunks(pl, X)) return;
+// n not a multiple of 16: gather items, row block X = item / NCHG, chunk item % NCHG.
+template <bool R4>
+__global__ __launch_bounds__(NT) void mttkrp_gather_kernel(const float *__restrict__ Tc,
+                                                         const float *__restrict__ B,
+                                                         float *__restrict__ partG, u32 n, u32 R, MttkrpPlan pl)
+{
+    __shared__ __attribute__((aligned(16))) LdsGather L;
+    const u32 lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    const u32 rbase = blockIdx.y * 64u;
+    const u32 rt = blockIdx.y * 4u + (wave & 3u);
+    const bool has_rt = rt * 16u < R;
 
+    const u32 item = blockIdx.x;
+    const u32 X = item / pl.NCHG, ch = item - X * pl.NCHG;
     f32x4 acc[4];
 #pragma unroll
     for (int t = 0; t < 4; ++t) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    LdsRow &L = *reinterpret_cast<LdsRow *>(lds_raw);
-    if (ch < pl.NCHR) {
-        const u32 v0 = ch * pl.PPR;
-        visit_loop<false, R4>(L, Tc, B, n, R, pl.NB, X, false, v0, min(strict_pairs(pl.NB - 1u - X), v0 + pl.PPR),
-                              rbase, has_rt, acc);
-    } else {
-        const u32 v0 = (ch - pl.NCHR) * pl.PPG;
-        visit_loop<true, R4>(L, Tc, B, n, R, pl.NB, X, pl.all_pairs != 0u, v0, min(pl.ngat, v0 + pl.PPG), rbase,
-                             has_rt, acc);
-    }
+    const u32 v0 = ch * pl.PPG;
+    gather_loop<R4>(L, Tc, B, n, R, pl.NB, X, v0, min(pl.ngat, v0 + pl.PPG), rbase, has_rt, acc);
 
     f32x4 sum;
 #pragma unroll
     for (u32 v = 0; v < 4; ++v) sum[v] = (acc[0][v] + acc[1][v]) + (acc[2][v] + acc[3][v]);
     // the waves of the upper half of the p range hand their sums to the lower half
-    // (the visit loops end with a barrier, so the tile buffer is free)
+    // (the visit loop ends with a barrier, so the tile buffer is free)
     f32x4 *xch = reinterpret_cast<f32x4 *>(&L.tile[0][0]);
     if (wave >= 4u) xch[(wave - 4u) * 64u + lane] = sum;
     __syncthreads();
@@ -482,18 +559,20 @@ __global__ __launch_bounds__(NT) void mttkrp_mfma_kernel(const float *__restrict
         const f32x4 o = xch[wave * 64u + lane];
         // D layout: lane holds column lane%16 of rows 4*(lane/16) + v
         const u32 lrow = lane & 15u, lq = lane >> 4;
-        float *dst = partA + ((size_t)item * 16u) * pl.Rpad + rt * 16u + lrow;
+        float *dst = partG + ((size_t)item * 16u) * pl.Rpad + rt * 16u + lrow;
 #pragma unroll
         for (u32 v = 0; v < 4; ++v) dst[(size_t)(4u * lq + v) * pl.Rpad] = sum[v] + o[v];
     }
 }
 
 // M(16X + x, r) = sum of the partial blocks that target row block X, in a fixed
-// order: 16 slices per output value -- slices 0..7 the row/gather chunks (ch mod 8),
-// slices 8..11 the pair items (X, Q) by Q mod 4, slices 12..15 the pair items
-// (P, X) by P mod 4; inside a slice ascending, then slices ascending.
-__global__ __launch_bounds__(512) void mttkrp_reduce_kernel(const float *__restrict__ partA,
-                                                          const float *__restrict__ partB,
+// order: 16 slices per output value.  Ragged n: the gather chunks by ch mod 16.
+// Otherwise slices 0..5 the (X,P) items by P mod 6, slices 6..10 the (X,Q) items of
+// kind (P,Q) by Q mod 5 (first output block), slices 11..15 the (P,X) items by
+// P mod 5 (second output block); inside a slice ascending, then slices ascending.
+__global__ __launch_bounds__(512) void mttkrp_reduce_kernel(const float *__restrict__ partG,
+                                                          const float *__restrict__ partPQ,
+                                                          const float *__restrict__ partXP,
                                                           float *__restrict__ M, u32 n, u32 R, MttkrpPlan pl)
 {
     __shared__ float accs[16][32];
@@ -503,27 +582,30 @@ __global__ __launch_bounds__(512) void mttkrp_reduce_kernel(const float *__restr
     if (t < n * R) {
         const u32 i = t / R, r = t - i * R, X = i >> 4, x = i & 15u;
         const size_t blk = (size_t)16u * pl.Rpad, off = (size_t)x * pl.Rpad + r;
-        if (sl < 8u) {
-            const u32 nr = row_chunks(pl, X);
-            const float *src = partA + (size_t)X * pl.NCHA * blk + off;
-#pragma unroll 4
-            for (u32 c = sl; c < nr; c += 8u) s += src[(size_t)c * blk];
+        if (pl.all_pairs) {
+            const float *src = partG + (size_t)X * pl.NCHG * blk + off;
 #pragma unroll 2
-            for (u32 c = sl; c < pl.NCHG; c += 8u) s += src[(size_t)(pl.NCHR + c) * blk];
-        } else if (sl < 12u) {
-            const u32 nc = pair_chunks(pl, X);
-            if (nc > 0u) {
-                // pair_index(X, Q) is consecutive in Q
-                const float *src = partB + (size_t)pair_index(pl.NB, X, X + 1u) * pl.CHB * 2u * blk + off;
+            for (u32 c = sl; c < pl.NCHG; c += 16u) s += src[(size_t)c * blk];
+        } else if (sl < 6u) {
+            // rank_sym2(X, P) is consecutive in P
+            const float *src = partXP + (size_t)rank_sym2<u32>(pl.NB, X, X) * pl.CHB * blk + off;
 #pragma unroll 2
-                for (u32 dq = sl - 8u; X + 1u + dq < pl.NB; dq += 4u)
-                    for (u32 c = 0; c < nc; ++c) s += src[((size_t)dq * pl.CHB + c) * 2u * blk];
+            for (u32 dp = sl; X + dp < pl.NB; dp += 6u) {
+                const u32 nc = chunks_of(pl, visits_xp(pl.NB, X + dp));
+                for (u32 c = 0; c < nc; ++c) s += src[((size_t)dp * pl.CHB + c) * blk];
             }
-        } else if (!pl.all_pairs) {
+        } else if (sl < 11u) {
+            const float *src = partPQ + (size_t)rank_sym2<u32>(pl.NB, X, X) * pl.CHB * 2u * blk + off;
 #pragma unroll 2
-            for (u32 P = 1u + (sl - 12u); P < X; P += 4u) {
-                const u32 nc = pair_chunks(pl, P);
-                const float *src = partB + (size_t)pair_index(pl.NB, P, X) * pl.CHB * 2u * blk + blk + off;
+            for (u32 dq = sl - 6u; X + dq < pl.NB; dq += 5u) {
+                const u32 nc = chunks_of(pl, visits_pq(X, X + dq));
+                for (u32 c = 0; c < nc; ++c) s += src[((size_t)dq * pl.CHB + c) * 2u * blk];
+            }
+        } else {
+#pragma unroll 2
+            for (u32 P = sl - 11u; P < X; P += 5u) {
+                const u32 nc = chunks_of(pl, visits_pq(P, X));
+                const float *src = partPQ + (size_t)rank_sym2<u32>(pl.NB, P, X) * pl.CHB * 2u * blk + blk + off;
                 for (u32 c = 0; c < nc; ++c) s += src[(size_t)c * 2u * blk];
             }
         }
@@ -546,51 +628,52 @@ static inline MttkrpPlan plan(int n, int R)
     p.Rpad = p.RT * 16u;
     p.all_pairs = (n % 16 != 0) ? 1u : 0u;
     const u32 npairs = p.NB * (p.NB + 1u) / 2u;
-    p.ngat = p.all_pairs ? npairs : 2u * p.NB - 1u;
-    p.npairs_strict = p.all_pairs ? 0u : strict_pairs(p.NB);
-    // work in visits: row and pair visits of the C(NB,3) sub-tensors with three different
-    // blocks, and gather visits (weighted 2: per-element address arithmetic)
-    uint64_t triples = p.all_pairs ? 0u : (uint64_t)p.NB * (p.NB - 1u) * (p.NB >= 2u ? p.NB - 2u : 0u) / 6u;
-    uint64_t work = 2u * triples + 2u * (uint64_t)p.NB * p.ngat;
-    u32 unit = (u32)((work + 1499u) / 1500u);          // about 1500 items in all
+    p.ngat = p.all_pairs ? npairs : 0u;
+    p.npairs = p.all_pairs ? 0u : npairs;
+    // work in visits: every block triple X <= P <= Q is visited twice (once by each pair
+    // kind; the triples that repeat a block split differently but add up to the same),
+    // or NB * npairs gather visits (weighted 2: per-element address arithmetic)
+    const uint64_t triples = (uint64_t)p.NB * (p.NB + 1u) * (p.NB + 2u) / 6u;
+    const uint64_t work = p.all_pairs ? 2u * (uint64_t)p.NB * npairs : 2u * triples;
+    u32 unit = (u32)((work + (ST_MTTKRP_ITEMS - 1u)) / ST_MTTKRP_ITEMS);   // about that many items in all
     if (unit < 2u) unit = 2u;
-    p.PPR = unit;
     p.PPB = unit;
     p.PPG = unit / 2u;
-    p.NCHR = p.all_pairs ? 0u : (strict_pairs(p.NB - 1u) + p.PPR - 1u) / p.PPR;
-    p.NCHG = (p.ngat + p.PPG - 1u) / p.PPG;
-    p.NCHA = p.NCHR + p.NCHG;
-    p.CHB = (p.all_pairs || p.NB < 3u) ? 1u : (p.NB - 2u + p.PPB - 1u) / p.PPB;
-    p.nitemsA = p.NB * p.NCHA;
+    p.NCHG = p.all_pairs ? (p.ngat + p.PPG - 1u) / p.PPG : 0u;
+    p.CHB = (p.NB + p.PPB - 1u) / p.PPB;                  // the longest item has NB visits
+    p.nitemsG = p.NB * p.NCHG;
     return p;
 }
 
-static inline size_t partA_floats(const MttkrpPlan &p) { return (size_t)p.nitemsA * 16u * p.Rpad; }
-static inline size_t partB_floats(const MttkrpPlan &p) { return (size_t)p.npairs_strict * p.CHB * 32u * p.Rpad; }
+static inline size_t partG_floats(const MttkrpPlan &p) { return (size_t)p.nitemsG * 16u * p.Rpad; }
+static inline size_t partPQ_floats(const MttkrpPlan &p) { return (size_t)p.npairs * p.CHB * 32u * p.Rpad; }
+static inline size_t partXP_floats(const MttkrpPlan &p) { return (size_t)p.npairs * p.CHB * 16u * p.Rpad; }
 
 size_t mttkrp_workspace(int n, int R)
 {
     MttkrpPlan p = plan(n, R);
-    return (partA_floats(p) + partB_floats(p)) * sizeof(float);
+    return (partG_floats(p) + partPQ_floats(p) + partXP_floats(p)) * sizeof(float);
 }
 
 st_status launch_mttkrp(const float *Tc, const float *B, float *M, int n, int R, void *ws, hipStream_t s)
 {
     MttkrpPlan p = plan(n, R);
     u32 gy = (p.RT + 3u) / 4u;
-    uint64_t items = (uint64_t)p.nitemsA + (uint64_t)p.npairs_strict * p.CHB;
+    uint64_t items = p.all_pairs ? (uint64_t)p.nitemsG : 2u * (uint64_t)p.npairs * p.CHB;
     if (items > 0x7fffffffull || gy > 65535u) return ST_ERR_UNSUPPORTED;
-    float *partA = static_cast<float *>(ws), *partB = partA + partA_floats(p);
-    if (R % 4 == 0)
-        hipLaunchKernelGGL(mttkrp_mfma_kernel<true>, dim3((u32)items, gy), dim3(NT), 0, s, Tc, B, partA, partB,
-                           (u32)n, (u32)R, p);
-    else
-        hipLaunchKernelGGL(mttkrp_mfma_kernel<false>, dim3((u32)items, gy), dim3(NT), 0, s, Tc, B, partA, partB,
-                           (u32)n, (u32)R, p);
+    float *partG = static_cast<float *>(ws), *partPQ = partG + partG_floats(p), *partXP = partPQ + partPQ_floats(p);
+    const dim3 grid((u32)items, gy), block(NT);
+    if (p.all_pairs) {
+        if (R % 4 == 0) hipLaunchKernelGGL(mttkrp_gather_kernel<true>, grid, block, 0, s, Tc, B, partG, (u32)n, (u32)R, p);
+        else hipLaunchKernelGGL(mttkrp_gather_kernel<false>, grid, block, 0, s, Tc, B, partG, (u32)n, (u32)R, p);
+    } else {
+        if (R % 4 == 0) hipLaunchKernelGGL(mttkrp_pair_kernel<true>, grid, block, 0, s, Tc, B, partPQ, partXP, (u32)n, (u32)R, p);
+        else hipLaunchKernelGGL(mttkrp_pair_kernel<false>, grid, block, 0, s, Tc, B, partPQ, partXP, (u32)n, (u32)R, p);
+    }
     if (hipGetLastError() != hipSuccess) return ST_ERR_LAUNCH;
     u32 total = (u32)n * (u32)R;
-    hipLaunchKernelGGL(mttkrp_reduce_kernel, dim3((total + 31u) / 32u), dim3(512), 0, s, partA, partB, M, (u32)n,
-                       (u32)R, p);
+    hipLaunchKernelGGL(mttkrp_reduce_kernel, dim3((total + 31u) / 32u), dim3(512), 0, s, partG, partPQ, partXP, M,
+                       (u32)n, (u32)R, p);
     return launch_status();
 }
 

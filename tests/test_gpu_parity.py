@@ -243,8 +243,8 @@ def test_moment3_full(st, oracle):
 
 
 # ---------------------------------------------------------------------- mttkrp
-@pytest.mark.parametrize("n,R", [(1, 1), (5, 4), (16, 16), (17, 3), (40, 16), (64, 16), (100, 20), (130, 64),
-                                 (48, 80)])
+@pytest.mark.parametrize("n,R", [(1, 1), (5, 4), (16, 16), (17, 3), (32, 5), (40, 16), (64, 16), (96, 32),
+                                 (100, 20), (130, 64), (48, 80), (160, 20), (208, 7)])
 def test_mttkrp_small(st, oracle, n, R):
     say("mttkrp n=%d R=%d" % (n, R))
     Tc, B = W.mttkrp_inputs(n, R, oracle.count_sym3(n), "uniform", config_index=1)
@@ -255,8 +255,8 @@ def test_mttkrp_small(st, oracle, n, R):
     assert np.array_equal(got, got2)                      # deterministic
 
 
-def test_mttkrp_all_ones(st):
-    n, R = 70, 8
+@pytest.mark.parametrize("n,R", [(70, 8), (80, 8)])
+def test_mttkrp_all_ones(st, n, R):
     B = W.uniform(501, n * R).reshape(n, R)
     ones = np.ones(st.count_sym3(n), dtype=np.float32)
     got = st.mttkrp_sym3(dev(ones), dev(B)).cpu().numpy()
