@@ -1,0 +1,84 @@
+// Driver of tests/test_kernel_bounds.py: one kernel family per build (-DCHECK_<NAME>),
+// compiled against the host stand-in of the HIP runtime with AddressSanitizer.  Buffers
+// have exactly the sizes the C-ABI documents, so any access outside them aborts.
+#if defined(CHECK_MTTKRP)
+#include "../../paper_2211_10482_amd/csrc/st_mttkrp.hip"
+#elif defined(CHECK_BATAX)
+#include "../../paper_2211_10482_amd/csrc/st_batax.hip"
+#elif defined(CHECK_TTM)
+#include "../../paper_2211_10482_amd/csrc/st_ttm.hip"
+#elif defined(CHECK_MOMENT3)
+#include "../../paper_2211_10482_amd/csrc/st_moment3.hip"
+#elif defined(CHECK_EXPAND)
+#include "../../paper_2211_10482_amd/csrc/st_expand.hip"
+#else
+#error "define CHECK_<KERNEL>"
+#endif
+#include <cstdio>
+#include <cstdlib>
+
+namespace st {
+float lds[160 * 1024 / 4];
+int num_cus() { return 256; }
+}  // namespace st
+
+static float *fbuf(size_t count)
+{
+    float *p = static_cast<float *>(malloc(count ? count * sizeof(float) : 1));
+    for (size_t i = 0; i < count; ++i) p[i] = 1.f;
+    return p;
+}
+
+int main(int argc, char **argv)
+{
+    long a[6] = {0, 0, 0, 0, 0, 0};
+    for (int i = 1; i < argc && i <= 6; ++i) a[i - 1] = atol(argv[i]);
+    int rc = -1;
+#if defined(CHECK_MTTKRP)
+    const int n = (int)a[0], R = (int)a[1];
+    const size_t cnt = (size_t)st::count_sym3<int64_t>(n), wsb = st::mttkrp_workspace(n, R);
+    float *Tc = fbuf(cnt), *B = fbuf((size_t)n * R), *M = fbuf((size_t)n * R);
+    void *ws = malloc(wsb ? wsb : 1);
+    rc = st::launch_mttkrp(Tc, B, M, n, R, ws, nullptr);
+    free(Tc); free(B); free(M); free(ws);
+#elif defined(CHECK_BATAX)
+    const int n = (int)a[0];
+    const size_t cnt = (size_t)st::count_sym2<int64_t>(n), wsb = st::batax_workspace(n);
+    float *Ap = fbuf(cnt), *x = fbuf(n), *y = fbuf(n);
+    void *ws = malloc(wsb ? wsb : 1);
+    rc = st::launch_batax(Ap, x, y, n, 0.5f, ws, nullptr);
+    free(Ap); free(x); free(y); free(ws);
+#elif defined(CHECK_TTM)
+    const long rows = a[0];
+    const int nl = (int)a[1], R = (int)a[2];
+    float *Tc = fbuf((size_t)rows * nl), *U = fbuf((size_t)nl * R), *Y = fbuf((size_t)rows * R);
+    rc = st::launch_ttm(Tc, U, Y, rows, nl, R, nullptr, nullptr);
+    free(Tc); free(U); free(Y);
+#elif defined(CHECK_MOMENT3)
+    const long N = a[0];
+    const int n = (int)a[1], accumulate = (int)a[2];
+    const size_t cnt = (size_t)st::count_sym3<int64_t>(n), wsb = st::moment3_workspace(N, n);
+    float *X = fbuf((size_t)N * n), *Sc = fbuf(cnt);
+    void *ws = malloc(wsb ? wsb : 1);
+    rc = st::launch_moment3(X, N, n, Sc, accumulate, ws, nullptr);
+    free(X); free(Sc); free(ws);
+#elif defined(CHECK_EXPAND)
+    const int n = (int)a[0], order = (int)a[1];
+    if (order == 2 || order == 3) {
+        const size_t cnt = (size_t)(order == 2 ? st::count_sym2<int64_t>(n) : st::count_sym3<int64_t>(n));
+        size_t full = 1;
+        for (int i = 0; i < order; ++i) full *= (size_t)n;
+        float *Sc = fbuf(cnt), *S = fbuf(full);
+        rc = st::launch_expand(Sc, S, n, order, nullptr);
+        free(Sc); free(S);
+    } else {   // order = 10 + kind: device unrank of `count` positions from p0
+        const int kind = order - 10;
+        const long w = a[2], p0 = a[3], count = a[4];
+        int32_t *out = static_cast<int32_t *>(malloc((size_t)count * (kind == 3 ? 3 : 2) * sizeof(int32_t) + 1));
+        rc = st::launch_unrank(kind, n, w, p0, count, out, nullptr);
+        free(out);
+    }
+#endif
+    printf("rc=%d\n", rc);
+    return rc == 0 ? 0 : 1;
+}

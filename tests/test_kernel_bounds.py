@@ -1,0 +1,59 @@
+"""Bounds check of every kernel's addressing on the CPU (no GPU involved).
+
+Each kernel family is compiled as plain C++ against tests/emul/hip/hip_runtime.h, a
+stand-in for the HIP runtime that runs a launch as nested loops over workgroups and
+threads, and linked with AddressSanitizer.  The driver (tests/emul/bounds_check.cpp)
+allocates the operands with exactly the sizes the C-ABI documents and calls the same
+launchers the library calls, so an index that leaves an operand, the workspace or an
+LDS array aborts here instead of faulting a GPU.  Values are not checked (barriers and
+cross-lane operations have no meaning in this emulation); parity is the GPU tests' job.
+"""
+import os
+import shutil
+import subprocess
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+EMUL = os.path.join(ROOT, "tests", "emul")
+CLANG = shutil.which("clang++", path="/opt/rocm/llvm/bin") or shutil.which("clang++")
+
+CASES = {
+    # mttkrp: n R  (multiples of 16 take the pair items, the others the gather items)
+    "MTTKRP": [(1, 1), (5, 4), (16, 16), (17, 3), (32, 5), (48, 80), (64, 16), (100, 20), (160, 20),
+               (208, 7), (256, 64), (512, 64)],
+    # batax: n  (one-pass kernel to 8192, two-pass beyond; n % 4 != 0 takes the guarded loads)
+    "BATAX": [(1,), (5,), (64,), (100,), (1000,), (1023,), (4096,), (8192,), (9001,)],
+    # ttm: rows nl R  (split-K shapes, the general MFMA path, the plain path)
+    "TTM": [(8632, 512, 64), (16590, 128, 48), (1090, 256, 16), (208, 512, 32), (1, 64, 16), (777, 48, 32),
+            (50, 7, 5), (33, 16, 256)],
+    # moment3: N n accumulate  (n = 64 is the MFMA path, others the plain path)
+    "MOMENT3": [(5000, 64, 0), (4097, 64, 1), (63, 64, 0), (100000, 64, 0), (1000, 20, 0), (3, 5, 1),
+                (700, 70, 0)],
+    # expand: n order | n 10+kind w p0 count  (device unrank of kind 2, 3, 4 = band)
+    "EXPAND": [(64, 3), (100, 2), (7, 3), (1, 2), (100, 12, 0, 17, 5000), (100, 13, 0, 17, 5000),
+               (100, 14, 7, 17, 1000)],
+}
+
+
+@pytest.fixture(scope="module")
+def builds(tmp_path_factory):
+    if CLANG is None:
+        pytest.skip("no clang++ for the host build")
+    out = tmp_path_factory.mktemp("emul")
+    exes = {}
+    for fam in CASES:
+        exe = str(out / ("bounds_" + fam.lower()))
+        cmd = [CLANG, "-std=c++17", "-O1", "-g", "-fsanitize=address", "-fno-omit-frame-pointer",
+               "-DCHECK_" + fam, "-I", EMUL, "-x", "c++", os.path.join(EMUL, "bounds_check.cpp"), "-o", exe]
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        assert r.returncode == 0, "host build of %s failed:\n%s" % (fam, r.stderr[-4000:])
+        exes[fam] = exe
+    return exes
+
+
+@pytest.mark.parametrize("fam", sorted(CASES))
+def test_kernel_addressing_in_bounds(builds, fam):
+    for case in CASES[fam]:
+        r = subprocess.run([builds[fam]] + [str(v) for v in case], capture_output=True, text=True, timeout=600)
+        assert r.returncode == 0 and "rc=0" in r.stdout, "%s %s:\n%s\n%s" % (fam, case, r.stdout[-500:], r.stderr[-4000:])
