@@ -71,6 +71,24 @@ template <int M> __device__ __forceinline__ float row_bcast(float v)
                                                                  0x150 + M, 0xf, 0xf, false));
 }
 
+// other * (lane M of bsrc's 16-lane row) in one VALU instruction.  Written out because
+// the compiler materialises a broadcast that has two users as a separate move.  The
+// instruction is opaque to the compiler's hazard checks, so the caller keeps VALU writes
+// of `bsrc` at least two instructions away (here: bsrc only ever comes from LDS loads,
+// and the block of these products starts with the required wait states).
+template <int M> __device__ __forceinline__ float mul_bcast(float bsrc, float other)
+{
+#ifdef ST_HOST_EMULATION   // CPU bounds-check build of the tests: no GPU instructions
+    return row_bcast<M>(bsrc) * other;
+#else
+    float r;
+    asm volatile("v_mul_f32_dpp %0, %1, %2 row_newbcast:%3 row_mask:0xf bank_mask:0xf bound_ctrl:1"
+                 : "=v"(r)
+                 : "v"(bsrc), "v"(other), "n"(M));
+    return r;
+#endif
+}
+
 // Tile descriptor shared by the accumulation kernel (compile time) and the
 // reduction kernel (run time).  Tile `local` of wave `w`:
 //   local 0..17 : pair-in-group tiles; half unit h = 9 w + local/2 = (g*9 + d)*2 + half,
@@ -96,7 +114,10 @@ __host__ __device__ constexpr TileDesc tile_desc(int w, int local)
     return TileDesc{1, (local - 22) % 2, 2, 3, 2 * w + (local - 22) / 2};
 }
 
-constexpr int M3_CH = 64;                          // samples per staged chunk (16 K-steps)
+#ifndef ST_M3_CH
+#define ST_M3_CH 64
+#endif
+constexpr int M3_CH = ST_M3_CH;                    // samples per staged chunk (a multiple of 16)
 constexpr int M3_THREADS = M3_WAVES * 64;
 constexpr int M3_LPT = M3_CH * 16 / M3_THREADS;    // 16-byte pieces of a chunk per thread (2)
 
@@ -145,16 +166,19 @@ __device__ __forceinline__ void m3_step(f32x4 (&acc)[M3_TPW], const f32x4 &xa)
     // 26 MFMAs back to back: a product that is formed right in front of its MFMA in
     // a recycled register has to wait for the previous MFMA to release it.
     float pw[9], p12[2], p13[2], p23[2];
+#ifndef ST_HOST_EMULATION
+    asm volatile("s_nop 1");
+#endif
+    static_for<2>([&](auto E) {
+        constexpr int m = 2 * W + E;
+        p12[E] = mul_bcast<m>(xa[1], xa[2]);
+        p13[E] = mul_bcast<m>(xa[1], xa[3]);
+        p23[E] = mul_bcast<m>(xa[2], xa[3]);
+    });
     static_for<9>([&](auto HU) {
         constexpr int h = 9 * W + HU;
         constexpr int gd = h / 2, g = gd / 9, d = gd % 9;
         pw[HU] = xa[g] * row_ror<d>(xa[g]);
-    });
-    static_for<2>([&](auto E) {
-        constexpr int m = 2 * W + E;
-        const float b1 = row_bcast<m>(xa[1]);
-        const float b2 = row_bcast<m>(xa[2]);
-        p12[E] = xa[2] * b1; p13[E] = xa[3] * b1; p23[E] = xa[3] * b2;
     });
     __builtin_amdgcn_sched_barrier(0);
     // pair-in-group half units
@@ -205,24 +229,23 @@ __device__ __forceinline__ void m3_wave(const float *__restrict__ X, int64_t s_b
         f32x4 xa[4];
 #pragma unroll
         for (int k = 0; k < 4; ++k) xa[k] = *reinterpret_cast<const f32x4 *>(src + k * 256);
-        // four groups of four K-steps; kept as a real loop so that the eight per-wave
+        // groups of four K-steps; kept as a real loop so that the eight per-wave
         // code streams stay small enough for the instruction cache
+        constexpr int NG = M3_CH / 16;
 #pragma unroll 1
-        for (int g = 0; g < 4; ++g) {
-            // the next four K-steps are read while these four are multiplied (the last
-            // group re-reads itself, which is harmless)
-            const float *nsrc = src + (g < 3 ? g + 1 : 3) * 1024;
-            f32x4 xb[4];
-#pragma unroll
-            for (int k = 0; k < 4; ++k) xb[k] = *reinterpret_cast<const f32x4 *>(nsrc + k * 256);
-            __builtin_amdgcn_sched_barrier(0);
+        for (int g = 0; g < NG; ++g) {
+            // (the last group re-reads itself, which is harmless)
+            const float *nsrc = src + (g < NG - 1 ? g + 1 : NG - 1) * 1024;
+            // each operand register is refilled with the next group's K-step right after
+            // its last use, so three steps of MFMAs cover the LDS latency
             m3_step<W>(acc, xa[0]);
+            xa[0] = *reinterpret_cast<const f32x4 *>(nsrc);
             m3_step<W>(acc, xa[1]);
+            xa[1] = *reinterpret_cast<const f32x4 *>(nsrc + 256);
             m3_step<W>(acc, xa[2]);
+            xa[2] = *reinterpret_cast<const f32x4 *>(nsrc + 512);
             m3_step<W>(acc, xa[3]);
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int k = 0; k < 4; ++k) xa[k] = xb[k];
+            xa[3] = *reinterpret_cast<const f32x4 *>(nsrc + 768);
         }
         __builtin_amdgcn_sched_barrier(0);
         __syncthreads();

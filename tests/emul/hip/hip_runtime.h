@@ -14,6 +14,7 @@
 #include <string.h>
 #include <algorithm>
 
+#define ST_HOST_EMULATION 1   // kernels skip their inline GPU assembly
 #define __global__
 #define __device__
 #define __host__
