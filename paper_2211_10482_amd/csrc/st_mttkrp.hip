@@ -507,8 +507,13 @@ __global__ __launch_bounds__(NT, ST_MTTKRP_WPE) void mttkrp_pair_kernel(const fl
     const u32 slot = (pos + ((kp * 0x9E3779B1u) >> 16)) % g;
     const bool xp = (slot & 1u) != 0u;
     const u32 c = slot >> 1;
+    // (P,Q) and (P,Q-1) read the two halves of the same 128-byte lines: with one slot
+    // pair per block pair they are placed 8 workgroups apart, i.e. on the same XCD (same
+    // L2) at about the same time.
+    u32 kq = kp;
+    if (!xp && g == 2u && (kp | 7u) < pl.npairs) kq = (kp & ~7u) + 2u * (kp & 3u) + ((kp >> 2) & 1u);
     u32 a, b;
-    unrank_sym2<u32>(pl.NB, pl.npairs - 1u - kp, a, b);          // a <= b, a descending
+    unrank_sym2<u32>(pl.NB, pl.npairs - 1u - kq, a, b);          // a <= b, a descending
     if (!xp) {
         const u32 P = a, Q = b, nvis = visits_pq(P, Q);
         const u32 nc = chunks_of(pl, nvis);
