@@ -31,6 +31,7 @@ def lib():
             "so_enum_band": (i64, [i64, i64, p]),
             "so_list_sym2": (i64, [i64, p]),
             "so_list_sym3": (i64, [i64, p]),
+            "so_list_sym4": (i64, [i64, p]),
             "so_list_band": (i64, [i64, i64, p]),
             "so_dense_sym3": (None, [p, i64, p]),
             "so_dense_utri": (None, [p, i64, p]),
@@ -41,6 +42,9 @@ def lib():
             "so_ttm_band": (None, [p, p, i64, i64, i64, i64, p]),
             "so_moment3_dense": (None, [p, i64, i64, p]),
             "so_moment3_entries": (None, [p, i64, i64, p, i64, p]),
+            "so_moment2_dense": (None, [p, i64, i64, p]),
+            "so_moment4_dense": (None, [p, i64, i64, p]),
+            "so_moment4_entries": (None, [p, i64, i64, p, i64, p]),
             "so_expand_sym": (C.c_int, [p, i64, C.c_int, p]),
             "so_num_threads": (C.c_int, []),
         }
@@ -103,6 +107,12 @@ def list_sym2(n):
 def list_sym3(n):
     out = np.empty((count_sym3(n), 3), dtype=np.int16)
     lib().so_list_sym3(n, out.ctypes.data)
+    return out
+
+
+def list_sym4(n):
+    out = np.empty((count_sym4(n), 4), dtype=np.int16)
+    lib().so_list_sym4(n, out.ctypes.data)
     return out
 
 
@@ -204,10 +214,38 @@ def moment3_entries(X, ijk):
     return out
 
 
+def moment2_dense(X):
+    """S(i,j) = sum_s x_s(i) x_s(j), all n^2 positions."""
+    X, pX = _f32(X)
+    N, n = X.shape
+    S = np.empty((n, n), dtype=np.float64)
+    lib().so_moment2_dense(pX, N, n, S.ctypes.data)
+    return S
+
+
+def moment4_dense(X):
+    """S(i,j,k,l) = sum_s x_s(i) x_s(j) x_s(k) x_s(l), all n^4 positions (small n only)."""
+    X, pX = _f32(X)
+    N, n = X.shape
+    S = np.empty((n, n, n, n), dtype=np.float64)
+    lib().so_moment4_dense(pX, N, n, S.ctypes.data)
+    return S
+
+
+def moment4_entries(X, ijkl):
+    X, pX = _f32(X)
+    N, n = X.shape
+    ijkl = np.ascontiguousarray(ijkl, dtype=np.int32).reshape(-1, 4)
+    assert ijkl.size == 0 or (ijkl.min() >= 0 and ijkl.max() < n)
+    out = np.empty(ijkl.shape[0], dtype=np.float64)
+    lib().so_moment4_entries(pX, N, n, ijkl.ctypes.data, ijkl.shape[0], out.ctypes.data)
+    return out
+
+
 def expand_sym(Sc, n, order):
     Sc, pS = _f32(Sc)
-    assert order in (2, 3)
-    assert Sc.size == (count_sym2(n) if order == 2 else count_sym3(n))
+    assert order in (2, 3, 4)
+    assert Sc.size == {2: count_sym2, 3: count_sym3, 4: count_sym4}[order](n)
     S = np.empty((n,) * order, dtype=np.float32)
     rc = lib().so_expand_sym(pS, n, order, S.ctypes.data)
     assert rc == 0

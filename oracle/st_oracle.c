@@ -134,6 +134,20 @@ SO_API int64_t so_list_sym3(int64_t n, int16_t *ijk)
     return c;
 }
 
+/* Order-4 unique set in packed order (M3 nest: for i; for j=i; for k=j; for l=k). */
+SO_API int64_t so_list_sym4(int64_t n, int16_t *ijkl)
+{
+    int64_t c = 0;
+    for (int64_t i = 0; i < n; ++i)
+        for (int64_t j = i; j < n; ++j)
+            for (int64_t k = j; k < n; ++k)
+                for (int64_t l = k; l < n; ++l) {
+                    ijkl[4 * c] = (int16_t)i; ijkl[4 * c + 1] = (int16_t)j;
+                    ijkl[4 * c + 2] = (int16_t)k; ijkl[4 * c + 3] = (int16_t)l; ++c;
+                }
+    return c;
+}
+
 SO_API int64_t so_list_band(int64_t n, int64_t w, int32_t *ij)
 {
     int64_t c = 0;
@@ -372,9 +386,90 @@ SO_API void so_moment3_entries(const float *X, int64_t N, int64_t n,
 }
 
 /* ------------------------------------------------------------------ */
+/* second and fourth moments: the other two terms of the degree-2       */
+/* polynomial-regression covariance, summed over the samples,           */
+/*   M1 = f (x) f              ->  S2(i,j)     = sum_s x_s(i) x_s(j)     */
+/*   M3 = vec(f(x)f) (x) vec(f(x)f) -> S4(i,j,k,l) = sum_s x_i x_j x_k x_l */
+/* Raw sums, all positions (dense) or a list of positions.              */
+/* ------------------------------------------------------------------ */
+SO_API void so_moment2_dense(const float *X, int64_t N, int64_t n, double *S)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i)
+        for (int64_t j = 0; j < n; ++j) {
+            double s = 0.0;
+            for (int64_t q = 0; q < N; ++q) {
+                const float *xs = X + q * n;
+                s += (double)xs[i] * (double)xs[j];
+            }
+            S[i * n + j] = s;
+        }
+}
+
+SO_API void so_moment4_dense(const float *X, int64_t N, int64_t n, double *S)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i)
+        for (int64_t j = 0; j < n; ++j)
+            for (int64_t k = 0; k < n; ++k)
+                for (int64_t l = 0; l < n; ++l) {
+                    double s = 0.0;
+                    for (int64_t q = 0; q < N; ++q) {
+                        const float *xs = X + q * n;
+                        s += (double)xs[i] * (double)xs[j] * (double)xs[k] * (double)xs[l];
+                    }
+                    S[((i * n + j) * n + k) * n + l] = s;
+                }
+}
+
+SO_API void so_moment4_entries(const float *X, int64_t N, int64_t n,
+                               const int32_t *ijkl, int64_t count, double *out)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t e = 0; e < count; ++e) {
+        int64_t i = ijkl[4 * e], j = ijkl[4 * e + 1], k = ijkl[4 * e + 2], l = ijkl[4 * e + 3];
+        double s = 0.0;
+        for (int64_t q = 0; q < N; ++q) {
+            const float *xs = X + q * n;
+            s += (double)xs[i] * (double)xs[j] * (double)xs[k] * (double)xs[l];
+        }
+        out[e] = s;
+    }
+}
+
+/* Start of each run (i,j,k,k..n-1) of the order-4 packed storage, found by running
+ * the M3 nest and noting the counter on entry to the l loop.  run[(i*n+j)*n+k] for
+ * i<=j<=k, -1 otherwise. */
+static int64_t *runs_sym4(int64_t n)
+{
+    int64_t *run = (int64_t *)malloc(sizeof(int64_t) * (size_t)(n * n * n));
+    for (int64_t q = 0; q < n * n * n; ++q) run[q] = -1;
+    int64_t c = 0;
+    for (int64_t i = 0; i < n; ++i)
+        for (int64_t j = i; j < n; ++j)
+            for (int64_t k = j; k < n; ++k) {
+                run[(i * n + j) * n + k] = c;
+                for (int64_t l = k; l < n; ++l) ++c;
+            }
+    return run;
+}
+
+static void sort4(int64_t *a, int64_t *b, int64_t *c, int64_t *d)
+{
+    int64_t v[4] = {*a, *b, *c, *d};
+    for (int x = 1; x < 4; ++x) {           /* insertion sort, ascending */
+        int64_t t = v[x];
+        int y = x - 1;
+        while (y >= 0 && v[y] > t) { v[y + 1] = v[y]; --y; }
+        v[y + 1] = t;
+    }
+    *a = v[0]; *b = v[1]; *c = v[2]; *d = v[3];
+}
+
+/* ------------------------------------------------------------------ */
 /* reconstruction  T(x) = T_C(x) + T_R(x,x') * T_C(x')   (Property 5)   */
 /* order 2: S(i,j) = Sc[pos(min,max)]  (class-S redundancy map)         */
-/* order 3: S(i,j,k) = Sc[pos(sorted triple)]                           */
+/* order 3: S(i,j,k) = Sc[pos(sorted triple)]; order 4 likewise          */
 /* fp32 in, fp32 out, a pure copy.                                      */
 /* ------------------------------------------------------------------ */
 SO_API int so_expand_sym(const float *Sc, int64_t n, int order, float *S)
@@ -399,6 +494,19 @@ SO_API int so_expand_sym(const float *Sc, int64_t n, int order, float *S)
                     sort3(&a, &b, &c);
                     S[(i * n + j) * n + k] = Sc[run[a * n + b] + (c - b)];
                 }
+        free(run);
+        return 0;
+    }
+    if (order == 4) {   /* S(i,j,k,l) = Sc[pos(sorted quadruple)] */
+        int64_t *run = runs_sym4(n);
+        for (int64_t i = 0; i < n; ++i)
+            for (int64_t j = 0; j < n; ++j)
+                for (int64_t k = 0; k < n; ++k)
+                    for (int64_t l = 0; l < n; ++l) {
+                        int64_t a = i, b = j, c = k, d = l;
+                        sort4(&a, &b, &c, &d);
+                        S[((i * n + j) * n + k) * n + l] = Sc[run[(a * n + b) * n + c] + (d - c)];
+                    }
         free(run);
         return 0;
     }

@@ -279,3 +279,83 @@ def test_expand(oracle, n):
     S2 = oracle.expand_sym(Sc2, n, 2)
     assert np.array_equal(S2, S2.T)                      # y[i][j] = y[j][i] for j < i
     assert np.array_equal(S2[np.triu_indices(n)], Sc2)   # unique half is the packed data
+
+
+# ------------------------------------------------- order-2 and order-4 moments (M1, M3)
+@pytest.mark.parametrize("n", [1, 2, 4, 7])
+def test_sym4_listing_is_lexicographic(oracle, n):
+    lst = oracle.list_sym4(n)
+    ref = np.array(list(itertools.combinations_with_replacement(range(n), 4)), dtype=np.int16).reshape(-1, 4)
+    assert np.array_equal(lst, ref)
+    assert lst.shape[0] == math.comb(n + 3, 4) == oracle.count_sym4(n)
+
+
+@pytest.mark.parametrize("N,n", [(1, 1), (1, 5), (9, 4), (60, 11)])
+def test_moment2_against_matmul(oracle, N, n):
+    X = W.normal(101, N * n).reshape(N, n)
+    X64 = X.astype(np.float64)
+    S = oracle.moment2_dense(X)
+    assert np.allclose(S, X64.T @ X64, rtol=1e-13, atol=1e-13)
+    assert np.allclose(S, S.T, rtol=1e-15, atol=1e-15)
+    if N == 1:   # the paper's M1 nest: M1[i][j] = f[i]*f[j]
+        assert np.allclose(S, np.outer(X64[0], X64[0]), rtol=1e-15)
+
+
+@pytest.mark.parametrize("N,n", [(1, 1), (1, 4), (6, 3), (25, 6)])
+def test_moment4_against_einsum(oracle, N, n):
+    X = W.normal(102, N * n).reshape(N, n)
+    X64 = X.astype(np.float64)
+    ref = np.einsum("si,sj,sk,sl->ijkl", X64, X64, X64, X64)
+    S = oracle.moment4_dense(X)
+    assert np.allclose(S, ref, rtol=1e-13, atol=1e-13)
+    for perm in [(1, 0, 2, 3), (0, 2, 1, 3), (0, 1, 3, 2), (3, 2, 1, 0)]:
+        assert np.allclose(S, np.transpose(S, perm), rtol=1e-14, atol=1e-14)
+    quad = np.array(list(itertools.product(range(n), repeat=4)), dtype=np.int32)
+    assert np.array_equal(oracle.moment4_entries(X, quad), S.reshape(-1))
+
+
+def test_moment4_special_cases(oracle):
+    n, N = 5, 13
+    X = np.zeros((N, n), dtype=np.float32)
+    X[:, 3] = 1.0
+    S = oracle.moment4_dense(X)
+    assert S[3, 3, 3, 3] == N and np.count_nonzero(S) == 1
+    # N = 1 is the paper's M3 nest: M3[i*n+j][k*n+l] = f_i f_j f_k f_l
+    f = W.normal(103, n)
+    f64 = f.astype(np.float64)
+    S = oracle.moment4_dense(f.reshape(1, n))
+    v = np.outer(f64, f64).reshape(-1)
+    assert np.allclose(S.reshape(n * n, n * n), np.outer(v, v), rtol=1e-15)
+    # sum_p mult(p) * S_C(p) = sum_s (1^T x_s)^4, mult = number of distinct permutations
+    X = W.normal(104, 30 * n).reshape(30, n)
+    lst = oracle.list_sym4(n)
+    Sc = oracle.moment4_entries(X, lst)
+    mult = np.array([len(set(itertools.permutations(tuple(t)))) for t in lst.tolist()])
+    assert set(mult.tolist()) <= {1, 4, 6, 12, 24} and mult.sum() == n ** 4
+    assert np.isclose((mult * Sc).sum(), (X.astype(np.float64).sum(axis=1) ** 4).sum(), rtol=1e-12)
+    # the order-4 moment restricted to k = l = a unit direction is the order-2 moment of x scaled by x_a
+    a = 2
+    Xa = (X.astype(np.float64) * X.astype(np.float64)[:, [a]])
+    S4 = oracle.moment4_dense(X)
+    assert np.allclose(S4[:, :, a, a], Xa.T @ Xa, rtol=1e-12, atol=1e-12)
+
+
+@pytest.mark.parametrize("n", [1, 2, 4, 7])
+def test_expand_order4(oracle, n):
+    Sc = W.uniform(105, math.comb(n + 3, 4))
+    S = oracle.expand_sym(Sc, n, 4)
+    assert S.dtype == np.float32 and S.shape == (n, n, n, n)
+    idx = np.sort(np.indices((n, n, n, n)).reshape(4, -1), axis=0)
+    pos = {t: p for p, t in enumerate(itertools.combinations_with_replacement(range(n), 4))}
+    ref = np.array([Sc[pos[tuple(int(v) for v in idx[:, q])]] for q in range(n ** 4)],
+                   dtype=np.float32).reshape(n, n, n, n)
+    assert np.array_equal(S.view(np.uint32), ref.view(np.uint32))
+    for perm in [(1, 0, 2, 3), (0, 2, 1, 3), (0, 1, 3, 2)]:
+        assert np.array_equal(S, np.transpose(S, perm))
+
+
+def test_pr2_covariance_distinct_elements(oracle):
+    # the three unique sets together are the distinct elements of the degree-2 polynomial-regression
+    # covariance: 65 for four features (golden file), counted here through the listings
+    n = 4
+    assert oracle.count_sym2(n) + oracle.count_sym3(n) + oracle.list_sym4(n).shape[0] == 65
