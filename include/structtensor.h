@@ -15,6 +15,8 @@
  *          n(n+1)/2 entries, row i holds columns i..n-1.
  *   sym3 : triples 0<=i<=j<=k<n   ("Tensor Structures": unique elements of a
  *          degree-3 interaction tensor), n(n+1)(n+2)/6 entries.
+ *   sym4 : quadruples 0<=i<=j<=k<=l<n (the M3 term of the same covariance),
+ *          n(n+1)(n+2)(n+3)/24 entries.
  *   band : pairs |i-j|<=w, 0<=i,j<n, row-major; a band 3-tensor stores one
  *          contiguous fibre of length nl per in-band pair.
  *
@@ -64,31 +66,36 @@ const char *st_status_string(st_status s);
  * clamped to n-1.  Return -1 for n < 0 or w < 0. */
 int64_t st_count_sym2(int64_t n);
 int64_t st_count_sym3(int64_t n);
+int64_t st_count_sym4(int64_t n);   /* i<=j<=k<=l quadruples (M3 nest), n(n+1)(n+2)(n+3)/24 */
 int64_t st_count_band(int64_t n, int64_t w);
 
 /* Position of an index tuple in packed storage (closed forms, no tables).
  * Return -1 if the tuple is outside the unique set. */
 int64_t st_rank_sym2(int64_t n, int64_t i, int64_t j);
 int64_t st_rank_sym3(int64_t n, int64_t i, int64_t j, int64_t k);
+int64_t st_rank_sym4(int64_t n, int64_t i, int64_t j, int64_t k, int64_t l);
 int64_t st_rank_band(int64_t n, int64_t w, int64_t i, int64_t j);
 
 /* Inverse maps.  ST_ERR_SHAPE if p is outside [0, count); ST_ERR_NULL for a
  * NULL result pointer. */
 st_status st_unrank_sym2(int64_t n, int64_t p, int64_t *i, int64_t *j);
 st_status st_unrank_sym3(int64_t n, int64_t p, int64_t *i, int64_t *j, int64_t *k);
+st_status st_unrank_sym4(int64_t n, int64_t p, int64_t *i, int64_t *j, int64_t *k, int64_t *l);
 st_status st_unrank_band(int64_t n, int64_t w, int64_t p, int64_t *i, int64_t *j);
 
 /* Batched inverse maps on the host: tuples of positions p0 .. p0+count-1
- * written to HOST memory `out` as int32, 2 (sym2, band) or 3 (sym3) per
- * position. */
+ * written to HOST memory `out` as int32, 2 (sym2, band), 3 (sym3) or 4 (sym4)
+ * per position. */
 st_status st_unrank_sym2_batch(int64_t n, int64_t p0, int64_t count, int32_t *out);
 st_status st_unrank_sym3_batch(int64_t n, int64_t p0, int64_t count, int32_t *out);
+st_status st_unrank_sym4_batch(int64_t n, int64_t p0, int64_t count, int32_t *out);
 st_status st_unrank_band_batch(int64_t n, int64_t w, int64_t p0, int64_t count, int32_t *out);
 
 /* The same inverse maps evaluated by the DEVICE code the kernels use (the
  * kernels turn a flat position into indices with these, instead of masks).
  * `out` is a DEVICE pointer to 2*count (kind 2: sym2, kind 4: band, with
- * w) or 3*count (kind 3: sym3) int32.  For checking the device index maps. */
+ * w), 3*count (kind 3: sym3) or 4*count (kind 5: sym4) int32.  For checking the
+ * device index maps. */
 st_status st_unrank_device(int kind, int64_t n, int64_t w, int64_t p0, int64_t count,
                            int32_t *out, void *stream);
 
@@ -143,7 +150,8 @@ st_status st_moment3_sym(const float *X, int64_t N, int n, float *Sc, int accumu
 /* Reconstruction through the redundancy map (Property 5:
  * T(x) = T_C(x) + T_R(x,x') * T_C(x')).  order 2: S(i,j) = Sc[rank2(min,max)]
  * (class S: i' = j, j' = i for j < i); order 3: S(i,j,k) = Sc[rank3(sorted
- * triple)].  S is the dense n^order array, overwritten.  A bit-exact copy. */
+ * triple)]; order 4: S(i,j,k,l) = Sc[rank4(sorted quadruple)] (n <= 256).  S is
+ * the dense n^order array, overwritten.  A bit-exact copy. */
 st_status st_expand_sym(const float *Sc, float *S, int n, int order, void *stream);
 
 #ifdef __cplusplus

@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     count_band,
     count_sym2,
     count_sym3,
+    count_sym4,
     expand_sym,
     batax_utri,
     lib,
@@ -19,6 +20,7 @@ from .binding import (  # noqa: F401
     rank_band,
     rank_sym2,
     rank_sym3,
+    rank_sym4,
     ttm_band,
     unrank_band,
     unrank_band_batch,
@@ -27,5 +29,7 @@ from .binding import (  # noqa: F401
     unrank_sym2_batch,
     unrank_sym3,
     unrank_sym3_batch,
+    unrank_sym4,
+    unrank_sym4_batch,
     workspace_bytes,
 )

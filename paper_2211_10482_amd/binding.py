@@ -26,15 +26,19 @@ SIGNATURES = {
     "st_status_string": (C.c_char_p, [_I32]),
     "st_count_sym2": (_I64, [_I64]),
     "st_count_sym3": (_I64, [_I64]),
+    "st_count_sym4": (_I64, [_I64]),
     "st_count_band": (_I64, [_I64, _I64]),
     "st_rank_sym2": (_I64, [_I64, _I64, _I64]),
     "st_rank_sym3": (_I64, [_I64, _I64, _I64, _I64]),
+    "st_rank_sym4": (_I64, [_I64, _I64, _I64, _I64, _I64]),
     "st_rank_band": (_I64, [_I64, _I64, _I64, _I64]),
     "st_unrank_sym2": (_I32, [_I64, _I64, _P, _P]),
     "st_unrank_sym3": (_I32, [_I64, _I64, _P, _P, _P]),
+    "st_unrank_sym4": (_I32, [_I64, _I64, _P, _P, _P, _P]),
     "st_unrank_band": (_I32, [_I64, _I64, _I64, _P, _P]),
     "st_unrank_sym2_batch": (_I32, [_I64, _I64, _I64, _P]),
     "st_unrank_sym3_batch": (_I32, [_I64, _I64, _I64, _P]),
+    "st_unrank_sym4_batch": (_I32, [_I64, _I64, _I64, _P]),
     "st_unrank_band_batch": (_I32, [_I64, _I64, _I64, _I64, _P]),
     "st_unrank_device": (_I32, [_I32, _I64, _I64, _I64, _I64, _P, _P]),
     "st_mttkrp_sym3_workspace": (_SZ, [_I32, _I32]),
@@ -76,9 +80,11 @@ def _check(status: int, what: str):
 # ---- host index utilities --------------------------------------------------------
 def count_sym2(n): return int(lib().st_count_sym2(n))
 def count_sym3(n): return int(lib().st_count_sym3(n))
+def count_sym4(n): return int(lib().st_count_sym4(n))
 def count_band(n, w): return int(lib().st_count_band(n, w))
 def rank_sym2(n, i, j): return int(lib().st_rank_sym2(n, i, j))
 def rank_sym3(n, i, j, k): return int(lib().st_rank_sym3(n, i, j, k))
+def rank_sym4(n, i, j, k, l): return int(lib().st_rank_sym4(n, i, j, k, l))
 def rank_band(n, w, i, j): return int(lib().st_rank_band(n, w, i, j))
 
 
@@ -92,6 +98,12 @@ def unrank_sym3(n, p):
     i, j, k = _I64(), _I64(), _I64()
     _check(lib().st_unrank_sym3(n, p, C.byref(i), C.byref(j), C.byref(k)), "st_unrank_sym3")
     return i.value, j.value, k.value
+
+
+def unrank_sym4(n, p):
+    i, j, k, l = _I64(), _I64(), _I64(), _I64()
+    _check(lib().st_unrank_sym4(n, p, C.byref(i), C.byref(j), C.byref(k), C.byref(l)), "st_unrank_sym4")
+    return i.value, j.value, k.value, l.value
 
 
 def unrank_band(n, w, p):
@@ -109,6 +121,12 @@ def unrank_sym2_batch(n, p0, count):
 def unrank_sym3_batch(n, p0, count):
     out = np.empty((count, 3), dtype=np.int32)
     _check(lib().st_unrank_sym3_batch(n, p0, count, out.ctypes.data), "st_unrank_sym3_batch")
+    return out
+
+
+def unrank_sym4_batch(n, p0, count):
+    out = np.empty((count, 4), dtype=np.int32)
+    _check(lib().st_unrank_sym4_batch(n, p0, count, out.ctypes.data), "st_unrank_sym4_batch")
     return out
 
 
@@ -159,7 +177,7 @@ def workspace_bytes(kernel: str, **kw) -> int:
 
 def unrank_device(kind, n, w, p0, count):
     torch = _torch()
-    width = 3 if kind == 3 else 2
+    width = {3: 3, 5: 4}.get(kind, 2)
     out = torch.empty((max(count, 1), width), dtype=torch.int32, device="cuda")
     _check(lib().st_unrank_device(kind, n, w, p0, count, C.c_void_p(out.data_ptr()), _stream()),
            "st_unrank_device")

@@ -48,6 +48,7 @@ const char *st_status_string(st_status s)
 /* ---- counts / rank / unrank on the host -------------------------------- */
 int64_t st_count_sym2(int64_t n) { return n < 0 ? -1 : count_sym2<i64>(n); }
 int64_t st_count_sym3(int64_t n) { return n < 0 ? -1 : count_sym3<i64>(n); }
+int64_t st_count_sym4(int64_t n) { return n < 0 ? -1 : count_sym4<i64>(n); }
 int64_t st_count_band(int64_t n, int64_t w)
 {
     if (n < 0 || w < 0) return -1;
@@ -64,6 +65,11 @@ int64_t st_rank_sym3(int64_t n, int64_t i, int64_t j, int64_t k)
 {
     if (n < 1 || i < 0 || i > j || j > k || k >= n) return -1;
     return rank_sym3<i64>(n, i, j, k);
+}
+int64_t st_rank_sym4(int64_t n, int64_t i, int64_t j, int64_t k, int64_t l)
+{
+    if (n < 1 || i < 0 || i > j || j > k || k > l || l >= n) return -1;
+    return rank_sym4<i64>(n, i, j, k, l);
 }
 int64_t st_rank_band(int64_t n, int64_t w, int64_t i, int64_t j)
 {
@@ -85,6 +91,13 @@ st_status st_unrank_sym3(int64_t n, int64_t p, int64_t *i, int64_t *j, int64_t *
     if (!i || !j || !k) return ST_ERR_NULL;
     if (n < 1 || p < 0 || p >= count_sym3<i64>(n)) return ST_ERR_SHAPE;
     unrank_sym3<i64>(n, p, *i, *j, *k);
+    return ST_OK;
+}
+st_status st_unrank_sym4(int64_t n, int64_t p, int64_t *i, int64_t *j, int64_t *k, int64_t *l)
+{
+    if (!i || !j || !k || !l) return ST_ERR_NULL;
+    if (n < 1 || n > 50000 || p < 0 || p >= count_sym4<i64>(n)) return ST_ERR_SHAPE;   /* counts fit 64 bits */
+    unrank_sym4<i64>(n, p, *i, *j, *k, *l);
     return ST_OK;
 }
 st_status st_unrank_band(int64_t n, int64_t w, int64_t p, int64_t *i, int64_t *j)
@@ -121,6 +134,19 @@ st_status st_unrank_sym3_batch(int64_t n, int64_t p0, int64_t count, int32_t *ou
     }
     return ST_OK;
 }
+st_status st_unrank_sym4_batch(int64_t n, int64_t p0, int64_t count, int32_t *out)
+{
+    if (count < 0) return ST_ERR_SHAPE;
+    if (count == 0) return ST_OK;
+    if (!out) return ST_ERR_NULL;
+    if (n < 1 || n > 50000 || p0 < 0 || p0 + count > count_sym4<i64>(n)) return ST_ERR_SHAPE;
+    for (i64 q = 0; q < count; ++q) {
+        i64 i, j, k, l;
+        unrank_sym4<i64>(n, p0 + q, i, j, k, l);
+        out[4 * q] = (int32_t)i; out[4 * q + 1] = (int32_t)j; out[4 * q + 2] = (int32_t)k; out[4 * q + 3] = (int32_t)l;
+    }
+    return ST_OK;
+}
 st_status st_unrank_band_batch(int64_t n, int64_t w, int64_t p0, int64_t count, int32_t *out)
 {
     if (count < 0) return ST_ERR_SHAPE;
@@ -140,10 +166,11 @@ st_status st_unrank_device(int kind, int64_t n, int64_t w, int64_t p0, int64_t c
                            int32_t *out, void *stream)
 {
     if (count < 0) return ST_ERR_SHAPE;
-    if (kind != 2 && kind != 3 && kind != 4) return ST_ERR_SHAPE;
+    if (kind != 2 && kind != 3 && kind != 4 && kind != 5) return ST_ERR_SHAPE;
     if (n < 1 || p0 < 0 || (kind == 4 && w < 0)) return ST_ERR_SHAPE;
-    if (n > 2000000) return ST_ERR_UNSUPPORTED;
-    i64 total = kind == 2 ? count_sym2<i64>(n) : kind == 3 ? count_sym3<i64>(n) : count_band<i64>(n, w);
+    if (n > (kind == 5 ? 50000 : 2000000)) return ST_ERR_UNSUPPORTED;
+    i64 total = kind == 2 ? count_sym2<i64>(n) : kind == 3 ? count_sym3<i64>(n) : kind == 5 ? count_sym4<i64>(n)
+                                                                                           : count_band<i64>(n, w);
     if (p0 + count > total) return ST_ERR_SHAPE;
     if (count == 0) return ST_OK;
     if (!out) return ST_ERR_NULL;
@@ -231,11 +258,11 @@ st_status st_moment3_sym(const float *X, int64_t N, int n, float *Sc, int accumu
 st_status st_expand_sym(const float *Sc, float *S, int n, int order, void *stream)
 {
     if (!Sc || !S) return ST_ERR_NULL;
-    if (n < 1 || (order != 2 && order != 3)) return ST_ERR_SHAPE;
-    if (n > (order == 2 ? 65000 : 2000)) return ST_ERR_UNSUPPORTED;
+    if (n < 1 || (order != 2 && order != 3 && order != 4)) return ST_ERR_SHAPE;
+    if (n > (order == 2 ? 65000 : order == 3 ? 2000 : 256)) return ST_ERR_UNSUPPORTED;
     if (!aligned16(Sc) || !aligned16(S)) return ST_ERR_ALIGN;
-    size_t cb = (size_t)(order == 2 ? count_sym2<i64>(n) : count_sym3<i64>(n)) * 4;
-    size_t db = (size_t)n * n * (order == 3 ? n : 1) * 4;
+    size_t cb = (size_t)(order == 2 ? count_sym2<i64>(n) : order == 3 ? count_sym3<i64>(n) : count_sym4<i64>(n)) * 4;
+    size_t db = (size_t)n * n * (order >= 3 ? n : 1) * (order == 4 ? n : 1) * 4;
     if (overlap(S, db, Sc, cb)) return ST_ERR_SHAPE;
     return launch_expand(Sc, S, n, order, (hipStream_t)stream);
 }

@@ -48,6 +48,38 @@ __global__ __launch_bounds__(256) void expand3_kernel(const float *__restrict__ 
     }
 }
 
+// order 4: one thread per l-quad of an (i,j,k) fibre; the three leading indices are sorted
+// once, the fourth is inserted per output
+__global__ __launch_bounds__(256) void expand4_kernel(const float *__restrict__ Sc,
+                                                      float *__restrict__ S, u32 n, u32 lq)
+{
+    const uint64_t t = (uint64_t)blockIdx.x * 256u + threadIdx.x;
+    const uint64_t nnn = (uint64_t)n * n * n;
+    if (t >= nnn * lq) return;
+    const u32 ijk = (u32)(t / lq), l0 = (u32)(t - (uint64_t)ijk * lq) * 4u;
+    const u32 i = ijk / (n * n), jk = ijk - i * n * n, j = jk / n, k = jk - j * n;
+    u32 a = i, b = j, c = k;
+    sort3(a, b, c);
+    float v[4];
+#pragma unroll
+    for (u32 e = 0; e < 4; ++e) {
+        const u32 l = l0 + e < n ? l0 + e : n - 1;
+        // insert l into a <= b <= c
+        const u32 q0 = min(a, l), r0 = max(a, l);
+        const u32 q1 = min(b, r0), r1 = max(b, r0);
+        const u32 q2 = min(c, r1), q3 = max(c, r1);
+        v[e] = Sc[rank_sym4<u32>(n, q0, q1, q2, q3)];
+    }
+    const size_t o = (size_t)ijk * n + l0;
+    if ((n & 3u) == 0) {
+        *reinterpret_cast<float4 *>(S + o) = make_float4(v[0], v[1], v[2], v[3]);
+    } else {
+#pragma unroll
+        for (u32 e = 0; e < 4; ++e)
+            if (l0 + e < n) S[o + e] = v[e];
+    }
+}
+
 // order 2: one thread per j-quad of a row
 __global__ __launch_bounds__(256) void expand2_kernel(const float *__restrict__ Sc,
                                                       float *__restrict__ S, u32 n, u32 jq)
@@ -75,7 +107,13 @@ __global__ __launch_bounds__(256) void expand2_kernel(const float *__restrict__ 
 st_status launch_expand(const float *Sc, float *S, int n, int order, hipStream_t s)
 {
     u32 un = (u32)n, q = (un + 3u) / 4u;
-    if (order == 3) {
+    if (order == 4) {
+        // n <= 256: every packed position (< 2^28) and 4*pent fit 32 bits
+        uint64_t threads = (uint64_t)un * un * un * q;
+        uint64_t blocks = (threads + 255) / 256;
+        if (blocks > 0x7fffffffull) return ST_ERR_UNSUPPORTED;
+        hipLaunchKernelGGL(expand4_kernel, dim3((u32)blocks), dim3(256), 0, s, Sc, S, un, q);
+    } else if (order == 3) {
         // n <= 2000: n*n*q < 2^32 and every packed position fits 32 bits
         uint64_t threads = (uint64_t)un * un * q;
         u32 blocks = (u32)((threads + 255) / 256);
@@ -100,6 +138,10 @@ __global__ __launch_bounds__(256) void unrank_kernel(int kind, I n, I w, I p0, i
         I i, j, k;
         unrank_sym3<I>(n, p, i, j, k);
         out[3 * t] = (int32_t)i; out[3 * t + 1] = (int32_t)j; out[3 * t + 2] = (int32_t)k;
+    } else if (kind == 5) {
+        I i, j, k, l;
+        unrank_sym4<I>(n, p, i, j, k, l);
+        out[4 * t] = (int32_t)i; out[4 * t + 1] = (int32_t)j; out[4 * t + 2] = (int32_t)k; out[4 * t + 3] = (int32_t)l;
     } else {
         I i, j;
         if (kind == 2) unrank_sym2<I>(n, p, i, j); else unrank_band<I>(n, w, p, i, j);
@@ -113,8 +155,10 @@ st_status launch_unrank(int kind, int64_t n, int64_t w, int64_t p0, int64_t coun
     if (count > ((int64_t)1 << 31) * 200) return ST_ERR_UNSUPPORTED;
     u32 blocks = (u32)((count + 255) / 256);
     // 32-bit index arithmetic is what the kernels use; it is valid while every
-    // intermediate (8*count+1 for sym2, 6*count for sym3) stays below 2^32.
-    bool small = (kind == 2 && n <= 20000) || (kind == 3 && n <= 1000) || (kind == 4 && n <= 20000 && w <= 20000);
+    // intermediate (8*count+1 for sym2, 6*count for sym3, 24*count in fp64 and 4*count
+    // in integers for sym4) stays below 2^32.
+    bool small = (kind == 2 && n <= 20000) || (kind == 3 && n <= 1000) || (kind == 4 && n <= 20000 && w <= 20000) ||
+                 (kind == 5 && n <= 256);
     if (small)
         hipLaunchKernelGGL(unrank_kernel<u32>, dim3(blocks), dim3(256), 0, s, kind, (u32)n,
                            (u32)(w > n ? n : w), (u32)p0, count, out);

@@ -2,6 +2,7 @@
 //
 //   sym2 : 0<=i<=j<n        (upper-triangular / symmetric unique set)
 //   sym3 : 0<=i<=j<=k<n     (generalised symmetric order-3 unique set)
+//   sym4 : 0<=i<=j<=k<=l<n  (order-4 analogue)
 //   band : |i-j|<=w         (square pair, row-major)
 //
 // Packed order is lexicographic with the last index fastest, i.e. the order in
@@ -25,8 +26,15 @@ template <typename I> ST_HD I tet(I m)                                       // 
     return tri<I>(m) * (m + 2) / 3;
 }
 
+template <typename I> ST_HD I pent(I m)                                      // tet(1)+..+tet(m)
+{
+    // tet(m)*(m+3) = 4*pent(m), exact; 32-bit use is valid to m = 320
+    return tet<I>(m) * (m + 3) / 4;
+}
+
 template <typename I> ST_HD I count_sym2(I n) { return tri<I>(n); }
 template <typename I> ST_HD I count_sym3(I n) { return tet<I>(n); }
+template <typename I> ST_HD I count_sym4(I n) { return pent<I>(n); }
 template <typename I> ST_HD I clamp_w(I n, I w) { return w > n - 1 ? n - 1 : w; }
 template <typename I> ST_HD I count_band(I n, I w)
 {
@@ -46,6 +54,14 @@ template <typename I> ST_HD I run_sym3(I n, I i, I j)
     return slab_sym3<I>(n, i) + tri<I>(n - i) - tri<I>(n - j);
 }
 template <typename I> ST_HD I rank_sym3(I n, I i, I j, I k) { return run_sym3<I>(n, i, j) + (k - j); }
+
+// position of (i,i,i,i) : the quadruples with first index i' < i are sym3 sets of sizes n, n-1, ..
+template <typename I> ST_HD I hslab_sym4(I n, I i) { return pent<I>(n) - pent<I>(n - i); }
+// the quadruples with first index i are the sym3 set of (j-i, k-i, l-i) over n-i values
+template <typename I> ST_HD I rank_sym4(I n, I i, I j, I k, I l)
+{
+    return hslab_sym4<I>(n, i) + rank_sym3<I>(n - i, j - i, k - i, l - i);
+}
 
 // first packed position of band row i
 template <typename I> ST_HD I row_band(I n, I w, I i)
@@ -80,6 +96,16 @@ template <typename I> ST_HD I tet_root(I q)
     return m;
 }
 
+// largest m with pent(m) <= q
+template <typename I> ST_HD I pent_root(I q)
+{
+    I m = (I)sqrt(sqrt(24.0 * (double)q));
+    m = m > 2 ? m - 2 : 0;
+    while (pent<I>(m + 1) <= q) ++m;
+    while (m > 0 && pent<I>(m) > q) --m;
+    return m;
+}
+
 template <typename I> ST_HD void unrank_sym2(I n, I p, I &i, I &j)
 {
     I q = tri<I>(n) - 1 - p;          // position counted from the end
@@ -97,6 +123,18 @@ template <typename I> ST_HD void unrank_sym3(I n, I p, I &i, I &j, I &k)
     unrank_sym2<I>(n - i, p - slab_sym3<I>(n, i), jj, kk);
     j = i + jj;
     k = i + kk;
+}
+
+template <typename I> ST_HD void unrank_sym4(I n, I p, I &i, I &j, I &k, I &l)
+{
+    I q = pent<I>(n) - 1 - p;
+    I m = pent_root<I>(q);            // first indices n-m .. n-1 hold pent(m) <= q entries
+    i = n - 1 - m;
+    I jj, kk, ll;
+    unrank_sym3<I>(n - i, p - hslab_sym4<I>(n, i), jj, kk, ll);
+    j = i + jj;
+    k = i + kk;
+    l = i + ll;
 }
 
 template <typename I> ST_HD void unrank_band(I n, I w, I p, I &i, I &j)

@@ -64,8 +64,10 @@ int main(int argc, char **argv)
     free(X); free(Sc); free(ws);
 #elif defined(CHECK_EXPAND)
     const int n = (int)a[0], order = (int)a[1];
-    if (order == 2 || order == 3) {
-        const size_t cnt = (size_t)(order == 2 ? st::count_sym2<int64_t>(n) : st::count_sym3<int64_t>(n));
+    if (order == 2 || order == 3 || order == 4) {
+        const size_t cnt = (size_t)(order == 2   ? st::count_sym2<int64_t>(n)
+                                    : order == 3 ? st::count_sym3<int64_t>(n)
+                                                 : st::count_sym4<int64_t>(n));
         size_t full = 1;
         for (int i = 0; i < order; ++i) full *= (size_t)n;
         float *Sc = fbuf(cnt), *S = fbuf(full);
@@ -74,7 +76,7 @@ int main(int argc, char **argv)
     } else {   // order = 10 + kind: device unrank of `count` positions from p0
         const int kind = order - 10;
         const long w = a[2], p0 = a[3], count = a[4];
-        int32_t *out = static_cast<int32_t *>(malloc((size_t)count * (kind == 3 ? 3 : 2) * sizeof(int32_t) + 1));
+        int32_t *out = static_cast<int32_t *>(malloc((size_t)count * (kind == 3 ? 3 : kind == 5 ? 4 : 2) * sizeof(int32_t) + 1));
         rc = st::launch_unrank(kind, n, w, p0, count, out, nullptr);
         free(out);
     }

@@ -53,9 +53,11 @@ def test_null_and_shape_errors():
     assert L.st_moment3_sym(P, -1, 4, P + 0x100000, 0, None, 0, None) == SHAPE
     assert L.st_moment3_sym(P, 10, 4, P + 0x100000, 2, None, 0, None) == SHAPE
     assert L.st_expand_sym(None, P, 4, 3, None) == NULL
-    assert L.st_expand_sym(P, P + 0x100000, 4, 4, None) == SHAPE
+    assert L.st_expand_sym(P, P + 0x100000, 4, 5, None) == SHAPE
+    assert L.st_expand_sym(P, P + 0x40000000, 300, 4, None) == UNSUPPORTED
     assert L.st_expand_sym(P, P + 0x100000, 0, 3, None) == SHAPE
-    assert L.st_unrank_device(5, 4, 0, 0, 1, P, None) == SHAPE
+    assert L.st_unrank_device(6, 4, 0, 0, 1, P, None) == SHAPE
+    assert L.st_unrank_device(5, 4, 0, 34, 2, P, None) == SHAPE
     assert L.st_unrank_device(3, 4, 0, 19, 2, P, None) == SHAPE
 
 

@@ -59,6 +59,19 @@ def test_device_unrank_small(st, oracle, n):
         assert np.array_equal(gotb, oracle.list_band(n, w))
 
 
+@pytest.mark.parametrize("n", [1, 3, 17, 64])
+def test_device_unrank_sym4(st, oracle, n):
+    say("device unrank sym4 n=%d" % n)
+    lst = oracle.list_sym4(n)
+    got = st.unrank_device(5, n, 0, 0, lst.shape[0]).cpu().numpy()
+    assert np.array_equal(got, lst)
+    if n == 64:   # the 64-bit device path on a window of a larger set
+        n2 = 300
+        ref = st.unrank_sym4_batch(n2, 200_000_000, 50_000)
+        got = st.unrank_device(5, n2, 0, 200_000_000, 50_000).cpu().numpy()
+        assert np.array_equal(got, ref)
+
+
 def test_device_unrank_full_sizes(st, oracle):
     say("device unrank sym3 n=512 (22.5M), sym2 n=8192 (33.6M), band (512,8)")
     lst = oracle.list_sym3(512)
@@ -91,6 +104,17 @@ def test_expand_order3(st, oracle, n):
         assert np.array_equal(got, np.transpose(got, perm))
     idx = oracle.list_sym3(n).astype(np.int64)
     assert np.array_equal(got[idx[:, 0], idx[:, 1], idx[:, 2]], Sc)
+
+
+@pytest.mark.parametrize("n", [1, 2, 5, 12, 17, 64])
+def test_expand_order4(st, oracle, n):
+    say("expand order 4 n=%d" % n)
+    Sc = W.uniform(103, oracle.count_sym4(n))
+    ref = oracle.expand_sym(Sc, n, 4)
+    got = st.expand_sym(dev(Sc), n, 4).cpu().numpy()
+    assert np.array_equal(got.view(np.uint32), ref.view(np.uint32))
+    idx = oracle.list_sym4(n).astype(np.int64)
+    assert np.array_equal(got[idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3]], Sc)
 
 
 @pytest.mark.parametrize("n", [1, 7, 64, 100, 1001])

@@ -37,6 +37,37 @@ def test_sym_rank_unrank_exhaustive(oracle, n):
     assert st.rank_sym3(n, *st.unrank_sym3(n, p)) == p
 
 
+@pytest.mark.parametrize("n", [1, 2, 3, 7, 16, 33, 64])
+def test_sym4_rank_unrank(oracle, n):
+    lst = oracle.list_sym4(n)
+    cnt = lst.shape[0]
+    assert st.count_sym4(n) == cnt == oracle.count_sym4(n)
+    assert np.array_equal(st.unrank_sym4_batch(n, 0, cnt), lst)
+    step = max(1, cnt // 3000)
+    for p in list(range(0, cnt, step)) + [cnt - 1]:
+        i, j, k, l = (int(v) for v in lst[p])
+        assert st.rank_sym4(n, i, j, k, l) == p
+        assert st.unrank_sym4(n, p) == (i, j, k, l)
+    assert st.rank_sym4(n, 0, 0, 0, 0) == 0 and st.rank_sym4(n, n - 1, n - 1, n - 1, n - 1) == cnt - 1
+    assert st.rank_sym4(n, 1, 0, 0, 0) == -1 and st.rank_sym4(n, 0, 0, 0, n) == -1
+    assert st.count_sym4(-2) == -1
+
+
+def test_sym4_large_n():
+    # 64-bit arithmetic far above the kernels' range: the ends and a few interior points
+    import math
+    for n in (300, 2000, 50000):
+        cnt = st.count_sym4(n)
+        assert cnt == math.comb(n + 3, 4)
+        assert st.unrank_sym4(n, 0) == (0, 0, 0, 0) and st.unrank_sym4(n, cnt - 1) == (n - 1,) * 4
+        for p in (1, n, cnt // 3, cnt // 2 + 12345, cnt - 2):
+            t = st.unrank_sym4(n, p)
+            assert t[0] <= t[1] <= t[2] <= t[3] < n and st.rank_sym4(n, *t) == p
+        # first entry with first index i sits right after all entries with smaller first index
+        i = n // 2
+        assert st.rank_sym4(n, i, i, i, i) == cnt - math.comb(n - i + 3, 4)
+
+
 def test_sym3_rank_all_small(oracle):
     for n in (1, 2, 3, 5, 9):
         tab3 = oracle.table_sym3(n)
