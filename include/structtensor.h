@@ -104,6 +104,7 @@ size_t st_mttkrp_sym3_workspace(int n, int R);
 size_t st_batax_utri_workspace(int n);
 size_t st_ttm_band_workspace(int n, int w, int nl, int R);
 size_t st_moment3_sym_workspace(int64_t N, int n);
+size_t st_moment2_sym_workspace(int64_t N, int n);
 
 /* ---- kernels -------------------------------------------------------------- */
 
@@ -145,6 +146,13 @@ st_status st_ttm_band(const float *Tc, const float *U, float *Yc, int n, int w, 
  * it.  Raw sums: no 1/N, no centring.  N >= 0 (N = 0 zero-fills when
  * accumulate = 0), n >= 1. */
 st_status st_moment3_sym(const float *X, int64_t N, int n, float *Sc, int accumulate,
+                         void *ws, size_t ws_bytes, void *stream);
+
+/* Second-moment accumulation over N samples, upper half only:
+ *     Sc(rank2(i,j)) (+)= sum_s X(s,i) * X(s,j)    for i<=j
+ * (the M1 = f (x) f term of the same covariance; its structure is plain
+ * symmetry).  Arguments as for st_moment3_sym; Sc has n(n+1)/2 entries. */
+st_status st_moment2_sym(const float *X, int64_t N, int n, float *Sc, int accumulate,
                          void *ws, size_t ws_bytes, void *stream);
 
 /* Reconstruction through the redundancy map (Property 5:

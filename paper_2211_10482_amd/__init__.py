@@ -15,6 +15,7 @@ from .binding import (  # noqa: F401
     expand_sym,
     batax_utri,
     lib,
+    moment2_sym,
     moment3_sym,
     mttkrp_sym3,
     rank_band,

@@ -45,10 +45,12 @@ SIGNATURES = {
     "st_batax_utri_workspace": (_SZ, [_I32]),
     "st_ttm_band_workspace": (_SZ, [_I32, _I32, _I32, _I32]),
     "st_moment3_sym_workspace": (_SZ, [_I64, _I32]),
+    "st_moment2_sym_workspace": (_SZ, [_I64, _I32]),
     "st_mttkrp_sym3": (_I32, [_P, _P, _P, _I32, _I32, _P, _SZ, _P]),
     "st_batax_utri": (_I32, [_P, _P, _P, _I32, _F, _P, _SZ, _P]),
     "st_ttm_band": (_I32, [_P, _P, _P, _I32, _I32, _I32, _I32, _P, _SZ, _P]),
     "st_moment3_sym": (_I32, [_P, _I64, _I32, _P, _I32, _P, _SZ, _P]),
+    "st_moment2_sym": (_I32, [_P, _I64, _I32, _P, _I32, _P, _SZ, _P]),
     "st_expand_sym": (_I32, [_P, _P, _I32, _I32, _P]),
 }
 
@@ -172,6 +174,8 @@ def workspace_bytes(kernel: str, **kw) -> int:
         return int(L.st_ttm_band_workspace(kw["n"], kw["w"], kw["nl"], kw["R"]))
     if kernel == "moment3_sym":
         return int(L.st_moment3_sym_workspace(kw["N"], kw["n"]))
+    if kernel == "moment2_sym":
+        return int(L.st_moment2_sym_workspace(kw["N"], kw["n"]))
     raise KeyError(kernel)
 
 
@@ -230,6 +234,26 @@ def moment3_sym(X, Sc=None, accumulate=False, ws=None):
     _check(lib().st_moment3_sym(px, N, n, _dev_f32(Sc, "Sc"), 1 if accumulate else 0, pws, wsb, _stream()),
            "st_moment3_sym")
     return Sc
+
+
+def _moment(order, X, Sc, accumulate, ws):
+    torch = _torch()
+    N, n = X.shape
+    name = "moment%d_sym" % order
+    count = {2: count_sym2, 3: count_sym3, 4: count_sym4}[order](n)
+    if Sc is None:
+        if accumulate:
+            raise ValueError("accumulate needs an existing Sc")
+        Sc = torch.empty(count, dtype=torch.float32, device=X.device)
+    ws, pws, wsb = _workspace(workspace_bytes(name, N=N, n=n), X, ws)
+    px = _dev_f32(X, "X") if N > 0 else C.c_void_p(X.data_ptr() if X.numel() else 0)
+    _check(getattr(lib(), "st_" + name)(px, N, n, _dev_f32(Sc, "Sc"), 1 if accumulate else 0, pws, wsb, _stream()),
+           "st_" + name)
+    return Sc
+
+
+def moment2_sym(X, Sc=None, accumulate=False, ws=None):
+    return _moment(2, X, Sc, accumulate, ws)
 
 
 def expand_sym(Sc, n, order, S=None):

@@ -9,6 +9,10 @@
 #include "../../paper_2211_10482_amd/csrc/st_ttm.hip"
 #elif defined(CHECK_MOMENT3)
 #include "../../paper_2211_10482_amd/csrc/st_moment3.hip"
+#elif defined(CHECK_MOMENT2)
+#include "../../paper_2211_10482_amd/csrc/st_moment2.hip"
+#elif defined(CHECK_MOMENT4)
+#include "../../paper_2211_10482_amd/csrc/st_moment4.hip"
 #elif defined(CHECK_EXPAND)
 #include "../../paper_2211_10482_amd/csrc/st_expand.hip"
 #else
@@ -61,6 +65,22 @@ int main(int argc, char **argv)
     float *X = fbuf((size_t)N * n), *Sc = fbuf(cnt);
     void *ws = malloc(wsb ? wsb : 1);
     rc = st::launch_moment3(X, N, n, Sc, accumulate, ws, nullptr);
+    free(X); free(Sc); free(ws);
+#elif defined(CHECK_MOMENT2) || defined(CHECK_MOMENT4)
+    const long N = a[0];
+    const int n = (int)a[1], accumulate = (int)a[2];
+#if defined(CHECK_MOMENT2)
+    const size_t cnt = (size_t)st::count_sym2<int64_t>(n), wsb = st::moment2_workspace(N, n);
+#else
+    const size_t cnt = (size_t)st::count_sym4<int64_t>(n), wsb = st::moment4_workspace(N, n);
+#endif
+    float *X = fbuf((size_t)N * n), *Sc = fbuf(cnt);
+    void *ws = malloc(wsb ? wsb : 1);
+#if defined(CHECK_MOMENT2)
+    rc = st::launch_moment2(X, N, n, Sc, accumulate, ws, nullptr);
+#else
+    rc = st::launch_moment4(X, N, n, Sc, accumulate, ws, nullptr);
+#endif
     free(X); free(Sc); free(ws);
 #elif defined(CHECK_EXPAND)
     const int n = (int)a[0], order = (int)a[1];

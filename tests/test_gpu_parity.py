@@ -266,6 +266,52 @@ def test_moment3_full(st, oracle):
     assert np.array_equal(S.view(np.uint32), ref_S.view(np.uint32))
 
 
+# ---------------------------------------------------------------------- moment2 (M1)
+@pytest.mark.parametrize("N,n", [(1, 1), (7, 5), (100, 64), (4097, 64), (33, 64), (1000, 20), (5000, 63), (300, 70),
+                                 (64, 200)])
+def test_moment2_small(st, oracle, N, n):
+    say("moment2 N=%d n=%d" % (N, n))
+    X = W.normal(301, N * n).reshape(N, n)
+    iu = np.triu_indices(n)
+    ref = oracle.moment2_dense(X)[iu]
+    got = st.moment2_sym(dev(X)).cpu().numpy()
+    assert rel_err(got, ref) <= TOL
+    got2 = st.moment2_sym(dev(X)).cpu().numpy()
+    assert np.array_equal(got, got2)                      # deterministic
+    # accumulate: two halves added into one result
+    h = N // 2
+    Sc = st.moment2_sym(dev(X[:h]))
+    st.moment2_sym(dev(X[h:]), Sc=Sc, accumulate=True)
+    assert rel_err(Sc.cpu().numpy(), ref) <= TOL
+
+
+def test_moment2_special_cases(st, oracle):
+    import torch
+    n, N = 64, 1000
+    X = np.zeros((N, n), dtype=np.float32)
+    X[:, 9] = 1.0
+    got = st.moment2_sym(dev(X)).cpu().numpy()
+    assert got[st.rank_sym2(n, 9, 9)] == N and np.count_nonzero(got) == 1
+    # N = 0 zero-fills, or leaves Sc alone when accumulating
+    Sc = torch.full((st.count_sym2(n),), 3.0, device="cuda")
+    st.moment2_sym(torch.empty((0, n), device="cuda"), Sc=Sc, accumulate=True)
+    assert float(Sc.min()) == 3.0
+    st.moment2_sym(torch.empty((0, n), device="cuda"), Sc=Sc)
+    assert float(Sc.abs().max()) == 0.0
+
+
+def test_moment2_full(st, oracle):
+    cfg = W.CONFIGS[5]
+    N, n = cfg["N"], cfg["n"]
+    say("moment2 full N=%d n=%d" % (N, n))
+    X = W.moment_inputs(N, n)
+    got = st.moment2_sym(dev(X)).cpu().numpy()
+    ref = oracle.moment2_dense(X)[np.triu_indices(n)]
+    err = rel_err(got, ref)
+    say("  norm-wise error %.3e" % err)
+    assert err <= TOL
+
+
 # ---------------------------------------------------------------------- mttkrp
 @pytest.mark.parametrize("n,R", [(1, 1), (5, 4), (16, 16), (17, 3), (32, 5), (40, 16), (64, 16), (96, 32),
                                  (100, 20), (130, 64), (48, 80), (160, 20), (208, 7)])
