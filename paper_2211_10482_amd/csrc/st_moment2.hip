@@ -28,12 +28,21 @@ namespace st {
 typedef uint32_t u32;
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int M2_WAVES = 8;
+#ifndef ST_M2_WAVES
+#define ST_M2_WAVES 8
+#endif
+constexpr int M2_WAVES = ST_M2_WAVES;             // 8 or 16
 constexpr int M2_THREADS = M2_WAVES * 64;
 constexpr int M2_TILES = 10;                      // group pairs ga <= gb
 constexpr int M2_ACC = M2_TILES * 256;            // accumulators per wave / workgroup
-constexpr int M2_DEPTH = 8;                       // loads in flight per lane
-constexpr int M2_GMAX = 768;                      // workgroups (three per CU)
+#ifndef ST_M2_DEPTH
+#define ST_M2_DEPTH 8
+#endif
+#ifndef ST_M2_GMAX
+#define ST_M2_GMAX 256
+#endif
+constexpr int M2_DEPTH = ST_M2_DEPTH;             // loads in flight per lane
+constexpr int M2_GMAX = ST_M2_GMAX;               // workgroups (one per CU measured best)
 
 // tile t = 0..9 <-> (ga, gb), ga <= gb, row-major over the upper triangle of 4 x 4
 __host__ __device__ constexpr int m2_ga(int t) { return t < 4 ? 0 : t < 7 ? 1 : t < 9 ? 2 : 3; }
@@ -84,7 +93,7 @@ template <bool FULL>
 __global__ __launch_bounds__(M2_THREADS) void moment2_mfma_kernel(const float *__restrict__ X, int64_t N, u32 n,
                                                                 float *__restrict__ ws)
 {
-    __shared__ __attribute__((aligned(16))) float red[4][M2_ACC];
+    __shared__ __attribute__((aligned(16))) float red[M2_WAVES / 2][M2_ACC];
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const int64_t nquads = (N + 3) / 4;
     const int64_t stride = (int64_t)gridDim.x * M2_WAVES;
@@ -111,9 +120,10 @@ __global__ __launch_bounds__(M2_THREADS) void moment2_mfma_kernel(const float *_
         }
     }
 
-    // fixed tree over the 8 waves: 4..7 -> 0..3, then 2,3 -> 0,1, then 1 -> 0
+    // fixed tree over the waves: upper half -> lower half, repeatedly (8 waves: 4..7 -> 0..3,
+    // then 2,3 -> 0,1, then 1 -> 0)
 #pragma unroll
-    for (u32 half = 4; half >= 1; half >>= 1) {
+    for (u32 half = M2_WAVES / 2; half >= 1; half >>= 1) {
         if (wave >= half && wave < 2 * half) {
             float *dst = &red[wave - half][lane];
 #pragma unroll
