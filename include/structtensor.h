@@ -105,6 +105,7 @@ size_t st_batax_utri_workspace(int n);
 size_t st_ttm_band_workspace(int n, int w, int nl, int R);
 size_t st_moment3_sym_workspace(int64_t N, int n);
 size_t st_moment2_sym_workspace(int64_t N, int n);
+size_t st_moment4_sym_workspace(int64_t N, int n);
 
 /* ---- kernels -------------------------------------------------------------- */
 
@@ -153,6 +154,14 @@ st_status st_moment3_sym(const float *X, int64_t N, int n, float *Sc, int accumu
  * (the M1 = f (x) f term of the same covariance; its structure is plain
  * symmetry).  Arguments as for st_moment3_sym; Sc has n(n+1)/2 entries. */
 st_status st_moment2_sym(const float *X, int64_t N, int n, float *Sc, int accumulate,
+                         void *ws, size_t ws_bytes, void *stream);
+
+/* Fourth-moment accumulation over N samples, unique entries only:
+ *     Sc(rank4(i,j,k,l)) (+)= sum_s X(s,i) * X(s,j) * X(s,k) * X(s,l)   for i<=j<=k<=l
+ * (the M3 = vec(f (x) f) (x) vec(f (x) f) term of the same covariance: about 23 of
+ * every 24 dense entries are redundant).  Arguments as for st_moment3_sym; Sc has
+ * st_count_sym4(n) entries; n <= 256. */
+st_status st_moment4_sym(const float *X, int64_t N, int n, float *Sc, int accumulate,
                          void *ws, size_t ws_bytes, void *stream);
 
 /* Reconstruction through the redundancy map (Property 5:

@@ -17,6 +17,7 @@ from .binding import (  # noqa: F401
     lib,
     moment2_sym,
     moment3_sym,
+    moment4_sym,
     mttkrp_sym3,
     rank_band,
     rank_sym2,

@@ -46,11 +46,13 @@ SIGNATURES = {
     "st_ttm_band_workspace": (_SZ, [_I32, _I32, _I32, _I32]),
     "st_moment3_sym_workspace": (_SZ, [_I64, _I32]),
     "st_moment2_sym_workspace": (_SZ, [_I64, _I32]),
+    "st_moment4_sym_workspace": (_SZ, [_I64, _I32]),
     "st_mttkrp_sym3": (_I32, [_P, _P, _P, _I32, _I32, _P, _SZ, _P]),
     "st_batax_utri": (_I32, [_P, _P, _P, _I32, _F, _P, _SZ, _P]),
     "st_ttm_band": (_I32, [_P, _P, _P, _I32, _I32, _I32, _I32, _P, _SZ, _P]),
     "st_moment3_sym": (_I32, [_P, _I64, _I32, _P, _I32, _P, _SZ, _P]),
     "st_moment2_sym": (_I32, [_P, _I64, _I32, _P, _I32, _P, _SZ, _P]),
+    "st_moment4_sym": (_I32, [_P, _I64, _I32, _P, _I32, _P, _SZ, _P]),
     "st_expand_sym": (_I32, [_P, _P, _I32, _I32, _P]),
 }
 
@@ -174,6 +176,8 @@ def workspace_bytes(kernel: str, **kw) -> int:
         return int(L.st_ttm_band_workspace(kw["n"], kw["w"], kw["nl"], kw["R"]))
     if kernel == "moment3_sym":
         return int(L.st_moment3_sym_workspace(kw["N"], kw["n"]))
+    if kernel == "moment4_sym":
+        return int(L.st_moment4_sym_workspace(kw["N"], kw["n"]))
     if kernel == "moment2_sym":
         return int(L.st_moment2_sym_workspace(kw["N"], kw["n"]))
     raise KeyError(kernel)
@@ -254,6 +258,10 @@ def _moment(order, X, Sc, accumulate, ws):
 
 def moment2_sym(X, Sc=None, accumulate=False, ws=None):
     return _moment(2, X, Sc, accumulate, ws)
+
+
+def moment4_sym(X, Sc=None, accumulate=False, ws=None):
+    return _moment(4, X, Sc, accumulate, ws)
 
 
 def expand_sym(Sc, n, order, S=None):

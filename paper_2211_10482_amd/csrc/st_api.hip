@@ -185,6 +185,7 @@ size_t st_ttm_band_workspace(int n, int w, int nl, int R)
     return (n < 1 || w < 0 || nl < 1 || R < 1) ? 0 : ttm_workspace(n, w, nl, R);
 }
 size_t st_moment3_sym_workspace(int64_t N, int n) { return (N < 0 || n < 1) ? 0 : moment3_workspace(N, n); }
+size_t st_moment4_sym_workspace(int64_t N, int n) { return (N < 0 || n < 1 || n > 256) ? 0 : moment4_workspace(N, n); }
 size_t st_moment2_sym_workspace(int64_t N, int n) { return (N < 0 || n < 1 || n > 65000) ? 0 : moment2_workspace(N, n); }
 
 /* ---- kernels ---------------------------------------------------------------- */
@@ -269,6 +270,21 @@ st_status st_moment2_sym(const float *X, int64_t N, int n, float *Sc, int accumu
     ST_REQUIRE_WS(need);
     if (need > 0 && (overlap(ws, need, Sc, sb) || (N > 0 && overlap(ws, need, X, xb)))) return ST_ERR_SHAPE;
     return launch_moment2(X, N, n, Sc, accumulate, ws, (hipStream_t)stream);
+}
+
+st_status st_moment4_sym(const float *X, int64_t N, int n, float *Sc, int accumulate, void *ws,
+                         size_t ws_bytes, void *stream)
+{
+    if (!Sc || (N > 0 && !X)) return ST_ERR_NULL;
+    if (N < 0 || n < 1 || (accumulate != 0 && accumulate != 1)) return ST_ERR_SHAPE;
+    if (n > 256) return ST_ERR_UNSUPPORTED;    /* packed positions are 32-bit on the device */
+    if (!aligned16(Sc) || (X && !aligned16(X))) return ST_ERR_ALIGN;
+    size_t sb = (size_t)count_sym4<i64>(n) * 4, xb = (size_t)N * n * 4;
+    if (N > 0 && overlap(Sc, sb, X, xb)) return ST_ERR_SHAPE;
+    size_t need = moment4_workspace(N, n);
+    ST_REQUIRE_WS(need);
+    if (need > 0 && (overlap(ws, need, Sc, sb) || (N > 0 && overlap(ws, need, X, xb)))) return ST_ERR_SHAPE;
+    return launch_moment4(X, N, n, Sc, accumulate, ws, (hipStream_t)stream);
 }
 
 st_status st_expand_sym(const float *Sc, float *S, int n, int order, void *stream)

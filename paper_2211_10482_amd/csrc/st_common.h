@@ -45,6 +45,10 @@ size_t moment2_workspace(int64_t N, int n);
 st_status launch_moment2(const float *X, int64_t N, int n, float *Sc, int accumulate, void *ws,
                          hipStream_t s);
 
+size_t moment4_workspace(int64_t N, int n);
+st_status launch_moment4(const float *X, int64_t N, int n, float *Sc, int accumulate, void *ws,
+                         hipStream_t s);
+
 size_t mttkrp_workspace(int n, int R);
 st_status launch_mttkrp(const float *Tc, const float *B, float *M, int n, int R, void *ws,
                         hipStream_t s);

@@ -312,6 +312,73 @@ def test_moment2_full(st, oracle):
     assert err <= TOL
 
 
+# ---------------------------------------------------------------------- moment4 (M3)
+@pytest.mark.parametrize("N,n", [(1, 1), (7, 5), (100, 16), (300, 64), (65, 64), (64, 64), (50, 20), (130, 63),
+                                 (40, 70)])
+def test_moment4_small(st, oracle, N, n):
+    say("moment4 N=%d n=%d" % (N, n))
+    X = W.normal(401, N * n).reshape(N, n)
+    lst = oracle.list_sym4(n)
+    ref = oracle.moment4_entries(X, lst)
+    got = st.moment4_sym(dev(X)).cpu().numpy()
+    assert got.shape[0] == lst.shape[0]
+    assert rel_err(got, ref) <= TOL
+    got2 = st.moment4_sym(dev(X)).cpu().numpy()
+    assert np.array_equal(got, got2)                      # deterministic
+    h = N // 2
+    Sc = st.moment4_sym(dev(X[:h]))
+    st.moment4_sym(dev(X[h:]), Sc=Sc, accumulate=True)
+    assert rel_err(Sc.cpu().numpy(), ref) <= TOL
+
+
+def test_moment4_special_cases(st, oracle):
+    import torch
+    n, N = 64, 200
+    X = np.zeros((N, n), dtype=np.float32)
+    X[:, 17] = 1.0
+    got = st.moment4_sym(dev(X)).cpu().numpy()
+    assert got[st.rank_sym4(n, 17, 17, 17, 17)] == N and np.count_nonzero(got) == 1
+    Sc = torch.full((st.count_sym4(n),), 2.0, device="cuda")
+    st.moment4_sym(torch.empty((0, n), device="cuda"), Sc=Sc, accumulate=True)
+    assert float(Sc.min()) == 2.0
+    st.moment4_sym(torch.empty((0, n), device="cuda"), Sc=Sc)
+    assert float(Sc.abs().max()) == 0.0
+    # sum_p mult(p) * S_C(p) = sum_s (1^T x_s)^4 at a size the oracle does not enumerate densely
+    N = 5000
+    X = W.normal(402, N * n).reshape(N, n)
+    got = st.moment4_sym(dev(X)).cpu().numpy().astype(np.float64)
+    lst = oracle.list_sym4(n).astype(np.int64)
+    srt = np.sort(lst, axis=1)
+    runs = np.concatenate([np.ones((len(srt), 1), dtype=bool), srt[:, 1:] != srt[:, :-1]], axis=1)
+    # multiplicity = 4! / prod(run lengths!)
+    import math
+    mult = np.empty(len(srt))
+    for q, row in enumerate(srt):
+        _, cnts = np.unique(row, return_counts=True)
+        mult[q] = 24 / np.prod([math.factorial(int(c)) for c in cnts])
+    lhs = float((mult * got).sum())
+    rhs = float((X.astype(np.float64).sum(axis=1) ** 4).sum())
+    assert abs(lhs - rhs) <= 1e-4 * abs(rhs)
+
+
+def test_moment4_full(st, oracle):
+    cfg = W.CONFIGS[5]
+    N, n = cfg["N"], cfg["n"]
+    say("moment4 full N=%d n=%d" % (N, n))
+    X = W.moment_inputs(N, n)
+    got = st.moment4_sym(dev(X)).cpu().numpy()
+    lst = oracle.list_sym4(n)
+    rng = np.random.default_rng(7)
+    pick = np.unique(np.concatenate([rng.integers(0, lst.shape[0], 1500), [0, lst.shape[0] - 1]]))
+    say("  oracle on %d sampled entries" % pick.size)
+    ref = oracle.moment4_entries(X, lst[pick])
+    scale = np.abs(ref).max()
+    err = float(np.abs(got[pick] - ref).max() / scale)
+    say("  norm-wise error on the sample %.3e" % err)
+    assert err <= TOL
+    assert np.all(np.isfinite(got))
+
+
 # ---------------------------------------------------------------------- mttkrp
 @pytest.mark.parametrize("n,R", [(1, 1), (5, 4), (16, 16), (17, 3), (32, 5), (40, 16), (64, 16), (96, 32),
                                  (100, 20), (130, 64), (48, 80), (160, 20), (208, 7)])
