@@ -28,6 +28,8 @@ import st_workloads as W  # noqa: E402
 # published MI355X peaks
 HBM_PEAK_GBS = 8000.0
 MFMA_FP32_PEAK_TFLOPS = 157.3
+# plain (unpacked) fp32 vector rate: 256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2.4 GHz; packed fp32 is compiled out
+ALU_FP32_PEAK_TFLOPS = 78.6
 
 
 def log(*a):
@@ -131,6 +133,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-next", action="store_true", help="skip the rows beyond the step (moment2, moment4, expand 4)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="after the timed region, run one plain 256 MiB device copy (a kernel of known "
                          "traffic for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
@@ -238,6 +241,45 @@ def main():
     roofline = dict(kernel=dom, bound="mfma", achieved=round(achieved, 3), peak=MFMA_FP32_PEAK_TFLOPS,
                     unit="TFLOP/s", frac=round(achieved / MFMA_FP32_PEAK_TFLOPS, 4), traffic=recorded_traffic())
 
+    # Rows beyond the step (order-2 and order-4 moments of the same samples, order-4 reconstruction): timed
+    # on their own after the step, reported for information, not part of `value`.
+    next_rows = None
+    if not args.no_next:
+        log("next rows (moment2, moment4, expand order 4) ...")
+        n5, N5 = c5["n"], c5["N"]
+        pent = n5 * (n5 + 1) * (n5 + 2) * (n5 + 3) // 24
+        Sc2 = torch.empty(tri(n5), **f32)
+        Sc4 = torch.empty(pent, **f32)
+        S4 = torch.empty((n5,) * 4, **f32)
+        ws2 = torch.empty(max(16, st.workspace_bytes("moment2_sym", N=N5, n=n5)), dtype=torch.uint8, device=dev)
+        ws4 = torch.empty(max(16, st.workspace_bytes("moment4_sym", N=N5, n=n5)), dtype=torch.uint8, device=dev)
+        extra = [
+            ("moment2_sym_N2e6_n64", lambda: st.moment2_sym(X, Sc=Sc2, ws=ws2),
+             dict(flops=N5 * 2 * tri(n5), bytes=4 * (N5 * n5 + tri(n5)), bound="hbm")),
+            ("moment4_sym_N2e6_n64", lambda: st.moment4_sym(X, Sc=Sc4, ws=ws4),
+             dict(flops=N5 * (2 * pent + tri(n5)), bytes=4 * (N5 * n5 + pent), bound="alu")),
+            ("expand_sym_order4_n64", lambda: st.expand_sym(Sc4, n5, 4, S=S4),
+             dict(flops=0, bytes=4 * (pent + n5 ** 4), bound="hbm")),
+        ]
+        next_rows = {}
+        for name, f, w in extra:
+            f()
+            torch.cuda.synchronize()
+            evs = []
+            for _ in range(3):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                f()
+                e1.record()
+                evs.append((e0, e1))
+            torch.cuda.synchronize()
+            ms = float(np.mean([a.elapsed_time(b) for a, b in evs]))
+            gflops = w["flops"] / (ms * 1e-3) / 1e9
+            gbs = w["bytes"] / (ms * 1e-3) / 1e9
+            frac = gbs / HBM_PEAK_GBS if w["bound"] == "hbm" else gflops / 1e3 / ALU_FP32_PEAK_TFLOPS
+            next_rows[name] = dict(ms=round(ms, 5), unique_gflops=round(gflops, 2), alg_gbs=round(gbs, 2),
+                                   bound=w["bound"], frac=round(frac, 4))
+
     result = {
         "metric": "unique-element GFLOP/s over the five structured kernels, 1xMI355X",
         "value": round(value, 2),
@@ -256,6 +298,7 @@ def main():
                                "moment3_sym N=2e6 n=64 + expand_sym n=64"},
         "roofline": roofline,
         "kernels": kernels,
+        "next_rows": next_rows,
     }
     if not args.no_cpu_baseline:
         log("cpu baseline (oracle on a bounded sample) ...")
