@@ -40,6 +40,9 @@ def lib():
             "so_batax_utri": (None, [p, p, i64, C.c_double, p]),
             "so_ttm_dense": (None, [p, p, i64, i64, i64, i64, p]),
             "so_ttm_band": (None, [p, p, i64, i64, i64, i64, p]),
+            "so_ttm_full": (None, [p, p, i64, i64, i64, i64, p]),
+            "so_thp_full": (None, [p, p, i64, p]),
+            "so_mttkrp_full": (None, [p, p, p, i64, i64, i64, i64, p]),
             "so_moment3_dense": (None, [p, i64, i64, p]),
             "so_moment3_entries": (None, [p, i64, i64, p, i64, p]),
             "so_moment2_dense": (None, [p, i64, i64, p]),
@@ -194,6 +197,41 @@ def ttm_band(Tc, U, n, w):
     Yc = np.empty((nb, R), dtype=np.float64)
     lib().so_ttm_band(pT, pU, n, w, nl, R, Yc.ctypes.data)
     return Yc
+
+
+def ttm_full(B, U):
+    """A(i,j,r) = sum_l B(i,j,l) U(l,r) on a dense B (ni x nj x nl)."""
+    B, pB = _f32(B)
+    U, pU = _f32(U)
+    ni, nj, nl = B.shape
+    assert U.shape[0] == nl
+    R = U.shape[1]
+    A = np.empty((ni, nj, R), dtype=np.float64)
+    lib().so_ttm_full(pB, pU, ni, nj, nl, R, A.ctypes.data)
+    return A
+
+
+def thp_full(B, C):
+    """A = B * C elementwise (dense operands of equal shape)."""
+    B, pB = _f32(B)
+    C, pC = _f32(C)
+    assert B.shape == C.shape
+    A = np.empty(B.shape, dtype=np.float64)
+    lib().so_thp_full(pB, pC, B.size, A.ctypes.data)
+    return A
+
+
+def mttkrp_full(B, C, D):
+    """A(i,j) = sum_kl B(i,k,l) C(k,j) D(l,j) on a dense B (ni x nk x nl)."""
+    B, pB = _f32(B)
+    C, pC = _f32(C)
+    D, pD = _f32(D)
+    ni, nk, nl = B.shape
+    R = C.shape[1]
+    assert C.shape[0] == nk and D.shape == (nl, R)
+    A = np.empty((ni, R), dtype=np.float64)
+    lib().so_mttkrp_full(pB, pC, pD, ni, nk, nl, R, A.ctypes.data)
+    return A
 
 
 def moment3_dense(X):

@@ -349,6 +349,49 @@ SO_API void so_ttm_band(const float *Tc, const float *U, int64_t n, int64_t w,
 }
 
 /* ------------------------------------------------------------------ */
+/* the three kernels of the kernel table on plain DENSE operands (the    */
+/* sparsity structures of the table only decide which entries of B are   */
+/* non-zero; the tests scatter a packed operand into a zero-filled dense  */
+/* one and read the result back through the same support):               */
+/*   TTM     A(i,j,k) = sum_l B(i,j,l) C(k,l)        (here U(l,k) = C(k,l)) */
+/*   THP     A(i,j,k) = B(i,j,k) C(i,j,k)                                */
+/*   MTTKRP  A(i,j)   = sum_{k,l} B(i,k,l) C(k,j) D(l,j)                 */
+/* ------------------------------------------------------------------ */
+SO_API void so_ttm_full(const float *B, const float *U, int64_t ni, int64_t nj, int64_t nl,
+                        int64_t R, double *A)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t ij = 0; ij < ni * nj; ++ij) {
+        double *Ar = A + ij * R;
+        for (int64_t r = 0; r < R; ++r) Ar[r] = 0.0;
+        for (int64_t l = 0; l < nl; ++l) {
+            double t = (double)B[ij * nl + l];
+            for (int64_t r = 0; r < R; ++r) Ar[r] += t * (double)U[l * R + r];
+        }
+    }
+}
+
+SO_API void so_thp_full(const float *B, const float *C, int64_t count, double *A)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t q = 0; q < count; ++q) A[q] = (double)B[q] * (double)C[q];
+}
+
+SO_API void so_mttkrp_full(const float *B, const float *C, const float *D, int64_t ni, int64_t nk,
+                           int64_t nl, int64_t R, double *A)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < ni; ++i)
+        for (int64_t j = 0; j < R; ++j) {
+            double s = 0.0;
+            for (int64_t k = 0; k < nk; ++k)
+                for (int64_t l = 0; l < nl; ++l)
+                    s += (double)B[(i * nk + k) * nl + l] * (double)C[k * R + j] * (double)D[l * R + j];
+            A[i * R + j] = s;
+        }
+}
+
+/* ------------------------------------------------------------------ */
 /* third moment  S(i,j,k) = sum_s x_s(i) x_s(j) x_s(k)                  */
 /* (degree-3 interaction term M2 = f (x) vec(f (x) f), summed over the  */
 /* samples: "creation and addition of covariance matrices").  Raw sum,  */

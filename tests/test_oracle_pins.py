@@ -359,3 +359,30 @@ def test_pr2_covariance_distinct_elements(oracle):
     # covariance: 65 for four features (golden file), counted here through the listings
     n = 4
     assert oracle.count_sym2(n) + oracle.count_sym3(n) + oracle.list_sym4(n).shape[0] == 65
+
+
+# ------------------------------------------------- the kernel table on dense operands
+def test_kernel_table_dense_definitions(oracle):
+    ni, nj, nl, R = 5, 4, 6, 3
+    B = W.uniform(111, ni * nj * nl).reshape(ni, nj, nl)
+    U = W.uniform(112, nl * R).reshape(nl, R)
+    B64, U64 = B.astype(np.float64), U.astype(np.float64)
+    assert np.allclose(oracle.ttm_full(B, U), np.einsum("ijl,lr->ijr", B64, U64), rtol=1e-13, atol=1e-14)
+    Cd = W.uniform(113, ni * nj * nl).reshape(ni, nj, nl)
+    assert np.array_equal(oracle.thp_full(B, Cd), B64 * Cd.astype(np.float64))
+    nk = nj
+    C = W.uniform(114, nk * R).reshape(nk, R)
+    D = W.uniform(115, nl * R).reshape(nl, R)
+    ref = np.einsum("ikl,kj,lj->ij", B64, C.astype(np.float64), D.astype(np.float64))
+    assert np.allclose(oracle.mttkrp_full(B, C, D), ref, rtol=1e-13, atol=1e-14)
+    # the symmetric special case agrees with the packed symmetric oracle
+    n = 6
+    Tc = W.uniform(116, oracle.count_sym3(n))
+    Bf = W.uniform(117, n * R).reshape(n, R)
+    T = oracle.dense_sym3(Tc, n).astype(np.float32)   # exact: the values are fp32
+    assert np.allclose(oracle.mttkrp_full(T, Bf, Bf), oracle.mttkrp_sym3(Tc, Bf), rtol=1e-12, atol=1e-13)
+    # a band TTM is the dense TTM of the zero-filled tensor
+    n, w = 7, 2
+    Tb = W.uniform(118, oracle.count_band(n, w) * nl)
+    Tdense = oracle.dense_band(Tb, n, w, nl).astype(np.float32)
+    assert np.allclose(oracle.ttm_full(Tdense, U), oracle.ttm_dense(Tb, U, n, w), rtol=1e-13, atol=1e-14)
