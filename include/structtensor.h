@@ -106,6 +106,8 @@ size_t st_ttm_band_workspace(int n, int w, int nl, int R);
 size_t st_moment3_sym_workspace(int64_t N, int n);
 size_t st_moment2_sym_workspace(int64_t N, int n);
 size_t st_moment4_sym_workspace(int64_t N, int n);
+size_t st_ttm_struct_workspace(int structure, int ni, int nj, int nl, int R);
+size_t st_mttkrp_fixed_workspace(int kind, int ni, int nk, int nl, int R);
 
 /* ---- kernels -------------------------------------------------------------- */
 
@@ -170,6 +172,63 @@ st_status st_moment4_sym(const float *X, int64_t N, int n, float *Sc, int accumu
  * triple)]; order 4: S(i,j,k,l) = Sc[rank4(sorted quadruple)] (n <= 256).  S is
  * the dense n^order array, overwritten.  A bit-exact copy. */
 st_status st_expand_sym(const float *Sc, float *S, int n, int order, void *stream);
+
+/* ---- the sparsity structures of the paper's kernel table -------------------
+ *
+ * The table evaluates TTM, THP and MTTKRP with an order-3 operand B(i,j,l)
+ * whose unique set restricts the index pair (i,j) and leaves l free.  Packed,
+ * such an operand is a list of its non-zero fibres B(i,j,:), `nl` contiguous
+ * values each, in the order of the table's unique set (i outer, j inner):
+ *   ST_STRUCT_DIAG    "diagonal (plane)", i = j:   fibre p is (p,p), min(ni,nj) fibres
+ *   ST_STRUCT_FIXED_I "fixed i",  i = I:           fibre p is (I,p), nj fibres
+ *   ST_STRUCT_FIXED_J "fixed j",  j = J:           fibre p is (p,J), ni fibres
+ *   ST_STRUCT_UPPER   "upper half cube", i <= j:   fibre p is the p-th sym2 pair,
+ *                     ni = nj required, ni(ni+1)/2 fibres
+ */
+enum { ST_STRUCT_DIAG = 0, ST_STRUCT_FIXED_I = 1, ST_STRUCT_FIXED_J = 2, ST_STRUCT_UPPER = 3 };
+
+/* Number of non-zero fibres of a structure; -1 for an unknown structure, a
+ * negative size, or ni != nj with ST_STRUCT_UPPER. */
+int64_t st_count_struct(int structure, int64_t ni, int64_t nj);
+
+/* TTM of the kernel table,  A(i,j,k) := B(i,j,l) * C(k,l),  U(l,k) = C(k,l):
+ *     Ac(p,r) = sum_l Bc(p,l) * U(l,r)      for every non-zero fibre p of B
+ * The output keeps the unique set of B (product and projection inference
+ * rules) and is packed the same way: Bc is [fibres][nl], U is nl x R, Ac is
+ * [fibres][R], overwritten.  The value of a fixed index does not enter. */
+st_status st_ttm_struct(int structure, const float *Bc, const float *U, float *Ac, int ni, int nj,
+                        int nl, int R, void *ws, size_t ws_bytes, void *stream);
+
+/* THP of the kernel table,  A(i,j,k) := B(i,j,k) * C(i,j,k):
+ *     Ac(p,l) = Bc(p,l) * C(i(p), j(p), l)
+ * B is packed ([fibres][nl]); C is a DENSE ni x nj x nl tensor of which only
+ * the fibres inside the unique set of B are read; Ac is packed like Bc,
+ * overwritten.  `fixed` is the value I or J of the fixed index (ignored for
+ * the other structures; ST_ERR_SHAPE if out of range). */
+st_status st_thp_struct(int structure, const float *Bc, const float *C, float *Ac, int ni, int nj,
+                        int nl, int fixed, void *stream);
+
+/* MTTKRP of the kernel table,  A(i,r) := B(i,k,l) * C(k,r) * D(l,r),  with
+ * indices of B fixed (the table names the positions of B (i,j,l): its
+ * "fixed j" is the contracted index k here):
+ *   ST_MTTKRP_FIXED_IK "fixed i, j": B(I,K,:) only.  Bc is [nl], A is [R] (row I
+ *                      of the result, every other row is zero):
+ *                      A(r) = C(K,r) * sum_l Bc(l) D(l,r)
+ *   ST_MTTKRP_FIXED_I  "fixed i": B(I,:,:) only.  Bc is [nk][nl], A is [R]:
+ *                      A(r) = sum_k C(k,r) * sum_l Bc(k,l) D(l,r)
+ *   ST_MTTKRP_FIXED_K  "fixed j": B(:,K,:) only.  Bc is [ni][nl], A is [ni][R]:
+ *                      A(i,r) = C(K,r) * sum_l Bc(i,l) D(l,r)
+ * C is nk x R, D is nl x R; `fixed_k` selects the row of C (ignored for
+ * ST_MTTKRP_FIXED_I; ST_ERR_SHAPE if outside [0, nk)). */
+enum { ST_MTTKRP_FIXED_IK = 0, ST_MTTKRP_FIXED_I = 1, ST_MTTKRP_FIXED_K = 2 };
+st_status st_mttkrp_fixed(int kind, const float *Bc, const float *C, const float *D, float *A, int ni,
+                          int nk, int nl, int R, int fixed_k, void *ws, size_t ws_bytes, void *stream);
+
+/* Zero-filled dense form of a packed band tensor (Property 5 restricted to a
+ * sparsity structure: T = T_C on the unique set, zero elsewhere):
+ *     T(i,j,l) = Tc(rank_band(i,j), l) if |i-j| <= w, else 0
+ * Tc is [st_count_band(n,w)][nl], T is n x n x nl, overwritten. */
+st_status st_expand_band(const float *Tc, float *T, int n, int w, int nl, void *stream);
 
 #ifdef __cplusplus
 }

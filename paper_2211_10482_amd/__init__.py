@@ -7,6 +7,18 @@ kernels.  There is no CPU fallback: if the library cannot be loaded, importing
 the binding's functions raises.
 """
 from .binding import (  # noqa: F401
+    MTTKRP_FIXED_I,
+    MTTKRP_FIXED_IK,
+    MTTKRP_FIXED_K,
+    STRUCT_DIAG,
+    STRUCT_FIXED_I,
+    STRUCT_FIXED_J,
+    STRUCT_UPPER,
+    count_struct,
+    expand_band,
+    mttkrp_fixed,
+    thp_struct,
+    ttm_struct,
     StructTensorError,
     count_band,
     count_sym2,

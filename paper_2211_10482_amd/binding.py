@@ -54,7 +54,18 @@ SIGNATURES = {
     "st_moment2_sym": (_I32, [_P, _I64, _I32, _P, _I32, _P, _SZ, _P]),
     "st_moment4_sym": (_I32, [_P, _I64, _I32, _P, _I32, _P, _SZ, _P]),
     "st_expand_sym": (_I32, [_P, _P, _I32, _I32, _P]),
+    "st_count_struct": (_I64, [_I32, _I64, _I64]),
+    "st_ttm_struct_workspace": (_SZ, [_I32, _I32, _I32, _I32, _I32]),
+    "st_mttkrp_fixed_workspace": (_SZ, [_I32, _I32, _I32, _I32, _I32]),
+    "st_ttm_struct": (_I32, [_I32, _P, _P, _P, _I32, _I32, _I32, _I32, _P, _SZ, _P]),
+    "st_thp_struct": (_I32, [_I32, _P, _P, _P, _I32, _I32, _I32, _I32, _P]),
+    "st_mttkrp_fixed": (_I32, [_I32, _P, _P, _P, _P, _I32, _I32, _I32, _I32, _I32, _P, _SZ, _P]),
+    "st_expand_band": (_I32, [_P, _P, _I32, _I32, _I32, _P]),
 }
+
+# structures of the kernel table (values of include/structtensor.h)
+STRUCT_DIAG, STRUCT_FIXED_I, STRUCT_FIXED_J, STRUCT_UPPER = 0, 1, 2, 3
+MTTKRP_FIXED_IK, MTTKRP_FIXED_I, MTTKRP_FIXED_K = 0, 1, 2
 
 
 def lib():
@@ -90,6 +101,9 @@ def rank_sym2(n, i, j): return int(lib().st_rank_sym2(n, i, j))
 def rank_sym3(n, i, j, k): return int(lib().st_rank_sym3(n, i, j, k))
 def rank_sym4(n, i, j, k, l): return int(lib().st_rank_sym4(n, i, j, k, l))
 def rank_band(n, w, i, j): return int(lib().st_rank_band(n, w, i, j))
+
+
+def count_struct(structure, ni, nj): return int(lib().st_count_struct(structure, ni, nj))
 
 
 def unrank_sym2(n, p):
@@ -180,6 +194,10 @@ def workspace_bytes(kernel: str, **kw) -> int:
         return int(L.st_moment4_sym_workspace(kw["N"], kw["n"]))
     if kernel == "moment2_sym":
         return int(L.st_moment2_sym_workspace(kw["N"], kw["n"]))
+    if kernel == "ttm_struct":
+        return int(L.st_ttm_struct_workspace(kw["structure"], kw["ni"], kw["nj"], kw["nl"], kw["R"]))
+    if kernel == "mttkrp_fixed":
+        return int(L.st_mttkrp_fixed_workspace(kw["kind"], kw["ni"], kw["nk"], kw["nl"], kw["R"]))
     raise KeyError(kernel)
 
 
@@ -270,3 +288,48 @@ def expand_sym(Sc, n, order, S=None):
         S = torch.empty((n,) * order, dtype=torch.float32, device=Sc.device)
     _check(lib().st_expand_sym(_dev_f32(Sc, "Sc"), _dev_f32(S, "S"), n, order, _stream()), "st_expand_sym")
     return S
+
+
+# ---- the kernel table's sparsity structures ---------------------------------------------
+def ttm_struct(structure, Bc, U, ni, nj, Ac=None, ws=None):
+    torch = _torch()
+    nl, R = U.shape
+    rows = count_struct(structure, ni, nj)
+    if Ac is None:
+        Ac = torch.empty((max(rows, 0), R), dtype=torch.float32, device=U.device)
+    ws, pws, wsb = _workspace(workspace_bytes("ttm_struct", structure=structure, ni=ni, nj=nj, nl=nl, R=R), U, ws)
+    _check(lib().st_ttm_struct(structure, _dev_f32(Bc, "Bc"), _dev_f32(U, "U"), _dev_f32(Ac, "Ac"), ni, nj, nl, R,
+                               pws, wsb, _stream()), "st_ttm_struct")
+    return Ac
+
+
+def thp_struct(structure, Bc, C, fixed=0, Ac=None):
+    torch = _torch()
+    ni, nj, nl = C.shape
+    rows = count_struct(structure, ni, nj)
+    if Ac is None:
+        Ac = torch.empty((max(rows, 0), nl), dtype=torch.float32, device=C.device)
+    _check(lib().st_thp_struct(structure, _dev_f32(Bc, "Bc"), _dev_f32(C, "C"), _dev_f32(Ac, "Ac"), ni, nj, nl,
+                               int(fixed), _stream()), "st_thp_struct")
+    return Ac
+
+
+def mttkrp_fixed(kind, Bc, C, D, ni, fixed_k=0, A=None, ws=None):
+    torch = _torch()
+    nk, R = C.shape
+    nl = D.shape[0]
+    if A is None:
+        shape = (ni, R) if kind == MTTKRP_FIXED_K else (R,)
+        A = torch.empty(shape, dtype=torch.float32, device=C.device)
+    ws, pws, wsb = _workspace(workspace_bytes("mttkrp_fixed", kind=kind, ni=ni, nk=nk, nl=nl, R=R), C, ws)
+    _check(lib().st_mttkrp_fixed(kind, _dev_f32(Bc, "Bc"), _dev_f32(C, "C"), _dev_f32(D, "D"), _dev_f32(A, "A"),
+                                 ni, nk, nl, R, int(fixed_k), pws, wsb, _stream()), "st_mttkrp_fixed")
+    return A
+
+
+def expand_band(Tc, n, w, nl, T=None):
+    torch = _torch()
+    if T is None:
+        T = torch.empty((n, n, nl), dtype=torch.float32, device=Tc.device)
+    _check(lib().st_expand_band(_dev_f32(Tc, "Tc"), _dev_f32(T, "T"), n, w, nl, _stream()), "st_expand_band")
+    return T

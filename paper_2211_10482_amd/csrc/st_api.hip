@@ -188,6 +188,25 @@ size_t st_moment3_sym_workspace(int64_t N, int n) { return (N < 0 || n < 1) ? 0 
 size_t st_moment4_sym_workspace(int64_t N, int n) { return (N < 0 || n < 1 || n > 256) ? 0 : moment4_workspace(N, n); }
 size_t st_moment2_sym_workspace(int64_t N, int n) { return (N < 0 || n < 1 || n > 65000) ? 0 : moment2_workspace(N, n); }
 
+static i64 struct_pairs(int structure, i64 ni, i64 nj)
+{
+    if (ni < 0 || nj < 0) return -1;
+    switch (structure) {
+    case ST_STRUCT_DIAG: return ni < nj ? ni : nj;
+    case ST_STRUCT_FIXED_I: return nj;
+    case ST_STRUCT_FIXED_J: return ni;
+    case ST_STRUCT_UPPER: return ni == nj ? count_sym2<i64>(ni) : -1;
+    default: return -1;
+    }
+}
+int64_t st_count_struct(int structure, int64_t ni, int64_t nj) { return struct_pairs(structure, ni, nj); }
+size_t st_ttm_struct_workspace(int, int, int, int, int) { return 0; }
+size_t st_mttkrp_fixed_workspace(int kind, int ni, int nk, int nl, int R)
+{
+    if (kind < 0 || kind > 2 || ni < 1 || nk < 1 || nl < 1 || R < 1) return 0;
+    return mttkrp_fixed_workspace(kind, ni, nk, nl, R);
+}
+
 /* ---- kernels ---------------------------------------------------------------- */
 #define ST_REQUIRE_WS(need)                                                     \
     do {                                                                        \
@@ -297,6 +316,70 @@ st_status st_expand_sym(const float *Sc, float *S, int n, int order, void *strea
     size_t db = (size_t)n * n * (order >= 3 ? n : 1) * (order == 4 ? n : 1) * 4;
     if (overlap(S, db, Sc, cb)) return ST_ERR_SHAPE;
     return launch_expand(Sc, S, n, order, (hipStream_t)stream);
+}
+
+st_status st_ttm_struct(int structure, const float *Bc, const float *U, float *Ac, int ni, int nj, int nl, int R,
+                        void *, size_t, void *stream)
+{
+    if (!Bc || !U || !Ac) return ST_ERR_NULL;
+    if (ni < 1 || nj < 1 || nl < 1 || R < 1) return ST_ERR_SHAPE;
+    i64 rows = struct_pairs(structure, ni, nj);
+    if (rows < 0) return ST_ERR_SHAPE;
+    if (!aligned16(Bc) || !aligned16(U) || !aligned16(Ac)) return ST_ERR_ALIGN;
+    if (rows * (i64)nl > ((i64)1 << 40) || (i64)nl * R > ((i64)1 << 31)) return ST_ERR_UNSUPPORTED;
+    size_t tb = (size_t)rows * nl * 4, ub = (size_t)nl * R * 4, yb = (size_t)rows * R * 4;
+    if (overlap(Ac, yb, Bc, tb) || overlap(Ac, yb, U, ub)) return ST_ERR_SHAPE;
+    return launch_ttm(Bc, U, Ac, rows, nl, R, nullptr, (hipStream_t)stream);
+}
+
+st_status st_thp_struct(int structure, const float *Bc, const float *C, float *Ac, int ni, int nj, int nl, int fixed,
+                        void *stream)
+{
+    if (!Bc || !C || !Ac) return ST_ERR_NULL;
+    if (ni < 1 || nj < 1 || nl < 1) return ST_ERR_SHAPE;
+    i64 rows = struct_pairs(structure, ni, nj);
+    if (rows < 0) return ST_ERR_SHAPE;
+    if (structure == ST_STRUCT_FIXED_I && (fixed < 0 || fixed >= ni)) return ST_ERR_SHAPE;
+    if (structure == ST_STRUCT_FIXED_J && (fixed < 0 || fixed >= nj)) return ST_ERR_SHAPE;
+    if (!aligned16(Bc) || !aligned16(C) || !aligned16(Ac)) return ST_ERR_ALIGN;
+    if (ni > 65000 || nj > 65000 || (i64)ni * nj * nl > ((i64)1 << 40)) return ST_ERR_UNSUPPORTED;
+    size_t pb = (size_t)rows * nl * 4, cb = (size_t)ni * nj * nl * 4;
+    if (overlap(Ac, pb, Bc, pb) || overlap(Ac, pb, C, cb)) return ST_ERR_SHAPE;
+    return launch_thp(structure, Bc, C, Ac, rows, nj, nl, fixed, (hipStream_t)stream);
+}
+
+st_status st_mttkrp_fixed(int kind, const float *Bc, const float *C, const float *D, float *A, int ni, int nk,
+                          int nl, int R, int fixed_k, void *ws, size_t ws_bytes, void *stream)
+{
+    if (!Bc || !C || !D || !A) return ST_ERR_NULL;
+    if (kind != ST_MTTKRP_FIXED_IK && kind != ST_MTTKRP_FIXED_I && kind != ST_MTTKRP_FIXED_K) return ST_ERR_SHAPE;
+    if (ni < 1 || nk < 1 || nl < 1 || R < 1) return ST_ERR_SHAPE;
+    if (kind != ST_MTTKRP_FIXED_I && (fixed_k < 0 || fixed_k >= nk)) return ST_ERR_SHAPE;
+    if (!aligned16(Bc) || !aligned16(C) || !aligned16(D) || !aligned16(A)) return ST_ERR_ALIGN;
+    if ((i64)nl * R > ((i64)1 << 31) || (i64)nk * R > ((i64)1 << 31) || (i64)ni * nl > ((i64)1 << 40) ||
+        (i64)nk * nl > ((i64)1 << 40))
+        return ST_ERR_UNSUPPORTED;
+    const i64 brows = kind == ST_MTTKRP_FIXED_IK ? 1 : kind == ST_MTTKRP_FIXED_I ? nk : ni;
+    const i64 arows = kind == ST_MTTKRP_FIXED_K ? ni : 1;
+    size_t bb = (size_t)brows * nl * 4, cb = (size_t)nk * R * 4, db = (size_t)nl * R * 4, ab = (size_t)arows * R * 4;
+    if (overlap(A, ab, Bc, bb) || overlap(A, ab, C, cb) || overlap(A, ab, D, db)) return ST_ERR_SHAPE;
+    size_t need = mttkrp_fixed_workspace(kind, ni, nk, nl, R);
+    ST_REQUIRE_WS(need);
+    if (need > 0 && (overlap(ws, need, Bc, bb) || overlap(ws, need, C, cb) || overlap(ws, need, D, db) ||
+                     overlap(ws, need, A, ab)))
+        return ST_ERR_SHAPE;
+    return launch_mttkrp_fixed(kind, Bc, C, D, A, ni, nk, nl, R, fixed_k, ws, (hipStream_t)stream);
+}
+
+st_status st_expand_band(const float *Tc, float *T, int n, int w, int nl, void *stream)
+{
+    if (!Tc || !T) return ST_ERR_NULL;
+    if (n < 1 || w < 0 || nl < 1) return ST_ERR_SHAPE;
+    if (n > 40000) return ST_ERR_UNSUPPORTED;   /* n*n and band positions are 32-bit on the device */
+    if (!aligned16(Tc) || !aligned16(T)) return ST_ERR_ALIGN;
+    size_t cb = (size_t)count_band<i64>(n, w) * nl * 4, db = (size_t)n * n * nl * 4;
+    if (overlap(T, db, Tc, cb)) return ST_ERR_SHAPE;
+    return launch_expand_band(Tc, T, n, w, nl, (hipStream_t)stream);
 }
 
 }  // extern "C"

@@ -53,4 +53,12 @@ size_t mttkrp_workspace(int n, int R);
 st_status launch_mttkrp(const float *Tc, const float *B, float *M, int n, int R, void *ws,
                         hipStream_t s);
 
+// the kernel table's sparsity structures (diagonal plane, fixed index, upper half cube)
+st_status launch_thp(int structure, const float *Bc, const float *C, float *Ac, int64_t pairs, int nj, int nl,
+                     int fixed, hipStream_t s);
+size_t mttkrp_fixed_workspace(int kind, int ni, int nk, int nl, int R);
+st_status launch_mttkrp_fixed(int kind, const float *Bc, const float *C, const float *D, float *A, int ni, int nk,
+                              int nl, int R, int fixed_k, void *ws, hipStream_t s);
+st_status launch_expand_band(const float *Tc, float *T, int n, int w, int nl, hipStream_t s);
+
 }  // namespace st

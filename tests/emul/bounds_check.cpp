@@ -15,6 +15,9 @@
 #include "../../paper_2211_10482_amd/csrc/st_moment4.hip"
 #elif defined(CHECK_EXPAND)
 #include "../../paper_2211_10482_amd/csrc/st_expand.hip"
+#elif defined(CHECK_TABLE)
+#include "../../paper_2211_10482_amd/csrc/st_ttm.hip"
+#include "../../paper_2211_10482_amd/csrc/st_table.hip"
 #else
 #error "define CHECK_<KERNEL>"
 #endif
@@ -99,6 +102,31 @@ int main(int argc, char **argv)
         int32_t *out = static_cast<int32_t *>(malloc((size_t)count * (kind == 3 ? 3 : kind == 5 ? 4 : 2) * sizeof(int32_t) + 1));
         rc = st::launch_unrank(kind, n, w, p0, count, out, nullptr);
         free(out);
+    }
+#elif defined(CHECK_TABLE)
+    // op (0 thp, 1 mttkrp with fixed indices, 2 band expand), structure | kind | w, ni, nj | nk, nl, R
+    const int op = (int)a[0], sk = (int)a[1], ni = (int)a[2], nj = (int)a[3], nl = (int)a[4], R = (int)a[5];
+    if (op == 0) {
+        const long pairs = sk == ST_STRUCT_DIAG ? (ni < nj ? ni : nj) : sk == ST_STRUCT_FIXED_I ? nj
+                           : sk == ST_STRUCT_FIXED_J ? ni : (long)st::count_sym2<int64_t>(ni);
+        const int fixed = sk == ST_STRUCT_FIXED_I ? ni - 1 : sk == ST_STRUCT_FIXED_J ? nj - 1 : 0;
+        float *Bc = fbuf((size_t)pairs * nl), *C = fbuf((size_t)ni * nj * nl), *Ac = fbuf((size_t)pairs * nl);
+        rc = st::launch_thp(sk, Bc, C, Ac, pairs, nj, nl, fixed, nullptr);
+        free(Bc); free(C); free(Ac);
+    } else if (op == 1) {
+        const int nk = nj;
+        const size_t brows = sk == ST_MTTKRP_FIXED_IK ? 1 : sk == ST_MTTKRP_FIXED_I ? nk : ni;
+        const size_t arows = sk == ST_MTTKRP_FIXED_K ? ni : 1;
+        const size_t wsb = st::mttkrp_fixed_workspace(sk, ni, nk, nl, R);
+        float *Bc = fbuf(brows * nl), *C = fbuf((size_t)nk * R), *D = fbuf((size_t)nl * R), *A = fbuf(arows * R);
+        void *ws = malloc(wsb ? wsb : 1);
+        rc = st::launch_mttkrp_fixed(sk, Bc, C, D, A, ni, nk, nl, R, nk - 1, ws, nullptr);
+        free(Bc); free(C); free(D); free(A); free(ws);
+    } else {
+        const int n = ni, w = sk;
+        float *Tc = fbuf((size_t)st::count_band<int64_t>(n, w) * nl), *T = fbuf((size_t)n * n * nl);
+        rc = st::launch_expand_band(Tc, T, n, w, nl, nullptr);
+        free(Tc); free(T);
     }
 #endif
     printf("rc=%d\n", rc);

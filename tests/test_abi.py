@@ -92,3 +92,35 @@ def test_binding_refuses_host_tensors():
         st.expand_sym(torch.zeros(20), 4, 3, S=torch.zeros(4, 4, 4))
     with pytest.raises(TypeError):
         st.expand_sym(np.zeros(20, dtype=np.float32), 4, 3, S=torch.zeros(4, 4, 4))
+
+
+def test_kernel_table_errors():
+    L = st.lib()
+    assert L.st_count_struct(0, 5, 7) == 5 and L.st_count_struct(1, 5, 7) == 7 and L.st_count_struct(2, 5, 7) == 5
+    assert L.st_count_struct(3, 6, 6) == 21 and L.st_count_struct(3, 5, 7) == -1 and L.st_count_struct(4, 5, 5) == -1
+    assert L.st_count_struct(0, -1, 5) == -1
+    Q = P + 0x1000000
+    assert L.st_ttm_struct(0, None, Q, Q + 0x1000000, 4, 4, 4, 4, None, 0, None) == NULL
+    assert L.st_ttm_struct(7, P, Q, Q + 0x1000000, 4, 4, 4, 4, None, 0, None) == SHAPE
+    assert L.st_ttm_struct(3, P, Q, Q + 0x1000000, 4, 5, 4, 4, None, 0, None) == SHAPE
+    assert L.st_ttm_struct(0, P, Q, Q + 0x1000000, 4, 4, 0, 4, None, 0, None) == SHAPE
+    assert L.st_ttm_struct(0, P + 4, Q, Q + 0x1000000, 4, 4, 4, 4, None, 0, None) == ALIGN
+    assert L.st_ttm_struct(0, P, Q, P, 4, 4, 4, 4, None, 0, None) == SHAPE            # output aliases B
+    assert L.st_thp_struct(1, P, Q, None, 4, 4, 4, 0, None) == NULL
+    assert L.st_thp_struct(1, P, Q, Q + 0x1000000, 4, 4, 4, 4, None) == SHAPE           # fixed i out of range
+    assert L.st_thp_struct(2, P, Q, Q + 0x1000000, 4, 6, 4, 6, None) == SHAPE           # fixed j out of range
+    assert L.st_thp_struct(0, P, Q, Q + 0x1000000, 4, 4, -1, 0, None) == SHAPE
+    assert L.st_thp_struct(0, P, Q, Q + 0x1000000, 70000, 4, 4, 0, None) == UNSUPPORTED
+    R3 = Q + 0x2000000
+    assert L.st_mttkrp_fixed(0, P, Q, None, R3, 4, 4, 4, 4, 0, None, 0, None) == NULL
+    assert L.st_mttkrp_fixed(3, P, Q, Q + 0x1000000, R3, 4, 4, 4, 4, 0, None, 0, None) == SHAPE
+    assert L.st_mttkrp_fixed(0, P, Q, Q + 0x1000000, R3, 4, 4, 4, 4, 4, None, 0, None) == SHAPE   # fixed k out of range
+    assert L.st_mttkrp_fixed(1, P, Q, Q + 0x1000000, R3, 4, 4, 4, 4, 9, None, 0, None) == WORKSPACE
+    assert L.st_mttkrp_fixed(2, P, Q, Q + 0x1000000, R3, 4, 4, 4, 4, 1, None, 0, None) == WORKSPACE
+    assert L.st_mttkrp_fixed_workspace(2, 4, 4, 8, 16) == 8 * 16 * 4
+    assert L.st_mttkrp_fixed_workspace(1, 4, 9, 8, 16) == 9 * 16 * 4
+    assert L.st_mttkrp_fixed_workspace(0, 4, 9, 8, 16) == 0
+    assert L.st_expand_band(None, P, 4, 1, 4, None) == NULL
+    assert L.st_expand_band(P, Q, 4, -1, 4, None) == SHAPE
+    assert L.st_expand_band(P, Q, 50000, 1, 4, None) == UNSUPPORTED
+    assert L.st_expand_band(P, P + 16, 4, 1, 4, None) == SHAPE                       # buffers overlap

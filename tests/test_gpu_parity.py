@@ -415,3 +415,138 @@ def test_mttkrp_full(st, oracle):
     say("  norm-wise error on the sampled rows %.3e" % err)
     assert err <= TOL
     assert np.all(np.isfinite(got))
+
+
+# ------------------------------------------- the kernel table's sparsity structures
+def _struct_support(st, structure, ni, nj, fixed):
+    """(i, j) of every packed fibre, in packed order (built here from the table's unique sets)."""
+    if structure == st.STRUCT_DIAG:
+        return [(p, p) for p in range(min(ni, nj))]
+    if structure == st.STRUCT_FIXED_I:
+        return [(fixed, j) for j in range(nj)]
+    if structure == st.STRUCT_FIXED_J:
+        return [(i, fixed) for i in range(ni)]
+    return [(i, j) for i in range(ni) for j in range(i, nj)]
+
+
+def _scatter(Bc, support, ni, nj, nl):
+    B = np.zeros((ni, nj, nl), dtype=np.float32)
+    for p, (i, j) in enumerate(support):
+        B[i, j] = Bc[p]
+    return B
+
+
+@pytest.mark.parametrize("structure,ni,nj,nl,R,fixed", [
+    (0, 9, 9, 16, 16, 0), (0, 40, 33, 64, 32, 0), (0, 300, 300, 128, 64, 0),
+    (2, 50, 7, 20, 5, 3), (2, 200, 9, 256, 48, 8), (1, 4, 77, 512, 16, 2),
+    (3, 12, 12, 24, 8, 0), (3, 40, 40, 64, 64, 0), (3, 1, 1, 1, 1, 0)])
+def test_ttm_struct(st, oracle, structure, ni, nj, nl, R, fixed):
+    say("ttm_struct s=%d ni=%d nj=%d nl=%d R=%d" % (structure, ni, nj, nl, R))
+    sup = _struct_support(st, structure, ni, nj, fixed)
+    assert st.count_struct(structure, ni, nj) == len(sup)
+    Bc = W.uniform(601, len(sup) * nl).reshape(len(sup), nl)
+    U = W.uniform(602, nl * R).reshape(nl, R)
+    full = oracle.ttm_full(_scatter(Bc, sup, ni, nj, nl), U)          # dense definition on the zero-filled B
+    ii, jj = np.array(sup).T
+    ref = full[ii, jj]
+    mask = np.ones((ni, nj), dtype=bool)
+    mask[ii, jj] = False
+    assert not full[mask].any()                                       # the output keeps the unique set of B
+    got = st.ttm_struct(structure, dev(Bc), dev(U), ni, nj).cpu().numpy()
+    assert got.shape == ref.shape
+    assert rel_err(got, ref) <= TOL
+
+
+@pytest.mark.parametrize("structure,ni,nj,nl,fixed", [
+    (0, 9, 9, 16, 0), (0, 40, 33, 7, 0), (0, 200, 200, 128, 0),
+    (1, 4, 77, 64, 2), (1, 9, 300, 5, 8), (2, 50, 7, 20, 3), (2, 300, 9, 256, 0),
+    (3, 12, 12, 24, 0), (3, 70, 70, 33, 0), (3, 1, 1, 1, 0)])
+def test_thp_struct(st, oracle, structure, ni, nj, nl, fixed):
+    say("thp_struct s=%d ni=%d nj=%d nl=%d" % (structure, ni, nj, nl))
+    sup = _struct_support(st, structure, ni, nj, fixed)
+    Bc = W.uniform(611, len(sup) * nl).reshape(len(sup), nl)
+    Cd = W.uniform(612, ni * nj * nl).reshape(ni, nj, nl)
+    full = oracle.thp_full(_scatter(Bc, sup, ni, nj, nl), Cd)
+    ii, jj = np.array(sup).T
+    ref = full[ii, jj]
+    got = st.thp_struct(structure, dev(Bc), dev(Cd), fixed).cpu().numpy()
+    assert got.shape == ref.shape
+    # one fp32 product: the correctly rounded fp64 product is the only right answer
+    assert np.array_equal(got, ref.astype(np.float32))
+    assert np.count_nonzero(full) == np.count_nonzero(ref)            # nothing outside the unique set
+
+
+@pytest.mark.parametrize("kind,ni,nk,nl,R,fi,fk", [
+    (0, 5, 7, 33, 70, 2, 6), (0, 3, 3, 512, 64, 0, 0),
+    (1, 5, 100, 64, 48, 4, 0), (1, 3, 9, 7, 300, 1, 0), (1, 2, 512, 512, 64, 0, 0),
+    (2, 77, 6, 128, 32, 0, 5), (2, 9, 4, 10, 3, 0, 1), (2, 512, 3, 512, 64, 0, 2)])
+def test_mttkrp_fixed(st, oracle, kind, ni, nk, nl, R, fi, fk):
+    say("mttkrp_fixed kind=%d ni=%d nk=%d nl=%d R=%d" % (kind, ni, nk, nl, R))
+    C = W.uniform(621, nk * R).reshape(nk, R)
+    D = W.uniform(622, nl * R).reshape(nl, R)
+    B = np.zeros((ni, nk, nl), dtype=np.float32)
+    if kind == st.MTTKRP_FIXED_IK:
+        Bc = W.uniform(623, nl)
+        B[fi, fk] = Bc
+    elif kind == st.MTTKRP_FIXED_I:
+        Bc = W.uniform(623, nk * nl).reshape(nk, nl)
+        B[fi] = Bc
+    else:
+        Bc = W.uniform(623, ni * nl).reshape(ni, nl)
+        B[:, fk] = Bc
+    full = oracle.mttkrp_full(B, C, D)                                # dense definition on the zero-filled B
+    if kind == st.MTTKRP_FIXED_K:
+        ref = full
+    else:
+        ref = full[fi]
+        assert not np.delete(full, fi, axis=0).any()                  # only row I of the output is non-zero
+    got = st.mttkrp_fixed(kind, dev(Bc), dev(C), dev(D), ni, fk).cpu().numpy()
+    assert got.shape == ref.shape
+    assert rel_err(got, ref) <= TOL
+    got2 = st.mttkrp_fixed(kind, dev(Bc), dev(C), dev(D), ni, fk).cpu().numpy()
+    assert np.array_equal(got, got2)                                  # deterministic
+
+
+@pytest.mark.parametrize("n,w,nl", [(1, 0, 1), (9, 0, 5), (20, 3, 8), (13, 40, 4), (64, 8, 64), (100, 5, 3)])
+def test_expand_band(st, oracle, n, w, nl):
+    say("expand_band n=%d w=%d nl=%d" % (n, w, nl))
+    Tc = W.uniform(631, oracle.count_band(n, w) * nl)
+    ref = oracle.dense_band(Tc, n, w, nl).astype(np.float32)
+    got = st.expand_band(dev(Tc), n, w, nl).cpu().numpy()
+    assert np.array_equal(got.view(np.uint32), ref.view(np.uint32))
+
+
+def test_table_full_sizes(st, oracle):
+    """The kernel table at the size of the band workload (512 x 512 x 512, R = 64): sampled fibres."""
+    ni = nj = nl = 512
+    R = 64
+    rng = np.random.default_rng(11)
+    U = W.uniform(642, nl * R).reshape(nl, R)
+    # TTM, upper half cube: 131,328 fibres
+    pairs = st.count_struct(st.STRUCT_UPPER, ni, nj)
+    say("table full: ttm upper half cube, %d fibres" % pairs)
+    Bc = W.uniform(641, pairs * nl).reshape(pairs, nl)
+    got = st.ttm_struct(st.STRUCT_UPPER, dev(Bc), dev(U), ni, nj).cpu().numpy()
+    pick = np.unique(np.concatenate([rng.integers(0, pairs, 500), [0, pairs - 1]]))
+    ref = oracle.ttm_full(Bc[pick][None], U)[0]                        # each fibre is independent
+    assert float(np.abs(got[pick] - ref).max() / np.abs(ref).max()) <= TOL
+    # THP, diagonal plane against a dense 512^3 operand
+    say("table full: thp diagonal plane")
+    Cd = W.uniform(643, ni * nj * nl).reshape(ni, nj, nl)
+    Bd = Bc[:ni]
+    got = st.thp_struct(st.STRUCT_DIAG, dev(Bd), dev(Cd)).cpu().numpy()
+    ref = oracle.thp_full(Bd, Cd[np.arange(ni), np.arange(ni)])
+    assert np.array_equal(got, ref.astype(np.float32))
+    # THP, upper half cube (every fibre of the dense operand above the diagonal is gathered)
+    say("table full: thp upper half cube")
+    got = st.thp_struct(st.STRUCT_UPPER, dev(Bc), dev(Cd)).cpu().numpy()
+    lst = oracle.list_sym2(ni).astype(np.int64)
+    ref = oracle.thp_full(Bc, Cd[lst[:, 0], lst[:, 1]])
+    assert np.array_equal(got, ref.astype(np.float32))
+    # band expansion of the band workload
+    say("table full: expand_band")
+    cfg = W.CONFIGS[3]
+    Tb, _ = W.ttm_inputs(cfg["band_pairs"], cfg["nl"], cfg["R"])
+    got = st.expand_band(dev(Tb), cfg["n"], cfg["w"], cfg["nl"]).cpu().numpy()
+    ref = oracle.dense_band(Tb, cfg["n"], cfg["w"], cfg["nl"]).astype(np.float32)
+    assert np.array_equal(got.view(np.uint32), ref.view(np.uint32))

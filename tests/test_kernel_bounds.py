@@ -38,6 +38,10 @@ CASES = {
     # expand: n order | n 10+kind w p0 count  (device unrank of kind 2, 3, 4 = band, 5 = sym4)
     "EXPAND": [(64, 3), (100, 2), (7, 3), (1, 2), (17, 4), (32, 4), (100, 12, 0, 17, 5000), (100, 13, 0, 17, 5000),
                (100, 14, 7, 17, 1000), (40, 15, 0, 17, 5000)],
+    # table: op (0 thp | 1 mttkrp with fixed indices | 2 band expand), structure | kind | w, ni, nj | nk, nl, R
+    "TABLE": [(0, 0, 33, 40, 20, 0), (0, 0, 7, 5, 3, 0), (0, 1, 9, 31, 64, 0), (0, 2, 31, 9, 6, 0), (0, 3, 50, 50, 12, 0),
+              (0, 3, 1, 1, 1, 0), (1, 0, 5, 7, 33, 70), (1, 1, 5, 100, 64, 48), (1, 1, 3, 9, 7, 300),
+              (1, 2, 77, 6, 128, 32), (1, 2, 9, 4, 10, 3), (2, 3, 20, 0, 8, 0), (2, 0, 9, 0, 5, 0), (2, 40, 13, 0, 4, 0)],
 }
 
 
