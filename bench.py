@@ -133,7 +133,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-next", action="store_true", help="skip the rows beyond the step (moment2, moment4, expand 4)")
+    ap.add_argument("--no-next", action="store_true", help="skip the rows beyond the step (moment2, moment4, expand 4, kernel table)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="after the timed region, run one plain 256 MiB device copy (a kernel of known "
                          "traffic for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
@@ -261,6 +261,28 @@ def main():
             ("expand_sym_order4_n64", lambda: st.expand_sym(Sc4, n5, 4, S=S4),
              dict(flops=0, bytes=4 * (pent + n5 ** 4), bound="hbm")),
         ]
+        # the kernel table's structures at the size of the band workload (512 x 512 x 512, R = 64)
+        nt, Rt = c3["n"], c3["R"]
+        up_pairs = st.count_struct(st.STRUCT_UPPER, nt, nt)
+        Bu = torch.empty((up_pairs, nt), **f32).uniform_(-1.0, 1.0)
+        Cd = torch.empty((nt, nt, nt), **f32).uniform_(-1.0, 1.0)
+        Au = torch.empty((up_pairs, Rt), **f32)
+        Hu = torch.empty((up_pairs, nt), **f32)
+        Tdense = torch.empty((nt, nt, c3["nl"]), **f32)
+        Afk = torch.empty((nt, Rt), **f32)
+        wsk = torch.empty(max(16, st.workspace_bytes("mttkrp_fixed", kind=st.MTTKRP_FIXED_K, ni=nt, nk=nt, nl=nt,
+                                                     R=Rt)), dtype=torch.uint8, device=dev)
+        extra += [
+            ("ttm_struct_upper_n512_R64", lambda: st.ttm_struct(st.STRUCT_UPPER, Bu, U, nt, nt, Ac=Au),
+             dict(flops=2 * up_pairs * nt * Rt, bytes=4 * (up_pairs * nt + nt * Rt + up_pairs * Rt), bound="mfma")),
+            ("thp_struct_upper_n512", lambda: st.thp_struct(st.STRUCT_UPPER, Bu, Cd, Ac=Hu),
+             dict(flops=up_pairs * nt, bytes=4 * 3 * up_pairs * nt, bound="hbm")),
+            ("mttkrp_fixed_k_n512_R64", lambda: st.mttkrp_fixed(st.MTTKRP_FIXED_K, Bu[:nt], B4, U, nt, 7, A=Afk,
+                                                                ws=wsk),
+             dict(flops=2 * nt * nt * Rt + nt * Rt, bytes=4 * (nt * nt + 3 * nt * Rt), bound="mfma")),
+            ("expand_band_n512_w8", lambda: st.expand_band(Tc3, c3["n"], c3["w"], c3["nl"], T=Tdense),
+             dict(flops=0, bytes=4 * (c3["band_pairs"] * c3["nl"] + nt * nt * c3["nl"]), bound="hbm")),
+        ]
         next_rows = {}
         for name, f, w in extra:
             f()
@@ -276,7 +298,8 @@ def main():
             ms = float(np.mean([a.elapsed_time(b) for a, b in evs]))
             gflops = w["flops"] / (ms * 1e-3) / 1e9
             gbs = w["bytes"] / (ms * 1e-3) / 1e9
-            frac = gbs / HBM_PEAK_GBS if w["bound"] == "hbm" else gflops / 1e3 / ALU_FP32_PEAK_TFLOPS
+            frac = (gbs / HBM_PEAK_GBS if w["bound"] == "hbm" else
+                    gflops / 1e3 / (ALU_FP32_PEAK_TFLOPS if w["bound"] == "alu" else MFMA_FP32_PEAK_TFLOPS))
             next_rows[name] = dict(ms=round(ms, 5), unique_gflops=round(gflops, 2), alg_gbs=round(gbs, 2),
                                    bound=w["bound"], frac=round(frac, 4))
 

@@ -4,9 +4,13 @@
 // a row has to stay on chip between its use in t_i = A(i,:) x and its use in
 // y += t_i A(i,:), so a workgroup of 1024 threads holds whole rows in
 // registers.  Thread `tid` owns the fixed columns 4*(tid + 1024 v) .. +3, v < 2, keeps
-// x and its partial y for those columns in registers for the whole kernel, and
-// rows are dealt to workgroups round-robin (row i -> workgroup i mod G), which
-// balances the triangular row lengths.  Per batch of RB rows: every thread
+// x and its partial y for those columns in registers for the whole kernel.
+// Rows are dealt to workgroups round-robin AND folded: a workgroup alternates
+// between a row i from the top half and its mirror image n-1-i from the bottom
+// half, so that every pair of consecutive rows holds n+1 entries -- the bytes in
+// flight per batch stay constant from the first batch to the last, instead of
+// shrinking with the triangle until the short rows are latency bound.
+// Per batch of RB rows: every thread
 // loads its (unaligned, 16-byte) pieces of the rows, a DPP wave reduction and
 // one LDS exchange give the RB dot products t_i to every thread in a fixed
 // summation order, and the same registers are reused for the rank-one update
@@ -56,6 +60,16 @@ __device__ __forceinline__ float wave_sum(float v)
     return (r0 + r1) + (r2 + r3);
 }
 
+// Row held by slot q of workgroup g: q even -> row g + G*(q/2) from the top, q odd ->
+// its mirror image from the bottom; the middle row of an odd n is dealt once, as a
+// top row.  Slots past the middle return n ("no row").
+__device__ __forceinline__ u32 row_of_slot(u32 n, u32 g, u32 G, u32 q)
+{
+    const u32 it = g + G * (q >> 1);
+    if (q & 1u) return (2u * it + 1u < n) ? n - 1u - it : n;
+    return (2u * it + 1u <= n) ? it : n;
+}
+
 // Raw (unmasked) pieces of RB rows.  FAST (n % 4 == 0, n >= 4): branch free, so
 // that all loads of a batch are in flight together -- a group of four columns
 // that starts left of the diagonal is read from up to three entries before the
@@ -64,11 +78,11 @@ __device__ __forceinline__ float wave_sum(float v)
 // not belong to the row.  Otherwise: guarded element loads.
 template <int V, bool FAST>
 __device__ __forceinline__ void load_batch(float4 (&a)[RB][V], const float *__restrict__ Ap, u32 n,
-                                           u32 row0, u32 rstride, u32 tid)
+                                           u32 g, u32 G, u32 q0, u32 tid)
 {
 #pragma unroll
     for (int r = 0; r < RB; ++r) {
-        u32 i = row0 + (u32)r * rstride;
+        u32 i = row_of_slot(n, g, G, q0 + (u32)r);
 #pragma unroll
         for (int v = 0; v < V; ++v) {
             u32 c0 = 4u * (tid + (u32)BT * v);
@@ -95,11 +109,11 @@ __device__ __forceinline__ void load_batch(float4 (&a)[RB][V], const float *__re
 }
 
 template <int V>
-__device__ __forceinline__ void mask_batch(float4 (&a)[RB][V], u32 n, u32 row0, u32 rstride, u32 tid)
+__device__ __forceinline__ void mask_batch(float4 (&a)[RB][V], u32 n, u32 g, u32 G, u32 q0, u32 tid)
 {
 #pragma unroll
     for (int r = 0; r < RB; ++r) {
-        u32 i = row0 + (u32)r * rstride;
+        u32 i = row_of_slot(n, g, G, q0 + (u32)r);
 #pragma unroll
         for (int v = 0; v < V; ++v) {
             u32 c0 = 4u * (tid + (u32)BT * v);
@@ -162,11 +176,12 @@ __global__ __launch_bounds__(BT) void batax_onepass_kernel(const float *__restri
     __shared__ float red[2][RB][BT / 64];
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6, g = blockIdx.x;
 
-    // rows g, g+G, g+2G, ...; batch b holds rows g + G*(RB*b + r)
-    const u32 nrows = (n > g) ? (n - g + G - 1) / G : 0;
-    const u32 nb = (nrows + RB - 1) / RB;
+    // batch b holds the slots RB*b .. RB*b + RB-1 of this workgroup (row_of_slot)
+    const u32 mid = (n - 1u) / 2u;                 // last row dealt from the top
+    const u32 nslots = (mid >= g) ? 2u * ((mid - g) / G + 1u) : 0u;
+    const u32 nb = (nslots + RB - 1) / RB;
     float4 a0[RB][V], a1[RB][V];
-    load_batch<V, FAST>(a0, Ap, n, g, G, tid);     // first rows go out before anything else
+    load_batch<V, FAST>(a0, Ap, n, g, G, 0u, tid); // first rows go out before anything else
 
     // x for the owned columns: branch-free (index clamped, value selected), so these
     // loads overlap the first batch instead of serialising in front of it
@@ -185,14 +200,14 @@ __global__ __launch_bounds__(BT) void batax_onepass_kernel(const float *__restri
     }
 
     for (u32 b = 0; b < nb; b += 2) {
-        load_batch<V, FAST>(a1, Ap, n, g + G * RB * (b + 1), G, tid);
+        load_batch<V, FAST>(a1, Ap, n, g, G, RB * (b + 1), tid);
         __builtin_amdgcn_sched_barrier(0);
-        mask_batch<V>(a0, n, g + G * RB * b, G, tid);
+        mask_batch<V>(a0, n, g, G, RB * b, tid);
         process_batch<V>(a0, xs, ya, red, 0, lane, wave);
         __builtin_amdgcn_sched_barrier(0);
-        load_batch<V, FAST>(a0, Ap, n, g + G * RB * (b + 2), G, tid);
+        load_batch<V, FAST>(a0, Ap, n, g, G, RB * (b + 2), tid);
         __builtin_amdgcn_sched_barrier(0);
-        mask_batch<V>(a1, n, g + G * RB * (b + 1), G, tid);
+        mask_batch<V>(a1, n, g, G, RB * (b + 1), tid);
         process_batch<V>(a1, xs, ya, red, 1, lane, wave);
         __builtin_amdgcn_sched_barrier(0);
     }
