@@ -8,14 +8,16 @@
 // which rows exist (rank/unrank of the row id is the caller's business).
 //
 // Split-K path (nl in {64,128,256,512}, R in {16,32,48,64}): workgroups of 16
-// waves, one per CU.  A wave owns a 16-row tile and one quarter of the l range
-// for all R columns: it issues every 16-byte load of its quarter rows at once,
-// before U is staged, so the HBM latency is paid once and overlaps the staging.
-// U is staged into LDS already permuted into MFMA B-operand order; per 16 values
-// of l a wave issues one ds_read_b128 of U per 16 columns and four MFMAs per
-// read (lane = (row, l-quad); the four components of a load feed four MFMAs whose
-// K slots are permuted consistently on the U side).  The four quarter sums of a
-// tile are added through LDS in a fixed order ((q0+q2)+(q1+q3)).
+// waves, one per CU, persistent over rounds of four 16-row tiles.  A wave owns
+// one tile and one quarter of the l range for all R columns; the rows of a
+// round are requested while the MFMAs of the round before run (those of the
+// first round right after U is staged).  U is staged once, in its natural
+// row-major order (the column tiles of a row tile are interleaved, see below),
+// per 16 values of l a wave issues four LDS reads of R/16 floats and 4*R/16
+// MFMAs (lane = (row, l-quad); the four components of a 16-byte load of T feed
+// four MFMAs whose K slots are permuted consistently on the U side).  The four
+// quarter sums of a tile are added through LDS in a fixed order
+// ((q0+q2)+(q1+q3)).
 //
 // General MFMA path (nl % 16 == 0, R % 16 == 0, R <= 256): persistent workgroups,
 // a work unit is a 16-row x 16-column output tile over the whole l range, U is
@@ -139,31 +141,138 @@ __global__ __launch_bounds__(TW * 64) void ttm_mfma_kernel(const float *__restri
     }
 }
 
-// Same staging with the shape known at compile time: every thread issues all of
-// its loads before the first LDS store, so the staging pays one memory latency.
-template <u32 NL, u32 RR, u32 NTHREADS>
-__device__ __forceinline__ void stage_u_static(float *lds, const float *__restrict__ U, u32 tid)
+// ---- split-K kernel --------------------------------------------------------------------
+// NS = 16-value steps of l per wave (nl = 64*NS), CT = R/16.
+//
+// Column mapping.  A lane of an MFMA B operand / D result stands for one column n = lane % 16 of a
+// 16-column tile.  Here the CT tiles of a row tile are interleaved: tile j holds the columns CT*n + j,
+// so the CT values a lane needs from one row of U, and the CT results it holds for one output row, are
+// CONSECUTIVE in memory.  U therefore stays in its natural row-major order in LDS (staged with plain
+// 16-byte copies), one LDS read of CT floats feeds CT MFMAs, and a lane stores CT consecutive columns
+// of Y at once.
+template <int CT> struct cols { float v[CT]; };
+
+template <int CT> __device__ __forceinline__ cols<CT> load_cols(const float *p)
 {
-    constexpr u32 CT = RR / 16u, ITEMS = (NL / 4u) * RR, PER = (ITEMS + NTHREADS - 1u) / NTHREADS;
-    float4 v[PER];
+    cols<CT> r;
+    if constexpr (CT == 4) {
+        const float4 t = *reinterpret_cast<const float4 *>(p);
+        r.v[0] = t.x; r.v[1] = t.y; r.v[2] = t.z; r.v[3] = t.w;
+    } else if constexpr (CT == 2) {
+        const float2 t = *reinterpret_cast<const float2 *>(p);
+        r.v[0] = t.x; r.v[1] = t.y;
+    } else {
 #pragma unroll
-    for (u32 it = 0; it < PER; ++it) {
-        const u32 e = min(tid + NTHREADS * it, ITEMS - 1u);
-        const u32 k4 = e / RR, col = e % RR;
-        const float *src = U + (size_t)(4u * k4) * RR + col;
-        v[it] = make_float4(src[0], src[RR], src[2u * RR], src[3u * RR]);
+        for (int j = 0; j < CT; ++j) r.v[j] = p[j];
     }
+    return r;
+}
+
+template <int CT> __device__ __forceinline__ void store_cols(float *p, const cols<CT> &r)
+{
+    if constexpr (CT == 4) *reinterpret_cast<float4 *>(p) = make_float4(r.v[0], r.v[1], r.v[2], r.v[3]);
+    else if constexpr (CT == 2) *reinterpret_cast<float2 *>(p) = make_float2(r.v[0], r.v[1]);
+    else {
 #pragma unroll
-    for (u32 it = 0; it < PER; ++it) {
-        const u32 e = tid + NTHREADS * it;
-        const u32 k4 = e / RR, col = e % RR;
-        const u32 s = k4 >> 2, q = k4 & 3u, ct = col >> 4, c = col & 15u;
-        if (e < ITEMS) *reinterpret_cast<float4 *>(lds + ((size_t)((s * CT + ct) * 64u + 16u * q + c)) * 4u) = v[it];
+        for (int j = 0; j < CT; ++j) p[j] = r.v[j];
     }
 }
 
-// ---- split-K kernel ---------------------------------------------------------------
-// NS = 16-value steps of l per wave (nl = 64*NS), CT = R/16.
+// U (nl x R, row-major) into LDS, same order: every thread issues all its 16-byte loads before its
+// first LDS store, so the staging pays one memory latency.
+template <u32 NL, u32 RR, u32 NTHREADS>
+__device__ __forceinline__ void stage_u_rowmajor(float *lds, const float *__restrict__ U, u32 tid)
+{
+    constexpr u32 ITEMS = NL * RR / 4u, PER = (ITEMS + NTHREADS - 1u) / NTHREADS;
+    float4 v[PER];
+#pragma unroll
+    for (u32 it = 0; it < PER; ++it)
+        v[it] = reinterpret_cast<const float4 *>(U)[min(tid + NTHREADS * it, ITEMS - 1u)];
+#pragma unroll
+    for (u32 it = 0; it < PER; ++it) {
+        const u32 e = tid + NTHREADS * it;
+        if (e < ITEMS) reinterpret_cast<float4 *>(lds)[e] = v[it];
+    }
+}
+
+// The 16-byte loads of a wave's quarter rows of row tile rt (A-operand layout: lane = (row, l-quad)).
+template <int NS>
+__device__ __forceinline__ const float4 *ttm_row_ptr(const float *__restrict__ Tc, u32 rt, u32 rtiles, u32 rows,
+                                                     u32 lrow, u32 lq, u32 kq)
+{
+    const u32 row = min((rt < rtiles ? rt : 0u) * 16u + lrow, rows - 1u);    // clamp: tail rows are discarded
+    return reinterpret_cast<const float4 *>(Tc + (size_t)row * (64u * NS) + kq * (16u * NS)) + lq;
+}
+
+// One round of a wave: the MFMAs of its quarter of a row tile, the addition of the four quarter sums
+// through LDS in the order (q0+q2)+(q1+q3), and the store of one output row in four (row 4*(lane/16) + kq:
+// every wave of the slot stores, so all waves issue the same memory operations per round).
+//   FULL: every tile of the round is a full tile and a next round exists: nothing is conditional, and
+//         the rows of the next round are requested one load per MFMA step (a wave whose request waits
+//         for room in the memory pipeline then holds up only its own MFMAs).  The wait counters the
+//         compiler derives for the prefetched rows are exact here; a conditional store between the
+//         request of a row and its use would make the wave wait for the store as well.
+//   else: guarded tail rounds; `prefetch` (workgroup-uniform) says whether another round follows.
+template <int NS, int CT, bool FULL>
+__device__ __forceinline__ void ttm_round(const float4 (&a)[NS], float4 (&an)[NS], const float4 *apn, bool prefetch,
+                                          const float *__restrict__ ub, f32x4 *mine, float *__restrict__ Yc, u32 rt,
+                                          u32 rtiles, u32 rows, u32 kq, u32 lrow, u32 lq)
+{
+    constexpr u32 R = 16u * CT;
+    const bool live = FULL ? true : rt < rtiles;
+    if (!FULL && prefetch) {
+#pragma unroll
+        for (int s = 0; s < NS; ++s) an[s] = apn[s * 4];
+    }
+    f32x4 acc[CT];
+#pragma unroll
+    for (int c = 0; c < CT; ++c) acc[c] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    if (live) {   // wave-uniform
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+            if (FULL) {
+                an[s] = apn[s * 4];
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            const float av[4] = {a[s].x, a[s].y, a[s].z, a[s].w};
+            cols<CT> b[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) b[t] = load_cols<CT>(ub + (size_t)(16 * s + t) * R);
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int c = 0; c < CT; ++c)
+                    acc[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[t], b[t].v[c], acc[c], 0, 0, 0);
+        }
+    }
+    if (kq >= 2u) {
+#pragma unroll
+        for (int c = 0; c < CT; ++c) mine[((kq - 2u) * CT + c) * 64u] = acc[c];
+    }
+    __syncthreads();
+    if (kq < 2u) {       // q0 += q2, q1 += q3; each wave overwrites only what it has just read
+#pragma unroll
+        for (int c = 0; c < CT; ++c) {
+            acc[c] += mine[(kq * CT + c) * 64u];
+            mine[(kq * CT + c) * 64u] = acc[c];
+        }
+    }
+    __syncthreads();
+    {
+        // D layout: a lane holds, for column tile c, the rows 4*(lane/16) + v of column CT*(lane%16) + c
+        const float *sums = reinterpret_cast<const float *>(mine);
+        const u32 row = rt * 16u + 4u * lq + kq;
+        cols<CT> y;
+#pragma unroll
+        for (int c = 0; c < CT; ++c) y.v[c] = sums[c * 256 + kq] + sums[(CT + c) * 256 + kq];
+        if (FULL || (live && row < rows)) store_cols<CT>(Yc + (size_t)row * R + CT * lrow, y);
+    }
+    __syncthreads();     // the exchange area is free for the next round
+}
+
+// Workgroups of 16 waves, one per CU, persistent over rounds of four row tiles.  U is staged once and
+// stays in LDS (nl*R*4 bytes) with the exchange area (4 slots * 2 * CT KB) behind it: 160 KB at
+// nl = 512, R = 64.
 template <int NS, int CT>
 __global__ __launch_bounds__(TW * 64) void ttm_splitk_kernel(const float *__restrict__ Tc,
                                                            const float *__restrict__ U, float *__restrict__ Yc,
@@ -174,76 +283,49 @@ __global__ __launch_bounds__(TW * 64) void ttm_splitk_kernel(const float *__rest
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     const u32 slot = wave >> 2, kq = wave & 3u;            // row-tile slot, quarter of the l range
     const u32 rtiles = (rows + 15u) / 16u;
-    const u32 nrounds = (rtiles + gridDim.x * 4u - 1u) / (gridDim.x * 4u);
+    const u32 stride = gridDim.x * 4u;
+    const u32 nrounds = (rtiles + stride - 1u) / stride;
+    // leading rounds in which the tiles of all four slots of this workgroup are full tiles
+    const u32 last_slot0 = blockIdx.x + gridDim.x * 3u, full_tiles = rows / 16u;
+    u32 nfull = full_tiles > last_slot0 ? (full_tiles - last_slot0 + stride - 1u) / stride : 0u;
+    if (nfull == nrounds && nfull > 0u) --nfull;           // the last round has nothing to prefetch
     const u32 lrow = lane & 15u, lq = lane >> 4;
-    f32x4 *xch = reinterpret_cast<f32x4 *>(lds);           // exchange area, aliases the staged U
+    f32x4 *mine = reinterpret_cast<f32x4 *>(lds + nl * R) + (size_t)(slot * 2u) * CT * 64u + lane;
+    // B operand of MFMA t of step s: lane (k = lane/16, n = lane%16) takes U(l, CT*n + c), l = 16 s + 4 k + t
+    const float *ub = lds + (size_t)(kq * (16u * NS) + 4u * lq) * R + CT * lrow;
+    const u32 rt0 = blockIdx.x + gridDim.x * slot;
 
-    for (u32 round = 0; round < nrounds; ++round) {
-        const u32 rt = blockIdx.x + gridDim.x * (slot + 4u * round);
-        const bool live = rt < rtiles;
-        // all loads of this wave's quarter rows go out first
-        float4 a[NS];
-        {
-            const u32 row = min((live ? rt : 0u) * 16u + lrow, rows - 1u);   // clamp: tail rows are discarded
-            const float4 *ap = reinterpret_cast<const float4 *>(Tc + (size_t)row * nl + kq * (16u * NS)) + lq;
+    // U first, then the rows of the first round: a wave cannot pass the request of its rows before the
+    // memory pipeline has room for them (with cold rows that takes microseconds for the last waves), so
+    // nothing that all waves have to finish is put behind those requests.  The waves whose rows arrive
+    // first start their MFMAs while the others still wait.
+    stage_u_rowmajor<nl, R, TW * 64u>(lds, U, tid);
+    __syncthreads();
+    float4 a0[NS], a1[NS];
+    {
+        const float4 *ap = ttm_row_ptr<NS>(Tc, rt0, rtiles, rows, lrow, lq, kq);
 #pragma unroll
-            for (int s = 0; s < NS; ++s) a[s] = ap[s * 4];
-        }
-        if (round > 0) __syncthreads();                    // exchange area of the previous round is free
-        stage_u_static<nl, R, TW * 64u>(lds, U, tid);
-        __syncthreads();
-
-        f32x4 acc[CT];
-#pragma unroll
-        for (int c = 0; c < CT; ++c) acc[c] = (f32x4){0.f, 0.f, 0.f, 0.f};
-        const f32x4 *bp = reinterpret_cast<const f32x4 *>(lds) + (size_t)(kq * NS) * CT * 64u + lane;
-        if (live) {   // wave-uniform: idle slots leave the matrix cores to the live ones
-#pragma unroll
-        for (int s = 0; s < NS; ++s) {
-            f32x4 b[CT];
-#pragma unroll
-            for (int c = 0; c < CT; ++c) b[c] = bp[(s * CT + c) * 64];
-            const float av[4] = {a[s].x, a[s].y, a[s].z, a[s].w};
-#pragma unroll
-            for (int t = 0; t < 4; ++t)
-#pragma unroll
-                for (int c = 0; c < CT; ++c)
-                    acc[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[t], b[c][t], acc[c], 0, 0, 0);
-        }
-        }
-        __syncthreads();                                   // every wave is done reading U
-
-        // quarters 2,3 -> quarters 0,1 ; then quarter 1 -> quarter 0
-        f32x4 *mine = xch + (size_t)(slot * 2u) * CT * 64u + lane;
-        if (kq >= 2u) {
-#pragma unroll
-            for (int c = 0; c < CT; ++c) mine[((kq - 2u) * CT + c) * 64u] = acc[c];
-        }
-        __syncthreads();
-        if (kq < 2u) {
-#pragma unroll
-            for (int c = 0; c < CT; ++c) {
-                const f32x4 o = mine[(kq * CT + c) * 64u];
-                acc[c] += o;
-            }
-        }
-        __syncthreads();
-        if (kq == 1u) {
-#pragma unroll
-            for (int c = 0; c < CT; ++c) mine[c * 64u] = acc[c];
-        }
-        __syncthreads();
-        if (kq == 0u && live) {
-#pragma unroll
-            for (int c = 0; c < CT; ++c) {
-                const f32x4 o = mine[c * 64u];
-                // D layout: lane holds column lane%16 of rows 4*(lane/16) + v
-#pragma unroll
-                for (u32 v = 0; v < 4; ++v) {
-                    const u32 row = rt * 16u + 4u * lq + v;
-                    if (row < rows) Yc[(size_t)row * R + c * 16u + lrow] = acc[c][v] + o[v];
-                }
-            }
+        for (int s = 0; s < NS; ++s) a0[s] = ap[s * 4];
+    }
+    u32 round = 0;
+    for (; round + 2u <= nfull; round += 2u) {
+        const u32 rt = rt0 + stride * round;
+        ttm_round<NS, CT, true>(a0, a1, ttm_row_ptr<NS>(Tc, rt + stride, rtiles, rows, lrow, lq, kq), true, ub, mine,
+                                Yc, rt, rtiles, rows, kq, lrow, lq);
+        __builtin_amdgcn_sched_barrier(0);
+        ttm_round<NS, CT, true>(a1, a0, ttm_row_ptr<NS>(Tc, rt + 2u * stride, rtiles, rows, lrow, lq, kq), true, ub,
+                                mine, Yc, rt + stride, rtiles, rows, kq, lrow, lq);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    for (; round < nrounds; round += 2u) {
+        const u32 rt = rt0 + stride * round;
+        ttm_round<NS, CT, false>(a0, a1, ttm_row_ptr<NS>(Tc, rt + stride, rtiles, rows, lrow, lq, kq),
+                                 round + 1u < nrounds, ub, mine, Yc, rt, rtiles, rows, kq, lrow, lq);
+        __builtin_amdgcn_sched_barrier(0);
+        if (round + 1u < nrounds) {                        // workgroup-uniform
+            ttm_round<NS, CT, false>(a1, a0, ttm_row_ptr<NS>(Tc, rt + 2u * stride, rtiles, rows, lrow, lq, kq),
+                                     round + 2u < nrounds, ub, mine, Yc, rt + stride, rtiles, rows, kq, lrow, lq);
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
 }
@@ -257,7 +339,7 @@ static bool launch_splitk_ct(int CT, u32 grid, size_t lds_bytes, hipStream_t s, 
         static bool attr = false;                                                                        \
         if (!attr) {                                                                                     \
             if (hipFuncSetAttribute(reinterpret_cast<const void *>(ttm_splitk_kernel<NS, C>),            \
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024) != hipSuccess) \
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) \
                 return false;                                                                            \
             attr = true;                                                                                 \
         }                                                                                                \
@@ -291,18 +373,26 @@ __global__ __launch_bounds__(256) void ttm_plain_kernel(const float *__restrict_
 
 size_t ttm_workspace(int, int, int, int) { return 0; }
 
+// whether a workgroup of the current device may hold 160 KB of LDS
+static bool lds_budget_160k()
+{
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return false;
+    if (hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess) return false;
+    return v >= 160 * 1024;
+}
+
 st_status launch_ttm(const float *Tc, const float *U, float *Yc, int64_t rows, int nl, int R, void *,
                      hipStream_t s)
 {
     if (rows == 0) return ST_OK;
     const bool splitk = (nl == 64 || nl == 128 || nl == 256 || nl == 512) && (R % 16 == 0) && R <= 64 &&
-                        rows < ((int64_t)1 << 31);
+                        rows < ((int64_t)1 << 31) && lds_budget_160k();
     if (splitk) {
         const u32 rtiles = (u32)((rows + 15) / 16);
         u32 grid = (u32)num_cus();
         if (grid > rtiles) grid = rtiles;
-        size_t lds_bytes = (size_t)nl * R * 4u;
-        if (lds_bytes < 32u * 1024u) lds_bytes = 32u * 1024u;     // room for the exchange area
+        const size_t lds_bytes = (size_t)nl * R * 4u + (size_t)8u * (R / 16u) * 1024u;   // U + exchange area
         bool ok = false;
         switch (nl / 64) {
         case 1: ok = launch_splitk_ct<1>(R / 16, grid, lds_bytes, s, Tc, U, Yc, (u32)rows); break;

@@ -53,11 +53,16 @@ static inline uint32_t max(uint32_t a, uint32_t b) { return a > b ? a : b; }
 typedef void *hipStream_t;
 typedef int hipError_t;
 enum { hipSuccess = 0 };
-enum { hipFuncAttributeMaxDynamicSharedMemorySize = 8, hipDeviceAttributeMultiprocessorCount = 63 };
+enum { hipFuncAttributeMaxDynamicSharedMemorySize = 8, hipDeviceAttributeMultiprocessorCount = 63,
+       hipDeviceAttributeMaxSharedMemoryPerBlock = 74 };
 static inline hipError_t hipGetLastError() { return hipSuccess; }
 static inline hipError_t hipFuncSetAttribute(const void *, int, int) { return hipSuccess; }
 static inline hipError_t hipGetDevice(int *d) { *d = 0; return hipSuccess; }
-static inline hipError_t hipDeviceGetAttribute(int *v, int, int) { *v = 256; return hipSuccess; }
+static inline hipError_t hipDeviceGetAttribute(int *v, int attr, int)
+{
+    *v = attr == hipDeviceAttributeMaxSharedMemoryPerBlock ? 160 * 1024 : 256;
+    return hipSuccess;
+}
 
 namespace st { extern float lds[]; }   // dynamic LDS (declared `extern __shared__` in the kernels)
 

@@ -162,7 +162,8 @@ def test_batax_full(st, oracle):
 @pytest.mark.parametrize("n,w,nl,R", [(1, 0, 1, 1), (7, 2, 5, 4), (9, 0, 16, 16), (40, 3, 32, 16),
                                       (64, 8, 48, 32), (33, 40, 64, 64), (50, 4, 80, 48),
                                       (30, 2, 1040, 256), (20, 3, 16, 272), (600, 14, 128, 48),
-                                      (100, 5, 256, 16), (70, 1, 512, 32)])
+                                      (100, 5, 256, 16), (70, 1, 512, 32), (700, 20, 64, 16),
+                                      (1100, 9, 512, 64)])
 def test_ttm_small(st, oracle, n, w, nl, R):
     say("ttm n=%d w=%d nl=%d R=%d" % (n, w, nl, R))
     nb = oracle.count_band(n, w)

@@ -25,8 +25,9 @@ CASES = {
     # batax: n  (one-pass kernel to 8192, two-pass beyond; n % 4 != 0 takes the guarded loads)
     "BATAX": [(1,), (5,), (64,), (100,), (1000,), (1023,), (4096,), (8192,), (9001,)],
     # ttm: rows nl R  (split-K shapes, the general MFMA path, the plain path)
+    # (more than 16384 rows: the streaming split-K kernel)
     "TTM": [(8632, 512, 64), (16590, 128, 48), (1090, 256, 16), (208, 512, 32), (1, 64, 16), (777, 48, 32),
-            (50, 7, 5), (33, 16, 256)],
+            (50, 7, 5), (33, 16, 256), (16385, 512, 64), (40001, 64, 16), (33000, 256, 48)],
     # moment3: N n accumulate  (n = 64 is the MFMA path, others the plain path)
     "MOMENT3": [(5000, 64, 0), (4097, 64, 1), (63, 64, 0), (100000, 64, 0), (1000, 20, 0), (3, 5, 1),
                 (700, 70, 0)],
