@@ -46,6 +46,9 @@
 // ds_read_b128 of the tile feeds four MFMAs whose K slots are permuted
 // consistently on the B side.
 //
+// Small tensors (n <= 96, R <= 32) skip all of this: one launch, one workgroup per
+// output row, on the vector ALUs (mttkrp_rows_kernel, near the end of this file).
+//
 // Algorithmic traffic: 4 bytes per stored entry (read by two or three items) + B + M.
 #include "st_common.h"
 #include "st_index.h"
@@ -654,6 +657,113 @@ static inline size_t partG_floats(const MttkrpPlan &p) { return (size_t)p.nitems
 static inline size_t partPQ_floats(const MttkrpPlan &p) { return (size_t)p.npairs * p.CHB * 32u * p.Rpad; }
 static inline size_t partXP_floats(const MttkrpPlan &p) { return (size_t)p.npairs * p.CHB * 16u * p.Rpad; }
 
+
+// ---- small tensors: one workgroup per output row, one launch ------------------------------------
+// When the whole packed tensor is a few hundred KB (n <= 96) the two-kernel item scheme above is all
+// launch and pipeline start-up.  Here (R <= 32) a workgroup owns output row i and evaluates
+//     M(i,r) = sum_{j<=k} w(j,k) T(sort(i,j,k)) B(j,r) B(k,r),   w = 1 for j = k, 2 otherwise,
+// on the vector ALUs.  The workgroup first gathers the slice T(i, j<=k) into LDS in sym2 order, weights
+// applied (closed-form unrank of the pair, rank3 of the sorted triple; all loads of a thread in flight
+// together, so the memory latency is paid once), and copies B to LDS (rows padded to RC+4 floats:
+// conflict-free 16-byte reads of different rows).  A wave then takes the rows j = wave, wave+16, ... and
+// its lanes the columns k = j + lane; every lane keeps RC accumulators, which are added over the lanes
+// with DPP and over the sixteen waves through LDS in a fixed order.  Each entry is read by the (up to
+// three) rows it belongs to; at this size those re-reads come from the cache.
+template <int CTRL> __device__ __forceinline__ float mk_dpp(float v)
+{
+    return __builtin_bit_cast(float,
+                              __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float mk_wave_sum(float v)     // same bits in every lane
+{
+    v += mk_dpp<0xB1>(v);     // quad_perm [1,0,3,2]
+    v += mk_dpp<0x4E>(v);     // quad_perm [2,3,0,1]
+    v += mk_dpp<0x141>(v);    // row_half_mirror
+    v += mk_dpp<0x140>(v);    // row_mirror
+    const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 0));
+    const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 16));
+    const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 32));
+    const float r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 48));
+    return (r0 + r1) + (r2 + r3);
+}
+
+constexpr u32 ROWS_NMAX = 96;      // largest n of the row kernel
+constexpr u32 ROWS_NT = 1024;      // threads per workgroup of the row kernel
+constexpr u32 ROWS_NW = ROWS_NT / 64;
+template <int RC>                  // accumulators per lane: R rounded up to 16 or 32
+__global__ __launch_bounds__(ROWS_NT) void mttkrp_rows_kernel(const float *__restrict__ Tc, const float *__restrict__ B,
+                                                         float *__restrict__ M, u32 n, u32 R)
+{
+    constexpr u32 LS = RC + 4;                      // LDS row stride of B
+    __shared__ __attribute__((aligned(16))) float Bs[ROWS_NMAX * LS];
+    __shared__ float Ts[ROWS_NMAX * (ROWS_NMAX + 1) / 2];
+    __shared__ float red[ROWS_NW][RC];
+    const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6, i = blockIdx.x;
+    // the slice T(i,:,:) of the symmetric tensor, upper half (j <= k) with its weight, gathered from the
+    // packed entries: five independent loads per thread in flight at a time
+    const u32 np = count_sym2<u32>(n);
+    for (u32 p0 = tid; p0 < np; p0 += 5u * ROWS_NT) {
+        float tv[5];
+        u32 jj[5], kk[5];
+#pragma unroll
+        for (int q = 0; q < 5; ++q) {
+            const u32 pp = min(p0 + ROWS_NT * q, np - 1u);
+            unrank_sym2<u32>(n, pp, jj[q], kk[q]);
+            u32 a = i, b = jj[q], c = kk[q];
+            sort3u(a, b, c);
+            tv[q] = Tc[rank_sym3<u32>(n, a, b, c)];
+        }
+#pragma unroll
+        for (int q = 0; q < 5; ++q) {
+            const u32 pp = p0 + ROWS_NT * q;
+            if (pp < np) Ts[pp] = jj[q] == kk[q] ? tv[q] : 2.f * tv[q];
+        }
+    }
+    for (u32 e = tid; e < n * RC; e += ROWS_NT) {
+        const u32 row = e / RC, r = e - row * RC;
+        Bs[row * LS + r] = r < R ? B[(size_t)row * R + r] : 0.f;
+    }
+    __syncthreads();
+    float acc[RC];
+#pragma unroll
+    for (int r = 0; r < RC; ++r) acc[r] = 0.f;
+    for (u32 j = wave; j < n; j += ROWS_NW) {
+        const float *bj = &Bs[j * LS];                          // wave-uniform: broadcast reads
+        const float *trow = &Ts[rank_sym2<u32>(n, j, j)];      // weighted entries (i; j, k >= j), contiguous in k
+        for (u32 k0 = j; k0 < n; k0 += 64u) {
+            const u32 k = k0 + lane;
+            const bool in = k < n;
+            const float t = in ? trow[k - j] : 0.f;
+            const float *bk = &Bs[(in ? k : j) * LS];
+#pragma unroll
+            for (int q = 0; q < RC / 4; ++q) {
+                const float4 v = *reinterpret_cast<const float4 *>(bk + 4 * q);
+                const float4 u = *reinterpret_cast<const float4 *>(bj + 4 * q);
+                acc[4 * q] += t * u.x * v.x;
+                acc[4 * q + 1] += t * u.y * v.y;
+                acc[4 * q + 2] += t * u.z * v.z;
+                acc[4 * q + 3] += t * u.w * v.w;
+            }
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < RC; ++r) {
+        const float v = mk_wave_sum(acc[r]);
+        if (lane == 0) red[wave][r] = v;
+    }
+    __syncthreads();
+    if (tid < R) {       // fixed pairwise tree over the waves
+        float v[ROWS_NW];
+#pragma unroll
+        for (u32 w = 0; w < ROWS_NW; ++w) v[w] = red[w][tid];
+#pragma unroll
+        for (u32 h = ROWS_NW / 2; h > 0; h >>= 1)
+#pragma unroll
+            for (u32 w = 0; w < h; ++w) v[w] += v[w + h];
+        M[(size_t)i * R + tid] = v[0];
+    }
+}
+
 size_t mttkrp_workspace(int n, int R)
 {
     MttkrpPlan p = plan(n, R);
@@ -662,6 +772,11 @@ size_t mttkrp_workspace(int n, int R)
 
 st_status launch_mttkrp(const float *Tc, const float *B, float *M, int n, int R, void *ws, hipStream_t s)
 {
+    if ((u32)n <= ROWS_NMAX && R <= 32) {
+        if (R <= 16) hipLaunchKernelGGL(mttkrp_rows_kernel<16>, dim3((u32)n), dim3(ROWS_NT), 0, s, Tc, B, M, (u32)n, (u32)R);
+        else hipLaunchKernelGGL(mttkrp_rows_kernel<32>, dim3((u32)n), dim3(ROWS_NT), 0, s, Tc, B, M, (u32)n, (u32)R);
+        return launch_status();
+    }
     MttkrpPlan p = plan(n, R);
     u32 gy = (p.RT + 3u) / 4u;
     uint64_t items = p.all_pairs ? (uint64_t)p.nitemsG : 2u * (uint64_t)p.npairs * p.CHB;
