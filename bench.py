@@ -139,7 +139,7 @@ def main():
                          "traffic for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build runs on one GPU only (--gpus 1); nothing here uses a second GPU")
+        sys.exit("bench.py: the library runs on one GPU only (--gpus 1); nothing here uses a second GPU")
 
     import torch
     if not torch.cuda.is_available():
