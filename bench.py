@@ -283,6 +283,21 @@ def main():
             ("expand_band_n512_w8", lambda: st.expand_band(Tc3, c3["n"], c3["w"], c3["nl"], T=Tdense),
              dict(flops=0, bytes=4 * (c3["band_pairs"] * c3["nl"] + nt * nt * c3["nl"]), bound="hbm")),
         ]
+        # kernels generated from a textual descriptor of the same structures (compiled at first use, which the
+        # untimed first call below absorbs)
+        dsym = st.Descriptor("T(i,j,k): (0<=i<n)*(i<=j<n)*(j<=k<n)", (n5, n5, n5), "sort", n=n5)
+        dband = st.Descriptor("B(i,j,l): (0<=i<n)*(i-w<=j<=i+w)*(0<=l<m)", (nt, nt, c3["nl"]), n=nt, w=c3["w"],
+                              m=c3["nl"])
+        Hb = torch.empty(c3["band_pairs"] * c3["nl"], **f32)
+        Tc3f = Tc3.reshape(-1)
+        extra += [
+            ("desc_expand_sym3_n64", lambda: dsym.expand(Sc, T=S),
+             dict(flops=0, bytes=4 * (tet(n5) + n5 ** 3), bound="hbm")),
+            ("desc_expand_band_n512_w8", lambda: dband.expand(Tc3f, T=Tdense),
+             dict(flops=0, bytes=4 * (c3["band_pairs"] * c3["nl"] + nt * nt * c3["nl"]), bound="hbm")),
+            ("desc_thp_band_n512_w8", lambda: dband.thp(Tc3f, Cd, Ac=Hb),
+             dict(flops=c3["band_pairs"] * c3["nl"], bytes=4 * 3 * c3["band_pairs"] * c3["nl"], bound="hbm")),
+        ]
         next_rows = {}
         for name, f, w in extra:
             f()

@@ -230,6 +230,63 @@ st_status st_mttkrp_fixed(int kind, const float *Bc, const float *C, const float
  * Tc is [st_count_band(n,w)][nl], T is n x n x nl, overwritten. */
 st_status st_expand_band(const float *Tc, float *T, int n, int w, int nl, void *stream);
 
+/* ---- descriptor-driven structures -------------------------------------------
+ *
+ * The paper describes a structure by a unique set T_U (a product of
+ * comparisons over the index variables) and a redundancy map T_R, and derives
+ * loop nests from them: variables in the order written, each from the maximum
+ * of its lower bounds to the minimum of its upper bounds (code generation
+ * section).  These entry points do that at run time for a descriptor given as
+ * text, and run kernels generated and compiled (hiprtc) for that descriptor.
+ *
+ *   unique_set   "T(i,j,k): (0<=i<n)*(i<=j<n)*(j<=k<n)"
+ *                NAME(variables): factors joined by '*'; a factor is a chain of
+ *                comparisons (<=, <, =, >=, >) of affine expressions over the
+ *                variables, the named parameters and integers.  Every
+ *                comparison bounds the LAST variable it mentions, which must
+ *                have coefficient 1 or -1 there (ST_ERR_UNSUPPORTED otherwise).
+ *   redundancy   NULL / "" (none: a sparsity structure, zero elsewhere), "sort"
+ *                (all permutations of a stored tuple hold its value; equal
+ *                sizes), or terms "(condition factors) -> (e0,e1,..)" joined by
+ *                ';': a dense index meeting the condition takes the value
+ *                stored at the unique index (e0,e1,..), e.g. "(0<=j<i<n) -> (j,i)".
+ *   dims[v]      dense extent of variable v (0 <= x_v < dims[v] always holds);
+ *                param_names/values bind the other names of the text.
+ *
+ * Packed layout: visiting order of the derived nest, last variable fastest.
+ * The host object is created without a GPU; the device kernels need the
+ * table (st_desc_table_bytes / st_desc_table: HOST buffer to be copied to the
+ * device by the caller, 16-byte aligned there) and compile on first use.
+ * On a parse error st_desc_create still returns an object whose
+ * st_desc_error() says what was wrong; destroy it like any other.
+ */
+typedef struct st_desc st_desc;
+st_status st_desc_create(const char *unique_set, const char *redundancy, const int64_t *dims, int ndims,
+                         const char *const *param_names, const int64_t *param_values, int nparams,
+                         st_desc **out);
+void st_desc_destroy(st_desc *desc);
+const char *st_desc_error(const st_desc *desc);
+int64_t st_desc_count(const st_desc *desc);         /* entries of the unique set                     */
+int64_t st_desc_runs(const st_desc *desc);          /* non-empty innermost runs                      */
+const char *st_desc_nest(const st_desc *desc);      /* the derived loop nest, as text                */
+const char *st_desc_source(const st_desc *desc);    /* the generated HIP source                      */
+size_t st_desc_table_bytes(const st_desc *desc);
+st_status st_desc_table(const st_desc *desc, void *host_out);
+st_status st_desc_compile(st_desc *desc);           /* compile the source for gfx950 (no GPU needed) */
+
+/* Generated kernels; `table` is the DEVICE copy of st_desc_table.
+ * st_desc_list: out[p][v] = value of variable v at packed position p (int32,
+ *   st_desc_count x order).
+ * st_desc_thp: Ac(p) = Bc(p) * C(x(p)) over the unique set, C dense (the
+ *   kernel table's THP for any structure).
+ * st_desc_expand: T(x) = Tc(rank(x)) on the unique set, the value of the
+ *   unique index given by the redundancy map elsewhere, 0 where neither
+ *   applies (Property 5). */
+st_status st_desc_list(st_desc *desc, const void *table, int32_t *out, void *stream);
+st_status st_desc_thp(st_desc *desc, const void *table, const float *Bc, const float *C, float *Ac,
+                      void *stream);
+st_status st_desc_expand(st_desc *desc, const void *table, const float *Tc, float *T, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

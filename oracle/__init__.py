@@ -288,3 +288,40 @@ def expand_sym(Sc, n, order):
     rc = lib().so_expand_sym(pS, n, order, S.ctypes.data)
     assert rc == 0
     return S
+
+
+# ---- structures given as predicates: brute force over the whole index box ----------------
+# (test infrastructure for the descriptor-driven kernels: nothing here parses a descriptor;
+# a test states the unique set and the redundancy map as plain Python functions)
+def struct_enumerate(dims, in_unique):
+    """Index tuples of the unique set in packed order: every tuple of the box, visited as nested
+    loops in the order the variables are written with the last one fastest (the visiting order of
+    the paper's generated nests, code generation section), kept when it satisfies the unique set."""
+    import itertools
+    return np.array([x for x in itertools.product(*[range(int(n)) for n in dims]) if in_unique(*x)],
+                    dtype=np.int32).reshape(-1, len(dims))
+
+
+def struct_expand(Tc, dims, in_unique, unique_of=None):
+    """Property 5, T(x) = T_C(x) + T_R(x,x') * T_C(x'): the stored value on the unique set, the
+    value stored at the unique index x' = unique_of(x) where the redundancy map gives one, zero
+    elsewhere.  Positions come from a dictionary built by the enumeration above."""
+    import itertools
+    Tc = np.asarray(Tc)
+    pos = {tuple(int(v) for v in x): p for p, x in enumerate(struct_enumerate(dims, in_unique))}
+    T = np.zeros(tuple(int(n) for n in dims), dtype=Tc.dtype)
+    for x in itertools.product(*[range(int(n)) for n in dims]):
+        if x in pos:
+            T[x] = Tc[pos[x]]
+        elif unique_of is not None:
+            y = unique_of(*x)
+            if y is not None and tuple(y) in pos:
+                T[x] = Tc[pos[tuple(y)]]
+    return T
+
+
+def struct_thp(Bc, C, dims, in_unique):
+    """THP of the kernel table, A(x) = B(x) * C(x), evaluated on the unique set of B only (fp64)."""
+    idx = struct_enumerate(dims, in_unique).astype(np.int64)
+    Cv = np.asarray(C, dtype=np.float64)[tuple(idx[:, v] for v in range(idx.shape[1]))]
+    return np.asarray(Bc, dtype=np.float64) * Cv

@@ -7,6 +7,7 @@ kernels.  There is no CPU fallback: if the library cannot be loaded, importing
 the binding's functions raises.
 """
 from .binding import (  # noqa: F401
+    Descriptor,
     MTTKRP_FIXED_I,
     MTTKRP_FIXED_IK,
     MTTKRP_FIXED_K,

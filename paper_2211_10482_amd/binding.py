@@ -61,6 +61,19 @@ SIGNATURES = {
     "st_thp_struct": (_I32, [_I32, _P, _P, _P, _I32, _I32, _I32, _I32, _P]),
     "st_mttkrp_fixed": (_I32, [_I32, _P, _P, _P, _P, _I32, _I32, _I32, _I32, _I32, _P, _SZ, _P]),
     "st_expand_band": (_I32, [_P, _P, _I32, _I32, _I32, _P]),
+    "st_desc_create": (_I32, [C.c_char_p, C.c_char_p, _P, _I32, _P, _P, _I32, _P]),
+    "st_desc_destroy": (None, [_P]),
+    "st_desc_error": (C.c_char_p, [_P]),
+    "st_desc_count": (_I64, [_P]),
+    "st_desc_runs": (_I64, [_P]),
+    "st_desc_nest": (C.c_char_p, [_P]),
+    "st_desc_source": (C.c_char_p, [_P]),
+    "st_desc_table_bytes": (_SZ, [_P]),
+    "st_desc_table": (_I32, [_P, _P]),
+    "st_desc_compile": (_I32, [_P]),
+    "st_desc_list": (_I32, [_P, _P, _P, _P]),
+    "st_desc_thp": (_I32, [_P, _P, _P, _P, _P, _P]),
+    "st_desc_expand": (_I32, [_P, _P, _P, _P, _P]),
 }
 
 # structures of the kernel table (values of include/structtensor.h)
@@ -333,3 +346,85 @@ def expand_band(Tc, n, w, nl, T=None):
         T = torch.empty((n, n, nl), dtype=torch.float32, device=Tc.device)
     _check(lib().st_expand_band(_dev_f32(Tc, "Tc"), _dev_f32(T, "T"), n, w, nl, _stream()), "st_expand_band")
     return T
+
+
+# ---- descriptor-driven structures -------------------------------------------------------
+class Descriptor:
+    """Host object of ``st_desc_create`` plus (lazily) the device copy of its table."""
+
+    def __init__(self, unique_set, dims, redundancy=None, **params):
+        self._h = C.c_void_p()
+        dims = [int(v) for v in dims]
+        da = (C.c_int64 * len(dims))(*dims)
+        names = sorted(params)
+        na = (C.c_char_p * max(len(names), 1))(*[k.encode() for k in names])
+        va = (C.c_int64 * max(len(names), 1))(*[int(params[k]) for k in names])
+        rc = lib().st_desc_create(unique_set.encode(), redundancy.encode() if redundancy else None, da, len(dims),
+                                  na, va, len(names), C.byref(self._h))
+        if rc != 0:
+            msg = lib().st_desc_error(self._h).decode() if self._h else ""
+            self.close()
+            raise StructTensorError(rc, "st_desc_create (%s)" % msg)
+        self.dims = tuple(dims)
+        self._table_dev = None
+
+    def close(self):
+        if getattr(self, "_h", None):
+            lib().st_desc_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @property
+    def count(self): return int(lib().st_desc_count(self._h))
+    @property
+    def runs(self): return int(lib().st_desc_runs(self._h))
+    @property
+    def nest(self): return lib().st_desc_nest(self._h).decode()
+    @property
+    def source(self): return lib().st_desc_source(self._h).decode()
+
+    def table(self):
+        out = np.empty(int(lib().st_desc_table_bytes(self._h)) // 4, dtype=np.int32)
+        _check(lib().st_desc_table(self._h, out.ctypes.data), "st_desc_table")
+        return out
+
+    def compile(self):
+        rc = lib().st_desc_compile(self._h)
+        if rc != 0:
+            raise StructTensorError(rc, "st_desc_compile (%s)" % lib().st_desc_error(self._h).decode())
+
+    def _tab(self):
+        if self._table_dev is None:
+            self._table_dev = _torch().from_numpy(self.table()).cuda()
+        return C.c_void_p(self._table_dev.data_ptr())
+
+    def _call(self, rc, what):
+        if rc != 0:
+            raise StructTensorError(rc, "%s (%s)" % (what, lib().st_desc_error(self._h).decode()))
+
+    def list(self):
+        torch = _torch()
+        out = torch.empty((max(self.count, 1), len(self.dims)), dtype=torch.int32, device="cuda")
+        self._call(lib().st_desc_list(self._h, self._tab(), C.c_void_p(out.data_ptr()), _stream()), "st_desc_list")
+        return out[:self.count]
+
+    def thp(self, Bc, Cd, Ac=None):
+        torch = _torch()
+        if Ac is None:
+            Ac = torch.empty(max(self.count, 4), dtype=torch.float32, device=Cd.device)
+        self._call(lib().st_desc_thp(self._h, self._tab(), _dev_f32(Bc, "Bc"), _dev_f32(Cd, "C"),
+                                     _dev_f32(Ac, "Ac"), _stream()), "st_desc_thp")
+        return Ac[:self.count]
+
+    def expand(self, Tc, T=None):
+        torch = _torch()
+        if T is None:
+            T = torch.empty(self.dims, dtype=torch.float32, device=Tc.device)
+        self._call(lib().st_desc_expand(self._h, self._tab(), _dev_f32(Tc, "Tc"), _dev_f32(T, "T"), _stream()),
+                   "st_desc_expand")
+        return T

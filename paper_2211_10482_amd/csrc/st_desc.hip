@@ -1,0 +1,758 @@
+// Descriptor-driven structures: from a textual unique set / redundancy map to generated kernels.
+//
+// The paper gives every tensor a unique set T_U (a product of comparisons over its index variables)
+// and a redundancy map T_R, and generates code from them: index variables are ordered as written,
+// each variable ranges from the maximum of its lower bounds to the minimum of its upper bounds, one
+// loop nest per product term, and the same procedure over T_R reconstructs the redundant part (code
+// generation section).  This file does that at run time for a descriptor given as text:
+//
+//   unique set   "T(i,j,k): (0<=i<n)*(i<=j<n)*(j<=k<n)"      factors: chained comparisons of affine
+//                "B(i,j,l): (0<=i<n)*(i-w<=j<=i+w)*(0<=l<m)"  expressions over the variables, named
+//                "D(i,j):   (0<=i<n)*(i=j)"                   parameters and integers
+//   redundancy   "(0<=j<i<n) -> (j,i)"   terms "condition -> unique index", separated by ';', or the
+//                word "sort" (every permutation of a stored tuple holds the same value)
+//
+// parse -> constraints  c*x_v + rest >= 0 | = 0,  attached to the LAST variable they mention (unit
+// coefficient there), i.e. a lower or an upper bound of that variable in terms of earlier ones ->
+// the loop nest (st_desc_nest) -> packed layout = visiting order of that nest -> host tables (start
+// of the innermost run of every index prefix) -> HIP source specialised to the descriptor (bounds
+// and sizes are literals) -> hiprtc -> module.  The generated kernels iterate runs of the unique set
+// (one wave per run, lanes along the last variable), never the bounding box with a mask; only the
+// reconstruction visits every dense element, as Property 5 requires.
+#include <hip/hiprtc.h>
+
+#include <algorithm>
+#include <cctype>
+#include <cstdio>
+#include <cstring>
+#include <map>
+#include <mutex>
+#include <string>
+#include <vector>
+
+#include "st_common.h"
+
+namespace st {
+namespace {
+
+typedef int64_t i64;
+constexpr int MAXD = 4;
+
+// affine expression: constant + sum coef[name] * name
+struct Affine {
+    i64 c = 0;
+    std::map<std::string, i64> t;
+    void add(const Affine &o, i64 s)
+    {
+        c += s * o.c;
+        for (auto &kv : o.t) {
+            t[kv.first] += s * kv.second;
+            if (t[kv.first] == 0) t.erase(kv.first);
+        }
+    }
+};
+
+struct Parser {
+    const char *p;
+    bool ok = true;
+    explicit Parser(const char *s) : p(s) {}
+    void ws() { while (*p && isspace((unsigned char)*p)) ++p; }
+    bool eat(char ch) { ws(); if (*p == ch) { ++p; return true; } return false; }
+    bool peek(char ch) { ws(); return *p == ch; }
+    std::string ident()
+    {
+        ws();
+        std::string s;
+        if (isalpha((unsigned char)*p) || *p == '_')
+            while (isalnum((unsigned char)*p) || *p == '_') s += *p++;
+        return s;
+    }
+    bool integer(i64 &v)
+    {
+        ws();
+        if (!isdigit((unsigned char)*p)) return false;
+        v = 0;
+        while (isdigit((unsigned char)*p)) { v = v * 10 + (*p - '0'); if (v > (i64)1 << 40) ok = false; ++p; }
+        return true;
+    }
+    // term := [int '*'] ident | int
+    bool term(Affine &out, i64 sign)
+    {
+        i64 v;
+        if (integer(v)) {
+            if (eat('*')) {
+                std::string id = ident();
+                if (id.empty()) return false;
+                out.t[id] += sign * v;
+                if (out.t[id] == 0) out.t.erase(id);
+            } else out.c += sign * v;
+            return true;
+        }
+        std::string id = ident();
+        if (id.empty()) return false;
+        out.t[id] += sign;
+        if (out.t[id] == 0) out.t.erase(id);
+        return true;
+    }
+    bool expr(Affine &out)
+    {
+        i64 sign = 1;
+        ws();
+        if (*p == '-') { sign = -1; ++p; } else if (*p == '+') ++p;
+        if (!term(out, sign)) return false;
+        for (;;) {
+            ws();
+            if (*p == '+') { ++p; if (!term(out, 1)) return false; }
+            else if (*p == '-' && p[1] != '>') { ++p; if (!term(out, -1)) return false; }
+            else return true;
+        }
+    }
+    // relation: 0 none, 1 <=, 2 <, 3 =, 4 >=, 5 >
+    int rel()
+    {
+        ws();
+        if (p[0] == '<' && p[1] == '=') { p += 2; return 1; }
+        if (p[0] == '>' && p[1] == '=') { p += 2; return 4; }
+        if (p[0] == '=' && p[1] == '=') { p += 2; return 3; }
+        if (p[0] == '<') { ++p; return 2; }
+        if (p[0] == '>') { ++p; return 5; }
+        if (p[0] == '=') { ++p; return 3; }
+        return 0;
+    }
+};
+
+// E >= 0 (eq = false) or E == 0 (eq = true)
+struct Constraint { Affine e; bool eq; };
+
+// '(' expr rel expr [rel expr ...] ')' appended to out
+bool parse_factor(Parser &ps, std::vector<Constraint> &out)
+{
+    if (!ps.eat('(')) return false;
+    Affine left;
+    if (!ps.expr(left)) return false;
+    int n = 0;
+    for (;;) {
+        int r = ps.rel();
+        if (r == 0) break;
+        Affine right;
+        if (!ps.expr(right)) return false;
+        Constraint c;
+        c.eq = (r == 3);
+        if (r == 1 || r == 2 || r == 3) { c.e.add(right, 1); c.e.add(left, -1); }   // right - left >= 0
+        else { c.e.add(left, 1); c.e.add(right, -1); }                               // left - right >= 0
+        if (r == 2 || r == 5) c.e.c -= 1;                                            // strict
+        out.push_back(c);
+        left = right;
+        ++n;
+    }
+    return n > 0 && ps.eat(')');
+}
+
+bool parse_product(Parser &ps, std::vector<Constraint> &out)
+{
+    if (!parse_factor(ps, out)) return false;
+    while (ps.eat('*'))
+        if (!parse_factor(ps, out)) return false;
+    return true;
+}
+
+// bound of a variable in terms of earlier variables: value = c + sum coef[u] * x_u
+struct Bound { i64 c; i64 coef[MAXD]; };
+
+struct RedTerm { std::vector<Bound> cond; /* each: expression >= 0 over all variables */ Bound map[MAXD]; };
+
+std::string bound_text(const Bound &b, const std::vector<std::string> &vars, int nv)
+{
+    std::string s;
+    char buf[64];
+    for (int u = 0; u < nv; ++u) {
+        if (b.coef[u] == 0) continue;
+        if (b.coef[u] == 1) snprintf(buf, sizeof buf, "%s%s", s.empty() ? "" : " + ", vars[u].c_str());
+        else if (b.coef[u] == -1) snprintf(buf, sizeof buf, "%s%s", s.empty() ? "-" : " - ", vars[u].c_str());
+        else snprintf(buf, sizeof buf, "%s%lld*%s", s.empty() ? "" : " + ", (long long)b.coef[u], vars[u].c_str());
+        s += buf;
+    }
+    if (b.c != 0 || s.empty()) {
+        if (s.empty()) snprintf(buf, sizeof buf, "%lld", (long long)b.c);
+        else snprintf(buf, sizeof buf, " %c %lld", b.c < 0 ? '-' : '+', (long long)(b.c < 0 ? -b.c : b.c));
+        s += buf;
+    }
+    return s;
+}
+
+// the same as a C expression over x0..x{nv-1}
+std::string bound_code(const Bound &b, int nv)
+{
+    std::string s = "(" + std::to_string((long long)b.c);
+    for (int u = 0; u < nv; ++u)
+        if (b.coef[u] != 0) s += " + (" + std::to_string((long long)b.coef[u]) + ") * x" + std::to_string(u);
+    return s + ")";
+}
+
+i64 bound_eval(const Bound &b, const i64 *x, int nv)
+{
+    i64 v = b.c;
+    for (int u = 0; u < nv; ++u) v += b.coef[u] * x[u];
+    return v;
+}
+
+}  // namespace
+
+struct Desc {
+    int d = 0;
+    std::string name;
+    std::vector<std::string> vars;
+    i64 dims[MAXD] = {0, 0, 0, 0};
+    i64 first[MAXD] = {0, 0, 0, 0}, last[MAXD] = {0, 0, 0, 0};   // constant part of every variable's range
+    bool first_implied[MAXD] = {false, false, false, false};    // some other lower bound never falls below `first`
+    bool last_implied[MAXD] = {false, false, false, false};     // some other upper bound never exceeds `last`
+    std::vector<Bound> lo[MAXD], hi[MAXD];       // x_v >= each lo, x_v <= each hi (over x_0..x_{v-1})
+    bool empty = false;                          // a constraint on the parameters alone is false
+    bool red_sort = false;
+    std::vector<RedTerm> red;
+    i64 count = 0, prefixes = 1;
+    std::vector<int32_t> table;                  // [prefixes] run start or -1, then [nruns] prefix ids
+    i64 nruns = 0;
+    std::string nest, source;
+    std::mutex mu;
+    struct Loaded { hipModule_t mod; hipFunction_t fn[3]; };   // list, thp, expand
+    std::map<int, Loaded> modules;               // per device
+    std::string error;
+};
+
+namespace {
+
+bool to_bound(const Affine &e, const Desc &D, const std::map<std::string, i64> &params, Bound &b, std::string &err)
+{
+    b.c = e.c;
+    for (int u = 0; u < MAXD; ++u) b.coef[u] = 0;
+    for (auto &kv : e.t) {
+        auto it = std::find(D.vars.begin(), D.vars.end(), kv.first);
+        if (it != D.vars.end()) b.coef[it - D.vars.begin()] += kv.second;
+        else {
+            auto pit = params.find(kv.first);
+            if (pit == params.end()) { err = "unknown name '" + kv.first + "'"; return false; }
+            b.c += kv.second * pit->second;
+        }
+    }
+    return true;
+}
+
+// attach  E >= 0 / E == 0  to the last variable it mentions
+bool attach(Desc &D, const Bound &b, bool eq, std::string &err)
+{
+    int v = -1;
+    for (int u = 0; u < D.d; ++u) if (b.coef[u] != 0) v = u;
+    if (v < 0) {
+        if (eq ? b.c != 0 : b.c < 0) D.empty = true;
+        return true;
+    }
+    const i64 c = b.coef[v];
+    if (c != 1 && c != -1) { err = "coefficient of the last variable of a comparison must be 1 or -1"; return false; }
+    Bound rest = b;
+    rest.coef[v] = 0;
+    // c = +1: x_v >= -rest ; c = -1: x_v <= rest
+    Bound neg = rest;
+    neg.c = -neg.c;
+    for (int u = 0; u < MAXD; ++u) neg.coef[u] = -neg.coef[u];
+    if (c == 1) { D.lo[v].push_back(neg); if (eq) D.hi[v].push_back(neg); }
+    else { D.hi[v].push_back(rest); if (eq) D.lo[v].push_back(rest); }
+    return true;
+}
+
+// Logical simplification of the bound lists: duplicates are dropped, constant bounds are folded into the
+// dense extent (a constant lower bound raises `first`, a constant upper bound lowers `last`).
+void simplify(Desc &D)
+{
+    for (int v = 0; v < D.d; ++v) {
+        D.first[v] = 0;
+        D.last[v] = D.dims[v] - 1;
+        for (int side = 0; side < 2; ++side) {
+            std::vector<Bound> &list = side ? D.hi[v] : D.lo[v];
+            std::vector<Bound> keep;
+            for (auto &b : list) {
+                bool constant = true;
+                for (int u = 0; u < MAXD; ++u) constant = constant && b.coef[u] == 0;
+                if (constant) {
+                    if (side) D.last[v] = std::min(D.last[v], b.c);
+                    else D.first[v] = std::max(D.first[v], b.c);
+                    continue;
+                }
+                bool dup = false;
+                for (auto &k : keep) dup = dup || (k.c == b.c && std::equal(k.coef, k.coef + MAXD, b.coef));
+                if (!dup) keep.push_back(b);
+            }
+            list.swap(keep);
+        }
+        // a constant bound is implied when another bound stays on its safe side over the whole box of the
+        // earlier variables (interval arithmetic on the affine expression)
+        for (auto &b : D.lo[v]) {
+            i64 mn = b.c;
+            for (int u = 0; u < v; ++u) mn += b.coef[u] * (b.coef[u] > 0 ? D.first[u] : D.last[u]);
+            if (mn >= D.first[v]) D.first_implied[v] = true;
+        }
+        for (auto &b : D.hi[v]) {
+            i64 mx = b.c;
+            for (int u = 0; u < v; ++u) mx += b.coef[u] * (b.coef[u] > 0 ? D.last[u] : D.first[u]);
+            if (mx <= D.last[v]) D.last_implied[v] = true;
+        }
+    }
+}
+
+void range_of(const Desc &D, int v, const i64 *x, i64 &lo, i64 &hi)
+{
+    lo = D.first[v];
+    hi = D.last[v];
+    for (auto &b : D.lo[v]) lo = std::max(lo, bound_eval(b, x, v));
+    for (auto &b : D.hi[v]) hi = std::min(hi, bound_eval(b, x, v));
+}
+
+void build_nest(Desc &D)
+{
+    std::string s;
+    for (int v = 0; v < D.d; ++v) {
+        std::vector<std::string> los, his;
+        if (!D.first_implied[v]) los.push_back(std::to_string((long long)D.first[v]));
+        if (!D.last_implied[v]) his.push_back(std::to_string((long long)D.last[v]));
+        for (auto &b : D.lo[v]) los.push_back(bound_text(b, D.vars, v));
+        for (auto &b : D.hi[v]) his.push_back(bound_text(b, D.vars, v));
+        auto join = [](const std::vector<std::string> &a, const char *f) {
+            if (a.size() == 1) return a[0];
+            std::string r = std::string(f) + "(";
+            for (size_t q = 0; q < a.size(); ++q) r += (q ? ", " : "") + a[q];
+            return r + ")";
+        };
+        s += std::string(2 * v, ' ') + "for (" + D.vars[v] + " = " + join(los, "max") + "; " + D.vars[v] + " <= " +
+             join(his, "min") + "; ++" + D.vars[v] + ")\n";
+    }
+    s += std::string(2 * D.d, ' ') + D.name + "_C[p++]\n";
+    D.nest = s;
+}
+
+// start of the innermost run of every prefix (x_0 .. x_{d-2}), in nest order
+bool build_tables(Desc &D, std::string &err)
+{
+    D.prefixes = 1;
+    for (int v = 0; v + 1 < D.d; ++v) D.prefixes *= D.dims[v];
+    i64 box = D.prefixes * D.dims[D.d - 1];
+    if (D.prefixes > ((i64)1 << 26) || box > ((i64)1 << 31) - 1) { err = "index box too large"; return false; }
+    D.table.assign((size_t)D.prefixes, -1);
+    std::vector<int32_t> runs;
+    i64 pos = 0;
+    if (!D.empty) {
+        i64 x[MAXD] = {0, 0, 0, 0};
+        // iterative nest over the prefix variables
+        const int np = D.d - 1;
+        i64 lo[MAXD], hi[MAXD];
+        int v = 0;
+        bool done = false;
+        if (np == 0) {
+            i64 l, h;
+            range_of(D, 0, x, l, h);
+            if (l <= h) { D.table[0] = 0; runs.push_back(0); pos = h - l + 1; }
+            done = true;
+        } else {
+            range_of(D, 0, x, lo[0], hi[0]);
+            x[0] = lo[0];
+        }
+        while (!done) {
+            if (x[v] > hi[v]) {
+                if (v == 0) break;
+                --v;
+                ++x[v];
+                continue;
+            }
+            if (v + 1 < np) {
+                ++v;
+                range_of(D, v, x, lo[v], hi[v]);
+                x[v] = lo[v];
+                continue;
+            }
+            // full prefix: innermost run
+            i64 l, h;
+            range_of(D, D.d - 1, x, l, h);
+            if (l <= h) {
+                i64 pf = 0;
+                for (int u = 0; u < np; ++u) pf = pf * D.dims[u] + x[u];
+                if (pos > ((i64)1 << 31) - 1 - (h - l + 1)) { err = "more than 2^31 unique entries"; return false; }
+                D.table[(size_t)pf] = (int32_t)pos;
+                runs.push_back((int32_t)pf);
+                pos += h - l + 1;
+            }
+            ++x[v];
+        }
+    }
+    D.count = pos;
+    D.nruns = (i64)runs.size();
+    D.table.insert(D.table.end(), runs.begin(), runs.end());
+    return true;
+}
+
+std::string args_list(int n, const char *prefix, bool typed)
+{
+    std::string s;
+    for (int u = 0; u < n; ++u) s += std::string(u ? ", " : "") + (typed ? "int " : "") + prefix + std::to_string(u);
+    return s;
+}
+
+void build_source(Desc &D)
+{
+    const int d = D.d;
+    std::string s;
+    s += "// generated for " + D.name + ": unique set of order " + std::to_string(d) + "\n";
+    s += "#define ST_D " + std::to_string(d) + "\n";
+    s += "#define ST_PREFIXES " + std::to_string((long long)D.prefixes) + "\n";
+    s += "#define ST_NRUNS " + std::to_string((long long)D.nruns) + "\n";
+    s += "#define ST_COUNT " + std::to_string((long long)D.count) + "\n";
+    for (int v = 0; v < d; ++v) s += "#define ST_DIM" + std::to_string(v) + " " + std::to_string((long long)D.dims[v]) + "\n";
+    s += "static __device__ __forceinline__ int st_max(int a, int b) { return a > b ? a : b; }\n";
+    s += "static __device__ __forceinline__ int st_min(int a, int b) { return a < b ? a : b; }\n";
+    // bounds of every variable from the earlier ones: max of the lower bounds, min of the upper bounds
+    for (int v = 0; v < d; ++v) {
+        std::string a = args_list(v, "x", true);
+        std::string lo = D.first_implied[v] ? "" : std::to_string((long long)D.first[v]);
+        std::string hi = D.last_implied[v] ? "" : std::to_string((long long)D.last[v]);
+        for (auto &b : D.lo[v]) lo = lo.empty() ? bound_code(b, v) : "st_max(" + lo + ", " + bound_code(b, v) + ")";
+        for (auto &b : D.hi[v]) hi = hi.empty() ? bound_code(b, v) : "st_min(" + hi + ", " + bound_code(b, v) + ")";
+        s += "static __device__ __forceinline__ int st_lo" + std::to_string(v) + "(" + a + ") { return " + lo + "; }\n";
+        s += "static __device__ __forceinline__ int st_hi" + std::to_string(v) + "(" + a + ") { return " + hi + "; }\n";
+    }
+    // membership and packed position of an index tuple
+    s += "static __device__ __forceinline__ bool st_in(" + args_list(d, "x", true) + ")\n{\n    return ";
+    s += D.empty ? "false" : "true";
+    for (int v = 0; v < d; ++v) {
+        std::string a = args_list(v, "x", false), xv = "x" + std::to_string(v);
+        s += "\n        && " + xv + " >= st_lo" + std::to_string(v) + "(" + a + ") && " + xv + " <= st_hi" + std::to_string(v) + "(" + a + ")";
+    }
+    s += ";\n}\n";
+    std::string pf = "0";
+    for (int v = 0; v + 1 < d; ++v) pf = "(" + pf + ") * ST_DIM" + std::to_string(v) + " + x" + std::to_string(v);
+    s += "static __device__ __forceinline__ int st_rank(const int *tab, " + args_list(d, "x", true) + ")\n{\n";
+    s += "    return tab[" + pf + "] + (x" + std::to_string(d - 1) + " - st_lo" + std::to_string(d - 1) + "(" + args_list(d - 1, "x", false) + "));\n}\n";
+    // prefix id -> x0 .. x{d-2}
+    s += "#define ST_DECODE_PREFIX(pf)";
+    {
+        std::string rem = "int st_r = (pf);";
+        std::string body;
+        for (int v = d - 2; v >= 0; --v) {
+            body += " const int x" + std::to_string(v) + " = st_r % ST_DIM" + std::to_string(v) + "; st_r /= ST_DIM" + std::to_string(v) + ";";
+        }
+        s += " " + rem + body + " (void)st_r;\n";
+    }
+    const std::string pre = args_list(d - 1, "x", false);
+    const std::string last = "x" + std::to_string(d - 1);
+    std::string dense = "0";
+    for (int v = 0; v < d; ++v) dense = "((long long)(" + dense + ")) * ST_DIM" + std::to_string(v) + " + x" + std::to_string(v);
+    // list: one wave per run, lanes along the last variable
+    s += "extern \"C\" __global__ void st_gen_list(const int *__restrict__ tab, int *__restrict__ out)\n{\n";
+    s += "    const int run = blockIdx.x * (blockDim.x / 64) + threadIdx.x / 64, lane = threadIdx.x % 64;\n";
+    s += "    if (run >= ST_NRUNS) return;\n    const int pf = tab[ST_PREFIXES + run];\n    ST_DECODE_PREFIX(pf)\n";
+    s += "    const int lo = st_lo" + std::to_string(d - 1) + "(" + pre + "), hi = st_hi" + std::to_string(d - 1) + "(" + pre + "), start = tab[pf];\n";
+    s += "    for (int " + last + " = lo + lane; " + last + " <= hi; " + last + " += 64) {\n";
+    s += "        int *o = out + (long long)(start + " + last + " - lo) * ST_D;\n";
+    for (int v = 0; v < d; ++v) s += "        o[" + std::to_string(v) + "] = x" + std::to_string(v) + ";\n";
+    s += "    }\n}\n";
+    // thp: Ac(p) = Bc(p) * C(x(p)), C dense
+    s += "extern \"C\" __global__ void st_gen_thp(const int *__restrict__ tab, const float *__restrict__ Bc,\n"
+         "                                      const float *__restrict__ C, float *__restrict__ Ac)\n{\n";
+    s += "    const int run = blockIdx.x * (blockDim.x / 64) + threadIdx.x / 64, lane = threadIdx.x % 64;\n";
+    s += "    if (run >= ST_NRUNS) return;\n    const int pf = tab[ST_PREFIXES + run];\n    ST_DECODE_PREFIX(pf)\n";
+    s += "    const int lo = st_lo" + std::to_string(d - 1) + "(" + pre + "), hi = st_hi" + std::to_string(d - 1) + "(" + pre + "), start = tab[pf];\n";
+    s += "    for (int " + last + " = lo + lane; " + last + " <= hi; " + last + " += 64) {\n";
+    s += "        const int p = start + " + last + " - lo;\n";
+    s += "        Ac[p] = Bc[p] * C[" + dense + "];\n    }\n}\n";
+    // value of one dense element: Tc(rank(x)) on the unique set, Tc(rank(x')) through the redundancy map, 0 elsewhere
+    const std::string xs = args_list(d, "x", false);
+    s += "static __device__ __forceinline__ float st_value(const int *__restrict__ tab, const float *__restrict__ Tc, " +
+         args_list(d, "x", true) + ")\n{\n";
+    s += "    int pos = -1;\n";
+    s += "    if (st_in(" + xs + ")) pos = st_rank(tab, " + xs + ");\n";
+    if (D.red_sort) {
+        s += "    else {\n        int y[ST_D] = {" + xs + "};\n";
+        s += "        for (int a = 1; a < ST_D; ++a)\n            for (int b = a; b > 0 && y[b - 1] > y[b]; --b) { const int t = y[b]; y[b] = y[b - 1]; y[b - 1] = t; }\n";
+        std::string ys;
+        for (int v = 0; v < d; ++v) ys += std::string(v ? ", " : "") + "y[" + std::to_string(v) + "]";
+        s += "        if (st_in(" + ys + ")) pos = st_rank(tab, " + ys + ");\n    }\n";
+    }
+    for (auto &t : D.red) {
+        s += "    if (pos < 0";
+        for (auto &c : t.cond) s += " && " + bound_code(c, d) + " >= 0";
+        s += ") {\n";
+        std::string ys;
+        for (int v = 0; v < d; ++v) {
+            s += "        const int y" + std::to_string(v) + " = " + bound_code(t.map[v], d) + ";\n";
+            ys += std::string(v ? ", " : "") + "y" + std::to_string(v);
+        }
+        s += "        if (st_in(" + ys + ")) pos = st_rank(tab, " + ys + ");\n    }\n";
+    }
+    s += "    return pos >= 0 ? Tc[pos] : 0.f;\n}\n";
+    // expand: one thread per dense element, or per four consecutive ones along the last variable (one 16-byte store)
+    const bool vec = D.dims[d - 1] % 4 == 0;
+    const std::string lastdim = "ST_DIM" + std::to_string(d - 1);
+    s += "extern \"C\" __global__ void st_gen_expand(const int *__restrict__ tab, const float *__restrict__ Tc,\n"
+         "                                         float *__restrict__ T)\n{\n";
+    std::string total = "1LL";
+    for (int v = 0; v < d; ++v) total += " * ST_DIM" + std::to_string(v);
+    s += "    const long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x;\n";
+    s += "    if (e >= " + total + (vec ? " / 4" : "") + ") return;\n";
+    s += "    long long st_r = e;\n";
+    for (int v = d - 1; v >= 0; --v) {
+        const std::string dim = "ST_DIM" + std::to_string(v);
+        if (v == d - 1 && vec)
+            s += "    const int x" + std::to_string(v) + " = 4 * (int)(st_r % (" + dim + " / 4)); st_r /= " + dim + " / 4;\n";
+        else
+            s += "    const int x" + std::to_string(v) + " = (int)(st_r % " + dim + "); st_r /= " + dim + ";\n";
+    }
+    if (vec) {
+        const std::string pre2 = d > 1 ? args_list(d - 1, "x", false) + ", " : std::string();
+        const std::string xl = "x" + std::to_string(d - 1);
+        s += "    float4 v;\n";
+        const char *comp[4] = {"x", "y", "z", "w"};
+        for (int q = 0; q < 4; ++q)
+            s += std::string("    v.") + comp[q] + " = st_value(tab, Tc, " + pre2 + xl + " + " + std::to_string(q) + ");\n";
+        s += "    *reinterpret_cast<float4 *>(T + 4 * e) = v;\n}\n";
+    } else {
+        s += "    T[e] = st_value(tab, Tc, " + xs + ");\n}\n";
+    }
+    D.source = s;
+}
+
+st_status parse_all(Desc &D, const char *unique_set, const char *redundancy, const i64 *dims, int ndims,
+                    const char *const *pnames, const i64 *pvalues, int nparams)
+{
+    std::map<std::string, i64> params;
+    for (int q = 0; q < nparams; ++q) {
+        if (!pnames[q]) { D.error = "NULL parameter name"; return ST_ERR_NULL; }
+        params[pnames[q]] = pvalues[q];
+    }
+    Parser ps(unique_set);
+    D.name = ps.ident();
+    if (D.name.empty() || !ps.eat('(')) { D.error = "expected NAME(vars): factors"; return ST_ERR_SHAPE; }
+    do {
+        std::string v = ps.ident();
+        if (v.empty()) { D.error = "expected an index variable"; return ST_ERR_SHAPE; }
+        if (std::find(D.vars.begin(), D.vars.end(), v) != D.vars.end() || params.count(v)) {
+            D.error = "name '" + v + "' used twice";
+            return ST_ERR_SHAPE;
+        }
+        D.vars.push_back(v);
+    } while (ps.eat(','));
+    if (!ps.eat(')') || !ps.eat(':')) { D.error = "expected NAME(vars): factors"; return ST_ERR_SHAPE; }
+    D.d = (int)D.vars.size();
+    if (D.d < 1 || D.d > MAXD) { D.error = "order must be 1..4"; return ST_ERR_UNSUPPORTED; }
+    if (D.d != ndims) { D.error = "number of sizes differs from the number of index variables"; return ST_ERR_SHAPE; }
+    for (int v = 0; v < D.d; ++v) {
+        if (dims[v] < 1 || dims[v] > ((i64)1 << 24)) { D.error = "size out of range"; return ST_ERR_SHAPE; }
+        D.dims[v] = dims[v];
+    }
+    std::vector<Constraint> cons;
+    if (!parse_product(ps, cons) || !ps.ok) { D.error = "cannot parse the unique set"; return ST_ERR_SHAPE; }
+    ps.ws();
+    if (*ps.p) { D.error = std::string("trailing text in the unique set: '") + ps.p + "'"; return ST_ERR_SHAPE; }
+    for (auto &c : cons) {
+        Bound b;
+        if (!to_bound(c.e, D, params, b, D.error)) return ST_ERR_SHAPE;
+        if (!attach(D, b, c.eq, D.error)) return ST_ERR_UNSUPPORTED;
+    }
+    if (redundancy && *redundancy) {
+        Parser pr(redundancy);
+        pr.ws();
+        if (strncmp(pr.p, "sort", 4) == 0) {
+            pr.p += 4;
+            pr.ws();
+            if (*pr.p) { D.error = "trailing text after 'sort'"; return ST_ERR_SHAPE; }
+            D.red_sort = true;
+            for (int v = 1; v < D.d; ++v)
+                if (D.dims[v] != D.dims[0]) { D.error = "'sort' needs equal sizes"; return ST_ERR_SHAPE; }
+        } else {
+            do {
+                std::vector<Constraint> cc;
+                if (!parse_product(pr, cc)) { D.error = "cannot parse a redundancy condition"; return ST_ERR_SHAPE; }
+                pr.ws();
+                if (!(pr.p[0] == '-' && pr.p[1] == '>')) { D.error = "expected '->' in a redundancy term"; return ST_ERR_SHAPE; }
+                pr.p += 2;
+                if (!pr.eat('(')) { D.error = "expected '(' after '->'"; return ST_ERR_SHAPE; }
+                RedTerm t;
+                for (auto &c : cc) {
+                    Bound b;
+                    if (!to_bound(c.e, D, params, b, D.error)) return ST_ERR_SHAPE;
+                    t.cond.push_back(b);
+                    if (c.eq) {               // E == 0  <=>  E >= 0 and -E >= 0
+                        Bound nb = b;
+                        nb.c = -nb.c;
+                        for (int u = 0; u < MAXD; ++u) nb.coef[u] = -nb.coef[u];
+                        t.cond.push_back(nb);
+                    }
+                }
+                for (int v = 0; v < D.d; ++v) {
+                    Affine e;
+                    if (!pr.expr(e)) { D.error = "cannot parse a redundancy target"; return ST_ERR_SHAPE; }
+                    if (!to_bound(e, D, params, t.map[v], D.error)) return ST_ERR_SHAPE;
+                    if (v + 1 < D.d && !pr.eat(',')) { D.error = "a redundancy target needs one expression per index"; return ST_ERR_SHAPE; }
+                }
+                if (!pr.eat(')')) { D.error = "expected ')' after a redundancy target"; return ST_ERR_SHAPE; }
+                D.red.push_back(t);
+            } while (pr.eat(';'));
+            pr.ws();
+            if (*pr.p || !pr.ok) { D.error = "trailing text in the redundancy map"; return ST_ERR_SHAPE; }
+        }
+    }
+    simplify(D);
+    build_nest(D);
+    if (!build_tables(D, D.error)) return ST_ERR_UNSUPPORTED;
+    build_source(D);
+    return ST_OK;
+}
+
+// compile the generated source for the current device and load it (once per device)
+st_status module_for(Desc &D, Desc::Loaded &out)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return ST_ERR_LAUNCH;
+    std::lock_guard<std::mutex> lock(D.mu);
+    auto it = D.modules.find(dev);
+    if (it != D.modules.end()) { out = it->second; return ST_OK; }
+    hiprtcProgram prog;
+    if (hiprtcCreateProgram(&prog, D.source.c_str(), "st_generated.hip", 0, nullptr, nullptr) != HIPRTC_SUCCESS)
+        return ST_ERR_LAUNCH;
+    const char *opts[] = {"--offload-arch=gfx950", "-O3", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"};
+    hiprtcResult rc = hiprtcCompileProgram(prog, 6, opts);
+    if (rc != HIPRTC_SUCCESS) {
+        size_t n = 0;
+        hiprtcGetProgramLogSize(prog, &n);
+        std::string log(n, '\0');
+        if (n) hiprtcGetProgramLog(prog, &log[0]);
+        D.error = "hiprtc: " + log;
+        hiprtcDestroyProgram(&prog);
+        return ST_ERR_LAUNCH;
+    }
+    size_t n = 0;
+    hiprtcGetCodeSize(prog, &n);
+    std::vector<char> code(n);
+    hiprtcGetCode(prog, code.data());
+    hiprtcDestroyProgram(&prog);
+    Desc::Loaded L;
+    if (hipModuleLoadData(&L.mod, code.data()) != hipSuccess) { D.error = "hipModuleLoadData failed"; return ST_ERR_LAUNCH; }
+    const char *names[3] = {"st_gen_list", "st_gen_thp", "st_gen_expand"};
+    for (int q = 0; q < 3; ++q)
+        if (hipModuleGetFunction(&L.fn[q], L.mod, names[q]) != hipSuccess) {
+            (void)hipModuleUnload(L.mod);
+            D.error = std::string("generated kernel missing: ") + names[q];
+            return ST_ERR_LAUNCH;
+        }
+    D.modules[dev] = L;
+    out = L;
+    return ST_OK;
+}
+
+st_status launch_generated(Desc &D, int which, unsigned blocks, void **args, hipStream_t s)
+{
+    if (blocks == 0) return ST_OK;
+    Desc::Loaded L;
+    st_status rc = module_for(D, L);
+    if (rc != ST_OK) return rc;
+    if (hipModuleLaunchKernel(L.fn[which], blocks, 1, 1, 256, 1, 1, 0, s, args, nullptr) != hipSuccess) return ST_ERR_LAUNCH;
+    return ST_OK;
+}
+
+}  // namespace
+}  // namespace st
+
+using namespace st;
+
+extern "C" {
+
+st_status st_desc_create(const char *unique_set, const char *redundancy, const int64_t *dims, int ndims,
+                         const char *const *param_names, const int64_t *param_values, int nparams, st_desc **out)
+{
+    if (!unique_set || !dims || !out || (nparams > 0 && (!param_names || !param_values))) return ST_ERR_NULL;
+    if (ndims < 1 || ndims > MAXD || nparams < 0) return ST_ERR_SHAPE;
+    Desc *D = new Desc();
+    st_status rc = parse_all(*D, unique_set, redundancy, dims, ndims, param_names, param_values, nparams);
+    *out = reinterpret_cast<st_desc *>(D);     // kept on failure too: st_desc_error tells why
+    return rc;
+}
+
+void st_desc_destroy(st_desc *desc)
+{
+    Desc *D = reinterpret_cast<Desc *>(desc);
+    if (!D) return;
+    for (auto &kv : D->modules) (void)hipModuleUnload(kv.second.mod);
+    delete D;
+}
+
+const char *st_desc_error(const st_desc *desc) { return desc ? reinterpret_cast<const Desc *>(desc)->error.c_str() : ""; }
+int64_t st_desc_count(const st_desc *desc) { return desc ? reinterpret_cast<const Desc *>(desc)->count : -1; }
+int64_t st_desc_runs(const st_desc *desc) { return desc ? reinterpret_cast<const Desc *>(desc)->nruns : -1; }
+const char *st_desc_nest(const st_desc *desc) { return desc ? reinterpret_cast<const Desc *>(desc)->nest.c_str() : ""; }
+const char *st_desc_source(const st_desc *desc) { return desc ? reinterpret_cast<const Desc *>(desc)->source.c_str() : ""; }
+size_t st_desc_table_bytes(const st_desc *desc)
+{
+    return desc ? reinterpret_cast<const Desc *>(desc)->table.size() * sizeof(int32_t) : 0;
+}
+
+st_status st_desc_table(const st_desc *desc, void *host_out)
+{
+    if (!desc || !host_out) return ST_ERR_NULL;
+    const Desc *D = reinterpret_cast<const Desc *>(desc);
+    memcpy(host_out, D->table.data(), D->table.size() * sizeof(int32_t));
+    return ST_OK;
+}
+
+st_status st_desc_compile(st_desc *desc)
+{
+    if (!desc) return ST_ERR_NULL;
+    Desc *D = reinterpret_cast<Desc *>(desc);
+    if (D->source.empty()) return ST_ERR_SHAPE;
+    hiprtcProgram prog;
+    if (hiprtcCreateProgram(&prog, D->source.c_str(), "st_generated.hip", 0, nullptr, nullptr) != HIPRTC_SUCCESS)
+        return ST_ERR_LAUNCH;
+    const char *opts[] = {"--offload-arch=gfx950", "-O3", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"};
+    hiprtcResult rc = hiprtcCompileProgram(prog, 6, opts);
+    if (rc != HIPRTC_SUCCESS) {
+        size_t n = 0;
+        hiprtcGetProgramLogSize(prog, &n);
+        std::string log(n, '\0');
+        if (n) hiprtcGetProgramLog(prog, &log[0]);
+        D->error = "hiprtc: " + log;
+    }
+    hiprtcDestroyProgram(&prog);
+    return rc == HIPRTC_SUCCESS ? ST_OK : ST_ERR_LAUNCH;
+}
+
+st_status st_desc_list(st_desc *desc, const void *table, int32_t *out, void *stream)
+{
+    if (!desc || !table || !out) return ST_ERR_NULL;
+    Desc *D = reinterpret_cast<Desc *>(desc);
+    if (D->source.empty()) return ST_ERR_SHAPE;
+    if (!aligned16(table) || !aligned16(out)) return ST_ERR_ALIGN;
+    void *args[] = {&table, &out};
+    return launch_generated(*D, 0, (unsigned)((D->nruns + 3) / 4), args, (hipStream_t)stream);
+}
+
+st_status st_desc_thp(st_desc *desc, const void *table, const float *Bc, const float *C, float *Ac, void *stream)
+{
+    if (!desc || !table || !Bc || !C || !Ac) return ST_ERR_NULL;
+    Desc *D = reinterpret_cast<Desc *>(desc);
+    if (D->source.empty()) return ST_ERR_SHAPE;
+    if (!aligned16(table) || !aligned16(Bc) || !aligned16(C) || !aligned16(Ac)) return ST_ERR_ALIGN;
+    size_t pb = (size_t)D->count * 4, cb = (size_t)D->prefixes * D->dims[D->d - 1] * 4;
+    if (overlap(Ac, pb, Bc, pb) || overlap(Ac, pb, C, cb)) return ST_ERR_SHAPE;
+    void *args[] = {&table, &Bc, &C, &Ac};
+    return launch_generated(*D, 1, (unsigned)((D->nruns + 3) / 4), args, (hipStream_t)stream);
+}
+
+st_status st_desc_expand(st_desc *desc, const void *table, const float *Tc, float *T, void *stream)
+{
+    if (!desc || !table || !Tc || !T) return ST_ERR_NULL;
+    Desc *D = reinterpret_cast<Desc *>(desc);
+    if (D->source.empty()) return ST_ERR_SHAPE;
+    if (!aligned16(table) || !aligned16(Tc) || !aligned16(T)) return ST_ERR_ALIGN;
+    const int64_t total = D->prefixes * D->dims[D->d - 1];
+    if (overlap(T, (size_t)total * 4, Tc, (size_t)D->count * 4)) return ST_ERR_SHAPE;
+    void *args[] = {&table, &Tc, &T};
+    const int64_t threads = D->dims[D->d - 1] % 4 == 0 ? total / 4 : total;     // as in the generated kernel
+    return launch_generated(*D, 2, (unsigned)((threads + 255) / 256), args, (hipStream_t)stream);
+}
+
+}  // extern "C"

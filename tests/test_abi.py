@@ -124,3 +124,30 @@ def test_kernel_table_errors():
     assert L.st_expand_band(P, Q, 4, -1, 4, None) == SHAPE
     assert L.st_expand_band(P, Q, 50000, 1, 4, None) == UNSUPPORTED
     assert L.st_expand_band(P, P + 16, 4, 1, 4, None) == SHAPE                       # buffers overlap
+
+
+def test_descriptor_errors():
+    L = st.lib()
+    h = C.c_void_p()
+    dims = (C.c_int64 * 2)(4, 4)
+    names = (C.c_char_p * 1)(b"n")
+    vals = (C.c_int64 * 1)(4)
+    assert L.st_desc_create(None, None, dims, 2, names, vals, 1, C.byref(h)) == NULL
+    assert L.st_desc_create(b"S(i,j): (0<=i<=j<n)", None, dims, 2, names, vals, 1, None) == NULL
+    assert L.st_desc_create(b"S(i,j): (0<=i<=j<n)", None, dims, 5, names, vals, 1, C.byref(h)) == SHAPE
+    assert L.st_desc_create(b"S(i,j): (0<=i<=j<q)", None, dims, 2, names, vals, 1, C.byref(h)) == SHAPE
+    assert b"unknown name" in L.st_desc_error(h)
+    assert L.st_desc_list(h, P, P + 0x10000, None) == SHAPE          # nothing was generated for a failed parse
+    L.st_desc_destroy(h)
+    assert L.st_desc_create(b"S(i,j): (0<=i<=j<n)", None, dims, 2, names, vals, 1, C.byref(h)) == OK
+    assert L.st_desc_count(h) == 10 and L.st_desc_runs(h) == 4 and L.st_desc_table_bytes(h) == (4 + 4) * 4
+    assert L.st_desc_list(h, None, P, None) == NULL
+    assert L.st_desc_list(h, P + 4, P + 0x10000, None) == ALIGN
+    assert L.st_desc_thp(h, P, P + 0x10000, None, P + 0x20000, None) == NULL
+    assert L.st_desc_thp(h, P, P + 0x10000, P + 0x20000, P + 0x10000, None) == SHAPE      # output aliases B
+    assert L.st_desc_expand(h, P, None, P + 0x10000, None) == NULL
+    assert L.st_desc_expand(h, P, P + 0x10000, P + 0x10010, None) == SHAPE                # buffers overlap
+    assert L.st_desc_table(h, None) == NULL
+    assert L.st_desc_count(None) == -1
+    L.st_desc_destroy(h)
+    L.st_desc_destroy(None)

@@ -1,0 +1,183 @@
+"""Descriptor-driven structures on the CPU: the parsed unique set / redundancy map against brute force
+over the index box (predicates written out by hand here), the derived nests against the paper's printed
+ones, the host tables against the closed-form index maps, and the GENERATED kernel source both compiled
+with hiprtc for gfx950 (no GPU needed) and run on the CPU through the host stand-in of the HIP runtime."""
+import os
+import shutil
+import subprocess
+
+import numpy as np
+import pytest
+
+import paper_2211_10482_amd as st
+import st_workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+EMUL = os.path.join(ROOT, "tests", "emul")
+CLANG = shutil.which("clang++", path="/opt/rocm/llvm/bin") or shutil.which("clang++")
+
+
+def _sorted(*x):
+    return tuple(sorted(x))
+
+
+# name -> (unique set text, dims, redundancy text, parameters, predicate, unique_of)
+CASES = {
+    # "Tensor Structures": unique elements of a symmetric matrix / degree-3 / degree-4 interaction tensor
+    "sym2": ("S(i,j): (0<=i<=j<n)", (7, 7), "(0<=j<i<n) -> (j,i)", dict(n=7),
+             lambda i, j: i <= j, lambda i, j: (j, i) if j < i else None),
+    "sym3": ("T(i,j,k): (0<=i<n)*(i<=j<n)*(j<=k<n)", (6, 6, 6), "sort", dict(n=6),
+             lambda i, j, k: i <= j <= k, _sorted),
+    "sym4": ("Q(i,j,k,l): (0<=i<=j<n)*(j<=k<=l<n)", (4, 4, 4, 4), "sort", dict(n=4),
+             lambda i, j, k, l: i <= j <= k <= l, _sorted),
+    # band |i-j| <= w with a free last index (the band tensor of the TTM workload)
+    "band": ("B(i,j,l): (0<=i<n)*(i-w<=j<=i+w)*(0<=l<m)", (9, 9, 5), None, dict(n=9, w=2, m=5),
+             lambda i, j, l: abs(i - j) <= 2, None),
+    # the kernel table: diagonal plane, fixed i, fixed j, upper half cube
+    "diag": ("B(i,j,l): (0<=i<n)*(i=j)*(0<=l<m)", (6, 6, 3), None, dict(n=6, m=3),
+             lambda i, j, l: i == j, None),
+    "fixed_i": ("B(i,j,l): (i=I)*(0<=j<n)*(0<=l<m)", (5, 6, 3), None, dict(I=2, n=6, m=3),
+                lambda i, j, l: i == 2, None),
+    "fixed_j": ("B(i,j,l): (0<=i<n)*(j=J)*(0<=l<m)", (5, 6, 3), None, dict(J=4, n=5, m=3),
+                lambda i, j, l: j == 4, None),
+    "upper_cube": ("B(i,j,l): (0<=i<n)*(i<=j<n)*(0<=l<m)", (6, 6, 4), None, dict(n=6, m=4),
+                   lambda i, j, l: i <= j, None),
+    # the paper's identical-rows example: only row 0 is stored, every other row repeats it
+    "same_rows": ("M(i,j): (i=0)*(0<=j<m)", (5, 7), "(1<=i<n) -> (0,j)", dict(n=5, m=7),
+                  lambda i, j: i == 0, lambda i, j: (0, j) if i >= 1 else None),
+    # strictly lower triangle; an anti-diagonal band (two bounds from both sides on the last variable)
+    "lower": ("L(i,j): (0<=j<i<n)", (6, 6), None, dict(n=6), lambda i, j: j < i, None),
+    "anti": ("A(i,j): (0<=i<n)*(n-2<=i+j<=n)", (7, 7), None, dict(n=7), lambda i, j: 5 <= i + j <= 7, None),
+    "order1": ("v(i): (2<=i<n)", (9,), None, dict(n=6), lambda i: 2 <= i < 6, None),
+    "sym3_vec": ("T(i,j,k): (0<=i<=j<n)*(j<=k<n)", (8, 8, 8), "sort", dict(n=8), lambda i, j, k: i <= j <= k, _sorted),
+    "order1_vec": ("v(i): (3<=i<=9)", (12,), None, dict(), lambda i: 3 <= i <= 9, None),
+    "empty": ("E(i,j): (0<=i<n)*(j<i)*(j>i)", (4, 4), None, dict(n=4), lambda i, j: False, None),
+    "none_by_param": ("E(i,j): (0<=i<n)*(n<=3)*(0<=j<n)", (4, 4), None, dict(n=4), lambda i, j: False, None),
+}
+
+
+@pytest.fixture(scope="module")
+def descs():
+    out = {}
+    for name, (text, dims, red, params, _, _) in CASES.items():
+        out[name] = st.Descriptor(text, dims, red, **params)
+    yield out
+    for d in out.values():
+        d.close()
+
+
+@pytest.mark.parametrize("name", sorted(CASES))
+def test_counts_and_tables_against_brute_force(descs, oracle, name):
+    text, dims, red, params, pred, _ = CASES[name]
+    d = descs[name]
+    lst = oracle.struct_enumerate(dims, pred)
+    assert d.count == lst.shape[0]
+    tab = d.table()
+    nprefix = int(np.prod(dims[:-1])) if len(dims) > 1 else 1
+    assert tab.size == nprefix + d.runs
+    # run starts: position of the first entry of every prefix that has one, -1 for the others
+    want = np.full(nprefix, -1, dtype=np.int64)
+    for p in range(lst.shape[0] - 1, -1, -1):
+        pf = 0
+        for v in range(len(dims) - 1):
+            pf = pf * dims[v] + int(lst[p, v])
+        want[pf] = p
+    assert np.array_equal(tab[:nprefix], want)
+    assert np.array_equal(tab[nprefix:], np.flatnonzero(want >= 0))
+
+
+def test_tables_match_the_closed_form_index_maps(oracle):
+    n, w, m = 40, 5, 3
+    d3 = st.Descriptor("T(i,j,k): (0<=i<n)*(i<=j<n)*(j<=k<n)", (n, n, n), "sort", n=n)
+    assert d3.count == st.count_sym3(n) == oracle.count_sym3(n)
+    tab = d3.table()[: n * n].reshape(n, n)
+    for i in range(n):
+        for j in range(n):
+            assert tab[i, j] == (st.rank_sym3(n, i, j, j) if i <= j else -1)
+    db = st.Descriptor("B(i,j,l): (0<=i<n)*(i-w<=j<=i+w)*(0<=l<m)", (n, n, m), n=n, w=w, m=m)
+    assert db.count == st.count_band(n, w) * m
+    tab = db.table()[: n * n].reshape(n, n)
+    for i in range(n):
+        for j in range(n):
+            assert tab[i, j] == (st.rank_band(n, w, i, j) * m if abs(i - j) <= w else -1)
+    d4 = st.Descriptor("Q(i,j,k,l): (0<=i<=j<n)*(j<=k<=l<n)", (9, 9, 9, 9), "sort", n=9)
+    assert d4.count == st.count_sym4(9)
+    # the distinct elements of the degree-2 polynomial-regression covariance of four features (golden file)
+    n = 4
+    total = sum(st.Descriptor(t, (n,) * o, n=n).count for t, o in (
+        ("S(i,j): (0<=i<=j<n)", 2), ("T(i,j,k): (0<=i<=j<n)*(j<=k<n)", 3), ("Q(i,j,k,l): (0<=i<=j<n)*(j<=k<=l<n)", 4)))
+    golden = dict(l.split()[:2] for l in open(os.path.join(ROOT, "tests", "golden", "paper_counts.txt"))
+                  if l.strip() and not l.startswith("#"))
+    assert total == int(golden["pr2_distinct_elements_n4"]) == 65
+
+
+def test_derived_nests(descs):
+    # the overview's M1, M2 and M3 nests: for i; for j = i; for k = j; for l = k
+    assert descs["sym3"].nest.splitlines()[:3] == [
+        "for (i = 0; i <= 5; ++i)", "  for (j = i; j <= 5; ++j)", "    for (k = j; k <= 5; ++k)"]
+    assert descs["sym4"].nest.splitlines()[:4] == [
+        "for (i = 0; i <= 3; ++i)", "  for (j = i; j <= 3; ++j)", "    for (k = j; k <= 3; ++k)",
+        "      for (l = k; l <= 3; ++l)"]
+    assert descs["sym2"].nest.splitlines()[:2] == ["for (i = 0; i <= 6; ++i)", "  for (j = i; j <= 6; ++j)"]
+    # bounds are the maximum of the lower and the minimum of the upper bounds
+    assert descs["band"].nest.splitlines()[1] == "  for (j = max(0, i - 2); j <= min(8, i + 2); ++j)"
+    assert descs["anti"].nest.splitlines()[1] == "  for (j = max(0, -i + 5); j <= min(6, -i + 7); ++j)"
+    assert descs["diag"].nest.splitlines()[1] == "  for (j = i; j <= i; ++j)"
+    assert descs["fixed_j"].nest.splitlines()[1] == "  for (j = 4; j <= 4; ++j)"
+    assert descs["lower"].nest.splitlines()[:2] == ["for (i = 0; i <= 5; ++i)", "  for (j = 0; j <= i - 1; ++j)"]
+
+
+def test_parse_errors():
+    bad = [
+        ("S(i,j) (0<=i<n)", (4, 4), None, dict(n=4)),                       # no colon
+        ("S(i,j): (0<=i<n)*(2*j<=i)", (4, 4), None, dict(n=4)),             # non-unit coefficient
+        ("S(i,j): (0<=i<q)", (4, 4), None, dict(n=4)),                      # unknown name
+        ("S(i,j): (0<=i<n)", (4,), None, dict(n=4)),                        # sizes / variables mismatch
+        ("S(i,i): (0<=i<n)", (4, 4), None, dict(n=4)),                      # variable twice
+        ("S(i,j): (0<=i<n) junk", (4, 4), None, dict(n=4)),                 # trailing text
+        ("S(i,j): (0<=i<=j<n)", (4, 5), "sort", dict(n=4)),                 # sort needs equal sizes
+        ("S(i,j): (0<=i<=j<n)", (4, 4), "(0<=j<i<n) -> (j)", dict(n=4)),    # target arity
+        ("S(i,j): (0<=i<=j<n)", (4, 4), "(0<=j<i<n) (j,i)", dict(n=4)),     # no arrow
+        ("S(i,j,k,l,m): (0<=i<n)", (4,) * 5, None, dict(n=4)),              # order > 4
+    ]
+    for text, dims, red, params in bad:
+        with pytest.raises(st.StructTensorError):
+            st.Descriptor(text, dims, red, **params)
+
+
+@pytest.mark.parametrize("name", sorted(CASES))
+def test_generated_source_compiles_for_gfx950(descs, name):
+    descs[name].compile()
+    src = descs[name].source
+    assert "st_gen_list" in src and "st_gen_thp" in src and "st_gen_expand" in src
+
+
+@pytest.mark.parametrize("name", sorted(CASES))
+def test_generated_kernels_on_the_cpu(descs, oracle, tmp_path, name):
+    if CLANG is None:
+        pytest.skip("no clang++ for the host build")
+    text, dims, red, params, pred, unique_of = CASES[name]
+    d = descs[name]
+    box = int(np.prod(dims))
+    src = tmp_path / "generated.hip"
+    src.write_text(d.source)
+    exe = str(tmp_path / "driver")
+    cmd = [CLANG, "-std=c++17", "-O1", "-g", "-fsanitize=address", "-fno-omit-frame-pointer",
+           '-DGEN_SRC="%s"' % src, "-I", EMUL, "-x", "c++", os.path.join(EMUL, "desc_driver.cpp"), "-o", exe]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr[-3000:]
+    Bc = W.uniform(701, max(d.count, 1))[: d.count]
+    Cd = W.uniform(702, box).reshape(dims)
+    d.table().tofile(str(tmp_path / "table.i32"))
+    Bc.tofile(str(tmp_path / "bc.f32"))
+    Cd.tofile(str(tmp_path / "c.f32"))
+    r = subprocess.run([exe, str(tmp_path), str(d.count), str(box), str(len(dims)), str(d.runs), str(dims[-1])],
+                       capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0 and "rc=0" in r.stdout, r.stderr[-3000:]
+    lst = np.fromfile(str(tmp_path / "list.i32"), dtype=np.int32).reshape(-1, len(dims))
+    assert np.array_equal(lst, oracle.struct_enumerate(dims, pred))
+    thp = np.fromfile(str(tmp_path / "thp.f32"), dtype=np.float32)
+    assert np.array_equal(thp, oracle.struct_thp(Bc, Cd, dims, pred).astype(np.float32))
+    ex = np.fromfile(str(tmp_path / "expand.f32"), dtype=np.float32).reshape(dims)
+    ref = oracle.struct_expand(Bc, dims, pred, unique_of)
+    assert np.array_equal(ex.view(np.uint32), ref.view(np.uint32))

@@ -1,0 +1,106 @@
+"""Descriptor-driven structures on the GPU: kernels generated for a textual unique set / redundancy map,
+compiled with hiprtc and run through the C ABI, against brute force over the index box (small cases) and
+against the hand-written kernels of the same structures (full sizes)."""
+import sys
+
+import numpy as np
+import pytest
+
+import st_workloads as W
+from test_desc import CASES
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def st():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    import paper_2211_10482_amd as lib
+    lib.lib()
+    return lib
+
+
+def dev(a):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.mark.parametrize("name", sorted(CASES))
+def test_generated_kernels_small(st, oracle, name):
+    say("descriptor", name)
+    text, dims, red, params, pred, unique_of = CASES[name]
+    d = st.Descriptor(text, dims, red, **params)
+    lst = oracle.struct_enumerate(dims, pred)
+    assert np.array_equal(d.list().cpu().numpy(), lst)
+    Bc = W.uniform(711, max(d.count, 4))
+    Cd = W.uniform(712, int(np.prod(dims))).reshape(dims)
+    got = d.thp(dev(Bc), dev(Cd)).cpu().numpy()[: d.count]
+    assert np.array_equal(got, oracle.struct_thp(Bc[: d.count], Cd, dims, pred).astype(np.float32))
+    ex = d.expand(dev(Bc)).cpu().numpy()
+    ref = oracle.struct_expand(Bc[: d.count], dims, pred, unique_of)
+    assert np.array_equal(ex.view(np.uint32), ref.view(np.uint32))
+    d.close()
+
+
+def test_generated_against_handwritten_sym3(st, oracle):
+    n = 64
+    say("descriptor sym3 n=%d against st_expand_sym / the closed-form unrank" % n)
+    d = st.Descriptor("T(i,j,k): (0<=i<n)*(i<=j<n)*(j<=k<n)", (n, n, n), "sort", n=n)
+    assert d.count == st.count_sym3(n)
+    assert np.array_equal(d.list().cpu().numpy(), oracle.list_sym3(n).astype(np.int32))
+    Sc = dev(W.uniform(721, d.count))
+    got = d.expand(Sc).cpu().numpy()
+    assert np.array_equal(got.view(np.uint32), st.expand_sym(Sc, n, 3).cpu().numpy().view(np.uint32))
+    assert np.array_equal(got.view(np.uint32), oracle.expand_sym(Sc.cpu().numpy(), n, 3).view(np.uint32))
+    d.close()
+
+
+def test_generated_against_handwritten_sym4(st, oracle):
+    n = 24
+    d = st.Descriptor("Q(i,j,k,l): (0<=i<=j<n)*(j<=k<=l<n)", (n,) * 4, "sort", n=n)
+    assert d.count == st.count_sym4(n)
+    assert np.array_equal(d.list().cpu().numpy(), oracle.list_sym4(n).astype(np.int32))
+    Sc = dev(W.uniform(722, d.count))
+    got = d.expand(Sc).cpu().numpy()
+    assert np.array_equal(got.view(np.uint32), oracle.expand_sym(Sc.cpu().numpy(), n, 4).view(np.uint32))
+    d.close()
+
+
+def test_generated_against_handwritten_band_full(st, oracle):
+    cfg = W.CONFIGS[3]
+    n, w, nl = cfg["n"], cfg["w"], cfg["nl"]
+    say("descriptor band n=%d w=%d nl=%d against st_expand_band / the band oracle" % (n, w, nl))
+    d = st.Descriptor("B(i,j,l): (0<=i<n)*(i-w<=j<=i+w)*(0<=l<m)", (n, n, nl), n=n, w=w, m=nl)
+    assert d.count == cfg["band_pairs"] * nl and d.runs == cfg["band_pairs"]
+    Tb, _ = W.ttm_inputs(cfg["band_pairs"], nl, cfg["R"])
+    Tbd = dev(Tb.reshape(-1))
+    got = d.expand(Tbd).cpu().numpy()
+    ref = oracle.dense_band(Tb, n, w, nl).astype(np.float32)
+    assert np.array_equal(got.view(np.uint32), ref.view(np.uint32))
+    assert np.array_equal(got, st.expand_band(Tbd, n, w, nl).cpu().numpy())
+    # THP over the band against a dense operand: every in-band fibre times the matching fibre of C
+    Cd = W.uniform(731, n * n * nl).reshape(n, n, nl)
+    thp = d.thp(Tbd, dev(Cd)).cpu().numpy().reshape(-1, nl)
+    pairs = oracle.list_band(n, w).astype(np.int64)
+    ref = oracle.thp_full(Tb.reshape(-1, nl), Cd[pairs[:, 0], pairs[:, 1]])
+    assert np.array_equal(thp, ref.astype(np.float32))
+    d.close()
+
+
+def test_generated_against_handwritten_upper_cube(st, oracle):
+    n, nl = 200, 64
+    d = st.Descriptor("B(i,j,l): (0<=i<n)*(i<=j<n)*(0<=l<m)", (n, n, nl), n=n, m=nl)
+    pairs = st.count_struct(st.STRUCT_UPPER, n, n)
+    assert d.count == pairs * nl
+    Bc = W.uniform(741, pairs * nl).reshape(pairs, nl)
+    Cd = W.uniform(742, n * n * nl).reshape(n, n, nl)
+    got = d.thp(dev(Bc.reshape(-1)), dev(Cd)).cpu().numpy().reshape(pairs, nl)
+    hand = st.thp_struct(st.STRUCT_UPPER, dev(Bc), dev(Cd)).cpu().numpy()
+    assert np.array_equal(got, hand)
+    d.close()
