@@ -402,6 +402,21 @@ def test_mttkrp_all_ones(st, n, R):
     assert rel_err(got, ref) <= TOL
 
 
+def test_mttkrp_one_item_per_pair(st, oracle):
+    """n = 496 (31 blocks): the smallest size with one unchunked item per block pair."""
+    n, R = 496, 48
+    say("mttkrp n=%d R=%d" % (n, R))
+    Tc, B = W.mttkrp_inputs(n, R, oracle.count_sym3(n), "normal", config_index=4)
+    got = st.mttkrp_sym3(dev(Tc), dev(B)).cpu().numpy()
+    rows = np.array([0, 7, 16, 100, 239, 240, 241, 255, 256, 300, 479, 480, 495], dtype=np.int64)
+    ref = oracle.mttkrp_sym3(Tc, B, rows=rows)
+    err = float(np.abs(got[rows] - ref).max() / np.abs(ref).max())
+    say("  norm-wise error on the sampled rows %.3e" % err)
+    assert err <= TOL
+    got2 = st.mttkrp_sym3(dev(Tc), dev(B)).cpu().numpy()
+    assert np.array_equal(got, got2)
+
+
 def test_mttkrp_full(st, oracle):
     cfg = W.CONFIGS[4]
     n, R = cfg["n"], cfg["R"]
