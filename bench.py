@@ -222,6 +222,28 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    # the same calls back to back (operands that fit the last-level cache stay in it): reported beside the
+    # step's figures, which see cold operands because a step touches more than the cache holds
+    warm = {}
+    ba = torch.randn((2048, 2048), **f32)
+    bc = torch.empty_like(ba)
+    for name, f in calls:
+        f()
+        torch.cuda.synchronize()
+        # keep the GPU busy (a few small matrix products, 48 MB in all) while the timed calls are enqueued,
+        # so that the events see kernels running back to back, not the host's launch latency
+        for _ in range(6):
+            torch.mm(ba, ba, out=bc)
+        evs = []
+        for _ in range(5):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            f()
+            e1.record()
+            evs.append((e0, e1))
+        torch.cuda.synchronize()
+        warm[name] = float(np.median([a.elapsed_time(b) for a, b in evs]))
+
     wl = workloads()
     kernels = {}
     for name, _ in calls:
@@ -231,7 +253,7 @@ def main():
         gbs = w["bytes"] / (ms * 1e-3) / 1e9
         frac = gbs / HBM_PEAK_GBS if w["bound"] == "hbm" else gflops / 1e3 / MFMA_FP32_PEAK_TFLOPS
         kernels[name] = dict(ms=round(ms, 5), unique_gflops=round(gflops, 2), alg_gbs=round(gbs, 2),
-                             bound=w["bound"], frac=round(frac, 4))
+                             bound=w["bound"], frac=round(frac, 4), warm_ms=round(warm[name], 5))
     total_flops = sum(w["flops"] for w in wl.values())
     value = total_flops / (ms_per_step * 1e-3) / 1e9
 

@@ -287,6 +287,15 @@ st_status st_desc_thp(st_desc *desc, const void *table, const float *Bc, const f
                       void *stream);
 st_status st_desc_expand(st_desc *desc, const void *table, const float *Tc, float *T, void *stream);
 
+/* TTM of the kernel table along the LAST variable of a descriptor that leaves it
+ * free (every run is a whole fibre, e.g. any structure on (i,j) of B(i,j,l)):
+ *     Ac(run, r) = sum_l Bc(run, l) * U(l, r)
+ * Bc is [st_desc_runs][dims[last]], U is dims[last] x R, Ac is [st_desc_runs][R]:
+ * the output keeps the structure of the other variables (product and projection
+ * inference rules).  Runs on the matrix cores through the kernels of st_ttm_band;
+ * ST_ERR_UNSUPPORTED when the last variable is bounded by the structure. */
+st_status st_desc_ttm(st_desc *desc, const float *Bc, const float *U, float *Ac, int R, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -74,6 +74,7 @@ SIGNATURES = {
     "st_desc_list": (_I32, [_P, _P, _P, _P]),
     "st_desc_thp": (_I32, [_P, _P, _P, _P, _P, _P]),
     "st_desc_expand": (_I32, [_P, _P, _P, _P, _P]),
+    "st_desc_ttm": (_I32, [_P, _P, _P, _P, _I32, _P]),
 }
 
 # structures of the kernel table (values of include/structtensor.h)
@@ -428,3 +429,12 @@ class Descriptor:
         self._call(lib().st_desc_expand(self._h, self._tab(), _dev_f32(Tc, "Tc"), _dev_f32(T, "T"), _stream()),
                    "st_desc_expand")
         return T
+
+    def ttm(self, Bc, U, Ac=None):
+        torch = _torch()
+        R = U.shape[1]
+        if Ac is None:
+            Ac = torch.empty((max(self.runs, 1), R), dtype=torch.float32, device=U.device)
+        self._call(lib().st_desc_ttm(self._h, _dev_f32(Bc, "Bc"), _dev_f32(U, "U"), _dev_f32(Ac, "Ac"), R, _stream()),
+                   "st_desc_ttm")
+        return Ac[:self.runs]

@@ -742,6 +742,24 @@ st_status st_desc_thp(st_desc *desc, const void *table, const float *Bc, const f
     return launch_generated(*D, 1, (unsigned)((D->nruns + 3) / 4), args, (hipStream_t)stream);
 }
 
+st_status st_desc_ttm(st_desc *desc, const float *Bc, const float *U, float *Ac, int R, void *stream)
+{
+    if (!desc || !Bc || !U || !Ac) return ST_ERR_NULL;
+    Desc *D = reinterpret_cast<Desc *>(desc);
+    if (D->source.empty() || R < 1) return ST_ERR_SHAPE;
+    const int last = D->d - 1;
+    // the contracted (last) variable must be free: every run is a whole fibre
+    if (D->d < 2 || !D->lo[last].empty() || !D->hi[last].empty() || D->first[last] != 0 ||
+        D->last[last] != D->dims[last] - 1)
+        return ST_ERR_UNSUPPORTED;
+    if (!aligned16(Bc) || !aligned16(U) || !aligned16(Ac)) return ST_ERR_ALIGN;
+    const int64_t rows = D->nruns, nl = D->dims[last];
+    if (nl * (int64_t)R > ((int64_t)1 << 31)) return ST_ERR_UNSUPPORTED;
+    size_t tb = (size_t)rows * nl * 4, ub = (size_t)nl * R * 4, yb = (size_t)rows * R * 4;
+    if (overlap(Ac, yb, Bc, tb) || overlap(Ac, yb, U, ub)) return ST_ERR_SHAPE;
+    return launch_ttm(Bc, U, Ac, rows, (int)nl, R, nullptr, (hipStream_t)stream);
+}
+
 st_status st_desc_expand(st_desc *desc, const void *table, const float *Tc, float *T, void *stream)
 {
     if (!desc || !table || !Tc || !T) return ST_ERR_NULL;

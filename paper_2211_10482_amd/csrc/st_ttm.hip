@@ -373,13 +373,17 @@ __global__ __launch_bounds__(256) void ttm_plain_kernel(const float *__restrict_
 
 size_t ttm_workspace(int, int, int, int) { return 0; }
 
-// whether a workgroup of the current device may hold 160 KB of LDS
+// whether a workgroup of the current device may hold 160 KB of LDS (asked once per device)
 static bool lds_budget_160k()
 {
+    static int cached[64] = {0};                       // 0 unknown, 1 yes, 2 no
     int dev = 0, v = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return false;
-    if (hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess) return false;
-    return v >= 160 * 1024;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return false;
+    if (cached[dev] == 0) {
+        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess) return false;
+        cached[dev] = v >= 160 * 1024 ? 1 : 2;
+    }
+    return cached[dev] == 1;
 }
 
 st_status launch_ttm(const float *Tc, const float *U, float *Yc, int64_t rows, int nl, int R, void *,

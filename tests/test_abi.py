@@ -148,6 +148,9 @@ def test_descriptor_errors():
     assert L.st_desc_expand(h, P, None, P + 0x10000, None) == NULL
     assert L.st_desc_expand(h, P, P + 0x10000, P + 0x10010, None) == SHAPE                # buffers overlap
     assert L.st_desc_table(h, None) == NULL
+    assert L.st_desc_ttm(h, P, None, P + 0x10000, 4, None) == NULL
+    assert L.st_desc_ttm(h, P, P + 0x10000, P + 0x20000, 4, None) == UNSUPPORTED   # last variable is bounded by i <= j
+    assert L.st_desc_ttm(h, P, P + 0x10000, P + 0x20000, 0, None) == SHAPE
     assert L.st_desc_count(None) == -1
     L.st_desc_destroy(h)
     L.st_desc_destroy(None)

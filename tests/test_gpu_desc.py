@@ -104,3 +104,47 @@ def test_generated_against_handwritten_upper_cube(st, oracle):
     hand = st.thp_struct(st.STRUCT_UPPER, dev(Bc), dev(Cd)).cpu().numpy()
     assert np.array_equal(got, hand)
     d.close()
+
+
+@pytest.mark.parametrize("name,R", [("band", 16), ("diag", 5), ("fixed_j", 32), ("upper_cube", 48)])
+def test_descriptor_ttm_small(st, oracle, name, R):
+    say("descriptor ttm", name)
+    text, dims, red, params, pred, _ = CASES[name]
+    d = st.Descriptor(text, dims, red, **params)
+    nl = dims[-1]
+    lst = oracle.struct_enumerate(dims, pred)
+    Bc = W.uniform(751, d.count)
+    U = W.uniform(752, nl * R).reshape(nl, R)
+    B = np.zeros(dims, dtype=np.float32)
+    B[tuple(lst[:, v] for v in range(len(dims)))] = Bc            # zero-filled dense operand
+    full = oracle.ttm_full(B, U)                                   # dense definition
+    heads = lst[::nl, :-1]                                         # one (i,j) per run, in packed order
+    ref = full[heads[:, 0], heads[:, 1]]
+    mask = np.ones(dims[:2], dtype=bool)
+    mask[heads[:, 0], heads[:, 1]] = False
+    assert not full[mask].any()                                    # the output keeps the structure of (i,j)
+    got = d.ttm(dev(Bc.reshape(-1, nl)), dev(U)).cpu().numpy()
+    assert got.shape == ref.shape
+    assert float(np.abs(got - ref).max() / np.abs(ref).max()) <= 1e-4
+    d.close()
+
+
+def test_descriptor_ttm_needs_a_free_last_variable(st):
+    d = st.Descriptor("T(i,j,k): (0<=i<n)*(i<=j<n)*(j<=k<n)", (8, 8, 8), "sort", n=8)
+    import torch
+    z = torch.zeros(4096, device="cuda")
+    with pytest.raises(st.StructTensorError):
+        d.ttm(z[:d.count], z[:64].reshape(8, 8))
+    d.close()
+
+
+def test_descriptor_ttm_band_full(st, oracle):
+    cfg = W.CONFIGS[3]
+    n, w, nl, R = cfg["n"], cfg["w"], cfg["nl"], cfg["R"]
+    d = st.Descriptor("B(i,j,l): (0<=i<n)*(i-w<=j<=i+w)*(0<=l<m)", (n, n, nl), n=n, w=w, m=nl)
+    Tb, U = W.ttm_inputs(cfg["band_pairs"], nl, R)
+    got = d.ttm(dev(Tb), dev(U)).cpu().numpy()
+    ref = oracle.ttm_band(Tb, U, n, w)
+    assert float(np.abs(got - ref).max() / np.abs(ref).max()) <= 1e-4
+    assert np.array_equal(got, st.ttm_band(dev(Tb), dev(U), n, w).cpu().numpy())
+    d.close()
