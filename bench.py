@@ -283,6 +283,13 @@ def main():
             ("expand_sym_order4_n64", lambda: st.expand_sym(Sc4, n5, 4, S=S4),
              dict(flops=0, bytes=4 * (pent + n5 ** 4), bound="hbm")),
         ]
+        S1c, S2c, S3c = torch.empty(tri(n5), **f32), torch.empty(tet(n5), **f32), torch.empty(pent, **f32)
+        wsc = torch.empty(max(16, st.workspace_bytes("covar_pr2", N=N5, n=n5)), dtype=torch.uint8, device=dev)
+        extra += [
+            ("covar_pr2_N2e6_n64", lambda: st.covar_pr2(X, S=(S1c, S2c, S3c), ws=wsc),
+             dict(flops=N5 * (2 * tri(n5) + 2 * tet(n5) + tri(n5) + 2 * pent + tri(n5)),
+                  bytes=4 * (3 * N5 * n5 + tri(n5) + tet(n5) + pent), bound="alu")),
+        ]
         # the kernel table's structures at the size of the band workload (512 x 512 x 512, R = 64)
         nt, Rt = c3["n"], c3["R"]
         up_pairs = st.count_struct(st.STRUCT_UPPER, nt, nt)

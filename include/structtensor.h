@@ -166,6 +166,19 @@ st_status st_moment2_sym(const float *X, int64_t N, int n, float *Sc, int accumu
 st_status st_moment4_sym(const float *X, int64_t N, int n, float *Sc, int accumulate,
                          void *ws, size_t ws_bytes, void *stream);
 
+/* Covariance of degree-2 polynomial regression over N samples, creation and
+ * addition, in the semi-ring form of the end-to-end experiment: the degree-2,
+ * degree-3 and degree-4 interaction terms M1 = f (x) f, M2 = f (x) vec(f (x) f)
+ * and M3 = vec(f (x) f) (x) vec(f (x) f) are kept apart, each with its unique
+ * entries only (for n = 4 features: 10 + 20 + 35 = 65 values instead of 400).
+ * One call = st_moment2_sym, st_moment3_sym and st_moment4_sym on the same X,
+ * enqueued on `stream` in that order with one shared workspace
+ * (st_covar_pr2_workspace).  S1, S2, S3 have st_count_sym2/3/4(n) entries;
+ * n <= 256. */
+size_t st_covar_pr2_workspace(int64_t N, int n);
+st_status st_covar_pr2(const float *X, int64_t N, int n, float *S1, float *S2, float *S3, int accumulate,
+                       void *ws, size_t ws_bytes, void *stream);
+
 /* Reconstruction through the redundancy map (Property 5:
  * T(x) = T_C(x) + T_R(x,x') * T_C(x')).  order 2: S(i,j) = Sc[rank2(min,max)]
  * (class S: i' = j, j' = i for j < i); order 3: S(i,j,k) = Sc[rank3(sorted

@@ -8,6 +8,7 @@ the binding's functions raises.
 """
 from .binding import (  # noqa: F401
     Descriptor,
+    covar_pr2,
     MTTKRP_FIXED_I,
     MTTKRP_FIXED_IK,
     MTTKRP_FIXED_K,

@@ -75,6 +75,8 @@ SIGNATURES = {
     "st_desc_thp": (_I32, [_P, _P, _P, _P, _P, _P]),
     "st_desc_expand": (_I32, [_P, _P, _P, _P, _P]),
     "st_desc_ttm": (_I32, [_P, _P, _P, _P, _I32, _P]),
+    "st_covar_pr2_workspace": (_SZ, [_I64, _I32]),
+    "st_covar_pr2": (_I32, [_P, _I64, _I32, _P, _P, _P, _I32, _P, _SZ, _P]),
 }
 
 # structures of the kernel table (values of include/structtensor.h)
@@ -208,6 +210,8 @@ def workspace_bytes(kernel: str, **kw) -> int:
         return int(L.st_moment4_sym_workspace(kw["N"], kw["n"]))
     if kernel == "moment2_sym":
         return int(L.st_moment2_sym_workspace(kw["N"], kw["n"]))
+    if kernel == "covar_pr2":
+        return int(L.st_covar_pr2_workspace(kw["N"], kw["n"]))
     if kernel == "ttm_struct":
         return int(L.st_ttm_struct_workspace(kw["structure"], kw["ni"], kw["nj"], kw["nl"], kw["R"]))
     if kernel == "mttkrp_fixed":
@@ -286,6 +290,21 @@ def _moment(order, X, Sc, accumulate, ws):
     _check(getattr(lib(), "st_" + name)(px, N, n, _dev_f32(Sc, "Sc"), 1 if accumulate else 0, pws, wsb, _stream()),
            "st_" + name)
     return Sc
+
+
+def covar_pr2(X, S=None, accumulate=False, ws=None):
+    """(S1, S2, S3): unique entries of the degree-2, -3 and -4 interaction terms of the samples X."""
+    torch = _torch()
+    N, n = X.shape
+    if S is None:
+        if accumulate:
+            raise ValueError("accumulate needs existing outputs")
+        S = tuple(torch.empty(c(n), dtype=torch.float32, device=X.device) for c in (count_sym2, count_sym3, count_sym4))
+    ws, pws, wsb = _workspace(workspace_bytes("covar_pr2", N=N, n=n), X, ws)
+    px = _dev_f32(X, "X") if N > 0 else C.c_void_p(X.data_ptr() if X.numel() else 0)
+    _check(lib().st_covar_pr2(px, N, n, _dev_f32(S[0], "S1"), _dev_f32(S[1], "S2"), _dev_f32(S[2], "S3"),
+                              1 if accumulate else 0, pws, wsb, _stream()), "st_covar_pr2")
+    return S
 
 
 def moment2_sym(X, Sc=None, accumulate=False, ws=None):

@@ -306,6 +306,37 @@ st_status st_moment4_sym(const float *X, int64_t N, int n, float *Sc, int accumu
     return launch_moment4(X, N, n, Sc, accumulate, ws, (hipStream_t)stream);
 }
 
+size_t st_covar_pr2_workspace(int64_t N, int n)
+{
+    if (N < 0 || n < 1 || n > 256) return 0;
+    size_t a = moment2_workspace(N, n), b = moment3_workspace(N, n), c = moment4_workspace(N, n);
+    return a > b ? (a > c ? a : c) : (b > c ? b : c);
+}
+
+st_status st_covar_pr2(const float *X, int64_t N, int n, float *S1, float *S2, float *S3, int accumulate, void *ws,
+                       size_t ws_bytes, void *stream)
+{
+    if (!S1 || !S2 || !S3 || (N > 0 && !X)) return ST_ERR_NULL;
+    if (N < 0 || n < 1 || (accumulate != 0 && accumulate != 1)) return ST_ERR_SHAPE;
+    if (n > 256) return ST_ERR_UNSUPPORTED;
+    if (!aligned16(S1) || !aligned16(S2) || !aligned16(S3) || (X && !aligned16(X))) return ST_ERR_ALIGN;
+    const size_t b1 = (size_t)count_sym2<i64>(n) * 4, b2 = (size_t)count_sym3<i64>(n) * 4,
+                 b3 = (size_t)count_sym4<i64>(n) * 4, xb = (size_t)N * n * 4;
+    if (overlap(S1, b1, S2, b2) || overlap(S1, b1, S3, b3) || overlap(S2, b2, S3, b3)) return ST_ERR_SHAPE;
+    if (N > 0 && (overlap(S1, b1, X, xb) || overlap(S2, b2, X, xb) || overlap(S3, b3, X, xb))) return ST_ERR_SHAPE;
+    size_t need = st_covar_pr2_workspace(N, n);
+    ST_REQUIRE_WS(need);
+    if (need > 0 && (overlap(ws, need, S1, b1) || overlap(ws, need, S2, b2) || overlap(ws, need, S3, b3) ||
+                     (N > 0 && overlap(ws, need, X, xb))))
+        return ST_ERR_SHAPE;
+    // the three kernels run one after the other on the stream, so they can share the workspace
+    st_status rc = launch_moment2(X, N, n, S1, accumulate, ws, (hipStream_t)stream);
+    if (rc != ST_OK) return rc;
+    rc = launch_moment3(X, N, n, S2, accumulate, ws, (hipStream_t)stream);
+    if (rc != ST_OK) return rc;
+    return launch_moment4(X, N, n, S3, accumulate, ws, (hipStream_t)stream);
+}
+
 st_status st_expand_sym(const float *Sc, float *S, int n, int order, void *stream)
 {
     if (!Sc || !S) return ST_ERR_NULL;

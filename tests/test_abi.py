@@ -154,3 +154,18 @@ def test_descriptor_errors():
     assert L.st_desc_count(None) == -1
     L.st_desc_destroy(h)
     L.st_desc_destroy(None)
+
+
+def test_covar_pr2_errors():
+    L = st.lib()
+    a, b, c, x = P, P + 0x1000000, P + 0x2000000, P + 0x3000000
+    assert L.st_covar_pr2(x, 10, 4, None, b, c, 0, None, 0, None) == NULL
+    assert L.st_covar_pr2(None, 10, 4, a, b, c, 0, None, 0, None) == NULL
+    assert L.st_covar_pr2(x, 10, 300, a, b, c, 0, None, 0, None) == UNSUPPORTED
+    assert L.st_covar_pr2(x, 10, 4, a, b, c, 2, None, 0, None) == SHAPE
+    assert L.st_covar_pr2(x, 10, 4, a, a, c, 0, None, 0, None) == SHAPE               # outputs alias
+    assert L.st_covar_pr2(x, 5000, 64, a, b, c, 0, None, 0, None) == WORKSPACE
+    need = L.st_covar_pr2_workspace(5000, 64)
+    assert need == max(L.st_moment2_sym_workspace(5000, 64), L.st_moment3_sym_workspace(5000, 64),
+                       L.st_moment4_sym_workspace(5000, 64)) > 0
+    assert L.st_covar_pr2_workspace(10, 300) == 0

@@ -380,6 +380,33 @@ def test_moment4_full(st, oracle):
     assert np.all(np.isfinite(got))
 
 
+# ------------------------------------------- degree-2 polynomial-regression covariance
+@pytest.mark.parametrize("N,n", [(300, 4), (1000, 13), (500, 64), (90, 70)])
+def test_covar_pr2(st, oracle, N, n):
+    """(M1, M2, M3) in one call, as two half-batches (creation and addition), against the dense definitions;
+    n = 4 has the paper's 65 distinct elements, 6 and 13 are the feature counts of its end-to-end data sets."""
+    say("covar_pr2 N=%d n=%d" % (N, n))
+    X = W.normal(451, N * n).reshape(N, n)
+    h = N // 2
+    S = st.covar_pr2(dev(X[:h]))
+    st.covar_pr2(dev(X[h:]), S=S, accumulate=True)
+    if n == 4:
+        assert sum(t.numel() for t in S) == 65
+    ref1 = oracle.moment2_dense(X)[np.triu_indices(n)]
+    ref2 = oracle.moment3_entries(X, oracle.list_sym3(n))
+    ref3 = oracle.moment4_entries(X, oracle.list_sym4(n))
+    for got, ref in zip(S, (ref1, ref2, ref3)):
+        assert got.numel() == ref.size
+        assert rel_err(got.cpu().numpy(), ref) <= TOL
+    # the same three results from the three separate entry points, bit for bit
+    A = (st.moment2_sym(dev(X[:h])), st.moment3_sym(dev(X[:h])), st.moment4_sym(dev(X[:h])))
+    st.moment2_sym(dev(X[h:]), Sc=A[0], accumulate=True)
+    st.moment3_sym(dev(X[h:]), Sc=A[1], accumulate=True)
+    st.moment4_sym(dev(X[h:]), Sc=A[2], accumulate=True)
+    for got, sep in zip(S, A):
+        assert np.array_equal(got.cpu().numpy(), sep.cpu().numpy())
+
+
 # ---------------------------------------------------------------------- mttkrp
 @pytest.mark.parametrize("n,R", [(1, 1), (5, 4), (16, 16), (17, 3), (32, 5), (40, 16), (64, 16), (96, 32),
                                  (100, 20), (130, 64), (48, 80), (160, 20), (208, 7)])
