@@ -380,9 +380,201 @@ static inline u32 plain_slices(int64_t N)
     return (u32)(s < 1 ? 1 : s > 16 ? 16 : s);
 }
 
+
+// ---- tile path: any n <= 256, plain fp32 vector arithmetic ------------------------------------
+// For feature counts other than the 64 the matrix-core kernel above is built around.  The indices are
+// cut into blocks of four; a block triple I <= J <= K (unranked with the closed form of the entries
+// themselves, on n/4 blocks) is owned by ONE lane with its 4 x 4 x 4 accumulators in registers: per
+// sample the lane reads the three 16-byte groups x_I, x_J, x_K from the staged sample row and does
+// 16 + 64 multiply(-add)s (a_ij = x_i x_j, acc_ijk += a_ij x_k).  Only the block diagonals are padded.
+// Samples go through a double-buffered LDS chunk per workgroup (rows padded to 4*ceil(n/4) floats,
+// loads of chunk c+2 in flight while chunk c is consumed); the sample range is cut into slices
+// (grid.y) so that the grid fills the chip; with fewer than 64 block triples (n <= 24) a wave holds every
+// triple several times and the copies share out the samples of a chunk.  Slice partials -> second kernel
+// adds them in a fixed order, keeps i <= j <= k < n and scatters through rank3.  No atomics.
+constexpr int M3T_LPT = 8;                         // 16-byte pieces of a chunk per thread
+constexpr int M3T_WGTARGET = 1024;                 // workgroups to aim for
+
+struct M3TPlan {
+    u32 nb4, np, nbt, threads, gx, ch, S;
+    u32 sub;                 // fewer than 64 block triples: a wave holds `sub` copies, copy q takes the samples = q mod sub
+    int64_t slice;
+};
+static inline M3TPlan m3t_plan(int64_t N, int n)
+{
+    M3TPlan p;
+    p.nb4 = ((u32)n + 3u) / 4u;
+    p.np = 4u * p.nb4;
+    p.nbt = (u32)count_sym3<int64_t>(p.nb4);
+    p.threads = p.nbt >= 256u ? 256u : ((p.nbt + 63u) / 64u) * 64u;
+    p.sub = p.nbt < 64u ? 64u / p.nbt : 1u;
+    p.gx = (p.nbt + p.threads - 1u) / p.threads;
+    u32 ch = (u32)M3T_LPT * p.threads * 4u / p.np;           // samples whose pieces fit the threads' registers
+    ch = ch > 64u ? 64u : ch & ~7u;
+    p.ch = ch;
+    int64_t S = (M3T_WGTARGET + p.gx - 1) / p.gx;
+    const int64_t smax = (N + p.ch - 1) / p.ch;
+    if (S > smax) S = smax;
+    if (S > 1024) S = 1024;
+    if (S < 1) S = 1;
+    p.slice = ((N + S - 1) / S + p.ch - 1) / p.ch * p.ch;    // whole chunks
+    p.S = (u32)((N + p.slice - 1) / p.slice);
+    return p;
+}
+
+__device__ __forceinline__ void m3t_load_chunk(f32x4 (&r)[M3T_LPT], const float *__restrict__ X, int64_t s0,
+                                               int64_t s_end, u32 n, u32 np4, u32 pieces, u32 tid, u32 nthreads)
+{
+#pragma unroll
+    for (int k = 0; k < M3T_LPT; ++k) {
+        const u32 j = min(tid + nthreads * (u32)k, pieces - 1u), smp = j / np4, c0 = 4u * (j - smp * np4);
+        const int64_t s = s0 + smp, sc = s < s_end ? s : s_end - 1;
+        const float *row = X + sc * (int64_t)n;
+#pragma unroll
+        for (u32 g = 0; g < 4; ++g) r[k][g] = row[c0 + g < n ? c0 + g : n - 1u];
+    }
+}
+
+__device__ __forceinline__ void m3t_store_chunk(const f32x4 (&r)[M3T_LPT], float *__restrict__ buf, int64_t s0,
+                                                int64_t s_end, u32 n, u32 np4, u32 pieces, u32 tid, u32 nthreads)
+{
+#pragma unroll
+    for (int k = 0; k < M3T_LPT; ++k) {
+        const u32 j = tid + nthreads * (u32)k, smp = j / np4, c0 = 4u * (j - smp * np4);
+        if (j >= pieces) continue;
+        const bool row_ok = s0 + smp < s_end;
+        f32x4 v;
+#pragma unroll
+        for (u32 g = 0; g < 4; ++g) v[g] = (row_ok && c0 + g < n) ? r[k][g] : 0.f;
+        *reinterpret_cast<f32x4 *>(buf + (size_t)j * 4u) = v;       // [sample][np] = piece order
+    }
+}
+
+// grid.x = block triples / blockDim.x, grid.y = sample slices; dynamic LDS: 2 chunks of ch x np floats.
+// SUBBED (fewer than 64 block triples, one wave per workgroup): the wave holds every triple `sub` times,
+// copy q takes the samples = q (mod sub) of a chunk, and the copies are added through LDS in a fixed
+// order before the slice partial is written.
+template <bool SUBBED>
+__global__ __launch_bounds__(256) void moment3_tile_kernel(const float *__restrict__ X, int64_t N, u32 n, u32 nb4,
+                                                          u32 nbt, u32 ch, u32 sub, int64_t slice,
+                                                          float *__restrict__ ws)
+{
+    extern __shared__ float lds[];
+    float *m3t_lds = lds;
+    const u32 tid = threadIdx.x, nthreads = blockDim.x, np = 4u * nb4, np4 = nb4;
+    const u32 pieces = ch * np4, chunk_f = ch * np;
+    // SUBBED: lane = (copy, triple)
+    const u32 copy = SUBBED ? tid / nbt : 0u;
+    const u32 bt = SUBBED ? tid - copy * nbt : blockIdx.x * nthreads + tid;
+    const bool active = SUBBED ? copy < sub : bt < nbt;
+    u32 I, J, K;
+    unrank_sym3<u32>(nb4, min(bt, nbt - 1u), I, J, K);
+    const u32 oi = 4u * I, oj = 4u * J, ok = 4u * K;
+
+    const int64_t s_begin = (int64_t)blockIdx.y * slice;
+    const int64_t s_end = s_begin + slice < N ? s_begin + slice : N;
+    const int64_t nchunks = s_end > s_begin ? (s_end - s_begin + ch - 1) / ch : 0;
+
+    float acc[64];
+#pragma unroll
+    for (int e = 0; e < 64; ++e) acc[e] = 0.f;
+
+    if (nchunks > 0) {
+        f32x4 r[M3T_LPT];
+        m3t_load_chunk(r, X, s_begin, s_end, n, np4, pieces, tid, nthreads);
+        m3t_store_chunk(r, m3t_lds, s_begin, s_end, n, np4, pieces, tid, nthreads);
+        if (nchunks > 1) m3t_load_chunk(r, X, s_begin + ch, s_end, n, np4, pieces, tid, nthreads);
+        __syncthreads();
+        for (int64_t c = 0; c < nchunks; ++c) {
+            const u32 cb = (u32)(c & 1);
+            // registers hold chunk c+1: park it in the other buffer (its readers finished before the
+            // barrier that ended the previous iteration), then put chunk c+2 in flight
+            if (c + 1 < nchunks)
+                m3t_store_chunk(r, m3t_lds + (cb ^ 1u) * chunk_f, s_begin + (c + 1) * ch, s_end, n, np4, pieces, tid,
+                                nthreads);
+            if (c + 2 < nchunks) m3t_load_chunk(r, X, s_begin + (c + 2) * ch, s_end, n, np4, pieces, tid, nthreads);
+            __builtin_amdgcn_sched_barrier(0);
+            const float *row = m3t_lds + cb * chunk_f + (SUBBED && active ? copy : 0u) * np;
+            const u32 sstep = SUBBED ? sub : 1u, rstep = sstep * np;
+#pragma unroll 2
+            for (u32 smp = SUBBED && active ? copy : 0u; smp < ch; smp += sstep, row += rstep) {
+                const f32x4 xi = *reinterpret_cast<const f32x4 *>(row + oi);
+                const f32x4 xj = *reinterpret_cast<const f32x4 *>(row + oj);
+                const f32x4 xk = *reinterpret_cast<const f32x4 *>(row + ok);
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const float a = xi[i] * xj[j];
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) acc[(i * 4 + j) * 4 + k] += a * xk[k];
+                    }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            __syncthreads();
+        }
+    }
+
+    if constexpr (SUBBED) {
+        // add the copies: lane -> LDS row (stride 65: conflict free), then thread e adds accumulator e of
+        // every triple over the copies in ascending order (the loop above ended with a barrier)
+        float *red = m3t_lds;
+#pragma unroll
+        for (int e = 0; e < 64; ++e) red[tid * 65u + e] = active ? acc[e] : 0.f;
+        __syncthreads();
+        for (u32 b = 0; b < nbt; ++b) {
+            float v = 0.f;
+            for (u32 c = 0; c < sub; ++c) v += red[(c * nbt + b) * 65u + tid];
+            ws[((size_t)blockIdx.y * nbt + b) * 64u + tid] = v;
+        }
+    } else if (active) {
+        f32x4 *dst = reinterpret_cast<f32x4 *>(ws + ((size_t)blockIdx.y * nbt + bt) * 64u);
+#pragma unroll
+        for (int e = 0; e < 16; ++e) dst[e] = (f32x4){acc[4 * e], acc[4 * e + 1], acc[4 * e + 2], acc[4 * e + 3]};
+    }
+}
+
+// A block owns 16 raw accumulators (block triple, i, j, k) and cuts the S slice partials into 16 groups
+// (slices g, g+16, ... ascending inside a group, groups ascending); stores the entries of the unique set.
+__global__ __launch_bounds__(256) void moment3_tile_reduce_kernel(const float *__restrict__ ws, u32 S, u32 n,
+                                                                 u32 nb4, u32 nbt, float *__restrict__ Sc,
+                                                                 int accumulate)
+{
+    __shared__ float part[16][16];
+    const u32 a = threadIdx.x & 15u, g = threadIdx.x >> 4;
+    const u32 t = blockIdx.x * 16u + a;                  // < nbt * 64
+    const size_t stride = (size_t)nbt * 64u;
+    float s = 0.f;
+    if (t < nbt * 64u) {
+#pragma unroll 4
+        for (u32 y = g; y < S; y += 16u) s += ws[(size_t)y * stride + t];
+    }
+    part[g][a] = s;
+    __syncthreads();
+    if (g != 0u || t >= nbt * 64u) return;
+    float v = 0.f;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) v += part[q][a];
+    const u32 bt = t >> 6, e = t & 63u;
+    u32 I, J, K;
+    unrank_sym3<u32>(nb4, bt, I, J, K);
+    const u32 i = 4u * I + (e >> 4), j = 4u * J + ((e >> 2) & 3u), k = 4u * K + (e & 3u);
+    if (!(i <= j && j <= k && k < n)) return;
+    const u32 p = rank_sym3<u32>(n, i, j, k);
+    Sc[p] = accumulate ? Sc[p] + v : v;
+}
+
+constexpr int M3T_NMAX = 256;                      // rows of up to 1 KB in LDS
+// the matrix-core kernel pads every n <= 64 to 64 features: the tile path wins below about 40
+static inline bool m3_use_tiles(int n) { return n <= 40 || (n > 64 && n <= M3T_NMAX); }
+
 size_t moment3_workspace(int64_t N, int n)
 {
     if (N == 0) return 0;
+    if (m3_use_tiles(n)) {
+        const M3TPlan p = m3t_plan(N, n);
+        return (size_t)p.S * p.nbt * 64u * sizeof(float);
+    }
     if (n <= 64) return (size_t)m3_groups(N) * M3_ACC * sizeof(float);
     return (size_t)plain_slices(N) * (size_t)count_sym3<int64_t>(n) * sizeof(float);
 }
@@ -396,6 +588,31 @@ st_status launch_moment3(const float *X, int64_t N, int n, float *Sc, int accumu
         return launch_status();
     }
     float *wsf = static_cast<float *>(ws);
+    if (m3_use_tiles(n)) {
+        const M3TPlan p = m3t_plan(N, n);
+        size_t lds_bytes = (size_t)2u * p.ch * p.np * sizeof(float);                // at most 64 KB
+        const bool subbed = p.sub > 1u;
+        if (subbed && lds_bytes < 64u * 65u * sizeof(float)) lds_bytes = 64u * 65u * sizeof(float);
+        static bool attr = false;
+        if (!attr) {
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(moment3_tile_kernel<false>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024) != hipSuccess ||
+                hipFuncSetAttribute(reinterpret_cast<const void *>(moment3_tile_kernel<true>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024) != hipSuccess)
+                return ST_ERR_LAUNCH;
+            attr = true;
+        }
+        if (subbed)
+            hipLaunchKernelGGL(moment3_tile_kernel<true>, dim3(p.gx, p.S), dim3(p.threads), lds_bytes, s, X, N, (u32)n,
+                               p.nb4, p.nbt, p.ch, p.sub, p.slice, wsf);
+        else
+            hipLaunchKernelGGL(moment3_tile_kernel<false>, dim3(p.gx, p.S), dim3(p.threads), lds_bytes, s, X, N, (u32)n,
+                               p.nb4, p.nbt, p.ch, p.sub, p.slice, wsf);
+        if (hipGetLastError() != hipSuccess) return ST_ERR_LAUNCH;
+        hipLaunchKernelGGL(moment3_tile_reduce_kernel, dim3((p.nbt * 64u + 15u) / 16u), dim3(256), 0, s, wsf, p.S,
+                           (u32)n, p.nb4, p.nbt, Sc, accumulate);
+        return launch_status();
+    }
     if (n <= 64) {
         int64_t chunk = m3_chunk(N);
         u32 G = m3_groups(N);

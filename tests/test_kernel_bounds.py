@@ -29,8 +29,10 @@ CASES = {
     "TTM": [(8632, 512, 64), (16590, 128, 48), (1090, 256, 16), (208, 512, 32), (1, 64, 16), (777, 48, 32),
             (50, 7, 5), (33, 16, 256), (16385, 512, 64), (40001, 64, 16), (33000, 256, 48)],
     # moment3: N n accumulate  (n = 64 is the MFMA path, others the plain path)
+    # (n <= 40 and 64 < n <= 256: the tile path; 40 < n <= 64: the MFMA path; larger n: the plain path)
     "MOMENT3": [(5000, 64, 0), (4097, 64, 1), (63, 64, 0), (100000, 64, 0), (1000, 20, 0), (3, 5, 1),
-                (700, 70, 0)],
+                (700, 70, 0), (100, 1, 0), (3000, 13, 1), (257, 40, 0), (500, 48, 0), (130, 129, 0), (70, 200, 0),
+                (33, 256, 0), (20, 300, 0)],
     # moment2: N n accumulate  (n <= 64 is the MFMA path, others the plain path)
     "MOMENT2": [(5000, 64, 0), (4097, 64, 1), (3, 64, 0), (100000, 64, 0), (1000, 20, 0), (3, 5, 1), (700, 70, 0),
                 (50, 300, 0)],
