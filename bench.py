@@ -290,6 +290,17 @@ def main():
              dict(flops=N5 * (2 * tri(n5) + 2 * tet(n5) + tri(n5) + 2 * pent + tri(n5)),
                   bytes=4 * (3 * N5 * n5 + tri(n5) + tet(n5) + pent), bound="alu")),
         ]
+        # the same covariance at 200 features (the widest the paper's comparison systems reach), 10,000 samples
+        nf, Nf = 200, 10_000
+        pent_f = nf * (nf + 1) * (nf + 2) * (nf + 3) // 24
+        Xf = torch.randn((Nf, nf), **f32)
+        Sf = (torch.empty(tri(nf), **f32), torch.empty(tet(nf), **f32), torch.empty(pent_f, **f32))
+        wsf = torch.empty(max(16, st.workspace_bytes("covar_pr2", N=Nf, n=nf)), dtype=torch.uint8, device=dev)
+        extra += [
+            ("covar_pr2_N1e4_n200", lambda: st.covar_pr2(Xf, S=Sf, ws=wsf),
+             dict(flops=Nf * (2 * tri(nf) + 2 * tet(nf) + tri(nf) + 2 * pent_f + tri(nf)),
+                  bytes=4 * (3 * Nf * nf + tri(nf) + tet(nf) + pent_f), bound="alu")),
+        ]
         # the kernel table's structures at the size of the band workload (512 x 512 x 512, R = 64)
         nt, Rt = c3["n"], c3["R"]
         up_pairs = st.count_struct(st.STRUCT_UPPER, nt, nt)

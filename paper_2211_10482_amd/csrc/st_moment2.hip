@@ -19,7 +19,8 @@
 // Algorithmic traffic: 4n bytes per sample, read once.  At n = 64 the matrix cores
 // need 10 MFMAs per four samples, about the same time as the HBM stream.
 //
-// General path (n > 64): one thread per unique entry and sample slice.
+// 64 < n <= 1024: 8 x 8 register tiles per lane on the vector ALUs (tile path below); larger n: one
+// thread per unique entry and sample slice.
 #include "st_common.h"
 #include "st_index.h"
 
@@ -231,10 +232,162 @@ static inline u32 m2_plain_slices(int64_t N, int n)
     return (u32)(s < 1 ? 1 : s);
 }
 
+// ---- tile path: 64 < n <= 1024, plain fp32 vector arithmetic --------------------------------
+// Blocks of eight indices; a block pair I <= J is owned by one lane with its 8 x 8 accumulators in
+// registers: per sample four 16-byte LDS reads and 64 multiply-adds.  Samples go through a
+// double-buffered LDS chunk per workgroup (rows padded to 8*ceil(n/8) floats), the sample range is cut
+// into slices (grid.y); slice partials -> second kernel adds them in a fixed order, keeps i <= j < n
+// and scatters through rank2.  No atomics.
+constexpr int M2T_THREADS = 256;
+constexpr int M2T_LPT = 8;                         // 16-byte pieces of a chunk per thread
+constexpr int M2T_NMAX = 1024;
+constexpr int M2T_WGTARGET = 1024;
+
+struct M2TPlan {
+    u32 nb8, np, nbp, gx, ch, S;
+    int64_t slice;
+};
+static inline M2TPlan m2t_plan(int64_t N, int n)
+{
+    M2TPlan p;
+    p.nb8 = ((u32)n + 7u) / 8u;
+    p.np = 8u * p.nb8;
+    p.nbp = (u32)count_sym2<int64_t>(p.nb8);
+    p.gx = (p.nbp + M2T_THREADS - 1u) / M2T_THREADS;
+    u32 ch = (u32)(M2T_LPT * M2T_THREADS * 4) / p.np;        // samples whose pieces fit the threads' registers
+    p.ch = ch > 64u ? 64u : ch & ~7u;                        // n <= 1024: at least 8
+    int64_t S = (M2T_WGTARGET + p.gx - 1) / p.gx;
+    const int64_t smax = (N + p.ch - 1) / p.ch;
+    if (S > smax) S = smax;
+    if (S > 512) S = 512;
+    if (S < 1) S = 1;
+    p.slice = ((N + S - 1) / S + p.ch - 1) / p.ch * p.ch;    // whole chunks
+    p.S = (u32)((N + p.slice - 1) / p.slice);
+    return p;
+}
+
+__device__ __forceinline__ void m2t_load_chunk(f32x4 (&r)[M2T_LPT], const float *__restrict__ X, int64_t s0,
+                                               int64_t s_end, u32 n, u32 np4, u32 pieces, u32 tid)
+{
+#pragma unroll
+    for (int k = 0; k < M2T_LPT; ++k) {
+        const u32 j = min(tid + (u32)M2T_THREADS * k, pieces - 1u), smp = j / np4, c0 = 4u * (j - smp * np4);
+        const int64_t s = s0 + smp, sc = s < s_end ? s : s_end - 1;
+        const float *row = X + sc * (int64_t)n;
+#pragma unroll
+        for (u32 g = 0; g < 4; ++g) r[k][g] = row[c0 + g < n ? c0 + g : n - 1u];
+    }
+}
+
+__device__ __forceinline__ void m2t_store_chunk(const f32x4 (&r)[M2T_LPT], float *__restrict__ buf, int64_t s0,
+                                                int64_t s_end, u32 n, u32 np4, u32 pieces, u32 tid)
+{
+#pragma unroll
+    for (int k = 0; k < M2T_LPT; ++k) {
+        const u32 j = tid + (u32)M2T_THREADS * k, smp = j / np4, c0 = 4u * (j - smp * np4);
+        if (j >= pieces) continue;
+        const bool row_ok = s0 + smp < s_end;
+        f32x4 v;
+#pragma unroll
+        for (u32 g = 0; g < 4; ++g) v[g] = (row_ok && c0 + g < n) ? r[k][g] : 0.f;
+        *reinterpret_cast<f32x4 *>(buf + (size_t)j * 4u) = v;
+    }
+}
+
+// grid.x = block pairs / 256, grid.y = sample slices; dynamic LDS: 2 chunks of ch x np floats
+__global__ __launch_bounds__(M2T_THREADS) void moment2_tile_kernel(const float *__restrict__ X, int64_t N, u32 n,
+                                                                u32 nb8, u32 nbp, u32 ch, int64_t slice,
+                                                                float *__restrict__ ws)
+{
+    extern __shared__ float lds[];
+    const u32 tid = threadIdx.x, np = 8u * nb8, np4 = 2u * nb8;
+    const u32 pieces = ch * np4, chunk_f = ch * np;
+    const u32 bp = blockIdx.x * (u32)M2T_THREADS + tid;
+    u32 I, J;
+    unrank_sym2<u32>(nb8, min(bp, nbp - 1u), I, J);
+    const u32 oi = 8u * I, oj = 8u * J;
+
+    const int64_t s_begin = (int64_t)blockIdx.y * slice;
+    const int64_t s_end = s_begin + slice < N ? s_begin + slice : N;
+    const int64_t nchunks = s_end > s_begin ? (s_end - s_begin + ch - 1) / ch : 0;
+
+    float acc[64];
+#pragma unroll
+    for (int e = 0; e < 64; ++e) acc[e] = 0.f;
+
+    if (nchunks > 0) {
+        f32x4 r[M2T_LPT];
+        m2t_load_chunk(r, X, s_begin, s_end, n, np4, pieces, tid);
+        m2t_store_chunk(r, lds, s_begin, s_end, n, np4, pieces, tid);
+        if (nchunks > 1) m2t_load_chunk(r, X, s_begin + ch, s_end, n, np4, pieces, tid);
+        __syncthreads();
+        for (int64_t c = 0; c < nchunks; ++c) {
+            const u32 cb = (u32)(c & 1);
+            if (c + 1 < nchunks) m2t_store_chunk(r, lds + (cb ^ 1u) * chunk_f, s_begin + (c + 1) * ch, s_end, n, np4, pieces, tid);
+            if (c + 2 < nchunks) m2t_load_chunk(r, X, s_begin + (c + 2) * ch, s_end, n, np4, pieces, tid);
+            __builtin_amdgcn_sched_barrier(0);
+            const float *row = lds + cb * chunk_f;
+#pragma unroll 2
+            for (u32 smp = 0; smp < ch; ++smp, row += np) {
+                const f32x4 a0 = *reinterpret_cast<const f32x4 *>(row + oi), a1 = *reinterpret_cast<const f32x4 *>(row + oi + 4u);
+                const f32x4 b0 = *reinterpret_cast<const f32x4 *>(row + oj), b1 = *reinterpret_cast<const f32x4 *>(row + oj + 4u);
+                const float xa[8] = {a0[0], a0[1], a0[2], a0[3], a1[0], a1[1], a1[2], a1[3]};
+                const float xb[8] = {b0[0], b0[1], b0[2], b0[3], b1[0], b1[1], b1[2], b1[3]};
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) acc[i * 8 + j] += xa[i] * xb[j];
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            __syncthreads();
+        }
+    }
+
+    if (bp < nbp) {
+        f32x4 *dst = reinterpret_cast<f32x4 *>(ws + ((size_t)blockIdx.y * nbp + bp) * 64u);
+#pragma unroll
+        for (int e = 0; e < 16; ++e) dst[e] = (f32x4){acc[4 * e], acc[4 * e + 1], acc[4 * e + 2], acc[4 * e + 3]};
+    }
+}
+
+// A block owns 16 raw accumulators (block pair, i, j) and cuts the S slice partials into 16 groups
+// (slices g, g+16, ... ascending inside a group, groups ascending); stores the entries of the unique set.
+__global__ __launch_bounds__(256) void moment2_tile_reduce_kernel(const float *__restrict__ ws, u32 S, u32 n,
+                                                                 u32 nb8, u32 nbp, float *__restrict__ Sc,
+                                                                 int accumulate)
+{
+    __shared__ float part[16][16];
+    const u32 a = threadIdx.x & 15u, g = threadIdx.x >> 4;
+    const u32 t = blockIdx.x * 16u + a;                  // < nbp * 64
+    const size_t stride = (size_t)nbp * 64u;
+    float s = 0.f;
+    if (t < nbp * 64u) {
+#pragma unroll 4
+        for (u32 y = g; y < S; y += 16u) s += ws[(size_t)y * stride + t];
+    }
+    part[g][a] = s;
+    __syncthreads();
+    if (g != 0u || t >= nbp * 64u) return;
+    float v = 0.f;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) v += part[q][a];
+    const u32 bp = t >> 6, e = t & 63u;
+    u32 I, J;
+    unrank_sym2<u32>(nb8, bp, I, J);
+    const u32 i = 8u * I + (e >> 3), j = 8u * J + (e & 7u);
+    if (!(i <= j && j < n)) return;
+    const u32 p = rank_sym2<u32>(n, i, j);
+    Sc[p] = accumulate ? Sc[p] + v : v;
+}
+
 size_t moment2_workspace(int64_t N, int n)
 {
     if (N == 0) return 0;
     if (n <= 64) return (size_t)m2_groups(N) * M2_ACC * sizeof(float);
+    if (n <= M2T_NMAX) {
+        const M2TPlan p = m2t_plan(N, n);
+        return (size_t)p.S * p.nbp * 64u * sizeof(float);
+    }
     return (size_t)m2_plain_slices(N, n) * (size_t)count_sym2<int64_t>(n) * sizeof(float);
 }
 
@@ -256,6 +409,23 @@ st_status launch_moment2(const float *X, int64_t N, int n, float *Sc, int accumu
         if (hipGetLastError() != hipSuccess) return ST_ERR_LAUNCH;
         hipLaunchKernelGGL(moment2_reduce_kernel, dim3(M2_ACC / 64), dim3(256), 0, s, wsf, G, (u32)n, Sc,
                            accumulate);
+        return launch_status();
+    }
+    if (n <= M2T_NMAX) {
+        const M2TPlan p = m2t_plan(N, n);
+        const size_t lds_bytes = (size_t)2u * p.ch * p.np * sizeof(float);          // at most 64 KB
+        static bool attr = false;
+        if (!attr) {
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(moment2_tile_kernel),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024) != hipSuccess)
+                return ST_ERR_LAUNCH;
+            attr = true;
+        }
+        hipLaunchKernelGGL(moment2_tile_kernel, dim3(p.gx, p.S), dim3(M2T_THREADS), lds_bytes, s, X, N, (u32)n, p.nb8,
+                           p.nbp, p.ch, p.slice, wsf);
+        if (hipGetLastError() != hipSuccess) return ST_ERR_LAUNCH;
+        hipLaunchKernelGGL(moment2_tile_reduce_kernel, dim3((p.nbp * 64u + 15u) / 16u), dim3(256), 0, s, wsf, p.S,
+                           (u32)n, p.nb8, p.nbp, Sc, accumulate);
         return launch_status();
     }
     u32 SY = m2_plain_slices(N, n);

@@ -21,7 +21,7 @@
 // Algorithmic work per sample: one multiply-add per unique quadruple (+ the pair
 // products).  Bound by the fp32 vector rate.
 //
-// General path (64 < n <= 256): one thread per unique entry over all samples.
+// 64 < n <= 256: the same tiles with sample rows of 4*ceil(n/4) floats in dynamic LDS.
 #include "st_common.h"
 #include "st_index.h"
 
@@ -136,6 +136,98 @@ __global__ __launch_bounds__(M4_THREADS) void moment4_tile_kernel(const float *_
     }
 }
 
+// ---- tile path for 64 < n <= 256: the same lanes and register tiles, sample rows of 4*ceil(n/4) floats ----
+// (dynamic LDS: two chunks of `ch` samples; a chunk is as many samples as the workgroup's threads can
+// hold in flight, four 16-byte pieces each)
+__device__ __forceinline__ void m4g_load_chunk(f32x4 (&r)[M4_LPT], const float *__restrict__ X, int64_t s0,
+                                               int64_t s_end, u32 n, u32 np4, u32 pieces, u32 tid)
+{
+#pragma unroll
+    for (int k = 0; k < M4_LPT; ++k) {
+        const u32 j = min(tid + (u32)M4_THREADS * k, pieces - 1u), smp = j / np4, c0 = 4u * (j - smp * np4);
+        const int64_t s = s0 + smp, sc = s < s_end ? s : s_end - 1;
+        const float *row = X + sc * (int64_t)n;
+#pragma unroll
+        for (u32 g = 0; g < 4; ++g) r[k][g] = row[c0 + g < n ? c0 + g : n - 1u];
+    }
+}
+
+__device__ __forceinline__ void m4g_store_chunk(const f32x4 (&r)[M4_LPT], float *__restrict__ buf, int64_t s0,
+                                                int64_t s_end, u32 n, u32 np4, u32 pieces, u32 tid)
+{
+#pragma unroll
+    for (int k = 0; k < M4_LPT; ++k) {
+        const u32 j = tid + (u32)M4_THREADS * k, smp = j / np4, c0 = 4u * (j - smp * np4);
+        if (j >= pieces) continue;
+        const bool row_ok = s0 + smp < s_end;
+        f32x4 v;
+#pragma unroll
+        for (u32 g = 0; g < 4; ++g) v[g] = (row_ok && c0 + g < n) ? r[k][g] : 0.f;
+        *reinterpret_cast<f32x4 *>(buf + (size_t)j * 4u) = v;
+    }
+}
+
+__global__ __launch_bounds__(M4_THREADS) void moment4_tile_general_kernel(const float *__restrict__ X, int64_t N,
+                                                                        u32 n, u32 nb4, u32 nbq, u32 ch,
+                                                                        int64_t slice, float *__restrict__ ws)
+{
+    extern __shared__ float lds[];
+    const u32 tid = threadIdx.x, ii = tid & 3u, np4 = nb4, np = 4u * nb4;
+    const u32 pieces = ch * np4, chunk_f = ch * np;
+    const u32 bq = blockIdx.x * 64u + (tid >> 2);
+    u32 I, J, K, L;
+    unrank_sym4<u32>(nb4, min(bq, nbq - 1u), I, J, K, L);
+    const u32 oi = 4u * I + ii, oj = 4u * J, ok = 4u * K, ol = 4u * L;
+
+    const int64_t s_begin = (int64_t)blockIdx.y * slice;
+    const int64_t s_end = s_begin + slice < N ? s_begin + slice : N;
+    const int64_t nchunks = s_end > s_begin ? (s_end - s_begin + ch - 1) / ch : 0;
+
+    float acc[64];
+#pragma unroll
+    for (int e = 0; e < 64; ++e) acc[e] = 0.f;
+
+    if (nchunks > 0) {
+        f32x4 r[M4_LPT];
+        m4g_load_chunk(r, X, s_begin, s_end, n, np4, pieces, tid);
+        m4g_store_chunk(r, lds, s_begin, s_end, n, np4, pieces, tid);
+        if (nchunks > 1) m4g_load_chunk(r, X, s_begin + ch, s_end, n, np4, pieces, tid);
+        __syncthreads();
+        for (int64_t c = 0; c < nchunks; ++c) {
+            const u32 cb = (u32)(c & 1);
+            if (c + 1 < nchunks) m4g_store_chunk(r, lds + (cb ^ 1u) * chunk_f, s_begin + (c + 1) * ch, s_end, n, np4, pieces, tid);
+            if (c + 2 < nchunks) m4g_load_chunk(r, X, s_begin + (c + 2) * ch, s_end, n, np4, pieces, tid);
+            __builtin_amdgcn_sched_barrier(0);
+            const float *row = lds + cb * chunk_f;
+#pragma unroll 2
+            for (u32 smp = 0; smp < ch; ++smp, row += np) {
+                const float xi = row[oi];
+                const f32x4 xj = *reinterpret_cast<const f32x4 *>(row + oj);
+                const f32x4 xk = *reinterpret_cast<const f32x4 *>(row + ok);
+                const f32x4 xl = *reinterpret_cast<const f32x4 *>(row + ol);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const float a = xi * xj[j];
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        const float b = a * xk[k];
+#pragma unroll
+                        for (int l = 0; l < 4; ++l) acc[(j * 4 + k) * 4 + l] += b * xl[l];
+                    }
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            __syncthreads();
+        }
+    }
+
+    if (bq < nbq) {
+        f32x4 *dst = reinterpret_cast<f32x4 *>(ws + (((size_t)blockIdx.y * nbq + bq) * 4u + ii) * 64u);
+#pragma unroll
+        for (int e = 0; e < 16; ++e) dst[e] = (f32x4){acc[4 * e], acc[4 * e + 1], acc[4 * e + 2], acc[4 * e + 3]};
+    }
+}
+
 // One thread per raw accumulator (block quadruple, lane, j, k, l): adds the S slice
 // partials in ascending order and stores the entries of the unique set.
 __global__ __launch_bounds__(256) void moment4_reduce_kernel(const float *__restrict__ ws, u32 S, u32 n, u32 nb4,
@@ -156,22 +248,6 @@ __global__ __launch_bounds__(256) void moment4_reduce_kernel(const float *__rest
     Sc[p] = accumulate ? Sc[p] + s : s;
 }
 
-// ---- general path -----------------------------------------------------------------
-__global__ __launch_bounds__(256) void moment4_plain_kernel(const float *__restrict__ X, int64_t N, u32 n,
-                                                           u32 count, float *__restrict__ Sc, int accumulate)
-{
-    u32 p = blockIdx.x * 256u + threadIdx.x;
-    if (p >= count) return;
-    u32 i, j, k, l;
-    unrank_sym4<u32>(n, p, i, j, k, l);
-    float s = 0.f;
-    for (int64_t q = 0; q < N; ++q) {
-        const float *row = X + q * (int64_t)n;
-        s += row[i] * row[j] * row[k] * row[l];
-    }
-    Sc[p] = accumulate ? Sc[p] + s : s;
-}
-
 __global__ __launch_bounds__(256) void moment4_zero_kernel(float *__restrict__ p, u32 count)
 {
     u32 t = blockIdx.x * 256u + threadIdx.x;
@@ -179,7 +255,7 @@ __global__ __launch_bounds__(256) void moment4_zero_kernel(float *__restrict__ p
 }
 
 struct M4Plan {
-    u32 nb4, nbq, gx, S;
+    u32 nb4, nbq, gx, S, ch;
     int64_t slice;
 };
 static inline M4Plan m4_plan(int64_t N, int n)
@@ -188,19 +264,22 @@ static inline M4Plan m4_plan(int64_t N, int n)
     p.nb4 = ((u32)n + 3u) / 4u;
     p.nbq = (u32)count_sym4<int64_t>(p.nb4);
     p.gx = (p.nbq + 63u) / 64u;
+    // samples per chunk: 64 up to n = 64; beyond, what the threads' 4 pieces each can hold (16 at n = 256)
+    p.ch = n <= 64 ? (u32)M4_CH : ((u32)(M4_LPT * M4_THREADS) / p.nb4) & ~3u;
+    if (p.ch > (u32)M4_CH) p.ch = (u32)M4_CH;
     int64_t S = (M4_WGTARGET + p.gx - 1) / p.gx;           // enough slices to fill the chip ...
-    int64_t smax = (N + M4_CH - 1) / M4_CH;                // ... each of at least one chunk
+    int64_t smax = (N + p.ch - 1) / p.ch;                  // ... each of at least one chunk
     if (S > smax) S = smax;
     if (S > 64) S = 64;
     if (S < 1) S = 1;
-    p.slice = ((N + S - 1) / S + M4_CH - 1) / M4_CH * M4_CH;   // whole chunks
+    p.slice = ((N + S - 1) / S + p.ch - 1) / p.ch * p.ch;      // whole chunks
     p.S = (u32)((N + p.slice - 1) / p.slice);
     return p;
 }
 
 size_t moment4_workspace(int64_t N, int n)
 {
-    if (N == 0 || n > 64) return 0;
+    if (N == 0) return 0;
     M4Plan p = m4_plan(N, n);
     return (size_t)p.S * p.nbq * 256u * sizeof(float);
 }
@@ -227,9 +306,24 @@ st_status launch_moment4(const float *X, int64_t N, int n, float *Sc, int accumu
                            accumulate);
         return launch_status();
     }
-    hipLaunchKernelGGL(moment4_plain_kernel, dim3((count + 255u) / 256u), dim3(256), 0, s, X, N, (u32)n, count, Sc,
-                       accumulate);
-    return launch_status();
+    {
+        const M4Plan p = m4_plan(N, n);
+        float *wsf = static_cast<float *>(ws);
+        const size_t lds_bytes = (size_t)2u * p.ch * 4u * p.nb4 * sizeof(float);      // at most 64 KB
+        static bool attr = false;
+        if (!attr) {
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(moment4_tile_general_kernel),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024) != hipSuccess)
+                return ST_ERR_LAUNCH;
+            attr = true;
+        }
+        hipLaunchKernelGGL(moment4_tile_general_kernel, dim3(p.gx, p.S), dim3(M4_THREADS), lds_bytes, s, X, N, (u32)n,
+                           p.nb4, p.nbq, p.ch, p.slice, wsf);
+        if (hipGetLastError() != hipSuccess) return ST_ERR_LAUNCH;
+        hipLaunchKernelGGL(moment4_reduce_kernel, dim3(p.nbq), dim3(256), 0, s, wsf, p.S, (u32)n, p.nb4, p.nbq, Sc,
+                           accumulate);
+        return launch_status();
+    }
 }
 
 }  // namespace st

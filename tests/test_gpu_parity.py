@@ -270,7 +270,7 @@ def test_moment3_full(st, oracle):
 
 # ---------------------------------------------------------------------- moment2 (M1)
 @pytest.mark.parametrize("N,n", [(1, 1), (7, 5), (100, 64), (4097, 64), (33, 64), (1000, 20), (5000, 63), (300, 70),
-                                 (64, 200)])
+                                 (64, 200), (700, 65), (90, 1024), (20, 1100)])
 def test_moment2_small(st, oracle, N, n):
     say("moment2 N=%d n=%d" % (N, n))
     X = W.normal(301, N * n).reshape(N, n)
@@ -316,7 +316,7 @@ def test_moment2_full(st, oracle):
 
 # ---------------------------------------------------------------------- moment4 (M3)
 @pytest.mark.parametrize("N,n", [(1, 1), (7, 5), (100, 16), (300, 64), (65, 64), (64, 64), (50, 20), (130, 63),
-                                 (40, 70)])
+                                 (40, 70), (70, 65), (33, 100)])
 def test_moment4_small(st, oracle, N, n):
     say("moment4 N=%d n=%d" % (N, n))
     X = W.normal(401, N * n).reshape(N, n)

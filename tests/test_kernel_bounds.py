@@ -33,11 +33,12 @@ CASES = {
     "MOMENT3": [(5000, 64, 0), (4097, 64, 1), (63, 64, 0), (100000, 64, 0), (1000, 20, 0), (3, 5, 1),
                 (700, 70, 0), (100, 1, 0), (3000, 13, 1), (257, 40, 0), (500, 48, 0), (130, 129, 0), (70, 200, 0),
                 (33, 256, 0), (20, 300, 0)],
-    # moment2: N n accumulate  (n <= 64 is the MFMA path, others the plain path)
+    # moment2: N n accumulate  (n <= 64: the MFMA path; n <= 1024: the tile path; beyond: the plain path)
     "MOMENT2": [(5000, 64, 0), (4097, 64, 1), (3, 64, 0), (100000, 64, 0), (1000, 20, 0), (3, 5, 1), (700, 70, 0),
-                (50, 300, 0)],
-    # moment4: N n accumulate  (n <= 64 is the tile path, others the plain path)
-    "MOMENT4": [(300, 64, 0), (65, 64, 1), (1, 64, 0), (200, 20, 0), (130, 63, 0), (3, 5, 1), (9, 70, 0)],
+                (50, 300, 0), (200, 65, 1), (40, 1024, 0), (9, 1030, 0)],
+    # moment4: N n accumulate  (n <= 64: static 64-column chunks; 64 < n <= 256: dynamic chunks of padded rows)
+    "MOMENT4": [(300, 64, 0), (65, 64, 1), (1, 64, 0), (200, 20, 0), (130, 63, 0), (3, 5, 1), (9, 70, 0),
+                (70, 65, 1), (3, 129, 0)],
     # expand: n order | n 10+kind w p0 count  (device unrank of kind 2, 3, 4 = band, 5 = sym4)
     "EXPAND": [(64, 3), (100, 2), (7, 3), (1, 2), (17, 4), (32, 4), (100, 12, 0, 17, 5000), (100, 13, 0, 17, 5000),
                (100, 14, 7, 17, 1000), (40, 15, 0, 17, 5000)],
