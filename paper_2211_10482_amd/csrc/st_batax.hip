@@ -1,9 +1,9 @@
 // y = beta * A^T (A x) for a packed upper-triangular A (unique set 0<=i<=j<n).
 //
-// One-pass kernel (n <= 8192).  The packed matrix is streamed from HBM once:
+// One-pass kernel (n <= 16384).  The packed matrix is streamed from HBM once:
 // a row has to stay on chip between its use in t_i = A(i,:) x and its use in
 // y += t_i A(i,:), so a workgroup of 1024 threads holds whole rows in
-// registers.  Thread `tid` owns the fixed columns 4*(tid + 1024 v) .. +3, v < 2, keeps
+// registers.  Thread `tid` owns the fixed columns 4*(tid + 1024 v) .. +3, v < 4, keeps
 // x and its partial y for those columns in registers for the whole kernel.
 // Rows are dealt to workgroups round-robin AND folded: a workgroup alternates
 // between a row i from the top half and its mirror image n-1-i from the bottom
@@ -20,7 +20,8 @@
 //
 // Algorithmic traffic: 4 bytes per stored entry, read once.
 //
-// General path (larger n): two plain passes (t = A x, then y = beta A^T t).
+// General path (larger n): two passes (t = A x, one wave per row; then y = beta A^T t in 64 row slices
+// whose partials are added in a fixed order).
 #include "st_common.h"
 #include "st_index.h"
 
@@ -35,7 +36,7 @@ typedef uint32_t u32;
 #define ST_BATAX_RB 4
 #endif
 constexpr int BT = ST_BATAX_BT;   // threads per workgroup
-constexpr int RB = ST_BATAX_RB;   // rows per batch
+constexpr int RB_SHORT = ST_BATAX_RB;   // rows per batch while a thread holds at most two column groups of a row
 constexpr int GMAX = 256;  // workgroups of the one-pass kernel (one per CU)
 
 struct __attribute__((packed, aligned(4))) f4u { float x, y, z, w; };
@@ -76,7 +77,7 @@ __device__ __forceinline__ u32 row_of_slot(u32 n, u32 g, u32 G, u32 q)
 // row start (the tail of the previous row, always inside the array for i >= 1),
 // groups entirely outside the row read position 0; mask_batch zeroes what does
 // not belong to the row.  Otherwise: guarded element loads.
-template <int V, bool FAST>
+template <int V, int RB, bool FAST>
 __device__ __forceinline__ void load_batch(float4 (&a)[RB][V], const float *__restrict__ Ap, u32 n,
                                            u32 g, u32 G, u32 q0, u32 tid)
 {
@@ -108,7 +109,7 @@ __device__ __forceinline__ void load_batch(float4 (&a)[RB][V], const float *__re
     }
 }
 
-template <int V>
+template <int V, int RB>
 __device__ __forceinline__ void mask_batch(float4 (&a)[RB][V], u32 n, u32 g, u32 G, u32 q0, u32 tid)
 {
 #pragma unroll
@@ -127,7 +128,7 @@ __device__ __forceinline__ void mask_batch(float4 (&a)[RB][V], u32 n, u32 g, u32
     }
 }
 
-template <int V>
+template <int V, int RB>
 __device__ __forceinline__ void process_batch(const float4 (&a)[RB][V], const float4 (&xs)[V],
                                               float4 (&ya)[V], float (*red)[RB][BT / 64], int pb,
                                               u32 lane, u32 wave)
@@ -167,7 +168,7 @@ __device__ __forceinline__ void process_batch(const float4 (&a)[RB][V], const fl
     }
 }
 
-template <int V, bool FAST>
+template <int V, int RB, bool FAST>
 __global__ __launch_bounds__(BT) void batax_onepass_kernel(const float *__restrict__ Ap,
                                                           const float *__restrict__ x,
                                                           float *__restrict__ part, u32 n, u32 npad,
@@ -181,7 +182,7 @@ __global__ __launch_bounds__(BT) void batax_onepass_kernel(const float *__restri
     const u32 nslots = (mid >= g) ? 2u * ((mid - g) / G + 1u) : 0u;
     const u32 nb = (nslots + RB - 1) / RB;
     float4 a0[RB][V], a1[RB][V];
-    load_batch<V, FAST>(a0, Ap, n, g, G, 0u, tid); // first rows go out before anything else
+    load_batch<V, RB, FAST>(a0, Ap, n, g, G, 0u, tid); // first rows go out before anything else
 
     // x for the owned columns: branch-free (index clamped, value selected), so these
     // loads overlap the first batch instead of serialising in front of it
@@ -200,15 +201,15 @@ __global__ __launch_bounds__(BT) void batax_onepass_kernel(const float *__restri
     }
 
     for (u32 b = 0; b < nb; b += 2) {
-        load_batch<V, FAST>(a1, Ap, n, g, G, RB * (b + 1), tid);
+        load_batch<V, RB, FAST>(a1, Ap, n, g, G, RB * (b + 1), tid);
         __builtin_amdgcn_sched_barrier(0);
-        mask_batch<V>(a0, n, g, G, RB * b, tid);
-        process_batch<V>(a0, xs, ya, red, 0, lane, wave);
+        mask_batch<V, RB>(a0, n, g, G, RB * b, tid);
+        process_batch<V, RB>(a0, xs, ya, red, 0, lane, wave);
         __builtin_amdgcn_sched_barrier(0);
-        load_batch<V, FAST>(a0, Ap, n, g, G, RB * (b + 2), tid);
+        load_batch<V, RB, FAST>(a0, Ap, n, g, G, RB * (b + 2), tid);
         __builtin_amdgcn_sched_barrier(0);
-        mask_batch<V>(a1, n, g, G, RB * (b + 1), tid);
-        process_batch<V>(a1, xs, ya, red, 1, lane, wave);
+        mask_batch<V, RB>(a1, n, g, G, RB * (b + 1), tid);
+        process_batch<V, RB>(a1, xs, ya, red, 1, lane, wave);
         __builtin_amdgcn_sched_barrier(0);
     }
 
@@ -271,19 +272,34 @@ __global__ __launch_bounds__(256) void batax_ax_kernel(const float *__restrict__
     if (lane == 0) t[i] = s;
 }
 
+// y partial of one row slice: thread j adds A(i,j) t_i over the rows i <= j of slice blockIdx.y (rows
+// ascending; the loads of a wave are contiguous in j)
+constexpr u32 ATY_SLICES = 64;
 __global__ __launch_bounds__(256) void batax_aty_kernel(const float *__restrict__ Ap,
-                                                       const float *__restrict__ t, float *__restrict__ y,
-                                                       u32 n, float beta)
+                                                       const float *__restrict__ t, float *__restrict__ part,
+                                                       u32 n, u32 npad)
+{
+    u32 j = blockIdx.x * 256u + threadIdx.x;
+    if (j >= n) return;
+    const u32 per = (n + ATY_SLICES - 1u) / ATY_SLICES, i0 = blockIdx.y * per, i1 = min(min(n, i0 + per), j + 1u);
+    float s = 0.f;
+#pragma unroll 4
+    for (u32 i = i0; i < i1; ++i) s += Ap[row_sym2<u32>(n, i) + (j - i)] * t[i];
+    part[(size_t)blockIdx.y * npad + j] = s;
+}
+
+__global__ __launch_bounds__(256) void batax_aty_reduce_kernel(const float *__restrict__ part, float *__restrict__ y,
+                                                              u32 n, u32 npad, float beta)
 {
     u32 j = blockIdx.x * 256u + threadIdx.x;
     if (j >= n) return;
     float s = 0.f;
-    for (u32 i = 0; i <= j; ++i) s += Ap[row_sym2<u32>(n, i) + (j - i)] * t[i];
+#pragma unroll 8
+    for (u32 q = 0; q < ATY_SLICES; ++q) s += part[(size_t)q * npad + j];
     y[j] = beta * s;
 }
 
-constexpr int NMAX_ONEPASS = 8192;          // rows of up to 32 KB stay in one workgroup's registers
-constexpr int VMAX = NMAX_ONEPASS / (4 * BT);
+constexpr int NMAX_ONEPASS = 16384;         // rows of up to 64 KB stay in one workgroup's registers
 
 static inline u32 onepass_grid(int n) { return (u32)(n < GMAX ? n : GMAX); }
 static inline u32 pad4(int n) { return ((u32)n + 3u) & ~3u; }
@@ -291,17 +307,19 @@ static inline u32 pad4(int n) { return ((u32)n + 3u) & ~3u; }
 size_t batax_workspace(int n)
 {
     if (n <= NMAX_ONEPASS) return (size_t)onepass_grid(n) * pad4(n) * sizeof(float);
-    return (size_t)pad4(n) * sizeof(float);
+    return (size_t)(1u + ATY_SLICES) * pad4(n) * sizeof(float);       // t, then the slice partials of y
 }
 
-template <int V>
+// V column groups per thread; a batch is RB_SHORT rows up to two groups, two rows at three, one row at four (the
+// registers of a 1024-thread workgroup hold that much twice)
+template <int V, int RB>
 static void launch_onepass(bool fast, u32 G, hipStream_t s, const float *Ap, const float *x, float *wsf, u32 un,
                            u32 npad)
 {
     if (fast)
-        hipLaunchKernelGGL((batax_onepass_kernel<V, true>), dim3(G), dim3(BT), 0, s, Ap, x, wsf, un, npad, G);
+        hipLaunchKernelGGL((batax_onepass_kernel<V, RB, true>), dim3(G), dim3(BT), 0, s, Ap, x, wsf, un, npad, G);
     else
-        hipLaunchKernelGGL((batax_onepass_kernel<V, false>), dim3(G), dim3(BT), 0, s, Ap, x, wsf, un, npad, G);
+        hipLaunchKernelGGL((batax_onepass_kernel<V, RB, false>), dim3(G), dim3(BT), 0, s, Ap, x, wsf, un, npad, G);
 }
 
 st_status launch_batax(const float *Ap, const float *x, float *y, int n, float beta, void *ws,
@@ -313,18 +331,22 @@ st_status launch_batax(const float *Ap, const float *x, float *y, int n, float b
         u32 G = onepass_grid(n), npad = pad4(n);
         const bool fast = (n % 4 == 0) && n >= 4;
         int V = (n + 4 * BT - 1) / (4 * BT);
-        if (V <= 1) launch_onepass<1>(fast, G, s, Ap, x, wsf, un, npad);
-        else if (V == 2) launch_onepass<2>(fast, G, s, Ap, x, wsf, un, npad);
-        else if (V <= 4) launch_onepass<(VMAX >= 4 ? 4 : VMAX)>(fast, G, s, Ap, x, wsf, un, npad);
-        else launch_onepass<VMAX>(fast, G, s, Ap, x, wsf, un, npad);
+        if (V <= 1) launch_onepass<1, RB_SHORT>(fast, G, s, Ap, x, wsf, un, npad);
+        else if (V == 2) launch_onepass<2, RB_SHORT>(fast, G, s, Ap, x, wsf, un, npad);
+        else if (V == 3) launch_onepass<3, 2>(fast, G, s, Ap, x, wsf, un, npad);
+        else launch_onepass<4, 1>(fast, G, s, Ap, x, wsf, un, npad);
         if (hipGetLastError() != hipSuccess) return ST_ERR_LAUNCH;
         hipLaunchKernelGGL(batax_reduce_kernel, dim3((npad / 4u + 7u) / 8u), dim3(256), 0, s, wsf, y, un, npad,
                            G, beta);
         return launch_status();
     }
+    const u32 npad = pad4(n);
     hipLaunchKernelGGL(batax_ax_kernel, dim3((un + 3u) / 4u), dim3(256), 0, s, Ap, x, wsf, un);
     if (hipGetLastError() != hipSuccess) return ST_ERR_LAUNCH;
-    hipLaunchKernelGGL(batax_aty_kernel, dim3((un + 255u) / 256u), dim3(256), 0, s, Ap, wsf, y, un, beta);
+    hipLaunchKernelGGL(batax_aty_kernel, dim3((un + 255u) / 256u, ATY_SLICES), dim3(256), 0, s, Ap, wsf, wsf + npad, un,
+                       npad);
+    if (hipGetLastError() != hipSuccess) return ST_ERR_LAUNCH;
+    hipLaunchKernelGGL(batax_aty_reduce_kernel, dim3((un + 255u) / 256u), dim3(256), 0, s, wsf + npad, y, un, npad, beta);
     return launch_status();
 }
 

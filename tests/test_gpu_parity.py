@@ -127,7 +127,7 @@ def test_expand_order2(st, oracle, n):
 
 
 # ----------------------------------------------------------------------- batax
-@pytest.mark.parametrize("n", [1, 2, 5, 33, 100, 257, 1000, 4096, 4100, 8200])
+@pytest.mark.parametrize("n", [1, 2, 5, 33, 100, 257, 1000, 4096, 4100, 8200, 9001, 12288, 16384, 16500])
 def test_batax_small(st, oracle, n):
     say("batax n=%d" % n)
     Ap = W.uniform(201, oracle.count_sym2(n))

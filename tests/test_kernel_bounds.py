@@ -22,8 +22,8 @@ CASES = {
     # mttkrp: n R  (multiples of 16 take the pair items, the others the gather items)
     "MTTKRP": [(1, 1), (5, 4), (16, 16), (17, 3), (32, 5), (48, 80), (64, 16), (100, 20), (160, 20),
                (208, 7), (256, 64), (512, 64)],
-    # batax: n  (one-pass kernel to 8192, two-pass beyond; n % 4 != 0 takes the guarded loads)
-    "BATAX": [(1,), (5,), (64,), (100,), (1000,), (1023,), (4096,), (8192,), (9001,)],
+    # batax: n  (one-pass kernel to 16384, two-pass beyond; n % 4 != 0 takes the guarded loads)
+    "BATAX": [(1,), (5,), (64,), (100,), (1000,), (1023,), (4096,), (8192,), (9001,), (12288,), (16384,), (16390,)],
     # ttm: rows nl R  (split-K shapes, the general MFMA path, the plain path)
     # (more than 16384 rows: the streaming split-K kernel)
     "TTM": [(8632, 512, 64), (16590, 128, 48), (1090, 256, 16), (208, 512, 32), (1, 64, 16), (777, 48, 32),
