@@ -19,9 +19,11 @@
 // quarter sums of a tile are added through LDS in a fixed order
 // ((q0+q2)+(q1+q3)).
 //
-// General MFMA path (nl % 16 == 0, R % 16 == 0, R <= 256): persistent workgroups,
-// a work unit is a 16-row x 16-column output tile over the whole l range, U is
-// staged in chunks of l.  Any other shape: one thread per output value.
+// General MFMA path (R <= 256): persistent workgroups, a work unit is a 16-row x
+// 16-column output tile over the whole l range, U is staged in chunks of l; sizes
+// that are not multiples of 16 are tiled over the next multiple with zeros staged
+// for what lies outside U and element loads of T.  R > 256: one thread per output
+// value.
 //
 // Algorithmic traffic per output row: 4*nl bytes read + 4*R written (+ U once).
 #include "st_common.h"
@@ -39,33 +41,67 @@ constexpr int MAXR = 4;       // row tiles a wave keeps accumulators for at once
 // A thread gathers the four rows t = 0..3 of one column (each of its loads is
 // coalesced along the column index across the wave) and writes them with one
 // conflict-free 16-byte LDS store.
-__device__ __forceinline__ void stage_u(float *lds, const float *__restrict__ U, u32 k0, u32 kc, u32 R,
+// RAGGED: nl and R are the true sizes, the tiling runs over their multiples of 16 (kc, CT) and what lies
+// outside U is staged as zeros.
+template <bool RAGGED>
+__device__ __forceinline__ void stage_u(float *lds, const float *__restrict__ U, u32 k0, u32 kc, u32 nl, u32 R,
                                         u32 CT, u32 tid, u32 nthreads)
 {
-    const u32 kq = kc / 4u;
-    for (u32 e = tid; e < kq * R; e += nthreads) {
-        u32 k4 = e / R, col = e - k4 * R;
-        const float *src = U + (size_t)(k0 + 4u * k4) * R + col;
-        float4 v = make_float4(src[0], src[R], src[2 * (size_t)R], src[3 * (size_t)R]);
+    const u32 kq = kc / 4u, Rp = CT * 16u;
+    for (u32 e = tid; e < kq * Rp; e += nthreads) {
+        u32 k4 = e / Rp, col = e - k4 * Rp;
+        const u32 l = k0 + 4u * k4;
+        float4 v;
+        if constexpr (RAGGED) {
+            const u32 cc = min(col, R - 1u);
+            float t[4];
+#pragma unroll
+            for (u32 q = 0; q < 4; ++q) {
+                const float x = U[(size_t)min(l + q, nl - 1u) * R + cc];
+                t[q] = (l + q < nl && col < R) ? x : 0.f;
+            }
+            v = make_float4(t[0], t[1], t[2], t[3]);
+        } else {
+            const float *src = U + (size_t)l * R + col;
+            v = make_float4(src[0], src[R], src[2 * (size_t)R], src[3 * (size_t)R]);
+        }
         u32 s = k4 >> 2, q = k4 & 3u, ct = col >> 4, c = col & 15u;
         *reinterpret_cast<float4 *>(lds + ((size_t)((s * CT + ct) * 64u + 16u * q + c)) * 4u) = v;
     }
 }
 
+// four values T(row, l .. l+3) of the A operand; RAGGED: element loads, zeros past the end of the row
+template <bool RAGGED>
+__device__ __forceinline__ float4 ttm_load_a(const float *__restrict__ rowp, u32 l, u32 nl)
+{
+    if constexpr (RAGGED) {
+        float t[4];
+#pragma unroll
+        for (u32 q = 0; q < 4; ++q) {
+            const float x = rowp[min(l + q, nl - 1u)];
+            t[q] = l + q < nl ? x : 0.f;
+        }
+        return make_float4(t[0], t[1], t[2], t[3]);
+    } else {
+        return *reinterpret_cast<const float4 *>(rowp + l);
+    }
+}
+
+template <bool RAGGED>
 __global__ __launch_bounds__(TW * 64) void ttm_mfma_kernel(const float *__restrict__ Tc,
                                                          const float *__restrict__ U, float *__restrict__ Yc,
                                                          u32 rows, u32 nl, u32 R, u32 KC)
 {
     extern __shared__ float lds[];
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
-    const u32 CT = R / 16u;
+    const u32 CT = (R + 15u) / 16u, nlp = (nl + 15u) & ~15u;   // the tiling runs over multiples of 16
     const u32 SLOTS = TW / CT;                 // row tiles in flight per workgroup
     const u32 slot = wave / CT, ct = wave - slot * CT;
     const bool active = slot < SLOTS;
     const u32 rtiles = (rows + 15u) / 16u;
     const u32 per_super = gridDim.x * SLOTS * MAXR;
     const u32 nsuper = (rtiles + per_super - 1u) / per_super;
-    const u32 nchunks = (nl + KC - 1u) / KC;
+    const u32 nchunks = (nlp + KC - 1u) / KC;
     const u32 lrow = lane & 15u, lq = lane >> 4;
 
     for (u32 sr = 0; sr < nsuper; ++sr) {
@@ -74,10 +110,10 @@ __global__ __launch_bounds__(TW * 64) void ttm_mfma_kernel(const float *__restri
         for (int r = 0; r < MAXR; ++r) acc[r] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
         for (u32 ch = 0; ch < nchunks; ++ch) {
-            const u32 k0 = ch * KC, kc = min(KC, nl - k0);
+            const u32 k0 = ch * KC, kc = min(KC, nlp - k0);
             if (!(nchunks == 1u && sr > 0u)) {
                 __syncthreads();
-                stage_u(lds, U, k0, kc, R, CT, tid, TW * 64u);
+                stage_u<RAGGED>(lds, U, k0, kc, nl, R, CT, tid, TW * 64u);
                 __syncthreads();
             }
             if (!active) continue;
@@ -87,13 +123,14 @@ __global__ __launch_bounds__(TW * 64) void ttm_mfma_kernel(const float *__restri
                 u32 rt = blockIdx.x + gridDim.x * (slot + SLOTS * ((u32)r + MAXR * sr));
                 if (rt >= rtiles) continue;
                 u32 row = min(rt * 16u + lrow, rows - 1u);          // clamp: tail rows are discarded
-                const float4 *ap = reinterpret_cast<const float4 *>(Tc + (size_t)row * nl + k0) + lq;
+                const float *rowp = Tc + (size_t)row * nl;
+                const u32 l0 = k0 + 4u * lq;
                 const f32x4 *bp = reinterpret_cast<const f32x4 *>(lds) + (size_t)ct * 64u + lane;
                 f32x4 c = acc[r];
                 u32 s = 0;
                 for (; s + 4u <= steps; s += 4u) {
-                    float4 a0 = ap[(s + 0u) * 4u], a1 = ap[(s + 1u) * 4u];
-                    float4 a2 = ap[(s + 2u) * 4u], a3 = ap[(s + 3u) * 4u];
+                    float4 a0 = ttm_load_a<RAGGED>(rowp, l0 + 16u * (s + 0u), nl), a1 = ttm_load_a<RAGGED>(rowp, l0 + 16u * (s + 1u), nl);
+                    float4 a2 = ttm_load_a<RAGGED>(rowp, l0 + 16u * (s + 2u), nl), a3 = ttm_load_a<RAGGED>(rowp, l0 + 16u * (s + 3u), nl);
                     f32x4 b0 = bp[(size_t)(s + 0u) * CT * 64u], b1 = bp[(size_t)(s + 1u) * CT * 64u];
                     f32x4 b2 = bp[(size_t)(s + 2u) * CT * 64u], b3 = bp[(size_t)(s + 3u) * CT * 64u];
                     c = __builtin_amdgcn_mfma_f32_16x16x4f32(a0.x, b0[0], c, 0, 0, 0);
@@ -114,7 +151,7 @@ __global__ __launch_bounds__(TW * 64) void ttm_mfma_kernel(const float *__restri
                     c = __builtin_amdgcn_mfma_f32_16x16x4f32(a3.w, b3[3], c, 0, 0, 0);
                 }
                 for (; s < steps; ++s) {
-                    float4 a0 = ap[s * 4u];
+                    float4 a0 = ttm_load_a<RAGGED>(rowp, l0 + 16u * s, nl);
                     f32x4 b0 = bp[(size_t)s * CT * 64u];
                     c = __builtin_amdgcn_mfma_f32_16x16x4f32(a0.x, b0[0], c, 0, 0, 0);
                     c = __builtin_amdgcn_mfma_f32_16x16x4f32(a0.y, b0[1], c, 0, 0, 0);
@@ -134,7 +171,7 @@ __global__ __launch_bounds__(TW * 64) void ttm_mfma_kernel(const float *__restri
 #pragma unroll
                 for (u32 v = 0; v < 4; ++v) {
                     u32 row = rt * 16u + 4u * lq + v;
-                    if (row < rows) Yc[(size_t)row * R + ct * 16u + lrow] = acc[r][v];
+                    if (row < rows && ct * 16u + lrow < R) Yc[(size_t)row * R + ct * 16u + lrow] = acc[r][v];
                 }
             }
         }
@@ -406,15 +443,19 @@ st_status launch_ttm(const float *Tc, const float *U, float *Yc, int64_t rows, i
         }
         return ok ? launch_status() : ST_ERR_LAUNCH;
     }
-    bool mfma = (nl % 16 == 0) && (R % 16 == 0) && R <= 256 && rows < ((int64_t)1 << 31);
+    bool mfma = R <= 256 && rows < ((int64_t)1 << 31) && (int64_t)nl < ((int64_t)1 << 30);
     if (mfma) {
+        const bool ragged = (nl % 16 != 0) || (R % 16 != 0);
+        const u32 Rp = ((u32)R + 15u) & ~15u, nlp = ((u32)nl + 15u) & ~15u;
         const u32 lds_budget = 128u * 1024u;
-        u32 KC = (lds_budget / ((u32)R * 4u)) & ~15u;      // rows of U per LDS chunk, multiple of 16
-        if (KC > (u32)nl) KC = (u32)nl;
-        size_t lds_bytes = (size_t)KC * R * 4u;
+        u32 KC = (lds_budget / (Rp * 4u)) & ~15u;          // rows of U per LDS chunk, multiple of 16
+        if (KC > nlp) KC = nlp;
+        size_t lds_bytes = (size_t)KC * Rp * 4u;
         static bool attr_set = false;
         if (!attr_set) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void *>(ttm_mfma_kernel),
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(ttm_mfma_kernel<false>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_budget) != hipSuccess ||
+                hipFuncSetAttribute(reinterpret_cast<const void *>(ttm_mfma_kernel<true>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_budget) != hipSuccess)
                 return ST_ERR_LAUNCH;
             attr_set = true;
@@ -422,8 +463,12 @@ st_status launch_ttm(const float *Tc, const float *U, float *Yc, int64_t rows, i
         u32 rtiles = (u32)((rows + 15) / 16);
         u32 grid = (u32)num_cus();
         if (grid > rtiles) grid = rtiles;
-        hipLaunchKernelGGL(ttm_mfma_kernel, dim3(grid), dim3(TW * 64), lds_bytes, s, Tc, U, Yc, (u32)rows,
-                           (u32)nl, (u32)R, KC);
+        if (ragged)
+            hipLaunchKernelGGL(ttm_mfma_kernel<true>, dim3(grid), dim3(TW * 64), lds_bytes, s, Tc, U, Yc, (u32)rows,
+                               (u32)nl, (u32)R, KC);
+        else
+            hipLaunchKernelGGL(ttm_mfma_kernel<false>, dim3(grid), dim3(TW * 64), lds_bytes, s, Tc, U, Yc, (u32)rows,
+                               (u32)nl, (u32)R, KC);
         return launch_status();
     }
     uint64_t total = (uint64_t)rows * R;

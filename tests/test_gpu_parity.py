@@ -163,7 +163,8 @@ def test_batax_full(st, oracle):
                                       (64, 8, 48, 32), (33, 40, 64, 64), (50, 4, 80, 48),
                                       (30, 2, 1040, 256), (20, 3, 16, 272), (600, 14, 128, 48),
                                       (100, 5, 256, 16), (70, 1, 512, 32), (700, 20, 64, 16),
-                                      (1100, 9, 512, 64)])
+                                      (1100, 9, 512, 64), (90, 6, 500, 50), (64, 3, 130, 250), (50, 2, 33, 17),
+                                      (40, 1, 100, 300)])
 def test_ttm_small(st, oracle, n, w, nl, R):
     say("ttm n=%d w=%d nl=%d R=%d" % (n, w, nl, R))
     nb = oracle.count_band(n, w)

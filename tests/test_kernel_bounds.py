@@ -24,10 +24,11 @@ CASES = {
                (208, 7), (256, 64), (512, 64)],
     # batax: n  (one-pass kernel to 16384, two-pass beyond; n % 4 != 0 takes the guarded loads)
     "BATAX": [(1,), (5,), (64,), (100,), (1000,), (1023,), (4096,), (8192,), (9001,), (12288,), (16384,), (16390,)],
-    # ttm: rows nl R  (split-K shapes, the general MFMA path, the plain path)
+    # ttm: rows nl R  (split-K shapes, the general MFMA path with and without ragged sizes, the plain path for R > 256)
     # (more than 16384 rows: the streaming split-K kernel)
     "TTM": [(8632, 512, 64), (16590, 128, 48), (1090, 256, 16), (208, 512, 32), (1, 64, 16), (777, 48, 32),
-            (50, 7, 5), (33, 16, 256), (16385, 512, 64), (40001, 64, 16), (33000, 256, 48)],
+            (50, 7, 5), (33, 16, 256), (16385, 512, 64), (40001, 64, 16), (33000, 256, 48), (100, 500, 50),
+            (10, 1, 1), (300, 130, 250), (40, 33, 300)],
     # moment3: N n accumulate  (n = 64 is the MFMA path, others the plain path)
     # (n <= 40 and 64 < n <= 256: the tile path; 40 < n <= 64: the MFMA path; larger n: the plain path)
     "MOMENT3": [(5000, 64, 0), (4097, 64, 1), (63, 64, 0), (100000, 64, 0), (1000, 20, 0), (3, 5, 1),
