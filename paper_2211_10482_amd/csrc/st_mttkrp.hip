@@ -4,8 +4,8 @@
 //
 // The index range is cut into blocks of 16, so the packed tensor is a set of
 // 16^3 sub-tensors, one per block triple A <= B <= C.  Every contraction below is
-// dense and runs on the fp32 matrix cores (v_mfma_f32_16x16x4_f32).  When n is a
-// multiple of 16 all work is done by two kinds of pair item, each a workgroup of
+// dense and runs on the fp32 matrix cores (v_mfma_f32_16x16x4_f32).  All work is done
+// by two kinds of pair item, each a workgroup of
 // 8 waves with a branch-free, software-pipelined loop over "visits" (one staged
 // 16^3 tile each) that uses plain rows of B as the second MFMA operand (no
 // Khatri-Rao products are ever formed):
@@ -30,10 +30,9 @@
 //     {A,C,C}: M[C] from item (P=C,Q=C) visit X=A,  M[A] from item (X=A,P=C) visit Q=C (1/2);
 //     {A,A,A}: item (X=A,P=A) visit Q=A (1/2), the only tile that needs a per-element sort.
 //
-// When n is not a multiple of 16 gather items do all the work instead (row block X,
-// every block pair P <= Q): owner-computes with a per-element sort + closed-form
-// rank3 gather and Khatri-Rao rows formed on the fly,
-//         M(x,r) += w * sum_{p,q} T(sort(x,p,q)) B(p,r) B(q,r),  w = 2 for P < Q.
+// When n is not a multiple of 16 the packed tensor is first copied into the packed layout of the
+// next multiple, zeros for every entry with an index >= n (mttkrp_repack_kernel), and the pair items
+// run on the copy.
 //
 // Both pair kinds run the same [256 x 16] . [16 x R] MFMA loop on a staged tile
 // D[i1][i2][k] (k fastest): (P,Q) items stage it transposed (i1 = p, i2 = q, k = x),
@@ -65,8 +64,6 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 #define ST_MTTKRP_ITEMS 350u
 #endif
 constexpr u32 NT = 512;            // threads per workgroup: 4 column waves x 2 halves
-constexpr u32 XS = 260;            // row/gather tile D[x][p][q]: stride between x-planes (16*16 + 4 pad)
-constexpr u32 TILE_F = 16 * XS;
 constexpr u32 QS = 20;             // pair tile D[p][q][x]: stride between q rows (16 + 4 pad)
 constexpr u32 PS = 16 * QS;        //                       stride between p planes
 constexpr u32 TILEB_F = 16 * PS;
@@ -84,13 +81,9 @@ __device__ __forceinline__ void sort3u(u32 &a, u32 &b, u32 &c)
 
 struct MttkrpPlan {
     u32 NB, RT, Rpad;
-    u32 all_pairs;          // ragged n: gather items only, no pair items
-    u32 ngat;               // gather visits per row block
-    u32 PPG, PPB;           // visits per gather / pair item
-    u32 NCHG;               // gather chunks per row block
+    u32 PPB;                // visits per pair item
     u32 CHB;                // chunk slots per block pair (either pair kind)
-    u32 nitemsG;            // NB * NCHG gather items
-    u32 npairs;             // block pairs P <= Q that have pair items
+    u32 npairs;             // block pairs P <= Q
 };
 
 // visits of a (P,Q) item: row blocks X <= P (P = Q: X < P, the tile of three equal
@@ -99,153 +92,10 @@ __host__ __device__ inline u32 visits_pq(u32 P, u32 Q) { return P < Q ? P + 1u :
 __host__ __device__ inline u32 visits_xp(u32 NB, u32 P) { return NB - P; }
 __host__ __device__ inline u32 chunks_of(const MttkrpPlan &pl, u32 visits) { return (visits + pl.PPB - 1u) / pl.PPB; }
 
-// ---- gather items (n not a multiple of 16) ---------------------------------------------------
-struct Visit {
-    u32 p0, q0;   // first index of blocks P and Q
-    float wgt;    // 2 for P < Q, 1 for P = Q
-};
-
-// Cursor over the visits of a gather item: every block pair P <= Q in sym2 order.
-// Only the first position is unranked; after that the cursor steps (wave-uniform
-// scalar work).
-struct Cursor {
-    u32 NB, a, b;
-
-    __device__ __forceinline__ Cursor(u32 NB_, u32 u) : NB(NB_) { unrank_sym2<u32>(NB, u, a, b); }
-    __device__ __forceinline__ void step()
-    {
-        if (b < NB - 1u) ++b; else { ++a; b = a; }
-    }
-    __device__ __forceinline__ Visit get() const
-    {
-        Visit v;
-        v.p0 = a * 16u; v.q0 = b * 16u; v.wgt = (a < b) ? 2.f : 1.f;
-        return v;
-    }
-};
-
-// Global -> registers for one visit: 8 sub-tensor values and one 16-byte piece of
-// the two staged blocks of B per thread.  Every load is unconditional (addresses
-// clamped) and the results are not touched here, so they stay in flight while
-// the previous visit is multiplied; store_visit zeroes what lies outside.
-template <bool R4>
-__device__ __forceinline__ void load_visit(const Visit &v, const float *__restrict__ Tc,
-                                           const float *__restrict__ B, u32 n, u32 R, u32 x0, u32 rbase,
-                                           u32 tid, float (&pf)[8], float (&bb)[4])
-{
-#pragma unroll
-    for (u32 it = 0; it < 8; ++it) {
-        const u32 e = tid + NT * it;
-        u32 a = x0 + (e >> 8), b = v.p0 + ((e >> 4) & 15u), c = v.q0 + (e & 15u);
-        sort3u(a, b, c);
-        pf[it] = Tc[c < n ? rank_sym3<u32>(n, a, b, c) : 0u];
-    }
-    // piece tid of the two 16 x 64 blocks of B: block tid/256 (P, then Q), row
-    // (tid%256)/16, columns rbase + 4*(tid%16) .. +3
-    const u32 h = tid >> 8, row = (tid & 255u) >> 4, col = rbase + 4u * (tid & 15u);
-    const u32 gr = (h == 0 ? v.p0 : v.q0) + row;
-    if constexpr (R4) {   // R % 4 == 0: rows of B are 16-byte aligned
-        const bool ok = gr < n && col < R;
-        float4 t = *reinterpret_cast<const float4 *>(B + (ok ? (size_t)gr * R + col : 0));
-        bb[0] = t.x; bb[1] = t.y; bb[2] = t.z; bb[3] = t.w;
-    } else {
-#pragma unroll
-        for (u32 q = 0; q < 4; ++q) bb[q] = B[(gr < n && col + q < R) ? (size_t)gr * R + col + q : 0];
-    }
-}
-
-// Registers -> LDS: dense tile D[x][p][q] (x-stride XS) and the two B blocks, the
-// P block scaled by the pair weight; positions outside the tensor become zero.
-__device__ __forceinline__ void store_visit(const Visit &v, u32 n, u32 R, u32 x0, u32 rbase,
-                                            float *__restrict__ tile, float *__restrict__ bp,
-                                            float *__restrict__ bq, u32 tid, const float (&pf)[8],
-                                            const float (&bb)[4])
-{
-#pragma unroll
-    for (u32 it = 0; it < 8; ++it) {
-        const u32 e = tid + NT * it;
-        const u32 x = e >> 8, p = (e >> 4) & 15u, q = e & 15u;
-        const bool ok = max(x0 + x, max(v.p0 + p, v.q0 + q)) < n;
-        tile[x * XS + p * 16u + q] = ok ? pf[it] : 0.f;
-    }
-    const u32 h = tid >> 8, row = (tid & 255u) >> 4, col = rbase + 4u * (tid & 15u);
-    const bool rok = (h == 0 ? v.p0 : v.q0) + row < n;
-    const float w = (h == 0) ? v.wgt : 1.f;
-    float *dst = (h == 0 ? bp : bq) + row * BS + 4u * (tid & 15u);
-    *reinterpret_cast<float4 *>(dst) =
-        make_float4((rok && col + 0u < R) ? w * bb[0] : 0.f, (rok && col + 1u < R) ? w * bb[1] : 0.f,
-                    (rok && col + 2u < R) ? w * bb[2] : 0.f, (rok && col + 3u < R) ? w * bb[3] : 0.f);
-}
-
-struct LdsGather {
-    float tile[2][TILE_F];
-    float bp[2][BBLK_F];
-    float bq[2][BBLK_F];
-};
 struct LdsPair {
     float tile[2][TILEB_F];
     float bk[2][BBLK_F];
 };
-
-// Visits [v0, v1) of a gather item of row block X: a [16 x 256] . [256 x R]
-// contraction per visit against Khatri-Rao rows formed on the fly (one VALU multiply
-// per MFMA).  Lane = (x, q-quad); wave (cw, half) accumulates columns 16*cw.. of its
-// half of the p range.
-template <bool R4>
-__device__ __forceinline__ void gather_loop(LdsGather &L, const float *__restrict__ Tc,
-                                            const float *__restrict__ B, u32 n, u32 R, u32 NB, u32 X,
-                                            u32 v0, u32 v1, u32 rbase, bool has_rt, f32x4 (&acc)[4])
-{
-    const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
-    const u32 x0 = X * 16u, lrow = lane & 15u, lq = lane >> 4;
-    if (v0 >= v1) return;
-    const u32 nv = v1 - v0;
-    Cursor cur(NB, v0);
-
-    float pf[8], bb[4];
-    Visit nxt = cur.get();
-    load_visit<R4>(nxt, Tc, B, n, R, x0, rbase, tid, pf, bb);
-    store_visit(nxt, n, R, x0, rbase, L.tile[0], L.bp[0], L.bq[0], tid, pf, bb);
-    if (nv > 1) {
-        cur.step();
-        nxt = cur.get();
-        load_visit<R4>(nxt, Tc, B, n, R, x0, rbase, tid, pf, bb);
-    }
-    __syncthreads();
-
-    for (u32 v = 0; v < nv; ++v) {
-        const u32 cb = v & 1u;
-        // registers hold visit v+1: park it in the other buffer (its last readers
-        // finished before the barrier that ended iteration v-1) ...
-        if (v + 1 < nv)
-            store_visit(nxt, n, R, x0, rbase, L.tile[cb ^ 1u], L.bp[cb ^ 1u], L.bq[cb ^ 1u], tid, pf, bb);
-        // ... and put visit v+2 in flight
-        if (v + 2 < nv) {
-            cur.step();
-            nxt = cur.get();
-            load_visit<R4>(nxt, Tc, B, n, R, x0, rbase, tid, pf, bb);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        if (has_rt) {
-            const u32 cw = wave & 3u, pbeg = (wave >> 2) * 8u;   // column block, first p
-            const float *bqp = &L.bq[cb][(4u * lq) * BS + cw * 16u + lrow];
-            const float bq0 = bqp[0], bq1 = bqp[BS], bq2 = bqp[2 * BS], bq3 = bqp[3 * BS];
-            const float *bpp = &L.bp[cb][pbeg * BS + cw * 16u + lrow];
-            const float *arow = &L.tile[cb][lrow * XS + pbeg * 16u + 4u * lq];
-#pragma unroll
-            for (u32 p = 0; p < 8; ++p) {
-                const float bpv = bpp[p * BS];
-                const f32x4 a = *reinterpret_cast<const f32x4 *>(arow + p * 16u);
-                acc[0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[0], bpv * bq0, acc[0], 0, 0, 0);
-                acc[1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[1], bpv * bq1, acc[1], 0, 0, 0);
-                acc[2] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[2], bpv * bq2, acc[2], 0, 0, 0);
-                acc[3] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[3], bpv * bq3, acc[3], 0, 0, 0);
-            }
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        __syncthreads();
-    }
-}
 
 // ---- pair items -----------------------------------------------------------------------
 // The staged tile is D[i1][i2][k] with k fastest (i2-stride QS, i1-stride PS); block b1
@@ -535,51 +385,11 @@ __global__ __launch_bounds__(NT, ST_MTTKRP_WPE) void mttkrp_pair_kernel(const fl
     }
 }
 
-// n not a multiple of 16: gather items, row block X = item / NCHG, chunk item % NCHG.
-template <bool R4>
-__global__ __launch_bounds__(NT) void mttkrp_gather_kernel(const float *__restrict__ Tc,
-                                                         const float *__restrict__ B,
-                                                         float *__restrict__ partG, u32 n, u32 R, MttkrpPlan pl)
-{
-    __shared__ __attribute__((aligned(16))) LdsGather L;
-    const u32 lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
-    const u32 rbase = blockIdx.y * 64u;
-    const u32 rt = blockIdx.y * 4u + (wave & 3u);
-    const bool has_rt = rt * 16u < R;
-
-    const u32 item = blockIdx.x;
-    const u32 X = item / pl.NCHG, ch = item - X * pl.NCHG;
-    f32x4 acc[4];
-#pragma unroll
-    for (int t = 0; t < 4; ++t) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    const u32 v0 = ch * pl.PPG;
-    gather_loop<R4>(L, Tc, B, n, R, pl.NB, X, v0, min(pl.ngat, v0 + pl.PPG), rbase, has_rt, acc);
-
-    f32x4 sum;
-#pragma unroll
-    for (u32 v = 0; v < 4; ++v) sum[v] = (acc[0][v] + acc[1][v]) + (acc[2][v] + acc[3][v]);
-    // the waves of the upper half of the p range hand their sums to the lower half
-    // (the visit loop ends with a barrier, so the tile buffer is free)
-    f32x4 *xch = reinterpret_cast<f32x4 *>(&L.tile[0][0]);
-    if (wave >= 4u) xch[(wave - 4u) * 64u + lane] = sum;
-    __syncthreads();
-    if (has_rt && wave < 4u) {
-        const f32x4 o = xch[wave * 64u + lane];
-        // D layout: lane holds column lane%16 of rows 4*(lane/16) + v
-        const u32 lrow = lane & 15u, lq = lane >> 4;
-        float *dst = partG + ((size_t)item * 16u) * pl.Rpad + rt * 16u + lrow;
-#pragma unroll
-        for (u32 v = 0; v < 4; ++v) dst[(size_t)(4u * lq + v) * pl.Rpad] = sum[v] + o[v];
-    }
-}
-
 // M(16X + x, r) = sum of the partial blocks that target row block X, in a fixed
-// order: 16 slices per output value.  Ragged n: the gather chunks by ch mod 16.
-// Otherwise slices 0..5 the (X,P) items by P mod 6, slices 6..10 the (X,Q) items of
+// order: 16 slices per output value: slices 0..5 the (X,P) items by P mod 6, slices 6..10 the (X,Q) items of
 // kind (P,Q) by Q mod 5 (first output block), slices 11..15 the (P,X) items by
 // P mod 5 (second output block); inside a slice ascending, then slices ascending.
-__global__ __launch_bounds__(512) void mttkrp_reduce_kernel(const float *__restrict__ partG,
-                                                          const float *__restrict__ partPQ,
+__global__ __launch_bounds__(512) void mttkrp_reduce_kernel(const float *__restrict__ partPQ,
                                                           const float *__restrict__ partXP,
                                                           float *__restrict__ M, u32 n, u32 R, MttkrpPlan pl)
 {
@@ -590,11 +400,7 @@ __global__ __launch_bounds__(512) void mttkrp_reduce_kernel(const float *__restr
     if (t < n * R) {
         const u32 i = t / R, r = t - i * R, X = i >> 4, x = i & 15u;
         const size_t blk = (size_t)16u * pl.Rpad, off = (size_t)x * pl.Rpad + r;
-        if (pl.all_pairs) {
-            const float *src = partG + (size_t)X * pl.NCHG * blk + off;
-#pragma unroll 2
-            for (u32 c = sl; c < pl.NCHG; c += 16u) s += src[(size_t)c * blk];
-        } else if (sl < 6u) {
+        if (sl < 6u) {
             // rank_sym2(X, P) is consecutive in P
             const float *src = partXP + (size_t)rank_sym2<u32>(pl.NB, X, X) * pl.CHB * blk + off;
 #pragma unroll 2
@@ -634,26 +440,17 @@ static inline MttkrpPlan plan(int n, int R)
     p.NB = ((u32)n + 15u) / 16u;
     p.RT = ((u32)R + 15u) / 16u;
     p.Rpad = p.RT * 16u;
-    p.all_pairs = (n % 16 != 0) ? 1u : 0u;
-    const u32 npairs = p.NB * (p.NB + 1u) / 2u;
-    p.ngat = p.all_pairs ? npairs : 0u;
-    p.npairs = p.all_pairs ? 0u : npairs;
-    // work in visits: every block triple X <= P <= Q is visited twice (once by each pair
-    // kind; the triples that repeat a block split differently but add up to the same),
-    // or NB * npairs gather visits (weighted 2: per-element address arithmetic)
-    const uint64_t triples = (uint64_t)p.NB * (p.NB + 1u) * (p.NB + 2u) / 6u;
-    const uint64_t work = p.all_pairs ? 2u * (uint64_t)p.NB * npairs : 2u * triples;
+    p.npairs = p.NB * (p.NB + 1u) / 2u;
+    // work in visits: every block triple X <= P <= Q is visited twice (once by each pair kind; the
+    // triples that repeat a block split differently but add up to the same)
+    const uint64_t work = (uint64_t)p.NB * (p.NB + 1u) * (p.NB + 2u) / 3u;
     u32 unit = (u32)((work + (ST_MTTKRP_ITEMS - 1u)) / ST_MTTKRP_ITEMS);   // about that many items in all
     if (unit < 2u) unit = 2u;
     p.PPB = unit;
-    p.PPG = unit / 2u;
-    p.NCHG = p.all_pairs ? (p.ngat + p.PPG - 1u) / p.PPG : 0u;
     p.CHB = (p.NB + p.PPB - 1u) / p.PPB;                  // the longest item has NB visits
-    p.nitemsG = p.NB * p.NCHG;
     return p;
 }
 
-static inline size_t partG_floats(const MttkrpPlan &p) { return (size_t)p.nitemsG * 16u * p.Rpad; }
 static inline size_t partPQ_floats(const MttkrpPlan &p) { return (size_t)p.npairs * p.CHB * 32u * p.Rpad; }
 static inline size_t partXP_floats(const MttkrpPlan &p) { return (size_t)p.npairs * p.CHB * 16u * p.Rpad; }
 
@@ -764,35 +561,72 @@ __global__ __launch_bounds__(ROWS_NT) void mttkrp_rows_kernel(const float *__res
     }
 }
 
+// ---- n not a multiple of 16: repack into the next multiple -------------------------------------
+// The pair items need whole 16^3 tiles.  For other n the packed tensor is copied once into the packed
+// layout of np = 16*ceil(n/16) with zeros for every entry that has an index >= n (one wave per run
+// (i,j): both layouts store the run k = j.. contiguously), B gets zero rows, and the pair items run on
+// the copy; rows >= n of the result are never written.  One extra read and write of the tensor (about
+// 0.5x the time of the contraction itself) instead of per-element gathers in the inner loop.
+__global__ __launch_bounds__(256) void mttkrp_repack_kernel(const float *__restrict__ Tc, const float *__restrict__ B,
+                                                           float *__restrict__ Tp, float *__restrict__ Bp, u32 n,
+                                                           u32 np, u32 R, u32 nruns)
+{
+    const u32 run = blockIdx.x * 4u + (threadIdx.x >> 6), lane = threadIdx.x & 63u;
+    if (run < nruns) {
+        u32 i, j;
+        unrank_sym2<u32>(np, run, i, j);
+        float *dst = Tp + rank_sym3<u32>(np, i, j, j);
+        const bool live = j < n;                                  // i <= j
+        const float *src = Tc + (live ? rank_sym3<u32>(n, i, j, j) : 0u);
+        for (u32 q = lane; q < np - j; q += 64u) dst[q] = (live && j + q < n) ? src[q] : 0.f;
+    }
+    // the first blocks also copy B (n x R) into np x R
+    const u32 e = blockIdx.x * 256u + threadIdx.x;
+    if (e < np * R) Bp[e] = e < n * R ? B[e] : 0.f;
+}
+
+static inline bool use_rows(int n, int R) { return (u32)n <= ROWS_NMAX && R <= 32; }
+static inline u32 pad16(int n) { return ((u32)n + 15u) & ~15u; }
+
 size_t mttkrp_workspace(int n, int R)
 {
-    MttkrpPlan p = plan(n, R);
-    return (partG_floats(p) + partPQ_floats(p) + partXP_floats(p)) * sizeof(float);
+    if (use_rows(n, R)) return 0;
+    const u32 np = pad16(n);
+    MttkrpPlan p = plan((int)np, R);
+    size_t floats = partPQ_floats(p) + partXP_floats(p);
+    if (np != (u32)n) floats += (size_t)count_sym3<int64_t>(np) + (size_t)np * R;   // repacked tensor and factor
+    return floats * sizeof(float);
 }
 
 st_status launch_mttkrp(const float *Tc, const float *B, float *M, int n, int R, void *ws, hipStream_t s)
 {
-    if ((u32)n <= ROWS_NMAX && R <= 32) {
+    if (use_rows(n, R)) {
         if (R <= 16) hipLaunchKernelGGL(mttkrp_rows_kernel<16>, dim3((u32)n), dim3(ROWS_NT), 0, s, Tc, B, M, (u32)n, (u32)R);
         else hipLaunchKernelGGL(mttkrp_rows_kernel<32>, dim3((u32)n), dim3(ROWS_NT), 0, s, Tc, B, M, (u32)n, (u32)R);
         return launch_status();
     }
-    MttkrpPlan p = plan(n, R);
+    const u32 np = pad16(n);
+    MttkrpPlan p = plan((int)np, R);
     u32 gy = (p.RT + 3u) / 4u;
-    uint64_t items = p.all_pairs ? (uint64_t)p.nitemsG : 2u * (uint64_t)p.npairs * p.CHB;
+    uint64_t items = 2u * (uint64_t)p.npairs * p.CHB;
     if (items > 0x7fffffffull || gy > 65535u) return ST_ERR_UNSUPPORTED;
-    float *partG = static_cast<float *>(ws), *partPQ = partG + partG_floats(p), *partXP = partPQ + partPQ_floats(p);
-    const dim3 grid((u32)items, gy), block(NT);
-    if (p.all_pairs) {
-        if (R % 4 == 0) hipLaunchKernelGGL(mttkrp_gather_kernel<true>, grid, block, 0, s, Tc, B, partG, (u32)n, (u32)R, p);
-        else hipLaunchKernelGGL(mttkrp_gather_kernel<false>, grid, block, 0, s, Tc, B, partG, (u32)n, (u32)R, p);
-    } else {
-        if (R % 4 == 0) hipLaunchKernelGGL(mttkrp_pair_kernel<true>, grid, block, 0, s, Tc, B, partPQ, partXP, (u32)n, (u32)R, p);
-        else hipLaunchKernelGGL(mttkrp_pair_kernel<false>, grid, block, 0, s, Tc, B, partPQ, partXP, (u32)n, (u32)R, p);
+    float *partPQ = static_cast<float *>(ws), *partXP = partPQ + partPQ_floats(p);
+    if (np != (u32)n) {
+        float *Tp = partXP + partXP_floats(p), *Bp = Tp + (size_t)count_sym3<int64_t>(np);
+        const u32 nruns = count_sym2<u32>(np);
+        u32 blocks = (nruns + 3u) / 4u, bblocks = (np * (u32)R + 255u) / 256u;
+        if (blocks < bblocks) blocks = bblocks;
+        hipLaunchKernelGGL(mttkrp_repack_kernel, dim3(blocks), dim3(256), 0, s, Tc, B, Tp, Bp, (u32)n, np, (u32)R, nruns);
+        if (hipGetLastError() != hipSuccess) return ST_ERR_LAUNCH;
+        Tc = Tp;
+        B = Bp;
     }
+    const dim3 grid((u32)items, gy), block(NT);
+    if (R % 4 == 0) hipLaunchKernelGGL(mttkrp_pair_kernel<true>, grid, block, 0, s, Tc, B, partPQ, partXP, np, (u32)R, p);
+    else hipLaunchKernelGGL(mttkrp_pair_kernel<false>, grid, block, 0, s, Tc, B, partPQ, partXP, np, (u32)R, p);
     if (hipGetLastError() != hipSuccess) return ST_ERR_LAUNCH;
     u32 total = (u32)n * (u32)R;
-    hipLaunchKernelGGL(mttkrp_reduce_kernel, dim3((total + 31u) / 32u), dim3(512), 0, s, partG, partPQ, partXP, M,
+    hipLaunchKernelGGL(mttkrp_reduce_kernel, dim3((total + 31u) / 32u), dim3(512), 0, s, partPQ, partXP, M,
                        (u32)n, (u32)R, p);
     return launch_status();
 }

@@ -19,7 +19,7 @@ EMUL = os.path.join(ROOT, "tests", "emul")
 CLANG = shutil.which("clang++", path="/opt/rocm/llvm/bin") or shutil.which("clang++")
 
 CASES = {
-    # mttkrp: n R  (multiples of 16 take the pair items, the others the gather items)
+    # mttkrp: n R  (n <= 96 with R <= 32: the row kernel; multiples of 16: pair items; others: repacked first)
     "MTTKRP": [(1, 1), (5, 4), (16, 16), (17, 3), (32, 5), (48, 80), (64, 16), (100, 20), (160, 20),
                (208, 7), (256, 64), (512, 64)],
     # batax: n  (one-pass kernel to 16384, two-pass beyond; n % 4 != 0 takes the guarded loads)
