@@ -459,13 +459,12 @@ static inline size_t partXP_floats(const MttkrpPlan &p) { return (size_t)p.npair
 // When the whole packed tensor is a few hundred KB (n <= 96) the two-kernel item scheme above is all
 // launch and pipeline start-up.  Here (R <= 32) a workgroup owns output row i and evaluates
 //     M(i,r) = sum_{j<=k} w(j,k) T(sort(i,j,k)) B(j,r) B(k,r),   w = 1 for j = k, 2 otherwise,
-// on the vector ALUs.  The workgroup first gathers the slice T(i, j<=k) into LDS in sym2 order, weights
-// applied (closed-form unrank of the pair, rank3 of the sorted triple; all loads of a thread in flight
-// together, so the memory latency is paid once), and copies B to LDS (rows padded to RC+4 floats:
-// conflict-free 16-byte reads of different rows).  A wave then takes the rows j = wave, wave+16, ... and
-// its lanes the columns k = j + lane; every lane keeps RC accumulators, which are added over the lanes
-// with DPP and over the sixteen waves through LDS in a fixed order.  Each entry is read by the (up to
-// three) rows it belongs to; at this size those re-reads come from the cache.
+// on the vector ALUs.  A wave takes the rows j = wave, wave+16, ... and its lanes the columns k = j + lane:
+// every lane first gathers its (at most 12) weighted entries through rank3 of the sorted triple, all loads
+// in flight together, while B is copied to LDS (rows padded to RC+4 floats: conflict-free 16-byte reads of
+// different rows); it keeps RC accumulators, which are added over the sixteen waves through LDS and over
+// the lanes with one DPP tree per output value, in a fixed order.  Each entry is read by the (up to three)
+// rows it belongs to; at this size those re-reads come from the cache.
 template <int CTRL> __device__ __forceinline__ float mk_dpp(float v)
 {
     return __builtin_bit_cast(float,
@@ -487,34 +486,30 @@ __device__ __forceinline__ float mk_wave_sum(float v)     // same bits in every 
 constexpr u32 ROWS_NMAX = 96;      // largest n of the row kernel
 constexpr u32 ROWS_NT = 1024;      // threads per workgroup of the row kernel
 constexpr u32 ROWS_NW = ROWS_NT / 64;
+constexpr u32 ROWS_SLOTS = ((ROWS_NMAX + ROWS_NW - 1) / ROWS_NW) * ((ROWS_NMAX + 63) / 64);   // (j, k chunk) per wave: 12
 template <int RC>                  // accumulators per lane: R rounded up to 16 or 32
 __global__ __launch_bounds__(ROWS_NT) void mttkrp_rows_kernel(const float *__restrict__ Tc, const float *__restrict__ B,
                                                          float *__restrict__ M, u32 n, u32 R)
 {
     constexpr u32 LS = RC + 4;                      // LDS row stride of B
     __shared__ __attribute__((aligned(16))) float Bs[ROWS_NMAX * LS];
-    __shared__ float Ts[ROWS_NMAX * (ROWS_NMAX + 1) / 2];
-    __shared__ float red[ROWS_NW][RC];
+    __shared__ float red[ROWS_NW][16][64];          // [wave][accumulator][lane]
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6, i = blockIdx.x;
-    // the slice T(i,:,:) of the symmetric tensor, upper half (j <= k) with its weight, gathered from the
-    // packed entries: five independent loads per thread in flight at a time
-    const u32 np = count_sym2<u32>(n);
-    for (u32 p0 = tid; p0 < np; p0 += 5u * ROWS_NT) {
-        float tv[5];
-        u32 jj[5], kk[5];
+    // A wave takes the rows j = wave, wave+16, ... and its lanes the columns k = j + lane (+64): slot q of
+    // a lane is one weighted entry w T(sort(i,j,k)), gathered through rank3 of the sorted triple.  All
+    // loads of a lane are issued before anything else (addresses clamped, results masked).
+    const u32 kchunks = (n + 63u) / 64u;
+    float tv[ROWS_SLOTS];
+    u32 kk[ROWS_SLOTS];
 #pragma unroll
-        for (int q = 0; q < 5; ++q) {
-            const u32 pp = min(p0 + ROWS_NT * q, np - 1u);
-            unrank_sym2<u32>(n, pp, jj[q], kk[q]);
-            u32 a = i, b = jj[q], c = kk[q];
-            sort3u(a, b, c);
-            tv[q] = Tc[rank_sym3<u32>(n, a, b, c)];
-        }
-#pragma unroll
-        for (int q = 0; q < 5; ++q) {
-            const u32 pp = p0 + ROWS_NT * q;
-            if (pp < np) Ts[pp] = jj[q] == kk[q] ? tv[q] : 2.f * tv[q];
-        }
+    for (u32 q = 0; q < ROWS_SLOTS; ++q) {
+        const u32 jq = wave + ROWS_NW * (q / 2u), k = jq + 64u * (q & 1u) + lane;
+        const bool in = (q & 1u) < kchunks && jq < n && k < n;
+        u32 a = i, b = in ? jq : i, c = in ? k : i;
+        sort3u(a, b, c);
+        const float t = Tc[rank_sym3<u32>(n, a, b, c)];
+        tv[q] = in ? (k == jq ? t : 2.f * t) : 0.f;
+        kk[q] = in ? k : 0u;
     }
     for (u32 e = tid; e < n * RC; e += ROWS_NT) {
         const u32 row = e / RC, r = e - row * RC;
@@ -524,40 +519,37 @@ __global__ __launch_bounds__(ROWS_NT) void mttkrp_rows_kernel(const float *__res
     float acc[RC];
 #pragma unroll
     for (int r = 0; r < RC; ++r) acc[r] = 0.f;
-    for (u32 j = wave; j < n; j += ROWS_NW) {
-        const float *bj = &Bs[j * LS];                          // wave-uniform: broadcast reads
-        const float *trow = &Ts[rank_sym2<u32>(n, j, j)];      // weighted entries (i; j, k >= j), contiguous in k
-        for (u32 k0 = j; k0 < n; k0 += 64u) {
-            const u32 k = k0 + lane;
-            const bool in = k < n;
-            const float t = in ? trow[k - j] : 0.f;
-            const float *bk = &Bs[(in ? k : j) * LS];
 #pragma unroll
-            for (int q = 0; q < RC / 4; ++q) {
-                const float4 v = *reinterpret_cast<const float4 *>(bk + 4 * q);
-                const float4 u = *reinterpret_cast<const float4 *>(bj + 4 * q);
-                acc[4 * q] += t * u.x * v.x;
-                acc[4 * q + 1] += t * u.y * v.y;
-                acc[4 * q + 2] += t * u.z * v.z;
-                acc[4 * q + 3] += t * u.w * v.w;
-            }
+    for (u32 q = 0; q < ROWS_SLOTS; ++q) {
+        const u32 jq = wave + ROWS_NW * (q / 2u);
+        if (jq >= n || (q & 1u) >= kchunks) continue;           // wave-uniform
+        const float *bj = &Bs[jq * LS];                         // wave-uniform: broadcast reads
+        const float *bk = &Bs[kk[q] * LS];
+        const float t = tv[q];
+#pragma unroll
+        for (int c = 0; c < RC / 4; ++c) {
+            const float4 v = *reinterpret_cast<const float4 *>(bk + 4 * c);
+            const float4 u = *reinterpret_cast<const float4 *>(bj + 4 * c);
+            acc[4 * c] += t * u.x * v.x;
+            acc[4 * c + 1] += t * u.y * v.y;
+            acc[4 * c + 2] += t * u.z * v.z;
+            acc[4 * c + 3] += t * u.w * v.w;
         }
     }
+    // M(i,r) = sum over waves and lanes, 16 accumulators at a time: every lane parks its values in LDS, then
+    // wave r adds accumulator r of all waves lane by lane (waves ascending) and over its 64 lanes (DPP tree)
 #pragma unroll
-    for (int r = 0; r < RC; ++r) {
-        const float v = mk_wave_sum(acc[r]);
-        if (lane == 0) red[wave][r] = v;
-    }
-    __syncthreads();
-    if (tid < R) {       // fixed pairwise tree over the waves
-        float v[ROWS_NW];
+    for (int h = 0; h < RC / 16; ++h) {
+        if (h > 0) __syncthreads();
 #pragma unroll
-        for (u32 w = 0; w < ROWS_NW; ++w) v[w] = red[w][tid];
+        for (int r = 0; r < 16; ++r) red[wave][r][lane] = acc[16 * h + r];
+        __syncthreads();
+        float v = 0.f;
 #pragma unroll
-        for (u32 h = ROWS_NW / 2; h > 0; h >>= 1)
-#pragma unroll
-            for (u32 w = 0; w < h; ++w) v[w] += v[w + h];
-        M[(size_t)i * R + tid] = v[0];
+        for (u32 w = 0; w < ROWS_NW; ++w) v += red[w][wave][lane];
+        v = mk_wave_sum(v);
+        const u32 r = 16u * (u32)h + wave;
+        if (lane == 0 && r < R) M[(size_t)i * R + r] = v;
     }
 }
 
