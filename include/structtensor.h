@@ -126,7 +126,8 @@ st_status st_mttkrp_sym3(const float *Tc, const float *B, float *M, int n, int R
  * (unique set 0<=i<=j<n of the upper-triangular compressed-tensor example;
  * matrix-vector products as sum-of-products rules).  Ap holds the n(n+1)/2
  * sym2-packed entries of A, x and y have n entries, y is overwritten.  A is
- * streamed from memory once.  n >= 1. */
+ * streamed from memory once for n <= 16384 (a row stays on chip between its
+ * two uses), twice beyond.  1 <= n <= 65000. */
 st_status st_batax_utri(const float *Ap, const float *x, float *y, int n, float beta,
                         void *ws, size_t ws_bytes, void *stream);
 
