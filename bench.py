@@ -109,12 +109,12 @@ def cpu_baseline(inputs):
     t_est += t
     parts.append("ttm full %.2fs" % t)
     Tc4, B4 = inputs["c4"]
-    rows = np.arange(0, 512, 2, dtype=np.int64)
+    rows = np.arange(0, 512, dtype=np.int64)
     t = timed(lambda: oracle.mttkrp_sym3(Tc4, B4, rows=rows))
     t_est += t * (512 / rows.size)
     parts.append("mttkrp n=512: %d of 512 rows %.2fs" % (rows.size, t))
     X = inputs["c5"]
-    ns = 100_000
+    ns = 500_000
     t = timed(lambda: oracle.moment3_dense(X[:ns]))
     t_est += t * (X.shape[0] / ns)
     parts.append("moment3: %d of %d samples %.2fs" % (ns, X.shape[0], t))
