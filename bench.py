@@ -114,7 +114,7 @@ def cpu_baseline(inputs):
     t_est += t * (512 / rows.size)
     parts.append("mttkrp n=512: %d of 512 rows %.2fs" % (rows.size, t))
     X = inputs["c5"]
-    ns = 500_000
+    ns = 250_000
     t = timed(lambda: oracle.moment3_dense(X[:ns]))
     t_est += t * (X.shape[0] / ns)
     parts.append("moment3: %d of %d samples %.2fs" % (ns, X.shape[0], t))
