@@ -338,6 +338,17 @@ def main():
             ("desc_thp_band_n512_w8", lambda: dband.thp(Tc3f, Cd, Ac=Hb),
              dict(flops=c3["band_pairs"] * c3["nl"], bytes=4 * 3 * c3["band_pairs"] * c3["nl"], bound="hbm")),
         ]
+        # moment accumulation generated from a descriptor: the symmetric third moment again (vector ALUs here,
+        # matrix cores in the hand-written kernel) and one only a descriptor gives: features at most 8 apart
+        dnear = st.Descriptor("T(i,j,k): (0<=i<=j<n)*(j<=k<=i+w)", (n5, n5, n5), None, n=n5, w=8)
+        near_count = dnear.count
+        Scn, Scd = torch.empty(max(near_count, 4), **f32), torch.empty(tet(n5), **f32)
+        extra += [
+            ("desc_moment_sym3_N2e6_n64", lambda: dsym.moment(X, Sc=Scd),
+             dict(flops=N5 * 2 * tet(n5), bytes=4 * (N5 * n5 + tet(n5)), bound="alu")),
+            ("desc_moment_near3_N2e6_n64_w8", lambda: dnear.moment(X, Sc=Scn),
+             dict(flops=N5 * 2 * near_count, bytes=4 * (N5 * n5 + near_count), bound="alu")),
+        ]
         next_rows = {}
         for name, f, w in extra:
             f()

@@ -301,6 +301,19 @@ st_status st_desc_thp(st_desc *desc, const void *table, const float *Bc, const f
                       void *stream);
 st_status st_desc_expand(st_desc *desc, const void *table, const float *Tc, float *T, void *stream);
 
+/* Moment accumulation over the unique set of a descriptor of order 2 or 3 whose
+ * variables all range over the n <= 256 features of X (N x n, row-major):
+ *     Sc(rank(x)) (+)= sum_s prod_v X(s, x_v)       for every x in the unique set
+ * (creation and addition of a covariance term for ANY structure: st_moment2_sym
+ * and st_moment3_sym are the cases i<=j and i<=j<=k; a band i<=j<=i+w keeps only
+ * the interactions of neighbouring features, and so on).  Generated kernels on
+ * the vector ALUs.  accumulate = 0 overwrites Sc (st_desc_count entries), 1 adds;
+ * ws of st_desc_moment_workspace(desc, N) bytes.  ST_ERR_UNSUPPORTED for other
+ * orders or unequal extents. */
+size_t st_desc_moment_workspace(const st_desc *desc, int64_t N);
+st_status st_desc_moment(st_desc *desc, const void *table, const float *X, int64_t N, float *Sc,
+                         int accumulate, void *ws, size_t ws_bytes, void *stream);
+
 /* TTM of the kernel table along the LAST variable of a descriptor that leaves it
  * free (every run is a whole fibre, e.g. any structure on (i,j) of B(i,j,l)):
  *     Ac(run, r) = sum_l Bc(run, l) * U(l, r)

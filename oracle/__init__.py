@@ -325,3 +325,18 @@ def struct_thp(Bc, C, dims, in_unique):
     idx = struct_enumerate(dims, in_unique).astype(np.int64)
     Cv = np.asarray(C, dtype=np.float64)[tuple(idx[:, v] for v in range(idx.shape[1]))]
     return np.asarray(Bc, dtype=np.float64) * Cv
+
+
+def struct_moment(X, dims, in_unique):
+    """Sc(p) = sum_s prod_v X(s, x_v(p)) over the unique set in packed order (fp64): the covariance term of
+    the overview's M1 / M2 nests ("creation and addition of covariance matrices") restricted to a structure."""
+    idx = struct_enumerate(dims, in_unique).astype(np.int64)
+    Xd = np.asarray(X, dtype=np.float64)
+    out = np.zeros(idx.shape[0], dtype=np.float64)
+    for s0 in range(0, Xd.shape[0], 256):
+        xs = Xd[s0:s0 + 256]
+        prod = np.ones((xs.shape[0], idx.shape[0]))
+        for v in range(idx.shape[1]):
+            prod = prod * xs[:, idx[:, v]]
+        out += prod.sum(axis=0)
+    return out

@@ -75,6 +75,8 @@ SIGNATURES = {
     "st_desc_thp": (_I32, [_P, _P, _P, _P, _P, _P]),
     "st_desc_expand": (_I32, [_P, _P, _P, _P, _P]),
     "st_desc_ttm": (_I32, [_P, _P, _P, _P, _I32, _P]),
+    "st_desc_moment_workspace": (_SZ, [_P, _I64]),
+    "st_desc_moment": (_I32, [_P, _P, _P, _I64, _P, _I32, _P, _SZ, _P]),
     "st_covar_pr2_workspace": (_SZ, [_I64, _I32]),
     "st_covar_pr2": (_I32, [_P, _I64, _I32, _P, _P, _P, _I32, _P, _SZ, _P]),
 }
@@ -457,3 +459,16 @@ class Descriptor:
         self._call(lib().st_desc_ttm(self._h, _dev_f32(Bc, "Bc"), _dev_f32(U, "U"), _dev_f32(Ac, "Ac"), R, _stream()),
                    "st_desc_ttm")
         return Ac[:self.runs]
+
+    def moment(self, X, Sc=None, accumulate=False, ws=None):
+        torch = _torch()
+        N = X.shape[0]
+        if Sc is None:
+            if accumulate:
+                raise ValueError("accumulate needs an existing Sc")
+            Sc = torch.empty(max(self.count, 4), dtype=torch.float32, device=X.device)
+        ws, pws, wsb = _workspace(int(lib().st_desc_moment_workspace(self._h, N)), X, ws)
+        px = _dev_f32(X, "X") if N > 0 else C.c_void_p(X.data_ptr() if X.numel() else 0)
+        self._call(lib().st_desc_moment(self._h, self._tab(), px, N, _dev_f32(Sc, "Sc"), 1 if accumulate else 0, pws,
+                                        wsb, _stream()), "st_desc_moment")
+        return Sc[:self.count]

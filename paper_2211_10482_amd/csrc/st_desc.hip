@@ -213,9 +213,12 @@ struct Desc {
     i64 count = 0, prefixes = 1;
     std::vector<int32_t> table;                  // [prefixes] run start or -1, then [nruns] prefix ids
     i64 nruns = 0;
+    // moment kernels (order 2 or 3, equal extents n <= 256): blocks of `mbs` indices, `ntiles` block tuples
+    // that hold at least one unique entry; their block coordinates follow the run list in the table
+    i64 mbs = 0, ntiles = 0, mnp = 0;
     std::string nest, source;
     std::mutex mu;
-    struct Loaded { hipModule_t mod; hipFunction_t fn[3]; };   // list, thp, expand
+    struct Loaded { hipModule_t mod; hipFunction_t fn[5]; };   // list, thp, expand, moment, moment_reduce
     std::map<int, Loaded> modules;               // per device
     std::string error;
 };
@@ -385,6 +388,34 @@ bool build_tables(Desc &D, std::string &err)
     D.count = pos;
     D.nruns = (i64)runs.size();
     D.table.insert(D.table.end(), runs.begin(), runs.end());
+    // block tuples for the moment kernels: walk the runs and mark the blocks each one touches
+    bool equal = D.d == 2 || D.d == 3;
+    for (int v = 1; v < D.d; ++v) equal = equal && D.dims[v] == D.dims[0];
+    if (equal && D.dims[0] <= 256) {
+        const int d = D.d;
+        D.mbs = d == 2 ? 8 : 4;                                  // 64 accumulators per lane either way
+        const i64 nb = (D.dims[0] + D.mbs - 1) / D.mbs;
+        D.mnp = nb * D.mbs;
+        i64 nbt = 1;
+        for (int v = 0; v < d; ++v) nbt *= nb;
+        std::vector<char> mark((size_t)nbt, 0);
+        for (i64 r = 0; r < D.nruns; ++r) {
+            i64 pf = runs[(size_t)r], x[MAXD] = {0, 0, 0, 0};
+            for (int v = d - 2; v >= 0; --v) { x[v] = pf % D.dims[v]; pf /= D.dims[v]; }
+            i64 l, h;
+            range_of(D, d - 1, x, l, h);
+            i64 base = 0;
+            for (int v = 0; v + 1 < d; ++v) base = base * nb + x[v] / D.mbs;
+            for (i64 b = l / D.mbs; b <= h / D.mbs; ++b) mark[(size_t)(base * nb + b)] = 1;
+        }
+        for (i64 t = 0; t < nbt; ++t) {
+            if (!mark[(size_t)t]) continue;
+            i64 c[MAXD], q = t;
+            for (int v = d - 1; v >= 0; --v) { c[v] = q % nb; q /= nb; }
+            for (int v = 0; v < d; ++v) D.table.push_back((int32_t)c[v]);
+            ++D.ntiles;
+        }
+    }
     return true;
 }
 
@@ -514,6 +545,77 @@ void build_source(Desc &D)
     } else {
         s += "    T[e] = st_value(tab, Tc, " + xs + ");\n}\n";
     }
+    if (D.ntiles > 0) {
+        // moment accumulation over the unique set: Sc(rank(x)) (+)= sum_s prod_v X(s, x_v).  One lane per block
+        // tuple with its ST_MBS^d = 64 accumulators in registers, sample rows staged through a double-buffered
+        // LDS chunk, sample slices over grid.y; a second kernel adds the slice partials in a fixed order, keeps
+        // the tuples of the unique set and scatters them through st_rank.
+        const int bs = (int)D.mbs;
+        s += "#define ST_MBS " + std::to_string(bs) + "\n#define ST_NTILES " + std::to_string((long long)D.ntiles) +
+             "\n#define ST_MNP " + std::to_string((long long)D.mnp) + "\n#define ST_TILES_OFF (ST_PREFIXES + ST_NRUNS)\n"
+             "#ifndef ST_DYN_LDS\n#define ST_DYN_LDS extern __shared__ float st_gen_lds[];\n#endif\n";
+        s += "extern \"C\" __global__ void st_gen_moment(const int *__restrict__ tab, const float *__restrict__ X, long long N,\n"
+             "                                         int ch, long long slice, float *__restrict__ ws)\n{\n";
+        s += "    ST_DYN_LDS\n";
+        s += "    const int tid = threadIdx.x, nthreads = blockDim.x, np4 = ST_MNP / 4, pieces = ch * np4, chunk_f = ch * ST_MNP;\n";
+        s += "    const int t = blockIdx.x * nthreads + tid, tc = t < ST_NTILES ? t : ST_NTILES - 1;\n";
+        for (int v = 0; v < d; ++v)
+            s += "    const int o" + std::to_string(v) + " = ST_MBS * tab[ST_TILES_OFF + tc * ST_D + " + std::to_string(v) + "];\n";
+        s += "    const long long s_begin = (long long)blockIdx.y * slice, s_end = s_begin + slice < N ? s_begin + slice : N;\n";
+        s += "    const long long nchunks = s_end > s_begin ? (s_end - s_begin + ch - 1) / ch : 0;\n";
+        s += "    float acc[64];\n    for (int e = 0; e < 64; ++e) acc[e] = 0.f;\n";
+        s += "    for (long long c = 0; c < nchunks; ++c) {\n";
+        s += "        const long long s0 = s_begin + c * ch;\n";
+        s += "        float *buf = st_gen_lds + (int)(c & 1) * chunk_f;          // double buffered: one barrier per chunk\n";
+        s += "        for (int j = tid; j < pieces; j += nthreads) {\n";
+        s += "            const int smp = j / np4, c0 = 4 * (j - smp * np4);\n";
+        s += "            const long long sq = s0 + smp, sc = sq < s_end ? sq : s_end - 1;\n";
+        s += "            const float *row = X + sc * ST_DIM0;\n";
+        s += "            float4 v;\n";
+        if (D.dims[0] % 4 == 0) {       // rows are 16-byte aligned and have no ragged end
+            s += "            v = *reinterpret_cast<const float4 *>(row + c0);\n";
+            s += "            if (sq >= s_end) v = make_float4(0.f, 0.f, 0.f, 0.f);\n";
+        } else {
+        s += "            v.x = (sq < s_end && c0 + 0 < ST_DIM0) ? row[c0 + 0 < ST_DIM0 ? c0 + 0 : ST_DIM0 - 1] : 0.f;\n";
+        s += "            v.y = (sq < s_end && c0 + 1 < ST_DIM0) ? row[c0 + 1 < ST_DIM0 ? c0 + 1 : ST_DIM0 - 1] : 0.f;\n";
+        s += "            v.z = (sq < s_end && c0 + 2 < ST_DIM0) ? row[c0 + 2 < ST_DIM0 ? c0 + 2 : ST_DIM0 - 1] : 0.f;\n";
+        s += "            v.w = (sq < s_end && c0 + 3 < ST_DIM0) ? row[c0 + 3 < ST_DIM0 ? c0 + 3 : ST_DIM0 - 1] : 0.f;\n";
+        }
+        s += "            *reinterpret_cast<float4 *>(buf + 4 * j) = v;\n        }\n";
+        s += "        __syncthreads();\n";
+        s += "        const float *row = buf;\n";
+        s += "        for (int smp = 0; smp < ch; ++smp, row += ST_MNP) {\n";
+        if (d == 3) {
+            s += "            const float4 a = *reinterpret_cast<const float4 *>(row + o0), b = *reinterpret_cast<const float4 *>(row + o1), cc = *reinterpret_cast<const float4 *>(row + o2);\n";
+            s += "            const float xa[4] = {a.x, a.y, a.z, a.w}, xb[4] = {b.x, b.y, b.z, b.w}, xc[4] = {cc.x, cc.y, cc.z, cc.w};\n";
+            s += "#pragma unroll\n            for (int i = 0; i < 4; ++i)\n#pragma unroll\n                for (int j = 0; j < 4; ++j) {\n                    const float p = xa[i] * xb[j];\n#pragma unroll\n                    for (int k = 0; k < 4; ++k) acc[(i * 4 + j) * 4 + k] += p * xc[k];\n                }\n";
+        } else {
+            s += "            const float4 a0 = *reinterpret_cast<const float4 *>(row + o0), a1 = *reinterpret_cast<const float4 *>(row + o0 + 4);\n";
+            s += "            const float4 b0 = *reinterpret_cast<const float4 *>(row + o1), b1 = *reinterpret_cast<const float4 *>(row + o1 + 4);\n";
+            s += "            const float xa[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w}, xb[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};\n";
+            s += "#pragma unroll\n            for (int i = 0; i < 8; ++i)\n#pragma unroll\n                for (int j = 0; j < 8; ++j) acc[i * 8 + j] += xa[i] * xb[j];\n";
+        }
+        s += "        }\n    }\n";
+        s += "    if (t < ST_NTILES) {\n        float *dst = ws + ((long long)blockIdx.y * ST_NTILES + t) * 64;\n";
+        s += "        for (int e = 0; e < 64; ++e) dst[e] = acc[e];\n    }\n}\n";
+        // reduce: 16 accumulators x 16 slice groups per block
+        s += "extern \"C\" __global__ void st_gen_moment_reduce(const int *__restrict__ tab, const float *__restrict__ ws, int S,\n"
+             "                                                float *__restrict__ Sc, int accumulate)\n{\n";
+        s += "    __shared__ float part[16][16];\n";
+        s += "    const int a = threadIdx.x & 15, g = threadIdx.x >> 4;\n    const long long t = (long long)blockIdx.x * 16 + a;\n";
+        s += "    float sum = 0.f;\n    if (t < (long long)ST_NTILES * 64)\n        for (int y = g; y < S; y += 16) sum += ws[(long long)y * ST_NTILES * 64 + t];\n";
+        s += "    part[g][a] = sum;\n    __syncthreads();\n    if (g != 0 || t >= (long long)ST_NTILES * 64) return;\n";
+        s += "    float v = 0.f;\n    for (int q = 0; q < 16; ++q) v += part[q][a];\n";
+        s += "    const int tile = (int)(t >> 6), e = (int)(t & 63);\n";
+        if (d == 3) {
+            s += "    const int x0 = ST_MBS * tab[ST_TILES_OFF + tile * 3] + (e >> 4), x1 = ST_MBS * tab[ST_TILES_OFF + tile * 3 + 1] + ((e >> 2) & 3),\n"
+                 "              x2 = ST_MBS * tab[ST_TILES_OFF + tile * 3 + 2] + (e & 3);\n";
+        } else {
+            s += "    const int x0 = ST_MBS * tab[ST_TILES_OFF + tile * 2] + (e >> 3), x1 = ST_MBS * tab[ST_TILES_OFF + tile * 2 + 1] + (e & 7);\n";
+        }
+        s += "    if (!st_in(" + xs + ")) return;\n";
+        s += "    const int p = st_rank(tab, " + xs + ");\n    Sc[p] = accumulate ? Sc[p] + v : v;\n}\n";
+    }
     D.source = s;
 }
 
@@ -633,8 +735,9 @@ st_status module_for(Desc &D, Desc::Loaded &out)
     hiprtcDestroyProgram(&prog);
     Desc::Loaded L;
     if (hipModuleLoadData(&L.mod, code.data()) != hipSuccess) { D.error = "hipModuleLoadData failed"; return ST_ERR_LAUNCH; }
-    const char *names[3] = {"st_gen_list", "st_gen_thp", "st_gen_expand"};
-    for (int q = 0; q < 3; ++q)
+    const char *names[5] = {"st_gen_list", "st_gen_thp", "st_gen_expand", "st_gen_moment", "st_gen_moment_reduce"};
+    L.fn[3] = L.fn[4] = nullptr;
+    for (int q = 0; q < (D.ntiles > 0 ? 5 : 3); ++q)
         if (hipModuleGetFunction(&L.fn[q], L.mod, names[q]) != hipSuccess) {
             (void)hipModuleUnload(L.mod);
             D.error = std::string("generated kernel missing: ") + names[q];
@@ -645,14 +748,35 @@ st_status module_for(Desc &D, Desc::Loaded &out)
     return ST_OK;
 }
 
-st_status launch_generated(Desc &D, int which, unsigned blocks, void **args, hipStream_t s)
+st_status launch_generated(Desc &D, int which, unsigned blocks, void **args, hipStream_t s, unsigned gy = 1,
+                           unsigned threads = 256, unsigned lds_bytes = 0)
 {
-    if (blocks == 0) return ST_OK;
+    if (blocks == 0 || gy == 0) return ST_OK;
     Desc::Loaded L;
     st_status rc = module_for(D, L);
     if (rc != ST_OK) return rc;
-    if (hipModuleLaunchKernel(L.fn[which], blocks, 1, 1, 256, 1, 1, 0, s, args, nullptr) != hipSuccess) return ST_ERR_LAUNCH;
+    if (hipModuleLaunchKernel(L.fn[which], blocks, gy, 1, threads, 1, 1, lds_bytes, s, args, nullptr) != hipSuccess)
+        return ST_ERR_LAUNCH;
     return ST_OK;
+}
+
+// sample slices and chunk size of the generated moment kernels
+struct MomentPlan { unsigned threads, gx, ch, S; i64 slice; };
+MomentPlan moment_plan(const Desc &D, i64 N)
+{
+    MomentPlan p;
+    p.threads = D.ntiles >= 256 ? 256u : (unsigned)((D.ntiles + 63) / 64) * 64u;
+    p.gx = (unsigned)((D.ntiles + p.threads - 1) / p.threads);
+    unsigned ch = (unsigned)(8192 / D.mnp);                  // two chunks of at most 8192 floats: 64 KB of LDS
+    p.ch = ch > 64u ? 64u : ch & ~3u;
+    i64 S = (1024 + p.gx - 1) / p.gx;
+    const i64 smax = (N + p.ch - 1) / p.ch;
+    if (S > smax) S = smax;
+    if (S > 1024) S = 1024;
+    if (S < 1) S = 1;
+    p.slice = ((N + S - 1) / S + p.ch - 1) / p.ch * p.ch;
+    p.S = (unsigned)((N + p.slice - 1) / p.slice);
+    return p;
 }
 
 }  // namespace
@@ -758,6 +882,48 @@ st_status st_desc_ttm(st_desc *desc, const float *Bc, const float *U, float *Ac,
     size_t tb = (size_t)rows * nl * 4, ub = (size_t)nl * R * 4, yb = (size_t)rows * R * 4;
     if (overlap(Ac, yb, Bc, tb) || overlap(Ac, yb, U, ub)) return ST_ERR_SHAPE;
     return launch_ttm(Bc, U, Ac, rows, (int)nl, R, nullptr, (hipStream_t)stream);
+}
+
+size_t st_desc_moment_workspace(const st_desc *desc, int64_t N)
+{
+    if (!desc || N <= 0) return 0;
+    const Desc *D = reinterpret_cast<const Desc *>(desc);
+    if (D->ntiles == 0) return 0;
+    const MomentPlan p = moment_plan(*D, N);
+    return (size_t)p.S * (size_t)D->ntiles * 64u * sizeof(float);
+}
+
+st_status st_desc_moment(st_desc *desc, const void *table, const float *X, int64_t N, float *Sc, int accumulate,
+                         void *ws, size_t ws_bytes, void *stream)
+{
+    if (!desc || !table || !Sc || (N > 0 && !X)) return ST_ERR_NULL;
+    Desc *D = reinterpret_cast<Desc *>(desc);
+    if (D->source.empty() || N < 0 || (accumulate != 0 && accumulate != 1)) return ST_ERR_SHAPE;
+    if (D->mbs == 0) return ST_ERR_UNSUPPORTED;      /* order 2 or 3 with equal extents <= 256 only */
+    if (!aligned16(table) || !aligned16(Sc) || (X && !aligned16(X))) return ST_ERR_ALIGN;
+    const size_t sb = (size_t)D->count * 4, xb = (size_t)N * D->dims[0] * 4;
+    if (N > 0 && overlap(Sc, sb, X, xb)) return ST_ERR_SHAPE;
+    if (D->ntiles == 0) return ST_OK;                /* empty unique set */
+    if (N == 0) {           /* overwrite: the reduce kernel over zero slices writes the zeros */
+        if (accumulate) return ST_OK;
+        int S0 = 0;
+        const void *none = table;
+        void *a0[] = {&table, &none, &S0, &Sc, &accumulate};
+        return launch_generated(*D, 4, (unsigned)((D->ntiles * 64 + 15) / 16), a0, (hipStream_t)stream);
+    }
+    const size_t need = st_desc_moment_workspace(desc, N);
+    if (!ws || ws_bytes < need) return ST_ERR_WORKSPACE;
+    if (!aligned16(ws)) return ST_ERR_ALIGN;
+    if (overlap(ws, need, Sc, sb) || overlap(ws, need, X, xb)) return ST_ERR_SHAPE;
+    const MomentPlan p = moment_plan(*D, N);
+    long long Nll = N, slice = p.slice;
+    int ch = (int)p.ch, S = (int)p.S;
+    void *a1[] = {&table, &X, &Nll, &ch, &slice, &ws};
+    st_status rc = launch_generated(*D, 3, p.gx, a1, (hipStream_t)stream, p.S, p.threads,
+                                    (unsigned)(2u * p.ch * D->mnp * sizeof(float)));
+    if (rc != ST_OK) return rc;
+    void *a2[] = {&table, &ws, &S, &Sc, &accumulate};
+    return launch_generated(*D, 4, (unsigned)((D->ntiles * 64 + 15) / 16), a2, (hipStream_t)stream);
 }
 
 st_status st_desc_expand(st_desc *desc, const void *table, const float *Tc, float *T, void *stream)

@@ -1,10 +1,17 @@
 // Driver of tests/test_desc.py: runs the kernels GENERATED for one descriptor on the CPU.
 // The generated source (-DGEN_SRC="file") is compiled as plain C++ against the host stand-in of
-// the HIP runtime, with AddressSanitizer; the kernels have no barriers or cross-lane operations,
-// so a launch run as nested loops computes exactly what the GPU computes.
-//   argv: dir count box order nruns last_dim   (dir holds table.i32, bc.f32 [count], c.f32 [box])
-//   writes list.i32 [count*order], thp.f32 [count], expand.f32 [box] (expansion of bc.f32)
+// the HIP runtime, with AddressSanitizer; the list, product and expansion kernels have no barriers or
+// cross-lane operations, so a launch run as nested loops computes exactly what the GPU computes; the
+// moment kernels are launched in a shape (one thread per block, one slice) for which that also holds.
+//   argv: dir count box order nruns last_dim [N]  (dir holds table.i32, bc.f32 [count], c.f32 [box], x.f32 [N*n])
+//   writes list.i32 [count*order], thp.f32 [count], expand.f32 [box] (expansion of bc.f32), moment.f32 [count]
 #include <hip/hip_runtime.h>
+// LDS of the generated moment kernels: the dynamic chunk buffer is a global here, static arrays keep their
+// zero initialisation (the reduce kernel reads rows of its array that other threads of the block wrote)
+extern "C" { float st_gen_lds[2 * 8192]; }
+#define ST_DYN_LDS
+#undef __shared__
+#define __shared__ static
 #include GEN_SRC
 #include <cstdio>
 #include <cstdlib>
@@ -45,6 +52,21 @@ int main(int argc, char **argv)
     }
     const size_t last_dim = (size_t)atol(argv[6]), ethreads = last_dim % 4 == 0 ? box / 4 : box;   // as the library launches it
     hipLaunchKernelGGL(st_gen_expand, dim3((unsigned)((ethreads + 255) / 256)), dim3(256), 0, 0, tab.data(), bc.data(), ex.data());
+#ifdef ST_NTILES
+    // moment kernels: one thread per block and one sample slice, so that the missing barriers change nothing
+    if (argc > 7) {
+        const long long N = atol(argv[7]);
+        std::vector<int> full = rd<int>(dir + "/table.i32", (size_t)ST_TILES_OFF + (size_t)ST_NTILES * ST_D);
+        std::vector<float> X = rd<float>(dir + "/x.f32", (size_t)N * ST_DIM0), ws((size_t)ST_NTILES * 64, -7.f), sc(count, -7.f);
+        int ch = 8192 / ST_MNP;
+        ch = ch > 64 ? 64 : ch & ~3;
+        const long long slice = (N + ch - 1) / ch * ch;
+        hipLaunchKernelGGL(st_gen_moment, dim3(ST_NTILES), dim3(1), 0, 0, full.data(), X.data(), N, ch, slice, ws.data());
+        hipLaunchKernelGGL(st_gen_moment_reduce, dim3((ST_NTILES * 64 + 15) / 16), dim3(256), 0, 0, full.data(), ws.data(), 1,
+                           sc.data(), 0);
+        wr(dir + "/moment.f32", sc);
+    }
+#endif
     wr(dir + "/list.i32", list);
     wr(dir + "/thp.f32", thp);
     wr(dir + "/expand.f32", ex);

@@ -78,9 +78,10 @@ def test_alignment_overlap_workspace_errors():
     need = L.st_moment3_sym_workspace(1000, 8)
     assert need > 0
     assert L.st_moment3_sym(P, 1000, 8, P + 0x100000, 0, None, 0, None) == WORKSPACE
-    need = L.st_mttkrp_sym3_workspace(20, 4)
+    assert L.st_mttkrp_sym3_workspace(20, 4) == 0          # one launch, no partial results
+    need = L.st_mttkrp_sym3_workspace(112, 48)
     assert need > 0
-    assert L.st_mttkrp_sym3(P, P + 0x100000, P + 0x200000, 20, 4, P + 0x300000, need - 4, None) == WORKSPACE
+    assert L.st_mttkrp_sym3(P, P + 0x1000000, P + 0x2000000, 112, 48, P + 0x3000000, need - 4, None) == WORKSPACE
     assert L.st_moment3_sym_workspace(0, 8) == 0 and L.st_ttm_band_workspace(8, 1, 8, 8) == 0
 
 
@@ -140,7 +141,7 @@ def test_descriptor_errors():
     assert L.st_desc_list(h, P, P + 0x10000, None) == SHAPE          # nothing was generated for a failed parse
     L.st_desc_destroy(h)
     assert L.st_desc_create(b"S(i,j): (0<=i<=j<n)", None, dims, 2, names, vals, 1, C.byref(h)) == OK
-    assert L.st_desc_count(h) == 10 and L.st_desc_runs(h) == 4 and L.st_desc_table_bytes(h) == (4 + 4) * 4
+    assert L.st_desc_count(h) == 10 and L.st_desc_runs(h) == 4 and L.st_desc_table_bytes(h) == (4 + 4 + 2) * 4
     assert L.st_desc_list(h, None, P, None) == NULL
     assert L.st_desc_list(h, P + 4, P + 0x10000, None) == ALIGN
     assert L.st_desc_thp(h, P, P + 0x10000, None, P + 0x20000, None) == NULL
@@ -148,6 +149,10 @@ def test_descriptor_errors():
     assert L.st_desc_expand(h, P, None, P + 0x10000, None) == NULL
     assert L.st_desc_expand(h, P, P + 0x10000, P + 0x10010, None) == SHAPE                # buffers overlap
     assert L.st_desc_table(h, None) == NULL
+    assert L.st_desc_moment(h, P, None, 10, P + 0x10000, 0, None, 0, None) == NULL
+    assert L.st_desc_moment(h, P, P + 0x20000, 10, P + 0x10000, 0, None, 0, None) == WORKSPACE
+    assert L.st_desc_moment(h, P, P + 0x20000, -1, P + 0x10000, 0, None, 0, None) == SHAPE
+    assert L.st_desc_moment_workspace(h, 10) == 1 * 1 * 64 * 4        # one slice, one 8 x 8 block pair
     assert L.st_desc_ttm(h, P, None, P + 0x10000, 4, None) == NULL
     assert L.st_desc_ttm(h, P, P + 0x10000, P + 0x20000, 4, None) == UNSUPPORTED   # last variable is bounded by i <= j
     assert L.st_desc_ttm(h, P, P + 0x10000, P + 0x20000, 0, None) == SHAPE

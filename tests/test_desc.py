@@ -74,7 +74,12 @@ def test_counts_and_tables_against_brute_force(descs, oracle, name):
     assert d.count == lst.shape[0]
     tab = d.table()
     nprefix = int(np.prod(dims[:-1])) if len(dims) > 1 else 1
-    assert tab.size == nprefix + d.runs
+    # orders 2 and 3 over one extent <= 256 also carry the block tuples (8 x 8, 4 x 4 x 4) that hold unique entries
+    tiles = np.zeros((0, len(dims)), dtype=np.int64)
+    if len(dims) in (2, 3) and len(set(dims)) == 1 and dims[0] <= 256 and lst.shape[0] > 0:
+        tiles = np.unique(lst.astype(np.int64) // (8 if len(dims) == 2 else 4), axis=0)
+    assert tab.size == nprefix + d.runs + tiles.size
+    assert np.array_equal(tab[nprefix + d.runs:].reshape(-1, len(dims)), tiles)
     # run starts: position of the first entry of every prefix that has one, -1 for the others
     want = np.full(nprefix, -1, dtype=np.int64)
     for p in range(lst.shape[0] - 1, -1, -1):
@@ -83,7 +88,7 @@ def test_counts_and_tables_against_brute_force(descs, oracle, name):
             pf = pf * dims[v] + int(lst[p, v])
         want[pf] = p
     assert np.array_equal(tab[:nprefix], want)
-    assert np.array_equal(tab[nprefix:], np.flatnonzero(want >= 0))
+    assert np.array_equal(tab[nprefix:nprefix + d.runs], np.flatnonzero(want >= 0))
 
 
 def test_tables_match_the_closed_form_index_maps(oracle):
@@ -171,8 +176,12 @@ def test_generated_kernels_on_the_cpu(descs, oracle, tmp_path, name):
     d.table().tofile(str(tmp_path / "table.i32"))
     Bc.tofile(str(tmp_path / "bc.f32"))
     Cd.tofile(str(tmp_path / "c.f32"))
-    r = subprocess.run([exe, str(tmp_path), str(d.count), str(box), str(len(dims)), str(d.runs), str(dims[-1])],
-                       capture_output=True, text=True, timeout=300)
+    has_moment = "st_gen_moment" in d.source
+    N = 7
+    X = W.normal(703, N * dims[0]).reshape(N, dims[0])
+    X.tofile(str(tmp_path / "x.f32"))
+    r = subprocess.run([exe, str(tmp_path), str(d.count), str(box), str(len(dims)), str(d.runs), str(dims[-1])]
+                       + ([str(N)] if has_moment else []), capture_output=True, text=True, timeout=300)
     assert r.returncode == 0 and "rc=0" in r.stdout, r.stderr[-3000:]
     lst = np.fromfile(str(tmp_path / "list.i32"), dtype=np.int32).reshape(-1, len(dims))
     assert np.array_equal(lst, oracle.struct_enumerate(dims, pred))
@@ -181,3 +190,7 @@ def test_generated_kernels_on_the_cpu(descs, oracle, tmp_path, name):
     ex = np.fromfile(str(tmp_path / "expand.f32"), dtype=np.float32).reshape(dims)
     ref = oracle.struct_expand(Bc, dims, pred, unique_of)
     assert np.array_equal(ex.view(np.uint32), ref.view(np.uint32))
+    if has_moment:
+        mom = np.fromfile(str(tmp_path / "moment.f32"), dtype=np.float32)
+        refm = oracle.struct_moment(X, dims, pred)
+        assert mom.size == refm.size and float(np.abs(mom - refm).max()) <= 1e-5 * max(float(np.abs(refm).max()), 1.0)

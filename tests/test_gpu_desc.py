@@ -148,3 +148,63 @@ def test_descriptor_ttm_band_full(st, oracle):
     assert float(np.abs(got - ref).max() / np.abs(ref).max()) <= 1e-4
     assert np.array_equal(got, st.ttm_band(dev(Tb), dev(U), n, w).cpu().numpy())
     d.close()
+
+
+MOMENT_CASES = {
+    # name -> (text, order, n, params, predicate)
+    "sym2": ("S(i,j): (0<=i<=j<n)", 2, 40, {}, lambda i, j: i <= j),
+    "sym3": ("T(i,j,k): (0<=i<=j<n)*(j<=k<n)", 3, 22, {}, lambda i, j, k: i <= j <= k),
+    "near2": ("S(i,j): (0<=i<n)*(i<=j<=i+w)", 2, 70, dict(w=3), lambda i, j: i <= j <= i + 3),
+    "near3": ("T(i,j,k): (0<=i<=j<n)*(j<=k<=i+w)", 3, 30, dict(w=5), lambda i, j, k: i <= j <= k <= i + 5),
+    "full2": ("G(i,j): (0<=i<n)*(0<=j<n)", 2, 9, {}, lambda i, j: True),
+    "diag3": ("D(i,j,k): (0<=i<n)*(i=j)*(j=k)", 3, 33, {}, lambda i, j, k: i == j == k),
+}
+
+
+@pytest.mark.parametrize("name", sorted(MOMENT_CASES))
+@pytest.mark.parametrize("N", [1, 257, 1500])
+def test_descriptor_moment(st, oracle, name, N):
+    say("descriptor moment", name, N)
+    text, order, n, params, pred = MOMENT_CASES[name]
+    d = st.Descriptor(text, (n,) * order, None, n=n, **params)
+    X = W.normal(761, N * n).reshape(N, n)
+    ref = oracle.struct_moment(X, (n,) * order, pred)
+    assert d.count == ref.size
+    got = d.moment(dev(X)).cpu().numpy()
+    scale = np.abs(ref).max()
+    assert float(np.abs(got - ref).max() / scale) <= 1e-4
+    # creation and addition: two batches
+    h = N // 2
+    Sc = d.moment(dev(X[:h])).clone() if h > 0 else None
+    if Sc is not None:
+        import torch
+        buf = torch.empty(max(d.count, 4), device="cuda")
+        buf[: d.count] = Sc
+        got2 = d.moment(dev(X[h:]), Sc=buf, accumulate=True).cpu().numpy()
+        assert float(np.abs(got2 - ref).max() / scale) <= 1e-4
+    d.close()
+
+
+def test_descriptor_moment_against_handwritten(st, oracle):
+    import torch
+    n, N = 64, 20000
+    X = dev(W.normal(762, N * n).reshape(N, n))
+    d3 = st.Descriptor("T(i,j,k): (0<=i<=j<n)*(j<=k<n)", (n, n, n), "sort", n=n)
+    a, b = d3.moment(X).cpu().numpy(), st.moment3_sym(X).cpu().numpy()
+    assert float(np.abs(a - b).max() / np.abs(b).max()) <= 2e-5
+    d2 = st.Descriptor("S(i,j): (0<=i<=j<n)", (n, n), None, n=n)
+    a, b = d2.moment(X).cpu().numpy(), st.moment2_sym(X).cpu().numpy()
+    assert float(np.abs(a - b).max() / np.abs(b).max()) <= 2e-5
+    # N = 0: overwrite gives zeros, accumulate leaves Sc alone
+    buf = torch.full((d2.count,), 3.0, device="cuda")
+    empty = torch.empty((0, n), device="cuda")
+    d2.moment(empty, Sc=buf, accumulate=True)
+    assert float(buf.min()) == 3.0
+    d2.moment(empty, Sc=buf)
+    assert float(buf.abs().max()) == 0.0
+    # unsupported: unequal extents
+    db = st.Descriptor("B(i,j,l): (0<=i<n)*(i-1<=j<=i+1)*(0<=l<m)", (8, 8, 4), n=8, m=4)
+    with pytest.raises(st.StructTensorError):
+        db.moment(torch.zeros((5, 8), device="cuda"))
+    for d in (d2, d3, db):
+        d.close()
