@@ -16,10 +16,13 @@
 //   * a pair inside one group g, third index anywhere (group r): columns = the
 //     16 pairs (m, m-d mod 16) of g at cyclic distance d = 0..8, rows = group r.
 //     P = xa[g] * rotate_d(xa[g]) is one VALU multiply with a DPP row rotate
-//     and is shared by the four row groups.  4 * 9 * 4 tiles.
-// 208 tiles cover every unordered triple (53,248 accumulators for the 45,760
-// unique entries, against 64^3 = 262,144 dense ones), 84 pair products per four
-// samples feed 208 MFMAs.  A workgroup (8 waves, 26 tiles = 104 accumulator
+//     and is shared by the four row groups.  When r = g all three indices lie in
+//     one group of 16; their three cyclic gaps add up to 16, so two of them are
+//     at distance <= 5 and the tiles (g, d >= 6, r = g) are not needed:
+//     4 * 9 * 4 - 12 tiles.
+// 196 tiles cover every unordered triple (50,176 accumulators for the 45,760
+// unique entries, against 64^3 = 262,144 dense ones).  A workgroup (8 waves,
+// 25 or 24 tiles per wave so that every SIMD has 49, about 100 accumulator
 // registers per wave) owns ALL accumulators and streams a contiguous slice of
 // the samples through a double-buffered LDS chunk of 64 samples that the whole
 // workgroup loads once (X is read from HBM exactly once; the loads of chunk c+2
@@ -51,9 +54,13 @@ template <int N, typename F> __device__ __forceinline__ void static_for(F &&f)
 }
 
 constexpr int M3_WAVES = 8;
-constexpr int M3_TPW = 26;                         // tiles per wave
-constexpr int M3_TILES = M3_WAVES * M3_TPW;        // 208
+constexpr int M3_TILES = 196;
 constexpr int M3_ACC = M3_TILES * 256;             // accumulators per workgroup
+// waves w and w+4 share a SIMD: 25 + 24 tiles on each of the four
+__host__ __device__ constexpr int m3_npair(int w) { return w < 4 ? 17 : 16; }                     // pair tiles of wave w
+__host__ __device__ constexpr int m3_pair_start(int w) { return w < 4 ? 17 * w : 68 + 16 * (w - 4); }
+__host__ __device__ constexpr int m3_tpw(int w) { return m3_npair(w) + 8; }                       // tiles of wave w
+__host__ __device__ constexpr int m3_tile_base(int w) { return w < 4 ? 25 * w : 100 + 24 * (w - 4); }
 constexpr int M3_GMAX = 256;
 
 // lane m of each 16-lane row reads lane (m - D) mod 16 of the same row
@@ -90,12 +97,13 @@ template <int M> __device__ __forceinline__ float mul_bcast(float bsrc, float ot
 }
 
 // Tile descriptor shared by the accumulation kernel (compile time) and the
-// reduction kernel (run time).  Tile `local` of wave `w`:
-//   local 0..17 : pair-in-group tiles; half unit h = 9 w + local/2 = (g*9 + d)*2 + half,
-//                 row group r = 2*half + local%2
-//   local 18,19 : groups (r=0, 1, 2), fixed element m = 2w + local-18 of group 1
-//   local 20,21 : groups (r=0, 1, 3), fixed element m = 2w + local-20 of group 1
-//   local 22..25: groups (r, 2, 3), fixed element m = 2w + (local-22)/2 of group 2, r = (local-22)%2
+// reduction kernel (run time).  The 132 pair-in-group tiles are listed by (group g,
+// distance d, row group r), r fastest, without the twelve (g, d >= 6, r = g); wave w
+// takes m3_npair(w) consecutive ones from m3_pair_start(w), then eight tiles of three
+// different groups:
+//   +0,+1 : groups (r=0, 1, 2), fixed element m = 2w + 0/1 of group 1
+//   +2,+3 : groups (r=0, 1, 3), fixed element m = 2w + 0/1 of group 1
+//   +4..7 : groups (r, 2, 3), fixed element m = 2w + (l-4)/2 of group 2, r = (l-4)%2
 struct TileDesc {
     int kind;   // 0: pair inside group gb at distance d; 1: (element m of gb) x (group gc)
     int r;      // row group
@@ -104,14 +112,26 @@ struct TileDesc {
 };
 __host__ __device__ constexpr TileDesc tile_desc(int w, int local)
 {
-    if (local < 18) {
-        int h = 9 * w + local / 2;
-        int gd = h / 2, half = h % 2;
-        return TileDesc{0, 2 * half + local % 2, gd / 9, 0, gd % 9};
+    if (local < m3_npair(w)) {
+        const int t = m3_pair_start(w) + local, g = t / 33, u = t % 33;
+        if (u < 24) return TileDesc{0, u % 4, g, 0, u / 4};
+        const int rr = (u - 24) % 3;
+        return TileDesc{0, rr + (rr >= g ? 1 : 0), g, 0, 6 + (u - 24) / 3};
     }
-    if (local < 20) return TileDesc{1, 0, 1, 2, 2 * w + (local - 18)};
-    if (local < 22) return TileDesc{1, 0, 1, 3, 2 * w + (local - 20)};
-    return TileDesc{1, (local - 22) % 2, 2, 3, 2 * w + (local - 22) / 2};
+    const int l = local - m3_npair(w);
+    if (l < 2) return TileDesc{1, 0, 1, 2, 2 * w + l};
+    if (l < 4) return TileDesc{1, 0, 1, 3, 2 * w + (l - 2)};
+    return TileDesc{1, (l - 4) % 2, 2, 3, 2 * w + (l - 4) / 2};
+}
+// first tile of the wave that multiplies by the same pair product
+__host__ __device__ constexpr int m3_product_of(int w, int local)
+{
+    const TileDesc a = tile_desc(w, local);
+    for (int u = 0; u < local; ++u) {
+        const TileDesc b = tile_desc(w, u);
+        if (a.kind == b.kind && a.gb == b.gb && a.gc == b.gc && a.d == b.d) return u;
+    }
+    return local;
 }
 
 #ifndef ST_M3_CH
@@ -160,41 +180,31 @@ __device__ __forceinline__ void store_chunk(const f32x4 (&r)[M3_LPT], float *__r
 }
 
 template <int W>
-__device__ __forceinline__ void m3_step(f32x4 (&acc)[M3_TPW], const f32x4 &xa)
+__device__ __forceinline__ void m3_step(f32x4 (&acc)[m3_tpw(W)], const f32x4 &xa)
 {
     // All pair products of the step first, each in a register of its own, then the
-    // 26 MFMAs back to back: a product that is formed right in front of its MFMA in
+    // MFMAs back to back: a product that is formed right in front of its MFMA in
     // a recycled register has to wait for the previous MFMA to release it.
-    float pw[9], p12[2], p13[2], p23[2];
+    constexpr int NT = m3_tpw(W);
+    float p[NT];
 #ifndef ST_HOST_EMULATION
     asm volatile("s_nop 1");
 #endif
-    static_for<2>([&](auto E) {
-        constexpr int m = 2 * W + E;
-        p12[E] = mul_bcast<m>(xa[1], xa[2]);
-        p13[E] = mul_bcast<m>(xa[1], xa[3]);
-        p23[E] = mul_bcast<m>(xa[2], xa[3]);
+    static_for<NT>([&](auto T) {
+        constexpr TileDesc td = tile_desc(W, decltype(T)::value);
+        if constexpr (td.kind == 1 && m3_product_of(W, decltype(T)::value) == decltype(T)::value)
+            p[T] = mul_bcast<td.d>(xa[td.gb], xa[td.gc]);
     });
-    static_for<9>([&](auto HU) {
-        constexpr int h = 9 * W + HU;
-        constexpr int gd = h / 2, g = gd / 9, d = gd % 9;
-        pw[HU] = xa[g] * row_ror<d>(xa[g]);
+    static_for<NT>([&](auto T) {
+        constexpr TileDesc td = tile_desc(W, decltype(T)::value);
+        if constexpr (td.kind == 0 && m3_product_of(W, decltype(T)::value) == decltype(T)::value)
+            p[T] = xa[td.gb] * row_ror<td.d>(xa[td.gb]);
     });
     __builtin_amdgcn_sched_barrier(0);
-    // pair-in-group half units
-    static_for<9>([&](auto HU) {
-        constexpr int h = 9 * W + HU;
-        constexpr int half = h % 2;
-        acc[2 * HU] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[2 * half], pw[HU], acc[2 * HU], 0, 0, 0);
-        acc[2 * HU + 1] =
-            __builtin_amdgcn_mfma_f32_16x16x4f32(xa[2 * half + 1], pw[HU], acc[2 * HU + 1], 0, 0, 0);
-    });
-    // three different groups
-    static_for<2>([&](auto E) {
-        acc[18 + E] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[0], p12[E], acc[18 + E], 0, 0, 0);
-        acc[20 + E] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[0], p13[E], acc[20 + E], 0, 0, 0);
-        acc[22 + 2 * E] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[0], p23[E], acc[22 + 2 * E], 0, 0, 0);
-        acc[23 + 2 * E] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[1], p23[E], acc[23 + 2 * E], 0, 0, 0);
+    static_for<NT>([&](auto T) {
+        constexpr TileDesc td = tile_desc(W, decltype(T)::value);
+        constexpr int pi = m3_product_of(W, decltype(T)::value);
+        acc[T] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[td.r], p[pi], acc[T], 0, 0, 0);
     });
     __builtin_amdgcn_sched_barrier(0);
 }
@@ -204,9 +214,10 @@ __device__ __forceinline__ void m3_wave(const float *__restrict__ X, int64_t s_b
                                         u32 n, float *__restrict__ part, float (*xs)[M3_CH * 64], u32 tid)
 {
     const u32 lane = tid & 63u;
-    f32x4 acc[M3_TPW];
+    constexpr int NT = m3_tpw(W);
+    f32x4 acc[NT];
 #pragma unroll
-    for (int t = 0; t < M3_TPW; ++t) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    for (int t = 0; t < NT; ++t) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
     const int64_t nchunks = (s_end - s_begin + M3_CH - 1) / M3_CH;
     f32x4 r[M3_LPT];
@@ -251,9 +262,9 @@ __device__ __forceinline__ void m3_wave(const float *__restrict__ X, int64_t s_b
         __syncthreads();
     }
 
-    float *dst = part + (size_t)W * M3_TPW * 256 + lane;
+    float *dst = part + (size_t)m3_tile_base(W) * 256 + lane;
 #pragma unroll
-    for (int t = 0; t < M3_TPW; ++t)
+    for (int t = 0; t < NT; ++t)
 #pragma unroll
         for (int v = 0; v < 4; ++v) dst[(t * 4 + v) * 64] = acc[t][v];
 }
@@ -298,7 +309,8 @@ __global__ __launch_bounds__(256) void moment3_reduce_kernel(const float *__rest
     const u32 lane = threadIdx.x & 63u, sl = threadIdx.x >> 6;
     const u32 e = blockIdx.x * 64u + lane;        // raw accumulator id, < M3_ACC
     const u32 tile = e >> 8, v = (e >> 6) & 3u;
-    TileDesc td = tile_desc((int)(tile / M3_TPW), (int)(tile % M3_TPW));
+    const int tw = tile < 100u ? (int)(tile / 25u) : 4 + (int)((tile - 100u) / 24u);
+    TileDesc td = tile_desc(tw, (int)tile - m3_tile_base(tw));
     // D layout of the 16x16 MFMA: lane holds column lane%16 of rows 4*(lane/16) + v
     u32 rowel = 4u * (lane >> 4) + v, col = lane & 15u;
     u32 i = 4u * rowel + (u32)td.r, j, k;
@@ -308,7 +320,15 @@ __global__ __launch_bounds__(256) void moment3_reduce_kernel(const float *__rest
         j = 4u * col + (u32)td.gb;
         k = 4u * other + (u32)td.gb;
         keep = (td.d < 8) || (col < 8u);                       // distance 8 lists each pair twice
-        if (td.r == td.gb) keep = keep && rowel <= min(col, other);   // row is the smallest of the three
+        if (td.r == td.gb) {
+            // all three in one group: the triple has up to three (row, pair) positions; the one whose pair is
+            // closest (then: whose row is smallest) is kept.  Three cyclic gaps add up to 16, so the closest pair
+            // is at distance <= 5 and the tiles (g, d >= 6, r = g) are never needed.
+            const u32 d1 = (rowel - other) & 15u, d2 = (rowel - col) & 15u;
+            const u32 key = 16u * (u32)td.d + rowel;
+            const u32 key1 = 16u * min(d1, 16u - d1) + col, key2 = 16u * min(d2, 16u - d2) + other;
+            keep = keep && key <= key1 && key <= key2;
+        }
     } else {
         j = 4u * (u32)td.d + (u32)td.gb;
         k = 4u * col + (u32)td.gc;
