@@ -17,12 +17,13 @@
 //     16 pairs (m, m-d mod 16) of g at cyclic distance d = 0..8, rows = group r.
 //     P = xa[g] * rotate_d(xa[g]) is one VALU multiply with a DPP row rotate
 //     and is shared by the four row groups.  When r = g all three indices lie in
-//     one group of 16; their three cyclic gaps add up to 16, so two of them are
-//     at distance <= 5 and the tiles (g, d >= 6, r = g) are not needed:
-//     4 * 9 * 4 - 12 tiles.
-// 196 tiles cover every unordered triple (50,176 accumulators for the 45,760
+//     one group of 16 and two of them have the same parity, i.e. an even
+//     distance: the tiles (g, odd d, r = g) are not needed.  At distance 8 there
+//     are only 8 pairs per group, so two groups share a tile (a lane select
+//     between two products).  4 * (4 * 4 + 4 * 3) + 8 tiles.
+// 184 tiles cover every unordered triple (47,104 accumulators for the 45,760
 // unique entries, against 64^3 = 262,144 dense ones).  A workgroup (8 waves,
-// 25 or 24 tiles per wave so that every SIMD has 49, about 100 accumulator
+// 23 tiles = 92 accumulator
 // registers per wave) owns ALL accumulators and streams a contiguous slice of
 // the samples through a double-buffered LDS chunk of 64 samples that the whole
 // workgroup loads once (X is read from HBM exactly once; the loads of chunk c+2
@@ -54,13 +55,9 @@ template <int N, typename F> __device__ __forceinline__ void static_for(F &&f)
 }
 
 constexpr int M3_WAVES = 8;
-constexpr int M3_TILES = 196;
+constexpr int M3_TPW = 23;                         // tiles per wave
+constexpr int M3_TILES = M3_WAVES * M3_TPW;        // 184
 constexpr int M3_ACC = M3_TILES * 256;             // accumulators per workgroup
-// waves w and w+4 share a SIMD: 25 + 24 tiles on each of the four
-__host__ __device__ constexpr int m3_npair(int w) { return w < 4 ? 17 : 16; }                     // pair tiles of wave w
-__host__ __device__ constexpr int m3_pair_start(int w) { return w < 4 ? 17 * w : 68 + 16 * (w - 4); }
-__host__ __device__ constexpr int m3_tpw(int w) { return m3_npair(w) + 8; }                       // tiles of wave w
-__host__ __device__ constexpr int m3_tile_base(int w) { return w < 4 ? 25 * w : 100 + 24 * (w - 4); }
 constexpr int M3_GMAX = 256;
 
 // lane m of each 16-lane row reads lane (m - D) mod 16 of the same row
@@ -97,28 +94,29 @@ template <int M> __device__ __forceinline__ float mul_bcast(float bsrc, float ot
 }
 
 // Tile descriptor shared by the accumulation kernel (compile time) and the
-// reduction kernel (run time).  The 132 pair-in-group tiles are listed by (group g,
-// distance d, row group r), r fastest, without the twelve (g, d >= 6, r = g); wave w
-// takes m3_npair(w) consecutive ones from m3_pair_start(w), then eight tiles of three
-// different groups:
-//   +0,+1 : groups (r=0, 1, 2), fixed element m = 2w + 0/1 of group 1
-//   +2,+3 : groups (r=0, 1, 3), fixed element m = 2w + 0/1 of group 1
-//   +4..7 : groups (r, 2, 3), fixed element m = 2w + (l-4)/2 of group 2, r = (l-4)%2
+// reduction kernel (run time).  Tile `local` of wave `w`:
+//   0..13  : pair-in-group tiles of group g = w/2: the 28 tiles (d, r) of the group, d = 0..7, r fastest,
+//            r = g only for even d; wave w takes the half w%2
+//   14     : distance-8 tile of the groups (2(w/4), 2(w/4)+1), row group r = w%4
+//   15,16  : groups (r=0, 1, 2), fixed element m = 2w + 0/1 of group 1
+//   17,18  : groups (r=0, 1, 3), fixed element m = 2w + 0/1 of group 1
+//   19..22 : groups (r, 2, 3), fixed element m = 2w + (l-19)/2 of group 2, r = (l-19)%2
 struct TileDesc {
-    int kind;   // 0: pair inside group gb at distance d; 1: (element m of gb) x (group gc)
+    int kind;   // 0: pair inside group gb at distance d; 1: (element m of gb) x (group gc);
+                // 2: pairs at distance 8, columns 0..7 of group gb, columns 8..15 of group gc
     int r;      // row group
     int gb, gc; // column groups (gc unused for kind 0)
-    int d;      // cyclic distance (kind 0) or fixed element m (kind 1)
+    int d;      // cyclic distance (kinds 0, 2) or fixed element m (kind 1)
 };
 __host__ __device__ constexpr TileDesc tile_desc(int w, int local)
 {
-    if (local < m3_npair(w)) {
-        const int t = m3_pair_start(w) + local, g = t / 33, u = t % 33;
-        if (u < 24) return TileDesc{0, u % 4, g, 0, u / 4};
-        const int rr = (u - 24) % 3;
-        return TileDesc{0, rr + (rr >= g ? 1 : 0), g, 0, 6 + (u - 24) / 3};
+    if (local < 14) {
+        const int g = w / 2, u = 14 * (w % 2) + local, dd = u / 7, v = u % 7;
+        if (v < 4) return TileDesc{0, v, g, 0, 2 * dd};
+        return TileDesc{0, (v - 4) + ((v - 4) >= g ? 1 : 0), g, 0, 2 * dd + 1};
     }
-    const int l = local - m3_npair(w);
+    if (local == 14) return TileDesc{2, w % 4, 2 * (w / 4), 2 * (w / 4) + 1, 8};
+    const int l = local - 15;
     if (l < 2) return TileDesc{1, 0, 1, 2, 2 * w + l};
     if (l < 4) return TileDesc{1, 0, 1, 3, 2 * w + (l - 2)};
     return TileDesc{1, (l - 4) % 2, 2, 3, 2 * w + (l - 4) / 2};
@@ -180,28 +178,33 @@ __device__ __forceinline__ void store_chunk(const f32x4 (&r)[M3_LPT], float *__r
 }
 
 template <int W>
-__device__ __forceinline__ void m3_step(f32x4 (&acc)[m3_tpw(W)], const f32x4 &xa)
+__device__ __forceinline__ void m3_step(f32x4 (&acc)[M3_TPW], const f32x4 &xa, bool upper)
 {
     // All pair products of the step first, each in a register of its own, then the
     // MFMAs back to back: a product that is formed right in front of its MFMA in
     // a recycled register has to wait for the previous MFMA to release it.
-    constexpr int NT = m3_tpw(W);
-    float p[NT];
+    float p[M3_TPW];
 #ifndef ST_HOST_EMULATION
     asm volatile("s_nop 1");
 #endif
-    static_for<NT>([&](auto T) {
+    static_for<M3_TPW>([&](auto T) {
         constexpr TileDesc td = tile_desc(W, decltype(T)::value);
         if constexpr (td.kind == 1 && m3_product_of(W, decltype(T)::value) == decltype(T)::value)
             p[T] = mul_bcast<td.d>(xa[td.gb], xa[td.gc]);
     });
-    static_for<NT>([&](auto T) {
+    static_for<M3_TPW>([&](auto T) {
         constexpr TileDesc td = tile_desc(W, decltype(T)::value);
-        if constexpr (td.kind == 0 && m3_product_of(W, decltype(T)::value) == decltype(T)::value)
-            p[T] = xa[td.gb] * row_ror<td.d>(xa[td.gb]);
+        if constexpr (m3_product_of(W, decltype(T)::value) == decltype(T)::value) {
+            if constexpr (td.kind == 0) p[T] = xa[td.gb] * row_ror<td.d>(xa[td.gb]);
+            if constexpr (td.kind == 2) {
+                // lanes m < 8: pair (m, m+8) of group gb; lanes m >= 8: pair (m-8, m) of group gc
+                const float lo = xa[td.gb] * row_ror<8>(xa[td.gb]), hi = xa[td.gc] * row_ror<8>(xa[td.gc]);
+                p[T] = upper ? hi : lo;
+            }
+        }
     });
     __builtin_amdgcn_sched_barrier(0);
-    static_for<NT>([&](auto T) {
+    static_for<M3_TPW>([&](auto T) {
         constexpr TileDesc td = tile_desc(W, decltype(T)::value);
         constexpr int pi = m3_product_of(W, decltype(T)::value);
         acc[T] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[td.r], p[pi], acc[T], 0, 0, 0);
@@ -214,10 +217,10 @@ __device__ __forceinline__ void m3_wave(const float *__restrict__ X, int64_t s_b
                                         u32 n, float *__restrict__ part, float (*xs)[M3_CH * 64], u32 tid)
 {
     const u32 lane = tid & 63u;
-    constexpr int NT = m3_tpw(W);
-    f32x4 acc[NT];
+    const bool upper = (lane & 8u) != 0u;
+    f32x4 acc[M3_TPW];
 #pragma unroll
-    for (int t = 0; t < NT; ++t) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    for (int t = 0; t < M3_TPW; ++t) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
     const int64_t nchunks = (s_end - s_begin + M3_CH - 1) / M3_CH;
     f32x4 r[M3_LPT];
@@ -249,22 +252,22 @@ __device__ __forceinline__ void m3_wave(const float *__restrict__ X, int64_t s_b
             const float *nsrc = src + (g < NG - 1 ? g + 1 : NG - 1) * 1024;
             // each operand register is refilled with the next group's K-step right after
             // its last use, so three steps of MFMAs cover the LDS latency
-            m3_step<W>(acc, xa[0]);
+            m3_step<W>(acc, xa[0], upper);
             xa[0] = *reinterpret_cast<const f32x4 *>(nsrc);
-            m3_step<W>(acc, xa[1]);
+            m3_step<W>(acc, xa[1], upper);
             xa[1] = *reinterpret_cast<const f32x4 *>(nsrc + 256);
-            m3_step<W>(acc, xa[2]);
+            m3_step<W>(acc, xa[2], upper);
             xa[2] = *reinterpret_cast<const f32x4 *>(nsrc + 512);
-            m3_step<W>(acc, xa[3]);
+            m3_step<W>(acc, xa[3], upper);
             xa[3] = *reinterpret_cast<const f32x4 *>(nsrc + 768);
         }
         __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
     }
 
-    float *dst = part + (size_t)m3_tile_base(W) * 256 + lane;
+    float *dst = part + (size_t)W * M3_TPW * 256 + lane;
 #pragma unroll
-    for (int t = 0; t < NT; ++t)
+    for (int t = 0; t < M3_TPW; ++t)
 #pragma unroll
         for (int v = 0; v < 4; ++v) dst[(t * 4 + v) * 64] = acc[t][v];
 }
@@ -309,25 +312,26 @@ __global__ __launch_bounds__(256) void moment3_reduce_kernel(const float *__rest
     const u32 lane = threadIdx.x & 63u, sl = threadIdx.x >> 6;
     const u32 e = blockIdx.x * 64u + lane;        // raw accumulator id, < M3_ACC
     const u32 tile = e >> 8, v = (e >> 6) & 3u;
-    const int tw = tile < 100u ? (int)(tile / 25u) : 4 + (int)((tile - 100u) / 24u);
-    TileDesc td = tile_desc(tw, (int)tile - m3_tile_base(tw));
+    TileDesc td = tile_desc((int)(tile / M3_TPW), (int)(tile % M3_TPW));
     // D layout of the 16x16 MFMA: lane holds column lane%16 of rows 4*(lane/16) + v
     u32 rowel = 4u * (lane >> 4) + v, col = lane & 15u;
     u32 i = 4u * rowel + (u32)td.r, j, k;
     bool keep;
-    if (td.kind == 0) {
-        u32 other = (col - (u32)td.d) & 15u;
-        j = 4u * col + (u32)td.gb;
-        k = 4u * other + (u32)td.gb;
-        keep = (td.d < 8) || (col < 8u);                       // distance 8 lists each pair twice
-        if (td.r == td.gb) {
-            // all three in one group: the triple has up to three (row, pair) positions; the one whose pair is
-            // closest (then: whose row is smallest) is kept.  Three cyclic gaps add up to 16, so the closest pair
-            // is at distance <= 5 and the tiles (g, d >= 6, r = g) are never needed.
+    if (td.kind != 1) {
+        const u32 other = (col - (u32)td.d) & 15u;
+        const u32 g = (td.kind == 0 || col < 8u) ? (u32)td.gb : (u32)td.gc;
+        j = 4u * col + g;
+        k = 4u * other + g;
+        keep = true;
+        if ((u32)td.r == g) {
+            // all three in one group: the triple has up to three (row, pair) positions, and only pairs at an
+            // even distance have a tile with r = g (two of three indices have the same parity); the position
+            // whose pair is closest (then: whose row is smallest) is kept.
             const u32 d1 = (rowel - other) & 15u, d2 = (rowel - col) & 15u;
+            const u32 c1 = min(d1, 16u - d1), c2 = min(d2, 16u - d2);
             const u32 key = 16u * (u32)td.d + rowel;
-            const u32 key1 = 16u * min(d1, 16u - d1) + col, key2 = 16u * min(d2, 16u - d2) + other;
-            keep = keep && key <= key1 && key <= key2;
+            const u32 key1 = (c1 & 1u) ? 0xffffu : 16u * c1 + col, key2 = (c2 & 1u) ? 0xffffu : 16u * c2 + other;
+            keep = key <= key1 && key <= key2;
         }
     } else {
         j = 4u * (u32)td.d + (u32)td.gb;
