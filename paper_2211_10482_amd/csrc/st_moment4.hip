@@ -3,10 +3,12 @@
 // (the M3 = vec(f (x) f) (x) vec(f (x) f) term of the degree-2 polynomial-regression
 // covariance, summed over the data; about 23 of every 24 dense entries are redundant).
 //
-// Tile path (n <= 64), plain fp32 vector arithmetic.  As a matrix-core contraction
-// (pair products times pair products) the unique set would fill 16 x 16 tiles to less
-// than half, which costs more than the factor two the matrix cores are faster; on the
-// vector ALUs any set of entries can be owned by any thread, so nothing but the block
+// Three paths: matrix cores for 52 < n <= 64 (described at its kernels below), and fp32
+// vector arithmetic for the other sizes, where padding every index range to 64 would cost
+// more than the matrix cores gain.
+//
+// Tile path (n <= 52), plain fp32 vector arithmetic: on the vector ALUs any set of entries
+// can be owned by any thread, so nothing but the block
 // diagonals is padded.  The indices are cut into blocks of four; a block quadruple
 // I <= J <= K <= L (unranked with the same closed form as the entries themselves, on
 // n/4 blocks) is owned by four neighbouring lanes, one per i in block I, each with the
@@ -254,6 +256,290 @@ __global__ __launch_bounds__(256) void moment4_zero_kernel(float *__restrict__ p
     if (t < count) p[t] = 0.f;
 }
 
+// ---- matrix-core path (52 < n <= 64, indices padded to 64) ------------------------------
+// Sc(i,j,k,l) = sum_s (x_i x_j)(x_k x_l): a contraction over the samples of pair products with
+// pair products, so a 16 x 16 MFMA tile is (16 row pairs) x (16 column pairs).  As in the third
+// moment the indices are split into four groups g = i mod 4 of 16 positions m; a PAIR SET
+// (ga, gb, d) holds the 16 pairs (position m of group ga, position m-d mod 16 of group gb):
+// in-group sets ga = gb, d = 0..8 (d = 8 names every pair twice), cross sets ga < gb, d = 0..15.
+// Every 4-multiset of indices is covered exactly once by the following (row set) x (column set)
+// tiles, by the group pattern of the four indices:
+//   {0,1,2,3}: cross(0,1,.) x cross(2,3,.)                                   all unique
+//   {a,a,b,c}: in(a,.) x cross(b,c,.)                                        all unique
+//   {a,a,b,b}: in(a,.) x in(b,.), a < b                                      all unique
+//   {a,a,a,b}: in(a, even d) x cross(a,b,.): two of the three positions in a have the same
+//              parity; the position whose row pair is the closest even pair is kept
+//   {a,a,a,a}: in(a, even d) x in(a,.); smallest (d_row, d_col, row pair) is kept
+// (the reduce kernel applies the rules; a brute-force count over all 766,480 multisets gives
+// exactly one kept accumulator each).  Tiles are grouped into wave blocks of 3 row sets x 8
+// column sets = 24 MFMAs fed by 11 products per four samples; 175 blocks (4,200 tiles for the
+// 2,994 that the unique entries would fill).  A workgroup of 8 waves owns 8 blocks (22 kinds of
+// workgroup) and streams a slice of the samples through a double-buffered LDS chunk stored as
+// [step of 4 samples][group][sample slot][position], so that a wave reads either operand of a
+// product, rotated or not, as 64 consecutive floats.  The sets are run-time data (one code
+// stream for all waves): per product two LDS reads and one multiply.
+constexpr int M4M_ROWS = 3, M4M_COLS = 8, M4M_SPECS = M4M_ROWS + M4M_COLS, M4M_TPB = M4M_ROWS * M4M_COLS;
+constexpr int M4M_BLOCKS = 175, M4M_WAVES = 8, M4M_KINDS = 22, M4M_SLOTS = M4M_KINDS * M4M_WAVES;
+constexpr int M4M_ACC = M4M_TPB * 256;               // accumulators per wave block
+constexpr int M4M_THREADS = M4M_WAVES * 64;
+constexpr int M4M_CH = 64, M4M_STEPS = M4M_CH / 4;   // samples per chunk, K-steps per chunk
+constexpr int M4M_LPT = M4M_CH * 16 / M4M_THREADS;   // 16-byte pieces of a chunk per thread (2)
+constexpr int M4M_FLUSH = 128;                       // chunks (8,192 samples) per fp32 accumulation chain
+constexpr int M4M_MIN_N = 53;                        // below, the vector-ALU tiles do less work
+
+// pair set: bit 12 = valid, bits 10..11 = ga, bits 8..9 = gb, bits 0..3 = d
+struct M4MTable { int spec[M4M_SLOTS][M4M_SPECS]; int blocks; };
+constexpr int m4m_set(int ga, int gb, int d) { return 0x1000 | (ga << 10) | (gb << 8) | d; }
+constexpr void m4m_add(M4MTable &t, const int *rows, int nr, const int *cols, int nc)
+{
+    for (int r0 = 0; r0 < nr; r0 += M4M_ROWS)
+        for (int c0 = 0; c0 < nc; c0 += M4M_COLS) {
+            for (int i = 0; i < M4M_ROWS; ++i) t.spec[t.blocks][i] = r0 + i < nr ? rows[r0 + i] : 0;
+            for (int j = 0; j < M4M_COLS; ++j) t.spec[t.blocks][M4M_ROWS + j] = c0 + j < nc ? cols[c0 + j] : 0;
+            ++t.blocks;
+        }
+}
+constexpr M4MTable m4m_make_table()
+{
+    M4MTable t{};
+    int rows[16] = {}, cols[64] = {};
+    for (int d = 0; d < 16; ++d) { rows[d] = m4m_set(0, 1, d); cols[d] = m4m_set(2, 3, d); }
+    m4m_add(t, rows, 16, cols, 16);
+    for (int a = 0; a < 4; ++a)
+        for (int b = 0; b < 4; ++b)
+            for (int c = b + 1; c < 4; ++c) {
+                if (b == a || c == a) continue;
+                for (int d = 0; d < 9; ++d) rows[d] = m4m_set(a, a, d);
+                for (int d = 0; d < 16; ++d) cols[d] = m4m_set(b, c, d);
+                m4m_add(t, rows, 9, cols, 16);
+            }
+    for (int a = 0; a < 3; ++a) {
+        int nc = 0;
+        for (int d = 0; d < 9; ++d) rows[d] = m4m_set(a, a, d);
+        for (int b = a + 1; b < 4; ++b)
+            for (int d = 0; d < 9; ++d) cols[nc++] = m4m_set(b, b, d);
+        m4m_add(t, rows, 9, cols, nc);
+    }
+    for (int a = 0; a < 4; ++a) {
+        int nc = 0;
+        for (int e = 0; e < 5; ++e) rows[e] = m4m_set(a, a, 2 * e);
+        for (int b = 0; b < 4; ++b)
+            if (b != a)
+                for (int d = 0; d < 16; ++d) cols[nc++] = m4m_set(a < b ? a : b, a < b ? b : a, d);
+        m4m_add(t, rows, 5, cols, nc);
+        for (int d = 0; d < 9; ++d) cols[d] = m4m_set(a, a, d);
+        m4m_add(t, rows, 5, cols, 9);
+    }
+    return t;
+}
+static_assert(m4m_make_table().blocks == M4M_BLOCKS, "wave blocks of the fourth-moment tile table");
+__constant__ M4MTable m4m_table = m4m_make_table();
+
+template <bool FULL>
+__device__ __forceinline__ void m4m_load_chunk(f32x4 (&r)[M4M_LPT], const float *__restrict__ X, int64_t s0,
+                                               int64_t s_end, u32 n, u32 tid)
+{
+#pragma unroll
+    for (int k = 0; k < M4M_LPT; ++k) {
+        const u32 j = tid + (u32)M4M_THREADS * k, smp = j >> 4, c0 = 4u * (j & 15u);
+        const int64_t s = s0 + smp, sc = s < s_end ? s : s_end - 1;
+        if constexpr (FULL) {
+            const float4 t = *reinterpret_cast<const float4 *>(X + sc * 64 + c0);
+            r[k] = (f32x4){t.x, t.y, t.z, t.w};
+        } else {
+            const float *row = X + sc * (int64_t)n;
+#pragma unroll
+            for (u32 g = 0; g < 4; ++g) r[k][g] = row[c0 + g < n ? c0 + g : n - 1];
+        }
+    }
+}
+// piece (sample smp, position m = columns 4m..4m+3) -> [step smp/4][group g][slot smp%4][m]
+template <bool FULL>
+__device__ __forceinline__ void m4m_store_chunk(const f32x4 (&r)[M4M_LPT], float *__restrict__ buf, int64_t s0,
+                                                int64_t s_end, u32 n, u32 tid)
+{
+#pragma unroll
+    for (int k = 0; k < M4M_LPT; ++k) {
+        const u32 j = tid + (u32)M4M_THREADS * k, smp = j >> 4, m = j & 15u;
+        const bool live = s0 + smp < s_end;
+        float *dst = buf + (smp >> 2) * 256u + (smp & 3u) * 16u + m;
+#pragma unroll
+        for (u32 g = 0; g < 4; ++g) dst[g * 64u] = (live && (FULL || 4u * m + g < n)) ? r[k][g] : 0.f;
+    }
+}
+
+template <bool FULL>
+__global__ __launch_bounds__(M4M_THREADS) void moment4_mfma_kernel(const float *__restrict__ X, int64_t N, u32 n,
+                                                                 int64_t slice, float *__restrict__ ws)
+{
+    __shared__ __attribute__((aligned(16))) float xs[2][M4M_CH * 64];
+    const u32 tid = threadIdx.x, lane = tid & 63u;
+    const u32 wave = (u32)__builtin_amdgcn_readfirstlane((int)(tid >> 6));
+    const u32 kind = blockIdx.x % (u32)M4M_KINDS, sl = blockIdx.x / (u32)M4M_KINDS;
+    const u32 block = kind * (u32)M4M_WAVES + wave;          // the last slot of the last kind is empty
+    const int64_t s_begin = (int64_t)sl * slice, s_end = s_begin + slice < N ? s_begin + slice : N;
+
+    // per-lane float offsets of the two operands of every product inside a K-step
+    u32 oa[M4M_SPECS], ob[M4M_SPECS];
+#pragma unroll
+    for (int u = 0; u < M4M_SPECS; ++u) {
+        const u32 sp = (u32)m4m_table.spec[block][u];
+        const u32 ga = (sp >> 10) & 3u, gb = (sp >> 8) & 3u, d = sp & 15u;
+        oa[u] = ga * 64u + lane;
+        ob[u] = gb * 64u + (lane & 48u) + ((lane - d) & 15u);
+    }
+    f32x4 acc[M4M_TPB];
+#pragma unroll
+    for (int t = 0; t < M4M_TPB; ++t) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+    const int64_t nchunks = (s_end - s_begin + M4M_CH - 1) / M4M_CH;
+    float *dst = ws + ((size_t)sl * M4M_SLOTS + block) * M4M_ACC + lane;
+    f32x4 r[M4M_LPT];
+    m4m_load_chunk<FULL>(r, X, s_begin, s_end, n, tid);
+    m4m_store_chunk<FULL>(r, xs[0], s_begin, s_end, n, tid);
+    if (nchunks > 1) m4m_load_chunk<FULL>(r, X, s_begin + M4M_CH, s_end, n, tid);
+    __syncthreads();
+
+    for (int64_t c = 0; c < nchunks; ++c) {
+        const u32 cb = (u32)(c & 1);
+        // registers hold chunk c+1: park it in the other buffer (its readers finished before the
+        // barrier that ended the previous iteration), then put chunk c+2 in flight
+        if (c + 1 < nchunks) m4m_store_chunk<FULL>(r, xs[cb ^ 1u], s_begin + (c + 1) * M4M_CH, s_end, n, tid);
+        if (c + 2 < nchunks) m4m_load_chunk<FULL>(r, X, s_begin + (c + 2) * M4M_CH, s_end, n, tid);
+        __builtin_amdgcn_sched_barrier(0);
+        const float *base = xs[cb];
+        float a[2][M4M_SPECS], b[2][M4M_SPECS];
+#pragma unroll
+        for (int u = 0; u < M4M_SPECS; ++u) { a[0][u] = base[oa[u]]; b[0][u] = base[ob[u]]; }
+#pragma unroll
+        for (int st = 0; st < M4M_STEPS; ++st) {
+            const int cur = st & 1, nxt = cur ^ 1;
+            if (st + 1 < M4M_STEPS) {          // operands of the next step are in flight under this step's MFMAs
+#pragma unroll
+                for (int u = 0; u < M4M_SPECS; ++u) {
+                    a[nxt][u] = base[(st + 1) * 256 + oa[u]];
+                    b[nxt][u] = base[(st + 1) * 256 + ob[u]];
+                }
+            }
+            float p[M4M_SPECS];
+#pragma unroll
+            for (int u = 0; u < M4M_SPECS; ++u) p[u] = a[cur][u] * b[cur][u];
+#pragma unroll
+            for (int i = 0; i < M4M_ROWS; ++i)
+#pragma unroll
+                for (int j = 0; j < M4M_COLS; ++j)
+                    acc[i * M4M_COLS + j] = __builtin_amdgcn_mfma_f32_16x16x4f32(p[i], p[M4M_ROWS + j],
+                                                                               acc[i * M4M_COLS + j], 0, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        __syncthreads();
+        // Long fp32 accumulation chains lose accuracy (a slice is ~180,000 samples at N = 2,000,000): every
+        // M4M_FLUSH chunks the accumulators are added to the wave's own partial in the workspace and cleared.
+        if ((c + 1) % M4M_FLUSH == 0 && c + 1 < nchunks) {
+            const bool first = c + 1 == M4M_FLUSH;
+#pragma unroll
+            for (int t = 0; t < M4M_TPB; ++t)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    float *q = dst + (t * 4 + v) * 64;
+                    *q = first ? acc[t][v] : *q + acc[t][v];
+                    acc[t][v] = 0.f;
+                }
+        }
+    }
+    const bool add = nchunks > M4M_FLUSH;
+#pragma unroll
+    for (int t = 0; t < M4M_TPB; ++t)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+            float *q = dst + (t * 4 + v) * 64;
+            *q = add ? *q + acc[t][v] : acc[t][v];
+        }
+}
+
+__device__ __forceinline__ u32 m4m_cyc(u32 x, u32 y)
+{
+    const u32 t = (x - y) & 15u;
+    return min(t, 16u - t);
+}
+
+// One thread per raw accumulator: decides whether it is the kept position of its index multiset,
+// adds the S slice partials in ascending order and scatters through rank4.
+__global__ __launch_bounds__(256) void moment4_mfma_reduce_kernel(const float *__restrict__ ws, u32 S, u32 n,
+                                                                 float *__restrict__ Sc, int accumulate)
+{
+    const u32 e = blockIdx.x * 256u + threadIdx.x;               // < M4M_BLOCKS * M4M_ACC
+    if (e >= (u32)M4M_BLOCKS * (u32)M4M_ACC) return;
+    const u32 block = e / (u32)M4M_ACC, loc = e - block * (u32)M4M_ACC;
+    const u32 t = loc >> 8, v = (loc >> 6) & 3u, lane = loc & 63u;
+    // D layout of the 16x16 MFMA: lane holds column lane%16 of rows 4*(lane/16) + v
+    const u32 m = 4u * (lane >> 4) + v, mp = lane & 15u;
+    const u32 rs = (u32)m4m_table.spec[block][t / (u32)M4M_COLS];
+    const u32 cs = (u32)m4m_table.spec[block][(u32)M4M_ROWS + t % (u32)M4M_COLS];
+    if (!(rs & 0x1000u) || !(cs & 0x1000u)) return;
+    const u32 g1 = (rs >> 10) & 3u, g2 = (rs >> 8) & 3u, dr = rs & 15u;
+    const u32 g3 = (cs >> 10) & 3u, g4 = (cs >> 8) & 3u, dc = cs & 15u;
+    const u32 x1 = m, x2 = (m - dr) & 15u, x3 = mp, x4 = (mp - dc) & 15u;
+    // an in-group set at distance 8 names every pair twice
+    if ((g1 == g2 && dr == 8u && m >= 8u) || (g3 == g4 && dc == 8u && mp >= 8u)) return;
+    bool keep = true;
+    if (g1 == g2) {
+        const u32 a = g1;
+        if (g3 != g4) {
+            if (g3 == a || g4 == a) {
+                // three positions in group a: the row pair must be the closest even pair (ties: smallest third)
+                const u32 z = g3 == a ? x3 : x4;
+                const u32 d1 = m4m_cyc(x1, z), d2 = m4m_cyc(x2, z);
+                const u32 k0 = 16u * dr + z;
+                const u32 k1 = (d1 & 1u) ? 0xffffu : 16u * d1 + x2, k2 = (d2 & 1u) ? 0xffffu : 16u * d2 + x1;
+                keep = k0 <= k1 && k0 <= k2;
+            }
+        } else if (g3 == a) {
+            // all four in group a: of the three pairings (either pair as the row pair, which needs an even
+            // distance) the smallest (d_row, d_col, row pair) is kept
+            const u32 el[4] = {x1, x2, x3, x4};
+            auto key = [](u32 r0, u32 r1, u32 c0, u32 c1) -> u32 {
+                const u32 d = m4m_cyc(r0, r1);
+                if (d & 1u) return 0xffffffffu;
+                return ((d * 9u + m4m_cyc(c0, c1)) * 16u + min(r0, r1)) * 16u + max(r0, r1);
+            };
+            const u32 k0 = key(x1, x2, x3, x4);
+            keep = key(x3, x4, x1, x2) >= k0 && key(el[0], el[2], el[1], el[3]) >= k0 &&
+                   key(el[1], el[3], el[0], el[2]) >= k0 && key(el[0], el[3], el[1], el[2]) >= k0 &&
+                   key(el[1], el[2], el[0], el[3]) >= k0;
+        }
+    }
+    u32 i = 4u * x1 + g1, j = 4u * x2 + g2, k = 4u * x3 + g3, l = 4u * x4 + g4;
+    if (!keep || i >= n || j >= n || k >= n || l >= n) return;
+    float s = 0.f;
+    const size_t stride = (size_t)M4M_SLOTS * M4M_ACC;
+#pragma unroll 4
+    for (u32 y = 0; y < S; ++y) s += ws[(size_t)y * stride + e];
+    // sort the four indices
+    u32 lo = min(i, j), hi = max(i, j); i = lo; j = hi;
+    lo = min(k, l); hi = max(k, l); k = lo; l = hi;
+    lo = min(i, k); hi = max(i, k); i = lo; k = hi;
+    lo = min(j, l); hi = max(j, l); j = lo; l = hi;
+    lo = min(j, k); hi = max(j, k); j = lo; k = hi;
+    const u32 pos = rank_sym4<u32>(n, i, j, k, l);
+    Sc[pos] = accumulate ? Sc[pos] + s : s;
+}
+
+// sample slices of the matrix-core path: one workgroup per compute unit
+struct M4MPlan { u32 S; int64_t slice; };
+static inline M4MPlan m4m_plan(int64_t N)
+{
+    M4MPlan p;
+    int64_t S = num_cus() / M4M_KINDS;
+    const int64_t smax = (N + M4M_CH - 1) / M4M_CH;
+    if (S > smax) S = smax;
+    if (S < 1) S = 1;
+    p.slice = ((N + S - 1) / S + M4M_CH - 1) / M4M_CH * M4M_CH;
+    p.S = (u32)((N + p.slice - 1) / p.slice);
+    return p;
+}
+static inline bool m4_use_mfma(int n) { return n >= M4M_MIN_N && n <= 64; }
+
 struct M4Plan {
     u32 nb4, nbq, gx, S, ch;
     int64_t slice;
@@ -280,6 +566,7 @@ static inline M4Plan m4_plan(int64_t N, int n)
 size_t moment4_workspace(int64_t N, int n)
 {
     if (N == 0) return 0;
+    if (m4_use_mfma(n)) return (size_t)m4m_plan(N).S * M4M_SLOTS * M4M_ACC * sizeof(float);
     M4Plan p = m4_plan(N, n);
     return (size_t)p.S * p.nbq * 256u * sizeof(float);
 }
@@ -290,6 +577,20 @@ st_status launch_moment4(const float *X, int64_t N, int n, float *Sc, int accumu
     if (N == 0) {
         if (!accumulate)
             hipLaunchKernelGGL(moment4_zero_kernel, dim3((count + 255u) / 256u), dim3(256), 0, s, Sc, count);
+        return launch_status();
+    }
+    if (m4_use_mfma(n)) {
+        const M4MPlan p = m4m_plan(N);
+        float *wsf = static_cast<float *>(ws);
+        if (n == 64)
+            hipLaunchKernelGGL(moment4_mfma_kernel<true>, dim3(M4M_KINDS * p.S), dim3(M4M_THREADS), 0, s, X, N, (u32)n,
+                               p.slice, wsf);
+        else
+            hipLaunchKernelGGL(moment4_mfma_kernel<false>, dim3(M4M_KINDS * p.S), dim3(M4M_THREADS), 0, s, X, N,
+                               (u32)n, p.slice, wsf);
+        if (hipGetLastError() != hipSuccess) return ST_ERR_LAUNCH;
+        hipLaunchKernelGGL(moment4_mfma_reduce_kernel, dim3((M4M_BLOCKS * M4M_ACC + 255) / 256), dim3(256), 0, s, wsf,
+                           p.S, (u32)n, Sc, accumulate);
         return launch_status();
     }
     if (n <= 64) {

@@ -20,6 +20,7 @@
 #define __host__
 #define __forceinline__ inline
 #define __shared__
+#define __constant__
 #define __launch_bounds__(...)
 #define __restrict__
 #define HIP_SYMBOL(x) x
