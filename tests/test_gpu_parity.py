@@ -317,7 +317,8 @@ def test_moment2_full(st, oracle):
 
 # ---------------------------------------------------------------------- moment4 (M3)
 @pytest.mark.parametrize("N,n", [(1, 1), (7, 5), (100, 16), (300, 64), (65, 64), (64, 64), (50, 20), (130, 63),
-                                 (40, 70), (70, 65), (33, 100), (200, 53), (90, 57), (3000, 60), (50, 52)])
+                                 (40, 70), (70, 65), (33, 100), (200, 53), (90, 57), (3000, 60), (50, 52),
+                                 (40, 80), (25, 75), (20, 128), (11, 113)])
 def test_moment4_small(st, oracle, N, n):
     say("moment4 N=%d n=%d" % (N, n))
     X = W.normal(401, N * n).reshape(N, n)
@@ -362,6 +363,41 @@ def test_moment4_special_cases(st, oracle):
     lhs = float((mult * got).sum())
     rhs = float((X.astype(np.float64).sum(axis=1) ** 4).sum())
     assert abs(lhs - rhs) <= 1e-4 * abs(rhs)
+
+
+def lex_position4(n, q):
+    """Position of the sorted quadruple q among all non-decreasing quadruples over 0..n-1 in lexicographic
+    order, by counting the ones in front of it (combinatorial number system; math.comb only)."""
+    from math import comb
+    i, j, k, l = (int(v) for v in q)
+    return (sum(comb(n - a + 2, 3) for a in range(i)) + sum(comb(n - b + 1, 2) for b in range(i, j))
+            + sum(n - c for c in range(j, k)) + (l - k))
+
+
+@pytest.mark.parametrize("N,n", [(5000, 128), (3000, 200), (700, 256), (9000, 96)])
+def test_moment4_wide(st, oracle, N, n):
+    """Feature counts beyond 64 (the matrix-core path with 6 to 16 index groups): sampled entries, among them
+    quadruples with repeated indices and with several indices in one group of 16."""
+    say("moment4 wide N=%d n=%d" % (N, n))
+    X = W.normal(404, N * n).reshape(N, n)
+    got = st.moment4_sym(dev(X)).cpu().numpy()
+    rng = np.random.default_rng(11)
+    quads = [rng.integers(0, n, 4) for _ in range(700)]
+    for _ in range(500):                                   # close together: same group, repeated values
+        base = int(rng.integers(0, n))
+        quads.append(np.clip(base + rng.integers(-9, 10, 4), 0, n - 1))
+    for _ in range(200):                                   # two pairs of neighbours
+        a, b = rng.integers(0, n, 2)
+        quads.append(np.clip(np.array([a, a + rng.integers(0, 3), b, b + rng.integers(0, 3)]), 0, n - 1))
+    quads += [np.array([0, 0, 0, 0]), np.array([n - 1] * 4), np.array([0, 0, n - 1, n - 1]), np.array([0, 1, 2, 3])]
+    quads = np.unique(np.sort(np.array(quads, dtype=np.int64), axis=1), axis=0)
+    pos = np.array([lex_position4(n, q) for q in quads], dtype=np.int64)
+    assert got.shape[0] == lex_position4(n, (n - 1,) * 4) + 1 == oracle.count_sym4(n)
+    ref = oracle.moment4_entries(X, quads.astype(np.int32))
+    err = float(np.abs(got[pos] - ref).max() / np.abs(ref).max())
+    say("  norm-wise error on %d sampled entries %.3e" % (pos.size, err))
+    assert err <= TOL
+    assert np.all(np.isfinite(got))
 
 
 def test_moment4_full(st, oracle):

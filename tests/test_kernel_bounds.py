@@ -38,8 +38,9 @@ CASES = {
     "MOMENT2": [(5000, 64, 0), (4097, 64, 1), (3, 64, 0), (100000, 64, 0), (1000, 20, 0), (3, 5, 1), (700, 70, 0),
                 (50, 300, 0), (200, 65, 1), (40, 1024, 0), (9, 1030, 0)],
     # moment4: N n accumulate  (n <= 64: static 64-column chunks; 64 < n <= 256: dynamic chunks of padded rows)
+    # (56 <= n <= 64 and 14*ceil(n/16) <= n <= 256: the matrix-core path, table in the workspace)
     "MOMENT4": [(300, 64, 0), (65, 64, 1), (1, 64, 0), (200, 20, 0), (130, 63, 0), (3, 5, 1), (9, 70, 0),
-                (70, 65, 1), (3, 129, 0)],
+                (70, 65, 1), (3, 129, 0), (100, 80, 0), (37, 75, 1), (20, 130, 0), (9, 200, 1)],
     # expand: n order | n 10+kind w p0 count  (device unrank of kind 2, 3, 4 = band, 5 = sym4)
     "EXPAND": [(64, 3), (100, 2), (7, 3), (1, 2), (17, 4), (32, 4), (100, 12, 0, 17, 5000), (100, 13, 0, 17, 5000),
                (100, 14, 7, 17, 1000), (40, 15, 0, 17, 5000)],
