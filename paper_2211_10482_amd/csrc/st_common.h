@@ -49,6 +49,12 @@ size_t moment4_workspace(int64_t N, int n);
 st_status launch_moment4(const float *X, int64_t N, int n, float *Sc, int accumulate, void *ws,
                          hipStream_t s);
 
+// third / fourth moment on the matrix cores for up to 256 features (st_moment_mfma.hip)
+bool moment_mfma_wins(int order, int n);
+size_t moment_mfma_workspace(int order, int64_t N, int n);
+st_status launch_moment_mfma(int order, const float *X, int64_t N, int n, float *Sc, int accumulate, void *ws,
+                             hipStream_t s);
+
 size_t mttkrp_workspace(int n, int R);
 st_status launch_mttkrp(const float *Tc, const float *B, float *M, int n, int R, void *ws,
                         hipStream_t s);

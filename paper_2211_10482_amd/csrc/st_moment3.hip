@@ -32,7 +32,9 @@
 // fixed order, drops the padding / duplicate positions and scatters through
 // rank3.  No float atomics.
 //
-// General path (n > 64): one thread per unique entry and sample slice.
+// Other feature counts: a table-driven matrix-core kernel for most 64 < n <= 256
+// (st_moment_mfma.hip), register tiles on the vector ALUs for n <= 40 and the rest
+// up to 256, one thread per unique entry and sample slice beyond.
 #include <type_traits>
 #include <utility>
 
@@ -595,6 +597,7 @@ static inline bool m3_use_tiles(int n) { return n <= 40 || (n > 64 && n <= M3T_N
 size_t moment3_workspace(int64_t N, int n)
 {
     if (N == 0) return 0;
+    if (moment_mfma_wins(3, n)) return moment_mfma_workspace(3, N, n);
     if (m3_use_tiles(n)) {
         const M3TPlan p = m3t_plan(N, n);
         return (size_t)p.S * p.nbt * 64u * sizeof(float);
@@ -611,6 +614,7 @@ st_status launch_moment3(const float *X, int64_t N, int n, float *Sc, int accumu
         if (!accumulate) hipLaunchKernelGGL(zero_kernel, dim3((count + 255u) / 256u), dim3(256), 0, s, Sc, count);
         return launch_status();
     }
+    if (moment_mfma_wins(3, n)) return launch_moment_mfma(3, X, N, n, Sc, accumulate, ws, s);
     float *wsf = static_cast<float *>(ws);
     if (m3_use_tiles(n)) {
         const M3TPlan p = m3t_plan(N, n);

@@ -9,10 +9,12 @@
 #include "../../paper_2211_10482_amd/csrc/st_ttm.hip"
 #elif defined(CHECK_MOMENT3)
 #include "../../paper_2211_10482_amd/csrc/st_moment3.hip"
+#include "../../paper_2211_10482_amd/csrc/st_moment_mfma.hip"
 #elif defined(CHECK_MOMENT2)
 #include "../../paper_2211_10482_amd/csrc/st_moment2.hip"
 #elif defined(CHECK_MOMENT4)
 #include "../../paper_2211_10482_amd/csrc/st_moment4.hip"
+#include "../../paper_2211_10482_amd/csrc/st_moment_mfma.hip"
 #elif defined(CHECK_EXPAND)
 #include "../../paper_2211_10482_amd/csrc/st_expand.hip"
 #elif defined(CHECK_TABLE)

@@ -198,7 +198,8 @@ def test_ttm_full(st, oracle):
 # --------------------------------------------------------------------- moment3
 @pytest.mark.parametrize("N,n", [(1, 5), (7, 4), (50, 9), (300, 17), (1000, 33), (100, 64), (5000, 64),
                                  (70, 1), (200, 70), (3000, 13), (2500, 6), (257, 40), (400, 48), (300, 129),
-                                 (150, 200), (40, 256), (30, 260)])
+                                 (150, 200), (40, 256), (30, 260), (500, 128), (20000, 100), (64, 65), (90, 96),
+                                 (9000, 80)])
 def test_moment3_small(st, oracle, N, n):
     say("moment3 N=%d n=%d" % (N, n))
     X = W.normal(401, N * n).reshape(N, n)
