@@ -299,7 +299,7 @@ def main():
         extra += [
             ("covar_pr2_N1e4_n200", lambda: st.covar_pr2(Xf, S=Sf, ws=wsf),
              dict(flops=Nf * (2 * tri(nf) + 2 * tet(nf) + tri(nf) + 2 * pent_f + tri(nf)),
-                  bytes=4 * (3 * Nf * nf + tri(nf) + tet(nf) + pent_f), bound="alu")),
+                  bytes=4 * (3 * Nf * nf + tri(nf) + tet(nf) + pent_f), bound="mfma")),
         ]
         # the kernel table's structures at the size of the band workload (512 x 512 x 512, R = 64)
         nt, Rt = c3["n"], c3["R"]

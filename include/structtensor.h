@@ -148,7 +148,10 @@ st_status st_ttm_band(const float *Tc, const float *U, float *Yc, int n, int w, 
  * covariance, summed over the data: "creation and addition of covariance
  * matrices").  X is N x n row-major.  accumulate = 0 overwrites Sc, 1 adds to
  * it.  Raw sums: no 1/N, no centring.  N >= 0 (N = 0 zero-fills when
- * accumulate = 0), n >= 1. */
+ * accumulate = 0), n >= 1.  The workspace can be large (64 < n <= 256: a tile
+ * table and the partial sums of every sample slice, up to 2 GB; ask
+ * st_moment3_sym_workspace); for those n the table is copied into it with
+ * hipMemcpyAsync on `stream` at every call. */
 st_status st_moment3_sym(const float *X, int64_t N, int n, float *Sc, int accumulate,
                          void *ws, size_t ws_bytes, void *stream);
 
@@ -163,7 +166,9 @@ st_status st_moment2_sym(const float *X, int64_t N, int n, float *Sc, int accumu
  *     Sc(rank4(i,j,k,l)) (+)= sum_s X(s,i) * X(s,j) * X(s,k) * X(s,l)   for i<=j<=k<=l
  * (the M3 = vec(f (x) f) (x) vec(f (x) f) term of the same covariance: about 23 of
  * every 24 dense entries are redundant).  Arguments as for st_moment3_sym; Sc has
- * st_count_sym4(n) entries; n <= 256. */
+ * st_count_sym4(n) entries; n <= 256.  For n >= 56 the workspace holds a tile
+ * table (copied in with hipMemcpyAsync at every call) and slice partials, up to
+ * about 2 GB. */
 st_status st_moment4_sym(const float *X, int64_t N, int n, float *Sc, int accumulate,
                          void *ws, size_t ws_bytes, void *stream);
 
