@@ -15,6 +15,8 @@
 #elif defined(CHECK_MOMENT4)
 #include "../../paper_2211_10482_amd/csrc/st_moment4.hip"
 #include "../../paper_2211_10482_amd/csrc/st_moment_mfma.hip"
+#elif defined(CHECK_MCOVER)
+#include "../../paper_2211_10482_amd/csrc/st_moment_mfma.hip"
 #elif defined(CHECK_EXPAND)
 #include "../../paper_2211_10482_amd/csrc/st_expand.hip"
 #elif defined(CHECK_TABLE)
@@ -71,6 +73,30 @@ int main(int argc, char **argv)
     void *ws = malloc(wsb ? wsb : 1);
     rc = st::launch_moment3(X, N, n, Sc, accumulate, ws, nullptr);
     free(X); free(Sc); free(ws);
+#elif defined(CHECK_MCOVER)
+    // The tile table and the kept-position rules of the matrix-core moment kernels: with every raw accumulator
+    // set to 1 and Sc to 0, the reduce kernel in accumulate mode must leave exactly 1 in every unique entry
+    // (each index multiset is kept at one position, no position falls outside the unique set).   args: order n
+    const int order = (int)a[0], n = (int)a[1];
+    const long N = 4;                                        // one slice
+    const size_t cnt = (size_t)(order == 3 ? st::count_sym3<int64_t>(n) : st::count_sym4<int64_t>(n));
+    const st::MMPlan p = st::mm_plan(order, N, n);
+    const st::MMTable &tab = st::mm_table(order, (int)p.G);
+    const size_t slots = (size_t)p.kinds * st::MM_WAVES, racc = (size_t)p.blocks * st::MM_ACC;
+    float *part = fbuf(slots * st::MM_ACC), *Sc = fbuf(cnt);
+    for (size_t q = 0; q < cnt; ++q) Sc[q] = 0.f;
+    if (p.S != 1) return 3;
+    if (order == 3)
+        hipLaunchKernelGGL(st::moment3_mfma_reduce_kernel, dim3((unsigned)((racc + 255) / 256)), dim3(256), 0, nullptr,
+                           part, tab.spec.data(), p.blocks, (unsigned)slots, 1u, (unsigned)n, Sc, 1);
+    else
+        hipLaunchKernelGGL(st::moment4_mfma_reduce_kernel, dim3((unsigned)((racc + 255) / 256)), dim3(256), 0, nullptr,
+                           part, tab.spec.data(), p.blocks, (unsigned)slots, 1u, (unsigned)n, Sc, 1);
+    size_t bad = 0;
+    for (size_t q = 0; q < cnt; ++q) bad += Sc[q] != 1.f;
+    printf("blocks=%u tiles=%u entries=%zu bad=%zu\n", p.blocks, p.blocks * st::MM_TPB, cnt, bad);
+    rc = bad == 0 ? 0 : 4;
+    free(part); free(Sc);
 #elif defined(CHECK_MOMENT2) || defined(CHECK_MOMENT4)
     const long N = a[0];
     const int n = (int)a[1], accumulate = (int)a[2];

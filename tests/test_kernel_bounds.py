@@ -7,6 +7,9 @@ allocates the operands with exactly the sizes the C-ABI documents and calls the 
 launchers the library calls, so an index that leaves an operand, the workspace or an
 LDS array aborts here instead of faulting a GPU.  Values are not checked (barriers and
 cross-lane operations have no meaning in this emulation); parity is the GPU tests' job.
+One family is a value check all the same: MCOVER runs the reduce kernels of the matrix-core
+moment path (no barriers in them) over accumulators that all hold 1 and counts, per unique
+entry, how many tile positions the tile table and the kept-position rules map to it: exactly one.
 """
 import os
 import shutil
@@ -41,6 +44,9 @@ CASES = {
     # (56 <= n <= 64 and 14*ceil(n/16) <= n <= 256: the matrix-core path, table in the workspace)
     "MOMENT4": [(300, 64, 0), (65, 64, 1), (1, 64, 0), (200, 20, 0), (130, 63, 0), (3, 5, 1), (9, 70, 0),
                 (70, 65, 1), (3, 129, 0), (100, 80, 0), (37, 75, 1), (20, 130, 0), (9, 200, 1)],
+    # cover of the matrix-core moment kernels: order n  (every unique entry kept at exactly one tile position)
+    "MCOVER": [(4, 64), (4, 56), (4, 80), (4, 75), (4, 100), (4, 128), (3, 65), (3, 80), (3, 100), (3, 128), (3, 200),
+               (3, 256), (3, 250)],
     # expand: n order | n 10+kind w p0 count  (device unrank of kind 2, 3, 4 = band, 5 = sym4)
     "EXPAND": [(64, 3), (100, 2), (7, 3), (1, 2), (17, 4), (32, 4), (100, 12, 0, 17, 5000), (100, 13, 0, 17, 5000),
                (100, 14, 7, 17, 1000), (40, 15, 0, 17, 5000)],
