@@ -475,21 +475,24 @@ static inline MMPlan mm_plan(int order, int64_t N, int n)
     p.table_bytes = (t.spec.size() * sizeof(int) + 255u) / 256u * 256u;
     const int64_t ch = 4 * p.steps;
     // Sample slices: every workgroup does the same work, so the kinds * S workgroups run in whole rounds of one
-    // per compute unit; the smallest S that fills at least 93 % of its rounds (else the best one), each slice at
-    // least four chunks long and the partials of all slices below 2 GB.
+    // per compute unit; S is chosen for the best filled rounds, less what the partials of a slice cost (written
+    // and read once, priced at 4 TB/s against the MFMA time of the whole job), each slice at least four chunks
+    // long and the partials of all slices below 2 GB.
     const int64_t cus = num_cus();
     int64_t smax = (N + 4 * ch - 1) / (4 * ch);
     const int64_t scap = (int64_t)(((size_t)2 << 30) / ((size_t)p.kinds * MM_WAVES * MM_ACC * sizeof(float)));
     if (smax > scap) smax = scap;
     if (smax > 256) smax = 256;
     if (smax < 1) smax = 1;
+    const double slice_bytes = (double)p.kinds * MM_WAVES * MM_ACC * sizeof(float);
+    const double mfma_seconds = (double)p.blocks * MM_TPB * ((double)N / 4.0) * 32.0 / (4.0 * (double)cus * 2.3e9);
+    const double per_slice = 0.001 + (2.0 * slice_bytes / 4e12) / mfma_seconds;
     int64_t S = 1;
-    double best = 0.0;
+    double best = -1.0;
     for (int64_t c = 1; c <= smax; ++c) {
         const int64_t wgs = (int64_t)p.kinds * c, rounds = (wgs + cus - 1) / cus;
-        const double fill = (double)wgs / (double)(rounds * cus);
-        if (fill > best + 1e-9) { best = fill; S = c; }
-        if (fill >= 0.93) { S = c; break; }
+        const double score = (double)wgs / (double)(rounds * cus) - per_slice * (double)c;
+        if (score > best + 1e-9) { best = score; S = c; }
     }
     p.slice = ((N + S - 1) / S + ch - 1) / ch * ch;
     p.S = (u32)((N + p.slice - 1) / p.slice);
