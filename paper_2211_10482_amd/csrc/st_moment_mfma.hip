@@ -327,24 +327,39 @@ __global__ __launch_bounds__(MM_THREADS) void moment_mfma_kernel(const float *__
         for (int u = 0; u < MM_SPECS; ++u) { a[0][u] = base[oa[u]]; b[0][u] = base[ob[u]]; }
 #pragma unroll
         for (int st = 0; st < STEPS; ++st) {
+            // The 22 operands of the next step are read under this step's MFMAs in three batches (8, 7, 7), one
+            // before each third of the MFMAs: the counter of outstanding LDS operations holds 15, and with more
+            // in flight the waits in front of the products drain everything.
             const int cur = st & 1, nxt = cur ^ 1;
-            if (st + 1 < STEPS) {          // operands of the next step are in flight under this step's MFMAs
+            const bool more = st + 1 < STEPS;
+            auto fetch = [&](int q0, int q1) {          // operands q of the next step: q < 11 first, else second
 #pragma unroll
-                for (int u = 0; u < MM_SPECS; ++u) {
-                    a[nxt][u] = base[(st + 1) * 64 + oa[u]];
-                    b[nxt][u] = base[(st + 1) * 64 + ob[u]];
+                for (int q = q0; q < q1; ++q) {
+                    if (q < MM_SPECS) a[nxt][q] = base[(st + 1) * 64 + oa[q]];
+                    else b[nxt][q - MM_SPECS] = base[(st + 1) * 64 + ob[q - MM_SPECS]];
                 }
-            }
+            };
+            if (more) fetch(0, 8);
+            __builtin_amdgcn_sched_barrier(0);
             float p[MM_SPECS];
 #pragma unroll
             for (int u = 0; u < MM_SPECS; ++u) p[u] = a[cur][u] * b[cur][u];
 #pragma unroll
-            for (int i = 0; i < MM_ROWS; ++i)
+            for (int t = 0; t < 8; ++t)
+                acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(p[t / MM_COLS], p[MM_ROWS + t % MM_COLS], acc[t], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (more) fetch(8, 15);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int j = 0; j < MM_COLS; ++j)
-                    acc[i * MM_COLS + j] = __builtin_amdgcn_mfma_f32_16x16x4f32(p[i], p[MM_ROWS + j],
-                                                                               acc[i * MM_COLS + j], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);      // keeps the operand reads of later steps out of this one
+            for (int t = 8; t < 16; ++t)
+                acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(p[t / MM_COLS], p[MM_ROWS + t % MM_COLS], acc[t], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (more) fetch(15, 22);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int t = 16; t < MM_TPB; ++t)
+                acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(p[t / MM_COLS], p[MM_ROWS + t % MM_COLS], acc[t], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
         __syncthreads();
         // Long fp32 accumulation chains lose accuracy (1.2e-4 norm-wise after 180,000 samples): every FLUSH
