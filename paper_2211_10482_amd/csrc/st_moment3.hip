@@ -32,9 +32,9 @@
 // fixed order, drops the padding / duplicate positions and scatters through
 // rank3.  No float atomics.
 //
-// Other feature counts: a table-driven matrix-core kernel for most 64 < n <= 256
-// (st_moment_mfma.hip), register tiles on the vector ALUs for n <= 40 and the rest
-// up to 256, one thread per unique entry and sample slice beyond.
+// Other feature counts: a table-driven matrix-core kernel for 64 < n <= 256 with
+// n >= 14 * ceil(n/16) (st_moment_mfma.hip), register tiles on the vector ALUs for
+// n <= 40 and the rest up to 256, one thread per unique entry and sample slice beyond.
 #include <type_traits>
 #include <utility>
 

@@ -3,11 +3,10 @@
 // (the M3 = vec(f (x) f) (x) vec(f (x) f) term of the degree-2 polynomial-regression
 // covariance, summed over the data; about 23 of every 24 dense entries are redundant).
 //
-// Matrix cores (st_moment_mfma.hip) where padding the indices to whole groups of 16 costs less
-// than they gain (56 <= n <= 64 and 14*ceil(n/16) <= n <= 256); fp32 vector arithmetic, in
-// this file, for the other sizes.
+// Matrix cores (st_moment_mfma.hip) from 53 features on; fp32 vector arithmetic, in this file,
+// below (where padding the indices to whole groups of 16 costs more than the matrix cores gain).
 //
-// Tile path (n <= 52), plain fp32 vector arithmetic: on the vector ALUs any set of entries
+// Tile path, plain fp32 vector arithmetic: on the vector ALUs any set of entries
 // can be owned by any thread, so nothing but the block
 // diagonals is padded.  The indices are cut into blocks of four; a block quadruple
 // I <= J <= K <= L (unranked with the same closed form as the entries themselves, on
@@ -22,8 +21,6 @@
 //
 // Algorithmic work per sample: one multiply-add per unique quadruple (+ the pair
 // products).  Bound by the fp32 vector rate.
-//
-// 64 < n <= 256: the same tiles with sample rows of 4*ceil(n/4) floats in dynamic LDS.
 #include "st_common.h"
 #include "st_index.h"
 
@@ -138,98 +135,6 @@ __global__ __launch_bounds__(M4_THREADS) void moment4_tile_kernel(const float *_
     }
 }
 
-// ---- tile path for 64 < n <= 256: the same lanes and register tiles, sample rows of 4*ceil(n/4) floats ----
-// (dynamic LDS: two chunks of `ch` samples; a chunk is as many samples as the workgroup's threads can
-// hold in flight, four 16-byte pieces each)
-__device__ __forceinline__ void m4g_load_chunk(f32x4 (&r)[M4_LPT], const float *__restrict__ X, int64_t s0,
-                                               int64_t s_end, u32 n, u32 np4, u32 pieces, u32 tid)
-{
-#pragma unroll
-    for (int k = 0; k < M4_LPT; ++k) {
-        const u32 j = min(tid + (u32)M4_THREADS * k, pieces - 1u), smp = j / np4, c0 = 4u * (j - smp * np4);
-        const int64_t s = s0 + smp, sc = s < s_end ? s : s_end - 1;
-        const float *row = X + sc * (int64_t)n;
-#pragma unroll
-        for (u32 g = 0; g < 4; ++g) r[k][g] = row[c0 + g < n ? c0 + g : n - 1u];
-    }
-}
-
-__device__ __forceinline__ void m4g_store_chunk(const f32x4 (&r)[M4_LPT], float *__restrict__ buf, int64_t s0,
-                                                int64_t s_end, u32 n, u32 np4, u32 pieces, u32 tid)
-{
-#pragma unroll
-    for (int k = 0; k < M4_LPT; ++k) {
-        const u32 j = tid + (u32)M4_THREADS * k, smp = j / np4, c0 = 4u * (j - smp * np4);
-        if (j >= pieces) continue;
-        const bool row_ok = s0 + smp < s_end;
-        f32x4 v;
-#pragma unroll
-        for (u32 g = 0; g < 4; ++g) v[g] = (row_ok && c0 + g < n) ? r[k][g] : 0.f;
-        *reinterpret_cast<f32x4 *>(buf + (size_t)j * 4u) = v;
-    }
-}
-
-__global__ __launch_bounds__(M4_THREADS) void moment4_tile_general_kernel(const float *__restrict__ X, int64_t N,
-                                                                        u32 n, u32 nb4, u32 nbq, u32 ch,
-                                                                        int64_t slice, float *__restrict__ ws)
-{
-    extern __shared__ float lds[];
-    const u32 tid = threadIdx.x, ii = tid & 3u, np4 = nb4, np = 4u * nb4;
-    const u32 pieces = ch * np4, chunk_f = ch * np;
-    const u32 bq = blockIdx.x * 64u + (tid >> 2);
-    u32 I, J, K, L;
-    unrank_sym4<u32>(nb4, min(bq, nbq - 1u), I, J, K, L);
-    const u32 oi = 4u * I + ii, oj = 4u * J, ok = 4u * K, ol = 4u * L;
-
-    const int64_t s_begin = (int64_t)blockIdx.y * slice;
-    const int64_t s_end = s_begin + slice < N ? s_begin + slice : N;
-    const int64_t nchunks = s_end > s_begin ? (s_end - s_begin + ch - 1) / ch : 0;
-
-    float acc[64];
-#pragma unroll
-    for (int e = 0; e < 64; ++e) acc[e] = 0.f;
-
-    if (nchunks > 0) {
-        f32x4 r[M4_LPT];
-        m4g_load_chunk(r, X, s_begin, s_end, n, np4, pieces, tid);
-        m4g_store_chunk(r, lds, s_begin, s_end, n, np4, pieces, tid);
-        if (nchunks > 1) m4g_load_chunk(r, X, s_begin + ch, s_end, n, np4, pieces, tid);
-        __syncthreads();
-        for (int64_t c = 0; c < nchunks; ++c) {
-            const u32 cb = (u32)(c & 1);
-            if (c + 1 < nchunks) m4g_store_chunk(r, lds + (cb ^ 1u) * chunk_f, s_begin + (c + 1) * ch, s_end, n, np4, pieces, tid);
-            if (c + 2 < nchunks) m4g_load_chunk(r, X, s_begin + (c + 2) * ch, s_end, n, np4, pieces, tid);
-            __builtin_amdgcn_sched_barrier(0);
-            const float *row = lds + cb * chunk_f;
-#pragma unroll 2
-            for (u32 smp = 0; smp < ch; ++smp, row += np) {
-                const float xi = row[oi];
-                const f32x4 xj = *reinterpret_cast<const f32x4 *>(row + oj);
-                const f32x4 xk = *reinterpret_cast<const f32x4 *>(row + ok);
-                const f32x4 xl = *reinterpret_cast<const f32x4 *>(row + ol);
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const float a = xi * xj[j];
-#pragma unroll
-                    for (int k = 0; k < 4; ++k) {
-                        const float b = a * xk[k];
-#pragma unroll
-                        for (int l = 0; l < 4; ++l) acc[(j * 4 + k) * 4 + l] += b * xl[l];
-                    }
-                }
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            __syncthreads();
-        }
-    }
-
-    if (bq < nbq) {
-        f32x4 *dst = reinterpret_cast<f32x4 *>(ws + (((size_t)blockIdx.y * nbq + bq) * 4u + ii) * 64u);
-#pragma unroll
-        for (int e = 0; e < 16; ++e) dst[e] = (f32x4){acc[4 * e], acc[4 * e + 1], acc[4 * e + 2], acc[4 * e + 3]};
-    }
-}
-
 // One thread per raw accumulator (block quadruple, lane, j, k, l): adds the S slice
 // partials in ascending order and stores the entries of the unique set.
 __global__ __launch_bounds__(256) void moment4_reduce_kernel(const float *__restrict__ ws, u32 S, u32 n, u32 nb4,
@@ -266,9 +171,7 @@ static inline M4Plan m4_plan(int64_t N, int n)
     p.nb4 = ((u32)n + 3u) / 4u;
     p.nbq = (u32)count_sym4<int64_t>(p.nb4);
     p.gx = (p.nbq + 63u) / 64u;
-    // samples per chunk: 64 up to n = 64; beyond, what the threads' 4 pieces each can hold (16 at n = 256)
-    p.ch = n <= 64 ? (u32)M4_CH : ((u32)(M4_LPT * M4_THREADS) / p.nb4) & ~3u;
-    if (p.ch > (u32)M4_CH) p.ch = (u32)M4_CH;
+    p.ch = (u32)M4_CH;
     int64_t S = (M4_WGTARGET + p.gx - 1) / p.gx;           // enough slices to fill the chip ...
     int64_t smax = (N + p.ch - 1) / p.ch;                  // ... each of at least one chunk
     if (S > smax) S = smax;
@@ -296,38 +199,15 @@ st_status launch_moment4(const float *X, int64_t N, int n, float *Sc, int accumu
         return launch_status();
     }
     if (moment_mfma_wins(4, n)) return launch_moment_mfma(4, X, N, n, Sc, accumulate, ws, s);
-    if (n <= 64) {
-        const M4Plan p = m4_plan(N, n);
-        float *wsf = static_cast<float *>(ws);
-        if (n == 64)
-            hipLaunchKernelGGL(moment4_tile_kernel<true>, dim3(p.gx, p.S), dim3(M4_THREADS), 0, s, X, N, (u32)n,
-                               p.nb4, p.nbq, p.slice, wsf);
-        else
-            hipLaunchKernelGGL(moment4_tile_kernel<false>, dim3(p.gx, p.S), dim3(M4_THREADS), 0, s, X, N, (u32)n,
-                               p.nb4, p.nbq, p.slice, wsf);
-        if (hipGetLastError() != hipSuccess) return ST_ERR_LAUNCH;
-        hipLaunchKernelGGL(moment4_reduce_kernel, dim3(p.nbq), dim3(256), 0, s, wsf, p.S, (u32)n, p.nb4, p.nbq, Sc,
-                           accumulate);
-        return launch_status();
-    }
-    {
-        const M4Plan p = m4_plan(N, n);
-        float *wsf = static_cast<float *>(ws);
-        const size_t lds_bytes = (size_t)2u * p.ch * 4u * p.nb4 * sizeof(float);      // at most 64 KB
-        static bool attr = false;
-        if (!attr) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void *>(moment4_tile_general_kernel),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024) != hipSuccess)
-                return ST_ERR_LAUNCH;
-            attr = true;
-        }
-        hipLaunchKernelGGL(moment4_tile_general_kernel, dim3(p.gx, p.S), dim3(M4_THREADS), lds_bytes, s, X, N, (u32)n,
-                           p.nb4, p.nbq, p.ch, p.slice, wsf);
-        if (hipGetLastError() != hipSuccess) return ST_ERR_LAUNCH;
-        hipLaunchKernelGGL(moment4_reduce_kernel, dim3(p.nbq), dim3(256), 0, s, wsf, p.S, (u32)n, p.nb4, p.nbq, Sc,
-                           accumulate);
-        return launch_status();
-    }
+    // n <= 52 from here on
+    const M4Plan p = m4_plan(N, n);
+    float *wsf = static_cast<float *>(ws);
+    hipLaunchKernelGGL(moment4_tile_kernel<false>, dim3(p.gx, p.S), dim3(M4_THREADS), 0, s, X, N, (u32)n, p.nb4, p.nbq,
+                       p.slice, wsf);
+    if (hipGetLastError() != hipSuccess) return ST_ERR_LAUNCH;
+    hipLaunchKernelGGL(moment4_reduce_kernel, dim3(p.nbq), dim3(256), 0, s, wsf, p.S, (u32)n, p.nb4, p.nbq, Sc,
+                       accumulate);
+    return launch_status();
 }
 
 }  // namespace st

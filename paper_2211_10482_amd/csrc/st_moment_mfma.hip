@@ -514,13 +514,13 @@ static inline MMPlan mm_plan(int order, int64_t N, int n)
     return p;
 }
 
-// Worth it while padding every index range to 16 * G costs less than the matrix cores gain over the vector-ALU
-// tiles: fourth moment 16 G <= 8/7 n, third moment (beyond the 64-feature kernel) 16 G <= 16/13 n.
+// Used where it was measured faster than the vector-ALU tiles (which pad to blocks of 4, not of 16): the fourth
+// moment from 53 features on, the third moment beyond the 64-feature kernel while 16 G <= 8/7 n.
 bool moment_mfma_wins(int order, int n)
 {
     const int G = (n + 15) / 16;
-    if (order == 4) return n >= 56 && n <= 256 && 14 * G <= n;
-    return n > 64 && n <= 256 && 13 * G <= n;
+    if (order == 4) return n >= 53 && n <= 256;
+    return n > 64 && n <= 256 && 14 * G <= n;
 }
 
 size_t moment_mfma_workspace(int order, int64_t N, int n)

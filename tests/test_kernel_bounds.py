@@ -40,8 +40,8 @@ CASES = {
     # moment2: N n accumulate  (n <= 64: the MFMA path; n <= 1024: the tile path; beyond: the plain path)
     "MOMENT2": [(5000, 64, 0), (4097, 64, 1), (3, 64, 0), (100000, 64, 0), (1000, 20, 0), (3, 5, 1), (700, 70, 0),
                 (50, 300, 0), (200, 65, 1), (40, 1024, 0), (9, 1030, 0)],
-    # moment4: N n accumulate  (n <= 64: static 64-column chunks; 64 < n <= 256: dynamic chunks of padded rows)
-    # (56 <= n <= 64 and 14*ceil(n/16) <= n <= 256: the matrix-core path, table in the workspace)
+    # moment4: N n accumulate  (n <= 52: register tiles on the vector ALUs; 53 <= n <= 256: the matrix-core path,
+    # table in the workspace)
     "MOMENT4": [(300, 64, 0), (65, 64, 1), (1, 64, 0), (200, 20, 0), (130, 63, 0), (3, 5, 1), (9, 70, 0),
                 (70, 65, 1), (3, 129, 0), (100, 80, 0), (37, 75, 1), (20, 130, 0), (9, 200, 1)],
     # cover of the matrix-core moment kernels: order n  (every unique entry kept at exactly one tile position)
