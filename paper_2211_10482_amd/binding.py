@@ -94,6 +94,10 @@ def lib():
             raise ImportError(
                 "libstructtensor_hip.so is not built: run `python -m paper_2211_10482_amd.build` "
                 "(there is no CPU fallback)")
+        # The device pointers and streams this binding passes come from PyTorch, so both must talk to ONE HIP
+        # runtime: PyTorch loads the copy it ships, and a library loaded after it binds to that copy.  Loaded
+        # the other way round, the library would pull in the system's runtime and every launch would fail.
+        import torch  # noqa: F401
         _lib = C.CDLL(LIB_PATH)
         for name, (res, args) in SIGNATURES.items():
             f = getattr(_lib, name)

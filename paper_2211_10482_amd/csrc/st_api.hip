@@ -2,6 +2,7 @@
 // and dispatch to the kernel launchers.  Every error is detected here, on the
 // host, before anything is enqueued.
 #include <mutex>
+#include <vector>
 
 #include "st_common.h"
 #include "st_index.h"
@@ -22,6 +23,21 @@ int num_cus()
         cached[dev] = v;
     }
     return cached[dev];
+}
+
+bool allow_dynamic_lds(const void *kernel, int bytes)
+{
+    struct Done { int dev; const void *kernel; int bytes; };
+    static std::mutex mu;
+    static std::vector<Done> done;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return false;
+    std::lock_guard<std::mutex> lock(mu);
+    for (const Done &d : done)
+        if (d.dev == dev && d.kernel == kernel && d.bytes >= bytes) return true;
+    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess) return false;
+    done.push_back(Done{dev, kernel, bytes});
+    return true;
 }
 
 }  // namespace st

@@ -11,6 +11,9 @@ namespace st {
 // Number of compute units of the current device (cached per device).
 int num_cus();
 
+// Raises the dynamic-LDS limit of `kernel` to `bytes` on the current device, once per device and kernel.
+bool allow_dynamic_lds(const void *kernel, int bytes);
+
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 inline bool overlap(const void *a, size_t abytes, const void *b, size_t bbytes)

@@ -414,13 +414,7 @@ st_status launch_moment2(const float *X, int64_t N, int n, float *Sc, int accumu
     if (n <= M2T_NMAX) {
         const M2TPlan p = m2t_plan(N, n);
         const size_t lds_bytes = (size_t)2u * p.ch * p.np * sizeof(float);          // at most 64 KB
-        static bool attr = false;
-        if (!attr) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void *>(moment2_tile_kernel),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024) != hipSuccess)
-                return ST_ERR_LAUNCH;
-            attr = true;
-        }
+        if (!allow_dynamic_lds(reinterpret_cast<const void *>(moment2_tile_kernel), 64 * 1024)) return ST_ERR_LAUNCH;
         hipLaunchKernelGGL(moment2_tile_kernel, dim3(p.gx, p.S), dim3(M2T_THREADS), lds_bytes, s, X, N, (u32)n, p.nb8,
                            p.nbp, p.ch, p.slice, wsf);
         if (hipGetLastError() != hipSuccess) return ST_ERR_LAUNCH;

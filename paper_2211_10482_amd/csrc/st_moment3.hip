@@ -621,15 +621,9 @@ st_status launch_moment3(const float *X, int64_t N, int n, float *Sc, int accumu
         size_t lds_bytes = (size_t)2u * p.ch * p.np * sizeof(float);                // at most 64 KB
         const bool subbed = p.sub > 1u;
         if (subbed && lds_bytes < 64u * 65u * sizeof(float)) lds_bytes = 64u * 65u * sizeof(float);
-        static bool attr = false;
-        if (!attr) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void *>(moment3_tile_kernel<false>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024) != hipSuccess ||
-                hipFuncSetAttribute(reinterpret_cast<const void *>(moment3_tile_kernel<true>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024) != hipSuccess)
-                return ST_ERR_LAUNCH;
-            attr = true;
-        }
+        if (!allow_dynamic_lds(reinterpret_cast<const void *>(moment3_tile_kernel<false>), 64 * 1024) ||
+            !allow_dynamic_lds(reinterpret_cast<const void *>(moment3_tile_kernel<true>), 64 * 1024))
+            return ST_ERR_LAUNCH;
         if (subbed)
             hipLaunchKernelGGL(moment3_tile_kernel<true>, dim3(p.gx, p.S), dim3(p.threads), lds_bytes, s, X, N, (u32)n,
                                p.nb4, p.nbt, p.ch, p.sub, p.slice, wsf);

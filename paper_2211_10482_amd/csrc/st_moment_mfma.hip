@@ -530,23 +530,6 @@ size_t moment_mfma_workspace(int order, int64_t N, int n)
     return p.table_bytes + (size_t)p.S * p.kinds * MM_WAVES * MM_ACC * sizeof(float);
 }
 
-// the kernels use up to 74 KB of dynamic LDS: raised once per device and instantiation
-template <typename K> static bool mm_allow_lds(K kernel, int which)
-{
-    static std::mutex mu;
-    static bool done[64][4] = {{false}};
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return false;
-    std::lock_guard<std::mutex> lock(mu);
-    if (!done[dev][which]) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                96 * 1024) != hipSuccess)
-            return false;
-        done[dev][which] = true;
-    }
-    return true;
-}
-
 st_status launch_moment_mfma(int order, const float *X, int64_t N, int n, float *Sc, int accumulate, void *ws,
                              hipStream_t s)
 {
@@ -563,18 +546,18 @@ st_status launch_moment_mfma(int order, const float *X, int64_t N, int n, float 
     bool ok;
     if (p.steps == 16u) {
         if (v4) {
-            ok = mm_allow_lds(moment_mfma_kernel<16, true>, 0);
+            ok = allow_dynamic_lds(reinterpret_cast<const void *>(moment_mfma_kernel<16, true>), 96 * 1024);   // up to 74 KB
             if (ok) hipLaunchKernelGGL((moment_mfma_kernel<16, true>), grid, block, lds_bytes, s, X, N, (u32)n, p.G, p.kinds, p.slice, table, wsf);
         } else {
-            ok = mm_allow_lds(moment_mfma_kernel<16, false>, 1);
+            ok = allow_dynamic_lds(reinterpret_cast<const void *>(moment_mfma_kernel<16, false>), 96 * 1024);   // up to 74 KB
             if (ok) hipLaunchKernelGGL((moment_mfma_kernel<16, false>), grid, block, lds_bytes, s, X, N, (u32)n, p.G, p.kinds, p.slice, table, wsf);
         }
     } else {
         if (v4) {
-            ok = mm_allow_lds(moment_mfma_kernel<8, true>, 2);
+            ok = allow_dynamic_lds(reinterpret_cast<const void *>(moment_mfma_kernel<8, true>), 96 * 1024);   // up to 74 KB
             if (ok) hipLaunchKernelGGL((moment_mfma_kernel<8, true>), grid, block, lds_bytes, s, X, N, (u32)n, p.G, p.kinds, p.slice, table, wsf);
         } else {
-            ok = mm_allow_lds(moment_mfma_kernel<8, false>, 3);
+            ok = allow_dynamic_lds(reinterpret_cast<const void *>(moment_mfma_kernel<8, false>), 96 * 1024);   // up to 74 KB
             if (ok) hipLaunchKernelGGL((moment_mfma_kernel<8, false>), grid, block, lds_bytes, s, X, N, (u32)n, p.G, p.kinds, p.slice, table, wsf);
         }
     }

@@ -26,6 +26,8 @@
 // value.
 //
 // Algorithmic traffic per output row: 4*nl bytes read + 4*R written (+ U once).
+#include <mutex>
+
 #include "st_common.h"
 
 namespace st {
@@ -373,13 +375,7 @@ static bool launch_splitk_ct(int CT, u32 grid, size_t lds_bytes, hipStream_t s, 
 {
 #define ST_TTM_CASE(C)                                                                                   \
     case C: {                                                                                            \
-        static bool attr = false;                                                                        \
-        if (!attr) {                                                                                     \
-            if (hipFuncSetAttribute(reinterpret_cast<const void *>(ttm_splitk_kernel<NS, C>),            \
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess) \
-                return false;                                                                            \
-            attr = true;                                                                                 \
-        }                                                                                                \
+        if (!allow_dynamic_lds(reinterpret_cast<const void *>(ttm_splitk_kernel<NS, C>), 160 * 1024)) return false; \
         hipLaunchKernelGGL((ttm_splitk_kernel<NS, C>), dim3(grid), dim3(TW * 64), lds_bytes, s, Tc, U, Yc, rows); \
         return true;                                                                                     \
     }
@@ -413,9 +409,11 @@ size_t ttm_workspace(int, int, int, int) { return 0; }
 // whether a workgroup of the current device may hold 160 KB of LDS (asked once per device)
 static bool lds_budget_160k()
 {
+    static std::mutex mu;
     static int cached[64] = {0};                       // 0 unknown, 1 yes, 2 no
     int dev = 0, v = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return false;
+    std::lock_guard<std::mutex> lock(mu);
     if (cached[dev] == 0) {
         if (hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess) return false;
         cached[dev] = v >= 160 * 1024 ? 1 : 2;
@@ -451,15 +449,9 @@ st_status launch_ttm(const float *Tc, const float *U, float *Yc, int64_t rows, i
         u32 KC = (lds_budget / (Rp * 4u)) & ~15u;          // rows of U per LDS chunk, multiple of 16
         if (KC > nlp) KC = nlp;
         size_t lds_bytes = (size_t)KC * Rp * 4u;
-        static bool attr_set = false;
-        if (!attr_set) {
-            if (hipFuncSetAttribute(reinterpret_cast<const void *>(ttm_mfma_kernel<false>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_budget) != hipSuccess ||
-                hipFuncSetAttribute(reinterpret_cast<const void *>(ttm_mfma_kernel<true>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_budget) != hipSuccess)
-                return ST_ERR_LAUNCH;
-            attr_set = true;
-        }
+        if (!allow_dynamic_lds(reinterpret_cast<const void *>(ttm_mfma_kernel<false>), (int)lds_budget) ||
+            !allow_dynamic_lds(reinterpret_cast<const void *>(ttm_mfma_kernel<true>), (int)lds_budget))
+            return ST_ERR_LAUNCH;
         u32 rtiles = (u32)((rows + 15) / 16);
         u32 grid = (u32)num_cus();
         if (grid > rtiles) grid = rtiles;

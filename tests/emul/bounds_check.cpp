@@ -31,6 +31,7 @@
 namespace st {
 float lds[160 * 1024 / 4];
 int num_cus() { return 256; }
+bool allow_dynamic_lds(const void *, int) { return true; }
 }  // namespace st
 
 static float *fbuf(size_t count)
