@@ -212,6 +212,39 @@ def test_moment3_small(st, oracle, N, n):
     assert np.array_equal(got, got2)                      # deterministic
 
 
+def lex_position3(n, t):
+    """Position of the sorted triple t among all non-decreasing triples over 0..n-1 in lexicographic order."""
+    from math import comb
+    i, j, k = (int(v) for v in t)
+    return sum(comb(n - a + 1, 2) for a in range(i)) + sum(n - b for b in range(i, j)) + (k - j)
+
+
+@pytest.mark.parametrize("N,n", [(300000, 80), (150000, 200), (60000, 256), (100000, 128)])
+def test_moment3_wide_long(st, oracle, N, n):
+    """More than 64 features and sample slices long enough for the periodic flush of the fp32 chains of the
+    matrix-core path: sampled entries (repeated indices and indices of one group of 16 among them), accumulate."""
+    say("moment3 wide N=%d n=%d" % (N, n))
+    X = W.normal(305, N * n).reshape(N, n)
+    rng = np.random.default_rng(13)
+    tr = [rng.integers(0, n, 3) for _ in range(800)]
+    for _ in range(600):
+        base = int(rng.integers(0, n))
+        tr.append(np.clip(base + rng.integers(-9, 10, 3), 0, n - 1))
+    tr += [np.array([0, 0, 0]), np.array([n - 1] * 3), np.array([0, n - 1, n - 1]), np.array([0, 1, 2])]
+    tr = np.unique(np.sort(np.array(tr, dtype=np.int64), axis=1), axis=0)
+    pos = np.array([lex_position3(n, t) for t in tr], dtype=np.int64)
+    ref = oracle.moment3_entries(X, tr.astype(np.int32))
+    h = N // 3
+    Sc = st.moment3_sym(dev(X[:h]))
+    st.moment3_sym(dev(X[h:]), Sc=Sc, accumulate=True)
+    got = Sc.cpu().numpy()
+    assert got.shape[0] == lex_position3(n, (n - 1,) * 3) + 1
+    err = float(np.abs(got[pos] - ref).max() / np.abs(ref).max())
+    say("  norm-wise error on %d sampled entries %.3e" % (pos.size, err))
+    assert err <= TOL
+    assert np.all(np.isfinite(got))
+
+
 def test_moment3_accumulate_and_empty(st, oracle):
     import torch
     N, n = 600, 20
@@ -375,7 +408,7 @@ def lex_position4(n, q):
             + sum(n - c for c in range(j, k)) + (l - k))
 
 
-@pytest.mark.parametrize("N,n", [(5000, 128), (3000, 200), (700, 256), (9000, 96)])
+@pytest.mark.parametrize("N,n", [(5000, 128), (3000, 200), (700, 256), (9000, 96), (40000, 144), (120000, 80)])
 def test_moment4_wide(st, oracle, N, n):
     """Feature counts beyond 64 (the matrix-core path with 6 to 16 index groups): sampled entries, among them
     quadruples with repeated indices and with several indices in one group of 16."""
