@@ -34,52 +34,50 @@ constexpr int M4_CH = 64;                          // samples per staged chunk
 constexpr int M4_LPT = M4_CH * 16 / M4_THREADS;    // 16-byte pieces of a chunk per thread (4)
 constexpr int M4_WGTARGET = 1024;                  // workgroups to aim for (four per CU)
 
-// A chunk of M4_CH samples is staged as [sample][64 columns]; columns >= n and samples
-// past the end of the slice become zeros.  load_chunk only issues the loads (row clamped
-// into the slice), store_chunk masks and writes.
-template <bool FULL>
+// A chunk of M4_CH samples is staged as [sample][64 columns]; only the 4*nb4 columns the tiles
+// read are loaded and written (columns >= n and samples past the end of the slice as zeros).
+// load_chunk only issues the loads (row clamped into the slice), store_chunk masks and writes.
 __device__ __forceinline__ void m4_load_chunk(f32x4 (&r)[M4_LPT], const float *__restrict__ X, int64_t s0,
-                                              int64_t s_end, u32 n, u32 tid)
+                                              int64_t s_end, u32 n, u32 nb4, u32 tid)
 {
 #pragma unroll
     for (int k = 0; k < M4_LPT; ++k) {
         const u32 j = tid + (u32)M4_THREADS * k, smp = j >> 4, c0 = 4u * (j & 15u);
+        if ((j & 15u) >= nb4) continue;
         const int64_t s = s0 + smp, sc = s < s_end ? s : s_end - 1;
-        if constexpr (FULL) {
-            const float4 t = *reinterpret_cast<const float4 *>(X + sc * 64 + c0);
-            r[k] = (f32x4){t.x, t.y, t.z, t.w};
-        } else {
-            const float *row = X + sc * (int64_t)n;
+        const float *row = X + sc * (int64_t)n;
 #pragma unroll
-            for (u32 g = 0; g < 4; ++g) r[k][g] = row[c0 + g < n ? c0 + g : n - 1];
-        }
+        for (u32 g = 0; g < 4; ++g) r[k][g] = row[c0 + g < n ? c0 + g : n - 1];
     }
 }
 
-template <bool FULL>
 __device__ __forceinline__ void m4_store_chunk(const f32x4 (&r)[M4_LPT], float *__restrict__ buf, int64_t s0,
-                                               int64_t s_end, u32 n, u32 tid)
+                                               int64_t s_end, u32 n, u32 nb4, u32 tid)
 {
 #pragma unroll
     for (int k = 0; k < M4_LPT; ++k) {
         const u32 j = tid + (u32)M4_THREADS * k, smp = j >> 4, c0 = 4u * (j & 15u);
+        if ((j & 15u) >= nb4) continue;
         const bool row_ok = s0 + smp < s_end;
         f32x4 v;
 #pragma unroll
-        for (u32 g = 0; g < 4; ++g) v[g] = (row_ok && (FULL || c0 + g < n)) ? r[k][g] : 0.f;
+        for (u32 g = 0; g < 4; ++g) v[g] = (row_ok && c0 + g < n) ? r[k][g] : 0.f;
         *reinterpret_cast<f32x4 *>(buf + smp * 64u + c0) = v;
     }
 }
 
-// grid.x = block quadruples / 64, grid.y = sample slices
-template <bool FULL>
+// grid.x = block quadruples / 64, grid.y = sample slices.  With fewer than 64 block quadruples (n <= 12) the
+// 64 quadruple slots of a workgroup hold `sub` copies of every quadruple; copy c takes the samples c, c+sub, ..
+// of a chunk, and the copies are added in LDS before the workgroup's partial is written.
 __global__ __launch_bounds__(M4_THREADS) void moment4_tile_kernel(const float *__restrict__ X, int64_t N, u32 n,
-                                                                u32 nb4, u32 nbq, int64_t slice,
+                                                                u32 nb4, u32 nbq, u32 sub, int64_t slice,
                                                                 float *__restrict__ ws)
 {
     __shared__ __attribute__((aligned(16))) float xs[2][M4_CH * 64];
-    const u32 tid = threadIdx.x, ii = tid & 3u;
-    const u32 bq = blockIdx.x * 64u + (tid >> 2);
+    const u32 tid = threadIdx.x, ii = tid & 3u, slot = tid >> 2;
+    const u32 copy = sub > 1u ? slot / nbq : 0u;
+    const u32 bq = sub > 1u ? slot - copy * nbq : blockIdx.x * 64u + slot;
+    const bool live = bq < nbq && copy < sub;
     u32 I, J, K, L;
     unrank_sym4<u32>(nb4, min(bq, nbq - 1u), I, J, K, L);
     const u32 oi = 4u * I + ii, oj = 4u * J, ok = 4u * K, ol = 4u * L;
@@ -94,20 +92,21 @@ __global__ __launch_bounds__(M4_THREADS) void moment4_tile_kernel(const float *_
 
     if (nchunks > 0) {
         f32x4 r[M4_LPT];
-        m4_load_chunk<FULL>(r, X, s_begin, s_end, n, tid);
-        m4_store_chunk<FULL>(r, xs[0], s_begin, s_end, n, tid);
-        if (nchunks > 1) m4_load_chunk<FULL>(r, X, s_begin + M4_CH, s_end, n, tid);
+        m4_load_chunk(r, X, s_begin, s_end, n, nb4, tid);
+        m4_store_chunk(r, xs[0], s_begin, s_end, n, nb4, tid);
+        if (nchunks > 1) m4_load_chunk(r, X, s_begin + M4_CH, s_end, n, nb4, tid);
         __syncthreads();
         for (int64_t c = 0; c < nchunks; ++c) {
             const u32 cb = (u32)(c & 1);
             // registers hold chunk c+1: park it in the other buffer (its readers finished
             // before the barrier that ended the previous iteration), then put chunk c+2 in flight
-            if (c + 1 < nchunks) m4_store_chunk<FULL>(r, xs[cb ^ 1u], s_begin + (c + 1) * M4_CH, s_end, n, tid);
-            if (c + 2 < nchunks) m4_load_chunk<FULL>(r, X, s_begin + (c + 2) * M4_CH, s_end, n, tid);
+            if (c + 1 < nchunks) m4_store_chunk(r, xs[cb ^ 1u], s_begin + (c + 1) * M4_CH, s_end, n, nb4, tid);
+            if (c + 2 < nchunks) m4_load_chunk(r, X, s_begin + (c + 2) * M4_CH, s_end, n, nb4, tid);
             __builtin_amdgcn_sched_barrier(0);
-            const float *row = xs[cb];
+            const float *row = xs[cb] + (live ? copy : 0u) * 64u;
+            const int step = (int)sub, first = live ? (int)copy : M4_CH;
 #pragma unroll 2
-            for (int smp = 0; smp < M4_CH; ++smp, row += 64) {
+            for (int smp = first; smp < M4_CH; smp += step, row += 64 * step) {
                 const float xi = row[oi];
                 const f32x4 xj = *reinterpret_cast<const f32x4 *>(row + oj);
                 const f32x4 xk = *reinterpret_cast<const f32x4 *>(row + ok);
@@ -128,29 +127,62 @@ __global__ __launch_bounds__(M4_THREADS) void moment4_tile_kernel(const float *_
         }
     }
 
-    if (bq < nbq) {
+    // the copies of a quadruple meet in LDS (the chunk buffers are free: the loop ended with a barrier), copy
+    // after copy in ascending order; copy 0 holds the sum
+    if (sub > 1u) {
+        float *buf = &xs[0][0];                              // nbq * 4 lanes x 64 floats <= 31 * 256
+        const u32 lane_slot = (bq * 4u + ii) * 64u;
+        for (u32 c = 1; c < sub; ++c) {
+            if (live && copy == c) {
+#pragma unroll
+                for (int e = 0; e < 16; ++e)
+                    *reinterpret_cast<f32x4 *>(buf + lane_slot + 4 * e) =
+                        (f32x4){acc[4 * e], acc[4 * e + 1], acc[4 * e + 2], acc[4 * e + 3]};
+            }
+            __syncthreads();
+            if (live && copy == 0u) {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const f32x4 v = *reinterpret_cast<const f32x4 *>(buf + lane_slot + 4 * e);
+                    acc[4 * e] += v[0]; acc[4 * e + 1] += v[1]; acc[4 * e + 2] += v[2]; acc[4 * e + 3] += v[3];
+                }
+            }
+            __syncthreads();
+        }
+    }
+    if (live && copy == 0u) {
         f32x4 *dst = reinterpret_cast<f32x4 *>(ws + (((size_t)blockIdx.y * nbq + bq) * 4u + ii) * 64u);
 #pragma unroll
         for (int e = 0; e < 16; ++e) dst[e] = (f32x4){acc[4 * e], acc[4 * e + 1], acc[4 * e + 2], acc[4 * e + 3]};
     }
 }
 
-// One thread per raw accumulator (block quadruple, lane, j, k, l): adds the S slice
-// partials in ascending order and stores the entries of the unique set.
+// Raw accumulators (block quadruple, lane, j, k, l) -> unique entries: a block owns 16 accumulators and cuts the
+// S slice partials into 16 groups (ascending inside a group, groups ascending), then keeps i <= j <= k <= l < n.
 __global__ __launch_bounds__(256) void moment4_reduce_kernel(const float *__restrict__ ws, u32 S, u32 n, u32 nb4,
                                                             u32 nbq, float *__restrict__ Sc, int accumulate)
 {
-    const u32 t = blockIdx.x * 256u + threadIdx.x;       // < nbq * 256
-    if (t >= nbq * 256u) return;
+    __shared__ float part[16][16];
+    const u32 a = threadIdx.x & 15u, g = threadIdx.x >> 4;
+    const u32 t = blockIdx.x * 16u + a;                  // < nbq * 256
+    const size_t stride = (size_t)nbq * 256u;
+    float s = 0.f;
+    if (t < nbq * 256u) {
+        const u32 per = (S + 15u) / 16u, y0 = min(S, g * per), y1 = min(S, y0 + per);
+#pragma unroll 4
+        for (u32 y = y0; y < y1; ++y) s += ws[(size_t)y * stride + t];
+    }
+    part[g][a] = s;
+    __syncthreads();
+    if (g != 0u || t >= nbq * 256u) return;
+    s = 0.f;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) s += part[q][a];
     const u32 bq = t >> 8, ii = (t >> 6) & 3u, e = t & 63u;
     u32 I, J, K, L;
     unrank_sym4<u32>(nb4, bq, I, J, K, L);
     const u32 i = 4u * I + ii, j = 4u * J + (e >> 4), k = 4u * K + ((e >> 2) & 3u), l = 4u * L + (e & 3u);
     if (!(i <= j && j <= k && k <= l && l < n)) return;
-    float s = 0.f;
-    const size_t stride = (size_t)nbq * 256u;
-#pragma unroll 4
-    for (u32 y = 0; y < S; ++y) s += ws[(size_t)y * stride + t];
     const u32 p = rank_sym4<u32>(n, i, j, k, l);
     Sc[p] = accumulate ? Sc[p] + s : s;
 }
@@ -162,7 +194,7 @@ __global__ __launch_bounds__(256) void moment4_zero_kernel(float *__restrict__ p
 }
 
 struct M4Plan {
-    u32 nb4, nbq, gx, S, ch;
+    u32 nb4, nbq, gx, S, ch, sub;
     int64_t slice;
 };
 static inline M4Plan m4_plan(int64_t N, int n)
@@ -172,10 +204,12 @@ static inline M4Plan m4_plan(int64_t N, int n)
     p.nbq = (u32)count_sym4<int64_t>(p.nb4);
     p.gx = (p.nbq + 63u) / 64u;
     p.ch = (u32)M4_CH;
-    int64_t S = (M4_WGTARGET + p.gx - 1) / p.gx;           // enough slices to fill the chip ...
+    p.sub = p.nbq < 64u ? 64u / p.nbq : 1u;                 // copies of every quadruple in a workgroup
+    int64_t S = (M4_WGTARGET + p.gx - 1) / p.gx;           // enough slices to fill the chip (four per CU) ...
     int64_t smax = (N + p.ch - 1) / p.ch;                  // ... each of at least one chunk
+    const int64_t scap = p.gx >= 12u ? 64 : 768 / (int64_t)p.gx;     // (measured: more slices of many quadruples lose)
+    if (S > scap) S = scap;
     if (S > smax) S = smax;
-    if (S > 64) S = 64;
     if (S < 1) S = 1;
     p.slice = ((N + S - 1) / S + p.ch - 1) / p.ch * p.ch;      // whole chunks
     p.S = (u32)((N + p.slice - 1) / p.slice);
@@ -202,10 +236,10 @@ st_status launch_moment4(const float *X, int64_t N, int n, float *Sc, int accumu
     // n <= 52 from here on
     const M4Plan p = m4_plan(N, n);
     float *wsf = static_cast<float *>(ws);
-    hipLaunchKernelGGL(moment4_tile_kernel<false>, dim3(p.gx, p.S), dim3(M4_THREADS), 0, s, X, N, (u32)n, p.nb4, p.nbq,
+    hipLaunchKernelGGL(moment4_tile_kernel, dim3(p.gx, p.S), dim3(M4_THREADS), 0, s, X, N, (u32)n, p.nb4, p.nbq, p.sub,
                        p.slice, wsf);
     if (hipGetLastError() != hipSuccess) return ST_ERR_LAUNCH;
-    hipLaunchKernelGGL(moment4_reduce_kernel, dim3(p.nbq), dim3(256), 0, s, wsf, p.S, (u32)n, p.nb4, p.nbq, Sc,
+    hipLaunchKernelGGL(moment4_reduce_kernel, dim3(p.nbq * 16u), dim3(256), 0, s, wsf, p.S, (u32)n, p.nb4, p.nbq, Sc,
                        accumulate);
     return launch_status();
 }
