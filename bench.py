@@ -301,6 +301,17 @@ def main():
              dict(flops=Nf * (2 * tri(nf) + 2 * tet(nf) + tri(nf) + 2 * pent_f + tri(nf)),
                   bytes=4 * (3 * Nf * nf + tri(nf) + tet(nf) + pent_f), bound="mfma")),
         ]
+        # and at 13 features (a feature count of the paper's end-to-end data sets), as many samples as config 5
+        ns, Ns = 13, N5
+        pent_s = ns * (ns + 1) * (ns + 2) * (ns + 3) // 24
+        Xs = torch.randn((Ns, ns), **f32)
+        Ss = (torch.empty(tri(ns), **f32), torch.empty(tet(ns), **f32), torch.empty(pent_s, **f32))
+        wss = torch.empty(max(16, st.workspace_bytes("covar_pr2", N=Ns, n=ns)), dtype=torch.uint8, device=dev)
+        extra += [
+            ("covar_pr2_N2e6_n13", lambda: st.covar_pr2(Xs, S=Ss, ws=wss),
+             dict(flops=Ns * (2 * tri(ns) + 2 * tet(ns) + tri(ns) + 2 * pent_s + tri(ns)),
+                  bytes=4 * (3 * Ns * ns + tri(ns) + tet(ns) + pent_s), bound="hbm")),
+        ]
         # the kernel table's structures at the size of the band workload (512 x 512 x 512, R = 64)
         nt, Rt = c3["n"], c3["R"]
         up_pairs = st.count_struct(st.STRUCT_UPPER, nt, nt)
