@@ -69,14 +69,16 @@ __device__ __forceinline__ void m4_store_chunk(const f32x4 (&r)[M4_LPT], float *
 // grid.x = block quadruples / 64, grid.y = sample slices.  With fewer than 64 block quadruples (n <= 12) the
 // 64 quadruple slots of a workgroup hold `sub` copies of every quadruple; copy c takes the samples c, c+sub, ..
 // of a chunk, and the copies are added in LDS before the workgroup's partial is written.
+template <bool SUBBED>
 __global__ __launch_bounds__(M4_THREADS) void moment4_tile_kernel(const float *__restrict__ X, int64_t N, u32 n,
-                                                                u32 nb4, u32 nbq, u32 sub, int64_t slice,
+                                                                u32 nb4, u32 nbq, u32 sub_arg, int64_t slice,
                                                                 float *__restrict__ ws)
 {
+    const u32 sub = SUBBED ? sub_arg : 1u;
     __shared__ __attribute__((aligned(16))) float xs[2][M4_CH * 64];
     const u32 tid = threadIdx.x, ii = tid & 3u, slot = tid >> 2;
-    const u32 copy = sub > 1u ? slot / nbq : 0u;
-    const u32 bq = sub > 1u ? slot - copy * nbq : blockIdx.x * 64u + slot;
+    const u32 copy = SUBBED ? slot / nbq : 0u;
+    const u32 bq = SUBBED ? slot - copy * nbq : blockIdx.x * 64u + slot;
     const bool live = bq < nbq && copy < sub;
     u32 I, J, K, L;
     unrank_sym4<u32>(nb4, min(bq, nbq - 1u), I, J, K, L);
@@ -103,8 +105,8 @@ __global__ __launch_bounds__(M4_THREADS) void moment4_tile_kernel(const float *_
             if (c + 1 < nchunks) m4_store_chunk(r, xs[cb ^ 1u], s_begin + (c + 1) * M4_CH, s_end, n, nb4, tid);
             if (c + 2 < nchunks) m4_load_chunk(r, X, s_begin + (c + 2) * M4_CH, s_end, n, nb4, tid);
             __builtin_amdgcn_sched_barrier(0);
-            const float *row = xs[cb] + (live ? copy : 0u) * 64u;
-            const int step = (int)sub, first = live ? (int)copy : M4_CH;
+            const float *row = xs[cb] + (SUBBED && live ? copy : 0u) * 64u;
+            const int step = SUBBED ? (int)sub : 1, first = SUBBED ? (live ? (int)copy : M4_CH) : 0;
 #pragma unroll 2
             for (int smp = first; smp < M4_CH; smp += step, row += 64 * step) {
                 const float xi = row[oi];
@@ -129,7 +131,7 @@ __global__ __launch_bounds__(M4_THREADS) void moment4_tile_kernel(const float *_
 
     // the copies of a quadruple meet in LDS (the chunk buffers are free: the loop ended with a barrier), copy
     // after copy in ascending order; copy 0 holds the sum
-    if (sub > 1u) {
+    if constexpr (SUBBED) {
         float *buf = &xs[0][0];                              // nbq * 4 lanes x 64 floats <= 31 * 256
         const u32 lane_slot = (bq * 4u + ii) * 64u;
         for (u32 c = 1; c < sub; ++c) {
@@ -236,8 +238,12 @@ st_status launch_moment4(const float *X, int64_t N, int n, float *Sc, int accumu
     // n <= 52 from here on
     const M4Plan p = m4_plan(N, n);
     float *wsf = static_cast<float *>(ws);
-    hipLaunchKernelGGL(moment4_tile_kernel, dim3(p.gx, p.S), dim3(M4_THREADS), 0, s, X, N, (u32)n, p.nb4, p.nbq, p.sub,
-                       p.slice, wsf);
+    if (p.sub > 1u)
+        hipLaunchKernelGGL(moment4_tile_kernel<true>, dim3(p.gx, p.S), dim3(M4_THREADS), 0, s, X, N, (u32)n, p.nb4,
+                           p.nbq, p.sub, p.slice, wsf);
+    else
+        hipLaunchKernelGGL(moment4_tile_kernel<false>, dim3(p.gx, p.S), dim3(M4_THREADS), 0, s, X, N, (u32)n, p.nb4,
+                           p.nbq, p.sub, p.slice, wsf);
     if (hipGetLastError() != hipSuccess) return ST_ERR_LAUNCH;
     hipLaunchKernelGGL(moment4_reduce_kernel, dim3(p.nbq * 16u), dim3(256), 0, s, wsf, p.S, (u32)n, p.nb4, p.nbq, Sc,
                        accumulate);
