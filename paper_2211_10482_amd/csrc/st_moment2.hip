@@ -3,7 +3,7 @@
 // (the M1 = f (x) f term of the degree-2 polynomial-regression covariance, summed
 // over the data; the structure is plain symmetry, the upper half is kept).
 //
-// MFMA path (n <= 64).  The sample sum is the dense contraction S = X^T X on the fp32
+// MFMA path (16 < n <= 64; n <= 16: one lane per sample, further down).  The sample sum is the dense contraction S = X^T X on the fp32
 // matrix cores (v_mfma_f32_16x16x4_f32).  The 64 indices are split into four groups
 // g = i mod 4, so one 16-byte load per lane -- lane (m, q) reads X(s+q, 4m .. 4m+3),
 // a wave reads four whole rows, 1 KB contiguous -- is at once the A operand of the
@@ -217,6 +217,83 @@ __global__ __launch_bounds__(256) void moment2_zero_kernel(float *__restrict__ p
     if (t < count) p[t] = 0.f;
 }
 
+// ---- a handful of features (n <= 16): one lane per sample ---------------------------------
+// The whole upper triangle fits a lane's registers (NP (NP + 1) / 2 accumulators for n padded to
+// NP = 4, 8, 12 or 16), so a lane takes whole samples: it reads its row (a wave reads 64
+// consecutive rows, every byte of them used) and adds the products; nothing is shared until the
+// end, when the lanes of a wave and then the four waves of the workgroup are added in a fixed
+// order.  Workgroup partials -> moment2_small_reduce_kernel.  Bound by the HBM stream.
+constexpr int M2S_WGS = 1024;                     // workgroups at most (four per CU)
+template <int NP>
+__global__ __launch_bounds__(256) void moment2_small_kernel(const float *__restrict__ X, int64_t N, u32 n,
+                                                           float *__restrict__ ws)
+{
+    constexpr int NA = NP * (NP + 1) / 2;
+    __shared__ float red[4][NA];
+    const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    float acc[NA];
+#pragma unroll
+    for (int a = 0; a < NA; ++a) acc[a] = 0.f;
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t s = (int64_t)blockIdx.x * 256 + tid; s < N; s += stride) {
+        const float *row = X + s * (int64_t)n;
+        float x[NP];
+#pragma unroll
+        for (int c = 0; c < NP; ++c) x[c] = (u32)c < n ? row[c] : 0.f;
+        int a = 0;
+#pragma unroll
+        for (int i = 0; i < NP; ++i)
+#pragma unroll
+            for (int j = i; j < NP; ++j) acc[a++] += x[i] * x[j];
+    }
+    // lanes of the wave (butterfly: every lane ends with the sum), then the four waves
+#pragma unroll
+    for (int a = 0; a < NA; ++a) {
+        float v = acc[a];
+        v += __shfl_xor(v, 1);
+        v += __shfl_xor(v, 2);
+        v += __shfl_xor(v, 4);
+        v += __shfl_xor(v, 8);
+        v += __shfl_xor(v, 16);
+        v += __shfl_xor(v, 32);
+        if (lane == 0u) red[wave][a] = v;
+    }
+    __syncthreads();
+    for (u32 a = tid; a < (u32)NA; a += 256u)
+        ws[(size_t)blockIdx.x * NA + a] = (red[0][a] + red[1][a]) + (red[2][a] + red[3][a]);
+}
+
+// 16 entries x 16 groups of workgroup partials per block; keeps i <= j < n of the padded triangle
+__global__ __launch_bounds__(256) void moment2_small_reduce_kernel(const float *__restrict__ ws, u32 G, u32 n, u32 np,
+                                                                  float *__restrict__ Sc, int accumulate)
+{
+    __shared__ float part[16][16];
+    const u32 a = threadIdx.x & 15u, g = threadIdx.x >> 4;
+    const u32 na = np * (np + 1u) / 2u, t = blockIdx.x * 16u + a;
+    float s = 0.f;
+    if (t < na) {
+        const u32 per = (G + 15u) / 16u, y0 = min(G, g * per), y1 = min(G, y0 + per);
+        for (u32 y = y0; y < y1; ++y) s += ws[(size_t)y * na + t];
+    }
+    part[g][a] = s;
+    __syncthreads();
+    if (g != 0u || t >= na) return;
+    s = 0.f;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) s += part[q][a];
+    u32 i, j;
+    unrank_sym2<u32>(np, t, i, j);                        // the kernel's accumulators are in packed order of np
+    if (j >= n) return;
+    const u32 p = rank_sym2<u32>(n, i, j);
+    Sc[p] = accumulate ? Sc[p] + s : s;
+}
+constexpr int M2S_NMAX = 16;
+static inline u32 m2s_groups(int64_t N)
+{
+    const int64_t g = (N + 255) / 256;
+    return (u32)(g < 1 ? 1 : g > M2S_WGS ? M2S_WGS : g);
+}
+
 static inline u32 m2_groups(int64_t N)
 {
     // at least M2_DEPTH quads per wave, at most M2_GMAX workgroups
@@ -383,6 +460,10 @@ __global__ __launch_bounds__(256) void moment2_tile_reduce_kernel(const float *_
 size_t moment2_workspace(int64_t N, int n)
 {
     if (N == 0) return 0;
+    if (n <= M2S_NMAX) {
+        const size_t np = ((size_t)n + 3u) / 4u * 4u;
+        return (size_t)m2s_groups(N) * (np * (np + 1u) / 2u) * sizeof(float);
+    }
     if (n <= 64) return (size_t)m2_groups(N) * M2_ACC * sizeof(float);
     if (n <= M2T_NMAX) {
         const M2TPlan p = m2t_plan(N, n);
@@ -400,6 +481,19 @@ st_status launch_moment2(const float *X, int64_t N, int n, float *Sc, int accumu
         return launch_status();
     }
     float *wsf = static_cast<float *>(ws);
+    if (n <= M2S_NMAX) {
+        const u32 G = m2s_groups(N), np = ((u32)n + 3u) / 4u * 4u, na = np * (np + 1u) / 2u;
+        switch (np) {
+        case 4: hipLaunchKernelGGL(moment2_small_kernel<4>, dim3(G), dim3(256), 0, s, X, N, (u32)n, wsf); break;
+        case 8: hipLaunchKernelGGL(moment2_small_kernel<8>, dim3(G), dim3(256), 0, s, X, N, (u32)n, wsf); break;
+        case 12: hipLaunchKernelGGL(moment2_small_kernel<12>, dim3(G), dim3(256), 0, s, X, N, (u32)n, wsf); break;
+        default: hipLaunchKernelGGL(moment2_small_kernel<16>, dim3(G), dim3(256), 0, s, X, N, (u32)n, wsf); break;
+        }
+        if (hipGetLastError() != hipSuccess) return ST_ERR_LAUNCH;
+        hipLaunchKernelGGL(moment2_small_reduce_kernel, dim3((na + 15u) / 16u), dim3(256), 0, s, wsf, G, (u32)n, np, Sc,
+                           accumulate);
+        return launch_status();
+    }
     if (n <= 64) {
         u32 G = m2_groups(N);
         if (n == 64)

@@ -305,7 +305,8 @@ def test_moment3_full(st, oracle):
 
 # ---------------------------------------------------------------------- moment2 (M1)
 @pytest.mark.parametrize("N,n", [(1, 1), (7, 5), (100, 64), (4097, 64), (33, 64), (1000, 20), (5000, 63), (300, 70),
-                                 (64, 200), (700, 65), (90, 1024), (20, 1100)])
+                                 (64, 200), (700, 65), (90, 1024), (20, 1100), (300000, 6), (70000, 13), (5000, 16),
+                                 (999, 2), (400000, 9), (257, 17)])
 def test_moment2_small(st, oracle, N, n):
     say("moment2 N=%d n=%d" % (N, n))
     X = W.normal(301, N * n).reshape(N, n)
