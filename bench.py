@@ -301,12 +301,23 @@ def main():
              dict(flops=Nf * (2 * tri(nf) + 2 * tet(nf) + tri(nf) + 2 * pent_f + tri(nf)),
                   bytes=4 * (3 * Nf * nf + tri(nf) + tet(nf) + pent_f), bound="mfma")),
         ]
-        # and at 13 features (a feature count of the paper's end-to-end data sets), as many samples as config 5
+        # and at 6 and 13 features (the feature counts of the paper's end-to-end data sets), as many samples as config 5;
+        # up to six features the call is ONE pass over the samples
         ns, Ns = 13, N5
         pent_s = ns * (ns + 1) * (ns + 2) * (ns + 3) // 24
         Xs = torch.randn((Ns, ns), **f32)
         Ss = (torch.empty(tri(ns), **f32), torch.empty(tet(ns), **f32), torch.empty(pent_s, **f32))
         wss = torch.empty(max(16, st.workspace_bytes("covar_pr2", N=Ns, n=ns)), dtype=torch.uint8, device=dev)
+        n6 = 6
+        pent_6 = n6 * (n6 + 1) * (n6 + 2) * (n6 + 3) // 24
+        X6 = torch.randn((Ns, n6), **f32)
+        S6 = (torch.empty(tri(n6), **f32), torch.empty(tet(n6), **f32), torch.empty(pent_6, **f32))
+        ws6 = torch.empty(max(16, st.workspace_bytes("covar_pr2", N=Ns, n=n6)), dtype=torch.uint8, device=dev)
+        extra += [
+            ("covar_pr2_N2e6_n6", lambda: st.covar_pr2(X6, S=S6, ws=ws6),
+             dict(flops=Ns * (2 * tri(n6) + 2 * tet(n6) + tri(n6) + 2 * pent_6 + tri(n6)),
+                  bytes=4 * (Ns * n6 + tri(n6) + tet(n6) + pent_6), bound="hbm")),
+        ]
         extra += [
             ("covar_pr2_N2e6_n13", lambda: st.covar_pr2(Xs, S=Ss, ws=wss),
              dict(flops=Ns * (2 * tri(ns) + 2 * tet(ns) + tri(ns) + 2 * pent_s + tri(ns)),

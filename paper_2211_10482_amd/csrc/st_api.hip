@@ -325,6 +325,7 @@ st_status st_moment4_sym(const float *X, int64_t N, int n, float *Sc, int accumu
 size_t st_covar_pr2_workspace(int64_t N, int n)
 {
     if (N < 0 || n < 1 || n > 256) return 0;
+    if (covar_small_applies(n)) return covar_small_workspace(N, n);
     size_t a = moment2_workspace(N, n), b = moment3_workspace(N, n), c = moment4_workspace(N, n);
     return a > b ? (a > c ? a : c) : (b > c ? b : c);
 }
@@ -345,6 +346,8 @@ st_status st_covar_pr2(const float *X, int64_t N, int n, float *S1, float *S2, f
     if (need > 0 && (overlap(ws, need, S1, b1) || overlap(ws, need, S2, b2) || overlap(ws, need, S3, b3) ||
                      (N > 0 && overlap(ws, need, X, xb))))
         return ST_ERR_SHAPE;
+    if (N > 0 && covar_small_applies(n))         // one pass over the samples for all three terms
+        return launch_covar_small(X, N, n, S1, S2, S3, accumulate, ws, (hipStream_t)stream);
     // the three kernels run one after the other on the stream, so they can share the workspace
     st_status rc = launch_moment2(X, N, n, S1, accumulate, ws, (hipStream_t)stream);
     if (rc != ST_OK) return rc;

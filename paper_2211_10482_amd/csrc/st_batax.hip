@@ -41,26 +41,6 @@ constexpr int GMAX = 256;  // workgroups of the one-pass kernel (one per CU)
 
 struct __attribute__((packed, aligned(4))) f4u { float x, y, z, w; };
 
-template <int CTRL> __device__ __forceinline__ float dpp_f(float v)
-{
-    return __builtin_bit_cast(
-        float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, false));
-}
-
-// Sum over the 64 lanes, same bits in every lane.
-__device__ __forceinline__ float wave_sum(float v)
-{
-    v += dpp_f<0xB1>(v);    // quad_perm [1,0,3,2]
-    v += dpp_f<0x4E>(v);    // quad_perm [2,3,0,1]
-    v += dpp_f<0x141>(v);   // row_half_mirror
-    v += dpp_f<0x140>(v);   // row_mirror
-    float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 0));
-    float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 16));
-    float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 32));
-    float r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 48));
-    return (r0 + r1) + (r2 + r3);
-}
-
 // Row held by slot q of workgroup g: q even -> row g + G*(q/2) from the top, q odd ->
 // its mirror image from the bottom; the middle row of an odd n is dealt once, as a
 // top row.  Slots past the middle return n ("no row").
@@ -153,10 +133,10 @@ __device__ __forceinline__ void process_batch(const float4 (&a)[RB][V], const fl
     // lane l holds partial (row l / NW, wave l % NW); DPP adds inside aligned
     // groups of NW lanes; the row sums are then read as wave-uniform scalars.
     float c = (lane < (u32)(NW * RB)) ? (&red[pb][0][0])[lane] : 0.f;
-    c += dpp_f<0xB1>(c);
-    c += dpp_f<0x4E>(c);
-    if constexpr (NW >= 8) c += dpp_f<0x141>(c);
-    if constexpr (NW >= 16) c += dpp_f<0x140>(c);
+    c += wave_dpp<0xB1>(c);
+    c += wave_dpp<0x4E>(c);
+    if constexpr (NW >= 8) c += wave_dpp<0x141>(c);
+    if constexpr (NW >= 16) c += wave_dpp<0x140>(c);
 #pragma unroll
     for (int r = 0; r < RB; ++r) {
         const float t = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, c), r * NW));

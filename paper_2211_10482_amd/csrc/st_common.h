@@ -27,6 +27,26 @@ inline st_status launch_status()
     return hipGetLastError() == hipSuccess ? ST_OK : ST_ERR_LAUNCH;
 }
 
+// Sum of a value over the 64 lanes of a wave, the same bits in every lane: four DPP steps inside the rows of 16,
+// then the four row sums through scalar registers, in a fixed order.
+template <int CTRL> __device__ __forceinline__ float wave_dpp(float v)
+{
+    return __builtin_bit_cast(float,
+                              __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float wave_sum(float v)
+{
+    v += wave_dpp<0xB1>(v);     // quad_perm [1,0,3,2]
+    v += wave_dpp<0x4E>(v);     // quad_perm [2,3,0,1]
+    v += wave_dpp<0x141>(v);    // row_half_mirror
+    v += wave_dpp<0x140>(v);    // row_mirror
+    const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 0));
+    const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 16));
+    const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 32));
+    const float r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 48));
+    return (r0 + r1) + (r2 + r3);
+}
+
 // ---- launchers (one translation unit per kernel family) -------------------
 st_status launch_unrank(int kind, int64_t n, int64_t w, int64_t p0, int64_t count, int32_t *out,
                         hipStream_t s);
@@ -57,6 +77,12 @@ bool moment_mfma_wins(int order, int n);
 size_t moment_mfma_workspace(int order, int64_t N, int n);
 st_status launch_moment_mfma(int order, const float *X, int64_t N, int n, float *Sc, int accumulate, void *ws,
                              hipStream_t s);
+
+// all three covariance terms in one pass for at most six features (st_covar_small.hip)
+bool covar_small_applies(int n);
+size_t covar_small_workspace(int64_t N, int n);
+st_status launch_covar_small(const float *X, int64_t N, int n, float *S1, float *S2, float *S3, int accumulate,
+                             void *ws, hipStream_t s);
 
 size_t mttkrp_workspace(int n, int R);
 st_status launch_mttkrp(const float *Tc, const float *B, float *M, int n, int R, void *ws,

@@ -246,16 +246,10 @@ __global__ __launch_bounds__(256) void moment2_small_kernel(const float *__restr
 #pragma unroll
             for (int j = i; j < NP; ++j) acc[a++] += x[i] * x[j];
     }
-    // lanes of the wave (butterfly: every lane ends with the sum), then the four waves
+    // lanes of the wave (DPP steps, every lane ends with the sum), then the four waves
 #pragma unroll
     for (int a = 0; a < NA; ++a) {
-        float v = acc[a];
-        v += __shfl_xor(v, 1);
-        v += __shfl_xor(v, 2);
-        v += __shfl_xor(v, 4);
-        v += __shfl_xor(v, 8);
-        v += __shfl_xor(v, 16);
-        v += __shfl_xor(v, 32);
+        const float v = wave_sum(acc[a]);
         if (lane == 0u) red[wave][a] = v;
     }
     __syncthreads();

@@ -465,24 +465,6 @@ static inline size_t partXP_floats(const MttkrpPlan &p) { return (size_t)p.npair
 // different rows); it keeps RC accumulators, which are added over the sixteen waves through LDS and over
 // the lanes with one DPP tree per output value, in a fixed order.  Each entry is read by the (up to three)
 // rows it belongs to; at this size those re-reads come from the cache.
-template <int CTRL> __device__ __forceinline__ float mk_dpp(float v)
-{
-    return __builtin_bit_cast(float,
-                              __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, false));
-}
-__device__ __forceinline__ float mk_wave_sum(float v)     // same bits in every lane
-{
-    v += mk_dpp<0xB1>(v);     // quad_perm [1,0,3,2]
-    v += mk_dpp<0x4E>(v);     // quad_perm [2,3,0,1]
-    v += mk_dpp<0x141>(v);    // row_half_mirror
-    v += mk_dpp<0x140>(v);    // row_mirror
-    const float r0 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 0));
-    const float r1 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 16));
-    const float r2 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 32));
-    const float r3 = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 48));
-    return (r0 + r1) + (r2 + r3);
-}
-
 constexpr u32 ROWS_NMAX = 96;      // largest n of the row kernel
 constexpr u32 ROWS_NT = 1024;      // threads per workgroup of the row kernel
 constexpr u32 ROWS_NW = ROWS_NT / 64;
@@ -547,7 +529,7 @@ __global__ __launch_bounds__(ROWS_NT) void mttkrp_rows_kernel(const float *__res
         float v = 0.f;
 #pragma unroll
         for (u32 w = 0; w < ROWS_NW; ++w) v += red[w][wave][lane];
-        v = mk_wave_sum(v);
+        v = wave_sum(v);
         const u32 r = 16u * (u32)h + wave;
         if (lane == 0 && r < R) M[(size_t)i * R + r] = v;
     }

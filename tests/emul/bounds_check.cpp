@@ -15,6 +15,8 @@
 #elif defined(CHECK_MOMENT4)
 #include "../../paper_2211_10482_amd/csrc/st_moment4.hip"
 #include "../../paper_2211_10482_amd/csrc/st_moment_mfma.hip"
+#elif defined(CHECK_COVARSMALL)
+#include "../../paper_2211_10482_amd/csrc/st_covar_small.hip"
 #elif defined(CHECK_MCOVER)
 #include "../../paper_2211_10482_amd/csrc/st_moment_mfma.hip"
 #elif defined(CHECK_EXPAND)
@@ -74,6 +76,15 @@ int main(int argc, char **argv)
     void *ws = malloc(wsb ? wsb : 1);
     rc = st::launch_moment3(X, N, n, Sc, accumulate, ws, nullptr);
     free(X); free(Sc); free(ws);
+#elif defined(CHECK_COVARSMALL)
+    const long N = a[0];
+    const int n = (int)a[1], accumulate = (int)a[2];
+    const size_t wsb = st::covar_small_workspace(N, n);
+    float *X = fbuf((size_t)N * n), *S1 = fbuf((size_t)st::count_sym2<int64_t>(n)),
+          *S2 = fbuf((size_t)st::count_sym3<int64_t>(n)), *S3 = fbuf((size_t)st::count_sym4<int64_t>(n));
+    void *ws = malloc(wsb ? wsb : 1);
+    rc = st::launch_covar_small(X, N, n, S1, S2, S3, accumulate, ws, nullptr);
+    free(X); free(S1); free(S2); free(S3); free(ws);
 #elif defined(CHECK_MCOVER)
     // The tile table and the kept-position rules of the matrix-core moment kernels: with every raw accumulator
     // set to 1 and Sc to 0, the reduce kernel in accumulate mode must leave exactly 1 in every unique entry
