@@ -302,7 +302,7 @@ def main():
                   bytes=4 * (3 * Nf * nf + tri(nf) + tet(nf) + pent_f), bound="mfma")),
         ]
         # and at 6 and 13 features (the feature counts of the paper's end-to-end data sets), as many samples as config 5;
-        # up to six features the call is ONE pass over the samples
+        # up to sixteen features the call is ONE pass over the samples
         ns, Ns = 13, N5
         pent_s = ns * (ns + 1) * (ns + 2) * (ns + 3) // 24
         Xs = torch.randn((Ns, ns), **f32)
@@ -321,7 +321,7 @@ def main():
         extra += [
             ("covar_pr2_N2e6_n13", lambda: st.covar_pr2(Xs, S=Ss, ws=wss),
              dict(flops=Ns * (2 * tri(ns) + 2 * tet(ns) + tri(ns) + 2 * pent_s + tri(ns)),
-                  bytes=4 * (3 * Ns * ns + tri(ns) + tet(ns) + pent_s), bound="hbm")),
+                  bytes=4 * (Ns * ns + tri(ns) + tet(ns) + pent_s), bound="alu")),
         ]
         # the kernel table's structures at the size of the band workload (512 x 512 x 512, R = 64)
         nt, Rt = c3["n"], c3["R"]

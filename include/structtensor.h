@@ -179,8 +179,8 @@ st_status st_moment4_sym(const float *X, int64_t N, int n, float *Sc, int accumu
  * entries only (for n = 4 features: 10 + 20 + 35 = 65 values instead of 400).
  * One call = st_moment2_sym, st_moment3_sym and st_moment4_sym on the same X,
  * enqueued on `stream` in that order with one shared workspace
- * (st_covar_pr2_workspace); with at most six features all three terms come
- * from ONE pass over X (same results within rounding, its own summation
+ * (st_covar_pr2_workspace); with at most sixteen features all three terms
+ * come from ONE pass over X (same results within rounding, its own summation
  * order).  S1, S2, S3 have st_count_sym2/3/4(n) entries; n <= 256. */
 size_t st_covar_pr2_workspace(int64_t N, int n);
 st_status st_covar_pr2(const float *X, int64_t N, int n, float *S1, float *S2, float *S3, int accumulate,

@@ -1,12 +1,16 @@
 // The three covariance terms of degree-2 polynomial regression in ONE pass over the samples,
-// for at most six features (the smaller of the paper's two end-to-end data sets has six):
+// for at most sixteen features (the paper's two end-to-end data sets have six and thirteen):
 //     S1(i,j) (+)= sum_s x_i x_j,   S2(i,j,k) (+)= sum_s x_i x_j x_k,   S3(i,j,k,l) (+)= sum_s x_i x_j x_k x_l
-// over the unique sets i <= j (<= k (<= l)).  All 21 + 56 + 126 unique entries of n = 6 fit a
-// lane's registers, so a lane takes whole samples (a wave reads 64 consecutive rows, every byte
-// of them used) and walks the nest  for i, for j = i, for k = j, for l = k  with the running
-// products x_i x_j and x_i x_j x_k shared by the inner loops.  Nothing is shared between lanes
-// until the end: the lanes of a wave, then the four waves of a workgroup, are added in a fixed
-// order; workgroup partials -> reduce kernel (fixed order, no atomics).  Bound by the HBM stream.
+// over the unique sets i <= j (<= k (<= l)).  A lane takes whole samples and walks the nest
+// for i, for j = i, for k = j, for l = k  with the running products x_i x_j and x_i x_j x_k shared
+// by the inner loops, every accumulator a register.
+//   * up to six features all 21 + 56 + 126 unique entries fit ONE lane: every lane of the grid has
+//     its own samples (a wave reads 64 consecutive rows, every byte of them used); the lanes of a
+//     wave, then the four waves of a workgroup, are added in a fixed order at the end;
+//   * seven to sixteen features: the waves of a workgroup take the same 64 samples and different
+//     parts of the nest (second half of this file).
+// Workgroup partials -> reduce kernel (fixed order, no atomics).  Bound by the HBM stream (six
+// features) or the fp32 vector rate (thirteen and more).
 #include "st_common.h"
 #include "st_index.h"
 
@@ -104,32 +108,250 @@ __global__ __launch_bounds__(256) void covar_small_reduce_kernel(const float *__
     }
 }
 
+// ---- seven to sixteen features: the same lanes, the accumulators split over the waves -------------
+// A lane still takes whole samples, but the unique entries no longer fit one lane's registers (13 features:
+// 91 + 455 + 1,820), so the waves of a workgroup take the SAME 64 samples and different parts of the loop nest:
+// the nest is cut by its (i, j) prefix -- S1(i,j), S2(i,j,k >= j) and S3(i,j,k,l >= k) belong together and
+// share the running products -- and the prefixes are dealt to 4, 8, 16 or 24 waves of at most CSP_BUDGET
+// accumulators each, 4 or 8 waves to a workgroup (one, two or three kinds of workgroup).  The 64 rows are
+// staged once per workgroup in LDS (coalesced; read back one column of 64 rows at a time).  No accumulator
+// has two owners in a workgroup, so a wave writes its sums straight into the workgroup's partial; X is read
+// once per kind of workgroup.
+constexpr int CSP_BUDGET = 210;                   // accumulators per wave at most (about 240 registers per lane in all)
+constexpr int CSP_NMAX = 16;
+template <int NP> constexpr int csp_prefix_count(int j) { return 1 + (NP - j) + (NP - j) * (NP - j + 1) / 2; }
+template <int NP> struct CspPlan {
+    int pi[NP * (NP + 1) / 2], pj[NP * (NP + 1) / 2];   // the prefixes (i, j), j >= i, in nest order
+    int first[65];            // wave w (over all kinds) owns the prefixes first[w] .. first[w+1]-1
+    int accs[64];             // accumulators of each wave
+    int waves;
+};
+// Prefixes are dealt to the waves largest first, each to the wave with the fewest accumulators so far; the
+// number of waves is the smallest of 4, 8, 16, 24, 32 that keeps a wave within CSP_BUDGET (whole SIMDs' worth
+// of equally loaded waves: a workgroup is 4 or 8 of them).
+template <int NP> constexpr CspPlan<NP> csp_make_plan()
+{
+    constexpr int NPAIR = NP * (NP + 1) / 2;
+    CspPlan<NP> p{};
+    int total = 0;
+    for (int i = 0; i < NP; ++i)
+        for (int j = i; j < NP; ++j) total += csp_prefix_count<NP>(j);
+    const int choices[5] = {4, 8, 16, 24, 32};
+    int K = 32;
+    for (int c = 4; c >= 0; --c)
+        if ((total + choices[c] - 1) / choices[c] <= CSP_BUDGET - 8) K = choices[c];
+    int load[32] = {}, owner[NPAIR] = {}, oi[NPAIR] = {}, oj[NPAIR] = {};
+    // prefixes by decreasing count: the count depends on j only and falls with j
+    int q = 0;
+    for (int j = 0; j < NP; ++j)
+        for (int i = 0; i <= j; ++i) {
+            int best = 0;
+            for (int w = 1; w < K; ++w)
+                if (load[w] < load[best]) best = w;
+            load[best] += csp_prefix_count<NP>(j);
+            owner[q] = best;
+            oi[q] = i;
+            oj[q] = j;
+            ++q;
+        }
+    q = 0;
+    for (int w = 0; w < K; ++w) {
+        p.first[w] = q;
+        p.accs[w] = load[w];
+        for (int t = 0; t < NPAIR; ++t)
+            if (owner[t] == w) { p.pi[q] = oi[t]; p.pj[q] = oj[t]; ++q; }
+    }
+    p.first[K] = q;
+    p.waves = K;
+    return p;
+}
+template <int NP> struct CspStatic { static constexpr CspPlan<NP> plan = csp_make_plan<NP>(); };
+template <int NP> constexpr int csp_kinds() { return (CspStatic<NP>::plan.waves + 7) / 8; }
+template <int NP> constexpr int csp_wpk() { return CspStatic<NP>::plan.waves < 8 ? CspStatic<NP>::plan.waves : 8; }
+
+// Staging of a group of 64 consecutive samples: the workgroup's threads read the 64 n floats (contiguous in X) in
+// order and park them as rows of LS = NP | 1 floats (odd: lanes that read one column of 64 rows hit 64 banks).
+constexpr int CSP_STAGE = 3;                      // elements per thread: 64 * 16 floats over at least 448 threads
+template <int NP> struct CspLds { static constexpr int LS = NP | 1, FLOATS = 64 * LS; };
+__device__ __forceinline__ void csp_stage_load(float (&r)[CSP_STAGE], const float *__restrict__ X, int64_t N, u32 n,
+                                               int64_t group, u32 tid, u32 nthreads)
+{
+    const int64_t base = group * 64 * (int64_t)n, end = N * (int64_t)n;
+#pragma unroll
+    for (int k = 0; k < CSP_STAGE; ++k) {
+        const u32 e = tid + nthreads * (u32)k;
+        r[k] = (e < 64u * n && base + e < end) ? X[base + e] : 0.f;
+    }
+}
+template <int NP>
+__device__ __forceinline__ void csp_stage_store(const float (&r)[CSP_STAGE], float *__restrict__ buf, u32 n, u32 tid,
+                                                u32 nthreads)
+{
+#pragma unroll
+    for (int k = 0; k < CSP_STAGE; ++k) {
+        const u32 e = tid + nthreads * (u32)k;
+        if (e < 64u * n) {
+            const u32 smp = e / n, c = e - smp * n;
+            buf[smp * (u32)CspLds<NP>::LS + c] = r[k];
+        }
+    }
+}
+
+// Wave W of the plan (W >= the number of waves: a wave that only helps with the staging).  Every wave of the
+// workgroup runs the same loop over the sample groups g, g + G, .. with one barrier per group.
+template <int NP, int W>
+__device__ __forceinline__ void csp_body(const float *__restrict__ X, int64_t N, u32 n, int64_t g, int64_t G,
+                                         float *__restrict__ part, float *__restrict__ lds, u32 tid, u32 nthreads)
+{
+    typedef CsCounts<NP> C;
+    constexpr bool REAL = W < CspStatic<NP>::plan.waves;
+    constexpr int NA = REAL ? CspStatic<NP>::plan.accs[REAL ? W : 0] : 1;
+    constexpr int Q0 = REAL ? CspStatic<NP>::plan.first[REAL ? W : 0] : 0;
+    constexpr int Q1 = REAL ? CspStatic<NP>::plan.first[REAL ? W + 1 : 0] : 0;
+    constexpr int LS = CspLds<NP>::LS;
+    const u32 lane = tid & 63u;
+    float acc[NA];
+#pragma unroll
+    for (int a = 0; a < NA; ++a) acc[a] = 0.f;
+    const int64_t ngroups = (N + 63) / 64;
+    // columns >= n of a staged row are never written: zero both buffers once
+    for (u32 e = tid; e < 2u * (u32)CspLds<NP>::FLOATS; e += nthreads) lds[e] = 0.f;
+    __syncthreads();
+    float r[CSP_STAGE];
+    csp_stage_load(r, X, N, n, g, tid, nthreads);
+    csp_stage_store<NP>(r, lds, n, tid, nthreads);
+    __syncthreads();
+    u32 cur = 0;
+    for (int64_t grp = g; grp < ngroups; grp += G, cur ^= 1u) {
+        const bool more = grp + G < ngroups;
+        if (more) csp_stage_load(r, X, N, n, grp + G, tid, nthreads);       // in flight under the products
+        if constexpr (REAL) {
+            const float *row = lds + cur * (u32)CspLds<NP>::FLOATS + lane * (u32)LS;
+            float x[NP];
+#pragma unroll
+            for (int c = 0; c < NP; ++c) x[c] = row[c];
+            int a = 0;
+#pragma unroll
+            for (int q = Q0; q < Q1; ++q) {
+                const int i = CspStatic<NP>::plan.pi[q], j = CspStatic<NP>::plan.pj[q];
+                const float pij = x[i] * x[j];
+                acc[a++] += pij;
+#pragma unroll
+                for (int k = j; k < NP; ++k) {
+                    const float pijk = pij * x[k];
+                    acc[a++] += pijk;
+#pragma unroll
+                    for (int l = k; l < NP; ++l) acc[a++] += pijk * x[l];
+                }
+            }
+        }
+        // the other buffer was read in the previous iteration, which ended with a barrier
+        if (more) csp_stage_store<NP>(r, lds + (cur ^ 1u) * (u32)CspLds<NP>::FLOATS, n, tid, nthreads);
+        __syncthreads();
+    }
+    if constexpr (REAL) {
+        int a = 0;
+#pragma unroll
+        for (int q = Q0; q < Q1; ++q) {
+            const int i = CspStatic<NP>::plan.pi[q], j = CspStatic<NP>::plan.pj[q];
+            float v = wave_sum(acc[a++]);
+            if (lane == 0u) part[rank_sym2<u32>(NP, i, j)] = v;
+#pragma unroll
+            for (int k = j; k < NP; ++k) {
+                v = wave_sum(acc[a++]);
+                if (lane == 0u) part[C::A2 + rank_sym3<u32>(NP, i, j, k)] = v;
+#pragma unroll
+                for (int l = k; l < NP; ++l) {
+                    v = wave_sum(acc[a++]);
+                    if (lane == 0u) part[C::A2 + C::A3 + rank_sym4<u32>(NP, i, j, k, l)] = v;
+                }
+            }
+        }
+    }
+}
+// gw in 0 .. kinds * waves-per-kind - 1; the slots past the plan's last wave run the helper body
+template <int NP, int W>
+__device__ __forceinline__ void csp_dispatch(int gw, const float *__restrict__ X, int64_t N, u32 n, int64_t g,
+                                             int64_t G, float *__restrict__ part, float *__restrict__ lds, u32 tid,
+                                             u32 nthreads)
+{
+    if constexpr (W + 1 < csp_kinds<NP>() * csp_wpk<NP>()) {
+        if (gw == W) csp_body<NP, W>(X, N, n, g, G, part, lds, tid, nthreads);
+        else csp_dispatch<NP, W + 1>(gw, X, N, n, g, G, part, lds, tid, nthreads);
+    } else {
+        csp_body<NP, W>(X, N, n, g, G, part, lds, tid, nthreads);
+    }
+}
+// grid.x = kinds * G: workgroup (kind, g) takes the sample groups g, g + G, .. of 64 samples
+template <int NP>
+__global__ __launch_bounds__(512) void covar_split_kernel(const float *__restrict__ X, int64_t N, u32 n, u32 G,
+                                                         float *__restrict__ ws)
+{
+    typedef CsCounts<NP> C;
+    __shared__ float lds[2 * CspLds<NP>::FLOATS];
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const u32 kind = blockIdx.x % (u32)csp_kinds<NP>(), g = blockIdx.x / (u32)csp_kinds<NP>();
+    const int gw = (int)kind * csp_wpk<NP>() + wave;
+    csp_dispatch<NP, 0>(gw, X, N, n, (int64_t)g, (int64_t)G, ws + (size_t)g * C::ALL, lds, threadIdx.x,
+                        64u * (u32)csp_wpk<NP>());
+}
+static inline u32 csp_np(int n) { return n <= 8 ? 8u : n <= 10 ? 10u : n <= 13 ? 13u : 16u; }
+template <int NP> static st_status csp_launch(const float *X, int64_t N, int n, u32 G, float *wsf, hipStream_t s)
+{
+    hipLaunchKernelGGL(covar_split_kernel<NP>, dim3(G * (u32)csp_kinds<NP>()), dim3(64u * (u32)csp_wpk<NP>()), 0, s, X, N,
+                       (u32)n, G, wsf);
+    return hipGetLastError() == hipSuccess ? ST_OK : ST_ERR_LAUNCH;
+}
+static inline u32 csp_groups(int64_t N, u32 np)
+{
+    const u32 kinds = np == 8u ? (u32)csp_kinds<8>() : np == 10u ? (u32)csp_kinds<10>()
+                                                   : np == 13u ? (u32)csp_kinds<13>() : (u32)csp_kinds<16>();
+    int64_t g = 2 * (int64_t)num_cus() / kinds;            // about two workgroups per compute unit in all
+    const int64_t gmax = (N + 63) / 64;
+    if (g > gmax) g = gmax;
+    return (u32)(g < 1 ? 1 : g);
+}
+
 static inline u32 cs_groups(int64_t N)
 {
     const int64_t g = (N + 255) / 256;
     return (u32)(g < 1 ? 1 : g > CS_WGS ? CS_WGS : g);
 }
-static inline u32 cs_np(int n) { return n <= 4 ? 4u : 6u; }
+static inline u32 cs_np(int n) { return n <= 4 ? 4u : n <= CS_NMAX ? 6u : csp_np(n); }
+static inline u32 cs_all(u32 np) { return count_sym2<u32>(np) + count_sym3<u32>(np) + count_sym4<u32>(np); }
 
-bool covar_small_applies(int n) { return n >= 1 && n <= CS_NMAX; }
+bool covar_small_applies(int n) { return n >= 1 && n <= CSP_NMAX; }
 
 size_t covar_small_workspace(int64_t N, int n)
 {
     if (N <= 0) return 0;
     const u32 np = cs_np(n);
-    return (size_t)cs_groups(N) * (count_sym2<u32>(np) + count_sym3<u32>(np) + count_sym4<u32>(np)) * sizeof(float);
+    const u32 G = n <= CS_NMAX ? cs_groups(N) : csp_groups(N, np);
+    return (size_t)G * cs_all(np) * sizeof(float);
 }
 
 // N >= 1
 st_status launch_covar_small(const float *X, int64_t N, int n, float *S1, float *S2, float *S3, int accumulate,
                              void *ws, hipStream_t s)
 {
-    const u32 G = cs_groups(N), np = cs_np(n);
+    const u32 np = cs_np(n);
     float *wsf = static_cast<float *>(ws);
-    if (np == 4u) hipLaunchKernelGGL(covar_small_kernel<4>, dim3(G), dim3(256), 0, s, X, N, (u32)n, wsf);
-    else hipLaunchKernelGGL(covar_small_kernel<6>, dim3(G), dim3(256), 0, s, X, N, (u32)n, wsf);
-    if (hipGetLastError() != hipSuccess) return ST_ERR_LAUNCH;
-    const u32 all = count_sym2<u32>(np) + count_sym3<u32>(np) + count_sym4<u32>(np);
+    u32 G;
+    if (n <= CS_NMAX) {
+        G = cs_groups(N);
+        if (np == 4u) hipLaunchKernelGGL(covar_small_kernel<4>, dim3(G), dim3(256), 0, s, X, N, (u32)n, wsf);
+        else hipLaunchKernelGGL(covar_small_kernel<6>, dim3(G), dim3(256), 0, s, X, N, (u32)n, wsf);
+        if (hipGetLastError() != hipSuccess) return ST_ERR_LAUNCH;
+    } else {
+        G = csp_groups(N, np);
+        st_status rc;
+        if (np == 8u) rc = csp_launch<8>(X, N, n, G, wsf, s);
+        else if (np == 10u) rc = csp_launch<10>(X, N, n, G, wsf, s);
+        else if (np == 13u) rc = csp_launch<13>(X, N, n, G, wsf, s);
+        else rc = csp_launch<16>(X, N, n, G, wsf, s);
+        if (rc != ST_OK) return rc;
+    }
+    const u32 all = cs_all(np);
     hipLaunchKernelGGL(covar_small_reduce_kernel, dim3((all + 15u) / 16u), dim3(256), 0, s, wsf, G, (u32)n, np, S1, S2,
                        S3, accumulate);
     return launch_status();

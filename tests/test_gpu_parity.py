@@ -456,7 +456,8 @@ def test_moment4_full(st, oracle):
 
 # ------------------------------------------- degree-2 polynomial-regression covariance
 @pytest.mark.parametrize("N,n", [(300, 4), (1000, 13), (500, 64), (90, 70), (20000, 6), (777, 5), (64, 1), (5000, 3),
-                                 (300000, 2), (1, 6), (700, 7)])
+                                 (300000, 2), (1, 6), (700, 7), (5000, 8), (333, 9), (2000, 10), (100, 11), (40000, 13),
+                                 (900, 14), (65, 15), (3000, 16), (200, 17)])
 def test_covar_pr2(st, oracle, N, n):
     """(M1, M2, M3) in one call, as two half-batches (creation and addition), against the dense definitions;
     n = 4 has the paper's 65 distinct elements, 6 and 13 are the feature counts of its end-to-end data sets."""
@@ -474,13 +475,13 @@ def test_covar_pr2(st, oracle, N, n):
         assert got.numel() == ref.size
         assert rel_err(got.cpu().numpy(), ref) <= TOL
     # the same three results from the three separate entry points: bit for bit where the call runs those three
-    # kernels; up to six features it is one fused pass of its own, with its own summation order
+    # kernels; up to sixteen features it is one fused pass of its own, with its own summation order
     A = (st.moment2_sym(dev(X[:h])), st.moment3_sym(dev(X[:h])), st.moment4_sym(dev(X[:h])))
     st.moment2_sym(dev(X[h:]), Sc=A[0], accumulate=True)
     st.moment3_sym(dev(X[h:]), Sc=A[1], accumulate=True)
     st.moment4_sym(dev(X[h:]), Sc=A[2], accumulate=True)
     for got, sep, ref in zip(S, A, (ref1, ref2, ref3)):
-        if n > 6:
+        if n > 16:
             assert np.array_equal(got.cpu().numpy(), sep.cpu().numpy())
         else:
             assert rel_err(sep.cpu().numpy(), ref) <= TOL

@@ -47,8 +47,10 @@ CASES = {
     "MOMENT4": [(300, 64, 0), (65, 64, 1), (1, 64, 0), (200, 20, 0), (130, 63, 0), (3, 5, 1), (9, 70, 0),
                 (70, 65, 1), (3, 129, 0), (100, 80, 0), (37, 75, 1), (20, 130, 0), (9, 200, 1), (500, 6, 0),
                 (130, 9, 1), (70, 13, 0), (90, 2, 0), (65, 1, 1), (300, 40, 0)],
-    # one-pass covariance for at most six features: N n accumulate
-    "COVARSMALL": [(1000, 6, 0), (3, 6, 1), (257, 5, 0), (300000, 4, 0), (70, 1, 1), (513, 3, 0)],
+    # one-pass covariance for at most sixteen features: N n accumulate  (n <= 6: every lane holds all entries;
+    # 7 <= n <= 16: the entries are split over the waves)
+    "COVARSMALL": [(1000, 6, 0), (3, 6, 1), (257, 5, 0), (300000, 4, 0), (70, 1, 1), (513, 3, 0), (1000, 13, 0),
+                   (65, 7, 1), (130, 16, 0), (3, 10, 0), (200, 9, 1), (50000, 14, 0)],
     # cover of the matrix-core moment kernels: order n  (every unique entry kept at exactly one tile position)
     "MCOVER": [(4, 64), (4, 56), (4, 80), (4, 75), (4, 100), (4, 128), (3, 65), (3, 80), (3, 100), (3, 128), (3, 200),
                (3, 256), (3, 250)],
