@@ -70,6 +70,7 @@ __global__ __launch_bounds__(256) void covar_small_kernel(const float *__restric
 }
 
 // 16 accumulators x 16 groups of workgroup partials per block; keeps the entries with every index < n
+// (S1 or S2 may be null: that term is not wanted)
 __global__ __launch_bounds__(256) void covar_small_reduce_kernel(const float *__restrict__ ws, u32 G, u32 n, u32 np,
                                                                 float *__restrict__ S1, float *__restrict__ S2,
                                                                 float *__restrict__ S3, int accumulate)
@@ -92,12 +93,12 @@ __global__ __launch_bounds__(256) void covar_small_reduce_kernel(const float *__
     u32 i, j, k, l;
     if (t < a2) {
         unrank_sym2<u32>(np, t, i, j);
-        if (j >= n) return;
+        if (j >= n || !S1) return;
         const u32 p = rank_sym2<u32>(n, i, j);
         S1[p] = accumulate ? S1[p] + s : s;
     } else if (t < a2 + a3) {
         unrank_sym3<u32>(np, t - a2, i, j, k);
-        if (k >= n) return;
+        if (k >= n || !S2) return;
         const u32 p = rank_sym3<u32>(n, i, j, k);
         S2[p] = accumulate ? S2[p] + s : s;
     } else {
@@ -330,7 +331,7 @@ size_t covar_small_workspace(int64_t N, int n)
     return (size_t)G * cs_all(np) * sizeof(float);
 }
 
-// N >= 1
+// N >= 1; S1 and S2 may be null (the fourth moment alone)
 st_status launch_covar_small(const float *X, int64_t N, int n, float *S1, float *S2, float *S3, int accumulate,
                              void *ws, hipStream_t s)
 {

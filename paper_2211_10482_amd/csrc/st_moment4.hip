@@ -3,8 +3,9 @@
 // (the M3 = vec(f (x) f) (x) vec(f (x) f) term of the degree-2 polynomial-regression
 // covariance, summed over the data; about 23 of every 24 dense entries are redundant).
 //
-// Matrix cores (st_moment_mfma.hip) from 53 features on; fp32 vector arithmetic, in this file,
-// below (where padding the indices to whole groups of 16 costs more than the matrix cores gain).
+// Matrix cores (st_moment_mfma.hip) from 53 features on; lanes that take whole samples up to 16
+// features (st_covar_small.hip); fp32 vector arithmetic on register tiles, in this file, between
+// (where padding the indices to whole groups of 16 costs more than the matrix cores gain).
 //
 // Tile path, plain fp32 vector arithmetic: on the vector ALUs any set of entries
 // can be owned by any thread, so nothing but the block
@@ -66,20 +67,15 @@ __device__ __forceinline__ void m4_store_chunk(const f32x4 (&r)[M4_LPT], float *
     }
 }
 
-// grid.x = block quadruples / 64, grid.y = sample slices.  With fewer than 64 block quadruples (n <= 12) the
-// 64 quadruple slots of a workgroup hold `sub` copies of every quadruple; copy c takes the samples c, c+sub, ..
-// of a chunk, and the copies are added in LDS before the workgroup's partial is written.
-template <bool SUBBED>
+// grid.x = block quadruples / 64, grid.y = sample slices (17 <= n <= 52: at least 70 block quadruples)
 __global__ __launch_bounds__(M4_THREADS) void moment4_tile_kernel(const float *__restrict__ X, int64_t N, u32 n,
-                                                                u32 nb4, u32 nbq, u32 sub_arg, int64_t slice,
+                                                                u32 nb4, u32 nbq, int64_t slice,
                                                                 float *__restrict__ ws)
 {
-    const u32 sub = SUBBED ? sub_arg : 1u;
     __shared__ __attribute__((aligned(16))) float xs[2][M4_CH * 64];
-    const u32 tid = threadIdx.x, ii = tid & 3u, slot = tid >> 2;
-    const u32 copy = SUBBED ? slot / nbq : 0u;
-    const u32 bq = SUBBED ? slot - copy * nbq : blockIdx.x * 64u + slot;
-    const bool live = bq < nbq && copy < sub;
+    const u32 tid = threadIdx.x, ii = tid & 3u;
+    const u32 bq = blockIdx.x * 64u + (tid >> 2);
+    const bool live = bq < nbq;
     u32 I, J, K, L;
     unrank_sym4<u32>(nb4, min(bq, nbq - 1u), I, J, K, L);
     const u32 oi = 4u * I + ii, oj = 4u * J, ok = 4u * K, ol = 4u * L;
@@ -105,10 +101,9 @@ __global__ __launch_bounds__(M4_THREADS) void moment4_tile_kernel(const float *_
             if (c + 1 < nchunks) m4_store_chunk(r, xs[cb ^ 1u], s_begin + (c + 1) * M4_CH, s_end, n, nb4, tid);
             if (c + 2 < nchunks) m4_load_chunk(r, X, s_begin + (c + 2) * M4_CH, s_end, n, nb4, tid);
             __builtin_amdgcn_sched_barrier(0);
-            const float *row = xs[cb] + (SUBBED && live ? copy : 0u) * 64u;
-            const int step = SUBBED ? (int)sub : 1, first = SUBBED ? (live ? (int)copy : M4_CH) : 0;
+            const float *row = xs[cb];
 #pragma unroll 2
-            for (int smp = first; smp < M4_CH; smp += step, row += 64 * step) {
+            for (int smp = 0; smp < M4_CH; ++smp, row += 64) {
                 const float xi = row[oi];
                 const f32x4 xj = *reinterpret_cast<const f32x4 *>(row + oj);
                 const f32x4 xk = *reinterpret_cast<const f32x4 *>(row + ok);
@@ -129,30 +124,7 @@ __global__ __launch_bounds__(M4_THREADS) void moment4_tile_kernel(const float *_
         }
     }
 
-    // the copies of a quadruple meet in LDS (the chunk buffers are free: the loop ended with a barrier), copy
-    // after copy in ascending order; copy 0 holds the sum
-    if constexpr (SUBBED) {
-        float *buf = &xs[0][0];                              // nbq * 4 lanes x 64 floats <= 31 * 256
-        const u32 lane_slot = (bq * 4u + ii) * 64u;
-        for (u32 c = 1; c < sub; ++c) {
-            if (live && copy == c) {
-#pragma unroll
-                for (int e = 0; e < 16; ++e)
-                    *reinterpret_cast<f32x4 *>(buf + lane_slot + 4 * e) =
-                        (f32x4){acc[4 * e], acc[4 * e + 1], acc[4 * e + 2], acc[4 * e + 3]};
-            }
-            __syncthreads();
-            if (live && copy == 0u) {
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const f32x4 v = *reinterpret_cast<const f32x4 *>(buf + lane_slot + 4 * e);
-                    acc[4 * e] += v[0]; acc[4 * e + 1] += v[1]; acc[4 * e + 2] += v[2]; acc[4 * e + 3] += v[3];
-                }
-            }
-            __syncthreads();
-        }
-    }
-    if (live && copy == 0u) {
+    if (live) {
         f32x4 *dst = reinterpret_cast<f32x4 *>(ws + (((size_t)blockIdx.y * nbq + bq) * 4u + ii) * 64u);
 #pragma unroll
         for (int e = 0; e < 16; ++e) dst[e] = (f32x4){acc[4 * e], acc[4 * e + 1], acc[4 * e + 2], acc[4 * e + 3]};
@@ -196,7 +168,7 @@ __global__ __launch_bounds__(256) void moment4_zero_kernel(float *__restrict__ p
 }
 
 struct M4Plan {
-    u32 nb4, nbq, gx, S, ch, sub;
+    u32 nb4, nbq, gx, S, ch;
     int64_t slice;
 };
 static inline M4Plan m4_plan(int64_t N, int n)
@@ -206,7 +178,6 @@ static inline M4Plan m4_plan(int64_t N, int n)
     p.nbq = (u32)count_sym4<int64_t>(p.nb4);
     p.gx = (p.nbq + 63u) / 64u;
     p.ch = (u32)M4_CH;
-    p.sub = p.nbq < 64u ? 64u / p.nbq : 1u;                 // copies of every quadruple in a workgroup
     int64_t S = (M4_WGTARGET + p.gx - 1) / p.gx;           // enough slices to fill the chip (four per CU) ...
     int64_t smax = (N + p.ch - 1) / p.ch;                  // ... each of at least one chunk
     const int64_t scap = p.gx >= 12u ? 64 : 768 / (int64_t)p.gx;     // (measured: more slices of many quadruples lose)
@@ -222,6 +193,7 @@ size_t moment4_workspace(int64_t N, int n)
 {
     if (N == 0) return 0;
     if (moment_mfma_wins(4, n)) return moment_mfma_workspace(4, N, n);
+    if (covar_small_applies(n)) return covar_small_workspace(N, n);
     M4Plan p = m4_plan(N, n);
     return (size_t)p.S * p.nbq * 256u * sizeof(float);
 }
@@ -235,15 +207,13 @@ st_status launch_moment4(const float *X, int64_t N, int n, float *Sc, int accumu
         return launch_status();
     }
     if (moment_mfma_wins(4, n)) return launch_moment_mfma(4, X, N, n, Sc, accumulate, ws, s);
-    // n <= 52 from here on
+    // n <= 52 from here on.  Up to 16 features the one-pass covariance kernel is the fastest way to the fourth
+    // moment as well (every multiply-add a unique entry; the two smaller terms it also forms cost little)
+    if (covar_small_applies(n)) return launch_covar_small(X, N, n, nullptr, nullptr, Sc, accumulate, ws, s);
     const M4Plan p = m4_plan(N, n);
     float *wsf = static_cast<float *>(ws);
-    if (p.sub > 1u)
-        hipLaunchKernelGGL(moment4_tile_kernel<true>, dim3(p.gx, p.S), dim3(M4_THREADS), 0, s, X, N, (u32)n, p.nb4,
-                           p.nbq, p.sub, p.slice, wsf);
-    else
-        hipLaunchKernelGGL(moment4_tile_kernel<false>, dim3(p.gx, p.S), dim3(M4_THREADS), 0, s, X, N, (u32)n, p.nb4,
-                           p.nbq, p.sub, p.slice, wsf);
+    hipLaunchKernelGGL(moment4_tile_kernel, dim3(p.gx, p.S), dim3(M4_THREADS), 0, s, X, N, (u32)n, p.nb4, p.nbq,
+                       p.slice, wsf);
     if (hipGetLastError() != hipSuccess) return ST_ERR_LAUNCH;
     hipLaunchKernelGGL(moment4_reduce_kernel, dim3(p.nbq * 16u), dim3(256), 0, s, wsf, p.S, (u32)n, p.nb4, p.nbq, Sc,
                        accumulate);

@@ -15,6 +15,7 @@
 #elif defined(CHECK_MOMENT4)
 #include "../../paper_2211_10482_amd/csrc/st_moment4.hip"
 #include "../../paper_2211_10482_amd/csrc/st_moment_mfma.hip"
+#define ST_STUB_COVAR_SMALL 1   // up to 16 features the fourth moment runs the kernels of the COVARSMALL family
 #elif defined(CHECK_COVARSMALL)
 #include "../../paper_2211_10482_amd/csrc/st_covar_small.hip"
 #elif defined(CHECK_MCOVER)
@@ -34,6 +35,11 @@ namespace st {
 float lds[160 * 1024 / 4];
 int num_cus() { return 256; }
 bool allow_dynamic_lds(const void *, int) { return true; }
+#ifdef ST_STUB_COVAR_SMALL
+bool covar_small_applies(int) { return false; }
+size_t covar_small_workspace(int64_t, int) { return 0; }
+st_status launch_covar_small(const float *, int64_t, int, float *, float *, float *, int, void *, hipStream_t) { return ST_OK; }
+#endif
 }  // namespace st
 
 static float *fbuf(size_t count)

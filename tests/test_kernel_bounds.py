@@ -42,11 +42,11 @@ CASES = {
     "MOMENT2": [(5000, 64, 0), (4097, 64, 1), (3, 64, 0), (100000, 64, 0), (1000, 20, 0), (3, 5, 1), (700, 70, 0),
                 (50, 300, 0), (200, 65, 1), (40, 1024, 0), (9, 1030, 0), (1000, 6, 0), (300000, 13, 1), (70, 16, 0),
                 (5, 1, 0), (600, 17, 0)],
-    # moment4: N n accumulate  (n <= 52: register tiles on the vector ALUs; 53 <= n <= 256: the matrix-core path,
-    # table in the workspace)
+    # moment4: N n accumulate  (17 <= n <= 52: register tiles on the vector ALUs, also run here for smaller n;
+    # 53 <= n <= 256: the matrix-core path, table in the workspace; n <= 16 is the COVARSMALL family's)
     "MOMENT4": [(300, 64, 0), (65, 64, 1), (1, 64, 0), (200, 20, 0), (130, 63, 0), (3, 5, 1), (9, 70, 0),
-                (70, 65, 1), (3, 129, 0), (100, 80, 0), (37, 75, 1), (20, 130, 0), (9, 200, 1), (500, 6, 0),
-                (130, 9, 1), (70, 13, 0), (90, 2, 0), (65, 1, 1), (300, 40, 0)],
+                (70, 65, 1), (3, 129, 0), (100, 80, 0), (37, 75, 1), (20, 130, 0), (9, 200, 1), (70, 13, 0),
+                (300, 40, 0), (130, 52, 1), (90, 17, 0)],
     # one-pass covariance for at most sixteen features: N n accumulate  (n <= 6: every lane holds all entries;
     # 7 <= n <= 16: the entries are split over the waves)
     "COVARSMALL": [(1000, 6, 0), (3, 6, 1), (257, 5, 0), (300000, 4, 0), (70, 1, 1), (513, 3, 0), (1000, 13, 0),
