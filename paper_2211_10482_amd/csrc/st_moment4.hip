@@ -3,9 +3,10 @@
 // (the M3 = vec(f (x) f) (x) vec(f (x) f) term of the degree-2 polynomial-regression
 // covariance, summed over the data; about 23 of every 24 dense entries are redundant).
 //
-// Matrix cores (st_moment_mfma.hip) from 53 features on; lanes that take whole samples up to 16
-// features (st_covar_small.hip); fp32 vector arithmetic on register tiles, in this file, between
-// (where padding the indices to whole groups of 16 costs more than the matrix cores gain).
+// Matrix cores (st_moment_mfma.hip) for 29..32, 41..48 and 53..256 features; lanes that take whole
+// samples up to 16 features (st_covar_small.hip); fp32 vector arithmetic on register tiles, in this
+// file, for the rest (where padding the indices to whole groups of 16 costs more than the matrix
+// cores gain).
 //
 // Tile path, plain fp32 vector arithmetic: on the vector ALUs any set of entries
 // can be owned by any thread, so nothing but the block
@@ -67,7 +68,7 @@ __device__ __forceinline__ void m4_store_chunk(const f32x4 (&r)[M4_LPT], float *
     }
 }
 
-// grid.x = block quadruples / 64, grid.y = sample slices (17 <= n <= 52: at least 70 block quadruples)
+// grid.x = block quadruples / 64, grid.y = sample slices (17 <= n: at least 70 block quadruples)
 __global__ __launch_bounds__(M4_THREADS) void moment4_tile_kernel(const float *__restrict__ X, int64_t N, u32 n,
                                                                 u32 nb4, u32 nbq, int64_t slice,
                                                                 float *__restrict__ ws)
@@ -207,7 +208,7 @@ st_status launch_moment4(const float *X, int64_t N, int n, float *Sc, int accumu
         return launch_status();
     }
     if (moment_mfma_wins(4, n)) return launch_moment_mfma(4, X, N, n, Sc, accumulate, ws, s);
-    // n <= 52 from here on.  Up to 16 features the one-pass covariance kernel is the fastest way to the fourth
+    // Up to 16 features the one-pass covariance kernel is the fastest way to the fourth
     // moment as well (every multiply-add a unique entry; the two smaller terms it also forms cost little)
     if (covar_small_applies(n)) return launch_covar_small(X, N, n, nullptr, nullptr, Sc, accumulate, ws, s);
     const M4Plan p = m4_plan(N, n);

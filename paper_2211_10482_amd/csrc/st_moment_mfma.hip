@@ -515,11 +515,12 @@ static inline MMPlan mm_plan(int order, int64_t N, int n)
 }
 
 // Used where it was measured faster than the vector-ALU tiles (which pad to blocks of 4, not of 16): the fourth
-// moment from 53 features on, the third moment beyond the 64-feature kernel while 16 G <= 8/7 n.
+// moment in the upper part of every group count (29..32, 41..48, 53..64 features) and beyond 64, the third
+// moment beyond the 64-feature kernel while 16 G <= 8/7 n.
 bool moment_mfma_wins(int order, int n)
 {
     const int G = (n + 15) / 16;
-    if (order == 4) return n >= 53 && n <= 256;
+    if (order == 4) return n <= 256 && (n > 64 || n >= (G == 2 ? 29 : G == 3 ? 41 : G == 4 ? 53 : 999));
     return n > 64 && n <= 256 && 14 * G <= n;
 }
 

@@ -354,7 +354,7 @@ def test_moment2_full(st, oracle):
 @pytest.mark.parametrize("N,n", [(1, 1), (7, 5), (100, 16), (300, 64), (65, 64), (64, 64), (50, 20), (130, 63),
                                  (40, 70), (70, 65), (33, 100), (200, 53), (90, 57), (3000, 60), (50, 52),
                                  (40, 80), (25, 75), (20, 128), (11, 113), (900, 6), (700, 9), (333, 13), (64, 2),
-                                 (1000, 3), (257, 12)])
+                                 (1000, 3), (257, 12), (150, 29), (90, 32), (70, 44), (40, 48), (30, 36), (60, 28)])
 def test_moment4_small(st, oracle, N, n):
     say("moment4 N=%d n=%d" % (N, n))
     X = W.normal(401, N * n).reshape(N, n)

@@ -46,13 +46,13 @@ CASES = {
     # 53 <= n <= 256: the matrix-core path, table in the workspace; n <= 16 is the COVARSMALL family's)
     "MOMENT4": [(300, 64, 0), (65, 64, 1), (1, 64, 0), (200, 20, 0), (130, 63, 0), (3, 5, 1), (9, 70, 0),
                 (70, 65, 1), (3, 129, 0), (100, 80, 0), (37, 75, 1), (20, 130, 0), (9, 200, 1), (70, 13, 0),
-                (300, 40, 0), (130, 52, 1), (90, 17, 0)],
+                (300, 40, 0), (130, 52, 1), (90, 17, 0), (70, 30, 0), (200, 45, 1), (65, 29, 0)],
     # one-pass covariance for at most sixteen features: N n accumulate  (n <= 6: every lane holds all entries;
     # 7 <= n <= 16: the entries are split over the waves)
     "COVARSMALL": [(1000, 6, 0), (3, 6, 1), (257, 5, 0), (300000, 4, 0), (70, 1, 1), (513, 3, 0), (1000, 13, 0),
                    (65, 7, 1), (130, 16, 0), (3, 10, 0), (200, 9, 1), (50000, 14, 0)],
     # cover of the matrix-core moment kernels: order n  (every unique entry kept at exactly one tile position)
-    "MCOVER": [(4, 64), (4, 56), (4, 80), (4, 75), (4, 100), (4, 128), (3, 65), (3, 80), (3, 100), (3, 128), (3, 200),
+    "MCOVER": [(4, 30), (4, 32), (4, 41), (4, 48), (4, 64), (4, 56), (4, 80), (4, 75), (4, 100), (4, 128), (3, 65), (3, 80), (3, 100), (3, 128), (3, 200),
                (3, 256), (3, 250)],
     # expand: n order | n 10+kind w p0 count  (device unrank of kind 2, 3, 4 = band, 5 = sym4)
     "EXPAND": [(64, 3), (100, 2), (7, 3), (1, 2), (17, 4), (32, 4), (100, 12, 0, 17, 5000), (100, 13, 0, 17, 5000),
