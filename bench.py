@@ -283,6 +283,14 @@ def main():
             ("expand_sym_order4_n64", lambda: st.expand_sym(Sc4, n5, 4, S=S4),
              dict(flops=0, bytes=4 * (pent + n5 ** 4), bound="hbm")),
         ]
+        # the second moment at 128 and 1024 features (linear-regression covariance of wide data): strips of 64
+        # columns on the matrix cores
+        for Nw, nw, tag in ((1_000_000, 128, "N1e6_n128"), (100_000, 1024, "N1e5_n1024")):
+            Xw = torch.randn((Nw, nw), **f32)
+            Scw = torch.empty(tri(nw), **f32)
+            wsw = torch.empty(max(16, st.workspace_bytes("moment2_sym", N=Nw, n=nw)), dtype=torch.uint8, device=dev)
+            extra.append(("moment2_sym_" + tag, lambda Xw=Xw, Scw=Scw, wsw=wsw: st.moment2_sym(Xw, Sc=Scw, ws=wsw),
+                          dict(flops=Nw * 2 * tri(nw), bytes=4 * (Nw * nw + tri(nw)), bound="mfma")))
         S1c, S2c, S3c = torch.empty(tri(n5), **f32), torch.empty(tet(n5), **f32), torch.empty(pent, **f32)
         wsc = torch.empty(max(16, st.workspace_bytes("covar_pr2", N=N5, n=n5)), dtype=torch.uint8, device=dev)
         extra += [

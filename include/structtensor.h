@@ -158,7 +158,10 @@ st_status st_moment3_sym(const float *X, int64_t N, int n, float *Sc, int accumu
 /* Second-moment accumulation over N samples, upper half only:
  *     Sc(rank2(i,j)) (+)= sum_s X(s,i) * X(s,j)    for i<=j
  * (the M1 = f (x) f term of the same covariance; its structure is plain
- * symmetry).  Arguments as for st_moment3_sym; Sc has n(n+1)/2 entries. */
+ * symmetry).  Arguments as for st_moment3_sym; Sc has n(n+1)/2 entries.  Up to
+ * 1024 features the sum runs on the matrix cores; the workspace holds slice
+ * partials (about 50 MB; more only for N in the tens of millions at several
+ * hundred features: a slice ends after 131,072 samples). */
 st_status st_moment2_sym(const float *X, int64_t N, int n, float *Sc, int accumulate,
                          void *ws, size_t ws_bytes, void *stream);
 

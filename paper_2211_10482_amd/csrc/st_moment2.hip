@@ -19,8 +19,8 @@
 // Algorithmic traffic: 4n bytes per sample, read once.  At n = 64 the matrix cores
 // need 10 MFMAs per four samples, about the same time as the HBM stream.
 //
-// 64 < n <= 1024: 8 x 8 register tiles per lane on the vector ALUs (tile path below); larger n: one
-// thread per unique entry and sample slice.
+// 64 < n <= 1024: strips of 64 columns on the matrix cores (strip path below; 128 < n < 180: 8 x 8 register
+// tiles per lane on the vector ALUs, the tile path); larger n: one thread per unique entry and sample slice.
 #include "st_common.h"
 #include "st_index.h"
 
@@ -29,6 +29,9 @@ namespace st {
 typedef uint32_t u32;
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
+#ifndef ST_M2_TILE_PATH
+#define ST_M2_TILE_PATH 0
+#endif
 #ifndef ST_M2_WAVES
 #define ST_M2_WAVES 8
 #endif
@@ -303,7 +306,7 @@ static inline u32 m2_plain_slices(int64_t N, int n)
     return (u32)(s < 1 ? 1 : s);
 }
 
-// ---- tile path: 64 < n <= 1024, plain fp32 vector arithmetic --------------------------------
+// ---- tile path: 128 < n < 180 (written for any n <= 1024), plain fp32 vector arithmetic -------
 // Blocks of eight indices; a block pair I <= J is owned by one lane with its 8 x 8 accumulators in
 // registers: per sample four 16-byte LDS reads and 64 multiply-adds.  Samples go through a
 // double-buffered LDS chunk per workgroup (rows padded to 8*ceil(n/8) floats), the sample range is cut
@@ -451,6 +454,333 @@ __global__ __launch_bounds__(256) void moment2_tile_reduce_kernel(const float *_
     Sc[p] = accumulate ? Sc[p] + v : v;
 }
 
+// ---- strip path: 64 < n <= 1024 on the matrix cores ------------------------------------------
+// The columns are cut into strips of 64 and a strip is split into the four residue groups of the
+// n <= 64 kernel, so one 16-byte load per lane is again four MFMA operands at once.  Two strips make
+// a block.  A workgroup owns one task and one sample slice; a task is either a whole diagonal block
+// (strip pairs (a0,a0), (a0,a1), (a1,a1): 10 + 16 + 10 tiles, only ga <= gb inside a strip) or one
+// strip of block IB against both strips of a block JB > IB (2 x 16 tiles).  The eight waves take the
+// quads of the slice in turn: a wave loads its four rows of the (two or three) strips straight from
+// memory, M2W_DEPTH quads in flight, and feeds every tile of the task; nothing goes through LDS until
+// the waves add their tiles at the end.  At n <= 128 there is one task and X is read once; beyond, a
+// strip is read by every task that contains it, and the workgroups of one slice are launched next to
+// each other on one XCD (block index -> XCD is round-robin) so that those re-reads meet in that XCD's
+// L2.  Slice partials -> moment2_strip_reduce_kernel (fixed order, keeps i <= j < n, scatters through
+// rank2).  No atomics.
+constexpr int M2W_NMAX = 1024;
+constexpr int M2W_WAVES = 8;
+constexpr int M2W_THREADS = M2W_WAVES * 64;
+constexpr int M2W_BLKS = 3;                       // accumulator blocks of 16 tiles per task
+constexpr int M2W_ACC = M2W_BLKS * 16 * 256;      // accumulators of a task
+#ifndef ST_M2W_DEPTH
+#define ST_M2W_DEPTH 2
+#endif
+constexpr int M2W_DEPTH = ST_M2W_DEPTH;          // quads per register set; two sets, one of them in flight
+constexpr int M2W_WGTARGET = 1024;
+constexpr int64_t M2W_SLICE_MAX = 131072;         // bounds the fp32 accumulation chain of a wave (16,384 samples)
+
+// Three strips with the third nearly empty (128 < n < 180) cost 3.8 times the matrix-core work of two; there the
+// vector-ALU tile path measures faster.
+static inline bool m2w_applies(int n)
+{
+    return !ST_M2_TILE_PATH && n > 64 && n <= M2W_NMAX && !(n > 128 && n < 180);
+}
+// tasks: nbb diagonal blocks first, then (IB < JB, strip of IB) in the order of unrank2 over the block pairs
+struct M2WPlan {
+    u32 nb, nbb, ntasks, S, S8;
+    int64_t slice;
+};
+static inline M2WPlan m2w_plan(int64_t N, int n)
+{
+    M2WPlan p;
+    p.nb = ((u32)n + 63u) / 64u;
+    p.nbb = (p.nb + 1u) / 2u;
+    p.ntasks = p.nbb + p.nbb * (p.nbb - 1u);      // diagonal blocks + 2 per block pair IB < JB
+    // Slices are dealt to the eight XCDs, so their number is a multiple of 8, and one workgroup fits a CU at a
+    // time.  An even number of strips makes tasks of (nearly) equal length: among the counts with at most
+    // M2W_WGTARGET workgroups the one that fills its rounds of 256 best wins (ties: the smallest, every workgroup
+    // ends with a reduction over its waves).  With a single strip in the last block the tasks differ by up to
+    // 3.6x, and as many workgroups as allowed let the CUs even that out.
+    int64_t S = 8;
+    double best = 0.0;
+    for (int64_t c = 8; c == 8 || c * p.ntasks <= M2W_WGTARGET; c += 8) {
+        const int64_t wgs = c * p.ntasks, rounds = (wgs + 255) / 256;
+        const double fill = (p.nb & 1u) ? (double)c : (double)wgs / (double)(rounds * 256);
+        if (fill > best + 1e-9) {
+            best = fill;
+            S = c;
+        }
+    }
+    const int64_t smax = (N + 63) / 64, smin = (N + M2W_SLICE_MAX - 1) / M2W_SLICE_MAX;
+    if (S > smax) S = smax;                       // at least two quads per wave
+    if (S < smin) S = smin;
+    if (S < 1) S = 1;
+    p.slice = ((N + S - 1) / S + 31) / 32 * 32;   // whole rounds of the eight waves
+    p.S = (u32)((N + p.slice - 1) / p.slice);
+    p.S8 = (p.S + 7u) / 8u;
+    return p;
+}
+// task -> first strips sa (rows) and sb (columns); diag: the task is the diagonal block of sa
+__host__ __device__ inline void m2w_task(u32 nbb, u32 task, u32 &sa, u32 &sb, bool &diag)
+{
+    if (task < nbb) {
+        sa = sb = 2u * task;
+        diag = true;
+        return;
+    }
+    // block pairs IB < JB, JB-major: pair index k = JB (JB - 1) / 2 + IB
+    const u32 t = task - nbb, k = t >> 1;
+    u32 JB = 1u;
+    while ((JB + 1u) * JB / 2u <= k) ++JB;        // at most 8 blocks
+    const u32 IB = k - JB * (JB - 1u) / 2u;
+    sa = 2u * IB + (t & 1u);
+    sb = 2u * JB;
+    diag = false;
+}
+
+// MODE 0 / 1: n % 4 == 0 (aligned 16-byte loads, a piece is wholly inside or outside; 0: n % 64 == 0, kept as
+// an instance of its own); 2: any n (16-byte loads at 4-byte alignment).  Rows past the end of the slice and
+// columns past n are clamped to ones that exist.
+// roq = q * n: the lane's row offset inside a quad (it does not change from quad to quad)
+template <int MODE>
+__device__ __forceinline__ f32x4 m2w_load(const float *__restrict__ X, int64_t s, int64_t s_end, u32 n, u32 c0, u32 roq)
+{
+    const int64_t rows = s_end - s;                                          // may be <= 0
+    const float *base = X + (rows > 0 ? s : s_end - 1) * (int64_t)n;        // wave-uniform
+    const u32 qm = rows >= 4 ? 3u : rows > 0 ? (u32)rows - 1u : 0u;          // last row of the quad that exists
+    const u32 ro = min(roq, qm * n);
+    if constexpr (MODE < 2) {
+        const u32 c = c0 < n ? c0 : 0u;                                      // does not change from quad to quad
+        const float4 t = *reinterpret_cast<const float4 *>(base + (ro + c));
+        return (f32x4){t.x, t.y, t.z, t.w};
+    } else {
+        // rows start at any multiple of four bytes: a 16-byte load that only promises that alignment (global
+        // memory needs no more); the one piece that straddles column n goes element by element
+        typedef float f32x4u __attribute__((ext_vector_type(4), aligned(4)));
+        f32x4 v;
+        if (c0 + 4u <= n || c0 >= n) {
+            v = *reinterpret_cast<const f32x4u *>(base + (ro + (c0 < n ? c0 : 0u)));
+        } else {
+#pragma unroll
+            for (u32 g = 0; g < 4; ++g) v[g] = base[ro + (c0 + g < n ? c0 + g : n - 1u)];
+        }
+        return v;
+    }
+}
+// Zeroes the rows past the end of the slice.  One operand of an MFMA is enough (the sum over the four samples
+// then has a zero factor), and columns >= n need no mask at all: they only reach accumulators that the reduce
+// kernel drops.
+__device__ __forceinline__ f32x4 m2w_mask(f32x4 v, int64_t s, int64_t s_end, u32 q)
+{
+    const int64_t rows = s_end - s;
+    if (rows < 4) {                                                          // wave-uniform, the end of a slice only
+#ifndef ST_HOST_EMULATION
+        asm volatile("" : "+v"(v));                                          // a branch, not four selects per quad
+#endif
+        const bool row_ok = (int64_t)q < rows;
+#pragma unroll
+        for (u32 g = 0; g < 4; ++g) v[g] = row_ok ? v[g] : 0.f;
+    }
+    return v;
+}
+template <int BLK>
+__device__ __forceinline__ void m2w_full(f32x4 (&acc)[M2W_BLKS * 16], const f32x4 &xa, const f32x4 &xb)
+{
+#pragma unroll
+    for (int ga = 0; ga < 4; ++ga)
+#pragma unroll
+        for (int gb = 0; gb < 4; ++gb)
+            acc[BLK * 16 + ga * 4 + gb] = __builtin_amdgcn_mfma_f32_16x16x4f32(xa[ga], xb[gb], acc[BLK * 16 + ga * 4 + gb], 0, 0, 0);
+}
+template <int BLK>
+__device__ __forceinline__ void m2w_upper(f32x4 (&acc)[M2W_BLKS * 16], const f32x4 &x)
+{
+#pragma unroll
+    for (int ga = 0; ga < 4; ++ga)
+#pragma unroll
+        for (int gb = ga; gb < 4; ++gb)
+            acc[BLK * 16 + ga * 4 + gb] = __builtin_amdgcn_mfma_f32_16x16x4f32(x[ga], x[gb], acc[BLK * 16 + ga * 4 + gb], 0, 0, 0);
+}
+// the sixteen tiles of accumulator block BLK: the eight waves' values meet in wave 0 (upper half -> lower half, repeatedly)
+template <int BLK>
+__device__ __forceinline__ void m2w_tree(f32x4 (&acc)[M2W_BLKS * 16], float (*red)[16 * 256], u32 wave, u32 lane)
+{
+#pragma unroll
+    for (u32 half = M2W_WAVES / 2; half >= 1; half >>= 1) {
+        if (wave >= half && wave < 2 * half) {
+            float *dst = &red[wave - half][lane];
+#pragma unroll
+            for (int t = 0; t < 16; ++t)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) dst[(t * 4 + v) * 64] = acc[BLK * 16 + t][v];
+        }
+        __syncthreads();
+        if (wave < half) {
+            const float *src = &red[wave][lane];
+#pragma unroll
+            for (int t = 0; t < 16; ++t)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) acc[BLK * 16 + t][v] += src[(t * 4 + v) * 64];
+        }
+        __syncthreads();
+    }
+}
+template <int BLK>
+__device__ __forceinline__ void m2w_emit(const f32x4 (&acc)[M2W_BLKS * 16], float *__restrict__ dst)
+{
+#pragma unroll
+    for (int t = 0; t < 16; ++t)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) dst[((BLK * 16 + t) * 4 + v) * 64] = acc[BLK * 16 + t][v];
+}
+
+// Accumulator blocks of a task: diagonal block: 0 = (sa, sa), 1 = (sa, sa+1), 2 = (sa+1, sa+1); else 0 = (sa, sb), 1 = (sa, sb+1).
+// Where the last block has a single strip, its second strip is loaded (clamped) and multiplied all the same: the
+// loop bodies stay free of branches, and the tiles it reaches are dropped by the reduce kernel.
+// grid.x = 8 * S8 * ntasks: block x works for slice 8 * (x / 8 / ntasks) + x % 8 and task (x / 8) % ntasks
+template <int MODE>
+__global__ __launch_bounds__(M2W_THREADS) void moment2_strip_kernel(const float *__restrict__ X, int64_t N, u32 n,
+                                                                  u32 nb, u32 nbb, u32 ntasks, u32 S, int64_t slice,
+                                                                  float *__restrict__ ws)
+{
+    __shared__ __attribute__((aligned(16))) float red[M2W_WAVES / 2][16 * 256];
+    const u32 tid = threadIdx.x, lane = tid & 63u, q = lane >> 4;
+    const u32 wave = (u32)__builtin_amdgcn_readfirstlane((int)(tid >> 6));
+    const u32 xcd = blockIdx.x & 7u, rest = blockIdx.x >> 3, round = rest / ntasks, task = rest - round * ntasks;
+    const u32 sl = round * 8u + xcd;
+    if (sl >= S) return;                                                   // the whole workgroup
+    u32 sa, sb;
+    bool diag;
+    m2w_task(nbb, task, sa, sb, diag);
+    const bool second = sb + 1u < nb;                                      // the column block has a second strip
+    const u32 m4 = 4u * (lane & 15u), roq = q * n;
+    const u32 ca = 64u * sa + m4, cb0 = 64u * sb + m4, cb1 = cb0 + 64u;
+    const int64_t s_begin = (int64_t)sl * slice, s_end = s_begin + slice < N ? s_begin + slice : N;
+    const int64_t quads = (s_end - s_begin + 3) / 4;
+    const int64_t mine = (int64_t)wave < quads ? (quads - wave + M2W_WAVES - 1) / M2W_WAVES : 0;
+    const int64_t first = s_begin + 4 * (int64_t)wave;
+    constexpr int64_t STEP = 4 * M2W_WAVES;                                 // samples from one quad of a wave to its next
+
+    f32x4 acc[M2W_BLKS * 16];
+#pragma unroll
+    for (int t = 0; t < M2W_BLKS * 16; ++t) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    // Two register sets of M2W_DEPTH quads each.  While one set is consumed the other one is in flight: its loads are
+    // issued behind the MFMAs that last read it, a whole set of quads before its values are needed.
+    f32x4 ra[M2W_DEPTH][3], rb[M2W_DEPTH][3];
+#pragma unroll
+    for (int d = 0; d < M2W_DEPTH; ++d)
+#pragma unroll
+        for (int k = 0; k < 3; ++k) ra[d][k] = rb[d][k] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+    if (diag) {
+        auto fetch = [&](f32x4 (&r)[M2W_DEPTH][3], int64_t kq) {
+#pragma unroll
+            for (int d = 0; d < M2W_DEPTH; ++d) {
+                r[d][1] = m2w_load<MODE>(X, first + (kq + d) * STEP, s_end, n, cb0, roq);
+                r[d][2] = m2w_load<MODE>(X, first + (kq + d) * STEP, s_end, n, cb1, roq);
+            }
+        };
+        auto feed = [&](const f32x4 (&r)[M2W_DEPTH][3], int64_t kq) {
+#pragma unroll
+            for (int d = 0; d < M2W_DEPTH; ++d) {
+                const int64_t s = first + (kq + d) * STEP;
+                const f32x4 y0 = m2w_mask(r[d][1], s, s_end, q), y1 = m2w_mask(r[d][2], s, s_end, q);
+                m2w_upper<0>(acc, y0);
+                m2w_full<1>(acc, y0, y1);
+                m2w_upper<2>(acc, y1);
+            }
+        };
+        fetch(ra, 0);
+        for (int64_t k = 0; k < mine; k += 2 * M2W_DEPTH) {
+            fetch(rb, k + M2W_DEPTH);
+            __builtin_amdgcn_sched_barrier(0);
+            feed(ra, k);
+            __builtin_amdgcn_sched_barrier(0);
+            fetch(ra, k + 2 * M2W_DEPTH);
+            __builtin_amdgcn_sched_barrier(0);
+            feed(rb, k + M2W_DEPTH);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    } else {
+        auto fetch = [&](f32x4 (&r)[M2W_DEPTH][3], int64_t kq) {
+#pragma unroll
+            for (int d = 0; d < M2W_DEPTH; ++d) {
+                r[d][0] = m2w_load<MODE>(X, first + (kq + d) * STEP, s_end, n, ca, roq);
+                r[d][1] = m2w_load<MODE>(X, first + (kq + d) * STEP, s_end, n, cb0, roq);
+                r[d][2] = m2w_load<MODE>(X, first + (kq + d) * STEP, s_end, n, cb1, roq);
+            }
+        };
+        auto feed = [&](const f32x4 (&r)[M2W_DEPTH][3], int64_t kq) {
+#pragma unroll
+            for (int d = 0; d < M2W_DEPTH; ++d) {
+                const int64_t s = first + (kq + d) * STEP;
+                const f32x4 x = m2w_mask(r[d][0], s, s_end, q);
+                m2w_full<0>(acc, x, r[d][1]);
+                m2w_full<1>(acc, x, r[d][2]);
+            }
+        };
+        fetch(ra, 0);
+        for (int64_t k = 0; k < mine; k += 2 * M2W_DEPTH) {
+            fetch(rb, k + M2W_DEPTH);
+            __builtin_amdgcn_sched_barrier(0);
+            feed(ra, k);
+            __builtin_amdgcn_sched_barrier(0);
+            fetch(ra, k + 2 * M2W_DEPTH);
+            __builtin_amdgcn_sched_barrier(0);
+            feed(rb, k + M2W_DEPTH);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+
+    // accumulator blocks in use (the same for all waves)
+    const bool use1 = second, use2 = diag && second;
+    float *dst = ws + ((size_t)sl * ntasks + task) * M2W_ACC + lane;
+    m2w_tree<0>(acc, red, wave, lane);
+    if (use1) m2w_tree<1>(acc, red, wave, lane);
+    if (use2) m2w_tree<2>(acc, red, wave, lane);
+    if (wave == 0) {
+        m2w_emit<0>(acc, dst);
+        if (use1) m2w_emit<1>(acc, dst);
+        if (use2) m2w_emit<2>(acc, dst);
+    }
+}
+
+// A block owns 32 raw accumulators of one task and cuts the S slice partials into 8 groups
+// (slices g, g+8, ... ascending inside a group, groups ascending); stores the entries of the unique set.
+__global__ __launch_bounds__(256) void moment2_strip_reduce_kernel(const float *__restrict__ ws, u32 S, u32 n,
+                                                                  u32 nb, u32 nbb, u32 ntasks, float *__restrict__ Sc,
+                                                                  int accumulate)
+{
+    __shared__ float part[8][32];
+    const u32 a = threadIdx.x & 31u, g = threadIdx.x >> 5;
+    const u32 id = blockIdx.x * 32u + a;                 // < ntasks * M2W_ACC
+    const u32 task = id / (u32)M2W_ACC, e = id % (u32)M2W_ACC;
+    const u32 blk = e >> 12, tile = (e >> 8) & 15u, v = (e >> 6) & 3u, lane = e & 63u;
+    const u32 ga = tile >> 2, gb = tile & 3u;
+    u32 sa, sb;
+    bool diag;
+    m2w_task(nbb, task, sa, sb, diag);
+    const u32 sI = diag ? sa + (blk >> 1) : sa, sJ = diag ? sb + ((blk + 1u) >> 1) : sb + blk;
+    // D layout of the 16x16 MFMA: lane holds column lane%16 of rows 4*(lane/16) + v
+    const u32 mrow = 4u * (lane >> 4) + v, mcol = lane & 15u;
+    const u32 i = 64u * sI + 4u * mrow + ga, j = 64u * sJ + 4u * mcol + gb;
+    const bool keep = (diag || blk < 2u) && (sI != sJ || ga < gb || (ga == gb && mrow <= mcol)) && i < n && j < n;
+    float s = 0.f;
+    if (keep) {
+        const size_t stride = (size_t)ntasks * M2W_ACC;
+#pragma unroll 4
+        for (u32 y = g; y < S; y += 8u) s += ws[(size_t)y * stride + id];
+    }
+    part[g][a] = s;
+    __syncthreads();
+    if (g != 0u || !keep) return;
+    float t = 0.f;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) t += part[k][a];
+    const u32 p = rank_sym2<u32>(n, min(i, j), max(i, j));
+    Sc[p] = accumulate ? Sc[p] + t : t;
+}
+
 size_t moment2_workspace(int64_t N, int n)
 {
     if (N == 0) return 0;
@@ -459,6 +789,10 @@ size_t moment2_workspace(int64_t N, int n)
         return (size_t)m2s_groups(N) * (np * (np + 1u) / 2u) * sizeof(float);
     }
     if (n <= 64) return (size_t)m2_groups(N) * M2_ACC * sizeof(float);
+    if (m2w_applies(n)) {
+        const M2WPlan p = m2w_plan(N, n);
+        return (size_t)p.S * p.ntasks * M2W_ACC * sizeof(float);
+    }
     if (n <= M2T_NMAX) {
         const M2TPlan p = m2t_plan(N, n);
         return (size_t)p.S * p.nbp * 64u * sizeof(float);
@@ -497,6 +831,20 @@ st_status launch_moment2(const float *X, int64_t N, int n, float *Sc, int accumu
         if (hipGetLastError() != hipSuccess) return ST_ERR_LAUNCH;
         hipLaunchKernelGGL(moment2_reduce_kernel, dim3(M2_ACC / 64), dim3(256), 0, s, wsf, G, (u32)n, Sc,
                            accumulate);
+        return launch_status();
+    }
+    if (m2w_applies(n)) {
+        const M2WPlan p = m2w_plan(N, n);
+        const dim3 grid(8u * p.S8 * p.ntasks), block(M2W_THREADS);
+        if (n % 64 == 0)
+            hipLaunchKernelGGL(moment2_strip_kernel<0>, grid, block, 0, s, X, N, (u32)n, p.nb, p.nbb, p.ntasks, p.S, p.slice, wsf);
+        else if (n % 4 == 0)
+            hipLaunchKernelGGL(moment2_strip_kernel<1>, grid, block, 0, s, X, N, (u32)n, p.nb, p.nbb, p.ntasks, p.S, p.slice, wsf);
+        else
+            hipLaunchKernelGGL(moment2_strip_kernel<2>, grid, block, 0, s, X, N, (u32)n, p.nb, p.nbb, p.ntasks, p.S, p.slice, wsf);
+        if (hipGetLastError() != hipSuccess) return ST_ERR_LAUNCH;
+        hipLaunchKernelGGL(moment2_strip_reduce_kernel, dim3(p.ntasks * (u32)M2W_ACC / 32u), dim3(256), 0, s, wsf, p.S,
+                           (u32)n, p.nb, p.nbb, p.ntasks, Sc, accumulate);
         return launch_status();
     }
     if (n <= M2T_NMAX) {

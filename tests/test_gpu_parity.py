@@ -306,7 +306,9 @@ def test_moment3_full(st, oracle):
 # ---------------------------------------------------------------------- moment2 (M1)
 @pytest.mark.parametrize("N,n", [(1, 1), (7, 5), (100, 64), (4097, 64), (33, 64), (1000, 20), (5000, 63), (300, 70),
                                  (64, 200), (700, 65), (90, 1024), (20, 1100), (300000, 6), (70000, 13), (5000, 16),
-                                 (999, 2), (400000, 9), (257, 17)])
+                                 (999, 2), (400000, 9), (257, 17), (3000, 128), (1001, 130), (2100, 192), (777, 250),
+                                 (1500, 256), (513, 258), (900, 260), (640, 384), (333, 513), (400, 1000), (5000, 180),
+                                 (2000, 188), (31, 320), (129, 66)])
 def test_moment2_small(st, oracle, N, n):
     say("moment2 N=%d n=%d" % (N, n))
     X = W.normal(301, N * n).reshape(N, n)
@@ -336,6 +338,35 @@ def test_moment2_special_cases(st, oracle):
     assert float(Sc.min()) == 3.0
     st.moment2_sym(torch.empty((0, n), device="cuda"), Sc=Sc)
     assert float(Sc.abs().max()) == 0.0
+
+
+@pytest.mark.parametrize("N,n", [(300000, 128), (100000, 320), (40000, 1024), (150001, 250)])
+def test_moment2_wide_long(st, oracle, N, n):
+    """64 < n <= 1024: strips of 64 columns on the matrix cores, many slices and long accumulation chains."""
+    say("moment2 wide N=%d n=%d" % (N, n))
+    X = W.moment_inputs(N, n)
+    got = st.moment2_sym(dev(X)).cpu().numpy()
+    ref = oracle.moment2_dense(X)[np.triu_indices(n)]
+    err = rel_err(got, ref)
+    say("  norm-wise error %.3e" % err)
+    assert err <= TOL
+
+
+@pytest.mark.parametrize("n", [128, 200, 258, 1024])
+def test_moment2_wide_exact_entries(st, n):
+    """Two columns set to 1 and 2, everything else zero: the three entries they reach are exact integers, and no
+    other entry may be touched -- for column pairs inside a strip, across strips and across blocks."""
+    N = 1000
+    cols = sorted({0, 3, 63, 64, 65, 127, 128, n // 2, n - 65, n - 2, n - 1} & set(range(n)))
+    for a in cols:
+        for b in cols:
+            if a >= b:
+                continue
+            X = np.zeros((N, n), dtype=np.float32)
+            X[:, a], X[:, b] = 1.0, 2.0
+            got = st.moment2_sym(dev(X)).cpu().numpy()
+            assert got[st.rank_sym2(n, a, a)] == N and got[st.rank_sym2(n, a, b)] == 2 * N and got[st.rank_sym2(n, b, b)] == 4 * N, (n, a, b)
+            assert np.count_nonzero(got) == 3, (n, a, b)
 
 
 def test_moment2_full(st, oracle):

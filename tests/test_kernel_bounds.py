@@ -37,11 +37,11 @@ CASES = {
     "MOMENT3": [(5000, 64, 0), (4097, 64, 1), (63, 64, 0), (100000, 64, 0), (1000, 20, 0), (3, 5, 1),
                 (700, 70, 0), (100, 1, 0), (3000, 13, 1), (257, 40, 0), (500, 48, 0), (130, 129, 0), (70, 200, 0),
                 (33, 256, 0), (20, 300, 0), (50, 66, 1), (40, 100, 0)],
-    # moment2: N n accumulate  (n <= 16: a lane per sample; n <= 64: the MFMA path; n <= 1024: the tile path;
-    # beyond: the plain path)
+    # moment2: N n accumulate  (n <= 16: a lane per sample; n <= 64: the MFMA path; n <= 1024: strips of 64
+    # columns on the matrix cores; beyond: the plain path)
     "MOMENT2": [(5000, 64, 0), (4097, 64, 1), (3, 64, 0), (100000, 64, 0), (1000, 20, 0), (3, 5, 1), (700, 70, 0),
                 (50, 300, 0), (200, 65, 1), (40, 1024, 0), (9, 1030, 0), (1000, 6, 0), (300000, 13, 1), (70, 16, 0),
-                (5, 1, 0), (600, 17, 0)],
+                (5, 1, 0), (600, 17, 0), (1000, 128, 0), (37, 130, 1), (300, 1000, 0), (5, 100, 0), (2100, 192, 0)],
     # moment4: N n accumulate  (17 <= n <= 52: register tiles on the vector ALUs, also run here for smaller n;
     # 53 <= n <= 256: the matrix-core path, table in the workspace; n <= 16 is the COVARSMALL family's)
     "MOMENT4": [(300, 64, 0), (65, 64, 1), (1, 64, 0), (200, 20, 0), (130, 63, 0), (3, 5, 1), (9, 70, 0),
