@@ -457,9 +457,10 @@ __global__ __launch_bounds__(256) void moment2_tile_reduce_kernel(const float *_
 // ---- strip path: 64 < n <= 1024 on the matrix cores ------------------------------------------
 // The columns are cut into strips of 64 and a strip is split into the four residue groups of the
 // n <= 64 kernel, so one 16-byte load per lane is again four MFMA operands at once.  Two strips make
-// a block.  A workgroup owns one task and one sample slice; a task is either a whole diagonal block
-// (strip pairs (a0,a0), (a0,a1), (a1,a1): 10 + 16 + 10 tiles, only ga <= gb inside a strip) or one
-// strip of block IB against both strips of a block JB > IB (2 x 16 tiles).  The eight waves take the
+// a block (an odd strip count: strip 0 is a block of its own).  A workgroup owns one task and one
+// sample slice; a task is either a whole diagonal block (strip pairs (a0,a0), (a0,a1), (a1,a1):
+// 10 + 16 + 10 tiles, only ga <= gb inside a strip) or one strip against both strips of a later
+// block (2 x 16 tiles).  The eight waves take the
 // quads of the slice in turn: a wave loads its four rows of the (two or three) strips straight from
 // memory, M2W_DEPTH quads in flight, and feeds every tile of the task; nothing goes through LDS until
 // the waves add their tiles at the end.  At n <= 128 there is one task and X is read once; beyond, a
@@ -483,9 +484,18 @@ constexpr int64_t M2W_SLICE_MAX = 131072;         // bounds the fp32 accumulatio
 // vector-ALU tile path measures faster.
 static inline bool m2w_applies(int n)
 {
+#ifdef ST_M2W_NO_TILE_RULE
+    return n > 64 && n <= M2W_NMAX;
+#endif
     return !ST_M2_TILE_PATH && n > 64 && n <= M2W_NMAX && !(n > 128 && n < 180);
 }
-// tasks: nbb diagonal blocks first, then (IB < JB, strip of IB) in the order of unrank2 over the block pairs
+// Blocks: two strips each; with an odd number of strips the FIRST block is the single strip 0, so that every
+// column block of an off-diagonal task is whole.  first strip of block b:
+__host__ __device__ inline u32 m2w_first(u32 nb, u32 b)
+{
+    return (nb & 1u) ? (b == 0u ? 0u : 2u * b - 1u) : 2u * b;
+}
+// tasks: the nbb diagonal blocks, then for every column block JB >= 1 the strips before it, one task each
 struct M2WPlan {
     u32 nb, nbb, ntasks, S, S8;
     int64_t slice;
@@ -495,17 +505,17 @@ static inline M2WPlan m2w_plan(int64_t N, int n)
     M2WPlan p;
     p.nb = ((u32)n + 63u) / 64u;
     p.nbb = (p.nb + 1u) / 2u;
-    p.ntasks = p.nbb + p.nbb * (p.nbb - 1u);      // diagonal blocks + 2 per block pair IB < JB
+    p.ntasks = p.nbb;
+    for (u32 JB = 1; JB < p.nbb; ++JB) p.ntasks += m2w_first(p.nb, JB);
     // Slices are dealt to the eight XCDs, so their number is a multiple of 8, and one workgroup fits a CU at a
-    // time.  An even number of strips makes tasks of (nearly) equal length: among the counts with at most
+    // time.  The tasks are of nearly equal length (36 or 32 MFMAs per quad): among the counts with at most
     // M2W_WGTARGET workgroups the one that fills its rounds of 256 best wins (ties: the smallest, every workgroup
-    // ends with a reduction over its waves).  With a single strip in the last block the tasks differ by up to
-    // 3.6x, and as many workgroups as allowed let the CUs even that out.
+    // ends with a reduction over its waves).
     int64_t S = 8;
     double best = 0.0;
     for (int64_t c = 8; c == 8 || c * p.ntasks <= M2W_WGTARGET; c += 8) {
         const int64_t wgs = c * p.ntasks, rounds = (wgs + 255) / 256;
-        const double fill = (p.nb & 1u) ? (double)c : (double)wgs / (double)(rounds * 256);
+        const double fill = (double)wgs / (double)(rounds * 256);
         if (fill > best + 1e-9) {
             best = fill;
             S = c;
@@ -520,22 +530,25 @@ static inline M2WPlan m2w_plan(int64_t N, int n)
     p.S8 = (p.S + 7u) / 8u;
     return p;
 }
-// task -> first strips sa (rows) and sb (columns); diag: the task is the diagonal block of sa
-__host__ __device__ inline void m2w_task(u32 nbb, u32 task, u32 &sa, u32 &sb, bool &diag)
+// task -> row strip sa and first column strip sb; diag: the task is the diagonal block that starts at sb;
+// single: that block is the single strip (accumulator blocks 1 and 2 then hold copies of block 0's pairs)
+__host__ __device__ inline void m2w_task(u32 nb, u32 nbb, u32 task, u32 &sa, u32 &sb, bool &diag, bool &single)
 {
     if (task < nbb) {
-        sa = sb = 2u * task;
+        sa = sb = m2w_first(nb, task);
         diag = true;
+        single = (nb & 1u) && task == 0u;
         return;
     }
-    // block pairs IB < JB, JB-major: pair index k = JB (JB - 1) / 2 + IB
-    const u32 t = task - nbb, k = t >> 1;
-    u32 JB = 1u;
-    while ((JB + 1u) * JB / 2u <= k) ++JB;        // at most 8 blocks
-    const u32 IB = k - JB * (JB - 1u) / 2u;
-    sa = 2u * IB + (t & 1u);
-    sb = 2u * JB;
+    u32 t = task - nbb, JB = 1u;
+    while (t >= m2w_first(nb, JB)) {               // at most 8 blocks
+        t -= m2w_first(nb, JB);
+        ++JB;
+    }
+    sa = t;
+    sb = m2w_first(nb, JB);
     diag = false;
+    single = false;
 }
 
 // MODE 0 / 1: n % 4 == 0 (aligned 16-byte loads, a piece is wholly inside or outside; 0: n % 64 == 0, kept as
@@ -634,9 +647,7 @@ __device__ __forceinline__ void m2w_emit(const f32x4 (&acc)[M2W_BLKS * 16], floa
         for (int v = 0; v < 4; ++v) dst[((BLK * 16 + t) * 4 + v) * 64] = acc[BLK * 16 + t][v];
 }
 
-// Accumulator blocks of a task: diagonal block: 0 = (sa, sa), 1 = (sa, sa+1), 2 = (sa+1, sa+1); else 0 = (sa, sb), 1 = (sa, sb+1).
-// Where the last block has a single strip, its second strip is loaded (clamped) and multiplied all the same: the
-// loop bodies stay free of branches, and the tiles it reaches are dropped by the reduce kernel.
+// Accumulator blocks of a task: diagonal block: 0 = (sb, sb), 1 = (sb, sb+1), 2 = (sb+1, sb+1); else 0 = (sa, sb), 1 = (sa, sb+1).
 // grid.x = 8 * S8 * ntasks: block x works for slice 8 * (x / 8 / ntasks) + x % 8 and task (x / 8) % ntasks
 template <int MODE>
 __global__ __launch_bounds__(M2W_THREADS) void moment2_strip_kernel(const float *__restrict__ X, int64_t N, u32 n,
@@ -650,11 +661,12 @@ __global__ __launch_bounds__(M2W_THREADS) void moment2_strip_kernel(const float 
     const u32 sl = round * 8u + xcd;
     if (sl >= S) return;                                                   // the whole workgroup
     u32 sa, sb;
-    bool diag;
-    m2w_task(nbb, task, sa, sb, diag);
-    const bool second = sb + 1u < nb;                                      // the column block has a second strip
+    bool diag, single;
+    m2w_task(nb, nbb, task, sa, sb, diag, single);
     const u32 m4 = 4u * (lane & 15u), roq = q * n;
-    const u32 ca = 64u * sa + m4, cb0 = 64u * sb + m4, cb1 = cb0 + 64u;
+    // the single strip stands in for its missing neighbour: the loops stay free of branches, and the reduce
+    // kernel reads accumulator block 0 of that task only
+    const u32 ca = 64u * sa + m4, cb0 = 64u * sb + m4, cb1 = single ? cb0 : cb0 + 64u;
     const int64_t s_begin = (int64_t)sl * slice, s_end = s_begin + slice < N ? s_begin + slice : N;
     const int64_t quads = (s_end - s_begin + 3) / 4;
     const int64_t mine = (int64_t)wave < quads ? (quads - wave + M2W_WAVES - 1) / M2W_WAVES : 0;
@@ -733,7 +745,7 @@ __global__ __launch_bounds__(M2W_THREADS) void moment2_strip_kernel(const float 
     }
 
     // accumulator blocks in use (the same for all waves)
-    const bool use1 = second, use2 = diag && second;
+    const bool use1 = !single, use2 = diag && !single;
     float *dst = ws + ((size_t)sl * ntasks + task) * M2W_ACC + lane;
     m2w_tree<0>(acc, red, wave, lane);
     if (use1) m2w_tree<1>(acc, red, wave, lane);
@@ -758,13 +770,14 @@ __global__ __launch_bounds__(256) void moment2_strip_reduce_kernel(const float *
     const u32 blk = e >> 12, tile = (e >> 8) & 15u, v = (e >> 6) & 3u, lane = e & 63u;
     const u32 ga = tile >> 2, gb = tile & 3u;
     u32 sa, sb;
-    bool diag;
-    m2w_task(nbb, task, sa, sb, diag);
-    const u32 sI = diag ? sa + (blk >> 1) : sa, sJ = diag ? sb + ((blk + 1u) >> 1) : sb + blk;
+    bool diag, single;
+    m2w_task(nb, nbb, task, sa, sb, diag, single);
+    const u32 sI = diag ? sb + (blk >> 1) : sa, sJ = diag ? sb + ((blk + 1u) >> 1) : sb + blk;
     // D layout of the 16x16 MFMA: lane holds column lane%16 of rows 4*(lane/16) + v
     const u32 mrow = 4u * (lane >> 4) + v, mcol = lane & 15u;
     const u32 i = 64u * sI + 4u * mrow + ga, j = 64u * sJ + 4u * mcol + gb;
-    const bool keep = (diag || blk < 2u) && (sI != sJ || ga < gb || (ga == gb && mrow <= mcol)) && i < n && j < n;
+    const bool keep = (diag ? (!single || blk == 0u) : blk < 2u) && (sI != sJ || ga < gb || (ga == gb && mrow <= mcol)) &&
+                      i < n && j < n;
     float s = 0.f;
     if (keep) {
         const size_t stride = (size_t)ntasks * M2W_ACC;

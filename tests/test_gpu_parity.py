@@ -352,7 +352,7 @@ def test_moment2_wide_long(st, oracle, N, n):
     assert err <= TOL
 
 
-@pytest.mark.parametrize("n", [128, 200, 258, 1024])
+@pytest.mark.parametrize("n", [128, 190, 200, 258, 1024])
 def test_moment2_wide_exact_entries(st, n):
     """Two columns set to 1 and 2, everything else zero: the three entries they reach are exact integers, and no
     other entry may be touched -- for column pairs inside a strip, across strips and across blocks."""
