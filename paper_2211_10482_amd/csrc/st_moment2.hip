@@ -29,9 +29,6 @@ namespace st {
 typedef uint32_t u32;
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-#ifndef ST_M2_TILE_PATH
-#define ST_M2_TILE_PATH 0
-#endif
 #ifndef ST_M2_WAVES
 #define ST_M2_WAVES 8
 #endif
@@ -473,21 +470,15 @@ constexpr int M2W_WAVES = 8;
 constexpr int M2W_THREADS = M2W_WAVES * 64;
 constexpr int M2W_BLKS = 3;                       // accumulator blocks of 16 tiles per task
 constexpr int M2W_ACC = M2W_BLKS * 16 * 256;      // accumulators of a task
-#ifndef ST_M2W_DEPTH
-#define ST_M2W_DEPTH 2
-#endif
-constexpr int M2W_DEPTH = ST_M2W_DEPTH;          // quads per register set; two sets, one of them in flight
+constexpr int M2W_DEPTH = 2;                      // quads per register set; two sets, one of them in flight
 constexpr int M2W_WGTARGET = 1024;
 constexpr int64_t M2W_SLICE_MAX = 131072;         // bounds the fp32 accumulation chain of a wave (16,384 samples)
 
-// Three strips with the third nearly empty (128 < n < 180) cost 3.8 times the matrix-core work of two; there the
+// Three strips with one nearly empty (128 < n < 180) cost 2.9 times the matrix-core work of two; there the
 // vector-ALU tile path measures faster.
 static inline bool m2w_applies(int n)
 {
-#ifdef ST_M2W_NO_TILE_RULE
-    return n > 64 && n <= M2W_NMAX;
-#endif
-    return !ST_M2_TILE_PATH && n > 64 && n <= M2W_NMAX && !(n > 128 && n < 180);
+    return n > 64 && n <= M2W_NMAX && !(n > 128 && n < 180);
 }
 // Blocks: two strips each; with an odd number of strips the FIRST block is the single strip 0, so that every
 // column block of an off-diagonal task is whole.  first strip of block b:
