@@ -20,6 +20,8 @@
 #include "../../paper_2211_10482_amd/csrc/st_covar_small.hip"
 #elif defined(CHECK_MCOVER)
 #include "../../paper_2211_10482_amd/csrc/st_moment_mfma.hip"
+#elif defined(CHECK_M2COVER)
+#include "../../paper_2211_10482_amd/csrc/st_moment2.hip"
 #elif defined(CHECK_EXPAND)
 #include "../../paper_2211_10482_amd/csrc/st_expand.hip"
 #elif defined(CHECK_TABLE)
@@ -113,6 +115,24 @@ int main(int argc, char **argv)
     size_t bad = 0;
     for (size_t q = 0; q < cnt; ++q) bad += Sc[q] != 1.f;
     printf("blocks=%u tiles=%u entries=%zu bad=%zu\n", p.blocks, p.blocks * st::MM_TPB, cnt, bad);
+    rc = bad == 0 ? 0 : 4;
+    free(part); free(Sc);
+#elif defined(CHECK_M2COVER)
+    // The tasks of the second moment's strip path and the kept-position rule of its reduce kernel: with every raw
+    // accumulator set to 1 and Sc to 0, the reduce kernel in accumulate mode must leave exactly 1 in every unique
+    // entry.  One slice: only the first of the kernel's eight slice groups adds anything, so the emulation's
+    // sequential threads see what a workgroup would.   args: n
+    const int n = (int)a[0];
+    const size_t cnt = (size_t)st::count_sym2<int64_t>(n);
+    const st::M2WPlan p = st::m2w_plan(4, n);
+    if (p.S != 1) return 3;
+    float *part = fbuf((size_t)p.ntasks * st::M2W_ACC), *Sc = fbuf(cnt);
+    for (size_t q = 0; q < cnt; ++q) Sc[q] = 0.f;
+    hipLaunchKernelGGL(st::moment2_strip_reduce_kernel, dim3(p.ntasks * (unsigned)st::M2W_ACC / 32u), dim3(256), 0, nullptr,
+                       part, 1u, (unsigned)n, p.nb, p.nbb, p.ntasks, Sc, 1);
+    size_t bad = 0;
+    for (size_t q = 0; q < cnt; ++q) bad += Sc[q] != 1.f;
+    printf("strips=%u tasks=%u entries=%zu bad=%zu\n", p.nb, p.ntasks, cnt, bad);
     rc = bad == 0 ? 0 : 4;
     free(part); free(Sc);
 #elif defined(CHECK_MOMENT2) || defined(CHECK_MOMENT4)

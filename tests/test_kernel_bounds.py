@@ -7,9 +7,9 @@ allocates the operands with exactly the sizes the C-ABI documents and calls the 
 launchers the library calls, so an index that leaves an operand, the workspace or an
 LDS array aborts here instead of faulting a GPU.  Values are not checked (barriers and
 cross-lane operations have no meaning in this emulation); parity is the GPU tests' job.
-One family is a value check all the same: MCOVER runs the reduce kernels of the matrix-core
-moment path (no barriers in them) over accumulators that all hold 1 and counts, per unique
-entry, how many tile positions the tile table and the kept-position rules map to it: exactly one.
+Two families are value checks all the same: MCOVER and M2COVER run the reduce kernels of the
+matrix-core moment paths over accumulators that all hold 1 and count, per unique entry, how many
+tile positions the tile table (or task list) and the kept-position rules map to it: exactly one.
 """
 import os
 import shutil
@@ -54,6 +54,8 @@ CASES = {
     # cover of the matrix-core moment kernels: order n  (every unique entry kept at exactly one tile position)
     "MCOVER": [(4, 30), (4, 32), (4, 41), (4, 48), (4, 64), (4, 56), (4, 80), (4, 75), (4, 100), (4, 128), (3, 65), (3, 80), (3, 100), (3, 128), (3, 200),
                (3, 256), (3, 250)],
+    # cover of the second moment's strip path: n  (every pair i <= j kept at exactly one tile position of one task)
+    "M2COVER": [(65,), (100,), (128,), (150,), (192,), (200,), (258,), (320,), (513,), (960,), (1000,), (1024,)],
     # expand: n order | n 10+kind w p0 count  (device unrank of kind 2, 3, 4 = band, 5 = sym4)
     "EXPAND": [(64, 3), (100, 2), (7, 3), (1, 2), (17, 4), (32, 4), (100, 12, 0, 17, 5000), (100, 13, 0, 17, 5000),
                (100, 14, 7, 17, 1000), (40, 15, 0, 17, 5000)],
