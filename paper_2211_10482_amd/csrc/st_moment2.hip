@@ -457,14 +457,14 @@ __global__ __launch_bounds__(256) void moment2_tile_reduce_kernel(const float *_
 // a block (an odd strip count: strip 0 is a block of its own).  A workgroup owns one task and one
 // sample slice; a task is either a whole diagonal block (strip pairs (a0,a0), (a0,a1), (a1,a1):
 // 10 + 16 + 10 tiles, only ga <= gb inside a strip) or one strip against both strips of a later
-// block (2 x 16 tiles).  The eight waves take the
-// quads of the slice in turn: a wave loads its four rows of the (two or three) strips straight from
-// memory, M2W_DEPTH quads in flight, and feeds every tile of the task; nothing goes through LDS until
-// the waves add their tiles at the end.  At n <= 128 there is one task and X is read once; beyond, a
-// strip is read by every task that contains it, and the workgroups of one slice are launched next to
-// each other on one XCD (block index -> XCD is round-robin) so that those re-reads meet in that XCD's
-// L2.  Slice partials -> moment2_strip_reduce_kernel (fixed order, keeps i <= j < n, scatters through
-// rank2).  No atomics.
+// block (2 x 16 tiles).  The eight waves take the quads of the slice in turn: a wave loads its four
+// rows of the (two or three) strips straight from memory, two register sets of M2W_DEPTH quads, one
+// of them in flight, and feeds every tile of the task; nothing goes through LDS until the waves add
+// their tiles at the end.  At n <= 128 there is one task and X is read once; beyond, a strip is read
+// by every task that contains it, and the workgroups of one slice are launched next to each other on
+// one XCD (block index -> XCD is round-robin) so that those re-reads meet in that XCD's L2.  Slice
+// partials -> moment2_strip_reduce_kernel (fixed order, keeps i <= j < n, scatters through rank2).
+// No atomics.
 constexpr int M2W_NMAX = 1024;
 constexpr int M2W_WAVES = 8;
 constexpr int M2W_THREADS = M2W_WAVES * 64;
