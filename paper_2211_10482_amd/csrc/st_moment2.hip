@@ -50,34 +50,40 @@ __host__ __device__ constexpr int m2_ga(int t) { return t < 4 ? 0 : t < 7 ? 1 : 
 __host__ __device__ constexpr int m2_gb(int t) { return t < 4 ? t : t < 7 ? t - 3 : t < 9 ? t - 5 : 3; }
 
 // Four samples s .. s+3 for this lane's row q = lane/16, columns 4m .. 4m+3 (m = lane%16).
-// Unconditional (row clamped); mask_quad zeroes what lies outside.
-template <bool FULL>
+// Unconditional (row clamped, columns >= n clamped to ones that exist); mask_quad zeroes the rows
+// past N, and what columns >= n bring only reaches accumulators the reduce kernel drops.
+// MODE 0: n == 64; 1: n % 4 == 0 (aligned 16-byte loads, a piece is wholly inside or outside);
+// 2: any n (four 4-byte loads).
+template <int MODE>
 __device__ __forceinline__ f32x4 load_quad(const float *__restrict__ X, int64_t s, int64_t N, u32 n, u32 lane)
 {
     const u32 m = lane & 15u, q = lane >> 4;
     const int64_t r = s + q < N ? s + q : N - 1;
-    if constexpr (FULL) {
+    if constexpr (MODE == 0) {
         const float4 t = *reinterpret_cast<const float4 *>(X + r * 64 + 4u * m);
         return (f32x4){t.x, t.y, t.z, t.w};
     } else {
         const float *row = X + r * (int64_t)n;
-        f32x4 v;
+        const u32 c0 = 4u * m;
+        if constexpr (MODE == 1) {
+            const float4 t = *reinterpret_cast<const float4 *>(row + (c0 < n ? c0 : 0u));
+            return (f32x4){t.x, t.y, t.z, t.w};
+        } else {
+            // rows start at any multiple of four bytes: element by element (16-byte loads that only promise
+            // 4-byte alignment measured 40 % slower here)
+            f32x4 v;
 #pragma unroll
-        for (u32 g = 0; g < 4; ++g) v[g] = row[4u * m + g < n ? 4u * m + g : n - 1u];
-        return v;
+            for (u32 g = 0; g < 4; ++g) v[g] = row[c0 + g < n ? c0 + g : n - 1u];
+            return v;
+        }
     }
 }
 
-template <bool FULL>
-__device__ __forceinline__ f32x4 mask_quad(f32x4 v, int64_t s, int64_t N, u32 n, u32 lane)
+__device__ __forceinline__ f32x4 mask_quad(f32x4 v, int64_t s, int64_t N, u32 lane)
 {
-    const u32 m = lane & 15u, q = lane >> 4;
-    const bool row_ok = s + q < N;
+    const bool row_ok = s + (lane >> 4) < N;
 #pragma unroll
-    for (u32 g = 0; g < 4; ++g) {
-        const bool ok = row_ok && (FULL || 4u * m + g < n);
-        v[g] = ok ? v[g] : 0.f;
-    }
+    for (u32 g = 0; g < 4; ++g) v[g] = row_ok ? v[g] : 0.f;
     return v;
 }
 
@@ -90,7 +96,7 @@ __device__ __forceinline__ void m2_step(f32x4 (&acc)[M2_TILES], const f32x4 &x)
 
 // Sample quads are dealt to the waves of the whole grid round-robin: quad index
 // w + k * (waves in the grid), so neighbouring waves stream neighbouring kilobytes.
-template <bool FULL>
+template <int MODE>
 __global__ __launch_bounds__(M2_THREADS) void moment2_mfma_kernel(const float *__restrict__ X, int64_t N, u32 n,
                                                                 float *__restrict__ ws)
 {
@@ -108,13 +114,13 @@ __global__ __launch_bounds__(M2_THREADS) void moment2_mfma_kernel(const float *_
     // ring of M2_DEPTH loads: quads past the end are clamped loads of the last row and masked
     f32x4 ring[M2_DEPTH];
 #pragma unroll
-    for (int d = 0; d < M2_DEPTH; ++d) ring[d] = load_quad<FULL>(X, 4 * (first + d * stride), N, n, lane);
+    for (int d = 0; d < M2_DEPTH; ++d) ring[d] = load_quad<MODE>(X, 4 * (first + d * stride), N, n, lane);
     for (int64_t k = 0; k < mine; k += M2_DEPTH) {
 #pragma unroll
         for (int d = 0; d < M2_DEPTH; ++d) {
             const int64_t s = 4 * (first + (k + d) * stride);
-            const f32x4 x = mask_quad<FULL>(ring[d], s, N, n, lane);
-            ring[d] = load_quad<FULL>(X, s + 4 * M2_DEPTH * stride, N, n, lane);
+            const f32x4 x = mask_quad(ring[d], s, N, lane);
+            ring[d] = load_quad<MODE>(X, s + 4 * M2_DEPTH * stride, N, n, lane);
             __builtin_amdgcn_sched_barrier(0);
             m2_step(acc, x);
             __builtin_amdgcn_sched_barrier(0);
@@ -543,7 +549,8 @@ __host__ __device__ inline void m2w_task(u32 nb, u32 nbb, u32 task, u32 &sa, u32
 }
 
 // MODE 0 / 1: n % 4 == 0 (aligned 16-byte loads, a piece is wholly inside or outside; 0: n % 64 == 0, kept as
-// an instance of its own); 2: any n (16-byte loads at 4-byte alignment).  Rows past the end of the slice and
+// an instance of its own); 2: any n (16-byte loads at 4-byte alignment: faster than 3 from three strips on,
+// slower with two); 3: any n (four 4-byte loads).  Rows past the end of the slice and
 // columns past n are clamped to ones that exist.
 // roq = q * n: the lane's row offset inside a quad (it does not change from quad to quad)
 template <int MODE>
@@ -557,6 +564,11 @@ __device__ __forceinline__ f32x4 m2w_load(const float *__restrict__ X, int64_t s
         const u32 c = c0 < n ? c0 : 0u;                                      // does not change from quad to quad
         const float4 t = *reinterpret_cast<const float4 *>(base + (ro + c));
         return (f32x4){t.x, t.y, t.z, t.w};
+    } else if constexpr (MODE == 3) {
+        f32x4 v;
+#pragma unroll
+        for (u32 g = 0; g < 4; ++g) v[g] = base[ro + (c0 + g < n ? c0 + g : n - 1u)];
+        return v;
     } else {
         // rows start at any multiple of four bytes: a 16-byte load that only promises that alignment (global
         // memory needs no more); the one piece that straddles column n goes element by element
@@ -834,9 +846,11 @@ st_status launch_moment2(const float *X, int64_t N, int n, float *Sc, int accumu
     if (n <= 64) {
         u32 G = m2_groups(N);
         if (n == 64)
-            hipLaunchKernelGGL(moment2_mfma_kernel<true>, dim3(G), dim3(M2_THREADS), 0, s, X, N, (u32)n, wsf);
+            hipLaunchKernelGGL(moment2_mfma_kernel<0>, dim3(G), dim3(M2_THREADS), 0, s, X, N, (u32)n, wsf);
+        else if (n % 4 == 0)
+            hipLaunchKernelGGL(moment2_mfma_kernel<1>, dim3(G), dim3(M2_THREADS), 0, s, X, N, (u32)n, wsf);
         else
-            hipLaunchKernelGGL(moment2_mfma_kernel<false>, dim3(G), dim3(M2_THREADS), 0, s, X, N, (u32)n, wsf);
+            hipLaunchKernelGGL(moment2_mfma_kernel<2>, dim3(G), dim3(M2_THREADS), 0, s, X, N, (u32)n, wsf);
         if (hipGetLastError() != hipSuccess) return ST_ERR_LAUNCH;
         hipLaunchKernelGGL(moment2_reduce_kernel, dim3(M2_ACC / 64), dim3(256), 0, s, wsf, G, (u32)n, Sc,
                            accumulate);
@@ -849,8 +863,10 @@ st_status launch_moment2(const float *X, int64_t N, int n, float *Sc, int accumu
             hipLaunchKernelGGL(moment2_strip_kernel<0>, grid, block, 0, s, X, N, (u32)n, p.nb, p.nbb, p.ntasks, p.S, p.slice, wsf);
         else if (n % 4 == 0)
             hipLaunchKernelGGL(moment2_strip_kernel<1>, grid, block, 0, s, X, N, (u32)n, p.nb, p.nbb, p.ntasks, p.S, p.slice, wsf);
-        else
+        else if (p.nb > 2u)
             hipLaunchKernelGGL(moment2_strip_kernel<2>, grid, block, 0, s, X, N, (u32)n, p.nb, p.nbb, p.ntasks, p.S, p.slice, wsf);
+        else
+            hipLaunchKernelGGL(moment2_strip_kernel<3>, grid, block, 0, s, X, N, (u32)n, p.nb, p.nbb, p.ntasks, p.S, p.slice, wsf);
         if (hipGetLastError() != hipSuccess) return ST_ERR_LAUNCH;
         hipLaunchKernelGGL(moment2_strip_reduce_kernel, dim3(p.ntasks * (u32)M2W_ACC / 32u), dim3(256), 0, s, wsf, p.S,
                            (u32)n, p.nb, p.nbb, p.ntasks, Sc, accumulate);
