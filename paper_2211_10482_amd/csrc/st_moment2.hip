@@ -583,9 +583,8 @@ __device__ __forceinline__ f32x4 m2w_load(const float *__restrict__ X, int64_t s
         return v;
     }
 }
-// Zeroes the rows past the end of the slice.  One operand of an MFMA is enough (the sum over the four samples
-// then has a zero factor), and columns >= n need no mask at all: they only reach accumulators that the reduce
-// kernel drops.
+// Zeroes the rows past the end of the slice (both operands: a clamped row may hold a value that is not finite, and
+// 0 * inf is not 0).  Columns >= n need no mask at all: they only reach accumulators that the reduce kernel drops.
 __device__ __forceinline__ f32x4 m2w_mask(f32x4 v, int64_t s, int64_t s_end, u32 q)
 {
     const int64_t rows = s_end - s;
@@ -730,8 +729,9 @@ __global__ __launch_bounds__(M2W_THREADS) void moment2_strip_kernel(const float 
             for (int d = 0; d < M2W_DEPTH; ++d) {
                 const int64_t s = first + (kq + d) * STEP;
                 const f32x4 x = m2w_mask(r[d][0], s, s_end, q);
-                m2w_full<0>(acc, x, r[d][1]);
-                m2w_full<1>(acc, x, r[d][2]);
+                const f32x4 y0 = m2w_mask(r[d][1], s, s_end, q), y1 = m2w_mask(r[d][2], s, s_end, q);
+                m2w_full<0>(acc, x, y0);
+                m2w_full<1>(acc, x, y1);
             }
         };
         fetch(ra, 0);
