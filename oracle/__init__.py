@@ -329,14 +329,15 @@ def struct_thp(Bc, C, dims, in_unique):
 
 def struct_moment(X, dims, in_unique):
     """Sc(p) = sum_s prod_v X(s, x_v(p)) over the unique set in packed order (fp64): the covariance term of
-    the overview's M1 / M2 nests ("creation and addition of covariance matrices") restricted to a structure."""
+    the overview's M1 / M2 nests ("creation and addition of covariance matrices") restricted to a structure.
+    One sample at a time, in sample order: the product of the sample's values at the indices of every unique
+    tuple, added to the running sum."""
     idx = struct_enumerate(dims, in_unique).astype(np.int64)
     Xd = np.asarray(X, dtype=np.float64)
     out = np.zeros(idx.shape[0], dtype=np.float64)
-    for s0 in range(0, Xd.shape[0], 256):
-        xs = Xd[s0:s0 + 256]
-        prod = np.ones((xs.shape[0], idx.shape[0]))
+    for s in range(Xd.shape[0]):
+        prod = np.ones(idx.shape[0], dtype=np.float64)
         for v in range(idx.shape[1]):
-            prod = prod * xs[:, idx[:, v]]
-        out += prod.sum(axis=0)
+            prod = prod * Xd[s, idx[:, v]]
+        out += prod
     return out

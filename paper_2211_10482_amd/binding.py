@@ -193,6 +193,25 @@ def _dev_f32(t, what):
     return C.c_void_p(t.data_ptr())
 
 
+def _expect(t, numel, what, at_least=False):
+    """The C ABI takes bare pointers, so a tensor of the wrong length would become an out-of-bounds device
+    access: every packed operand and caller-supplied output is checked against the size of its unique set
+    here, before anything is marshalled."""
+    if not isinstance(t, _torch().Tensor):
+        raise TypeError("%s must be a contiguous float32 CUDA tensor" % what)
+    have = int(t.numel())
+    if have != int(numel) and not (at_least and have > int(numel)):
+        raise ValueError("%s holds %d elements, expected %s%d" % (what, have, "at least " if at_least else "", numel))
+
+
+def _matrix(t, what):
+    if not isinstance(t, _torch().Tensor):
+        raise TypeError("%s must be a contiguous float32 CUDA tensor" % what)
+    if t.dim() != 2:
+        raise ValueError("%s must be a matrix, got %d dimensions" % (what, t.dim()))
+    return int(t.shape[0]), int(t.shape[1])
+
+
 def _workspace(nbytes, like, ws):
     torch = _torch()
     if ws is None:
@@ -236,9 +255,11 @@ def unrank_device(kind, n, w, p0, count):
 
 def mttkrp_sym3(Tc, B, M=None, ws=None):
     torch = _torch()
-    n, R = B.shape
+    n, R = _matrix(B, "B")
+    _expect(Tc, count_sym3(n), "Tc")
     if M is None:
         M = torch.empty((n, R), dtype=torch.float32, device=B.device)
+    _expect(M, n * R, "M")
     ws, pws, wsb = _workspace(workspace_bytes("mttkrp_sym3", n=n, R=R), B, ws)
     _check(lib().st_mttkrp_sym3(_dev_f32(Tc, "Tc"), _dev_f32(B, "B"), _dev_f32(M, "M"), n, R, pws, wsb,
                                 _stream()), "st_mttkrp_sym3")
@@ -248,8 +269,10 @@ def mttkrp_sym3(Tc, B, M=None, ws=None):
 def batax_utri(Ap, x, beta, y=None, ws=None):
     torch = _torch()
     n = x.numel()
+    _expect(Ap, count_sym2(n), "Ap")
     if y is None:
         y = torch.empty(n, dtype=torch.float32, device=x.device)
+    _expect(y, n, "y")
     ws, pws, wsb = _workspace(workspace_bytes("batax_utri", n=n), x, ws)
     _check(lib().st_batax_utri(_dev_f32(Ap, "Ap"), _dev_f32(x, "x"), _dev_f32(y, "y"), n, float(beta), pws,
                                wsb, _stream()), "st_batax_utri")
@@ -258,10 +281,14 @@ def batax_utri(Ap, x, beta, y=None, ws=None):
 
 def ttm_band(Tc, U, n, w, Yc=None, ws=None):
     torch = _torch()
-    nl, R = U.shape
+    nl, R = _matrix(U, "U")
     rows = count_band(n, w)
+    if rows < 0:
+        raise ValueError("n and w must be non-negative")
+    _expect(Tc, rows * nl, "Tc")
     if Yc is None:
         Yc = torch.empty((rows, R), dtype=torch.float32, device=U.device)
+    _expect(Yc, rows * R, "Yc")
     ws, pws, wsb = _workspace(workspace_bytes("ttm_band", n=n, w=w, nl=nl, R=R), U, ws)
     _check(lib().st_ttm_band(_dev_f32(Tc, "Tc"), _dev_f32(U, "U"), _dev_f32(Yc, "Yc"), n, w, nl, R, pws, wsb,
                              _stream()), "st_ttm_band")
@@ -270,11 +297,12 @@ def ttm_band(Tc, U, n, w, Yc=None, ws=None):
 
 def moment3_sym(X, Sc=None, accumulate=False, ws=None):
     torch = _torch()
-    N, n = X.shape
+    N, n = _matrix(X, "X")
     if Sc is None:
         if accumulate:
             raise ValueError("accumulate needs an existing Sc")
         Sc = torch.empty(count_sym3(n), dtype=torch.float32, device=X.device)
+    _expect(Sc, count_sym3(n), "Sc")
     ws, pws, wsb = _workspace(workspace_bytes("moment3_sym", N=N, n=n), X, ws)
     px = _dev_f32(X, "X") if N > 0 else C.c_void_p(X.data_ptr() if X.numel() else 0)
     _check(lib().st_moment3_sym(px, N, n, _dev_f32(Sc, "Sc"), 1 if accumulate else 0, pws, wsb, _stream()),
@@ -284,13 +312,14 @@ def moment3_sym(X, Sc=None, accumulate=False, ws=None):
 
 def _moment(order, X, Sc, accumulate, ws):
     torch = _torch()
-    N, n = X.shape
+    N, n = _matrix(X, "X")
     name = "moment%d_sym" % order
     count = {2: count_sym2, 3: count_sym3, 4: count_sym4}[order](n)
     if Sc is None:
         if accumulate:
             raise ValueError("accumulate needs an existing Sc")
         Sc = torch.empty(count, dtype=torch.float32, device=X.device)
+    _expect(Sc, count, "Sc")
     ws, pws, wsb = _workspace(workspace_bytes(name, N=N, n=n), X, ws)
     px = _dev_f32(X, "X") if N > 0 else C.c_void_p(X.data_ptr() if X.numel() else 0)
     _check(getattr(lib(), "st_" + name)(px, N, n, _dev_f32(Sc, "Sc"), 1 if accumulate else 0, pws, wsb, _stream()),
@@ -301,11 +330,15 @@ def _moment(order, X, Sc, accumulate, ws):
 def covar_pr2(X, S=None, accumulate=False, ws=None):
     """(S1, S2, S3): unique entries of the degree-2, -3 and -4 interaction terms of the samples X."""
     torch = _torch()
-    N, n = X.shape
+    N, n = _matrix(X, "X")
     if S is None:
         if accumulate:
             raise ValueError("accumulate needs existing outputs")
         S = tuple(torch.empty(c(n), dtype=torch.float32, device=X.device) for c in (count_sym2, count_sym3, count_sym4))
+    if len(S) != 3:
+        raise ValueError("S must hold the three terms (S1, S2, S3)")
+    for t, c, what in zip(S, (count_sym2, count_sym3, count_sym4), ("S1", "S2", "S3")):
+        _expect(t, c(n), what)
     ws, pws, wsb = _workspace(workspace_bytes("covar_pr2", N=N, n=n), X, ws)
     px = _dev_f32(X, "X") if N > 0 else C.c_void_p(X.data_ptr() if X.numel() else 0)
     _check(lib().st_covar_pr2(px, N, n, _dev_f32(S[0], "S1"), _dev_f32(S[1], "S2"), _dev_f32(S[2], "S3"),
@@ -323,8 +356,12 @@ def moment4_sym(X, Sc=None, accumulate=False, ws=None):
 
 def expand_sym(Sc, n, order, S=None):
     torch = _torch()
+    if order not in (2, 3, 4) or n < 1:
+        raise ValueError("order must be 2, 3 or 4 and n positive")
+    _expect(Sc, {2: count_sym2, 3: count_sym3, 4: count_sym4}[order](n), "Sc")
     if S is None:
         S = torch.empty((n,) * order, dtype=torch.float32, device=Sc.device)
+    _expect(S, n ** order, "S")
     _check(lib().st_expand_sym(_dev_f32(Sc, "Sc"), _dev_f32(S, "S"), n, order, _stream()), "st_expand_sym")
     return S
 
@@ -332,10 +369,14 @@ def expand_sym(Sc, n, order, S=None):
 # ---- the kernel table's sparsity structures ---------------------------------------------
 def ttm_struct(structure, Bc, U, ni, nj, Ac=None, ws=None):
     torch = _torch()
-    nl, R = U.shape
+    nl, R = _matrix(U, "U")
     rows = count_struct(structure, ni, nj)
+    if rows < 0:
+        raise ValueError("unknown structure, or extents it does not allow")
+    _expect(Bc, rows * nl, "Bc")
     if Ac is None:
         Ac = torch.empty((max(rows, 0), R), dtype=torch.float32, device=U.device)
+    _expect(Ac, rows * R, "Ac")
     ws, pws, wsb = _workspace(workspace_bytes("ttm_struct", structure=structure, ni=ni, nj=nj, nl=nl, R=R), U, ws)
     _check(lib().st_ttm_struct(structure, _dev_f32(Bc, "Bc"), _dev_f32(U, "U"), _dev_f32(Ac, "Ac"), ni, nj, nl, R,
                                pws, wsb, _stream()), "st_ttm_struct")
@@ -344,10 +385,16 @@ def ttm_struct(structure, Bc, U, ni, nj, Ac=None, ws=None):
 
 def thp_struct(structure, Bc, C, fixed=0, Ac=None):
     torch = _torch()
-    ni, nj, nl = C.shape
+    if C.dim() != 3:
+        raise ValueError("C must be a dense order-3 tensor")
+    ni, nj, nl = (int(v) for v in C.shape)
     rows = count_struct(structure, ni, nj)
+    if rows < 0:
+        raise ValueError("unknown structure, or extents it does not allow")
+    _expect(Bc, rows * nl, "Bc")
     if Ac is None:
         Ac = torch.empty((max(rows, 0), nl), dtype=torch.float32, device=C.device)
+    _expect(Ac, rows * nl, "Ac")
     _check(lib().st_thp_struct(structure, _dev_f32(Bc, "Bc"), _dev_f32(C, "C"), _dev_f32(Ac, "Ac"), ni, nj, nl,
                                int(fixed), _stream()), "st_thp_struct")
     return Ac
@@ -355,11 +402,17 @@ def thp_struct(structure, Bc, C, fixed=0, Ac=None):
 
 def mttkrp_fixed(kind, Bc, C, D, ni, fixed_k=0, A=None, ws=None):
     torch = _torch()
-    nk, R = C.shape
-    nl = D.shape[0]
+    nk, R = _matrix(C, "C")
+    nl, RD = _matrix(D, "D")
+    if RD != R:
+        raise ValueError("C and D must have the same number of columns")
+    if kind not in (MTTKRP_FIXED_IK, MTTKRP_FIXED_I, MTTKRP_FIXED_K):
+        raise ValueError("unknown kind")
+    _expect(Bc, {MTTKRP_FIXED_IK: 1, MTTKRP_FIXED_I: nk, MTTKRP_FIXED_K: ni}[kind] * nl, "Bc")
     if A is None:
         shape = (ni, R) if kind == MTTKRP_FIXED_K else (R,)
         A = torch.empty(shape, dtype=torch.float32, device=C.device)
+    _expect(A, (ni if kind == MTTKRP_FIXED_K else 1) * R, "A")
     ws, pws, wsb = _workspace(workspace_bytes("mttkrp_fixed", kind=kind, ni=ni, nk=nk, nl=nl, R=R), C, ws)
     _check(lib().st_mttkrp_fixed(kind, _dev_f32(Bc, "Bc"), _dev_f32(C, "C"), _dev_f32(D, "D"), _dev_f32(A, "A"),
                                  ni, nk, nl, R, int(fixed_k), pws, wsb, _stream()), "st_mttkrp_fixed")
@@ -368,8 +421,13 @@ def mttkrp_fixed(kind, Bc, C, D, ni, fixed_k=0, A=None, ws=None):
 
 def expand_band(Tc, n, w, nl, T=None):
     torch = _torch()
+    rows = count_band(n, w)
+    if rows < 0 or nl < 1:
+        raise ValueError("n, w must be non-negative and nl positive")
+    _expect(Tc, rows * nl, "Tc")
     if T is None:
         T = torch.empty((n, n, nl), dtype=torch.float32, device=Tc.device)
+    _expect(T, n * n * nl, "T")
     _check(lib().st_expand_band(_dev_f32(Tc, "Tc"), _dev_f32(T, "T"), n, w, nl, _stream()), "st_expand_band")
     return T
 
@@ -441,36 +499,48 @@ class Descriptor:
 
     def thp(self, Bc, Cd, Ac=None):
         torch = _torch()
+        _expect(Bc, self.count, "Bc", at_least=True)
+        _expect(Cd, int(np.prod(self.dims)), "C")
         if Ac is None:
             Ac = torch.empty(max(self.count, 4), dtype=torch.float32, device=Cd.device)
+        _expect(Ac, self.count, "Ac", at_least=True)
         self._call(lib().st_desc_thp(self._h, self._tab(), _dev_f32(Bc, "Bc"), _dev_f32(Cd, "C"),
                                      _dev_f32(Ac, "Ac"), _stream()), "st_desc_thp")
         return Ac[:self.count]
 
     def expand(self, Tc, T=None):
         torch = _torch()
+        _expect(Tc, self.count, "Tc", at_least=True)
         if T is None:
             T = torch.empty(self.dims, dtype=torch.float32, device=Tc.device)
+        _expect(T, int(np.prod(self.dims)), "T")
         self._call(lib().st_desc_expand(self._h, self._tab(), _dev_f32(Tc, "Tc"), _dev_f32(T, "T"), _stream()),
                    "st_desc_expand")
         return T
 
     def ttm(self, Bc, U, Ac=None):
         torch = _torch()
-        R = U.shape[1]
+        nl, R = _matrix(U, "U")
+        if nl != self.dims[-1]:
+            raise ValueError("U must have as many rows as the last extent of the descriptor")
+        _expect(Bc, self.runs * nl, "Bc", at_least=True)
         if Ac is None:
             Ac = torch.empty((max(self.runs, 1), R), dtype=torch.float32, device=U.device)
+        _expect(Ac, self.runs * R, "Ac", at_least=True)
         self._call(lib().st_desc_ttm(self._h, _dev_f32(Bc, "Bc"), _dev_f32(U, "U"), _dev_f32(Ac, "Ac"), R, _stream()),
                    "st_desc_ttm")
         return Ac[:self.runs]
 
     def moment(self, X, Sc=None, accumulate=False, ws=None):
         torch = _torch()
-        N = X.shape[0]
+        N, n = _matrix(X, "X")
+        if n != self.dims[-1]:
+            raise ValueError("X must have one column per feature of the descriptor")
         if Sc is None:
             if accumulate:
                 raise ValueError("accumulate needs an existing Sc")
             Sc = torch.empty(max(self.count, 4), dtype=torch.float32, device=X.device)
+        _expect(Sc, self.count, "Sc", at_least=True)
         ws, pws, wsb = _workspace(int(lib().st_desc_moment_workspace(self._h, N)), X, ws)
         px = _dev_f32(X, "X") if N > 0 else C.c_void_p(X.data_ptr() if X.numel() else 0)
         self._call(lib().st_desc_moment(self._h, self._tab(), px, N, _dev_f32(Sc, "Sc"), 1 if accumulate else 0, pws,

@@ -174,3 +174,63 @@ def test_covar_pr2_errors():
     assert need == max(L.st_moment2_sym_workspace(5000, 64), L.st_moment3_sym_workspace(5000, 64),
                        L.st_moment4_sym_workspace(5000, 64)) > 0
     assert L.st_covar_pr2_workspace(10, 300) == 0
+
+
+def test_binding_rejects_wrong_sized_tensors():
+    """The binding compares every packed operand and caller-supplied output with the size of its unique set
+    before it marshals anything: a wrong length is a ValueError, raised on the host (CPU tensors suffice: the
+    size check comes before the device check, and a right-sized CPU tensor then fails as 'not a CUDA tensor')."""
+    import pytest
+    import torch
+    z = lambda *shape: torch.zeros(*shape)
+    n, R = 6, 3
+    bad = [
+        lambda: st.mttkrp_sym3(z(st.count_sym3(n) - 1), z(n, R)),
+        lambda: st.mttkrp_sym3(z(st.count_sym3(n)), z(n, R), M=z(n, R + 1)),
+        lambda: st.mttkrp_sym3(z(st.count_sym3(n)), z(n * R)),
+        lambda: st.batax_utri(z(st.count_sym2(n) + 4), z(n), 0.5),
+        lambda: st.batax_utri(z(st.count_sym2(n)), z(n), 0.5, y=z(n - 1)),
+        lambda: st.ttm_band(z(st.count_band(n, 1), 8)[:-1], z(8, R), n, 1),
+        lambda: st.ttm_band(z(st.count_band(n, 1), 8), z(8, R), n, 1, Yc=z(st.count_band(n, 1), R - 1)),
+        lambda: st.moment3_sym(z(10, n), Sc=z(st.count_sym3(n) - 1)),
+        lambda: st.moment2_sym(z(10, n), Sc=z(st.count_sym2(n) + 1)),
+        lambda: st.moment4_sym(z(10, n), Sc=z(st.count_sym4(n) - 1)),
+        lambda: st.moment3_sym(z(10 * n)),
+        lambda: st.covar_pr2(z(10, n), S=(z(st.count_sym2(n)), z(st.count_sym3(n)), z(st.count_sym4(n) - 2))),
+        lambda: st.expand_sym(z(st.count_sym3(n) - 1), n, 3),
+        lambda: st.expand_sym(z(st.count_sym3(n)), n, 3, S=z(n, n, n - 1)),
+        lambda: st.expand_sym(z(st.count_sym2(n)), n, 3),
+        lambda: st.ttm_struct(st.STRUCT_UPPER, z(st.count_sym2(n), 8)[1:], z(8, R), n, n),
+        lambda: st.ttm_struct(st.STRUCT_DIAG, z(n, 8), z(8, R), n, n, Ac=z(n - 1, R)),
+        lambda: st.ttm_struct(st.STRUCT_UPPER, z(n, 8), z(8, R), n, n + 1),
+        lambda: st.thp_struct(st.STRUCT_FIXED_I, z(n - 1, 8), z(4, n, 8)),
+        lambda: st.thp_struct(st.STRUCT_DIAG, z(n, 8), z(n, n, 8), Ac=z(n, 7)),
+        lambda: st.mttkrp_fixed(st.MTTKRP_FIXED_K, z(5, 8)[:-1], z(4, R), z(8, R), 5),
+        lambda: st.mttkrp_fixed(st.MTTKRP_FIXED_I, z(4, 8), z(4, R), z(8, R + 1), 5),
+        lambda: st.mttkrp_fixed(st.MTTKRP_FIXED_I, z(4, 8), z(4, R), z(8, R), 5, A=z(R + 1)),
+        lambda: st.expand_band(z(st.count_band(n, 2) * 4 - 1), n, 2, 4),
+        lambda: st.expand_band(z(st.count_band(n, 2) * 4), n, 2, 4, T=z(n, n, 3)),
+    ]
+    for q, f in enumerate(bad):
+        with pytest.raises(ValueError):
+            f()
+            raise AssertionError("case %d was accepted" % q)
+    # right sizes pass the size checks and stop at the device check: nothing was launched
+    with pytest.raises(TypeError):
+        st.mttkrp_sym3(z(st.count_sym3(n)), z(n, R), ws=torch.zeros(1 << 20, dtype=torch.uint8))
+    with pytest.raises(TypeError):
+        st.expand_sym(z(st.count_sym2(n)), n, 2)
+    # descriptor calls
+    d = st.Descriptor("T(i,j,k): (0<=i<n)*(i<=j<n)*(j<=k<n)", (n, n, n), "sort", n=n)
+    for f in (lambda: d.expand(z(d.count - 1)), lambda: d.expand(z(d.count), T=z(n, n, n + 1)),
+              lambda: d.thp(z(d.count), z(n, n, n - 1)), lambda: d.thp(z(d.count - 3), z(n, n, n)),
+              lambda: d.moment(z(10, n + 1)), lambda: d.moment(z(10, n), Sc=z(d.count - 1))):
+        with pytest.raises(ValueError):
+            f()
+    d.close()
+    db = st.Descriptor("B(i,j,l): (0<=i<n)*(i-1<=j<=i+1)*(0<=l<m)", (n, n, 4), n=n, m=4)
+    for f in (lambda: db.ttm(z(db.runs, 4), z(5, R)), lambda: db.ttm(z(db.runs - 1, 4), z(4, R)),
+              lambda: db.ttm(z(db.runs, 4), z(4, R), Ac=z(db.runs - 1, R))):
+        with pytest.raises(ValueError):
+            f()
+    db.close()

@@ -41,7 +41,8 @@ CASES = {
     # columns on the matrix cores; beyond: the plain path)
     "MOMENT2": [(5000, 64, 0), (4097, 64, 1), (3, 64, 0), (100000, 64, 0), (1000, 20, 0), (3, 5, 1), (700, 70, 0),
                 (50, 300, 0), (200, 65, 1), (40, 1024, 0), (9, 1030, 0), (1000, 6, 0), (300000, 13, 1), (70, 16, 0),
-                (5, 1, 0), (600, 17, 0), (1000, 128, 0), (37, 130, 1), (300, 1000, 0), (5, 100, 0), (2100, 192, 0)],
+                (5, 1, 0), (600, 17, 0), (1000, 128, 0), (37, 130, 1), (300, 1000, 0), (5, 100, 0), (2100, 192, 0),
+                (37, 190, 0), (50, 513, 0), (9, 250, 1)],   # n % 4 != 0 with three or more strips
     # moment4: N n accumulate  (17 <= n <= 52: register tiles on the vector ALUs, also run here for smaller n;
     # 53 <= n <= 256: the matrix-core path, table in the workspace; n <= 16 is the COVARSMALL family's)
     "MOMENT4": [(300, 64, 0), (65, 64, 1), (1, 64, 0), (200, 20, 0), (130, 63, 0), (3, 5, 1), (9, 70, 0),

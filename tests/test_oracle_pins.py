@@ -386,3 +386,125 @@ def test_kernel_table_dense_definitions(oracle):
     Tb = W.uniform(118, oracle.count_band(n, w) * nl)
     Tdense = oracle.dense_band(Tb, n, w, nl).astype(np.float32)
     assert np.allclose(oracle.ttm_full(Tdense, U), oracle.ttm_dense(Tb, U, n, w), rtol=1e-13, atol=1e-14)
+
+
+# ------------------------------------------------- structures given as predicates (brute force over the box)
+# The predicate helpers check the descriptor-driven kernels; here they are pinned to the C oracle's counting-loop
+# listings and dense definitions (pinned above), to numpy's own index routines and to the paper's two worked
+# examples of a unique set / redundancy map.
+@pytest.mark.parametrize("n", [1, 2, 5, 12])
+def test_struct_enumerate_symmetric_sets(oracle, n):
+    assert np.array_equal(oracle.struct_enumerate((n, n), lambda i, j: i <= j), oracle.list_sym2(n))
+    assert np.array_equal(oracle.struct_enumerate((n,) * 3, lambda i, j, k: i <= j <= k), oracle.list_sym3(n))
+    if n <= 5:
+        assert np.array_equal(oracle.struct_enumerate((n,) * 4, lambda i, j, k, l: i <= j <= k <= l),
+                              oracle.list_sym4(n))
+
+
+@pytest.mark.parametrize("n,w", [(1, 0), (4, 0), (7, 2), (12, 3), (9, 20)])
+def test_struct_enumerate_band(oracle, n, w):
+    assert np.array_equal(oracle.struct_enumerate((n, n), lambda i, j: abs(i - j) <= w), oracle.list_band(n, w))
+    # with a free last index every in-band pair is one run of nl consecutive positions
+    nl = 3
+    lst = oracle.struct_enumerate((n, n, nl), lambda i, j, l: abs(i - j) <= w)
+    pairs = oracle.list_band(n, w)
+    assert np.array_equal(lst[:, :2], np.repeat(pairs, nl, axis=0))
+    assert np.array_equal(lst[:, 2], np.tile(np.arange(nl), pairs.shape[0]))
+
+
+def test_struct_chess_board_example(oracle):
+    # "Chess Pattern Unique Set": even rows keep the odd columns, odd rows the even columns
+    m, n = 6, 8
+    pred = lambda i, j: (i % 2 == 0 and j % 2 == 1) or (i % 2 == 1 and j % 2 == 0)
+    lst = oracle.struct_enumerate((m, n), pred)
+    assert lst.shape[0] == 2 * (m // 2) * (n // 2)
+    I, J = np.indices((m, n))
+    assert np.array_equal(lst, np.argwhere((I + J) % 2 == 1))
+    # written as the example writes it: i = 2i', j = 2j'+1  and  i = 2i'+1, j = 2j'
+    want = sorted([(2 * a, 2 * b + 1) for a in range(m // 2) for b in range(n // 2)] +
+                  [(2 * a + 1, 2 * b) for a in range(m // 2) for b in range(n // 2)])
+    assert [tuple(int(v) for v in t) for t in lst] == want
+    # no redundancy map: reconstruction puts the stored values on the pattern and zeros elsewhere
+    Tc = W.uniform(201, lst.shape[0])
+    T = oracle.struct_expand(Tc, (m, n), pred)
+    assert np.array_equal(T[lst[:, 0], lst[:, 1]], Tc)
+    assert not T[(I + J) % 2 == 0].any()
+
+
+def test_struct_identical_rows_example(oracle):
+    # "Identical Row Matrix Redundancy Map": T_U = (i=0)*(0<=j<n), T_R: (0<i<m)*(0<=j<n) -> (0, j)
+    m, n = 5, 7
+    pred = lambda i, j: i == 0
+    lst = oracle.struct_enumerate((m, n), pred)
+    assert np.array_equal(lst, np.stack([np.zeros(n, dtype=np.int32), np.arange(n, dtype=np.int32)], axis=1))
+    Tc = W.uniform(202, n)
+    T = oracle.struct_expand(Tc, (m, n), pred, lambda i, j: (0, j) if 0 < i < m else None)
+    assert np.array_equal(T, np.tile(Tc, (m, 1)))
+    # Property 1: no index is both unique and redundant; without the map only the first row is filled
+    assert all(not (pred(i, j) and 0 < i < m) for i in range(m) for j in range(n))
+    T0 = oracle.struct_expand(Tc, (m, n), pred)
+    assert np.array_equal(T0[0], Tc) and not T0[1:].any()
+
+
+@pytest.mark.parametrize("n", [1, 2, 5, 9])
+def test_struct_expand_is_property5(oracle, n):
+    # full symmetry (x' = ascending sort of x) must reproduce the C oracle's reconstruction bit for bit
+    order_preds = {2: lambda i, j: i <= j, 3: lambda i, j, k: i <= j <= k, 4: lambda i, j, k, l: i <= j <= k <= l}
+    counts = {2: oracle.count_sym2, 3: oracle.count_sym3, 4: oracle.count_sym4}
+    for order in (2, 3, 4):
+        if order == 4 and n > 5:
+            continue
+        Sc = W.uniform(210 + order, counts[order](n))
+        got = oracle.struct_expand(Sc, (n,) * order, order_preds[order], lambda *x: tuple(sorted(x)))
+        assert np.array_equal(got.view(np.uint32), oracle.expand_sym(Sc, n, order).view(np.uint32))
+    # the class-S map written out: for j < i the unique index is (j, i)
+    Sc = W.uniform(215, oracle.count_sym2(n))
+    got = oracle.struct_expand(Sc, (n, n), order_preds[2], lambda i, j: (j, i) if j < i else None)
+    assert np.array_equal(got, oracle.expand_sym(Sc, n, 2))
+    # a band has no redundancy: zero-filled dense form
+    w, nl = min(2, n - 1), 3
+    Tb = W.uniform(216, oracle.count_band(n, w) * nl)
+    got = oracle.struct_expand(Tb, (n, n, nl), lambda i, j, l: abs(i - j) <= w)
+    assert np.array_equal(got.astype(np.float64), oracle.dense_band(Tb, n, w, nl))
+
+
+def test_struct_thp_on_the_band(oracle):
+    n, w, nl = 9, 2, 5
+    pred = lambda i, j, l: abs(i - j) <= w
+    Bc = W.uniform(221, oracle.count_band(n, w) * nl)
+    Cd = W.uniform(222, n * n * nl).reshape(n, n, nl)
+    pairs = oracle.list_band(n, w).astype(np.int64)
+    ref = oracle.thp_full(Bc.reshape(-1, nl), Cd[pairs[:, 0], pairs[:, 1]])      # gathered fibres, dense THP
+    assert np.array_equal(oracle.struct_thp(Bc, Cd, (n, n, nl), pred), ref.reshape(-1))
+    # and through the zero-filled dense operand: the product keeps the support of B
+    dense = oracle.thp_full(oracle.dense_band(Bc, n, w, nl).astype(np.float32), Cd)
+    I, J = np.indices((n, n))
+    assert np.array_equal(dense[np.abs(I - J) <= w].reshape(-1), ref.reshape(-1))
+    assert not dense[np.abs(I - J) > w].any()
+
+
+@pytest.mark.parametrize("N,n", [(1, 4), (7, 6), (300, 9)])
+def test_struct_moment_against_dense_moments(oracle, N, n):
+    X = W.normal(230, N * n).reshape(N, n)
+    tol = dict(rtol=1e-12, atol=1e-12)
+    # the symmetric unique sets: the C oracle's entry-wise and dense moments
+    got3 = oracle.struct_moment(X, (n,) * 3, lambda i, j, k: i <= j <= k)
+    assert np.allclose(got3, oracle.moment3_entries(X, oracle.list_sym3(n)), **tol)
+    got2 = oracle.struct_moment(X, (n, n), lambda i, j: i <= j)
+    assert np.allclose(got2, oracle.moment2_dense(X)[np.triu_indices(n)], **tol)
+    if n <= 6:
+        got4 = oracle.struct_moment(X, (n,) * 4, lambda i, j, k, l: i <= j <= k <= l)
+        assert np.allclose(got4, oracle.moment4_entries(X, oracle.list_sym4(n)), **tol)
+    # structures only a descriptor gives: the dense moment read at the listed positions
+    S3, S2 = oracle.moment3_dense(X), oracle.moment2_dense(X)
+    for pred in (lambda i, j, k: i <= j <= k <= i + 2, lambda i, j, k: i == j == k):
+        idx = oracle.struct_enumerate((n,) * 3, pred).astype(np.int64)
+        assert np.allclose(oracle.struct_moment(X, (n,) * 3, pred), S3[idx[:, 0], idx[:, 1], idx[:, 2]], **tol)
+    for pred in (lambda i, j: i <= j <= i + 3, lambda i, j: True):
+        idx = oracle.struct_enumerate((n, n), pred).astype(np.int64)
+        assert np.allclose(oracle.struct_moment(X, (n, n), pred), S2[idx[:, 0], idx[:, 1]], **tol)
+    # independent of the C oracle altogether
+    X64 = X.astype(np.float64)
+    idx = oracle.struct_enumerate((n,) * 3, lambda i, j, k: i <= j <= k <= i + 2).astype(np.int64)
+    ein = np.einsum("si,sj,sk->ijk", X64, X64, X64)[idx[:, 0], idx[:, 1], idx[:, 2]]
+    assert np.allclose(oracle.struct_moment(X, (n,) * 3, lambda i, j, k: i <= j <= k <= i + 2), ein, **tol)
