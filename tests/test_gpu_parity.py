@@ -638,14 +638,16 @@ def test_moment3_infinite_sample(st, oracle, N, n, c):
 @pytest.mark.parametrize("n,i", [(300, 7), (1000, 998), (4100, 2000), (8192, 8190)])
 def test_batax_infinite_entry(st, oracle, n, i):
     """The last entry of packed row i is infinite: the next row's leading 16-byte group starts before that row
-    and reads it, so it must be dropped by selection, never by a multiplication with zero."""
+    and reads it, so it must be dropped by selection, never by a multiplication with zero.  t_i is infinite,
+    so y_j is infinite for j >= i; for j < i the dense definition multiplies the structural zero A(i,j) by the
+    infinite t_i, which is NaN in IEEE arithmetic -- in the definition and in the kernel alike."""
     say("batax with an infinite entry n=%d row %d" % (n, i))
     Ap = W.uniform(473, oracle.count_sym2(n)).copy()
     x = W.uniform(474, n)
     row_end = sum(n - a for a in range(i + 1)) - 1          # position of A(i, n-1)
     Ap[row_end] = np.inf
     ref = oracle.batax_utri(Ap, x, 0.5)
-    assert np.isinf(ref).sum() == n - i and not np.isnan(ref).any()
+    assert np.isinf(ref[i:]).all() and np.isnan(ref[:i]).all()
     inf_pattern_matches(st.batax_utri(dev(Ap), dev(x), 0.5).cpu().numpy(), ref)
 
 
