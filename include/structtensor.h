@@ -131,6 +131,19 @@ st_status st_mttkrp_sym3(const float *Tc, const float *B, float *M, int n, int R
 st_status st_batax_utri(const float *Ap, const float *x, float *y, int n, float beta,
                         void *ws, size_t ws_bytes, void *stream);
 
+/* st_batax_utri for callers that cannot allocate device memory or pass a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments, same kernels and bit-identical results;
+ * the per-workgroup partial results go to a static device array of the library
+ * (8 MiB per GPU, held until the process ends) instead of `ws`, and the call
+ * allocates nothing.  n <= st_batax_utri_noalloc_max_n() = 8192
+ * (ST_ERR_UNSUPPORTED beyond).  All calls on one GPU share that array: calls
+ * that overlap in time on the same GPU (different streams or threads) race and
+ * give undefined results; calls ordered on one stream are fine. */
+int st_batax_utri_noalloc_max_n(void);
+st_status st_batax_utri_noalloc(const float *Ap, const float *x, float *y, int n, float beta,
+                                void *stream);
+
 /* Tensor-times-matrix along mode 3 of a band tensor:
  *     Y(i,j,r) = sum_l T(i,j,l) * U(l,r)   for |i-j| <= w, zero elsewhere
  * (kernel table, TTM row  A(i,j,k) := B(i,j,l) * C(k,l)  with U(l,r) =

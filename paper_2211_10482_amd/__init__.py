@@ -28,6 +28,7 @@ from .binding import (  # noqa: F401
     count_sym4,
     expand_sym,
     batax_utri,
+    batax_utri_noalloc,
     lib,
     moment2_sym,
     moment3_sym,

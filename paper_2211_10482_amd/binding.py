@@ -49,6 +49,8 @@ SIGNATURES = {
     "st_moment4_sym_workspace": (_SZ, [_I64, _I32]),
     "st_mttkrp_sym3": (_I32, [_P, _P, _P, _I32, _I32, _P, _SZ, _P]),
     "st_batax_utri": (_I32, [_P, _P, _P, _I32, _F, _P, _SZ, _P]),
+    "st_batax_utri_noalloc_max_n": (_I32, []),
+    "st_batax_utri_noalloc": (_I32, [_P, _P, _P, _I32, _F, _P]),
     "st_ttm_band": (_I32, [_P, _P, _P, _I32, _I32, _I32, _I32, _P, _SZ, _P]),
     "st_moment3_sym": (_I32, [_P, _I64, _I32, _P, _I32, _P, _SZ, _P]),
     "st_moment2_sym": (_I32, [_P, _I64, _I32, _P, _I32, _P, _SZ, _P]),
@@ -276,6 +278,17 @@ def batax_utri(Ap, x, beta, y=None, ws=None):
     ws, pws, wsb = _workspace(workspace_bytes("batax_utri", n=n), x, ws)
     _check(lib().st_batax_utri(_dev_f32(Ap, "Ap"), _dev_f32(x, "x"), _dev_f32(y, "y"), n, float(beta), pws,
                                wsb, _stream()), "st_batax_utri")
+    return y
+
+
+def batax_utri_noalloc(Ap, x, beta, y):
+    """st_batax_utri through the library's static scratch array: the call allocates nothing, so the caller
+    passes the output as well."""
+    n = x.numel()
+    _expect(Ap, count_sym2(n), "Ap")
+    _expect(y, n, "y")
+    _check(lib().st_batax_utri_noalloc(_dev_f32(Ap, "Ap"), _dev_f32(x, "x"), _dev_f32(y, "y"), n, float(beta),
+                                       _stream()), "st_batax_utri_noalloc")
     return y
 
 

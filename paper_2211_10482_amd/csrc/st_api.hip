@@ -262,6 +262,19 @@ st_status st_batax_utri(const float *Ap, const float *x, float *y, int n, float 
     return launch_batax(Ap, x, y, n, beta, ws, (hipStream_t)stream);
 }
 
+int st_batax_utri_noalloc_max_n(void) { return batax_static_max_n(); }
+
+st_status st_batax_utri_noalloc(const float *Ap, const float *x, float *y, int n, float beta, void *stream)
+{
+    if (!Ap || !x || !y) return ST_ERR_NULL;
+    if (n < 1) return ST_ERR_SHAPE;
+    if (n > batax_static_max_n()) return ST_ERR_UNSUPPORTED;   /* the library's static scratch array ends there */
+    if (!aligned16(Ap) || !aligned16(x) || !aligned16(y)) return ST_ERR_ALIGN;
+    size_t ab = (size_t)count_sym2<i64>(n) * 4, vb = (size_t)n * 4;
+    if (overlap(y, vb, Ap, ab) || overlap(y, vb, x, vb)) return ST_ERR_SHAPE;
+    return launch_batax_static(Ap, x, y, n, beta, (hipStream_t)stream);
+}
+
 st_status st_ttm_band(const float *Tc, const float *U, float *Yc, int n, int w, int nl, int R,
                       void *ws, size_t ws_bytes, void *stream)
 {

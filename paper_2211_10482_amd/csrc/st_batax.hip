@@ -22,6 +22,8 @@
 //
 // General path (larger n): two passes (t = A x, one wave per row; then y = beta A^T t in 64 row slices
 // whose partials are added in a fixed order).
+#include <mutex>
+
 #include "st_common.h"
 #include "st_index.h"
 
@@ -328,6 +330,39 @@ st_status launch_batax(const float *Ap, const float *x, float *y, int n, float b
     if (hipGetLastError() != hipSuccess) return ST_ERR_LAUNCH;
     hipLaunchKernelGGL(batax_aty_reduce_kernel, dim3((un + 255u) / 256u), dim3(256), 0, s, wsf + npad, y, un, npad, beta);
     return launch_status();
+}
+
+// ---- the same computation for callers that cannot allocate ------------------------------------------
+// The per-workgroup partial results live in a file-scope device array instead of a caller workspace.  The
+// array's name is only a host-side handle: its device address is looked up once per device (each GPU holds
+// its own copy at its own address) and that address is what the kernels receive, exactly as they receive
+// the caller's workspace in launch_batax.  Every call on a GPU uses the same array, so two calls that
+// overlap in time on one GPU race; nothing in it has to start at zero (every word a call reads, it has
+// written before).
+constexpr int NMAX_STATIC = 8192;
+constexpr size_t SCRATCH_BYTES = (size_t)GMAX * NMAX_STATIC * sizeof(float);        // 8 MiB
+static __device__ __align__(256) unsigned char scratch[SCRATCH_BYTES];
+
+int batax_static_max_n() { return NMAX_STATIC; }
+
+st_status launch_batax_static(const float *Ap, const float *x, float *y, int n, float beta, hipStream_t s)
+{
+    static std::mutex mu;
+    static void *scratch_of_device[64] = {nullptr};
+    if (n < 1 || n > NMAX_STATIC || batax_workspace(n) > SCRATCH_BYTES) return ST_ERR_UNSUPPORTED;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return ST_ERR_LAUNCH;
+    void *ptr = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(mu);
+        if (scratch_of_device[dev] == nullptr) {
+            void *p = nullptr;
+            if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return ST_ERR_LAUNCH;
+            scratch_of_device[dev] = p;
+        }
+        ptr = scratch_of_device[dev];
+    }
+    return launch_batax(Ap, x, y, n, beta, ptr, s);
 }
 
 }  // namespace st

@@ -56,6 +56,10 @@ size_t batax_workspace(int n);
 st_status launch_batax(const float *Ap, const float *x, float *y, int n, float beta, void *ws,
                        hipStream_t s);
 
+// partial results in a static device array of the library (for callers that cannot allocate)
+int batax_static_max_n();
+st_status launch_batax_static(const float *Ap, const float *x, float *y, int n, float beta, hipStream_t s);
+
 size_t ttm_workspace(int n, int w, int nl, int R);
 st_status launch_ttm(const float *Tc, const float *U, float *Yc, int64_t rows, int nl, int R,
                      void *ws, hipStream_t s);

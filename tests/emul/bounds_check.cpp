@@ -69,6 +69,8 @@ int main(int argc, char **argv)
     float *Ap = fbuf(cnt), *x = fbuf(n), *y = fbuf(n);
     void *ws = malloc(wsb ? wsb : 1);
     rc = st::launch_batax(Ap, x, y, n, 0.5f, ws, nullptr);
+    if (rc == 0 && n <= st::batax_static_max_n())      // the same kernels on the library's static scratch array
+        rc = st::launch_batax_static(Ap, x, y, n, 0.5f, nullptr);
     free(Ap); free(x); free(y); free(ws);
 #elif defined(CHECK_TTM)
     const long rows = a[0];

@@ -24,6 +24,7 @@
 #define __launch_bounds__(...)
 #define __restrict__
 #define HIP_SYMBOL(x) x
+#define __align__(n) __attribute__((aligned(n)))
 
 struct dim3 {
     unsigned x, y, z;
@@ -63,6 +64,7 @@ static inline hipError_t hipMemcpyAsync(void *dst, const void *src, size_t bytes
     return hipSuccess;
 }
 static inline hipError_t hipGetLastError() { return hipSuccess; }
+static inline hipError_t hipGetSymbolAddress(void **p, const void *symbol) { *p = const_cast<void *>(symbol); return hipSuccess; }
 static inline hipError_t hipFuncSetAttribute(const void *, int, int) { return hipSuccess; }
 static inline hipError_t hipGetDevice(int *d) { *d = 0; return hipSuccess; }
 static inline hipError_t hipDeviceGetAttribute(int *v, int attr, int)
