@@ -536,7 +536,7 @@ class Descriptor:
         nl, R = _matrix(U, "U")
         if nl != self.dims[-1]:
             raise ValueError("U must have as many rows as the last extent of the descriptor")
-        _expect(Bc, self.runs * nl, "Bc", at_least=True)
+        _expect(Bc, self.count, "Bc", at_least=True)      # = runs * nl when the last variable is free (else the library refuses)
         if Ac is None:
             Ac = torch.empty((max(self.runs, 1), R), dtype=torch.float32, device=U.device)
         _expect(Ac, self.runs * R, "Ac", at_least=True)

@@ -369,6 +369,161 @@ __global__ __launch_bounds__(TW * 64) void ttm_splitk_kernel(const float *__rest
     }
 }
 
+// ---- one-shot kernel: a few row tiles per workgroup -------------------------------------------------------
+// With so few rows (the band workload: 540 row tiles on 256 CUs) a call is a few microseconds of memory
+// latency around a few microseconds of MFMA work: everything is requested at once, no wave waits for
+// another before its last MFMA, and the MFMA work is dealt evenly.
+//   * Work: a workgroup owns FULL row tiles b, b+G, .. and, when the tile count is not a multiple of G,
+//     single COLUMN tiles of the left-over row tiles (unit q = b + G e is column tile q % CT of row tile
+//     full*G + q / CT): the left-over tiles are dealt in quarters, so no CU carries a whole tile more than
+//     another (540 tiles on 256 CUs: 2.25 tiles at most instead of 3).
+//   * Split of the l range over the W waves of the workgroup (W = 16, or nl/16 when that is less): wave w
+//     owns l in [LW w, LW (w+1)), LW = nl / W, for ALL columns.  Its slice of U is LW x R floats, which it
+//     keeps in REGISTERS as MFMA B operands, loaded straight from L2 with CT-float loads (the interleaved
+//     column mapping of the persistent kernel: column tile j holds the columns CT n + j); its slice of the
+//     rows of a tile is LW consecutive floats per row, 16-byte loads straight into A-operand registers.
+//     Nothing is staged, there is no barrier in front of the MFMAs, every byte is requested once.
+//   * The W partial results of a tile meet in LDS at the end and are added in wave order (fixed), one
+//     output value per thread.
+template <int NS, int CT, int FULL, bool EX>
+__global__ __launch_bounds__((NS >= 4 ? 16 : 4 * NS) * 64) void ttm_oneshot_kernel(const float *__restrict__ Tc,
+                                                             const float *__restrict__ U, float *__restrict__ Yc,
+                                                             u32 rows)
+{
+    extern __shared__ float lds[];
+    constexpr u32 nl = 64u * NS, R = 16u * CT, W = NS >= 4 ? 16u : 4u * NS, LW = nl / W, SPW = LW / 16u;
+    constexpr u32 SLOTF = W * CT * 256u;                 // floats of one exchange buffer: [W][CT][64 lanes][4]
+    constexpr int TT = FULL + (EX ? 1 : 0);              // tile slots: FULL whole row tiles, then one column-tile unit
+    const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const u32 lrow = lane & 15u, lq = lane >> 4;
+    const u32 rtiles = (rows + 15u) / 16u, G = gridDim.x;
+    // the column-tile unit of this workgroup: column tile xc of row tile xrt (xrt >= rtiles: none)
+    const u32 xrt = FULL * G + blockIdx.x / CT, xc = blockIdx.x % CT;
+
+    // B operands: MFMA t of step s, lane (k = lane/16, n = lane%16), column tile c: U(l, CT n + c), l = LW w + 16 s + 4 k + t
+    cols<CT> u[SPW][4];
+    {
+        const float *up = U + (size_t)(wave * LW + 4u * lq) * R + CT * lrow;
+#pragma unroll
+        for (u32 s = 0; s < SPW; ++s)
+#pragma unroll
+            for (u32 t = 0; t < 4; ++t) u[s][t] = load_cols<CT>(up + (size_t)(16u * s + t) * R);
+    }
+    // A operands: lane (row = lane%16, k = lane/16) takes T(row, LW w + 16 s + 4 k .. +3)
+    float4 a[TT][SPW];
+#pragma unroll
+    for (int t = 0; t < TT; ++t) {
+        const u32 rt = t < FULL ? blockIdx.x + G * (u32)t : xrt;
+        const u32 grow = min(rt * 16u + lrow, rows - 1u);            // clamp: rows past the end are never stored
+        const float4 *ap = reinterpret_cast<const float4 *>(Tc + (size_t)grow * nl + wave * LW) + lq;
+#pragma unroll
+        for (u32 s = 0; s < SPW; ++s) a[t][s] = ap[4u * s];
+    }
+    // all MFMAs first, slot after slot as the rows arrive (each slot has an exchange buffer of its own), then ONE
+    // barrier, then the additions: no wave waits for another before its last MFMA
+#pragma unroll
+    for (int t = 0; t < TT; ++t) {
+        float *buf = lds + (size_t)t * SLOTF;
+        if (t < FULL) {
+            f32x4 acc[CT];
+#pragma unroll
+            for (int c = 0; c < CT; ++c) acc[c] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (u32 s = 0; s < SPW; ++s) {
+                const float av[4] = {a[t][s].x, a[t][s].y, a[t][s].z, a[t][s].w};
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+#pragma unroll
+                    for (int c = 0; c < CT; ++c)
+                        acc[c] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[k], u[s][k].v[c], acc[c], 0, 0, 0);
+            }
+#pragma unroll
+            for (int c = 0; c < CT; ++c)
+                *reinterpret_cast<f32x4 *>(buf + ((size_t)(wave * CT + (u32)c) * 64u + lane) * 4u) = acc[c];
+        } else if (xrt < rtiles) {                       // workgroup-uniform: one column tile, chosen by selects
+            f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (u32 s = 0; s < SPW; ++s) {
+                const float av[4] = {a[t][s].x, a[t][s].y, a[t][s].z, a[t][s].w};
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    float b = u[s][k].v[0];
+#pragma unroll
+                    for (int c = 1; c < CT; ++c) b = xc == (u32)c ? u[s][k].v[c] : b;
+                    acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av[k], b, acc, 0, 0, 0);
+                }
+            }
+            *reinterpret_cast<f32x4 *>(buf + ((size_t)wave * 64u + lane) * 4u) = acc;     // [W][64 lanes][4]
+        }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int t = 0; t < TT; ++t) {
+        const float *buf = lds + (size_t)t * SLOTF;
+        const bool whole = t < FULL;
+        const u32 rt = whole ? blockIdx.x + G * (u32)t : xrt;
+        if (rt >= rtiles) continue;
+        // one output value per thread and pass, the W partial results added in wave order; value j of a
+        // column tile c is element v = j % 4 of lane j / 4: row 4 (lane/16) + v, column CT (lane%16) + c
+#pragma unroll 1
+        for (u32 j = tid; j < (whole ? CT : 1u) * 256u; j += W * 64u) {
+            const u32 c = whole ? j >> 8 : xc, jl = j & 255u, ln = jl >> 2, v = jl & 3u;
+            const u32 wstride = whole ? CT * 256u : 256u, off = whole ? c * 256u + jl : jl;
+            float y = 0.f;
+#pragma unroll
+            for (u32 w = 0; w < W; ++w) y += buf[(size_t)w * wstride + off];
+            const u32 row = rt * 16u + 4u * (ln >> 4) + v;
+            if (row < rows) Yc[(size_t)row * R + CT * (ln & 15u) + c] = y;
+        }
+    }
+}
+
+constexpr u32 ONESHOT_FULL = 2;    // whole row tiles per workgroup the one-shot kernel is built for (+ one column-tile unit)
+
+// whole row tiles per workgroup, and whether the left-over tiles, dealt as single column tiles, fit one unit per
+// workgroup; ok = false when the shape needs more than the kernel is built for
+static inline void oneshot_split(u32 rtiles, u32 grid, u32 CT, u32 &full, bool &extra, bool &ok)
+{
+    full = rtiles / grid;
+    const u32 rem = rtiles - full * grid;
+    extra = rem > 0;
+    ok = full <= ONESHOT_FULL && rem * CT <= grid && full + (extra ? 1u : 0u) >= 1u;
+}
+
+template <int NS, int CT>
+static bool launch_oneshot_tt(u32 full, bool extra, u32 grid, hipStream_t s, const float *Tc, const float *U, float *Yc,
+                              u32 rows)
+{
+    constexpr u32 W = NS >= 4 ? 16u : 4u * NS;
+#define ST_TTM_ONESHOT(F, X)                                                                               \
+    {                                                                                                      \
+        const size_t lds_bytes = (size_t)F * W * CT * 1024u + (X ? W * 1024u : 0u);   /* one exchange buffer per slot */ \
+        if (!allow_dynamic_lds(reinterpret_cast<const void *>(ttm_oneshot_kernel<NS, CT, F, X>), 160 * 1024)) return false; \
+        hipLaunchKernelGGL((ttm_oneshot_kernel<NS, CT, F, X>), dim3(grid), dim3(W * 64u), lds_bytes, s, Tc, U, Yc, rows); \
+        return true;                                                                                       \
+    }
+    if (full == 0 && extra) ST_TTM_ONESHOT(0, true)
+    if (full == 1 && !extra) ST_TTM_ONESHOT(1, false)
+    if (full == 1 && extra) ST_TTM_ONESHOT(1, true)
+    if (full == 2 && !extra) ST_TTM_ONESHOT(2, false)
+    if (full == 2 && extra) ST_TTM_ONESHOT(2, true)
+#undef ST_TTM_ONESHOT
+    return false;
+}
+
+template <int NS>
+static bool launch_oneshot_ct(int CT, u32 full, bool extra, u32 grid, hipStream_t s, const float *Tc, const float *U,
+                              float *Yc, u32 rows)
+{
+    switch (CT) {
+    case 1: return launch_oneshot_tt<NS, 1>(full, extra, grid, s, Tc, U, Yc, rows);
+    case 2: return launch_oneshot_tt<NS, 2>(full, extra, grid, s, Tc, U, Yc, rows);
+    case 3: return launch_oneshot_tt<NS, 3>(full, extra, grid, s, Tc, U, Yc, rows);
+    case 4: return launch_oneshot_tt<NS, 4>(full, extra, grid, s, Tc, U, Yc, rows);
+    }
+    return false;
+}
+
 template <int NS>
 static bool launch_splitk_ct(int CT, u32 grid, size_t lds_bytes, hipStream_t s, const float *Tc, const float *U,
                              float *Yc, u32 rows)
@@ -431,8 +586,20 @@ st_status launch_ttm(const float *Tc, const float *U, float *Yc, int64_t rows, i
         const u32 rtiles = (u32)((rows + 15) / 16);
         u32 grid = (u32)num_cus();
         if (grid > rtiles) grid = rtiles;
-        const size_t lds_bytes = (size_t)nl * R * 4u + (size_t)8u * (R / 16u) * 1024u;   // U + exchange area
         bool ok = false;
+        u32 full = 0;
+        bool extra = false, fits = false;
+        oneshot_split(rtiles, grid, (u32)R / 16u, full, extra, fits);
+        if (fits) {                                      // a few row tiles per CU: everything in one round
+            switch (nl / 64) {
+            case 1: ok = launch_oneshot_ct<1>(R / 16, full, extra, grid, s, Tc, U, Yc, (u32)rows); break;
+            case 2: ok = launch_oneshot_ct<2>(R / 16, full, extra, grid, s, Tc, U, Yc, (u32)rows); break;
+            case 4: ok = launch_oneshot_ct<4>(R / 16, full, extra, grid, s, Tc, U, Yc, (u32)rows); break;
+            case 8: ok = launch_oneshot_ct<8>(R / 16, full, extra, grid, s, Tc, U, Yc, (u32)rows); break;
+            }
+            return ok ? launch_status() : ST_ERR_LAUNCH;
+        }
+        const size_t lds_bytes = (size_t)nl * R * 4u + (size_t)8u * (R / 16u) * 1024u;   // U + exchange area
         switch (nl / 64) {
         case 1: ok = launch_splitk_ct<1>(R / 16, grid, lds_bytes, s, Tc, U, Yc, (u32)rows); break;
         case 2: ok = launch_splitk_ct<2>(R / 16, grid, lds_bytes, s, Tc, U, Yc, (u32)rows); break;

@@ -203,7 +203,10 @@ def test_batax_full(st, oracle):
                                       (30, 2, 1040, 256), (20, 3, 16, 272), (600, 14, 128, 48),
                                       (100, 5, 256, 16), (70, 1, 512, 32), (700, 20, 64, 16),
                                       (1100, 9, 512, 64), (90, 6, 500, 50), (64, 3, 130, 250), (50, 2, 33, 17),
-                                      (40, 1, 100, 300)])
+                                      (40, 1, 100, 300),
+                                      # one to three row tiles per CU (one-shot kernel), every l-range / column count
+                                      (300, 3, 128, 48), (400, 10, 256, 32), (50, 2, 64, 16), (700, 8, 512, 64),
+                                      (257, 7, 512, 16), (130, 20, 256, 64), (600, 9, 64, 48), (723, 8, 512, 64)])
 def test_ttm_small(st, oracle, n, w, nl, R):
     say("ttm n=%d w=%d nl=%d R=%d" % (n, w, nl, R))
     nb = oracle.count_band(n, w)

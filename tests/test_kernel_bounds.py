@@ -31,7 +31,10 @@ CASES = {
     # (more than 16384 rows: the streaming split-K kernel)
     "TTM": [(8632, 512, 64), (16590, 128, 48), (1090, 256, 16), (208, 512, 32), (1, 64, 16), (777, 48, 32),
             (50, 7, 5), (33, 16, 256), (16385, 512, 64), (40001, 64, 16), (33000, 256, 48), (100, 500, 50),
-            (10, 1, 1), (300, 130, 250), (40, 33, 300)],
+            (10, 1, 1), (300, 130, 250), (40, 33, 300),
+            # at most three row tiles per CU: the one-shot kernel (all NS, several CT, ragged last tile)
+            (1089, 64, 64), (2088, 128, 48), (8290, 256, 32), (244, 64, 16), (11828, 512, 64), (12288, 512, 64),
+            (4097, 128, 16), (12289, 512, 64)],
     # moment3: N n accumulate  (n = 64 is the MFMA path, others the plain path)
     # (n <= 40 and 64 < n <= 256: the tile path; 40 < n <= 64: the MFMA path; larger n: the plain path)
     "MOMENT3": [(5000, 64, 0), (4097, 64, 1), (63, 64, 0), (100000, 64, 0), (1000, 20, 0), (3, 5, 1),
