@@ -8,6 +8,10 @@ accumulation (N=2e6, n=64) followed by the expansion of its result.  Inputs are
 resident in HBM before the timed region.  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline]
+
+Per-call figures are MEDIANS of event pairs on the launch stream over the timed steps (the mean is kept beside
+them); `kernels[*].kernel_us` and `kernels[*].traffic` come from the committed rocprofv3 summary
+profiles/bench_step_counters.txt and are null once the kernel's source has changed since it was taken.
 """
 from __future__ import annotations
 
@@ -63,75 +67,128 @@ def workloads():
     return out
 
 
-def recorded_traffic():
-    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter summary, or None when
-    the kernel source has changed since the counters were taken."""
+# entry point of the step -> source file of its kernels (for the hash guard of the recorded counters)
+SOURCES = {
+    "mttkrp_sym3_n64_R16": "st_mttkrp.hip", "batax_utri_n8192": "st_batax.hip", "ttm_band_n512_w8_R64": "st_ttm.hip",
+    "mttkrp_sym3_n512_R64": "st_mttkrp.hip", "moment3_sym_N2e6_n64": "st_moment3.hip", "expand_sym_n64": "st_expand.hip",
+}
+
+
+def recorded_counters():
+    """Per call of the step: kernel time (sum of the average durations of its kernels, rocprofv3 kernel trace)
+    and HBM bytes (FETCH_SIZE + WRITE_SIZE, scaled by the copy probe) from the committed summary -- or None for
+    a call whose kernel source has changed since the counters were taken."""
     import hashlib
-    rec = os.path.join(ROOT, "profiles", "moment3_sym_N2e6_n64_traffic.txt")
-    src = os.path.join(ROOT, "paper_2211_10482_amd", "csrc", "st_moment3.hip")
+    rec = os.path.join(ROOT, "profiles", "bench_step_counters.txt")
+    out = {}
     try:
-        kv = {}
         with open(rec) as f:
             for line in f:
                 parts = line.split()
-                if len(parts) == 2 and not line.startswith("#"):
-                    kv[parts[0]] = parts[1]
-        with open(src, "rb") as f:
-            sha = hashlib.sha256(f.read()).hexdigest()
-        if kv.get("kernel_source_sha256") != sha:
-            return None
-        return float(kv["traffic_bytes"])
-    except (OSError, KeyError, ValueError):
-        return None
+                if len(parts) != 6 or line.startswith("#"):
+                    continue
+                call, src, sha, kus, fetch, write = parts
+                with open(os.path.join(ROOT, "paper_2211_10482_amd", "csrc", src), "rb") as g:
+                    if hashlib.sha256(g.read()).hexdigest() != sha:
+                        continue
+                out[call] = dict(kernel_us=float(kus), traffic=float(fetch) + float(write))
+    except (OSError, ValueError):
+        pass
+    return out
 
 
-def cpu_baseline(inputs):
-    """The oracle as it stands, timed on a bounded sample of the same step."""
+def cpu_model():
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def errors(got, ref):
+    """Norm-wise error max|got-ref| / max|ref| and floored element-wise error max |got-ref| / max(|ref|, 1e-3 max|ref|)."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    scale = float(np.abs(ref).max())
+    d = np.abs(got - ref)
+    if scale == 0.0:
+        return float(d.max()), float(d.max())
+    return float(d.max() / scale), float((d / np.maximum(np.abs(ref), 1e-3 * scale)).max())
+
+
+def cpu_baseline(inputs, gpu_out):
+    """The oracle as it stands, timed on a bounded sample of the same step: on all host cores and on ONE
+    thread (the paper's protocol, "Experimental Setup"); its results are also what `parity` compares the GPU
+    outputs of the timed step with."""
     import oracle
-    t_est = 0.0
-    parts = []
 
     def timed(f):
         t0 = time.perf_counter()
-        f()
-        return time.perf_counter() - t0
+        r = f()
+        return r, time.perf_counter() - t0
 
     Tc1, B1 = inputs["c1"]
-    t = timed(lambda: oracle.mttkrp_sym3(Tc1, B1))
-    t_est += t
-    parts.append("mttkrp n=64 full %.2fs" % t)
     Ap, x = inputs["c2"]
-    t = timed(lambda: oracle.batax_utri(Ap, x, 0.5))
-    t_est += t
-    parts.append("batax n=8192 full %.2fs" % t)
     Tc3, U = inputs["c3"]
-    t = timed(lambda: oracle.ttm_band(Tc3, U, 512, 8))
-    t_est += t
-    parts.append("ttm full %.2fs" % t)
     Tc4, B4 = inputs["c4"]
-    rows = np.arange(0, 512, dtype=np.int64)
-    t = timed(lambda: oracle.mttkrp_sym3(Tc4, B4, rows=rows))
-    t_est += t * (512 / rows.size)
-    parts.append("mttkrp n=512: %d of 512 rows %.2fs" % (rows.size, t))
     X = inputs["c5"]
-    ns = 250_000
-    t = timed(lambda: oracle.moment3_dense(X[:ns]))
-    t_est += t * (X.shape[0] / ns)
-    parts.append("moment3: %d of %d samples %.2fs" % (ns, X.shape[0], t))
     Sc = W.uniform(7, tet(64))
-    t = timed(lambda: oracle.expand_sym(Sc, 64, 3))
-    t_est += t
-    parts.append("expand full %.3fs" % t)
     total_flops = sum(w["flops"] for w in workloads().values())
-    return dict(value=total_flops / t_est / 1e9, unit="GFLOP/s", cores=oracle.num_threads(), kind="oracle",
-                sample="; ".join(parts) + "; scaled to one full step = %.1fs" % t_est)
+    legs, parity = {}, {}
+    all_cores = oracle.num_threads()
+    # (threads, rows of the n=512 MTTKRP, samples of the third moment): about 10-20 s of CPU work per leg
+    for label, threads, nrows, ns in (("all_cores", all_cores, 512, 250_000), ("one_thread", 1, 48, 24_000)):
+        oracle.set_num_threads(threads)
+        t_est, parts = 0.0, []
+        r1, t = timed(lambda: oracle.mttkrp_sym3(Tc1, B1))
+        t_est += t
+        parts.append("mttkrp n=64 full %.2fs" % t)
+        r2, t = timed(lambda: oracle.batax_utri(Ap, x, 0.5))
+        t_est += t
+        parts.append("batax n=8192 full %.2fs" % t)
+        r3, t = timed(lambda: oracle.ttm_band(Tc3, U, 512, 8))
+        t_est += t
+        parts.append("ttm full %.2fs" % t)
+        rows = np.linspace(0, 511, nrows).round().astype(np.int64) if nrows < 512 else np.arange(512, dtype=np.int64)
+        r4, t = timed(lambda: oracle.mttkrp_sym3(Tc4, B4, rows=rows))
+        t_est += t * (512 / rows.size)
+        parts.append("mttkrp n=512: %d of 512 rows %.2fs" % (rows.size, t))
+        r5, t = timed(lambda: oracle.moment3_dense(X[:ns]))
+        t_est += t * (X.shape[0] / ns)
+        parts.append("moment3: %d of %d samples %.2fs" % (ns, X.shape[0], t))
+        r6, t = timed(lambda: oracle.expand_sym(Sc, 64, 3))
+        t_est += t
+        parts.append("expand full %.3fs" % t)
+        legs[label] = dict(value=total_flops / t_est / 1e9, cores=threads,
+                           sample="; ".join(parts) + "; scaled to one full step = %.1fs" % t_est)
+        if label == "all_cores" and gpu_out is not None:
+            lst = oracle.list_sym3(64).astype(np.int64)
+            for name, got, ref in (("mttkrp_sym3_n64_R16", gpu_out["M1"], r1), ("batax_utri_n8192", gpu_out["y"], r2),
+                                   ("ttm_band_n512_w8_R64", gpu_out["Yc"], r3), ("mttkrp_sym3_n512_R64", gpu_out["M4"], r4),
+                                   ("moment3_sym_first_%d_samples_n64" % ns, gpu_out["moment3_sample"](ns),
+                                    r5[lst[:, 0], lst[:, 1], lst[:, 2]])):
+                e, ee = errors(got, ref)
+                parity[name] = dict(normwise=float("%.3e" % e), elementwise_floored=float("%.3e" % ee))
+            Sd = gpu_out["S"]
+            parity["expand_sym_n64"] = dict(bit_exact=bool(np.array_equal(
+                Sd.view(np.uint32), oracle.expand_sym(gpu_out["Sc"], 64, 3).view(np.uint32))))
+    oracle.set_num_threads(all_cores)
+    a = legs["all_cores"]
+    out = dict(value=a["value"], unit="GFLOP/s", cores=a["cores"], kind="oracle", sample=a["sample"],
+               cpu_model=cpu_model(),
+               one_thread=dict(value=legs["one_thread"]["value"], unit="GFLOP/s", cores=1,
+                               sample=legs["one_thread"]["sample"]))
+    return out, parity
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-next", action="store_true", help="skip the rows beyond the step (moment2, moment4, expand 4, kernel table)")
     ap.add_argument("--copy-probe", action="store_true",
@@ -244,16 +301,51 @@ def main():
         torch.cuda.synchronize()
         warm[name] = float(np.median([a.elapsed_time(b) for a, b in evs]))
 
+    # floors of the short calls: an empty launch, and a plain streaming read of the operand, in the launch shape
+    # of the kernel (event pairs like everything else; the kernel-trace durations are in profiles/)
+    floors = {}
+    sink = torch.zeros(16, **f32)
+    def timed_median(f, reps=30):
+        f()
+        torch.cuda.synchronize()
+        evs = []
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            f()
+            e1.record()
+            evs.append((e0, e1))
+        torch.cuda.synchronize()
+        return float(np.median([a.elapsed_time(b) for a, b in evs])) * 1e3
+    floors["empty_launch_256x1024_us"] = round(timed_median(lambda: st.probe_empty(256, 1024)), 2)
+    for tag, buf, shape in (("ttm_operand_17.7MB", Tc3, (256, 1024)), ("mttkrp_operand_90MB", Tc4, (4096, 256)),
+                            ("batax_operand_134MB", Ap, (8192, 256))):
+        copies = [buf] + [buf.clone() for _ in range(max(2, int(600e6 // (buf.numel() * 4))))]
+        k = [0]
+        def f(copies=copies, shape=shape):
+            k[0] += 1
+            st.probe_stream(copies[k[0] % len(copies)], shape[0], shape[1], sink)
+        floors["stream_read_%s_cold_%dx%d_us" % ((tag,) + shape)] = round(timed_median(f), 2)
+        del copies
+
     wl = workloads()
+    rec = recorded_counters()
     kernels = {}
     for name, _ in calls:
-        ms = float(np.mean([a.elapsed_time(b) for a, b in events[name]]))
+        t = np.array([a.elapsed_time(b) for a, b in events[name]])
+        ms, ms_mean = float(np.median(t)), float(t.mean())
         w = wl[name]
         gflops = w["flops"] / (ms * 1e-3) / 1e9
         gbs = w["bytes"] / (ms * 1e-3) / 1e9
-        frac = gbs / HBM_PEAK_GBS if w["bound"] == "hbm" else gflops / 1e3 / MFMA_FP32_PEAK_TFLOPS
-        kernels[name] = dict(ms=round(ms, 5), unique_gflops=round(gflops, 2), alg_gbs=round(gbs, 2),
-                             bound=w["bound"], frac=round(frac, 4), warm_ms=round(warm[name], 5))
+        peak = HBM_PEAK_GBS if w["bound"] == "hbm" else MFMA_FP32_PEAK_TFLOPS * 1e3
+        frac = (gbs if w["bound"] == "hbm" else gflops) / peak
+        r = rec.get(name)
+        kus = r["kernel_us"] if r else None
+        kfrac = ((w["bytes"] if w["bound"] == "hbm" else w["flops"]) / (kus * 1e-6) / 1e9 / peak) if kus else None
+        kernels[name] = dict(ms=round(ms, 5), ms_mean=round(ms_mean, 5), unique_gflops=round(gflops, 2),
+                             alg_gbs=round(gbs, 2), bound=w["bound"], frac=round(frac, 4), warm_ms=round(warm[name], 5),
+                             kernel_us=kus, frac_kernel_trace=round(kfrac, 4) if kfrac else None,
+                             alg_bytes=w["bytes"], traffic=r["traffic"] if r else None)
     total_flops = sum(w["flops"] for w in wl.values())
     value = total_flops / (ms_per_step * 1e-3) / 1e9
 
@@ -261,7 +353,10 @@ def main():
     dom_ms = kernels[dom]["ms"]
     achieved = wl[dom]["flops"] / (dom_ms * 1e-3) / 1e12
     roofline = dict(kernel=dom, bound="mfma", achieved=round(achieved, 3), peak=MFMA_FP32_PEAK_TFLOPS,
-                    unit="TFLOP/s", frac=round(achieved / MFMA_FP32_PEAK_TFLOPS, 4), traffic=recorded_traffic())
+                    unit="TFLOP/s", frac=round(achieved / MFMA_FP32_PEAK_TFLOPS, 4),
+                    frac_kernel_trace=kernels[dom]["frac_kernel_trace"], traffic=kernels[dom]["traffic"],
+                    timing="median of %d event pairs around the call (main kernel + its partial-sum kernel); "
+                           "frac_kernel_trace = the same flops over the rocprofv3 kernel durations in profiles/" % args.steps)
 
     # Rows beyond the step (order-2 and order-4 moments of the same samples, order-4 reconstruction): timed
     # on their own after the step, reported for information, not part of `value`.
@@ -417,11 +512,15 @@ def main():
                                "moment3_sym N=2e6 n=64 + expand_sym n=64"},
         "roofline": roofline,
         "kernels": kernels,
+        "floors": floors,
         "next_rows": next_rows,
     }
     if not args.no_cpu_baseline:
-        log("cpu baseline (oracle on a bounded sample) ...")
-        result["cpu_baseline"] = cpu_baseline(host)
+        log("cpu baseline (oracle on a bounded sample, all cores and one thread) and parity of the step's outputs ...")
+        gpu_out = dict(M1=M1.cpu().numpy(), y=y.cpu().numpy(), Yc=Yc.cpu().numpy(), M4=M4.cpu().numpy(),
+                       Sc=Sc.cpu().numpy(), S=S.cpu().numpy(),
+                       moment3_sample=lambda ns: st.moment3_sym(X[:ns]).cpu().numpy())
+        result["cpu_baseline"], result["parity"] = cpu_baseline(host, gpu_out)
     else:
         result["cpu_baseline"] = None
     print(json.dumps(result), flush=True)

@@ -345,6 +345,18 @@ st_status st_desc_moment(st_desc *desc, const void *table, const float *X, int64
  * ST_ERR_UNSUPPORTED when the last variable is bounded by the structure. */
 st_status st_desc_ttm(st_desc *desc, const float *Bc, const float *U, float *Ac, int R, void *stream);
 
+/* ---- measurement support (no computation) -----------------------------------
+ *
+ * The floors a short call is judged against: an empty launch of `grid`
+ * workgroups of `block` threads, and a plain streaming read of `bytes` bytes
+ * at DEVICE pointer `src` in that launch shape (16-byte loads, every byte
+ * once, at most 32 loads per thread: ST_ERR_UNSUPPORTED beyond; `sink` is a
+ * DEVICE float the kernel never writes in practice).  The benchmark times
+ * them beside the kernels so that a kernel time can be split into launch,
+ * memory and the rest. */
+st_status st_probe_empty(int grid, int block, void *stream);
+st_status st_probe_stream(const void *src, size_t bytes, int grid, int block, float *sink, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

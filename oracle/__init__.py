@@ -50,6 +50,7 @@ def lib():
             "so_moment4_entries": (None, [p, i64, i64, p, i64, p]),
             "so_expand_sym": (C.c_int, [p, i64, C.c_int, p]),
             "so_num_threads": (C.c_int, []),
+            "so_set_num_threads": (None, [C.c_int]),
         }
         for name, (res, args) in sig.items():
             f = getattr(_lib, name)
@@ -64,6 +65,11 @@ def _f32(a):
 
 def num_threads():
     return int(lib().so_num_threads())
+
+
+def set_num_threads(threads):
+    """Threads of the parallel loops from now on (results do not depend on it)."""
+    lib().so_set_num_threads(int(threads))
 
 
 # ---- enumeration ---------------------------------------------------------

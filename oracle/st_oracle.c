@@ -46,6 +46,17 @@ SO_API int so_num_threads(void)
 #endif
 }
 
+/* Sets the number of threads of the parallel loops (timing on one thread, the paper's protocol, beside all
+ * cores); no effect on any result: every output value is summed by one thread in a fixed order. */
+SO_API void so_set_num_threads(int threads)
+{
+#ifdef _OPENMP
+    if (threads >= 1) omp_set_num_threads(threads);
+#else
+    (void)threads;
+#endif
+}
+
 /* ------------------------------------------------------------------ */
 /* enumeration by counting                                             */
 /* ------------------------------------------------------------------ */

@@ -29,6 +29,8 @@ from .binding import (  # noqa: F401
     expand_sym,
     batax_utri,
     batax_utri_noalloc,
+    probe_empty,
+    probe_stream,
     lib,
     moment2_sym,
     moment3_sym,

@@ -79,6 +79,8 @@ SIGNATURES = {
     "st_desc_ttm": (_I32, [_P, _P, _P, _P, _I32, _P]),
     "st_desc_moment_workspace": (_SZ, [_P, _I64]),
     "st_desc_moment": (_I32, [_P, _P, _P, _I64, _P, _I32, _P, _SZ, _P]),
+    "st_probe_empty": (_I32, [_I32, _I32, _P]),
+    "st_probe_stream": (_I32, [_P, _SZ, _I32, _I32, _P, _P]),
     "st_covar_pr2_workspace": (_SZ, [_I64, _I32]),
     "st_covar_pr2": (_I32, [_P, _I64, _I32, _P, _P, _P, _I32, _P, _SZ, _P]),
 }
@@ -443,6 +445,16 @@ def expand_band(Tc, n, w, nl, T=None):
     _expect(T, n * n * nl, "T")
     _check(lib().st_expand_band(_dev_f32(Tc, "Tc"), _dev_f32(T, "T"), n, w, nl, _stream()), "st_expand_band")
     return T
+
+
+# ---- measurement support ----------------------------------------------------------------
+def probe_empty(grid, block):
+    _check(lib().st_probe_empty(int(grid), int(block), _stream()), "st_probe_empty")
+
+
+def probe_stream(src, grid, block, sink):
+    _check(lib().st_probe_stream(C.c_void_p(src.data_ptr()), src.numel() * src.element_size(), int(grid), int(block),
+                                 _dev_f32(sink, "sink"), _stream()), "st_probe_stream")
 
 
 # ---- descriptor-driven structures -------------------------------------------------------

@@ -10,7 +10,8 @@ CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libstructtensor_hip.so")
 SOURCES = ["st_api.hip", "st_expand.hip", "st_batax.hip", "st_ttm.hip", "st_moment3.hip", "st_mttkrp.hip",
-           "st_moment2.hip", "st_moment4.hip", "st_moment_mfma.hip", "st_covar_small.hip", "st_table.hip", "st_desc.hip"]
+           "st_moment2.hip", "st_moment4.hip", "st_moment_mfma.hip", "st_covar_small.hip", "st_table.hip", "st_desc.hip",
+           "st_probe.hip"]
 FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-fvisibility=hidden",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
