@@ -25,13 +25,24 @@
  *     aligned (ST_ERR_ALIGN otherwise); dense matrices are row-major;
  *   - the caller owns every buffer, including the workspace `ws` of at least
  *     st_<kernel>_workspace(...) bytes (may be NULL when that is 0);
- *     the library allocates no device memory and keeps no state between calls;
+ *     the library allocates no device memory and no result depends on an
+ *     earlier call.  What it does keep, per process and behind locks, are
+ *     host-side caches: the CU count and the dynamic-LDS limits it has raised
+ *     per device, the tile tables of the table-driven moment kernels (built
+ *     at first use, with a copy in pinned host memory), the compiled modules
+ *     of descriptors, and the address of the static scratch array of
+ *     st_batax_utri_noalloc;
  *   - inputs and outputs must not overlap;
  *   - work is enqueued on `stream` (a hipStream_t passed as void*, NULL =
- *     the default stream) and the call returns without synchronising;
+ *     the default stream) and the call returns without synchronising: every
+ *     entry point enqueues kernels only (the moment kernels for 64 < n <= 256
+ *     bring their tile table into the workspace with a small kernel that
+ *     reads the pinned copy);
  *   - arguments are validated on the host before anything is launched: on
- *     any status other than ST_OK nothing was launched and outputs are
- *     untouched;
+ *     ST_ERR_NULL / SHAPE / ALIGN / WORKSPACE / UNSUPPORTED nothing was
+ *     launched and outputs are untouched.  ST_ERR_LAUNCH means the HIP
+ *     runtime refused a launch: entry points that enqueue several kernels
+ *     may then have enqueued the earlier ones, and outputs are undefined;
  *   - results are deterministic: same inputs, same bits (no float atomics).
  */
 #ifndef STRUCTTENSOR_H
@@ -163,8 +174,8 @@ st_status st_ttm_band(const float *Tc, const float *U, float *Yc, int n, int w, 
  * it.  Raw sums: no 1/N, no centring.  N >= 0 (N = 0 zero-fills when
  * accumulate = 0), n >= 1.  The workspace can be large (64 < n <= 256: a tile
  * table and the partial sums of every sample slice, up to 2 GB; ask
- * st_moment3_sym_workspace); for those n the table is copied into it with
- * hipMemcpyAsync on `stream` at every call. */
+ * st_moment3_sym_workspace); for those n a small kernel copies the table
+ * into it at every call. */
 st_status st_moment3_sym(const float *X, int64_t N, int n, float *Sc, int accumulate,
                          void *ws, size_t ws_bytes, void *stream);
 
@@ -183,7 +194,7 @@ st_status st_moment2_sym(const float *X, int64_t N, int n, float *Sc, int accumu
  * (the M3 = vec(f (x) f) (x) vec(f (x) f) term of the same covariance: about 23 of
  * every 24 dense entries are redundant).  Arguments as for st_moment3_sym; Sc has
  * st_count_sym4(n) entries; n <= 256.  For n >= 56 the workspace holds a tile
- * table (copied in with hipMemcpyAsync at every call) and slice partials, up to
+ * table (copied in by a small kernel at every call) and slice partials, up to
  * about 2 GB. */
 st_status st_moment4_sym(const float *X, int64_t N, int n, float *Sc, int accumulate,
                          void *ws, size_t ws_bytes, void *stream);

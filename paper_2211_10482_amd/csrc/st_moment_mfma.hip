@@ -33,6 +33,7 @@
 // copied into the workspace): one code stream for all waves; per product two LDS reads and one
 // multiply.  Slice partials -> reduce kernel: keeps the positions above, adds the slices in
 // ascending order, sorts the indices and scatters through the closed-form rank.  No atomics.
+#include <cstring>
 #include <mutex>
 #include <vector>
 
@@ -61,6 +62,7 @@ __host__ __device__ __forceinline__ u32 mm_d(u32 sp) { return sp & 15u; }
 struct MMTable {
     std::vector<int> spec;     // [slots][MM_SPECS], slots = 8 * kinds
     u32 blocks = 0, kinds = 0;
+    int *pinned = nullptr;     // the same table in pinned, device-visible host memory (what a call's copy kernel reads)
 };
 static void mm_add(MMTable &t, const std::vector<int> &rows, const std::vector<int> &cols)
 {
@@ -147,15 +149,30 @@ static MMTable mm_build_table3(int G)
     t.spec.resize((size_t)t.kinds * MM_WAVES * MM_SPECS, 0);
     return t;
 }
-// one table per moment and G, built at first use and kept (the copies into workspaces read from it)
+// One table per moment and G, built at first use and kept for the life of the process, with a copy in pinned
+// host memory that every GPU can read: a call brings the table into its workspace with a small KERNEL that
+// reads that copy, so the call enqueues kernels only (nothing blocks the host, and a caller may capture it).
 static const MMTable &mm_table(int order, int G)
 {
     static std::mutex mu;
     static MMTable *cache[2][17] = {{nullptr}};
     std::lock_guard<std::mutex> lock(mu);
     MMTable *&slot = cache[order - 3][G];
-    if (!slot) slot = new MMTable(order == 3 ? mm_build_table3(G) : mm_build_table4(G));
+    if (!slot) {
+        slot = new MMTable(order == 3 ? mm_build_table3(G) : mm_build_table4(G));
+        void *host = nullptr;
+        const size_t bytes = slot->spec.size() * sizeof(int);
+        if (hipHostMalloc(&host, bytes ? bytes : sizeof(int), hipHostMallocPortable) == hipSuccess && host) {
+            memcpy(host, slot->spec.data(), bytes);
+            slot->pinned = static_cast<int *>(host);
+        }
+    }
     return *slot;
+}
+
+__global__ __launch_bounds__(256) void mm_table_copy_kernel(const int *__restrict__ src, int *__restrict__ dst, u32 count)
+{
+    for (u32 e = blockIdx.x * 256u + threadIdx.x; e < count; e += gridDim.x * 256u) dst[e] = src[e];
 }
 
 // Staging: a unit is (group g, 16 consecutive samples): lane (sample, quarter) loads X(s, 16g + 4*quarter ..+3)
@@ -538,9 +555,15 @@ st_status launch_moment_mfma(int order, const float *X, int64_t N, int n, float 
     const MMTable &tab = mm_table(order, (int)p.G);
     int *table = static_cast<int *>(ws);
     float *wsf = reinterpret_cast<float *>(static_cast<char *>(ws) + p.table_bytes);
-    // the table lives for the life of the process, so the copy may complete after this call returns
-    if (hipMemcpyAsync(table, tab.spec.data(), tab.spec.size() * sizeof(int), hipMemcpyHostToDevice, s) != hipSuccess)
-        return ST_ERR_LAUNCH;
+    // the table: pinned host memory -> workspace, by a kernel on the caller's stream
+    if (tab.pinned == nullptr) return ST_ERR_LAUNCH;
+    {
+        const u32 count = (u32)tab.spec.size();
+        u32 cb = (count + 255u) / 256u;
+        if (cb > 64u) cb = 64u;
+        if (cb > 0u) hipLaunchKernelGGL(mm_table_copy_kernel, dim3(cb), dim3(256), 0, s, tab.pinned, table, count);
+        if (hipGetLastError() != hipSuccess) return ST_ERR_LAUNCH;
+    }
     const dim3 grid(p.kinds * p.S), block(MM_THREADS);
     const size_t lds_bytes = (size_t)2u * (p.G + 1u) * p.steps * 64u * sizeof(float);
     const bool v4 = n % 4 == 0;

@@ -11,6 +11,7 @@
 #include <math.h>
 #include <stddef.h>
 #include <stdint.h>
+#include <stdlib.h>
 #include <string.h>
 #include <algorithm>
 
@@ -64,6 +65,8 @@ static inline hipError_t hipMemcpyAsync(void *dst, const void *src, size_t bytes
     return hipSuccess;
 }
 static inline hipError_t hipGetLastError() { return hipSuccess; }
+enum { hipHostMallocPortable = 1 };
+static inline hipError_t hipHostMalloc(void **p, size_t bytes, unsigned) { *p = malloc(bytes); return *p ? hipSuccess : 1; }
 static inline hipError_t hipGetSymbolAddress(void **p, const void *symbol) { *p = const_cast<void *>(symbol); return hipSuccess; }
 static inline hipError_t hipFuncSetAttribute(const void *, int, int) { return hipSuccess; }
 static inline hipError_t hipGetDevice(int *d) { *d = 0; return hipSuccess; }

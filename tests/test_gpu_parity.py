@@ -801,3 +801,31 @@ def test_table_full_sizes(st, oracle):
     got = st.expand_band(dev(Tb), cfg["n"], cfg["w"], cfg["nl"]).cpu().numpy()
     ref = oracle.dense_band(Tb, cfg["n"], cfg["w"], cfg["nl"]).astype(np.float32)
     assert np.array_equal(got.view(np.uint32), ref.view(np.uint32))
+
+
+# ------------------------------------------------------------ calls enqueue kernels only
+@pytest.mark.parametrize("order,n,N", [(3, 128, 3000), (4, 80, 600), (3, 64, 5000)])
+def test_moment_calls_can_be_captured(st, oracle, order, n, N):
+    """A call enqueues kernels only (the table-driven paths bring their tile table into the workspace with a
+    kernel), so it can be captured in a HIP graph: captured once, replayed three times on changing inputs with
+    eager work and synchronisations in between, every replay compared with the eager result."""
+    import torch
+    say("graph capture of moment%d n=%d" % (order, n))
+    f = st.moment3_sym if order == 3 else st.moment4_sym
+    count = st.count_sym3(n) if order == 3 else st.count_sym4(n)
+    X = dev(W.normal(481, N * n).reshape(N, n))
+    Sc = torch.empty(count, device="cuda")
+    ws = torch.empty(max(16, st.workspace_bytes("moment%d_sym" % order, N=N, n=n)), dtype=torch.uint8, device="cuda")
+    f(X, Sc=Sc, ws=ws)                                     # first use outside the capture (builds the table)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        f(X, Sc=Sc, ws=ws)
+    for rep in range(3):
+        X.copy_(dev(W.normal(482 + rep, N * n).reshape(N, n)))
+        want = f(X.clone()).clone()                        # eager, its own workspace and output
+        torch.cuda.synchronize()
+        Sc.fill_(float("nan"))
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(Sc, want), (order, n, rep)
