@@ -306,6 +306,9 @@ st_status st_expand_band(const float *Tc, float *T, int n, int w, int nl, void *
  * device by the caller, 16-byte aligned there) and compile on first use.
  * On a parse error st_desc_create still returns an object whose
  * st_desc_error() says what was wrong; destroy it like any other.
+ * A redundancy term whose condition holds for a stored entry is an error
+ * (ST_ERR_SHAPE): the unique set and the redundancy map must be disjoint
+ * (Property 1 of the semantics, T_U * T_R is empty).
  */
 typedef struct st_desc st_desc;
 st_status st_desc_create(const char *unique_set, const char *redundancy, const int64_t *dims, int ndims,
@@ -333,6 +336,33 @@ st_status st_desc_list(st_desc *desc, const void *table, int32_t *out, void *str
 st_status st_desc_thp(st_desc *desc, const void *table, const float *Bc, const float *C, float *Ac,
                       void *stream);
 st_status st_desc_expand(st_desc *desc, const void *table, const float *Tc, float *T, void *stream);
+
+/* Structure inference for an element-wise product  A(x) := M(x) * V(x)  of two
+ * structured operands of the same shape ("Structure Inference", general rule for
+ * products):  A_U = M_U*V_U + M_U*V_R + M_R*V_U,  A_R = M_R*V_R, followed by the
+ * logical simplification: summands whose comparisons contradict each other are
+ * empty and drop out.  The result is a new descriptor (packed layout = its own
+ * derived nest).  E.g. upper-triangular times symmetric gives the upper
+ * triangle with no redundancy (the paper's UHS walk-through); symmetric times
+ * symmetric stays symmetric.  ST_ERR_UNSUPPORTED when more than one summand of
+ * A_U survives (a descriptor holds one product of comparisons), for 'sort'
+ * maps of order above 2, or when two surviving redundancy terms disagree.
+ * The object is returned on failure too (st_desc_error says why).
+ * Destroy it like any other descriptor. */
+st_status st_desc_product(const st_desc *m, const st_desc *v, st_desc **out);
+
+/* Values of a structured tensor at a LIST of dense positions, times an
+ * optional factor per position:
+ *     out[p] = (scale ? scale[p] : 1) * T(idx[p][0], .., idx[p][order-1])
+ * with T(x) the stored value on the unique set, the value at the unique index
+ * the redundancy map names elsewhere, 0 where neither applies or x lies
+ * outside the dense extents (Property 5, evaluated only where asked).  idx is
+ * DEVICE int32 [count][order] (e.g. st_desc_list of a product descriptor), Tc
+ * the packed operand of `desc`, scale NULL or DEVICE fp32 [count].  Two calls
+ * evaluate an element-wise product of two structured operands on the unique
+ * set of the result only:  A_C = gather(V, list(A), scale = gather(M, list(A))). */
+st_status st_desc_gather(st_desc *desc, const void *table, const float *Tc, const int32_t *idx, int64_t count,
+                         const float *scale, float *out, void *stream);
 
 /* Moment accumulation over the unique set of a descriptor of order 2 or 3 whose
  * variables all range over the n <= 256 features of X (N x n, row-major):

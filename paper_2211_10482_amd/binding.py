@@ -77,6 +77,8 @@ SIGNATURES = {
     "st_desc_thp": (_I32, [_P, _P, _P, _P, _P, _P]),
     "st_desc_expand": (_I32, [_P, _P, _P, _P, _P]),
     "st_desc_ttm": (_I32, [_P, _P, _P, _P, _I32, _P]),
+    "st_desc_product": (_I32, [_P, _P, _P]),
+    "st_desc_gather": (_I32, [_P, _P, _P, _P, _I64, _P, _P, _P]),
     "st_desc_moment_workspace": (_SZ, [_P, _I64]),
     "st_desc_moment": (_I32, [_P, _P, _P, _I64, _P, _I32, _P, _SZ, _P]),
     "st_probe_empty": (_I32, [_I32, _I32, _P]),
@@ -447,6 +449,16 @@ def expand_band(Tc, n, w, nl, T=None):
     return T
 
 
+def hadamard_struct(dm, Mc, dv, Vc):
+    """A(x) := M(x) * V(x) for two structured operands: the descriptor of the result (inferred) and its packed
+    values, evaluated on the unique set of the result only."""
+    da = dm.product(dv)
+    if da.count == 0:
+        return da, _torch().empty(0, dtype=_torch().float32, device=Mc.device)
+    idx = da.list().contiguous()
+    return da, dv.gather(Vc, idx, scale=dm.gather(Mc, idx))
+
+
 # ---- measurement support ----------------------------------------------------------------
 def probe_empty(grid, block):
     _check(lib().st_probe_empty(int(grid), int(block), _stream()), "st_probe_empty")
@@ -461,7 +473,12 @@ def probe_stream(src, grid, block, sink):
 class Descriptor:
     """Host object of ``st_desc_create`` plus (lazily) the device copy of its table."""
 
-    def __init__(self, unique_set, dims, redundancy=None, **params):
+    def __init__(self, unique_set, dims, redundancy=None, _handle=None, **params):
+        if _handle is not None:                       # an object the library made (st_desc_product)
+            self._h = _handle
+            self.dims = tuple(int(v) for v in dims)
+            self._table_dev = None
+            return
         self._h = C.c_void_p()
         dims = [int(v) for v in dims]
         da = (C.c_int64 * len(dims))(*dims)
@@ -543,6 +560,36 @@ class Descriptor:
                    "st_desc_expand")
         return T
 
+    def product(self, other):
+        """Descriptor of the element-wise product of two structured operands (structure inference)."""
+        h = C.c_void_p()
+        rc = lib().st_desc_product(self._h, other._h, C.byref(h))
+        if rc != 0:
+            msg = lib().st_desc_error(h).decode() if h else ""
+            if h:
+                lib().st_desc_destroy(h)
+            raise StructTensorError(rc, "st_desc_product (%s)" % msg)
+        return Descriptor(None, self.dims, _handle=h)
+
+    def gather(self, Tc, idx, scale=None, out=None):
+        """Values of the structured tensor at the dense positions idx ([count][order] int32), times scale."""
+        torch = _torch()
+        if not (isinstance(idx, torch.Tensor) and idx.is_cuda and idx.dtype == torch.int32 and idx.is_contiguous()):
+            raise TypeError("idx must be a contiguous int32 CUDA tensor")
+        if idx.dim() != 2 or idx.shape[1] != len(self.dims):
+            raise ValueError("idx must be [count][order]")
+        count = int(idx.shape[0])
+        _expect(Tc, self.count, "Tc", at_least=True)
+        if scale is not None:
+            _expect(scale, count, "scale", at_least=True)
+        if out is None:
+            out = torch.empty(max(count, 4), dtype=torch.float32, device=Tc.device)
+        _expect(out, count, "out", at_least=True)
+        self._call(lib().st_desc_gather(self._h, self._tab(), _dev_f32(Tc, "Tc"), C.c_void_p(idx.data_ptr()), count,
+                                        _dev_f32(scale, "scale") if scale is not None else None,
+                                        _dev_f32(out, "out"), _stream()), "st_desc_gather")
+        return out[:count]
+
     def ttm(self, Bc, U, Ac=None):
         torch = _torch()
         nl, R = _matrix(U, "U")
@@ -559,7 +606,7 @@ class Descriptor:
     def moment(self, X, Sc=None, accumulate=False, ws=None):
         torch = _torch()
         N, n = _matrix(X, "X")
-        if n != self.dims[-1]:
+        if len(set(self.dims)) == 1 and n != self.dims[0]:     # (unequal extents: the library refuses the call)
             raise ValueError("X must have one column per feature of the descriptor")
         if Sc is None:
             if accumulate:

@@ -218,7 +218,7 @@ struct Desc {
     i64 mbs = 0, ntiles = 0, mnp = 0;
     std::string nest, source;
     std::mutex mu;
-    struct Loaded { hipModule_t mod; hipFunction_t fn[5]; };   // list, thp, expand, moment, moment_reduce
+    struct Loaded { hipModule_t mod; hipFunction_t fn[6]; };   // list, thp, expand, gather, moment, moment_reduce
     std::map<int, Loaded> modules;               // per device
     std::string error;
 };
@@ -263,8 +263,9 @@ bool attach(Desc &D, const Bound &b, bool eq, std::string &err)
     return true;
 }
 
-// Logical simplification of the bound lists: duplicates are dropped, constant bounds are folded into the
-// dense extent (a constant lower bound raises `first`, a constant upper bound lowers `last`).
+// Logical simplification of the bound lists: duplicates and bounds implied by a tighter one of the same form
+// are dropped, constant bounds are folded into the dense extent (a constant lower bound raises `first`, a
+// constant upper bound lowers `last`).
 void simplify(Desc &D)
 {
     for (int v = 0; v < D.d; ++v) {
@@ -281,8 +282,14 @@ void simplify(Desc &D)
                     else D.first[v] = std::max(D.first[v], b.c);
                     continue;
                 }
+                // the same expression up to its constant: only the tighter bound is kept (x >= i - 2 and x >= i is
+                // x >= i), which also drops exact duplicates
                 bool dup = false;
-                for (auto &k : keep) dup = dup || (k.c == b.c && std::equal(k.coef, k.coef + MAXD, b.coef));
+                for (auto &k : keep)
+                    if (std::equal(k.coef, k.coef + MAXD, b.coef)) {
+                        k.c = side ? std::min(k.c, b.c) : std::max(k.c, b.c);
+                        dup = true;
+                    }
                 if (!dup) keep.push_back(b);
             }
             list.swap(keep);
@@ -545,6 +552,23 @@ void build_source(Desc &D)
     } else {
         s += "    T[e] = st_value(tab, Tc, " + xs + ");\n}\n";
     }
+    // gather: the value of the structured tensor at a LIST of dense positions (unique set, redundancy map or
+    // zero, as in the reconstruction), optionally times a factor per position -- what an element-wise product
+    // with another structured operand needs, evaluated only where the product's unique set says
+    s += "extern \"C\" __global__ void st_gen_gather(const int *__restrict__ tab, const float *__restrict__ Tc,\n"
+         "                                         const int *__restrict__ idx, long long count,\n"
+         "                                         const float *__restrict__ scale, float *__restrict__ out)\n{\n";
+    s += "    const long long p = (long long)blockIdx.x * blockDim.x + threadIdx.x;\n    if (p >= count) return;\n";
+    {
+        std::string at;
+        for (int v = 0; v < d; ++v) {
+            const std::string xv = "x" + std::to_string(v);
+            s += "    const int " + xv + " = idx[p * ST_D + " + std::to_string(v) + "];\n";
+            at += std::string(v ? " && " : "") + xv + " >= 0 && " + xv + " < ST_DIM" + std::to_string(v);
+        }
+        s += "    const float v = (" + at + ") ? st_value(tab, Tc, " + xs + ") : 0.f;\n";
+    }
+    s += "    out[p] = scale ? scale[p] * v : v;\n}\n";
     if (D.ntiles > 0) {
         // moment accumulation over the unique set: Sc(rank(x)) (+)= sum_s prod_v X(s, x_v).  One lane per block
         // tuple with its ST_MBS^d = 64 accumulators in registers, sample rows staged through a double-buffered
@@ -617,6 +641,56 @@ void build_source(Desc &D)
         s += "    const int p = st_rank(tab, " + xs + ");\n    Sc[p] = accumulate ? Sc[p] + v : v;\n}\n";
     }
     D.source = s;
+}
+
+// Property 1 of the semantics (T_U * T_R is empty): no index may be both a stored entry and the source of a
+// redundancy term.  Every run of the unique set (prefix fixed, last variable in [l, h]) is cut against the
+// term's condition, which for a fixed prefix is an interval of the last variable.
+bool first_overlap(const Desc &D, size_t term, i64 *where)
+{
+    const RedTerm &t = D.red[term];
+    const int d = D.d, np = d - 1;
+    for (i64 r = 0; r < D.nruns; ++r) {
+        i64 pf = D.table[(size_t)(D.prefixes + r)], x[MAXD] = {0, 0, 0, 0};
+        for (int v = np - 1; v >= 0; --v) { x[v] = pf % D.dims[v]; pf /= D.dims[v]; }
+        i64 l, h;
+        range_of(D, np, x, l, h);
+        bool none = false;
+        for (auto &c : t.cond) {                       // c.c + sum coef*x >= 0
+            i64 rest = c.c;
+            for (int u = 0; u < np; ++u) rest += c.coef[u] * x[u];
+            const i64 a = c.coef[np];
+            if (a == 0) { if (rest < 0) none = true; }
+            else if (a > 0) l = std::max(l, -(rest >= 0 ? rest / a : -((-rest + a - 1) / a)));      // x >= ceil(-rest / a)
+            else h = std::min(h, rest >= 0 ? rest / (-a) : -((-rest + (-a) - 1) / (-a)));           // x <= floor(rest / -a)
+            if (none) break;
+        }
+        if (!none && l <= h) {
+            for (int u = 0; u < np; ++u) where[u] = x[u];
+            where[np] = l;
+            return true;
+        }
+    }
+    return false;
+}
+
+// simplification, nest, tables, Property 1, generated source: the common tail of every way to make a descriptor
+st_status finish(Desc &D)
+{
+    simplify(D);
+    build_nest(D);
+    if (!build_tables(D, D.error)) return ST_ERR_UNSUPPORTED;
+    for (size_t q = 0; q < D.red.size(); ++q) {
+        i64 at[MAXD];
+        if (first_overlap(D, q, at)) {
+            D.error = "redundancy term " + std::to_string(q + 1) + " applies to the stored entry (";
+            for (int v = 0; v < D.d; ++v) D.error += (v ? "," : "") + std::to_string((long long)at[v]);
+            D.error += "): the unique set and the redundancy map must be disjoint (T_U * T_R is empty)";
+            return ST_ERR_SHAPE;
+        }
+    }
+    build_source(D);
+    return ST_OK;
 }
 
 st_status parse_all(Desc &D, const char *unique_set, const char *redundancy, const i64 *dims, int ndims,
@@ -699,11 +773,131 @@ st_status parse_all(Desc &D, const char *unique_set, const char *redundancy, con
             if (*pr.p || !pr.ok) { D.error = "trailing text in the redundancy map"; return ST_ERR_SHAPE; }
         }
     }
-    simplify(D);
-    build_nest(D);
-    if (!build_tables(D, D.error)) return ST_ERR_UNSUPPORTED;
-    build_source(D);
-    return ST_OK;
+    return finish(D);
+}
+
+// ---- structure inference for an element-wise product ------------------------------------------------
+// A(x) := M(x) * V(x) over the same index vector.  General rule of the inference figure:
+//     A_U = M_U * V_U  +  M_U * V_R  +  M_R * V_U,        A_R = M_R * V_R,
+// every summand a product of comparisons.  Simplification: a product whose comparisons contradict each other
+// is the empty set and drops out of the sum (decided here by deriving its nest and counting: zero entries).
+// What remains must be ONE product (a descriptor holds one); in A_R a pair of terms survives when both send x
+// to the same unique index.
+void add_box(Desc &D, const Desc &S)          // the comparisons of a finished descriptor: ranges and bound lists
+{
+    for (int v = 0; v < S.d; ++v) {
+        Bound b;
+        for (int u = 0; u < MAXD; ++u) b.coef[u] = 0;
+        b.c = S.first[v];
+        D.lo[v].push_back(b);
+        b.c = S.last[v];
+        D.hi[v].push_back(b);
+        for (auto &q : S.lo[v]) D.lo[v].push_back(q);
+        for (auto &q : S.hi[v]) D.hi[v].push_back(q);
+    }
+    D.empty = D.empty || S.empty;
+}
+
+std::vector<RedTerm> terms_of(const Desc &S)   // 'sort' of order 2 is the class-S map (x1 < x0) -> (x1, x0)
+{
+    std::vector<RedTerm> out = S.red;
+    if (S.red_sort && S.d == 2) {
+        RedTerm t;
+        Bound c;
+        for (int u = 0; u < MAXD; ++u) c.coef[u] = 0;
+        c.c = -1; c.coef[0] = 1; c.coef[1] = -1;                 // x0 - x1 - 1 >= 0
+        t.cond.push_back(c);
+        for (int v = 0; v < MAXD; ++v) { t.map[v].c = 0; for (int u = 0; u < MAXD; ++u) t.map[v].coef[u] = 0; }
+        t.map[0].coef[1] = 1;
+        t.map[1].coef[0] = 1;
+        out.push_back(t);
+    }
+    return out;
+}
+
+bool same_map(const RedTerm &a, const RedTerm &b, int d)
+{
+    for (int v = 0; v < d; ++v)
+        if (a.map[v].c != b.map[v].c || !std::equal(a.map[v].coef, a.map[v].coef + MAXD, b.map[v].coef)) return false;
+    return true;
+}
+
+st_status infer_product(const Desc &M, const Desc &V, Desc &A)
+{
+    if (M.d != V.d || !std::equal(M.dims, M.dims + MAXD, V.dims)) { A.error = "operands of different shape"; return ST_ERR_SHAPE; }
+    if ((M.red_sort || V.red_sort) && M.d != 2) {
+        A.error = "a 'sort' redundancy map of order above 2 is a sum of conditions: not supported in a product";
+        return ST_ERR_UNSUPPORTED;
+    }
+    const int d = M.d;
+    const std::vector<RedTerm> mr = terms_of(M), vr = terms_of(V);
+    // the summands of A_U, each as a candidate descriptor; kept when not empty
+    struct Cand { const Desc *u; const RedTerm *t; const Desc *other; };
+    std::vector<Cand> cands;
+    cands.push_back(Cand{&M, nullptr, &V});
+    for (auto &t : vr) cands.push_back(Cand{&M, &t, nullptr});
+    for (auto &t : mr) cands.push_back(Cand{&V, &t, nullptr});
+    int kept = -1, nkept = 0;
+    for (size_t q = 0; q < cands.size(); ++q) {
+        Desc T;
+        T.d = d; T.name = "A"; T.vars = M.vars;
+        std::copy(M.dims, M.dims + MAXD, T.dims);
+        add_box(T, *cands[q].u);
+        if (cands[q].other) add_box(T, *cands[q].other);
+        std::string err;
+        bool ok = true;
+        if (cands[q].t) for (auto &c : cands[q].t->cond) ok = ok && attach(T, c, false, err);
+        if (!ok) { A.error = "a redundancy condition cannot be turned into loop bounds: " + err; return ST_ERR_UNSUPPORTED; }
+        simplify(T);
+        if (!build_tables(T, err)) { A.error = err; return ST_ERR_UNSUPPORTED; }
+        if (T.count > 0) { kept = (int)q; ++nkept; }
+    }
+    A.d = d; A.name = "A"; A.vars = M.vars;
+    std::copy(M.dims, M.dims + MAXD, A.dims);
+    if (nkept > 1) {
+        A.error = "the unique set of the product is a sum of " + std::to_string(nkept) + " non-empty products; a descriptor holds one";
+        return ST_ERR_UNSUPPORTED;
+    }
+    if (nkept == 0) A.empty = true;
+    else {
+        add_box(A, *cands[(size_t)kept].u);
+        if (cands[(size_t)kept].other) add_box(A, *cands[(size_t)kept].other);
+        std::string err;
+        if (cands[(size_t)kept].t) for (auto &c : cands[(size_t)kept].t->cond) attach(A, c, false, err);
+    }
+    // A_R = M_R * V_R: both conditions hold and both maps name the same unique index
+    for (auto &a : mr)
+        for (auto &b : vr) {
+            if (!same_map(a, b, d)) continue;
+            RedTerm t = a;
+            for (auto &c : b.cond) t.cond.push_back(c);
+            A.red.push_back(t);
+        }
+    return finish(A);
+}
+
+// the generated source compiled for gfx950 (no GPU needed); on failure D.error holds the compiler's log
+st_status compile_source(Desc &D, std::vector<char> *code)
+{
+    hiprtcProgram prog;
+    if (hiprtcCreateProgram(&prog, D.source.c_str(), "st_generated.hip", 0, nullptr, nullptr) != HIPRTC_SUCCESS)
+        return ST_ERR_LAUNCH;
+    const char *opts[] = {"--offload-arch=gfx950", "-O3", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"};
+    const hiprtcResult rc = hiprtcCompileProgram(prog, 6, opts);
+    if (rc != HIPRTC_SUCCESS) {
+        size_t n = 0;
+        hiprtcGetProgramLogSize(prog, &n);
+        std::string log(n, '\0');
+        if (n) hiprtcGetProgramLog(prog, &log[0]);
+        D.error = "hiprtc: " + log;
+    } else if (code) {
+        size_t n = 0;
+        hiprtcGetCodeSize(prog, &n);
+        code->resize(n);
+        hiprtcGetCode(prog, code->data());
+    }
+    hiprtcDestroyProgram(&prog);
+    return rc == HIPRTC_SUCCESS ? ST_OK : ST_ERR_LAUNCH;
 }
 
 // compile the generated source for the current device and load it (once per device)
@@ -714,30 +908,14 @@ st_status module_for(Desc &D, Desc::Loaded &out)
     std::lock_guard<std::mutex> lock(D.mu);
     auto it = D.modules.find(dev);
     if (it != D.modules.end()) { out = it->second; return ST_OK; }
-    hiprtcProgram prog;
-    if (hiprtcCreateProgram(&prog, D.source.c_str(), "st_generated.hip", 0, nullptr, nullptr) != HIPRTC_SUCCESS)
-        return ST_ERR_LAUNCH;
-    const char *opts[] = {"--offload-arch=gfx950", "-O3", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"};
-    hiprtcResult rc = hiprtcCompileProgram(prog, 6, opts);
-    if (rc != HIPRTC_SUCCESS) {
-        size_t n = 0;
-        hiprtcGetProgramLogSize(prog, &n);
-        std::string log(n, '\0');
-        if (n) hiprtcGetProgramLog(prog, &log[0]);
-        D.error = "hiprtc: " + log;
-        hiprtcDestroyProgram(&prog);
-        return ST_ERR_LAUNCH;
-    }
-    size_t n = 0;
-    hiprtcGetCodeSize(prog, &n);
-    std::vector<char> code(n);
-    hiprtcGetCode(prog, code.data());
-    hiprtcDestroyProgram(&prog);
+    std::vector<char> code;
+    if (compile_source(D, &code) != ST_OK) return ST_ERR_LAUNCH;
     Desc::Loaded L;
     if (hipModuleLoadData(&L.mod, code.data()) != hipSuccess) { D.error = "hipModuleLoadData failed"; return ST_ERR_LAUNCH; }
-    const char *names[5] = {"st_gen_list", "st_gen_thp", "st_gen_expand", "st_gen_moment", "st_gen_moment_reduce"};
-    L.fn[3] = L.fn[4] = nullptr;
-    for (int q = 0; q < (D.ntiles > 0 ? 5 : 3); ++q)
+    const char *names[6] = {"st_gen_list", "st_gen_thp", "st_gen_expand", "st_gen_gather", "st_gen_moment",
+                            "st_gen_moment_reduce"};
+    L.fn[4] = L.fn[5] = nullptr;
+    for (int q = 0; q < (D.ntiles > 0 ? 6 : 4); ++q)
         if (hipModuleGetFunction(&L.fn[q], L.mod, names[q]) != hipSuccess) {
             (void)hipModuleUnload(L.mod);
             D.error = std::string("generated kernel missing: ") + names[q];
@@ -828,20 +1006,7 @@ st_status st_desc_compile(st_desc *desc)
     if (!desc) return ST_ERR_NULL;
     Desc *D = reinterpret_cast<Desc *>(desc);
     if (D->source.empty()) return ST_ERR_SHAPE;
-    hiprtcProgram prog;
-    if (hiprtcCreateProgram(&prog, D->source.c_str(), "st_generated.hip", 0, nullptr, nullptr) != HIPRTC_SUCCESS)
-        return ST_ERR_LAUNCH;
-    const char *opts[] = {"--offload-arch=gfx950", "-O3", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"};
-    hiprtcResult rc = hiprtcCompileProgram(prog, 6, opts);
-    if (rc != HIPRTC_SUCCESS) {
-        size_t n = 0;
-        hiprtcGetProgramLogSize(prog, &n);
-        std::string log(n, '\0');
-        if (n) hiprtcGetProgramLog(prog, &log[0]);
-        D->error = "hiprtc: " + log;
-    }
-    hiprtcDestroyProgram(&prog);
-    return rc == HIPRTC_SUCCESS ? ST_OK : ST_ERR_LAUNCH;
+    return compile_source(*D, nullptr);
 }
 
 st_status st_desc_list(st_desc *desc, const void *table, int32_t *out, void *stream)
@@ -909,7 +1074,7 @@ st_status st_desc_moment(st_desc *desc, const void *table, const float *X, int64
         int S0 = 0;
         const void *none = table;
         void *a0[] = {&table, &none, &S0, &Sc, &accumulate};
-        return launch_generated(*D, 4, (unsigned)((D->ntiles * 64 + 15) / 16), a0, (hipStream_t)stream);
+        return launch_generated(*D, 5, (unsigned)((D->ntiles * 64 + 15) / 16), a0, (hipStream_t)stream);
     }
     const size_t need = st_desc_moment_workspace(desc, N);
     if (!ws || ws_bytes < need) return ST_ERR_WORKSPACE;
@@ -919,11 +1084,40 @@ st_status st_desc_moment(st_desc *desc, const void *table, const float *X, int64
     long long Nll = N, slice = p.slice;
     int ch = (int)p.ch, S = (int)p.S;
     void *a1[] = {&table, &X, &Nll, &ch, &slice, &ws};
-    st_status rc = launch_generated(*D, 3, p.gx, a1, (hipStream_t)stream, p.S, p.threads,
+    st_status rc = launch_generated(*D, 4, p.gx, a1, (hipStream_t)stream, p.S, p.threads,
                                     (unsigned)(2u * p.ch * D->mnp * sizeof(float)));
     if (rc != ST_OK) return rc;
     void *a2[] = {&table, &ws, &S, &Sc, &accumulate};
-    return launch_generated(*D, 4, (unsigned)((D->ntiles * 64 + 15) / 16), a2, (hipStream_t)stream);
+    return launch_generated(*D, 5, (unsigned)((D->ntiles * 64 + 15) / 16), a2, (hipStream_t)stream);
+}
+
+st_status st_desc_product(const st_desc *m, const st_desc *v, st_desc **out)
+{
+    if (!m || !v || !out) return ST_ERR_NULL;
+    const Desc *M = reinterpret_cast<const Desc *>(m), *V = reinterpret_cast<const Desc *>(v);
+    if (M->source.empty() || V->source.empty()) return ST_ERR_SHAPE;
+    Desc *A = new Desc();
+    const st_status rc = infer_product(*M, *V, *A);
+    *out = reinterpret_cast<st_desc *>(A);      // kept on failure too: st_desc_error tells why
+    return rc;
+}
+
+st_status st_desc_gather(st_desc *desc, const void *table, const float *Tc, const int32_t *idx, int64_t count,
+                         const float *scale, float *out, void *stream)
+{
+    if (!desc || !table || !Tc || (count > 0 && (!idx || !out))) return ST_ERR_NULL;
+    Desc *D = reinterpret_cast<Desc *>(desc);
+    if (D->source.empty() || count < 0) return ST_ERR_SHAPE;
+    if (count > ((int64_t)1 << 31) * 200) return ST_ERR_UNSUPPORTED;
+    if (!aligned16(table) || !aligned16(Tc) || !aligned16(idx) || !aligned16(out) || (scale && !aligned16(scale)))
+        return ST_ERR_ALIGN;
+    if (count == 0) return ST_OK;
+    if (overlap(out, (size_t)count * 4, Tc, (size_t)D->count * 4) ||
+        overlap(out, (size_t)count * 4, idx, (size_t)count * 4 * D->d))
+        return ST_ERR_SHAPE;
+    long long cnt = count;
+    void *args[] = {&table, &Tc, &idx, &cnt, &scale, &out};
+    return launch_generated(*D, 3, (unsigned)((count + 255) / 256), args, (hipStream_t)stream);
 }
 
 st_status st_desc_expand(st_desc *desc, const void *table, const float *Tc, float *T, void *stream)

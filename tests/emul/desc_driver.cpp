@@ -5,6 +5,7 @@
 // moment kernels are launched in a shape (one thread per block, one slice) for which that also holds.
 //   argv: dir count box order nruns last_dim [N]  (dir holds table.i32, bc.f32 [count], c.f32 [box], x.f32 [N*n])
 //   writes list.i32 [count*order], thp.f32 [count], expand.f32 [box] (expansion of bc.f32), moment.f32 [count]
+//   when dir holds gather.i32 ([g][order] dense positions; gather_scale.f32 [g] optional): gather.f32 [g]
 #include <hip/hip_runtime.h>
 // LDS of the generated moment kernels: the dynamic chunk buffer is a global here, static arrays keep their
 // zero initialisation (the reduce kernel reads rows of its array that other threads of the block wrote)
@@ -67,6 +68,17 @@ int main(int argc, char **argv)
         wr(dir + "/moment.f32", sc);
     }
 #endif
+    if (FILE *f = fopen((dir + "/gather.i32").c_str(), "rb")) {
+        fseek(f, 0, SEEK_END);
+        const size_t g = (size_t)ftell(f) / (sizeof(int) * order);
+        fclose(f);
+        std::vector<int> idx = rd<int>(dir + "/gather.i32", g * order);
+        std::vector<float> scale, out(g, -7.f);
+        if (FILE *h = fopen((dir + "/gather_scale.f32").c_str(), "rb")) { fclose(h); scale = rd<float>(dir + "/gather_scale.f32", g); }
+        if (g) hipLaunchKernelGGL(st_gen_gather, dim3((unsigned)((g + 255) / 256)), dim3(256), 0, 0, tab.data(), bc.data(), idx.data(),
+                                  (long long)g, scale.empty() ? (const float *)nullptr : scale.data(), out.data());
+        wr(dir + "/gather.f32", out);
+    }
     wr(dir + "/list.i32", list);
     wr(dir + "/thp.f32", thp);
     wr(dir + "/expand.f32", ex);

@@ -194,3 +194,125 @@ def test_generated_kernels_on_the_cpu(descs, oracle, tmp_path, name):
         mom = np.fromfile(str(tmp_path / "moment.f32"), dtype=np.float32)
         refm = oracle.struct_moment(X, dims, pred)
         assert mom.size == refm.size and float(np.abs(mom - refm).max()) <= 1e-5 * max(float(np.abs(refm).max()), 1.0)
+
+
+# ------------------------------------------------------------------ Property 1: T_U * T_R is empty
+def test_redundancy_term_must_not_meet_the_unique_set():
+    """The unique set and the redundancy map are disjoint ("Properties" of the semantics, property 1): a term
+    whose condition holds for a stored entry is refused, with the first such entry in the message."""
+    bad = [
+        ("S(i,j): (0<=i<=j<n)", (5, 5), "(0<=j<=i<n) -> (j,i)", dict(n=5), "(0,0)"),          # meets the diagonal
+        ("M(i,j): (i=0)*(0<=j<m)", (4, 6), "(0<=i<n) -> (0,j)", dict(n=4, m=6), "(0,0)"),      # row 0 is stored
+        ("B(i,j,l): (0<=i<n)*(i-1<=j<=i+1)*(0<=l<m)", (5, 5, 3), "(0<=i<n)*(j=i+1)*(l=2) -> (i,i,l)", dict(n=5, m=3), "(0,1,2)"),
+    ]
+    for text, dims, red, params, where in bad:
+        with pytest.raises(st.StructTensorError) as e:
+            st.Descriptor(text, dims, red, **params)
+        assert e.value.status == 2 and where in str(e.value) and "disjoint" in str(e.value), str(e.value)
+    # the hand-wired maps of the library's own structures are disjoint by the same check
+    for text, dims, red, params in (("S(i,j): (0<=i<=j<n)", (9, 9), "(0<=j<i<n) -> (j,i)", dict(n=9)),
+                                    ("M(i,j): (i=0)*(0<=j<m)", (4, 6), "(1<=i<n) -> (0,j)", dict(n=4, m=6))):
+        st.Descriptor(text, dims, red, **params).close()
+
+
+# ------------------------------------------------------------------ structure inference for element-wise products
+SYM_RED = "(0<=j<i<n) -> (j,i)"
+_swap = lambda i, j: (j, i) if j < i else None
+# name -> (M: text, redundancy, predicate, unique_of), (V: ...), dims, params, expected (predicate, unique_of) or None
+PRODUCTS = {
+    # the paper's walk-through: upper triangular (.) symmetric = upper triangular, no redundancy
+    "uhs": (("M(i,j): (0<=i<=j<n)", None, lambda i, j: i <= j, None),
+            ("N(i,j): (0<=i<=j<n)", "sort", lambda i, j: i <= j, _swap), (7, 7), dict(n=7),
+            (lambda i, j: i <= j, None), ["for (i = 0; i <= 6; ++i)", "  for (j = i; j <= 6; ++j)"]),
+    "sym_sym": (("M(i,j): (0<=i<=j<n)", SYM_RED, lambda i, j: i <= j, _swap),
+                ("N(i,j): (0<=i<=j<n)", "sort", lambda i, j: i <= j, _swap), (6, 6), dict(n=6),
+                (lambda i, j: i <= j, _swap), None),
+    "band_upper": (("M(i,j): (0<=i<n)*(i-w<=j<=i+w)", None, lambda i, j: abs(i - j) <= 2, None),
+                   ("N(i,j): (0<=i<=j<n)", None, lambda i, j: i <= j, None), (8, 8), dict(n=8, w=2),
+                   (lambda i, j: i <= j <= i + 2, None), ["for (i = 0; i <= 7; ++i)", "  for (j = i; j <= min(7, i + 2); ++j)"]),
+    "rows_rows": (("M(i,j): (i=0)*(0<=j<m)", "(1<=i<n) -> (0,j)", lambda i, j: i == 0, lambda i, j: (0, j) if i >= 1 else None),
+                  ("N(i,j): (i=0)*(0<=j<m)", "(1<=i<n) -> (0,j)", lambda i, j: i == 0, lambda i, j: (0, j) if i >= 1 else None),
+                  (4, 5), dict(n=4, m=5), (lambda i, j: i == 0, lambda i, j: (0, j) if i >= 1 else None), None),
+    "diag_sym": (("M(i,j): (0<=i<n)*(i=j)", None, lambda i, j: i == j, None),
+                 ("N(i,j): (0<=i<=j<n)", SYM_RED, lambda i, j: i <= j, _swap), (5, 5), dict(n=5),
+                 (lambda i, j: i == j, None), None),
+    "disjoint": (("M(i,j): (0<=j<i<n)", None, lambda i, j: j < i, None),
+                 ("N(i,j): (0<=i<j<n)", None, lambda i, j: i < j, None), (5, 5), dict(n=5),
+                 (lambda i, j: False, None), None),
+    "band3_cube": (("M(i,j,l): (0<=i<n)*(i-1<=j<=i+1)*(0<=l<m)", None, lambda i, j, l: abs(i - j) <= 1, None),
+                   ("N(i,j,l): (0<=i<n)*(i<=j<n)*(0<=l<m)", None, lambda i, j, l: i <= j, None), (6, 6, 4), dict(n=6, m=4),
+                   (lambda i, j, l: i <= j <= i + 1, None), None),
+    # lower triangle (.) symmetric: the diagonal comes from M_U * N_U, the strict lower part from M_U * N_R: two summands
+    "lower_sym": (("M(i,j): (0<=j<=i<n)", None, lambda i, j: j <= i, None),
+                  ("N(i,j): (0<=i<=j<n)", SYM_RED, lambda i, j: i <= j, _swap), (5, 5), dict(n=5), None, None),
+}
+
+
+def _run_generated(d, workdir, dims, Tc, gather_idx=None, scale=None):
+    """Compile the generated source of descriptor d against the host stand-in and run the driver in workdir."""
+    os.makedirs(workdir, exist_ok=True)
+    src = os.path.join(workdir, "generated.hip")
+    open(src, "w").write(d.source)
+    exe = os.path.join(workdir, "driver")
+    cmd = [CLANG, "-std=c++17", "-O1", "-g", "-fsanitize=address", "-fno-omit-frame-pointer",
+           '-DGEN_SRC="%s"' % src, "-I", EMUL, "-x", "c++", os.path.join(EMUL, "desc_driver.cpp"), "-o", exe]
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr[-3000:]
+    box = int(np.prod(dims))
+    d.table().tofile(os.path.join(workdir, "table.i32"))
+    np.asarray(Tc, dtype=np.float32).tofile(os.path.join(workdir, "bc.f32"))
+    np.zeros(box, dtype=np.float32).tofile(os.path.join(workdir, "c.f32"))
+    if gather_idx is not None:
+        np.ascontiguousarray(gather_idx, dtype=np.int32).tofile(os.path.join(workdir, "gather.i32"))
+        if scale is not None:
+            np.asarray(scale, dtype=np.float32).tofile(os.path.join(workdir, "gather_scale.f32"))
+    r = subprocess.run([exe, workdir, str(d.count), str(box), str(len(dims)), str(d.runs), str(dims[-1])],
+                       capture_output=True, text=True, timeout=300)
+    assert r.returncode == 0 and "rc=0" in r.stdout, r.stderr[-3000:]
+    return np.fromfile(os.path.join(workdir, "gather.f32"), dtype=np.float32) if gather_idx is not None else None
+
+
+@pytest.mark.parametrize("name", sorted(PRODUCTS))
+def test_product_inference(oracle, tmp_path, name):
+    """A(x) := M(x) * V(x): the inferred unique set and redundancy map against predicates written out by hand
+    (brute force over the box), and the values -- the generated gather kernels run on the CPU -- against the
+    product of the two reconstructed dense operands: bit for bit on the unique set, and Property 5 for the
+    result (reconstructing A from A_C through the inferred map gives the dense product everywhere)."""
+    if CLANG is None:
+        pytest.skip("no clang++ for the host build")
+    (mt, mred, mpred, muniq), (vt, vred, vpred, vuniq), dims, params, want, nest = PRODUCTS[name]
+    dm, dv = st.Descriptor(mt, dims, mred, **params), st.Descriptor(vt, dims, vred, **params)
+    if want is None:
+        with pytest.raises(st.StructTensorError) as e:
+            dm.product(dv)
+        assert e.value.status == 6 and "sum of 2" in str(e.value)
+        return
+    apred, auniq = want
+    da = dm.product(dv)
+    lst = oracle.struct_enumerate(dims, apred)
+    assert da.count == lst.shape[0]
+    if nest is not None:
+        assert da.nest.splitlines()[:len(nest)] == nest
+    Mc, Vc = W.uniform(771, max(dm.count, 1))[: dm.count], W.uniform(772, max(dv.count, 1))[: dv.count]
+    Md = oracle.struct_expand(Mc, dims, mpred, muniq)
+    Vd = oracle.struct_expand(Vc, dims, vpred, vuniq)
+    dense = Md * Vd                                              # fp32 products, correctly rounded
+    if da.count == 0:
+        assert not dense.any()
+        return
+    gm = _run_generated(dm, str(tmp_path / "m"), dims, Mc, gather_idx=lst)
+    ac = _run_generated(dv, str(tmp_path / "v"), dims, Vc, gather_idx=lst, scale=gm)
+    cols = tuple(lst[:, v].astype(np.int64) for v in range(len(dims)))
+    assert np.array_equal(gm, Md[cols])
+    assert np.array_equal(ac.view(np.uint32), dense[cols].view(np.uint32))
+    # Property 5 for the result, through the library's own reconstruction of A_C (CPU run of A's expand kernel)
+    _run_generated(da, str(tmp_path / "a"), dims, ac)
+    ex = np.fromfile(str(tmp_path / "a" / "expand.f32"), dtype=np.float32).reshape(dims)
+    # (by value: a structural zero times a negative entry is -0 in the dense product, +0 in a reconstruction)
+    assert np.array_equal(ex, dense)
+    assert np.array_equal(oracle.struct_expand(ac, dims, apred, auniq), dense)
+    # positions outside the dense extents read as zero
+    out = _run_generated(dm, str(tmp_path / "o"), dims, Mc, gather_idx=np.array([[-1] * len(dims), list(dims)], dtype=np.int32))
+    assert np.array_equal(out, np.zeros(2, dtype=np.float32))
+    for d in (dm, dv, da):
+        d.close()

@@ -208,3 +208,55 @@ def test_descriptor_moment_against_handwritten(st, oracle):
         db.moment(torch.zeros((5, 8), device="cuda"))
     for d in (d2, d3, db):
         d.close()
+
+
+# ------------------------------------------------------------ element-wise products of two structured operands
+from test_desc import PRODUCTS
+
+
+@pytest.mark.parametrize("name", sorted(k for k, v in PRODUCTS.items() if v[4] is not None))
+def test_product_of_structured_operands_small(st, oracle, name):
+    say("descriptor product", name)
+    (mt, mred, mpred, muniq), (vt, vred, vpred, vuniq), dims, params, (apred, auniq), _ = PRODUCTS[name]
+    dm, dv = st.Descriptor(mt, dims, mred, **params), st.Descriptor(vt, dims, vred, **params)
+    Mc, Vc = W.uniform(771, max(dm.count, 4)), W.uniform(772, max(dv.count, 4))
+    da, Ac = st.hadamard_struct(dm, dev(Mc), dv, dev(Vc))
+    lst = oracle.struct_enumerate(dims, apred)
+    assert da.count == lst.shape[0] == Ac.numel()
+    dense = oracle.struct_expand(Mc[: dm.count], dims, mpred, muniq) * oracle.struct_expand(Vc[: dv.count], dims, vpred, vuniq)
+    if da.count:
+        assert np.array_equal(da.list().cpu().numpy(), lst)
+        cols = tuple(lst[:, v].astype(np.int64) for v in range(len(dims)))
+        got = Ac.cpu().numpy()
+        assert np.array_equal(got.view(np.uint32), dense[cols].view(np.uint32))
+        import torch
+        buf = torch.zeros(max(da.count, 4), device="cuda")
+        buf[: da.count] = Ac
+        assert np.array_equal(da.expand(buf).cpu().numpy(), dense)          # Property 5 for the result
+    else:
+        assert not dense.any()
+    for d in (dm, dv, da):
+        d.close()
+
+
+def test_upper_triangular_times_symmetric_full(st, oracle):
+    """The paper's UHS walk-through at n = 2048: the inferred structure is the upper triangle with no redundancy,
+    the values are the products of the stored entries (both operands share the packing), checked against the C
+    oracle's dense forms of the two operands."""
+    n = 2048
+    say("descriptor product: upper triangular (.) symmetric, n=%d" % n)
+    dm = st.Descriptor("M(i,j): (0<=i<=j<n)", (n, n), None, n=n)
+    dv = st.Descriptor("N(i,j): (0<=i<=j<n)", (n, n), "sort", n=n)
+    cnt = oracle.count_sym2(n)
+    Mc, Vc = W.uniform(781, cnt), W.uniform(782, cnt)
+    da, Ac = st.hadamard_struct(dm, dev(Mc), dv, dev(Vc))
+    assert da.count == cnt and da.nest.splitlines()[1].strip() == "for (j = i; j <= %d; ++j)" % (n - 1)
+    dense = oracle.dense_utri(Mc, n).astype(np.float32) * oracle.expand_sym(Vc, n, 2)
+    iu = np.triu_indices(n)
+    assert np.array_equal(Ac.cpu().numpy(), dense[iu])
+    assert not np.tril(dense, -1).any()                    # nothing below the diagonal: no redundancy map needed
+    # the other order of the operands gives the same structure and values
+    db, Bc = st.hadamard_struct(dv, dev(Vc), dm, dev(Mc))
+    assert db.count == cnt and np.array_equal(Bc.cpu().numpy(), Ac.cpu().numpy())
+    for d in (dm, dv, da, db):
+        d.close()
