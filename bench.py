@@ -317,9 +317,11 @@ def main():
             evs.append((e0, e1))
         torch.cuda.synchronize()
         return float(np.median([a.elapsed_time(b) for a, b in evs])) * 1e3
+    # (not in a --copy-probe run: the copies made here would be counted with the probe's)
+    floor_cases = () if args.copy_probe else (("ttm_operand_17.7MB", Tc3, (256, 1024)), ("mttkrp_operand_90MB", Tc4, (4096, 256)),
+                                              ("batax_operand_134MB", Ap, (8192, 256)))
     floors["empty_launch_256x1024_us"] = round(timed_median(lambda: st.probe_empty(256, 1024)), 2)
-    for tag, buf, shape in (("ttm_operand_17.7MB", Tc3, (256, 1024)), ("mttkrp_operand_90MB", Tc4, (4096, 256)),
-                            ("batax_operand_134MB", Ap, (8192, 256))):
+    for tag, buf, shape in floor_cases:
         copies = [buf] + [buf.clone() for _ in range(max(2, int(600e6 // (buf.numel() * 4))))]
         k = [0]
         def f(copies=copies, shape=shape):
