@@ -330,6 +330,16 @@ def main():
         floors["stream_read_%s_cold_%dx%d_us" % ((tag,) + shape)] = round(timed_median(f), 2)
         del copies
 
+    # matrix-core floor of the single-precision kernels: 23 MFMAs 16x16x4 per block from registers, alone and with
+    # the 13 cross-lane multiplies per block that the third-moment kernel needs for its pair products (on this
+    # chip the fp32 MFMA and the vector ALU do not overlap, so the second figure is that kernel's ceiling)
+    msink = torch.empty(256 * 512, **f32)
+    for valu, tag in ((0, "mfma_f32_registers_only_tflops"), (13, "mfma_f32_with_13_valu_per_23_mfma_tflops")):
+        fl = [0]
+        def f(valu=valu):
+            fl[0] = st.probe_mfma_f32(valu, 4000, msink)
+        floors[tag] = round(fl[0] / 1e6 / timed_median(f, reps=10) if timed_median(f, reps=3) and fl[0] else 0.0, 2)
+
     wl = workloads()
     rec = recorded_counters()
     kernels = {}
@@ -357,6 +367,10 @@ def main():
     roofline = dict(kernel=dom, bound="mfma", achieved=round(achieved, 3), peak=MFMA_FP32_PEAK_TFLOPS,
                     unit="TFLOP/s", frac=round(achieved / MFMA_FP32_PEAK_TFLOPS, 4),
                     frac_kernel_trace=kernels[dom]["frac_kernel_trace"], traffic=kernels[dom]["traffic"],
+                    measured_ceiling=dict(mfma_only=floors["mfma_f32_registers_only_tflops"],
+                                          with_pair_products=floors["mfma_f32_with_13_valu_per_23_mfma_tflops"],
+                                          unit="TFLOP/s (matrix-core flops of the probe; the kernel's padded tiles do "
+                                               "47104/45760 of its unique flops on the matrix cores)"),
                     timing="median of %d event pairs around the call (main kernel + its partial-sum kernel); "
                            "frac_kernel_trace = the same flops over the rocprofv3 kernel durations in profiles/" % args.steps)
 

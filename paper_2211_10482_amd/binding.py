@@ -83,6 +83,7 @@ SIGNATURES = {
     "st_desc_moment": (_I32, [_P, _P, _P, _I64, _P, _I32, _P, _SZ, _P]),
     "st_probe_empty": (_I32, [_I32, _I32, _P]),
     "st_probe_stream": (_I32, [_P, _SZ, _I32, _I32, _P, _P]),
+    "st_probe_mfma_f32": (_I32, [_I32, _I32, _P, _P]),
     "st_covar_pr2_workspace": (_SZ, [_I64, _I32]),
     "st_covar_pr2": (_I32, [_P, _I64, _I32, _P, _P, _P, _I32, _P, _SZ, _P]),
 }
@@ -467,6 +468,14 @@ def probe_empty(grid, block):
 def probe_stream(src, grid, block, sink):
     _check(lib().st_probe_stream(C.c_void_p(src.data_ptr()), src.numel() * src.element_size(), int(grid), int(block),
                                  _dev_f32(sink, "sink"), _stream()), "st_probe_stream")
+
+
+def probe_mfma_f32(valu, iters, sink):
+    """256 x 512 threads repeat `iters` times: `valu` (0 or 13) cross-lane multiplies, then 23 MFMAs 16x16x4 (fp32).
+    Returns the flops the launch performs on the matrix cores."""
+    _expect(sink, 256 * 512, "sink", at_least=True)
+    _check(lib().st_probe_mfma_f32(int(valu), int(iters), _dev_f32(sink, "sink"), _stream()), "st_probe_mfma_f32")
+    return 256 * 8 * int(iters) * 23 * 2048
 
 
 # ---- descriptor-driven structures -------------------------------------------------------
