@@ -419,6 +419,10 @@ __global__ __launch_bounds__((NS >= 4 ? 16 : 4 * NS) * 64) void ttm_oneshot_kern
 #pragma unroll
         for (u32 s = 0; s < SPW; ++s) a[t][s] = ap[4u * s];
     }
+    // every request of the wave is issued before its first MFMA (left to itself the compiler moves the requests
+    // of the later tiles down between the MFMAs of the earlier ones, and their latency then adds to the MFMA time
+    // instead of running under it)
+    __builtin_amdgcn_sched_barrier(0);
     // all MFMAs first, slot after slot as the rows arrive (each slot has an exchange buffer of its own), then ONE
     // barrier, then the additions: no wave waits for another before its last MFMA
 #pragma unroll
@@ -440,7 +444,8 @@ __global__ __launch_bounds__((NS >= 4 ? 16 : 4 * NS) * 64) void ttm_oneshot_kern
 #pragma unroll
             for (int c = 0; c < CT; ++c)
                 *reinterpret_cast<f32x4 *>(buf + ((size_t)(wave * CT + (u32)c) * 64u + lane) * 4u) = acc[c];
-        } else if (xrt < rtiles) {                       // workgroup-uniform: one column tile, chosen by selects
+        } else {                                         // one column tile, chosen by selects (a workgroup without a
+                                                         // unit multiplies clamped rows; its result is never read)
             f32x4 acc = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (u32 s = 0; s < SPW; ++s) {
