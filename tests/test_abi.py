@@ -59,6 +59,16 @@ def test_null_and_shape_errors():
     assert L.st_unrank_device(6, 4, 0, 0, 1, P, None) == SHAPE
     assert L.st_unrank_device(5, 4, 0, 34, 2, P, None) == SHAPE
     assert L.st_unrank_device(3, 4, 0, 19, 2, P, None) == SHAPE
+    # measurement support: shapes are checked before anything is launched
+    assert L.st_probe_empty(0, 64, None) == SHAPE
+    assert L.st_probe_empty(4, 2048, None) == SHAPE
+    assert L.st_probe_stream(None, 1024, 4, 64, P, None) == NULL
+    assert L.st_probe_stream(P, 8, 4, 64, P + 0x1000, None) == SHAPE
+    assert L.st_probe_stream(P + 4, 1024, 4, 64, P + 0x1000, None) == ALIGN
+    assert L.st_probe_stream(P, 1 << 30, 4, 64, P + 0x40000000, None) == UNSUPPORTED      # more than 32 loads per thread
+    assert L.st_probe_mfma_f32(0, 10, None, None) == NULL
+    assert L.st_probe_mfma_f32(5, 10, P, None) == SHAPE
+    assert L.st_probe_mfma_f32(13, 0, P, None) == SHAPE
 
 
 def test_alignment_overlap_workspace_errors():
