@@ -829,3 +829,55 @@ def test_moment_calls_can_be_captured(st, oracle, order, n, N):
         g.replay()
         torch.cuda.synchronize()
         assert torch.equal(Sc, want), (order, n, rep)
+
+
+def test_whole_step_can_be_captured(st, oracle):
+    """The six calls of one step (both MTTKRP paths, the one-pass BATAX, the one-shot TTM, the third moment and
+    its reconstruction) recorded into ONE HIP graph and replayed three times on changing inputs, with eager work
+    and synchronisations between the replays: every output of every replay equals the eager result bit for bit
+    (all reductions are in a fixed order), and the first replay is also compared with the oracle."""
+    import torch
+    say("graph capture of a whole step (small shapes)")
+    n1, R1, n2, nb, w, nl, R3, n4, R4, N, n5 = 64, 16, 1000, 96, 3, 512, 64, 96 + 16, 64, 9000, 64
+    pairs = oracle.count_band(nb, w)
+    def inputs(seed):
+        u = lambda k, c: dev(W.uniform(seed * 16 + k, c))
+        return dict(T1=u(0, oracle.count_sym3(n1)), B1=u(1, n1 * R1).reshape(n1, R1), Ap=u(2, oracle.count_sym2(n2)), x=u(3, n2),
+                    T3=u(4, pairs * nl).reshape(pairs, nl), U=u(5, nl * R3).reshape(nl, R3), T4=u(6, oracle.count_sym3(n4)),
+                    B4=dev(W.normal(seed * 16 + 7, n4 * R4, std=0.1).reshape(n4, R4)), X=dev(W.normal(seed * 16 + 8, N * n5).reshape(N, n5)))
+    buf = inputs(700)
+    f32 = dict(dtype=torch.float32, device="cuda")
+    out = dict(M1=torch.empty((n1, R1), **f32), y=torch.empty(n2, **f32), Yc=torch.empty((pairs, R3), **f32),
+               M4=torch.empty((n4, R4), **f32), Sc=torch.empty(oracle.count_sym3(n5), **f32), S=torch.empty((n5,) * 3, **f32))
+    wsb = max(st.workspace_bytes("mttkrp_sym3", n=n1, R=R1), st.workspace_bytes("batax_utri", n=n2),
+              st.workspace_bytes("ttm_band", n=nb, w=w, nl=nl, R=R3), st.workspace_bytes("mttkrp_sym3", n=n4, R=R4),
+              st.workspace_bytes("moment3_sym", N=N, n=n5), 16)
+    def step(o, ws):
+        st.mttkrp_sym3(buf["T1"], buf["B1"], M=o["M1"], ws=ws)
+        st.batax_utri(buf["Ap"], buf["x"], 0.5, y=o["y"], ws=ws)
+        st.ttm_band(buf["T3"], buf["U"], nb, w, Yc=o["Yc"], ws=ws)
+        st.mttkrp_sym3(buf["T4"], buf["B4"], M=o["M4"], ws=ws)
+        st.moment3_sym(buf["X"], Sc=o["Sc"], ws=ws)
+        st.expand_sym(o["Sc"], n5, 3, S=o["S"])
+    ws = torch.empty(wsb, dtype=torch.uint8, device="cuda")
+    step(out, ws)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step(out, ws)
+    ws2 = torch.empty(wsb, dtype=torch.uint8, device="cuda")
+    for rep in range(3):
+        for k, v in inputs(701 + rep).items():
+            buf[k].copy_(v)
+        want = {k: torch.empty_like(v) for k, v in out.items()}
+        step(want, ws2)                                    # eager, its own outputs and workspace
+        torch.cuda.synchronize()
+        for v in out.values():
+            v.fill_(float("nan"))
+        g.replay()
+        torch.cuda.synchronize()
+        for k in out:
+            assert torch.equal(out[k], want[k]), (k, rep)
+        if rep == 0:
+            check(out["M4"].cpu().numpy(), oracle.mttkrp_sym3(buf["T4"].cpu().numpy(), buf["B4"].cpu().numpy()), "captured mttkrp")
+            check(out["y"].cpu().numpy(), oracle.batax_utri(buf["Ap"].cpu().numpy(), buf["x"].cpu().numpy(), 0.5), "captured batax")
