@@ -401,16 +401,11 @@ __global__ __launch_bounds__((NS >= 4 ? 16 : 4 * NS) * 64) void ttm_oneshot_kern
     const u32 xrt = FULL * G + blockIdx.x / CT, xc = blockIdx.x % CT;
 
     // B operands: MFMA t of step s, lane (k = lane/16, n = lane%16), column tile c: U(l, CT n + c), l = LW w + 16 s + 4 k + t
-    cols<CT> u[SPW][4];
-    {
-        const float *up = U + (size_t)(wave * LW + 4u * lq) * R + CT * lrow;
-#pragma unroll
-        for (u32 s = 0; s < SPW; ++s)
-#pragma unroll
-            for (u32 t = 0; t < 4; ++t) u[s][t] = load_cols<CT>(up + (size_t)(16u * s + t) * R);
-    }
     // A operands: lane (row = lane%16, k = lane/16) takes T(row, LW w + 16 s + 4 k .. +3)
+    // Request order: the rows of the first slot (cold, the longest latency of the launch), then the slice of U (the
+    // same for every workgroup, so it comes from L2), then the rows of the other slots.
     float4 a[TT][SPW];
+    cols<CT> u[SPW][4];
 #pragma unroll
     for (int t = 0; t < TT; ++t) {
         const u32 rt = t < FULL ? blockIdx.x + G * (u32)t : xrt;
@@ -418,6 +413,15 @@ __global__ __launch_bounds__((NS >= 4 ? 16 : 4 * NS) * 64) void ttm_oneshot_kern
         const float4 *ap = reinterpret_cast<const float4 *>(Tc + (size_t)grow * nl + wave * LW) + lq;
 #pragma unroll
         for (u32 s = 0; s < SPW; ++s) a[t][s] = ap[4u * s];
+        if (t == 0) {
+            __builtin_amdgcn_sched_barrier(0);
+            const float *up = U + (size_t)(wave * LW + 4u * lq) * R + CT * lrow;
+#pragma unroll
+            for (u32 s = 0; s < SPW; ++s)
+#pragma unroll
+                for (u32 q = 0; q < 4; ++q) u[s][q] = load_cols<CT>(up + (size_t)(16u * s + q) * R);
+            __builtin_amdgcn_sched_barrier(0);
+        }
     }
     // every request of the wave is issued before its first MFMA (left to itself the compiler moves the requests
     // of the later tiles down between the MFMAs of the earlier ones, and their latency then adds to the MFMA time
