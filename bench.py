@@ -497,6 +497,16 @@ def main():
             ("desc_moment_near3_N2e6_n64_w8", lambda: dnear.moment(X, Sc=Scn),
              dict(flops=N5 * 2 * near_count, bytes=4 * (N5 * n5 + near_count), bound="alu")),
         ]
+        # the kernel table's MTTKRP generated for a sparsity structure no hand-written kernel has: the tetrahedron
+        # i <= j <= l as a pattern of non-zeros (not a symmetry), 256 indices, 64 columns
+        nm, Rm = 256, 64
+        dtet = st.Descriptor("B(i,j,l): (0<=i<n)*(i<=j<n)*(j<=l<n)", (nm, nm, nm), None, n=nm)
+        Bm = torch.randn(dtet.count, **f32)
+        Cm, Dm, Am = torch.randn((nm, Rm), **f32), torch.randn((nm, Rm), **f32), torch.empty((nm, Rm), **f32)
+        extra += [
+            ("desc_mttkrp_tetra_n256_R64", lambda: dtet.mttkrp(Bm, Cm, Dm, A=Am),
+             dict(flops=3 * Rm * dtet.count, bytes=4 * (dtet.count + 3 * nm * Rm), bound="alu")),
+        ]
         next_rows = {}
         for name, f, w in extra:
             f()

@@ -337,6 +337,20 @@ st_status st_desc_thp(st_desc *desc, const void *table, const float *Bc, const f
                       void *stream);
 st_status st_desc_expand(st_desc *desc, const void *table, const float *Tc, float *T, void *stream);
 
+/* The kernel table's MTTKRP for ANY sparsity structure of an order-3 operand
+ * ("Tensor Kernels": A(i,j) := B(i,k,l) * C(k,j) * D(l,j)), evaluated over the
+ * unique set only:
+ *     A(x0, r) = sum over the stored (x1, x2) of row x0 of Bc(rank(x)) * C(x1, r) * D(x2, r)
+ * Bc is the packed operand (st_desc_count floats), C is dims[1] x R, D is
+ * dims[2] x R, A is dims[0] x R (all row-major, DEVICE, 16-byte aligned; rows
+ * of A without a stored entry are written as zeros).  Vector-ALU kernel, one
+ * workgroup per output row and 16 columns, sums in a fixed order.
+ * ST_ERR_UNSUPPORTED for orders other than 3 and for descriptors with a
+ * redundancy map (their operand has entries outside the unique set; the
+ * fully symmetric case is st_mttkrp_sym3). */
+st_status st_desc_mttkrp(st_desc *desc, const void *table, const float *Bc, const float *C, const float *D,
+                         float *A, int R, void *stream);
+
 /* Structure inference for an element-wise product  A(x) := M(x) * V(x)  of two
  * structured operands of the same shape ("Structure Inference", general rule for
  * products):  A_U = M_U*V_U + M_U*V_R + M_R*V_U,  A_R = M_R*V_R, followed by the

@@ -75,6 +75,7 @@ SIGNATURES = {
     "st_desc_compile": (_I32, [_P]),
     "st_desc_list": (_I32, [_P, _P, _P, _P]),
     "st_desc_thp": (_I32, [_P, _P, _P, _P, _P, _P]),
+    "st_desc_mttkrp": (_I32, [_P, _P, _P, _P, _P, _P, _I32, _P]),
     "st_desc_expand": (_I32, [_P, _P, _P, _P, _P]),
     "st_desc_ttm": (_I32, [_P, _P, _P, _P, _I32, _P]),
     "st_desc_product": (_I32, [_P, _P, _P]),
@@ -558,6 +559,24 @@ class Descriptor:
         self._call(lib().st_desc_thp(self._h, self._tab(), _dev_f32(Bc, "Bc"), _dev_f32(Cd, "C"),
                                      _dev_f32(Ac, "Ac"), _stream()), "st_desc_thp")
         return Ac[:self.count]
+
+    def mttkrp(self, Bc, Cm, Dm, A=None):
+        """A(x0, r) = sum over the stored (x1, x2) of Bc(rank(x)) C(x1, r) D(x2, r) (order 3, no redundancy map)."""
+        torch = _torch()
+        _expect(Bc, self.count, "Bc", at_least=True)
+        if len(self.dims) != 3:
+            raise StructTensorError(6, "st_desc_mttkrp (order 3 only)")
+        _matrix(Cm, "C")
+        _matrix(Dm, "D")
+        R = int(Cm.shape[1])
+        _expect(Cm, self.dims[1] * R, "C")
+        _expect(Dm, self.dims[2] * R, "D")
+        if A is None:
+            A = torch.empty((self.dims[0], R), dtype=torch.float32, device=Cm.device)
+        _expect(A, self.dims[0] * R, "A")
+        self._call(lib().st_desc_mttkrp(self._h, self._tab(), _dev_f32(Bc, "Bc"), _dev_f32(Cm, "C"), _dev_f32(Dm, "D"),
+                                        _dev_f32(A, "A"), R, _stream()), "st_desc_mttkrp")
+        return A
 
     def expand(self, Tc, T=None):
         torch = _torch()

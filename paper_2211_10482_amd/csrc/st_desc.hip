@@ -218,7 +218,7 @@ struct Desc {
     i64 mbs = 0, ntiles = 0, mnp = 0;
     std::string nest, source;
     std::mutex mu;
-    struct Loaded { hipModule_t mod; hipFunction_t fn[6]; };   // list, thp, expand, gather, moment, moment_reduce
+    struct Loaded { hipModule_t mod; hipFunction_t fn[7]; };   // list, thp, expand, gather, moment, moment_reduce, mttkrp
     std::map<int, Loaded> modules;               // per device
     std::string error;
 };
@@ -569,6 +569,58 @@ void build_source(Desc &D)
         s += "    const float v = (" + at + ") ? st_value(tab, Tc, " + xs + ") : 0.f;\n";
     }
     s += "    out[p] = scale ? scale[p] * v : v;\n}\n";
+    if (d == 3) {
+        // MTTKRP of the kernel table over the unique set: A(x0, r) = sum over the stored (x1, x2) of row x0 of
+        // Bc(rank(x)) * C(x1, r) * D(x2, r).  One workgroup per output row x0 and block of 16 columns r; its
+        // waves take the runs (x1) of the row in turn, the lanes the entries of a run; sixteen accumulators per
+        // thread, added over the threads in two levels, each in a fixed order.  Written so that a
+        // launch with any number of threads per workgroup (also one) computes the same sums.
+        s += "#define ST_MK_COLS 16\n#define ST_MK_MAXT 1024\n#define ST_MK_PARTS 16\n";
+        // sixteen consecutive values of a row of C or D (zeros past the last column); 16-byte loads when the rows
+        // are 16-byte aligned (R a multiple of 4)
+        s += "static __device__ __forceinline__ void st_mk_row(float (&o)[ST_MK_COLS], const float *__restrict__ p, int left, bool v4)\n{\n";
+        s += "    if (v4) {\n        for (int q = 0; q < ST_MK_COLS / 4; ++q) {\n";
+        s += "            float4 t = make_float4(0.f, 0.f, 0.f, 0.f);\n";
+        s += "            if (4 * q < left) t = *reinterpret_cast<const float4 *>(p + 4 * q);\n";
+        s += "            o[4 * q] = t.x; o[4 * q + 1] = t.y; o[4 * q + 2] = t.z; o[4 * q + 3] = t.w;\n        }\n";
+        s += "    } else {\n        for (int c = 0; c < ST_MK_COLS; ++c) o[c] = c < left ? p[c] : 0.f;\n    }\n}\n";
+        s += "extern \"C\" __global__ void st_gen_mttkrp(const int *__restrict__ tab, const float *__restrict__ Bc,\n"
+             "                                         const float *__restrict__ C, const float *__restrict__ Dm,\n"
+             "                                         float *__restrict__ A, int R)\n{\n";
+        s += "    __shared__ float st_red[ST_MK_COLS][ST_MK_MAXT];\n";
+        s += "    __shared__ float st_red2[ST_MK_COLS][ST_MK_PARTS];\n";
+        s += "    const int tid = threadIdx.x, nt = blockDim.x, L = nt < 64 ? nt : 64, ln = tid % L, wv = tid / L, nw = nt / L;\n";
+        s += "    const int x0 = blockIdx.x, r0 = blockIdx.y * ST_MK_COLS;\n";
+        s += "    const bool v4 = (R & 3) == 0;\n";
+        s += "    float acc[ST_MK_COLS];\n    for (int c = 0; c < ST_MK_COLS; ++c) acc[c] = 0.f;\n";
+        s += "    if (x0 >= st_lo0() && x0 <= st_hi0()) {\n";
+        s += "        for (int x1 = st_lo1(x0) + wv; x1 <= st_hi1(x0); x1 += nw) {\n";
+        s += "            const int lo = st_lo2(x0, x1), hi = st_hi2(x0, x1);\n";
+        s += "            if (lo > hi) continue;\n";
+        s += "            const int start = tab[x0 * ST_DIM1 + x1];\n";
+        s += "            float cr[ST_MK_COLS];\n";
+        s += "            st_mk_row(cr, C + (long long)x1 * R + r0, R - r0, v4);\n";
+        s += "#pragma unroll 2\n";
+        s += "            for (int x2 = lo + ln; x2 <= hi; x2 += L) {\n";
+        s += "                const float b = Bc[start + x2 - lo];\n";
+        s += "                float dr[ST_MK_COLS];\n";
+        s += "                st_mk_row(dr, Dm + (long long)x2 * R + r0, R - r0, v4);\n";
+        s += "                for (int c = 0; c < ST_MK_COLS; ++c) acc[c] += (b * cr[c]) * dr[c];\n";
+        s += "            }\n        }\n    }\n";
+        s += "    for (int c = 0; c < ST_MK_COLS; ++c) st_red[c][tid] = acc[c];\n";
+        s += "    __syncthreads();\n";
+        // two levels, both in a fixed order: sixteen parts of consecutive threads per column, then the parts
+        s += "    const int per = (nt + ST_MK_PARTS - 1) / ST_MK_PARTS;\n";
+        s += "    for (int q = tid; q < ST_MK_COLS * ST_MK_PARTS; q += nt) {\n";
+        s += "        const int c = q / ST_MK_PARTS, part = q % ST_MK_PARTS;\n";
+        s += "        float v = 0.f;\n";
+        s += "        for (int t = part * per; t < (part + 1) * per && t < nt; ++t) v += st_red[c][t];\n";
+        s += "        st_red2[c][part] = v;\n    }\n";
+        s += "    __syncthreads();\n";
+        s += "    for (int c = tid; c < ST_MK_COLS && r0 + c < R; c += nt) {\n";
+        s += "        float v = 0.f;\n        for (int part = 0; part < ST_MK_PARTS; ++part) v += st_red2[c][part];\n";
+        s += "        A[(long long)x0 * R + r0 + c] = v;\n    }\n}\n";
+    }
     if (D.ntiles > 0) {
         // moment accumulation over the unique set: Sc(rank(x)) (+)= sum_s prod_v X(s, x_v).  One lane per block
         // tuple with its ST_MBS^d = 64 accumulators in registers, sample rows staged through a double-buffered
@@ -914,13 +966,16 @@ st_status module_for(Desc &D, Desc::Loaded &out)
     if (hipModuleLoadData(&L.mod, code.data()) != hipSuccess) { D.error = "hipModuleLoadData failed"; return ST_ERR_LAUNCH; }
     const char *names[6] = {"st_gen_list", "st_gen_thp", "st_gen_expand", "st_gen_gather", "st_gen_moment",
                             "st_gen_moment_reduce"};
-    L.fn[4] = L.fn[5] = nullptr;
-    for (int q = 0; q < (D.ntiles > 0 ? 6 : 4); ++q)
-        if (hipModuleGetFunction(&L.fn[q], L.mod, names[q]) != hipSuccess) {
+    L.fn[4] = L.fn[5] = L.fn[6] = nullptr;
+    for (int q = 0; q < 7; ++q) {
+        if ((q == 4 || q == 5) && D.ntiles == 0) continue;      // moment kernels: equal extents only
+        if (q == 6 && D.d != 3) continue;                       // MTTKRP: order 3 only
+        if (hipModuleGetFunction(&L.fn[q], L.mod, q == 6 ? "st_gen_mttkrp" : names[q]) != hipSuccess) {
             (void)hipModuleUnload(L.mod);
-            D.error = std::string("generated kernel missing: ") + names[q];
+            D.error = std::string("generated kernel missing: ") + (q == 6 ? "st_gen_mttkrp" : names[q]);
             return ST_ERR_LAUNCH;
         }
+    }
     D.modules[dev] = L;
     out = L;
     return ST_OK;
@@ -1029,6 +1084,25 @@ st_status st_desc_thp(st_desc *desc, const void *table, const float *Bc, const f
     if (overlap(Ac, pb, Bc, pb) || overlap(Ac, pb, C, cb)) return ST_ERR_SHAPE;
     void *args[] = {&table, &Bc, &C, &Ac};
     return launch_generated(*D, 1, (unsigned)((D->nruns + 3) / 4), args, (hipStream_t)stream);
+}
+
+st_status st_desc_mttkrp(st_desc *desc, const void *table, const float *Bc, const float *C, const float *Dm, float *A,
+                         int R, void *stream)
+{
+    if (!desc || !table || !Bc || !C || !Dm || !A) return ST_ERR_NULL;
+    Desc *D = reinterpret_cast<Desc *>(desc);
+    if (D->source.empty() || R < 1) return ST_ERR_SHAPE;
+    // order 3, sparsity structures only: with a redundancy map the operand has entries outside its unique set
+    if (D->d != 3 || D->red_sort || !D->red.empty()) return ST_ERR_UNSUPPORTED;
+    if ((int64_t)R * std::max(D->dims[1], D->dims[2]) > ((int64_t)1 << 31) || D->dims[0] > 0x7fffffff) return ST_ERR_UNSUPPORTED;
+    if (!aligned16(table) || !aligned16(Bc) || !aligned16(C) || !aligned16(Dm) || !aligned16(A)) return ST_ERR_ALIGN;
+    const size_t bb = (size_t)D->count * 4, cb = (size_t)D->dims[1] * R * 4, db = (size_t)D->dims[2] * R * 4,
+                 ab = (size_t)D->dims[0] * R * 4;
+    if (overlap(A, ab, Bc, bb) || overlap(A, ab, C, cb) || overlap(A, ab, Dm, db)) return ST_ERR_SHAPE;
+    void *args[] = {&table, &Bc, &C, &Dm, &A, &R};
+    // the runs of a row are a serial chain of dependent loads per wave: long rows get sixteen waves
+    const unsigned threads = D->dims[1] >= 64 ? 1024u : 256u;
+    return launch_generated(*D, 6, (unsigned)D->dims[0], args, (hipStream_t)stream, (unsigned)((R + 15) / 16), threads);
 }
 
 st_status st_desc_ttm(st_desc *desc, const float *Bc, const float *U, float *Ac, int R, void *stream)

@@ -6,6 +6,7 @@
 //   argv: dir count box order nruns last_dim [N]  (dir holds table.i32, bc.f32 [count], c.f32 [box], x.f32 [N*n])
 //   writes list.i32 [count*order], thp.f32 [count], expand.f32 [box] (expansion of bc.f32), moment.f32 [count]
 //   when dir holds gather.i32 ([g][order] dense positions; gather_scale.f32 [g] optional): gather.f32 [g]
+//   when dir holds mk_r.i32 (order 3): mttkrp.f32 [dim0][R] from mk_c.f32 [dim1][R] and mk_d.f32 [dim2][R]
 #include <hip/hip_runtime.h>
 // LDS of the generated moment kernels: the dynamic chunk buffer is a global here, static arrays keep their
 // zero initialisation (the reduce kernel reads rows of its array that other threads of the block wrote)
@@ -79,6 +80,19 @@ int main(int argc, char **argv)
                                   (long long)g, scale.empty() ? (const float *)nullptr : scale.data(), out.data());
         wr(dir + "/gather.f32", out);
     }
+#if ST_D == 3
+    // the generated MTTKRP, launched with one thread per workgroup (its sums over the threads of a workgroup need a
+    // barrier): mk_r.i32 holds R, mk_c.f32 is [dim1][R], mk_d.f32 is [dim2][R]; writes mttkrp.f32 [dim0][R]
+    if (FILE *f = fopen((dir + "/mk_r.i32").c_str(), "rb")) {
+        fclose(f);
+        const int R = rd<int>(dir + "/mk_r.i32", 1)[0];
+        std::vector<float> Cm = rd<float>(dir + "/mk_c.f32", (size_t)ST_DIM1 * R), Dm = rd<float>(dir + "/mk_d.f32", (size_t)ST_DIM2 * R);
+        std::vector<float> A((size_t)ST_DIM0 * R, -7.f);
+        hipLaunchKernelGGL(st_gen_mttkrp, dim3(ST_DIM0, (unsigned)((R + 15) / 16)), dim3(1), 0, 0, tab.data(), bc.data(), Cm.data(),
+                           Dm.data(), A.data(), R);
+        wr(dir + "/mttkrp.f32", A);
+    }
+#endif
     wr(dir + "/list.i32", list);
     wr(dir + "/thp.f32", thp);
     wr(dir + "/expand.f32", ex);

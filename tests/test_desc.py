@@ -180,6 +180,14 @@ def test_generated_kernels_on_the_cpu(descs, oracle, tmp_path, name):
     N = 7
     X = W.normal(703, N * dims[0]).reshape(N, dims[0])
     X.tofile(str(tmp_path / "x.f32"))
+    has_mttkrp = len(dims) == 3 and red is None          # the kernel table's MTTKRP: order 3, sparsity only
+    R = 24 if name in ("band", "diag") else 21          # two column blocks, the second one ragged; 24: 16-byte row loads
+    if has_mttkrp:
+        assert "st_gen_mttkrp" in d.source
+        Cm, Dm = W.uniform(704, dims[1] * R).reshape(dims[1], R), W.uniform(705, dims[2] * R).reshape(dims[2], R)
+        np.array([R], dtype=np.int32).tofile(str(tmp_path / "mk_r.i32"))
+        Cm.tofile(str(tmp_path / "mk_c.f32"))
+        Dm.tofile(str(tmp_path / "mk_d.f32"))
     r = subprocess.run([exe, str(tmp_path), str(d.count), str(box), str(len(dims)), str(d.runs), str(dims[-1])]
                        + ([str(N)] if has_moment else []), capture_output=True, text=True, timeout=300)
     assert r.returncode == 0 and "rc=0" in r.stdout, r.stderr[-3000:]
@@ -190,6 +198,15 @@ def test_generated_kernels_on_the_cpu(descs, oracle, tmp_path, name):
     ex = np.fromfile(str(tmp_path / "expand.f32"), dtype=np.float32).reshape(dims)
     ref = oracle.struct_expand(Bc, dims, pred, unique_of)
     assert np.array_equal(ex.view(np.uint32), ref.view(np.uint32))
+    if has_mttkrp:
+        # against the dense definition on the zero-filled operand (the C oracle), row by row
+        got = np.fromfile(str(tmp_path / "mttkrp.f32"), dtype=np.float32).reshape(dims[0], R)
+        Bd = np.zeros(dims, dtype=np.float32)
+        Bd[tuple(lst[:, v].astype(np.int64) for v in range(3))] = Bc
+        refa = oracle.mttkrp_full(Bd, Cm, Dm)
+        assert float(np.abs(got - refa).max()) <= 1e-5 * max(float(np.abs(refa).max()), 1.0)
+        empty_rows = ~Bd.reshape(dims[0], -1).any(axis=1)
+        assert not got[empty_rows].any()                  # rows without a stored entry are written as zeros
     if has_moment:
         mom = np.fromfile(str(tmp_path / "moment.f32"), dtype=np.float32)
         refm = oracle.struct_moment(X, dims, pred)

@@ -129,6 +129,77 @@ def test_descriptor_ttm_small(st, oracle, name, R):
     d.close()
 
 
+# the kernel table's MTTKRP over ANY sparsity structure of an order-3 operand, generated from the descriptor
+MTTKRP_CASES = {
+    # name: (unique set, dims, parameters, predicate, R)
+    "band": ("B(i,j,l): (0<=i<n)*(i-w<=j<=i+w)*(0<=l<m)", (40, 40, 33), dict(n=40, w=3, m=33), lambda i, j, l: abs(i - j) <= 3, 21),
+    "diag": ("B(i,j,l): (0<=i<n)*(i=j)*(0<=l<m)", (50, 50, 70), dict(n=50, m=70), lambda i, j, l: i == j, 64),
+    "fixed_i": ("B(i,j,l): (i=I)*(0<=j<n)*(0<=l<m)", (9, 30, 65), dict(I=4, n=30, m=65), lambda i, j, l: i == 4, 16),
+    "fixed_j": ("B(i,j,l): (0<=i<n)*(j=J)*(0<=l<m)", (37, 12, 129), dict(J=7, n=37, m=129), lambda i, j, l: j == 7, 48),
+    "upper_cube": ("B(i,j,l): (0<=i<n)*(i<=j<n)*(0<=l<m)", (33, 33, 40), dict(n=33, m=40), lambda i, j, l: i <= j, 5),
+    # a structure on all three indices, which no hand-written kernel here has: the tetrahedron as a SPARSITY pattern
+    "tetra": ("B(i,j,l): (0<=i<n)*(i<=j<n)*(j<=l<n)", (30, 30, 30), dict(n=30), lambda i, j, l: i <= j <= l, 33),
+    "staircase": ("B(i,j,l): (0<=i<n)*(0<=j<=i)*(i-j<=l<m)", (25, 25, 31), dict(n=25, m=31), lambda i, j, l: j <= i and l >= i - j, 17),
+}
+
+
+@pytest.mark.parametrize("name", sorted(MTTKRP_CASES))
+def test_descriptor_mttkrp_small(st, oracle, name):
+    """A(i,r) = sum_kl B(i,k,l) C(k,r) D(l,r) over the unique set only, against the dense definition (C oracle) on
+    the zero-filled operand; rows without a stored entry come back as zeros."""
+    say("descriptor mttkrp", name)
+    text, dims, params, pred, R = MTTKRP_CASES[name]
+    d = st.Descriptor(text, dims, None, **params)
+    lst = oracle.struct_enumerate(dims, pred)
+    assert d.count == lst.shape[0]
+    Bc = W.uniform(761, d.count)
+    Cm, Dm = W.uniform(762, dims[1] * R).reshape(dims[1], R), W.uniform(763, dims[2] * R).reshape(dims[2], R)
+    B = np.zeros(dims, dtype=np.float32)
+    B[tuple(lst[:, v].astype(np.int64) for v in range(3))] = Bc
+    ref = oracle.mttkrp_full(B, Cm, Dm)
+    import torch
+    A = torch.full((dims[0], R), float("nan"), device="cuda")
+    got = d.mttkrp(dev(Bc), dev(Cm), dev(Dm), A=A).cpu().numpy()
+    assert float(np.abs(got - ref).max()) <= 1e-4 * float(np.abs(ref).max())
+    empty = ~B.reshape(dims[0], -1).any(axis=1)
+    assert not got[empty].any()
+    again = d.mttkrp(dev(Bc), dev(Cm), dev(Dm)).cpu().numpy()
+    assert np.array_equal(got.view(np.uint32), again.view(np.uint32))          # fixed summation order
+    d.close()
+
+
+def test_descriptor_mttkrp_against_handwritten_fixed_k(st, oracle):
+    """The kernel table's "fixed j" structure at full size (n = 512): the generated kernel against the hand-written
+    st_mttkrp_fixed, and sampled rows against the oracle."""
+    n, nl, R, K = 512, 512, 64, 100
+    say("descriptor mttkrp fixed k n=%d against st_mttkrp_fixed" % n)
+    d = st.Descriptor("B(i,k,l): (0<=i<n)*(k=K)*(0<=l<m)", (n, n, nl), None, n=n, K=K, m=nl)
+    Bc = W.uniform(771, n * nl).reshape(n, nl)
+    Cm, Dm = W.uniform(772, n * R).reshape(n, R), W.uniform(773, nl * R).reshape(nl, R)
+    got = d.mttkrp(dev(Bc.reshape(-1)), dev(Cm), dev(Dm)).cpu().numpy()
+    hand = st.mttkrp_fixed(st.MTTKRP_FIXED_K, dev(Bc), dev(Cm), dev(Dm), n, fixed_k=K).cpu().numpy()
+    assert float(np.abs(got - hand).max()) <= 1e-4 * float(np.abs(hand).max())
+    rows = np.array([0, 1, 77, 255, 256, 511])
+    ref = (Bc[rows].astype(np.float64) @ Dm.astype(np.float64)) * Cm[K].astype(np.float64)
+    assert float(np.abs(got[rows] - ref).max()) <= 1e-4 * float(np.abs(ref).max())
+    d.close()
+
+
+def test_descriptor_mttkrp_refuses_what_it_does_not_cover(st):
+    import torch
+    z = torch.zeros(4096, device="cuda")
+    d = st.Descriptor("T(i,j,k): (0<=i<n)*(i<=j<n)*(j<=k<n)", (8, 8, 8), "sort", n=8)        # redundancy map
+    with pytest.raises(st.StructTensorError) as e:
+        d.mttkrp(z[:d.count], z[:64].reshape(8, 8), z[:64].reshape(8, 8))
+    assert e.value.status == 6
+    d.close()
+    d = st.Descriptor("S(i,j): (0<=i<=j<n)", (8, 8), None, n=8)                               # order 2
+    with pytest.raises(st.StructTensorError) as e:
+        d.mttkrp(z[:d.count], z[:64].reshape(8, 8), z[:64].reshape(8, 8))
+    assert e.value.status == 6
+    d.close()
+
+
 def test_descriptor_ttm_needs_a_free_last_variable(st):
     d = st.Descriptor("T(i,j,k): (0<=i<n)*(i<=j<n)*(j<=k<n)", (8, 8, 8), "sort", n=8)
     import torch
