@@ -371,12 +371,35 @@ st_status st_desc_product(const st_desc *m, const st_desc *v, st_desc **out);
  * with T(x) the stored value on the unique set, the value at the unique index
  * the redundancy map names elsewhere, 0 where neither applies or x lies
  * outside the dense extents (Property 5, evaluated only where asked).  idx is
- * DEVICE int32 [count][order] (e.g. st_desc_list of a product descriptor), Tc
- * the packed operand of `desc`, scale NULL or DEVICE fp32 [count].  Two calls
- * evaluate an element-wise product of two structured operands on the unique
- * set of the result only:  A_C = gather(V, list(A), scale = gather(M, list(A))). */
+ * DEVICE int32 with `idx_stride` ints per position, of which the `order` ints
+ * from `idx_offset` on are the position (idx_stride = order, idx_offset = 0
+ * for a plain [count][order] list such as st_desc_list gives; an outer
+ * product reads the two halves of its own list: ST_ERR_SHAPE unless
+ * 0 <= idx_offset and idx_offset + order <= idx_stride <= 64).  Tc is the
+ * packed operand of `desc`, scale NULL or DEVICE fp32 [count].  Two calls
+ * evaluate a product of two structured operands on the unique set of the
+ * result only:  A_C = gather(V, list(A), scale = gather(M, list(A))). */
 st_status st_desc_gather(st_desc *desc, const void *table, const float *Tc, const int32_t *idx, int64_t count,
-                         const float *scale, float *out, void *stream);
+                         int idx_stride, int idx_offset, const float *scale, float *out, void *stream);
+
+/* Structure inference for the tensor outer product  T(x, y) := M(x) * V(y)
+ * over disjoint index lists, the variables of V behind those of M, total order
+ * at most 4 ("Redundancy Map Inference", outer-product rule):
+ *     T_U = M_U * V_U,   T_R = M_U * V_R + M_R * V_U + M_R * V_R
+ * ('sort' maps of order 2 enter as the class-S term; of higher order:
+ * ST_ERR_UNSUPPORTED).  The values on T_U are two st_desc_gather calls on the
+ * two halves of st_desc_list(T). */
+st_status st_desc_outer(const st_desc *m, const st_desc *v, st_desc **out);
+
+/* Structure inference for the k-fold outer product of a VECTOR with itself,
+ * T(x_1..x_k) := v(x_1) * .. * v(x_k), k = 2..4 (the self-multiplication rule
+ * and its extension to higher degrees; the vector self-outer-product
+ * example): the unique set is v's range on every index and
+ * x_1 <= x_2 <= .. <= x_k, the redundancy map is `sort`.  These are the
+ * structures of the covariance terms M1, M2, M3 ("Tensor Structures"); with
+ * st_desc_moment they give the accumulation over samples.  ST_ERR_UNSUPPORTED
+ * for descriptors of order above 1 or with a redundancy map. */
+st_status st_desc_power(const st_desc *v, int k, st_desc **out);
 
 /* Moment accumulation over the unique set of a descriptor of order 2 or 3 whose
  * variables all range over the n <= 256 features of X (N x n, row-major):

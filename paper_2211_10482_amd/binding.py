@@ -79,7 +79,9 @@ SIGNATURES = {
     "st_desc_expand": (_I32, [_P, _P, _P, _P, _P]),
     "st_desc_ttm": (_I32, [_P, _P, _P, _P, _I32, _P]),
     "st_desc_product": (_I32, [_P, _P, _P]),
-    "st_desc_gather": (_I32, [_P, _P, _P, _P, _I64, _P, _P, _P]),
+    "st_desc_gather": (_I32, [_P, _P, _P, _P, _I64, _I32, _I32, _P, _P, _P]),
+    "st_desc_outer": (_I32, [_P, _P, _P]),
+    "st_desc_power": (_I32, [_P, _I32, _P]),
     "st_desc_moment_workspace": (_SZ, [_P, _I64]),
     "st_desc_moment": (_I32, [_P, _P, _P, _I64, _P, _I32, _P, _SZ, _P]),
     "st_probe_empty": (_I32, [_I32, _I32, _P]),
@@ -461,6 +463,16 @@ def hadamard_struct(dm, Mc, dv, Vc):
     return da, dv.gather(Vc, idx, scale=dm.gather(Mc, idx))
 
 
+def outer_struct(dm, Mc, dv, Vc):
+    """T(x, y) := M(x) * V(y) for two structured operands: the inferred descriptor of the result and its packed
+    values, from the two halves of the result's own index list."""
+    dt = dm.outer(dv)
+    if dt.count == 0:
+        return dt, _torch().empty(0, dtype=_torch().float32, device=Mc.device)
+    idx = dt.list().contiguous()
+    return dt, dv.gather(Vc, idx, scale=dm.gather(Mc, idx), offset=len(dm.dims))
+
+
 # ---- measurement support ----------------------------------------------------------------
 def probe_empty(grid, block):
     _check(lib().st_probe_empty(int(grid), int(block), _stream()), "st_probe_empty")
@@ -599,14 +611,34 @@ class Descriptor:
             raise StructTensorError(rc, "st_desc_product (%s)" % msg)
         return Descriptor(None, self.dims, _handle=h)
 
-    def gather(self, Tc, idx, scale=None, out=None):
-        """Values of the structured tensor at the dense positions idx ([count][order] int32), times scale."""
+    def _derived(self, rc, h, what, dims):
+        if rc != 0:
+            msg = lib().st_desc_error(h).decode() if h else ""
+            if h:
+                lib().st_desc_destroy(h)
+            raise StructTensorError(rc, "%s (%s)" % (what, msg))
+        return Descriptor(None, dims, _handle=h)
+
+    def outer(self, other):
+        """Descriptor of the tensor outer product T(x, y) = self(x) * other(y) (structure inference)."""
+        h = C.c_void_p()
+        return self._derived(lib().st_desc_outer(self._h, other._h, C.byref(h)), h, "st_desc_outer",
+                             tuple(self.dims) + tuple(other.dims))
+
+    def power(self, k):
+        """Descriptor of the k-fold outer product of a vector with itself: x_1 <= .. <= x_k, redundancy map sort."""
+        h = C.c_void_p()
+        return self._derived(lib().st_desc_power(self._h, int(k), C.byref(h)), h, "st_desc_power",
+                             tuple(self.dims) * int(k))
+
+    def gather(self, Tc, idx, scale=None, out=None, offset=0):
+        """Values of the structured tensor at the dense positions idx[:, offset:offset+order] (int32), times scale."""
         torch = _torch()
         if not (isinstance(idx, torch.Tensor) and idx.is_cuda and idx.dtype == torch.int32 and idx.is_contiguous()):
             raise TypeError("idx must be a contiguous int32 CUDA tensor")
-        if idx.dim() != 2 or idx.shape[1] != len(self.dims):
-            raise ValueError("idx must be [count][order]")
-        count = int(idx.shape[0])
+        if idx.dim() != 2 or offset < 0 or idx.shape[1] < offset + len(self.dims):
+            raise ValueError("idx must be [count][>= offset + order]")
+        count, stride = int(idx.shape[0]), int(idx.shape[1])
         _expect(Tc, self.count, "Tc", at_least=True)
         if scale is not None:
             _expect(scale, count, "scale", at_least=True)
@@ -614,7 +646,7 @@ class Descriptor:
             out = torch.empty(max(count, 4), dtype=torch.float32, device=Tc.device)
         _expect(out, count, "out", at_least=True)
         self._call(lib().st_desc_gather(self._h, self._tab(), _dev_f32(Tc, "Tc"), C.c_void_p(idx.data_ptr()), count,
-                                        _dev_f32(scale, "scale") if scale is not None else None,
+                                        stride, int(offset), _dev_f32(scale, "scale") if scale is not None else None,
                                         _dev_f32(out, "out"), _stream()), "st_desc_gather")
         return out[:count]
 

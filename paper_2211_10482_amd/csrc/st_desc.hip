@@ -556,14 +556,14 @@ void build_source(Desc &D)
     // zero, as in the reconstruction), optionally times a factor per position -- what an element-wise product
     // with another structured operand needs, evaluated only where the product's unique set says
     s += "extern \"C\" __global__ void st_gen_gather(const int *__restrict__ tab, const float *__restrict__ Tc,\n"
-         "                                         const int *__restrict__ idx, long long count,\n"
+         "                                         const int *__restrict__ idx, long long count, int stride, int offset,\n"
          "                                         const float *__restrict__ scale, float *__restrict__ out)\n{\n";
     s += "    const long long p = (long long)blockIdx.x * blockDim.x + threadIdx.x;\n    if (p >= count) return;\n";
     {
         std::string at;
         for (int v = 0; v < d; ++v) {
             const std::string xv = "x" + std::to_string(v);
-            s += "    const int " + xv + " = idx[p * ST_D + " + std::to_string(v) + "];\n";
+            s += "    const int " + xv + " = idx[p * stride + offset + " + std::to_string(v) + "];\n";
             at += std::string(v ? " && " : "") + xv + " >= 0 && " + xv + " < ST_DIM" + std::to_string(v);
         }
         s += "    const float v = (" + at + ") ? st_value(tab, Tc, " + xs + ") : 0.f;\n";
@@ -928,6 +928,115 @@ st_status infer_product(const Desc &M, const Desc &V, Desc &A)
     return finish(A);
 }
 
+// Tensor outer product T(x, y) := M(x) * V(y) over disjoint index lists ("Redundancy Map Inference", outer
+// product rule): T_U = M_U * V_U; T_R = M_U * V_R + M_R * V_U + M_R * V_R.  The variables of V follow those of M.
+// A term of V alone maps the V part and keeps the M part (and the other way round); where both parts are
+// redundant the first two lead outside the unique set and the combined term applies (the reconstruction tries
+// the terms in order and takes the first whose target is stored).
+static Bound shifted(const Bound &b, int by)
+{
+    Bound r;
+    r.c = b.c;
+    for (int u = 0; u < MAXD; ++u) r.coef[u] = 0;
+    for (int u = 0; u + by < MAXD; ++u) r.coef[u + by] = b.coef[u];
+    return r;
+}
+static Bound identity_map(int v)
+{
+    Bound r;
+    r.c = 0;
+    for (int u = 0; u < MAXD; ++u) r.coef[u] = u == v ? 1 : 0;
+    return r;
+}
+
+st_status infer_outer(const Desc &M, const Desc &V, Desc &A)
+{
+    const int dm = M.d, dv = V.d, d = dm + dv;
+    if (d > MAXD) { A.error = "the order of an outer product is limited to " + std::to_string(MAXD); return ST_ERR_UNSUPPORTED; }
+    if ((M.red_sort && dm != 2) || (V.red_sort && dv != 2)) {
+        A.error = "a 'sort' redundancy map of order above 2 is a sum of conditions: not supported in an outer product";
+        return ST_ERR_UNSUPPORTED;
+    }
+    A.d = d;
+    A.name = "T";
+    for (int v = 0; v < dm; ++v) { A.vars.push_back(M.vars[(size_t)v]); A.dims[v] = M.dims[v]; }
+    for (int v = 0; v < dv; ++v) {
+        std::string name = V.vars[(size_t)v];
+        while (std::find(A.vars.begin(), A.vars.end(), name) != A.vars.end()) name += "2";
+        A.vars.push_back(name);
+        A.dims[dm + v] = V.dims[v];
+    }
+    Desc Vs;                                              // V with its variables moved behind those of M
+    Vs.d = d;
+    for (int v = 0; v < dv; ++v) {
+        Vs.first[dm + v] = V.first[v];
+        Vs.last[dm + v] = V.last[v];
+        for (auto &b : V.lo[v]) Vs.lo[dm + v].push_back(shifted(b, dm));
+        for (auto &b : V.hi[v]) Vs.hi[dm + v].push_back(shifted(b, dm));
+    }
+    for (int v = 0; v < dm; ++v) { Vs.first[v] = 0; Vs.last[v] = M.dims[v] - 1; }
+    Vs.empty = V.empty;
+    add_box(A, M);                                        // (add_box walks S.d variables: the M part only)
+    add_box(A, Vs);
+    const std::vector<RedTerm> mr = terms_of(M), vr0 = terms_of(V);
+    std::vector<RedTerm> vr;
+    for (auto &t : vr0) {
+        RedTerm q;
+        for (int v = 0; v < MAXD; ++v) q.map[v] = identity_map(v);
+        for (auto &c : t.cond) q.cond.push_back(shifted(c, dm));
+        for (int v = 0; v < dv; ++v) q.map[dm + v] = shifted(t.map[v], dm);
+        vr.push_back(q);
+    }
+    std::vector<RedTerm> mrx;
+    for (auto &t : mr) {
+        RedTerm q = t;
+        for (int v = 0; v < dv; ++v) q.map[dm + v] = identity_map(dm + v);
+        mrx.push_back(q);
+    }
+    for (auto &t : vr) A.red.push_back(t);                // M_U * V_R
+    for (auto &t : mrx) A.red.push_back(t);               // M_R * V_U
+    for (auto &a : mrx)                                   // M_R * V_R
+        for (auto &b : vr) {
+            RedTerm q;
+            for (int v = 0; v < MAXD; ++v) q.map[v] = identity_map(v);
+            q.cond = a.cond;
+            for (auto &c : b.cond) q.cond.push_back(c);
+            for (int v = 0; v < dm; ++v) q.map[v] = a.map[v];
+            for (int v = 0; v < dv; ++v) q.map[dm + v] = b.map[dm + v];
+            A.red.push_back(q);
+        }
+    return finish(A);
+}
+
+// k-fold outer product of a vector with itself, T(x_1..x_k) := v(x_1) * .. * v(x_k): the self-multiplication rule
+// extended to higher degrees ("Extensions" of the inference rules; the vector self-outer-product example for
+// k = 2): the unique set gains x_1 <= x_2 <= .. <= x_k on top of v's range on every index, every permutation of
+// a stored tuple holds the same value (redundancy map: sort).  These are the structures of the covariance terms
+// M1, M2, M3 of the overview.
+st_status infer_power(const Desc &V, int k, Desc &A)
+{
+    if (V.d != 1) { A.error = "the self-product rule is implemented for vectors (order-1 descriptors)"; return ST_ERR_UNSUPPORTED; }
+    if (k < 2 || k > MAXD) { A.error = "degree of the self product: 2.." + std::to_string(MAXD); return ST_ERR_SHAPE; }
+    if (!V.red.empty() || V.red_sort) { A.error = "a vector with a redundancy map is not supported here"; return ST_ERR_UNSUPPORTED; }
+    A.d = k;
+    A.name = "T";
+    const char *names[MAXD] = {"i", "j", "k", "l"};
+    for (int v = 0; v < k; ++v) {
+        A.vars.push_back(names[v]);
+        A.dims[v] = V.dims[0];
+        Bound b;
+        for (int u = 0; u < MAXD; ++u) b.coef[u] = 0;
+        b.c = V.first[0];
+        A.lo[v].push_back(b);
+        b.c = V.last[0];
+        A.hi[v].push_back(b);
+        if (v > 0) A.lo[v].push_back(identity_map(v - 1));         // x_v >= x_{v-1}
+    }
+    A.empty = V.empty;
+    A.red_sort = true;
+    return finish(A);
+}
+
 // the generated source compiled for gfx950 (no GPU needed); on failure D.error holds the compiler's log
 st_status compile_source(Desc &D, std::vector<char> *code)
 {
@@ -1176,21 +1285,44 @@ st_status st_desc_product(const st_desc *m, const st_desc *v, st_desc **out)
     return rc;
 }
 
+st_status st_desc_outer(const st_desc *m, const st_desc *v, st_desc **out)
+{
+    if (!m || !v || !out) return ST_ERR_NULL;
+    const Desc *M = reinterpret_cast<const Desc *>(m), *V = reinterpret_cast<const Desc *>(v);
+    if (M->source.empty() || V->source.empty()) return ST_ERR_SHAPE;
+    Desc *A = new Desc();
+    const st_status rc = infer_outer(*M, *V, *A);
+    *out = reinterpret_cast<st_desc *>(A);      // kept on failure too: st_desc_error tells why
+    return rc;
+}
+
+st_status st_desc_power(const st_desc *v, int k, st_desc **out)
+{
+    if (!v || !out) return ST_ERR_NULL;
+    const Desc *V = reinterpret_cast<const Desc *>(v);
+    if (V->source.empty()) return ST_ERR_SHAPE;
+    Desc *A = new Desc();
+    const st_status rc = infer_power(*V, k, *A);
+    *out = reinterpret_cast<st_desc *>(A);
+    return rc;
+}
+
 st_status st_desc_gather(st_desc *desc, const void *table, const float *Tc, const int32_t *idx, int64_t count,
-                         const float *scale, float *out, void *stream)
+                         int idx_stride, int idx_offset, const float *scale, float *out, void *stream)
 {
     if (!desc || !table || !Tc || (count > 0 && (!idx || !out))) return ST_ERR_NULL;
     Desc *D = reinterpret_cast<Desc *>(desc);
     if (D->source.empty() || count < 0) return ST_ERR_SHAPE;
+    if (idx_offset < 0 || idx_stride < idx_offset + D->d || idx_stride > 64) return ST_ERR_SHAPE;
     if (count > ((int64_t)1 << 31) * 200) return ST_ERR_UNSUPPORTED;
     if (!aligned16(table) || !aligned16(Tc) || !aligned16(idx) || !aligned16(out) || (scale && !aligned16(scale)))
         return ST_ERR_ALIGN;
     if (count == 0) return ST_OK;
     if (overlap(out, (size_t)count * 4, Tc, (size_t)D->count * 4) ||
-        overlap(out, (size_t)count * 4, idx, (size_t)count * 4 * D->d))
+        overlap(out, (size_t)count * 4, idx, (size_t)count * 4 * (size_t)idx_stride))
         return ST_ERR_SHAPE;
     long long cnt = count;
-    void *args[] = {&table, &Tc, &idx, &cnt, &scale, &out};
+    void *args[] = {&table, &Tc, &idx, &cnt, &idx_stride, &idx_offset, &scale, &out};
     return launch_generated(*D, 3, (unsigned)((count + 255) / 256), args, (hipStream_t)stream);
 }
 

@@ -77,7 +77,7 @@ int main(int argc, char **argv)
         std::vector<float> scale, out(g, -7.f);
         if (FILE *h = fopen((dir + "/gather_scale.f32").c_str(), "rb")) { fclose(h); scale = rd<float>(dir + "/gather_scale.f32", g); }
         if (g) hipLaunchKernelGGL(st_gen_gather, dim3((unsigned)((g + 255) / 256)), dim3(256), 0, 0, tab.data(), bc.data(), idx.data(),
-                                  (long long)g, scale.empty() ? (const float *)nullptr : scale.data(), out.data());
+                                  (long long)g, (int)order, 0, scale.empty() ? (const float *)nullptr : scale.data(), out.data());
         wr(dir + "/gather.f32", out);
     }
 #if ST_D == 3

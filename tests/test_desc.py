@@ -333,3 +333,114 @@ def test_product_inference(oracle, tmp_path, name):
     assert np.array_equal(out, np.zeros(2, dtype=np.float32))
     for d in (dm, dv, da):
         d.close()
+
+
+# ------------------------------------------------------------------ structure inference for outer products
+_rows = lambda i, j: (0, j) if i >= 1 else None
+# name -> (M: text, dims, redundancy, params, predicate, unique_of), (V: ...), expected unique_of of the result or "none"
+OUTERS = {
+    # the shape of the paper's walk-through of the outer-product rule: no redundancy x symmetric
+    "lower_x_sym": (("M(a,b): (0<=b<a<n)", (5, 5), None, dict(n=5), lambda a, b: b < a, None),
+                    ("V(c,d): (0<=c<=d<m)", (4, 4), "(0<=d<c<m) -> (d,c)", dict(m=4), lambda c, d: c <= d, _swap)),
+    # both redundant: all three summands of T_R
+    "sym_x_sym": (("M(i,j): (0<=i<=j<n)", (4, 4), "sort", dict(n=4), lambda i, j: i <= j, _swap),
+                  ("N(i,j): (0<=i<=j<m)", (3, 3), "(0<=j<i<m) -> (j,i)", dict(m=3), lambda i, j: i <= j, _swap)),
+    "rows_x_vec": (("M(i,j): (i=0)*(0<=j<m)", (3, 5), "(1<=i<n) -> (0,j)", dict(n=3, m=5), lambda i, j: i == 0, _rows),
+                   ("v(k): (1<=k<n)", (6,), None, dict(n=6), lambda k: 1 <= k, None)),
+    "vec_x_band": (("v(i): (0<=i<n)", (4,), None, dict(n=4), lambda i: True, None),
+                   ("B(j,l): (0<=j<n)*(j-1<=l<=j+1)", (6, 6), None, dict(n=6), lambda j, l: abs(j - l) <= 1, None)),
+    # same variable names in both operands: the result renames
+    "vec_x_vec": (("v(i): (2<=i<n)", (7,), None, dict(n=7), lambda i: i >= 2, None),
+                  ("w(i): (0<=i<=m)", (5,), None, dict(m=2), lambda i: i <= 2, None)),
+}
+
+
+@pytest.mark.parametrize("name", sorted(OUTERS))
+def test_outer_product_inference(oracle, tmp_path, name):
+    """T(x, y) := M(x) * V(y): T_U = M_U * V_U and T_R = M_U*V_R + M_R*V_U + M_R*V_R against predicates written out
+    by hand (brute force over the box); values on T_U from the two operands' generated gather kernels (CPU run)
+    against the dense outer product, bit for bit; Property 5 for the result through its own generated
+    reconstruction."""
+    if CLANG is None:
+        pytest.skip("no clang++ for the host build")
+    (mt, mdims, mred, mpar, mpred, muniq), (vt, vdims, vred, vpar, vpred, vuniq) = OUTERS[name]
+    dm, dv = st.Descriptor(mt, mdims, mred, **mpar), st.Descriptor(vt, vdims, vred, **vpar)
+    k = len(mdims)
+    dims = tuple(mdims) + tuple(vdims)
+    dt = dm.outer(dv)
+    pred = lambda *x: mpred(*x[:k]) and vpred(*x[k:])
+    def unique_of(*x):
+        a = (muniq(*x[:k]) if muniq and not mpred(*x[:k]) else None) or x[:k]
+        b = (vuniq(*x[k:]) if vuniq and not vpred(*x[k:]) else None) or x[k:]
+        return tuple(a) + tuple(b) if tuple(a) + tuple(b) != tuple(x) else None
+    lst = oracle.struct_enumerate(dims, pred)
+    assert dt.count == lst.shape[0] == dm.count * dv.count
+    Mc, Vc = W.uniform(781, dm.count), W.uniform(782, dv.count)
+    Md, Vd = oracle.struct_expand(Mc, mdims, mpred, muniq), oracle.struct_expand(Vc, vdims, vpred, vuniq)
+    dense = (Md.reshape(mdims + (1,) * len(vdims)) * Vd.reshape((1,) * k + vdims)).astype(np.float32)
+    gm = _run_generated(dm, str(tmp_path / "m"), mdims, Mc, gather_idx=lst[:, :k])
+    tc = _run_generated(dv, str(tmp_path / "v"), vdims, Vc, gather_idx=lst[:, k:], scale=gm)
+    cols = tuple(lst[:, v].astype(np.int64) for v in range(len(dims)))
+    assert np.array_equal(tc.view(np.uint32), dense[cols].view(np.uint32))
+    _run_generated(dt, str(tmp_path / "t"), dims, tc)
+    got = np.fromfile(str(tmp_path / "t" / "list.i32"), dtype=np.int32).reshape(-1, len(dims))
+    assert np.array_equal(got, lst)
+    ex = np.fromfile(str(tmp_path / "t" / "expand.f32"), dtype=np.float32).reshape(dims)
+    assert np.array_equal(ex, dense)
+    assert np.array_equal(oracle.struct_expand(tc, dims, pred, unique_of), dense)      # the same map, written by hand
+
+
+def test_outer_product_limits():
+    a = st.Descriptor("B(i,j,l): (0<=i<n)*(i<=j<n)*(0<=l<n)", (3, 3, 3), None, n=3)
+    b = st.Descriptor("S(i,j): (0<=i<=j<n)", (3, 3), "sort", n=3)
+    with pytest.raises(st.StructTensorError) as e:
+        a.outer(b)                                                   # order 5
+    assert e.value.status == 6
+    t = st.Descriptor("T(i,j,k): (0<=i<n)*(i<=j<n)*(j<=k<n)", (3, 3, 3), "sort", n=3)
+    v = st.Descriptor("v(i): (0<=i<n)", (3,), None, n=3)
+    with pytest.raises(st.StructTensorError) as e:
+        t.outer(v)                                                   # a sort map of order 3 is a sum of conditions
+    assert e.value.status == 6 and "sort" in str(e.value)
+
+
+# ------------------------------------------------------------------ the self-multiplication rule and its extension
+@pytest.mark.parametrize("k", [2, 3, 4])
+def test_vector_self_product_inference(oracle, tmp_path, k):
+    """x (x) x (x) .. (k factors) of a vector: the inferred structure is the one the moment kernels are written
+    for -- the nests of the overview (for i; for j = i; for k = j), the closed-form counts, the packed order of
+    the C oracle, and a reconstruction that equals the oracle's bit for bit."""
+    if CLANG is None:
+        pytest.skip("no clang++ for the host build")
+    n = 6
+    v = st.Descriptor("x(i): (0<=i<n)", (n,), None, n=n)
+    p = v.power(k)
+    names = "ijkl"
+    want = ["for (i = 0; i <= 5; ++i)"] + ["%sfor (%s = %s; %s <= 5; ++%s)" % ("  " * t, names[t], names[t - 1], names[t], names[t])
+                                             for t in range(1, k)]
+    assert p.nest.splitlines()[:k] == want
+    ref = {2: oracle.list_sym2, 3: oracle.list_sym3, 4: oracle.list_sym4}[k](n)
+    assert p.count == ref.shape[0] == {2: 21, 3: 56, 4: 126}[k]
+    Tc = W.uniform(791, p.count)
+    _run_generated(p, str(tmp_path / "p"), (n,) * k, Tc)
+    lst = np.fromfile(str(tmp_path / "p" / "list.i32"), dtype=np.int32).reshape(-1, k)
+    assert np.array_equal(lst, ref.astype(np.int32))
+    ex = np.fromfile(str(tmp_path / "p" / "expand.f32"), dtype=np.float32).reshape((n,) * k)
+    assert np.array_equal(ex.view(np.uint32), oracle.expand_sym(Tc, n, k).view(np.uint32))
+    # a vector whose unique set is a sub-range: the same structure on that range
+    w = st.Descriptor("x(i): (2<=i<n)", (n,), None, n=n).power(k)
+    sub = {2: oracle.list_sym2, 3: oracle.list_sym3, 4: oracle.list_sym4}[k](n - 2) + 2
+    assert w.count == sub.shape[0]
+    _run_generated(w, str(tmp_path / "w"), (n,) * k, W.uniform(792, w.count))
+    assert np.array_equal(np.fromfile(str(tmp_path / "w" / "list.i32"), dtype=np.int32).reshape(-1, k), sub.astype(np.int32))
+
+
+def test_vector_self_product_limits():
+    s = st.Descriptor("S(i,j): (0<=i<=j<n)", (3, 3), None, n=3)
+    with pytest.raises(st.StructTensorError) as e:
+        s.power(2)
+    assert e.value.status == 6
+    v = st.Descriptor("x(i): (0<=i<n)", (3,), None, n=3)
+    for k in (1, 5):
+        with pytest.raises(st.StructTensorError) as e:
+            v.power(k)
+        assert e.value.status == 2

@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 
 import st_workloads as W
-from test_desc import CASES
+from test_desc import CASES, OUTERS
 
 pytestmark = pytest.mark.gpu
 
@@ -331,3 +331,52 @@ def test_upper_triangular_times_symmetric_full(st, oracle):
     assert db.count == cnt and np.array_equal(Bc.cpu().numpy(), Ac.cpu().numpy())
     for d in (dm, dv, da, db):
         d.close()
+
+
+@pytest.mark.parametrize("name", sorted(OUTERS))
+def test_outer_product_of_structured_operands(st, oracle, name):
+    """T(x, y) := M(x) * V(y) on the GPU: inferred descriptor, values from two gathers over the two halves of the
+    result's own index list, against the dense outer product (bit for bit), and Property 5 through the generated
+    reconstruction of the result."""
+    say("descriptor outer product", name)
+    (mt, mdims, mred, mpar, mpred, muniq), (vt, vdims, vred, vpar, vpred, vuniq) = OUTERS[name]
+    dm, dv = st.Descriptor(mt, mdims, mred, **mpar), st.Descriptor(vt, vdims, vred, **vpar)
+    k, dims = len(mdims), tuple(mdims) + tuple(vdims)
+    Mc, Vc = W.uniform(781, max(dm.count, 4)), W.uniform(782, max(dv.count, 4))
+    dt, Tc = st.outer_struct(dm, dev(Mc), dv, dev(Vc))
+    lst = oracle.struct_enumerate(dims, lambda *x: mpred(*x[:k]) and vpred(*x[k:]))
+    assert dt.count == lst.shape[0] == Tc.numel()
+    assert np.array_equal(dt.list().cpu().numpy(), lst)
+    Md = oracle.struct_expand(Mc[: dm.count], mdims, mpred, muniq)
+    Vd = oracle.struct_expand(Vc[: dv.count], vdims, vpred, vuniq)
+    dense = (Md.reshape(mdims + (1,) * len(vdims)) * Vd.reshape((1,) * k + vdims)).astype(np.float32)
+    cols = tuple(lst[:, v].astype(np.int64) for v in range(len(dims)))
+    assert np.array_equal(Tc.cpu().numpy().view(np.uint32), dense[cols].view(np.uint32))
+    import torch
+    buf = torch.zeros(max(dt.count, 4), device="cuda")
+    buf[: dt.count] = Tc
+    assert np.array_equal(dt.expand(buf).cpu().numpy(), dense)
+    for d in (dm, dv, dt):
+        d.close()
+
+
+@pytest.mark.parametrize("k", [2, 3])
+def test_self_product_structure_drives_the_moment_kernels(st, oracle, k):
+    """The covariance terms as the inference gives them: the k-fold self product of the feature vector has the
+    structure x_1 <= .. <= x_k with a sort map; accumulating over samples on that descriptor equals the hand-written
+    moment kernels (same packed order) and the oracle, and its reconstruction equals st_expand_sym."""
+    n, N = 64, 3000
+    say("self product of a vector, degree %d, n=%d: moments through the inferred descriptor" % (k, n))
+    v = st.Descriptor("f(i): (0<=i<n)", (n,), None, n=n)
+    p = v.power(k)
+    assert p.count == (st.count_sym2(n) if k == 2 else st.count_sym3(n))
+    X = W.normal(795, N * n).reshape(N, n)
+    got = p.moment(dev(X)).cpu().numpy()
+    hand = (st.moment2_sym if k == 2 else st.moment3_sym)(dev(X)).cpu().numpy()
+    ref = oracle.moment2_dense(X)[np.triu_indices(n)] if k == 2 else oracle.moment3_entries(X, oracle.list_sym3(n))
+    scale = float(np.abs(ref).max())
+    assert float(np.abs(got - ref).max()) <= 1e-4 * scale and float(np.abs(got - hand).max()) <= 1e-4 * scale
+    Sc = dev(W.uniform(796, p.count))
+    assert np.array_equal(p.expand(Sc).cpu().numpy().view(np.uint32), st.expand_sym(Sc, n, k).cpu().numpy().view(np.uint32))
+    v.close()
+    p.close()
