@@ -593,7 +593,7 @@ void build_source(Desc &D)
         s += "    const int x0 = blockIdx.x, r0 = blockIdx.y * ST_MK_COLS;\n";
         s += "    const bool v4 = (R & 3) == 0;\n";
         s += "    float acc[ST_MK_COLS];\n    for (int c = 0; c < ST_MK_COLS; ++c) acc[c] = 0.f;\n";
-        s += "    if (x0 >= st_lo0() && x0 <= st_hi0()) {\n";
+        s += "    if (ST_COUNT > 0 && x0 >= st_lo0() && x0 <= st_hi0()) {      // (an empty unique set: zeros)\n";
         s += "        for (int x1 = st_lo1(x0) + wv; x1 <= st_hi1(x0); x1 += nw) {\n";
         s += "            const int lo = st_lo2(x0, x1), hi = st_hi2(x0, x1);\n";
         s += "            if (lo > hi) continue;\n";
