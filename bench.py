@@ -503,9 +503,17 @@ def main():
         dtet = st.Descriptor("B(i,j,l): (0<=i<n)*(i<=j<n)*(j<=l<n)", (nm, nm, nm), None, n=nm)
         Bm = torch.randn(dtet.count, **f32)
         Cm, Dm, Am = torch.randn((nm, Rm), **f32), torch.randn((nm, Rm), **f32), torch.empty((nm, Rm), **f32)
+        # ... and for the upper half cube at 512^3 (last variable free: the contraction over it runs on the matrix cores,
+        # a generated kernel combines the runs of every row with the rows of C)
+        dup = st.Descriptor("B(i,k,l): (0<=i<n)*(i<=k<n)*(0<=l<m)", (nt, nt, c3["nl"]), None, n=nt, m=c3["nl"])
+        Bq = torch.randn(dup.count, **f32)
+        Cq, Dq, Aq = torch.randn((nt, Rt), **f32), torch.randn((c3["nl"], Rt), **f32), torch.empty((nt, Rt), **f32)
+        wsq = torch.empty(max(16, int(st.lib().st_desc_mttkrp_workspace(dup._h, Rt))), dtype=torch.uint8, device=dev)
         extra += [
             ("desc_mttkrp_tetra_n256_R64", lambda: dtet.mttkrp(Bm, Cm, Dm, A=Am),
              dict(flops=3 * Rm * dtet.count, bytes=4 * (dtet.count + 3 * nm * Rm), bound="alu")),
+            ("desc_mttkrp_upper_n512_R64", lambda: dup.mttkrp(Bq, Cq, Dq, A=Aq, ws=wsq),
+             dict(flops=2 * Rt * dup.count + 2 * Rt * dup.runs, bytes=4 * (dup.count + 3 * nt * Rt), bound="mfma")),
         ]
         next_rows = {}
         for name, f, w in extra:

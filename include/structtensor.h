@@ -343,13 +343,20 @@ st_status st_desc_expand(st_desc *desc, const void *table, const float *Tc, floa
  *     A(x0, r) = sum over the stored (x1, x2) of row x0 of Bc(rank(x)) * C(x1, r) * D(x2, r)
  * Bc is the packed operand (st_desc_count floats), C is dims[1] x R, D is
  * dims[2] x R, A is dims[0] x R (all row-major, DEVICE, 16-byte aligned; rows
- * of A without a stored entry are written as zeros).  Vector-ALU kernel, one
- * workgroup per output row and 16 columns, sums in a fixed order.
- * ST_ERR_UNSUPPORTED for orders other than 3 and for descriptors with a
- * redundancy map (their operand has entries outside the unique set; the
- * fully symmetric case is st_mttkrp_sym3). */
+ * of A without a stored entry are written as zeros).  Two routes, chosen by
+ * the structure: when it leaves the LAST variable free (every run is a whole
+ * fibre: diagonal plane, fixed index, band or upper half on (i,k)) the
+ * contraction over l runs on the matrix cores through the kernels of
+ * st_ttm_band into Y(run, r) in the workspace, and a generated kernel adds
+ * C(x1, r) * Y(run, r) over the runs of every row; otherwise a generated
+ * vector-ALU kernel, one workgroup per output row and 16 columns.  Sums in a
+ * fixed order either way.  st_desc_mttkrp_workspace is 0 for the second route
+ * (ws may be NULL then).  ST_ERR_UNSUPPORTED for orders other than 3 and for
+ * descriptors with a redundancy map (their operand has entries outside the
+ * unique set; the fully symmetric case is st_mttkrp_sym3). */
+size_t st_desc_mttkrp_workspace(const st_desc *desc, int R);
 st_status st_desc_mttkrp(st_desc *desc, const void *table, const float *Bc, const float *C, const float *D,
-                         float *A, int R, void *stream);
+                         float *A, int R, void *ws, size_t ws_bytes, void *stream);
 
 /* Structure inference for an element-wise product  A(x) := M(x) * V(x)  of two
  * structured operands of the same shape ("Structure Inference", general rule for

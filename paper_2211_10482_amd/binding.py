@@ -75,7 +75,8 @@ SIGNATURES = {
     "st_desc_compile": (_I32, [_P]),
     "st_desc_list": (_I32, [_P, _P, _P, _P]),
     "st_desc_thp": (_I32, [_P, _P, _P, _P, _P, _P]),
-    "st_desc_mttkrp": (_I32, [_P, _P, _P, _P, _P, _P, _I32, _P]),
+    "st_desc_mttkrp_workspace": (_SZ, [_P, _I32]),
+    "st_desc_mttkrp": (_I32, [_P, _P, _P, _P, _P, _P, _I32, _P, _SZ, _P]),
     "st_desc_expand": (_I32, [_P, _P, _P, _P, _P]),
     "st_desc_ttm": (_I32, [_P, _P, _P, _P, _I32, _P]),
     "st_desc_product": (_I32, [_P, _P, _P]),
@@ -572,7 +573,7 @@ class Descriptor:
                                      _dev_f32(Ac, "Ac"), _stream()), "st_desc_thp")
         return Ac[:self.count]
 
-    def mttkrp(self, Bc, Cm, Dm, A=None):
+    def mttkrp(self, Bc, Cm, Dm, A=None, ws=None):
         """A(x0, r) = sum over the stored (x1, x2) of Bc(rank(x)) C(x1, r) D(x2, r) (order 3, no redundancy map)."""
         torch = _torch()
         _expect(Bc, self.count, "Bc", at_least=True)
@@ -586,8 +587,10 @@ class Descriptor:
         if A is None:
             A = torch.empty((self.dims[0], R), dtype=torch.float32, device=Cm.device)
         _expect(A, self.dims[0] * R, "A")
+        need = int(lib().st_desc_mttkrp_workspace(self._h, R))
+        ws, wsp, wsb = _workspace(need, Cm, ws)
         self._call(lib().st_desc_mttkrp(self._h, self._tab(), _dev_f32(Bc, "Bc"), _dev_f32(Cm, "C"), _dev_f32(Dm, "D"),
-                                        _dev_f32(A, "A"), R, _stream()), "st_desc_mttkrp")
+                                        _dev_f32(A, "A"), R, wsp, wsb, _stream()), "st_desc_mttkrp")
         return A
 
     def expand(self, Tc, T=None):

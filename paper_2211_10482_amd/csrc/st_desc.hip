@@ -218,7 +218,7 @@ struct Desc {
     i64 mbs = 0, ntiles = 0, mnp = 0;
     std::string nest, source;
     std::mutex mu;
-    struct Loaded { hipModule_t mod; hipFunction_t fn[7]; };   // list, thp, expand, gather, moment, moment_reduce, mttkrp
+    struct Loaded { hipModule_t mod; hipFunction_t fn[8]; };   // list, thp, expand, gather, moment, moment_reduce, mttkrp, mttkrp_combine
     std::map<int, Loaded> modules;               // per device
     std::string error;
 };
@@ -620,6 +620,32 @@ void build_source(Desc &D)
         s += "    for (int c = tid; c < ST_MK_COLS && r0 + c < R; c += nt) {\n";
         s += "        float v = 0.f;\n        for (int part = 0; part < ST_MK_PARTS; ++part) v += st_red2[c][part];\n";
         s += "        A[(long long)x0 * R + r0 + c] = v;\n    }\n}\n";
+        // second half of the matrix-core route (last variable free: every run is a whole fibre): Y(run, r) =
+        // sum_l Bc(run, l) D(l, r) comes from the TTM kernels; here A(x0, r) = sum over the runs (x0, x1) of
+        // C(x1, r) * Y(run, r).  A workgroup per row x0 and block of 64 columns; the runs of a row are consecutive
+        // in the run list (first one by binary search), dealt to ST_MC_SLOTS thread groups, partial sums added in
+        // slot order.
+        s += "#define ST_MC_SLOTS 16\n";
+        s += "extern \"C\" __global__ void st_gen_mttkrp_combine(const int *__restrict__ tab, const float *__restrict__ Y,\n"
+             "                                                 const float *__restrict__ C, float *__restrict__ A, int R)\n{\n";
+        s += "    __shared__ float st_part[ST_MC_SLOTS][64];\n";
+        s += "    const int tid = threadIdx.x, nt = blockDim.x, L = nt < 64 ? nt : 64, ln = tid % L, sl = tid / L, ns = nt / L;\n";
+        s += "    const int x0 = blockIdx.x, r0 = blockIdx.y * 64;\n";
+        s += "    const int *runs = tab + ST_PREFIXES;\n";
+        s += "    int ra = 0, rb = ST_NRUNS;                       // first run whose prefix belongs to row x0 or a later one\n";
+        s += "    while (ra < rb) { const int mid = (ra + rb) / 2; if (runs[mid] / ST_DIM1 < x0) ra = mid + 1; else rb = mid; }\n";
+        s += "    for (int cb = 0; cb < 64; cb += L) {              // (one pass when the workgroup has 64 lanes per slot)\n";
+        s += "        const int r = r0 + cb + ln;\n";
+        s += "        float acc = 0.f;\n";
+        s += "        if (r < R)\n";
+        s += "            for (int run = ra + sl; run < ST_NRUNS && runs[run] / ST_DIM1 == x0; run += ns)\n";
+        s += "                acc += C[(long long)(runs[run] % ST_DIM1) * R + r] * Y[(long long)run * R + r];\n";
+        s += "        st_part[sl][ln] = acc;\n";
+        s += "        __syncthreads();\n";
+        s += "        if (sl == 0 && r < R) {\n";
+        s += "            float v = 0.f;\n            for (int q = 0; q < ns; ++q) v += st_part[q][ln];\n";
+        s += "            A[(long long)x0 * R + r] = v;\n        }\n";
+        s += "        __syncthreads();\n    }\n}\n";
     }
     if (D.ntiles > 0) {
         // moment accumulation over the unique set: Sc(rank(x)) (+)= sum_s prod_v X(s, x_v).  One lane per block
@@ -1075,13 +1101,14 @@ st_status module_for(Desc &D, Desc::Loaded &out)
     if (hipModuleLoadData(&L.mod, code.data()) != hipSuccess) { D.error = "hipModuleLoadData failed"; return ST_ERR_LAUNCH; }
     const char *names[6] = {"st_gen_list", "st_gen_thp", "st_gen_expand", "st_gen_gather", "st_gen_moment",
                             "st_gen_moment_reduce"};
-    L.fn[4] = L.fn[5] = L.fn[6] = nullptr;
-    for (int q = 0; q < 7; ++q) {
+    L.fn[4] = L.fn[5] = L.fn[6] = L.fn[7] = nullptr;
+    for (int q = 0; q < 8; ++q) {
         if ((q == 4 || q == 5) && D.ntiles == 0) continue;      // moment kernels: equal extents only
-        if (q == 6 && D.d != 3) continue;                       // MTTKRP: order 3 only
-        if (hipModuleGetFunction(&L.fn[q], L.mod, q == 6 ? "st_gen_mttkrp" : names[q]) != hipSuccess) {
+        if (q >= 6 && D.d != 3) continue;                       // MTTKRP: order 3 only
+        const char *name = q == 6 ? "st_gen_mttkrp" : q == 7 ? "st_gen_mttkrp_combine" : names[q];
+        if (hipModuleGetFunction(&L.fn[q], L.mod, name) != hipSuccess) {
             (void)hipModuleUnload(L.mod);
-            D.error = std::string("generated kernel missing: ") + (q == 6 ? "st_gen_mttkrp" : names[q]);
+            D.error = std::string("generated kernel missing: ") + name;
             return ST_ERR_LAUNCH;
         }
     }
@@ -1195,8 +1222,23 @@ st_status st_desc_thp(st_desc *desc, const void *table, const float *Bc, const f
     return launch_generated(*D, 1, (unsigned)((D->nruns + 3) / 4), args, (hipStream_t)stream);
 }
 
+// every run of the unique set is a whole fibre of the last variable
+static bool last_variable_free(const Desc &D)
+{
+    const int last = D.d - 1;
+    return D.d >= 2 && D.lo[last].empty() && D.hi[last].empty() && D.first[last] == 0 && D.last[last] == D.dims[last] - 1;
+}
+
+size_t st_desc_mttkrp_workspace(const st_desc *desc, int R)
+{
+    if (!desc || R < 1) return 0;
+    const Desc *D = reinterpret_cast<const Desc *>(desc);
+    if (D->d != 3 || D->source.empty() || !last_variable_free(*D) || D->nruns == 0) return 0;
+    return ((size_t)D->nruns * (size_t)R * sizeof(float) + 255u) & ~(size_t)255u;          // Y(run, r)
+}
+
 st_status st_desc_mttkrp(st_desc *desc, const void *table, const float *Bc, const float *C, const float *Dm, float *A,
-                         int R, void *stream)
+                         int R, void *ws, size_t ws_bytes, void *stream)
 {
     if (!desc || !table || !Bc || !C || !Dm || !A) return ST_ERR_NULL;
     Desc *D = reinterpret_cast<Desc *>(desc);
@@ -1208,6 +1250,23 @@ st_status st_desc_mttkrp(st_desc *desc, const void *table, const float *Bc, cons
     const size_t bb = (size_t)D->count * 4, cb = (size_t)D->dims[1] * R * 4, db = (size_t)D->dims[2] * R * 4,
                  ab = (size_t)D->dims[0] * R * 4;
     if (overlap(A, ab, Bc, bb) || overlap(A, ab, C, cb) || overlap(A, ab, Dm, db)) return ST_ERR_SHAPE;
+    const size_t need = st_desc_mttkrp_workspace(desc, R);
+    if (need > 0) {
+        // last variable free: the contraction over it runs on the matrix cores (the fibres of the unique set are the
+        // rows of a plain matrix), then the runs of every output row are combined with the rows of C
+        if (!ws || ws_bytes < need) return ST_ERR_WORKSPACE;
+        if (!aligned16(ws)) return ST_ERR_ALIGN;
+        if (overlap(ws, need, Bc, bb) || overlap(ws, need, C, cb) || overlap(ws, need, Dm, db) || overlap(ws, need, A, ab))
+            return ST_ERR_SHAPE;
+        if ((int64_t)D->nruns * R > ((int64_t)1 << 40)) return ST_ERR_UNSUPPORTED;
+        float *Y = static_cast<float *>(ws);
+        const st_status rc = launch_ttm(Bc, Dm, Y, D->nruns, (int)D->dims[2], R, nullptr, (hipStream_t)stream);
+        if (rc != ST_OK) return rc;
+        const float *Yc = Y;
+        void *args[] = {&table, &Yc, &C, &A, &R};
+        const unsigned threads = D->dims[1] >= 16 ? 1024u : 256u;             // 16 or 4 run slots of 64 columns
+        return launch_generated(*D, 7, (unsigned)D->dims[0], args, (hipStream_t)stream, (unsigned)((R + 63) / 64), threads);
+    }
     void *args[] = {&table, &Bc, &C, &Dm, &A, &R};
     // the runs of a row are a serial chain of dependent loads per wave: long rows get sixteen waves
     const unsigned threads = D->dims[1] >= 64 ? 1024u : 256u;
@@ -1221,9 +1280,7 @@ st_status st_desc_ttm(st_desc *desc, const float *Bc, const float *U, float *Ac,
     if (D->source.empty() || R < 1) return ST_ERR_SHAPE;
     const int last = D->d - 1;
     // the contracted (last) variable must be free: every run is a whole fibre
-    if (D->d < 2 || !D->lo[last].empty() || !D->hi[last].empty() || D->first[last] != 0 ||
-        D->last[last] != D->dims[last] - 1)
-        return ST_ERR_UNSUPPORTED;
+    if (!last_variable_free(*D)) return ST_ERR_UNSUPPORTED;
     if (!aligned16(Bc) || !aligned16(U) || !aligned16(Ac)) return ST_ERR_ALIGN;
     const int64_t rows = D->nruns, nl = D->dims[last];
     if (nl * (int64_t)R > ((int64_t)1 << 31)) return ST_ERR_UNSUPPORTED;

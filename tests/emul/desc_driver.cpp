@@ -91,6 +91,20 @@ int main(int argc, char **argv)
         hipLaunchKernelGGL(st_gen_mttkrp, dim3(ST_DIM0, (unsigned)((R + 15) / 16)), dim3(1), 0, 0, tab.data(), bc.data(), Cm.data(),
                            Dm.data(), A.data(), R);
         wr(dir + "/mttkrp.f32", A);
+        // the second half of the matrix-core route, when every run is a whole fibre (count = runs * dim2): Y(run, r)
+        // = sum_l Bc(run, l) D(l, r) in plain loops here, then the generated combine kernel, one thread per workgroup
+        if (nruns > 0 && count == nruns * (size_t)ST_DIM2) {
+            std::vector<float> Y(nruns * (size_t)R, 0.f), A2((size_t)ST_DIM0 * R, -7.f);
+            for (size_t run = 0; run < nruns; ++run)
+                for (int r = 0; r < R; ++r) {
+                    float acc = 0.f;
+                    for (size_t l = 0; l < (size_t)ST_DIM2; ++l) acc += bc[run * ST_DIM2 + l] * Dm[l * R + r];
+                    Y[run * R + r] = acc;
+                }
+            hipLaunchKernelGGL(st_gen_mttkrp_combine, dim3(ST_DIM0, (unsigned)((R + 63) / 64)), dim3(1), 0, 0, tab.data(), Y.data(),
+                               Cm.data(), A2.data(), R);
+            wr(dir + "/mttkrp_combine.f32", A2);
+        }
     }
 #endif
     wr(dir + "/list.i32", list);

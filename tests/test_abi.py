@@ -166,20 +166,26 @@ def test_descriptor_errors():
     assert L.st_desc_ttm(h, P, None, P + 0x10000, 4, None) == NULL
     assert L.st_desc_ttm(h, P, P + 0x10000, P + 0x20000, 4, None) == UNSUPPORTED   # last variable is bounded by i <= j
     assert L.st_desc_ttm(h, P, P + 0x10000, P + 0x20000, 0, None) == SHAPE
-    assert L.st_desc_mttkrp(h, P, P + 0x10000, P + 0x20000, P + 0x30000, P + 0x40000, 4, None) == UNSUPPORTED    # order 2
+    assert L.st_desc_mttkrp(h, P, P + 0x10000, P + 0x20000, P + 0x30000, P + 0x40000, 4, None, 0, None) == UNSUPPORTED    # order 2
     assert L.st_desc_count(None) == -1
     L.st_desc_destroy(h)
     L.st_desc_destroy(None)
     # the generated MTTKRP: order 3 without a redundancy map
     dims3 = (C.c_int64 * 3)(4, 4, 4)
     assert L.st_desc_create(b"B(i,j,l): (0<=i<n)*(i<=j<n)*(0<=l<n)", None, dims3, 3, names, vals, 1, C.byref(h)) == OK
-    assert L.st_desc_mttkrp(h, P, None, P + 0x20000, P + 0x30000, P + 0x40000, 4, None) == NULL
-    assert L.st_desc_mttkrp(h, P, P + 0x10000, P + 0x20000, P + 0x30000, P + 0x40000, 0, None) == SHAPE
-    assert L.st_desc_mttkrp(h, P, P + 0x10000, P + 0x20004, P + 0x30000, P + 0x40000, 4, None) == ALIGN
-    assert L.st_desc_mttkrp(h, P, P + 0x10000, P + 0x20000, P + 0x30000, P + 0x20000, 4, None) == SHAPE          # A aliases C
+    assert L.st_desc_mttkrp(h, P, None, P + 0x20000, P + 0x30000, P + 0x40000, 4, None, 0, None) == NULL
+    assert L.st_desc_mttkrp(h, P, P + 0x10000, P + 0x20000, P + 0x30000, P + 0x40000, 0, None, 0, None) == SHAPE
+    assert L.st_desc_mttkrp(h, P, P + 0x10000, P + 0x20004, P + 0x30000, P + 0x40000, 4, None, 0, None) == ALIGN
+    assert L.st_desc_mttkrp(h, P, P + 0x10000, P + 0x20000, P + 0x30000, P + 0x20000, 4, None, 0, None) == SHAPE  # A aliases C
+    # the last variable is free: ten runs of four entries, Y(run, r) in the workspace
+    assert L.st_desc_mttkrp_workspace(h, 4) == 256 and L.st_desc_mttkrp_workspace(h, 0) == 0
+    assert L.st_desc_mttkrp(h, P, P + 0x10000, P + 0x20000, P + 0x30000, P + 0x40000, 4, None, 0, None) == WORKSPACE
+    assert L.st_desc_mttkrp(h, P, P + 0x10000, P + 0x20000, P + 0x30000, P + 0x40000, 4, P + 0x50000, 16, None) == WORKSPACE
+    assert L.st_desc_mttkrp(h, P, P + 0x10000, P + 0x20000, P + 0x30000, P + 0x40000, 4, P + 0x40000, 256, None) == SHAPE  # ws aliases A
     L.st_desc_destroy(h)
     assert L.st_desc_create(b"T(i,j,k): (0<=i<n)*(i<=j<n)*(j<=k<n)", b"sort", dims3, 3, names, vals, 1, C.byref(h)) == OK
-    assert L.st_desc_mttkrp(h, P, P + 0x10000, P + 0x20000, P + 0x30000, P + 0x40000, 4, None) == UNSUPPORTED    # redundancy map
+    assert L.st_desc_mttkrp(h, P, P + 0x10000, P + 0x20000, P + 0x30000, P + 0x40000, 4, None, 0, None) == UNSUPPORTED    # redundancy map
+    assert L.st_desc_mttkrp_workspace(h, 4) == 0
     L.st_desc_destroy(h)
 
 

@@ -207,6 +207,10 @@ def test_generated_kernels_on_the_cpu(descs, oracle, tmp_path, name):
         assert float(np.abs(got - refa).max()) <= 1e-5 * max(float(np.abs(refa).max()), 1.0)
         empty_rows = ~Bd.reshape(dims[0], -1).any(axis=1)
         assert not got[empty_rows].any()                  # rows without a stored entry are written as zeros
+        if name in ("band", "diag", "fixed_i", "fixed_j", "upper_cube"):       # last variable free: the second route
+            got2 = np.fromfile(str(tmp_path / "mttkrp_combine.f32"), dtype=np.float32).reshape(dims[0], R)
+            assert float(np.abs(got2 - refa).max()) <= 1e-5 * max(float(np.abs(refa).max()), 1.0)
+            assert not got2[empty_rows].any()
     if has_moment:
         mom = np.fromfile(str(tmp_path / "moment.f32"), dtype=np.float32)
         refm = oracle.struct_moment(X, dims, pred)
