@@ -632,14 +632,19 @@ void build_source(Desc &D)
         s += "    const int tid = threadIdx.x, nt = blockDim.x, L = nt < 64 ? nt : 64, ln = tid % L, sl = tid / L, ns = nt / L;\n";
         s += "    const int x0 = blockIdx.x, r0 = blockIdx.y * 64;\n";
         s += "    const int *runs = tab + ST_PREFIXES;\n";
-        s += "    int ra = 0, rb = ST_NRUNS;                       // first run whose prefix belongs to row x0 or a later one\n";
-        s += "    while (ra < rb) { const int mid = (ra + rb) / 2; if (runs[mid] / ST_DIM1 < x0) ra = mid + 1; else rb = mid; }\n";
+        s += "    int ra = 0, re = ST_NRUNS;                       // first run whose prefix belongs to row x0 or a later one\n";
+        s += "    while (ra < re) { const int mid = (ra + re) / 2; if (runs[mid] / ST_DIM1 < x0) ra = mid + 1; else re = mid; }\n";
+        s += "    int rb = ra;                                     // ... to row x0 + 1 or a later one\n";
+        s += "    re = ST_NRUNS;\n";
+        s += "    while (rb < re) { const int mid = (rb + re) / 2; if (runs[mid] / ST_DIM1 <= x0) rb = mid + 1; else re = mid; }\n";
         s += "    for (int cb = 0; cb < 64; cb += L) {              // (one pass when the workgroup has 64 lanes per slot)\n";
         s += "        const int r = r0 + cb + ln;\n";
         s += "        float acc = 0.f;\n";
-        s += "        if (r < R)\n";
-        s += "            for (int run = ra + sl; run < ST_NRUNS && runs[run] / ST_DIM1 == x0; run += ns)\n";
+        s += "        if (r < R) {\n";
+        s += "#pragma unroll 4\n";
+        s += "            for (int run = ra + sl; run < rb; run += ns)\n";
         s += "                acc += C[(long long)(runs[run] % ST_DIM1) * R + r] * Y[(long long)run * R + r];\n";
+        s += "        }\n";
         s += "        st_part[sl][ln] = acc;\n";
         s += "        __syncthreads();\n";
         s += "        if (sl == 0 && r < R) {\n";
