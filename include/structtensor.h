@@ -374,7 +374,7 @@ st_status st_desc_product(const st_desc *m, const st_desc *v, st_desc **out);
 
 /* Values of a structured tensor at a LIST of dense positions, times an
  * optional factor per position:
- *     out[p] = (scale ? scale[p] : 1) * T(idx[p][0], .., idx[p][order-1])
+ *     out[p] = (scale ? scale[p] : 1) * T(idx[p][0], .., idx[p][order-1]) + (addend ? addend[p] : 0)
  * with T(x) the stored value on the unique set, the value at the unique index
  * the redundancy map names elsewhere, 0 where neither applies or x lies
  * outside the dense extents (Property 5, evaluated only where asked).  idx is
@@ -383,11 +383,28 @@ st_status st_desc_product(const st_desc *m, const st_desc *v, st_desc **out);
  * for a plain [count][order] list such as st_desc_list gives; an outer
  * product reads the two halves of its own list: ST_ERR_SHAPE unless
  * 0 <= idx_offset and idx_offset + order <= idx_stride <= 64).  Tc is the
- * packed operand of `desc`, scale NULL or DEVICE fp32 [count].  Two calls
+ * packed operand of `desc`, scale and addend NULL or DEVICE fp32 [count]
+ * (either may be `out` itself: element p is read before out[p] is written, by
+ * the same thread).  Two calls
  * evaluate a product of two structured operands on the unique set of the
  * result only:  A_C = gather(V, list(A), scale = gather(M, list(A))). */
 st_status st_desc_gather(st_desc *desc, const void *table, const float *Tc, const int32_t *idx, int64_t count,
-                         int idx_stride, int idx_offset, const float *scale, float *out, void *stream);
+                         int idx_stride, int idx_offset, const float *scale, const float *addend, float *out,
+                         void *stream);
+
+/* Structure inference for a sum  A(x) := M(x) + V(x)  of two structured operands
+ * of the same shape ("Unique Set Inference": the unique set of a sum is the
+ * union; "Redundancy Map Inference": operands of the same structure keep it,
+ * otherwise every non-zero element of an operand, unique or redundant, counts
+ * as stored and the result has no redundancy map).  The union has to be one
+ * nest: the unique set of an operand without a redundancy map, or the whole
+ * box; each candidate is checked point by point against the union of the two
+ * supports (box of at most 2^26 elements).  E.g. diagonal + upper triangular
+ * is upper triangular, symmetric + symmetric stays symmetric, symmetric +
+ * upper triangular is the whole box.  ST_ERR_UNSUPPORTED otherwise (band +
+ * a row: a sum of nests).  Values: out = gather(V, list(A), addend =
+ * gather(M, list(A))). */
+st_status st_desc_sum(const st_desc *m, const st_desc *v, st_desc **out);
 
 /* Structure inference for the tensor outer product  T(x, y) := M(x) * V(y)
  * over disjoint index lists, the variables of V behind those of M, total order

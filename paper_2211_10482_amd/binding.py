@@ -80,7 +80,8 @@ SIGNATURES = {
     "st_desc_expand": (_I32, [_P, _P, _P, _P, _P]),
     "st_desc_ttm": (_I32, [_P, _P, _P, _P, _I32, _P]),
     "st_desc_product": (_I32, [_P, _P, _P]),
-    "st_desc_gather": (_I32, [_P, _P, _P, _P, _I64, _I32, _I32, _P, _P, _P]),
+    "st_desc_gather": (_I32, [_P, _P, _P, _P, _I64, _I32, _I32, _P, _P, _P, _P]),
+    "st_desc_sum": (_I32, [_P, _P, _P]),
     "st_desc_outer": (_I32, [_P, _P, _P]),
     "st_desc_power": (_I32, [_P, _I32, _P]),
     "st_desc_moment_workspace": (_SZ, [_P, _I64]),
@@ -464,6 +465,16 @@ def hadamard_struct(dm, Mc, dv, Vc):
     return da, dv.gather(Vc, idx, scale=dm.gather(Mc, idx))
 
 
+def add_struct(dm, Mc, dv, Vc):
+    """A(x) := M(x) + V(x) for two structured operands of the same shape: the inferred descriptor of the result
+    and its packed values (each operand read through its own unique set and redundancy map)."""
+    da = dm.sum(dv)
+    if da.count == 0:
+        return da, _torch().empty(0, dtype=_torch().float32, device=Mc.device)
+    idx = da.list().contiguous()
+    return da, dv.gather(Vc, idx, addend=dm.gather(Mc, idx))
+
+
 def outer_struct(dm, Mc, dv, Vc):
     """T(x, y) := M(x) * V(y) for two structured operands: the inferred descriptor of the result and its packed
     values, from the two halves of the result's own index list."""
@@ -634,7 +645,12 @@ class Descriptor:
         return self._derived(lib().st_desc_power(self._h, int(k), C.byref(h)), h, "st_desc_power",
                              tuple(self.dims) * int(k))
 
-    def gather(self, Tc, idx, scale=None, out=None, offset=0):
+    def sum(self, other):
+        """Descriptor of the sum of two structured operands of the same shape (structure inference)."""
+        h = C.c_void_p()
+        return self._derived(lib().st_desc_sum(self._h, other._h, C.byref(h)), h, "st_desc_sum", self.dims)
+
+    def gather(self, Tc, idx, scale=None, out=None, offset=0, addend=None):
         """Values of the structured tensor at the dense positions idx[:, offset:offset+order] (int32), times scale."""
         torch = _torch()
         if not (isinstance(idx, torch.Tensor) and idx.is_cuda and idx.dtype == torch.int32 and idx.is_contiguous()):
@@ -645,11 +661,14 @@ class Descriptor:
         _expect(Tc, self.count, "Tc", at_least=True)
         if scale is not None:
             _expect(scale, count, "scale", at_least=True)
+        if addend is not None:
+            _expect(addend, count, "addend", at_least=True)
         if out is None:
             out = torch.empty(max(count, 4), dtype=torch.float32, device=Tc.device)
         _expect(out, count, "out", at_least=True)
         self._call(lib().st_desc_gather(self._h, self._tab(), _dev_f32(Tc, "Tc"), C.c_void_p(idx.data_ptr()), count,
                                         stride, int(offset), _dev_f32(scale, "scale") if scale is not None else None,
+                                        _dev_f32(addend, "addend") if addend is not None else None,
                                         _dev_f32(out, "out"), _stream()), "st_desc_gather")
         return out[:count]
 

@@ -557,7 +557,8 @@ void build_source(Desc &D)
     // with another structured operand needs, evaluated only where the product's unique set says
     s += "extern \"C\" __global__ void st_gen_gather(const int *__restrict__ tab, const float *__restrict__ Tc,\n"
          "                                         const int *__restrict__ idx, long long count, int stride, int offset,\n"
-         "                                         const float *__restrict__ scale, float *__restrict__ out)\n{\n";
+         "                                         const float *__restrict__ scale, const float *__restrict__ addend,\n"
+         "                                         float *__restrict__ out)\n{\n";
     s += "    const long long p = (long long)blockIdx.x * blockDim.x + threadIdx.x;\n    if (p >= count) return;\n";
     {
         std::string at;
@@ -568,7 +569,7 @@ void build_source(Desc &D)
         }
         s += "    const float v = (" + at + ") ? st_value(tab, Tc, " + xs + ") : 0.f;\n";
     }
-    s += "    out[p] = scale ? scale[p] * v : v;\n}\n";
+    s += "    const float w = scale ? scale[p] * v : v;\n    out[p] = addend ? w + addend[p] : w;\n}\n";
     if (d == 3) {
         // MTTKRP of the kernel table over the unique set: A(x0, r) = sum over the stored (x1, x2) of row x0 of
         // Bc(rank(x)) * C(x1, r) * D(x2, r).  One workgroup per output row x0 and block of 16 columns r; its
@@ -957,6 +958,89 @@ st_status infer_product(const Desc &M, const Desc &V, Desc &A)
             A.red.push_back(t);
         }
     return finish(A);
+}
+
+// ---- membership on the host (used by the inference of sums, which checks its candidates point by point) ----
+static bool in_unique(const Desc &D, const i64 *x)
+{
+    if (D.empty) return false;
+    for (int v = 0; v < D.d; ++v) {
+        i64 l, h;
+        range_of(D, v, x, l, h);
+        if (x[v] < l || x[v] > h) return false;
+    }
+    return true;
+}
+// the unique index the redundancy map gives for x (x itself on the unique set); false where the tensor is zero
+static bool unique_of(const Desc &D, const i64 *x, i64 *y)
+{
+    for (int v = 0; v < D.d; ++v) y[v] = x[v];
+    if (in_unique(D, x)) return true;
+    if (D.red_sort) {
+        std::sort(y, y + D.d);
+        if (in_unique(D, y)) return true;
+    }
+    for (auto &t : D.red) {
+        bool ok = true;
+        for (auto &c : t.cond) ok = ok && bound_eval(c, x, D.d) >= 0;
+        if (!ok) continue;
+        for (int v = 0; v < D.d; ++v) y[v] = bound_eval(t.map[v], x, D.d);
+        if (in_unique(D, y)) return true;
+    }
+    return false;
+}
+template <typename F> static bool for_all_box(const Desc &D, F &&f)      // f(x) for every x of the box, until it returns false
+{
+    i64 x[MAXD] = {0, 0, 0, 0};
+    i64 total = 1;
+    for (int v = 0; v < D.d; ++v) total *= D.dims[v];
+    for (i64 e = 0; e < total; ++e) {
+        i64 r = e;
+        for (int v = D.d - 1; v >= 0; --v) { x[v] = r % D.dims[v]; r /= D.dims[v]; }
+        if (!f(x)) return false;
+    }
+    return true;
+}
+
+// A(x) := M(x) + V(x) ("Unique Set Inference": a sum is non-zero where either operand is, so the unique set of a
+// sum is the union; "Redundancy Map Inference": operands of the SAME structure keep it, otherwise the
+// redundancy maps are dropped first -- every non-zero element of an operand, unique or redundant, counts as
+// stored -- and the result has none).  A descriptor holds one nest, so the union must be one: the candidates
+// are the unique set of an operand without a redundancy map and the whole box, each checked point by point
+// against the union of the two supports.
+st_status infer_sum(const Desc &M, const Desc &V, Desc &A)
+{
+    if (M.d != V.d || !std::equal(M.dims, M.dims + MAXD, V.dims)) { A.error = "operands of different shape"; return ST_ERR_SHAPE; }
+    const int d = M.d;
+    i64 total = 1;
+    for (int v = 0; v < d; ++v) total *= M.dims[v];
+    if (total > ((i64)1 << 26)) { A.error = "the inference of a sum checks its result point by point: box above 2^26 elements"; return ST_ERR_UNSUPPORTED; }
+    A.d = d; A.name = "A"; A.vars = M.vars;
+    std::copy(M.dims, M.dims + MAXD, A.dims);
+    // same structure: the same unique set and, off it, the same unique index
+    const bool same = for_all_box(M, [&](const i64 *x) {
+        i64 a[MAXD], b[MAXD];
+        const bool ma = unique_of(M, x, a), vb = unique_of(V, x, b);
+        return in_unique(M, x) == in_unique(V, x) && ma == vb && (!ma || std::equal(a, a + d, b));
+    });
+    if (same) {
+        add_box(A, M);
+        A.red = M.red;
+        A.red_sort = M.red_sort;
+        return finish(A);
+    }
+    auto support = [&](const i64 *x) { i64 y[MAXD]; return unique_of(M, x, y) || unique_of(V, x, y); };
+    const Desc *cands[3] = {(M.red.empty() && !M.red_sort) ? &M : nullptr, (V.red.empty() && !V.red_sort) ? &V : nullptr, nullptr};
+    for (int q = 0; q < 3; ++q) {
+        if (q < 2 && !cands[q]) continue;
+        const Desc *Cd = cands[q];
+        const bool fits = for_all_box(M, [&](const i64 *x) { return (Cd ? in_unique(*Cd, x) : true) == support(x); });
+        if (!fits) continue;
+        if (Cd) add_box(A, *Cd);                 // (the whole box: no comparisons at all)
+        return finish(A);
+    }
+    A.error = "the union of the two supports is neither an operand's unique set nor the whole box: a sum of nests";
+    return ST_ERR_UNSUPPORTED;
 }
 
 // Tensor outer product T(x, y) := M(x) * V(y) over disjoint index lists ("Redundancy Map Inference", outer
@@ -1358,6 +1442,17 @@ st_status st_desc_outer(const st_desc *m, const st_desc *v, st_desc **out)
     return rc;
 }
 
+st_status st_desc_sum(const st_desc *m, const st_desc *v, st_desc **out)
+{
+    if (!m || !v || !out) return ST_ERR_NULL;
+    const Desc *M = reinterpret_cast<const Desc *>(m), *V = reinterpret_cast<const Desc *>(v);
+    if (M->source.empty() || V->source.empty()) return ST_ERR_SHAPE;
+    Desc *A = new Desc();
+    const st_status rc = infer_sum(*M, *V, *A);
+    *out = reinterpret_cast<st_desc *>(A);
+    return rc;
+}
+
 st_status st_desc_power(const st_desc *v, int k, st_desc **out)
 {
     if (!v || !out) return ST_ERR_NULL;
@@ -1370,21 +1465,23 @@ st_status st_desc_power(const st_desc *v, int k, st_desc **out)
 }
 
 st_status st_desc_gather(st_desc *desc, const void *table, const float *Tc, const int32_t *idx, int64_t count,
-                         int idx_stride, int idx_offset, const float *scale, float *out, void *stream)
+                         int idx_stride, int idx_offset, const float *scale, const float *addend, float *out,
+                         void *stream)
 {
     if (!desc || !table || !Tc || (count > 0 && (!idx || !out))) return ST_ERR_NULL;
     Desc *D = reinterpret_cast<Desc *>(desc);
     if (D->source.empty() || count < 0) return ST_ERR_SHAPE;
     if (idx_offset < 0 || idx_stride < idx_offset + D->d || idx_stride > 64) return ST_ERR_SHAPE;
     if (count > ((int64_t)1 << 31) * 200) return ST_ERR_UNSUPPORTED;
-    if (!aligned16(table) || !aligned16(Tc) || !aligned16(idx) || !aligned16(out) || (scale && !aligned16(scale)))
+    if (!aligned16(table) || !aligned16(Tc) || !aligned16(idx) || !aligned16(out) || (scale && !aligned16(scale)) ||
+        (addend && !aligned16(addend)))
         return ST_ERR_ALIGN;
     if (count == 0) return ST_OK;
     if (overlap(out, (size_t)count * 4, Tc, (size_t)D->count * 4) ||
         overlap(out, (size_t)count * 4, idx, (size_t)count * 4 * (size_t)idx_stride))
         return ST_ERR_SHAPE;
     long long cnt = count;
-    void *args[] = {&table, &Tc, &idx, &cnt, &idx_stride, &idx_offset, &scale, &out};
+    void *args[] = {&table, &Tc, &idx, &cnt, &idx_stride, &idx_offset, &scale, &addend, &out};
     return launch_generated(*D, 3, (unsigned)((count + 255) / 256), args, (hipStream_t)stream);
 }
 

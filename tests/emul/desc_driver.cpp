@@ -76,8 +76,11 @@ int main(int argc, char **argv)
         std::vector<int> idx = rd<int>(dir + "/gather.i32", g * order);
         std::vector<float> scale, out(g, -7.f);
         if (FILE *h = fopen((dir + "/gather_scale.f32").c_str(), "rb")) { fclose(h); scale = rd<float>(dir + "/gather_scale.f32", g); }
+        std::vector<float> addend;
+        if (FILE *h = fopen((dir + "/gather_addend.f32").c_str(), "rb")) { fclose(h); addend = rd<float>(dir + "/gather_addend.f32", g); }
         if (g) hipLaunchKernelGGL(st_gen_gather, dim3((unsigned)((g + 255) / 256)), dim3(256), 0, 0, tab.data(), bc.data(), idx.data(),
-                                  (long long)g, (int)order, 0, scale.empty() ? (const float *)nullptr : scale.data(), out.data());
+                                  (long long)g, (int)order, 0, scale.empty() ? (const float *)nullptr : scale.data(),
+                                  addend.empty() ? (const float *)nullptr : addend.data(), out.data());
         wr(dir + "/gather.f32", out);
     }
 #if ST_D == 3

@@ -269,7 +269,7 @@ PRODUCTS = {
 }
 
 
-def _run_generated(d, workdir, dims, Tc, gather_idx=None, scale=None):
+def _run_generated(d, workdir, dims, Tc, gather_idx=None, scale=None, addend=None):
     """Compile the generated source of descriptor d against the host stand-in and run the driver in workdir."""
     os.makedirs(workdir, exist_ok=True)
     src = os.path.join(workdir, "generated.hip")
@@ -287,6 +287,8 @@ def _run_generated(d, workdir, dims, Tc, gather_idx=None, scale=None):
         np.ascontiguousarray(gather_idx, dtype=np.int32).tofile(os.path.join(workdir, "gather.i32"))
         if scale is not None:
             np.asarray(scale, dtype=np.float32).tofile(os.path.join(workdir, "gather_scale.f32"))
+        if addend is not None:
+            np.asarray(addend, dtype=np.float32).tofile(os.path.join(workdir, "gather_addend.f32"))
     r = subprocess.run([exe, workdir, str(d.count), str(box), str(len(dims)), str(d.runs), str(dims[-1])],
                        capture_output=True, text=True, timeout=300)
     assert r.returncode == 0 and "rc=0" in r.stdout, r.stderr[-3000:]
@@ -448,3 +450,61 @@ def test_vector_self_product_limits():
         with pytest.raises(st.StructTensorError) as e:
             v.power(k)
         assert e.value.status == 2
+
+
+# ------------------------------------------------------------------ structure inference for sums
+# name -> (M: text, redundancy, predicate, unique_of), (V: ...), dims, params, expected (predicate, unique_of) or None
+SUMS = {
+    # the same structure on both sides is kept, redundancy map included
+    "sym_sym": (("M(i,j): (0<=i<=j<n)", SYM_RED, lambda i, j: i <= j, _swap),
+                ("N(i,j): (0<=i<=j<n)", "sort", lambda i, j: i <= j, _swap), (6, 6), dict(n=6), (lambda i, j: i <= j, _swap)),
+    "rows_rows": (("M(i,j): (i=0)*(0<=j<m)", "(1<=i<n) -> (0,j)", lambda i, j: i == 0, _rows),
+                  ("N(i,j): (i=0)*(0<=j<m)", "(1<=i<n) -> (0,j)", lambda i, j: i == 0, _rows), (4, 5), dict(n=4, m=5),
+                  (lambda i, j: i == 0, _rows)),
+    # one support inside the other: the larger unique set, no redundancy
+    "diag_upper": (("D(i,j): (0<=i<n)*(i=j)", None, lambda i, j: i == j, None),
+                   ("U(i,j): (0<=i<=j<n)", None, lambda i, j: i <= j, None), (7, 7), dict(n=7), (lambda i, j: i <= j, None)),
+    "band_diag3": (("B(i,j,l): (0<=i<n)*(i-w<=j<=i+w)*(0<=l<m)", None, lambda i, j, l: abs(i - j) <= 2, None),
+                   ("D(i,j,l): (0<=i<n)*(i=j)*(0<=l<m)", None, lambda i, j, l: i == j, None), (8, 8, 3), dict(n=8, w=2, m=3),
+                   (lambda i, j, l: abs(i - j) <= 2, None)),
+    # different structures with a redundancy map: the maps are dropped, every non-zero element counts: the whole box
+    "sym_upper": (("M(i,j): (0<=i<=j<n)", "sort", lambda i, j: i <= j, _swap),
+                  ("U(i,j): (0<=i<=j<n)", None, lambda i, j: i <= j, None), (5, 5), dict(n=5), (lambda i, j: True, None)),
+    "upper_lower": (("U(i,j): (0<=i<=j<n)", None, lambda i, j: i <= j, None),
+                    ("L(i,j): (0<=j<i<n)", None, lambda i, j: j < i, None), (6, 6), dict(n=6), (lambda i, j: True, None)),
+    # the union is a sum of nests: refused
+    "band_row": (("B(i,j): (0<=i<n)*(i-1<=j<=i+1)", None, lambda i, j: abs(i - j) <= 1, None),
+                 ("R(i,j): (i=0)*(0<=j<n)", None, lambda i, j: i == 0, None), (6, 6), dict(n=6), None),
+}
+
+
+@pytest.mark.parametrize("name", sorted(SUMS))
+def test_sum_inference(oracle, tmp_path, name):
+    """A(x) := M(x) + V(x): the inferred structure against predicates written out by hand, the values (two generated
+    gather kernels run on the CPU, the second with the first as its addend) against the sum of the two reconstructed
+    dense operands, bit for bit, and Property 5 for the result."""
+    if CLANG is None:
+        pytest.skip("no clang++ for the host build")
+    (mt, mred, mpred, muniq), (vt, vred, vpred, vuniq), dims, params, want = SUMS[name]
+    dm, dv = st.Descriptor(mt, dims, mred, **params), st.Descriptor(vt, dims, vred, **params)
+    if want is None:
+        with pytest.raises(st.StructTensorError) as e:
+            dm.sum(dv)
+        assert e.value.status == 6 and "sum of nests" in str(e.value)
+        return
+    apred, auniq = want
+    da = dm.sum(dv)
+    lst = oracle.struct_enumerate(dims, apred)
+    assert da.count == lst.shape[0]
+    Mc, Vc = W.uniform(801, dm.count), W.uniform(802, dv.count)
+    dense = oracle.struct_expand(Mc, dims, mpred, muniq) + oracle.struct_expand(Vc, dims, vpred, vuniq)     # fp32 sums
+    gm = _run_generated(dm, str(tmp_path / "m"), dims, Mc, gather_idx=lst)
+    ac = _run_generated(dv, str(tmp_path / "v"), dims, Vc, gather_idx=lst, addend=gm)
+    cols = tuple(lst[:, v].astype(np.int64) for v in range(len(dims)))
+    assert np.array_equal(ac, dense[cols])
+    _run_generated(da, str(tmp_path / "a"), dims, ac)
+    got = np.fromfile(str(tmp_path / "a" / "list.i32"), dtype=np.int32).reshape(-1, len(dims))
+    assert np.array_equal(got, lst)
+    ex = np.fromfile(str(tmp_path / "a" / "expand.f32"), dtype=np.float32).reshape(dims)
+    assert np.array_equal(ex, dense)
+    assert np.array_equal(oracle.struct_expand(ac, dims, apred, auniq), dense)

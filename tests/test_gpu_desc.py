@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 
 import st_workloads as W
-from test_desc import CASES, OUTERS
+from test_desc import CASES, OUTERS, SUMS
 
 pytestmark = pytest.mark.gpu
 
@@ -382,3 +382,26 @@ def test_self_product_structure_drives_the_moment_kernels(st, oracle, k):
     assert np.array_equal(p.expand(Sc).cpu().numpy().view(np.uint32), st.expand_sym(Sc, n, k).cpu().numpy().view(np.uint32))
     v.close()
     p.close()
+
+
+@pytest.mark.parametrize("name", sorted(k for k, v in SUMS.items() if v[4] is not None))
+def test_sum_of_structured_operands(st, oracle, name):
+    """A(x) := M(x) + V(x) on the GPU: inferred descriptor, values from two gathers (the second adds the first),
+    against the sum of the two reconstructed dense operands, and Property 5 for the result."""
+    say("descriptor sum", name)
+    (mt, mred, mpred, muniq), (vt, vred, vpred, vuniq), dims, params, (apred, auniq) = SUMS[name]
+    dm, dv = st.Descriptor(mt, dims, mred, **params), st.Descriptor(vt, dims, vred, **params)
+    Mc, Vc = W.uniform(801, max(dm.count, 4)), W.uniform(802, max(dv.count, 4))
+    da, Ac = st.add_struct(dm, dev(Mc), dv, dev(Vc))
+    lst = oracle.struct_enumerate(dims, apred)
+    assert da.count == lst.shape[0] == Ac.numel()
+    assert np.array_equal(da.list().cpu().numpy(), lst)
+    dense = oracle.struct_expand(Mc[: dm.count], dims, mpred, muniq) + oracle.struct_expand(Vc[: dv.count], dims, vpred, vuniq)
+    cols = tuple(lst[:, v].astype(np.int64) for v in range(len(dims)))
+    assert np.array_equal(Ac.cpu().numpy(), dense[cols])
+    import torch
+    buf = torch.zeros(max(da.count, 4), device="cuda")
+    buf[: da.count] = Ac
+    assert np.array_equal(da.expand(buf).cpu().numpy(), dense)
+    for d in (dm, dv, da):
+        d.close()
