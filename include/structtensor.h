@@ -406,6 +406,22 @@ st_status st_desc_gather(st_desc *desc, const void *table, const float *Tc, cons
  * gather(M, list(A))). */
 st_status st_desc_sum(const st_desc *m, const st_desc *v, st_desc **out);
 
+/* Marginalization of the LAST variable,  A(x_0..x_{d-2}) := sum over x_{d-1} of
+ * B(x)  (a rule whose head leaves a variable of the body out sums over it;
+ * "Unique Set Inference", projection: the output is non-zero wherever some
+ * value of the dropped variable is stored).  st_desc_project infers the
+ * descriptor of A: the bounds of the earlier variables plus, for every pair
+ * (lower bound, upper bound) of the dropped variable, the comparison
+ * lower <= upper -- exact for the affine integer bounds descriptors have.
+ * Its packed order is the run order of B, so st_desc_sum_last(B) writes the
+ * packed values of A: out[run] = sum of the entries of the run (DEVICE fp32,
+ * st_desc_runs(B) = st_desc_count(A) values, fixed summation order).  The
+ * output structure of the kernel table's TTM is
+ * st_desc_outer(st_desc_project(B), <range of k>).  ST_ERR_UNSUPPORTED for
+ * operands with a redundancy map. */
+st_status st_desc_project(const st_desc *b, st_desc **out);
+st_status st_desc_sum_last(st_desc *desc, const void *table, const float *Bc, float *out, void *stream);
+
 /* Structure inference for the tensor outer product  T(x, y) := M(x) * V(y)
  * over disjoint index lists, the variables of V behind those of M, total order
  * at most 4 ("Redundancy Map Inference", outer-product rule):

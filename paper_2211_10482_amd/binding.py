@@ -82,6 +82,8 @@ SIGNATURES = {
     "st_desc_product": (_I32, [_P, _P, _P]),
     "st_desc_gather": (_I32, [_P, _P, _P, _P, _I64, _I32, _I32, _P, _P, _P, _P]),
     "st_desc_sum": (_I32, [_P, _P, _P]),
+    "st_desc_project": (_I32, [_P, _P]),
+    "st_desc_sum_last": (_I32, [_P, _P, _P, _P, _P]),
     "st_desc_outer": (_I32, [_P, _P, _P]),
     "st_desc_power": (_I32, [_P, _I32, _P]),
     "st_desc_moment_workspace": (_SZ, [_P, _I64]),
@@ -644,6 +646,22 @@ class Descriptor:
         h = C.c_void_p()
         return self._derived(lib().st_desc_power(self._h, int(k), C.byref(h)), h, "st_desc_power",
                              tuple(self.dims) * int(k))
+
+    def project(self):
+        """Descriptor of A(x_0..x_{d-2}) = sum over the last variable of this tensor (structure inference)."""
+        h = C.c_void_p()
+        return self._derived(lib().st_desc_project(self._h, C.byref(h)), h, "st_desc_project", self.dims[:-1])
+
+    def sum_last(self, Bc, out=None):
+        """Packed values of the projection: the sum of every run of the unique set (in run order)."""
+        torch = _torch()
+        _expect(Bc, self.count, "Bc", at_least=True)
+        if out is None:
+            out = torch.empty(max(self.runs, 4), dtype=torch.float32, device=Bc.device)
+        _expect(out, self.runs, "out", at_least=True)
+        self._call(lib().st_desc_sum_last(self._h, self._tab(), _dev_f32(Bc, "Bc"), _dev_f32(out, "out"), _stream()),
+                   "st_desc_sum_last")
+        return out[:self.runs]
 
     def sum(self, other):
         """Descriptor of the sum of two structured operands of the same shape (structure inference)."""

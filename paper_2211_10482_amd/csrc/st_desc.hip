@@ -218,7 +218,7 @@ struct Desc {
     i64 mbs = 0, ntiles = 0, mnp = 0;
     std::string nest, source;
     std::mutex mu;
-    struct Loaded { hipModule_t mod; hipFunction_t fn[8]; };   // list, thp, expand, gather, moment, moment_reduce, mttkrp, mttkrp_combine
+    struct Loaded { hipModule_t mod; hipFunction_t fn[9]; };   // list, thp, expand, gather, moment, moment_reduce, mttkrp, mttkrp_combine, sum_last
     std::map<int, Loaded> modules;               // per device
     std::string error;
 };
@@ -570,6 +570,22 @@ void build_source(Desc &D)
         s += "    const float v = (" + at + ") ? st_value(tab, Tc, " + xs + ") : 0.f;\n";
     }
     s += "    const float w = scale ? scale[p] * v : v;\n    out[p] = addend ? w + addend[p] : w;\n}\n";
+    // marginalization of the last variable: out(run) = sum of the entries of the run, in a fixed order (the lanes'
+    // partial sums in lane order); a group of L = min(64, workgroup size) threads per run
+    s += "extern \"C\" __global__ void st_gen_sum_last(const int *__restrict__ tab, const float *__restrict__ Bc,\n"
+         "                                           float *__restrict__ out)\n{\n";
+    s += "    __shared__ float st_lane[256];\n";
+    s += "    const int tid = threadIdx.x, nt = blockDim.x, L = nt < 64 ? nt : 64, ln = tid % L, g = tid / L;\n";
+    s += "    const int run = blockIdx.x * (nt / L) + g;\n";
+    s += "    float acc = 0.f;\n";
+    s += "    int start = 0;\n";
+    s += "    if (run < ST_NRUNS) {\n        const int pf = tab[ST_PREFIXES + run];\n        ST_DECODE_PREFIX(pf)\n";
+    s += "        const int lo = st_lo" + std::to_string(d - 1) + "(" + pre + "), hi = st_hi" + std::to_string(d - 1) + "(" + pre + ");\n";
+    s += "        start = tab[pf];\n";
+    s += "        for (int p = ln; p <= hi - lo; p += L) acc += Bc[start + p];\n    }\n";
+    s += "    st_lane[tid] = acc;\n    __syncthreads();\n";
+    s += "    if (ln == 0 && run < ST_NRUNS) {\n        float v = 0.f;\n        for (int q = 0; q < L; ++q) v += st_lane[g * L + q];\n";
+    s += "        out[run] = v;\n    }\n}\n";
     if (d == 3) {
         // MTTKRP of the kernel table over the unique set: A(x0, r) = sum over the stored (x1, x2) of row x0 of
         // Bc(rank(x)) * C(x1, r) * D(x2, r).  One workgroup per output row x0 and block of 16 columns r; its
@@ -1043,6 +1059,47 @@ st_status infer_sum(const Desc &M, const Desc &V, Desc &A)
     return ST_ERR_UNSUPPORTED;
 }
 
+// A(x_0..x_{d-2}) := sum over x_{d-1} of B(x): a rule head that leaves a variable of the body out sums over it
+// ("marginalization"); "Unique Set Inference", projection: the output is non-zero where ANY value of the dropped
+// variable is stored, i.e. where the run of that prefix is not empty.  With affine integer bounds and a unit
+// coefficient on the dropped variable, "some x with every lower bound <= x <= every upper bound" is exactly
+// "every lower bound <= every upper bound": one comparison among the earlier variables per pair of bounds.
+// The packed order of the result is the run order of the operand.
+st_status infer_project(const Desc &B, Desc &A)
+{
+    if (B.d < 2) { A.error = "nothing is left of an order-1 tensor"; return ST_ERR_SHAPE; }
+    if (B.red_sort || !B.red.empty()) { A.error = "projection of an operand with a redundancy map is not supported"; return ST_ERR_UNSUPPORTED; }
+    const int d = B.d - 1, last = B.d - 1;
+    A.d = d;
+    A.name = "A";
+    for (int v = 0; v < d; ++v) { A.vars.push_back(B.vars[(size_t)v]); A.dims[v] = B.dims[v]; }
+    Bound k;
+    for (int u = 0; u < MAXD; ++u) k.coef[u] = 0;
+    for (int v = 0; v < d; ++v) {
+        k.c = B.first[v];
+        A.lo[v].push_back(k);
+        k.c = B.last[v];
+        A.hi[v].push_back(k);
+        for (auto &q : B.lo[v]) A.lo[v].push_back(q);
+        for (auto &q : B.hi[v]) A.hi[v].push_back(q);
+    }
+    A.empty = B.empty;
+    std::vector<Bound> los = B.lo[last], his = B.hi[last];
+    k.c = B.first[last];
+    los.push_back(k);
+    k.c = B.last[last];
+    his.push_back(k);
+    for (auto &l : los)
+        for (auto &h : his) {
+            Bound c;                                       // h - l >= 0
+            c.c = h.c - l.c;
+            for (int u = 0; u < MAXD; ++u) c.coef[u] = h.coef[u] - l.coef[u];
+            std::string err;
+            if (!attach(A, c, false, err)) { A.error = "the comparison left by the dropped variable: " + err; return ST_ERR_UNSUPPORTED; }
+        }
+    return finish(A);
+}
+
 // Tensor outer product T(x, y) := M(x) * V(y) over disjoint index lists ("Redundancy Map Inference", outer
 // product rule): T_U = M_U * V_U; T_R = M_U * V_R + M_R * V_U + M_R * V_R.  The variables of V follow those of M.
 // A term of V alone maps the V part and keeps the M part (and the other way round); where both parts are
@@ -1190,11 +1247,11 @@ st_status module_for(Desc &D, Desc::Loaded &out)
     if (hipModuleLoadData(&L.mod, code.data()) != hipSuccess) { D.error = "hipModuleLoadData failed"; return ST_ERR_LAUNCH; }
     const char *names[6] = {"st_gen_list", "st_gen_thp", "st_gen_expand", "st_gen_gather", "st_gen_moment",
                             "st_gen_moment_reduce"};
-    L.fn[4] = L.fn[5] = L.fn[6] = L.fn[7] = nullptr;
-    for (int q = 0; q < 8; ++q) {
+    L.fn[4] = L.fn[5] = L.fn[6] = L.fn[7] = L.fn[8] = nullptr;
+    for (int q = 0; q < 9; ++q) {
         if ((q == 4 || q == 5) && D.ntiles == 0) continue;      // moment kernels: equal extents only
-        if (q >= 6 && D.d != 3) continue;                       // MTTKRP: order 3 only
-        const char *name = q == 6 ? "st_gen_mttkrp" : q == 7 ? "st_gen_mttkrp_combine" : names[q];
+        if ((q == 6 || q == 7) && D.d != 3) continue;           // MTTKRP: order 3 only
+        const char *name = q == 6 ? "st_gen_mttkrp" : q == 7 ? "st_gen_mttkrp_combine" : q == 8 ? "st_gen_sum_last" : names[q];
         if (hipModuleGetFunction(&L.fn[q], L.mod, name) != hipSuccess) {
             (void)hipModuleUnload(L.mod);
             D.error = std::string("generated kernel missing: ") + name;
@@ -1451,6 +1508,29 @@ st_status st_desc_sum(const st_desc *m, const st_desc *v, st_desc **out)
     const st_status rc = infer_sum(*M, *V, *A);
     *out = reinterpret_cast<st_desc *>(A);
     return rc;
+}
+
+st_status st_desc_project(const st_desc *b, st_desc **out)
+{
+    if (!b || !out) return ST_ERR_NULL;
+    const Desc *B = reinterpret_cast<const Desc *>(b);
+    if (B->source.empty()) return ST_ERR_SHAPE;
+    Desc *A = new Desc();
+    const st_status rc = infer_project(*B, *A);
+    *out = reinterpret_cast<st_desc *>(A);
+    return rc;
+}
+
+st_status st_desc_sum_last(st_desc *desc, const void *table, const float *Bc, float *out, void *stream)
+{
+    if (!desc || !table || !Bc || !out) return ST_ERR_NULL;
+    Desc *D = reinterpret_cast<Desc *>(desc);
+    if (D->source.empty()) return ST_ERR_SHAPE;
+    if (D->red_sort || !D->red.empty()) return ST_ERR_UNSUPPORTED;
+    if (!aligned16(table) || !aligned16(Bc) || !aligned16(out)) return ST_ERR_ALIGN;
+    if (overlap(out, (size_t)D->nruns * 4, Bc, (size_t)D->count * 4)) return ST_ERR_SHAPE;
+    void *args[] = {&table, &Bc, &out};
+    return launch_generated(*D, 8, (unsigned)((D->nruns + 3) / 4), args, (hipStream_t)stream);
 }
 
 st_status st_desc_power(const st_desc *v, int k, st_desc **out)

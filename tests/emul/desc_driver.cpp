@@ -4,7 +4,8 @@
 // cross-lane operations, so a launch run as nested loops computes exactly what the GPU computes; the
 // moment kernels are launched in a shape (one thread per block, one slice) for which that also holds.
 //   argv: dir count box order nruns last_dim [N]  (dir holds table.i32, bc.f32 [count], c.f32 [box], x.f32 [N*n])
-//   writes list.i32 [count*order], thp.f32 [count], expand.f32 [box] (expansion of bc.f32), moment.f32 [count]
+//   writes list.i32 [count*order], thp.f32 [count], expand.f32 [box] (expansion of bc.f32), moment.f32 [count],
+//   sum_last.f32 [nruns] (every run of bc.f32 summed)
 //   when dir holds gather.i32 ([g][order] dense positions; gather_scale.f32 [g] optional): gather.f32 [g]
 //   when dir holds mk_r.i32 (order 3): mttkrp.f32 [dim0][R] from mk_c.f32 [dim1][R] and mk_d.f32 [dim2][R]
 #include <hip/hip_runtime.h>
@@ -110,6 +111,12 @@ int main(int argc, char **argv)
         }
     }
 #endif
+    {   // marginalization of the last variable, one thread per workgroup (its sum over the lanes needs a barrier)
+        std::vector<float> sums(nruns ? nruns : 1, -7.f);
+        if (nruns) hipLaunchKernelGGL(st_gen_sum_last, dim3((unsigned)nruns), dim3(1), 0, 0, tab.data(), bc.data(), sums.data());
+        sums.resize(nruns);
+        wr(dir + "/sum_last.f32", sums);
+    }
     wr(dir + "/list.i32", list);
     wr(dir + "/thp.f32", thp);
     wr(dir + "/expand.f32", ex);

@@ -198,6 +198,16 @@ def test_generated_kernels_on_the_cpu(descs, oracle, tmp_path, name):
     ex = np.fromfile(str(tmp_path / "expand.f32"), dtype=np.float32).reshape(dims)
     ref = oracle.struct_expand(Bc, dims, pred, unique_of)
     assert np.array_equal(ex.view(np.uint32), ref.view(np.uint32))
+    # every run summed (marginalization of the last variable): against the zero-filled dense operand summed over
+    # its last axis, at the prefixes that hold a run, in nest order
+    if red is None and d.count:
+        sums = np.fromfile(str(tmp_path / "sum_last.f32"), dtype=np.float32)
+        Bz = np.zeros(dims, dtype=np.float64)
+        Bz[tuple(lst[:, v].astype(np.int64) for v in range(len(dims)))] = Bc
+        tot, hit = Bz.sum(axis=-1).reshape(-1), np.zeros(dims, dtype=bool)
+        hit[tuple(lst[:, v].astype(np.int64) for v in range(len(dims)))] = True
+        want = tot[hit.any(axis=-1).reshape(-1)]
+        assert sums.size == d.runs == want.size and float(np.abs(sums - want).max()) <= 1e-5 * max(float(np.abs(want).max()), 1.0)
     if has_mttkrp:
         # against the dense definition on the zero-filled operand (the C oracle), row by row
         got = np.fromfile(str(tmp_path / "mttkrp.f32"), dtype=np.float32).reshape(dims[0], R)
@@ -508,3 +518,52 @@ def test_sum_inference(oracle, tmp_path, name):
     ex = np.fromfile(str(tmp_path / "a" / "expand.f32"), dtype=np.float32).reshape(dims)
     assert np.array_equal(ex, dense)
     assert np.array_equal(oracle.struct_expand(ac, dims, apred, auniq), dense)
+
+
+# ------------------------------------------------------------------ projection: a rule head that drops the last variable
+# name -> (text, dims, params, predicate, expected nest lines of the projection or None)
+PROJECTIONS = {
+    # the band tensor of the TTM workload: the last variable is free, the projection is the band on (i,j)
+    "band": ("B(i,j,l): (0<=i<n)*(i-w<=j<=i+w)*(0<=l<m)", (9, 9, 5), dict(n=9, w=2, m=5), lambda i, j, l: abs(i - j) <= 2,
+             ["for (i = 0; i <= 8; ++i)", "  for (j = max(0, i - 2); j <= min(8, i + 2); ++j)"]),
+    # a tetrahedron of non-zeros: some l >= j exists for every j
+    "tetra": ("B(i,j,l): (0<=i<n)*(i<=j<n)*(j<=l<n)", (6, 6, 6), dict(n=6), lambda i, j, l: i <= j <= l,
+              ["for (i = 0; i <= 5; ++i)", "  for (j = i; j <= 5; ++j)"]),
+    # the run of (i,j) is i-j <= l < m: not empty only when i - j <= m - 1, a comparison the dropped variable leaves behind
+    "staircase": ("B(i,j,l): (0<=i<n)*(0<=j<=i)*(i-j<=l<m)", (7, 7, 3), dict(n=7, m=3), lambda i, j, l: j <= i and i - j <= l < 3,
+                  ["for (i = 0; i <= 6; ++i)", "  for (j = max(0, i - 2); j <= i; ++j)"]),
+    # two bounds on both sides of the last variable (an anti-diagonal band): every row keeps some column
+    "anti": ("A(i,j): (0<=i<n)*(n-2<=i+j<=n)", (7, 7), dict(n=7), lambda i, j: 5 <= i + j <= 7, ["for (i = 0; i <= 6; ++i)"]),
+    # nothing stored below a threshold of the first variable
+    "late": ("L(i,j): (0<=i<n)*(0<=j<=i-3)", (8, 8), dict(n=8), lambda i, j: j <= i - 3, ["for (i = 3; i <= 7; ++i)"]),
+    "diag": ("D(i,j): (0<=i<n)*(i=j)", (6, 6), dict(n=6), lambda i, j: i == j, ["for (i = 0; i <= 5; ++i)"]),
+}
+
+
+@pytest.mark.parametrize("name", sorted(PROJECTIONS))
+def test_projection_inference(oracle, name):
+    """A(x') := sum over the last variable of B(x', l): the inferred unique set is "some l is stored" (brute force),
+    its nest is the expected one, and its packed order is the run order of B."""
+    text, dims, params, pred, nest = PROJECTIONS[name]
+    b = st.Descriptor(text, dims, None, **params)
+    a = b.project()
+    exists = lambda *x: any(pred(*x, l) for l in range(dims[-1]))
+    lst = oracle.struct_enumerate(dims[:-1], exists)
+    assert a.count == lst.shape[0] == b.runs
+    assert a.nest.splitlines()[:len(nest)] == nest, a.nest
+    full = oracle.struct_enumerate(dims, pred)
+    heads = np.unique(full[:, :-1], axis=0)                          # prefixes that hold a run, sorted = nest order
+    assert np.array_equal(heads.reshape(lst.shape), lst)
+    a.close()
+    b.close()
+
+
+def test_projection_limits():
+    s = st.Descriptor("S(i,j): (0<=i<=j<n)", (4, 4), "sort", n=4)
+    with pytest.raises(st.StructTensorError) as e:
+        s.project()
+    assert e.value.status == 6
+    v = st.Descriptor("v(i): (0<=i<n)", (4,), None, n=4)
+    with pytest.raises(st.StructTensorError) as e:
+        v.project()
+    assert e.value.status == 2

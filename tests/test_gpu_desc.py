@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 
 import st_workloads as W
-from test_desc import CASES, OUTERS, SUMS
+from test_desc import CASES, OUTERS, PROJECTIONS, SUMS
 
 pytestmark = pytest.mark.gpu
 
@@ -404,4 +404,47 @@ def test_sum_of_structured_operands(st, oracle, name):
     buf[: da.count] = Ac
     assert np.array_equal(da.expand(buf).cpu().numpy(), dense)
     for d in (dm, dv, da):
+        d.close()
+
+
+@pytest.mark.parametrize("name", sorted(PROJECTIONS))
+def test_projection_of_a_structured_operand(st, oracle, name):
+    """A(x') := sum_l B(x', l) on the GPU: inferred descriptor (packed order = run order of B) and the run sums of
+    the generated kernel against the zero-filled dense operand summed over its last axis; bit-identical twice."""
+    say("descriptor projection", name)
+    text, dims, params, pred, _ = PROJECTIONS[name]
+    b = st.Descriptor(text, dims, None, **params)
+    a = b.project()
+    lst = oracle.struct_enumerate(dims, pred)
+    Bc = W.uniform(811, max(b.count, 4))
+    Bz = np.zeros(dims, dtype=np.float64)
+    cols = tuple(lst[:, v].astype(np.int64) for v in range(len(dims)))
+    Bz[cols] = Bc[: b.count]
+    alst = a.list().cpu().numpy()
+    want = Bz.sum(axis=-1)[tuple(alst[:, v].astype(np.int64) for v in range(len(dims) - 1))]
+    got = b.sum_last(dev(Bc)).cpu().numpy()
+    assert got.shape == want.shape and float(np.abs(got - want).max()) <= 1e-5 * max(float(np.abs(want).max()), 1.0)
+    assert np.array_equal(got, b.sum_last(dev(Bc)).cpu().numpy())
+    a.close()
+    b.close()
+
+
+def test_ttm_output_structure_is_projection_times_range(st, oracle):
+    """The kernel table's TTM, A(i,j,k) := B(i,j,l) * C(k,l): its output structure by inference is the projection of
+    B's over l, outer product with the range of k -- and that is the packed layout st_desc_ttm writes: row p of its
+    output is entry (i,j) number p of the projected descriptor, all k."""
+    n, w, nl, R = 40, 3, 64, 16
+    b = st.Descriptor("B(i,j,l): (0<=i<n)*(i-w<=j<=i+w)*(0<=l<m)", (n, n, nl), None, n=n, w=w, m=nl)
+    k = st.Descriptor("k(r): (0<=r<R)", (R,), None, R=R)
+    a = b.project().outer(k)
+    assert a.count == b.runs * R and a.dims == (n, n, R)
+    pairs = oracle.list_band(n, w).astype(np.int32)
+    want = np.concatenate([np.repeat(pairs, R, axis=0), np.tile(np.arange(R, dtype=np.int32), pairs.shape[0])[:, None]], axis=1)
+    assert np.array_equal(a.list().cpu().numpy(), want)
+    Bc, U = W.uniform(821, b.count).reshape(-1, nl), W.uniform(822, nl * R).reshape(nl, R)
+    Ac = b.ttm(dev(Bc), dev(U))                                       # [runs][R] = the packed values of A
+    dense = a.expand(Ac.reshape(-1)).cpu().numpy()                    # reconstruction through the inferred descriptor
+    ref = oracle.ttm_dense(Bc.reshape(-1), U, n, w)
+    assert float(np.abs(dense - ref).max()) <= 1e-4 * float(np.abs(ref).max())
+    for d in (a, b, k):
         d.close()
