@@ -6,6 +6,17 @@
 
 #include "../../include/structtensor.h"
 
+// Two statements the kernels use to steer the compiler, as macros so that a build of the kernel sources for
+// another target can give them its own meaning (the CPU bounds-check build of the tests defines both as nothing):
+// ST_PIN_VGPR(x): an empty statement the compiler cannot see through, which pins x in a vector register here;
+// ST_WAIT_STATES(n): n + 1 idle issue cycles.
+#ifndef ST_PIN_VGPR
+#define ST_PIN_VGPR(x) asm volatile("" : "+v"(x))
+#endif
+#ifndef ST_WAIT_STATES
+#define ST_WAIT_STATES(n) asm volatile("s_nop " #n)
+#endif
+
 namespace st {
 
 // Number of compute units of the current device (cached per device).

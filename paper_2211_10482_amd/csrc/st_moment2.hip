@@ -589,9 +589,7 @@ __device__ __forceinline__ f32x4 m2w_mask(f32x4 v, int64_t s, int64_t s_end, u32
 {
     const int64_t rows = s_end - s;
     if (rows < 4) {                                                          // wave-uniform, the end of a slice only
-#ifndef ST_HOST_EMULATION
-        asm volatile("" : "+v"(v));                                          // a branch, not four selects per quad
-#endif
+        ST_PIN_VGPR(v);                                                      // a branch, not four selects per quad
         const bool row_ok = (int64_t)q < rows;
 #pragma unroll
         for (u32 g = 0; g < 4; ++g) v[g] = row_ok ? v[g] : 0.f;
@@ -768,11 +766,6 @@ __global__ __launch_bounds__(256) void moment2_strip_reduce_kernel(const float *
 {
     __shared__ float part[8][32];
     const u32 a = threadIdx.x & 31u, g = threadIdx.x >> 5;
-#ifdef ST_HOST_EMULATION
-    // threads run one after the other there, each with an array of its own: what the other groups would have
-    // written (zeros, the emulated runs have one slice) is set here
-    for (u32 k = 0; k < 8u; ++k) part[k][a] = 0.f;
-#endif
     const u32 id = blockIdx.x * 32u + a;                 // < ntasks * M2W_ACC
     const u32 task = id / (u32)M2W_ACC, e = id % (u32)M2W_ACC;
     const u32 blk = e >> 12, tile = (e >> 8) & 15u, v = (e >> 6) & 3u, lane = e & 63u;

@@ -84,7 +84,7 @@ template <int M> __device__ __forceinline__ float row_bcast(float v)
 // and the block of these products starts with the required wait states).
 template <int M> __device__ __forceinline__ float mul_bcast(float bsrc, float other)
 {
-#ifdef ST_HOST_EMULATION   // CPU bounds-check build of the tests: no GPU instructions
+#ifdef ST_NO_GPU_ASSEMBLY   // a build of this source for another target (the CPU bounds check of the tests)
     return row_bcast<M>(bsrc) * other;
 #else
     float r;
@@ -186,9 +186,7 @@ __device__ __forceinline__ void m3_step(f32x4 (&acc)[M3_TPW], const f32x4 &xa, b
     // MFMAs back to back: a product that is formed right in front of its MFMA in
     // a recycled register has to wait for the previous MFMA to release it.
     float p[M3_TPW];
-#ifndef ST_HOST_EMULATION
-    asm volatile("s_nop 1");
-#endif
+    ST_WAIT_STATES(1);
     static_for<M3_TPW>([&](auto T) {
         constexpr TileDesc td = tile_desc(W, decltype(T)::value);
         if constexpr (td.kind == 1 && m3_product_of(W, decltype(T)::value) == decltype(T)::value)

@@ -258,11 +258,9 @@ __device__ __forceinline__ void mm_store_chunk(const f32x4 (&r)[MM_UNITS], const
 // partial (+)= accumulators, six tiles at a time (all 96 values in flight at once would not fit the registers)
 __device__ __forceinline__ void mm_flush(const f32x4 (&acc)[MM_TPB], float *dst, bool add)
 {
-#ifndef ST_HOST_EMULATION
     // the 96 addresses are formed here, from immediates, and not ahead of the chunk loop (where they would be
     // kept in registers the loop needs)
-    asm volatile("" : "+v"(dst));
-#endif
+    ST_PIN_VGPR(dst);
 #pragma unroll
     for (int t0 = 0; t0 < MM_TPB; t0 += 6) {
         float old[6][4];

@@ -15,7 +15,9 @@
 #include <string.h>
 #include <algorithm>
 
-#define ST_HOST_EMULATION 1   // kernels skip their inline GPU assembly
+#define ST_NO_GPU_ASSEMBLY 1   // the one hand-written GPU instruction of the kernels falls back to its plain form
+#define ST_PIN_VGPR(x) ((void)0)
+#define ST_WAIT_STATES(n) ((void)0)
 #define __global__
 #define __device__
 #define __host__

@@ -79,7 +79,9 @@ def builds(tmp_path_factory):
     def build(fam):
         exe = str(out / ("bounds_" + fam.lower()))
         opt = "-O0" if fam == "COVARSMALL" else "-O1"       # its unrolled loop nests take minutes to optimise
-        cmd = [CLANG, "-std=c++17", opt, "-g", "-fsanitize=address", "-fno-omit-frame-pointer",
+        # (a shared array is a local array of the emulated thread; locals start at zero so that a thread which reads
+        # what the other threads of its workgroup would have written reads zeros, not stack contents)
+        cmd = [CLANG, "-std=c++17", opt, "-g", "-fsanitize=address", "-fno-omit-frame-pointer", "-ftrivial-auto-var-init=zero",
                "-DCHECK_" + fam, "-I", EMUL, "-x", "c++", os.path.join(EMUL, "bounds_check.cpp"), "-o", exe]
         r = subprocess.run(cmd, capture_output=True, text=True)
         assert r.returncode == 0, "host build of %s failed:\n%s" % (fam, r.stderr[-4000:])
