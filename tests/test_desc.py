@@ -567,3 +567,23 @@ def test_projection_limits():
     with pytest.raises(st.StructTensorError) as e:
         v.project()
     assert e.value.status == 2
+
+
+def test_constant_range_rule_written_as_text(oracle, tmp_path):
+    """The constant-range rule (T(x) := b <= x < c: only x = b is stored, every other element of the range takes its
+    value): one redundancy term per variable, each excluding b itself so that Property 1 holds; a single stored
+    value reconstructs the whole range, zero outside it."""
+    if CLANG is None:
+        pytest.skip("no clang++ for the host build")
+    dims = (5, 6)
+    d = st.Descriptor("T(i,j): (i=1)*(j=2)", dims, "(1<i<4)*(2<=j<5) -> (1,2); (i=1)*(2<j<5) -> (1,2)")
+    assert d.count == 1
+    _run_generated(d, str(tmp_path / "c"), dims, np.array([3.25], dtype=np.float32))
+    ex = np.fromfile(str(tmp_path / "c" / "expand.f32"), dtype=np.float32).reshape(dims)
+    want = np.zeros(dims, dtype=np.float32)
+    want[1:4, 2:5] = 3.25
+    assert np.array_equal(ex, want)
+    with pytest.raises(st.StructTensorError) as e:                  # the range itself as the condition meets (1,2)
+        st.Descriptor("T(i,j): (i=1)*(j=2)", dims, "(1<=i<4)*(2<=j<5) -> (1,2)")
+    assert e.value.status == 2 and "disjoint" in str(e.value)
+    d.close()
