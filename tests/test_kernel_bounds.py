@@ -98,3 +98,20 @@ def test_kernel_addressing_in_bounds(builds, fam):
     for case in CASES[fam]:
         r = subprocess.run([builds[fam]] + [str(v) for v in case], capture_output=True, text=True, timeout=600)
         assert r.returncode == 0 and "rc=0" in r.stdout, "%s %s:\n%s\n%s" % (fam, case, r.stdout[-500:], r.stderr[-4000:])
+
+
+def test_random_ttm_shapes_in_bounds(builds):
+    """The contraction launcher picks among five kernels by shape (one-shot, persistent split-K, streaming split-K,
+    general MFMA, plain): a seeded sweep of 400 random shapes, dense around the row counts where the choice changes,
+    through the same bounds check."""
+    import random
+    rng = random.Random(20221118)
+    for _ in range(400):
+        nl = rng.choice([64, 128, 192, 256, 320, 384, 448, 512, 576, 1024, 33, 100, 7, 1, 16, 48])
+        R = rng.choice([16, 32, 48, 64, 5, 20, 50, 63, 1, 128, 250, 300])
+        rows = rng.choice([rng.randint(1, 600), rng.randint(3900, 4300), rng.randint(8000, 8400), rng.randint(12000, 12400),
+                           rng.randint(16300, 16500), rng.randint(1, 40000)])
+        if rows * nl > 12_000_000:
+            continue
+        r = subprocess.run([builds["TTM"], str(rows), str(nl), str(R)], capture_output=True, text=True, timeout=600)
+        assert r.returncode == 0 and "rc=0" in r.stdout, "TTM %s:\n%s" % ((rows, nl, R), r.stderr[-3000:])
