@@ -881,3 +881,34 @@ def test_whole_step_can_be_captured(st, oracle):
         if rep == 0:
             check(out["M4"].cpu().numpy(), oracle.mttkrp_sym3(buf["T4"].cpu().numpy(), buf["B4"].cpu().numpy()), "captured mttkrp")
             check(out["y"].cpu().numpy(), oracle.batax_utri(buf["Ap"].cpu().numpy(), buf["x"].cpu().numpy(), 0.5), "captured batax")
+
+
+def test_random_shapes_against_the_oracle(st, oracle):
+    """A seeded sweep over shapes no other case names: the launchers choose kernels by shape (row kernel, pair items
+    and repacked tensors for MTTKRP; one- and two-pass BATAX; five contraction kernels behind the band TTM; the
+    lane-per-sample, matrix-core and register-tile moment kernels), and every choice must agree with the oracle."""
+    import random
+    rng = random.Random(20221118)
+    say("random shapes against the oracle")
+    for _ in range(24):
+        n = rng.choice([rng.randint(1, 40), rng.randint(41, 100), rng.choice([16, 32, 48, 64, 96, 112])])
+        R = rng.choice([1, 3, 16, 20, 32, 33, 64, 80])
+        Tc, B = W.uniform(rng.randrange(1 << 30), oracle.count_sym3(n)), W.uniform(rng.randrange(1 << 30), n * R).reshape(n, R)
+        check(st.mttkrp_sym3(dev(Tc), dev(B)).cpu().numpy(), oracle.mttkrp_sym3(Tc, B), None)
+    for _ in range(12):
+        n = rng.choice([rng.randint(1, 300), rng.randint(1000, 3000)])
+        Ap, x = W.uniform(rng.randrange(1 << 30), oracle.count_sym2(n)), W.uniform(rng.randrange(1 << 30), n)
+        check(st.batax_utri(dev(Ap), dev(x), 0.5).cpu().numpy(), oracle.batax_utri(Ap, x, 0.5), None)
+    for _ in range(24):
+        n, w = rng.randint(1, 60), rng.randint(0, 9)
+        nl, R = rng.choice([64, 128, 192, 256, 512, 33, 100, 7, 1]), rng.choice([16, 32, 48, 64, 5, 20, 63, 1, 130])
+        pairs = oracle.count_band(n, w)
+        Tc, U = W.uniform(rng.randrange(1 << 30), pairs * nl).reshape(pairs, nl), W.uniform(rng.randrange(1 << 30), nl * R).reshape(nl, R)
+        check(st.ttm_band(dev(Tc), dev(U), n, w).cpu().numpy(), oracle.ttm_band(Tc.reshape(-1), U, n, w), None)
+    for _ in range(24):
+        n, N = rng.choice([rng.randint(1, 64), rng.randint(65, 100)]), rng.choice([1, 3, 63, 64, 65, 257, 1000])
+        X = W.normal(rng.randrange(1 << 30), N * n).reshape(N, n)
+        check(st.moment3_sym(dev(X)).cpu().numpy(), oracle.moment3_entries(X, oracle.list_sym3(n)), None)
+        check(st.moment2_sym(dev(X)).cpu().numpy(), oracle.moment2_dense(X)[np.triu_indices(n)], None)
+        if n <= 40:
+            check(st.moment4_sym(dev(X)).cpu().numpy(), oracle.moment4_entries(X, oracle.list_sym4(n)), None)
