@@ -347,3 +347,21 @@ def struct_moment(X, dims, in_unique):
             prod = prod * Xd[s, idx[:, v]]
         out += prod
     return out
+
+
+def direct_sum(M, V):
+    """T = M (+) V for two dense arrays of the same order ("Representation of linear algebra operations", the
+    rule for the direct sum; "Redundancy Map Inference", direct-sum rule): with d = dims(M), element x of the
+    result is M(x) where every index lies below d, V(x - d) where every index lies at or above d, zero
+    elsewhere.  Written as that case distinction, one element at a time."""
+    import itertools
+    M, V = np.asarray(M), np.asarray(V)
+    assert M.ndim == V.ndim and M.dtype == V.dtype
+    d = M.shape
+    T = np.zeros(tuple(a + b for a, b in zip(M.shape, V.shape)), dtype=M.dtype)
+    for x in itertools.product(*[range(n) for n in T.shape]):
+        if all(x[v] < d[v] for v in range(M.ndim)):
+            T[x] = M[x]
+        elif all(x[v] >= d[v] for v in range(M.ndim)):
+            T[x] = V[tuple(x[v] - d[v] for v in range(M.ndim))]
+    return T

@@ -508,3 +508,21 @@ def test_struct_moment_against_dense_moments(oracle, N, n):
     idx = oracle.struct_enumerate((n,) * 3, lambda i, j, k: i <= j <= k <= i + 2).astype(np.int64)
     ein = np.einsum("si,sj,sk->ijk", X64, X64, X64)[idx[:, 0], idx[:, 1], idx[:, 2]]
     assert np.allclose(oracle.struct_moment(X, (n,) * 3, lambda i, j, k: i <= j <= k <= i + 2), ein, **tol)
+
+
+def test_direct_sum_definition(oracle):
+    """The direct sum against a library routine for matrices (scipy's block-diagonal stacking), against plain
+    concatenation for vectors, and by its defining property at order 3: the two diagonal blocks are the operands,
+    everything else is zero."""
+    import scipy.linalg
+    M, V = W.uniform(240, 12).reshape(3, 4), W.uniform(241, 10).reshape(5, 2)
+    assert np.array_equal(oracle.direct_sum(M, V), scipy.linalg.block_diag(M, V))
+    a, b = W.uniform(242, 4), W.uniform(243, 7)
+    assert np.array_equal(oracle.direct_sum(a, b), np.concatenate([a, b]))
+    A, B = W.uniform(244, 24).reshape(2, 3, 4), W.uniform(245, 6).reshape(3, 1, 2)
+    T = oracle.direct_sum(A, B)
+    assert T.shape == (5, 4, 6)
+    assert np.array_equal(T[:2, :3, :4], A) and np.array_equal(T[2:, 3:, 4:], B)
+    assert np.count_nonzero(T) == np.count_nonzero(A) + np.count_nonzero(B)
+    # not commutative: the operands swap corners
+    assert np.array_equal(oracle.direct_sum(V, M), scipy.linalg.block_diag(V, M))
