@@ -441,6 +441,31 @@ st_status st_desc_outer(const st_desc *m, const st_desc *v, st_desc **out);
  * for descriptors of order above 1 or with a redundancy map. */
 st_status st_desc_power(const st_desc *v, int k, st_desc **out);
 
+/* Structure inference for the direct sum  T := M (+) V  of two operands of the
+ * same order ("Redundancy Map Inference", direct-sum rule; "Representation of
+ * linear algebra operations", the rule for (+)): with d = dims(M), T has
+ * dims(M) + dims(V) on every index and
+ *     T_U(x)     = M_U(x) + V_U(y) * (y = x - d),
+ *     T_R(x, x') = M_R(x, x') + V_R(y, y') * (y = x - d) * (y' = x' - d).
+ * The two summands lie in disjoint boxes, so T_U is a sum of two nests; as in
+ * the code generation of the paper every summand gets a nest of its own, and
+ * each is returned as an ordinary descriptor over the box of T: *out_m is the
+ * structure of M inside that box, *out_v the structure of V moved by d (every
+ * bound, condition and map of V read at x - d).  The packed array of T is M_C
+ * followed by V_C: each part keeps the packed order of its operand.  The dense
+ * T is st_desc_expand of the first part and st_desc_expand_onto of the second
+ * on the same array; every other call works on a part as on any descriptor.
+ * Both outputs are NULL on ST_ERR_NULL / ST_ERR_SHAPE (different orders);
+ * otherwise *out_m is always set and *out_v once *out_m has succeeded; a
+ * failed one still has to be destroyed (st_desc_error tells why). */
+st_status st_desc_direct_sum(const st_desc *m, const st_desc *v, st_desc **out_m, st_desc **out_v);
+
+/* st_desc_expand that writes ONLY the elements the structure holds (stored, or
+ * reached through its redundancy map) and leaves every other element of the
+ * dense array T as it was: lays one summand of a sum of nests over what the
+ * previous summands wrote.  Arguments, alignment and errors as st_desc_expand. */
+st_status st_desc_expand_onto(st_desc *desc, const void *table, const float *Tc, float *T, void *stream);
+
 /* Moment accumulation over the unique set of a descriptor of order 2 or 3 whose
  * variables all range over the n <= 256 features of X (N x n, row-major):
  *     Sc(rank(x)) (+)= sum_s prod_v X(s, x_v)       for every x in the unique set

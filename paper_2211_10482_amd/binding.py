@@ -86,6 +86,8 @@ SIGNATURES = {
     "st_desc_sum_last": (_I32, [_P, _P, _P, _P, _P]),
     "st_desc_outer": (_I32, [_P, _P, _P]),
     "st_desc_power": (_I32, [_P, _I32, _P]),
+    "st_desc_direct_sum": (_I32, [_P, _P, _P, _P]),
+    "st_desc_expand_onto": (_I32, [_P, _P, _P, _P, _P]),
     "st_desc_moment_workspace": (_SZ, [_P, _I64]),
     "st_desc_moment": (_I32, [_P, _P, _P, _I64, _P, _I32, _P, _SZ, _P]),
     "st_probe_empty": (_I32, [_I32, _I32, _P]),
@@ -615,6 +617,30 @@ class Descriptor:
         self._call(lib().st_desc_expand(self._h, self._tab(), _dev_f32(Tc, "Tc"), _dev_f32(T, "T"), _stream()),
                    "st_desc_expand")
         return T
+
+    def expand_onto(self, Tc, T):
+        """Write the elements this structure holds into the dense array T; every other element of T stays."""
+        _expect(Tc, self.count, "Tc", at_least=True)
+        _expect(T, int(np.prod(self.dims)), "T")
+        self._call(lib().st_desc_expand_onto(self._h, self._tab(), _dev_f32(Tc, "Tc"), _dev_f32(T, "T"), _stream()),
+                   "st_desc_expand_onto")
+        return T
+
+    def direct_sum(self, other):
+        """The two summands of the direct sum self (+) other, each a descriptor over the box of the result
+        (structure inference); the packed array of the result is self's followed by other's."""
+        if len(self.dims) != len(other.dims):
+            raise ValueError("the operands of a direct sum have the same order")
+        dims = tuple(a + b for a, b in zip(self.dims, other.dims))
+        hm, hv = C.c_void_p(), C.c_void_p()
+        rc = lib().st_desc_direct_sum(self._h, other._h, C.byref(hm), C.byref(hv))
+        if rc != 0:
+            msg = "; ".join(lib().st_desc_error(h).decode() for h in (hm, hv) if h)
+            for h in (hm, hv):
+                if h:
+                    lib().st_desc_destroy(h)
+            raise StructTensorError(rc, "st_desc_direct_sum (%s)" % msg)
+        return Descriptor(None, dims, _handle=hm), Descriptor(None, dims, _handle=hv)
 
     def product(self, other):
         """Descriptor of the element-wise product of two structured operands (structure inference)."""

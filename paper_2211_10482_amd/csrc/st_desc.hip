@@ -218,7 +218,7 @@ struct Desc {
     i64 mbs = 0, ntiles = 0, mnp = 0;
     std::string nest, source;
     std::mutex mu;
-    struct Loaded { hipModule_t mod; hipFunction_t fn[9]; };   // list, thp, expand, gather, moment, moment_reduce, mttkrp, mttkrp_combine, sum_last
+    struct Loaded { hipModule_t mod; hipFunction_t fn[10]; };  // list, thp, expand, gather, moment, moment_reduce, mttkrp, mttkrp_combine, sum_last, expand_onto
     std::map<int, Loaded> modules;               // per device
     std::string error;
 };
@@ -501,8 +501,7 @@ void build_source(Desc &D)
     s += "        Ac[p] = Bc[p] * C[" + dense + "];\n    }\n}\n";
     // value of one dense element: Tc(rank(x)) on the unique set, Tc(rank(x')) through the redundancy map, 0 elsewhere
     const std::string xs = args_list(d, "x", false);
-    s += "static __device__ __forceinline__ float st_value(const int *__restrict__ tab, const float *__restrict__ Tc, " +
-         args_list(d, "x", true) + ")\n{\n";
+    s += "static __device__ __forceinline__ int st_pos(const int *__restrict__ tab, " + args_list(d, "x", true) + ")\n{\n";
     s += "    int pos = -1;\n";
     s += "    if (st_in(" + xs + ")) pos = st_rank(tab, " + xs + ");\n";
     if (D.red_sort) {
@@ -523,7 +522,10 @@ void build_source(Desc &D)
         }
         s += "        if (st_in(" + ys + ")) pos = st_rank(tab, " + ys + ");\n    }\n";
     }
-    s += "    return pos >= 0 ? Tc[pos] : 0.f;\n}\n";
+    s += "    return pos;\n}\n";
+    s += "static __device__ __forceinline__ float st_value(const int *__restrict__ tab, const float *__restrict__ Tc, " +
+         args_list(d, "x", true) + ")\n{\n";
+    s += "    const int pos = st_pos(tab, " + xs + ");\n    return pos >= 0 ? Tc[pos] : 0.f;\n}\n";
     // expand: one thread per dense element, or per four consecutive ones along the last variable (one 16-byte store)
     const bool vec = D.dims[d - 1] % 4 == 0;
     const std::string lastdim = "ST_DIM" + std::to_string(d - 1);
@@ -552,6 +554,19 @@ void build_source(Desc &D)
     } else {
         s += "    T[e] = st_value(tab, Tc, " + xs + ");\n}\n";
     }
+    // expand onto: the same reconstruction, but only the elements this structure holds (stored, or reached through
+    // its redundancy map) are written; everything else keeps what the dense array held -- the second and later
+    // summands of a structure that is a sum of nests (the direct sum) are laid over the first this way
+    s += "extern \"C\" __global__ void st_gen_expand_onto(const int *__restrict__ tab, const float *__restrict__ Tc,\n"
+         "                                              float *__restrict__ T)\n{\n";
+    s += "    const long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x;\n";
+    s += "    if (e >= " + total + ") return;\n";
+    s += "    long long st_r = e;\n";
+    for (int v = d - 1; v >= 0; --v) {
+        const std::string dim = "ST_DIM" + std::to_string(v);
+        s += "    const int x" + std::to_string(v) + " = (int)(st_r % " + dim + "); st_r /= " + dim + ";\n";
+    }
+    s += "    const int pos = st_pos(tab, " + xs + ");\n    if (pos >= 0) T[e] = Tc[pos];\n}\n";
     // gather: the value of the structured tensor at a LIST of dense positions (unique set, redundancy map or
     // zero, as in the reconstruction), optionally times a factor per position -- what an element-wise product
     // with another structured operand needs, evaluated only where the product's unique set says
@@ -1209,6 +1224,67 @@ st_status infer_power(const Desc &V, int k, Desc &A)
     return finish(A);
 }
 
+// Direct sum T := M (+) V ("Redundancy Map Inference", direct-sum rule; the top-right rule of "Representation of
+// linear algebra operations"): with d = dims(M),
+//     T_U(x)     := M_U(x) + V_U(y) * (y = x - d),
+//     T_R(x, x') := M_R(x, x') + V_R(y, y') * (y = x - d) * (y' = x' - d).
+// The two summands lie in disjoint boxes, so the unique set is a sum of two nests, and (as the paper's code
+// generation gives every summand a nest of its own) each summand is returned as a descriptor of its own over the
+// box of T: `place` writes the structure of S at offset `off` inside a box `dims` -- every bound, every condition
+// and every map of S with x - off in the place of x.  The packed array of T is M_C followed by V_C; the shift
+// keeps the nest order, so each part's packed order is the operand's.
+st_status place(const Desc &S, const i64 *off, const i64 *dims, Desc &A)
+{
+    A.d = S.d;
+    A.name = S.name;
+    A.vars = S.vars;
+    for (int v = 0; v < S.d; ++v) {
+        if (off[v] < 0 || off[v] + S.dims[v] > dims[v]) { A.error = "the operand does not fit the box at this offset"; return ST_ERR_SHAPE; }
+        if (S.red_sort && off[v] != off[0]) {
+            A.error = "a 'sort' redundancy map needs the same offset on every index";
+            return ST_ERR_UNSUPPORTED;
+        }
+        A.dims[v] = dims[v];
+    }
+    // value = c + sum coef[u] * x_u, read at x - off; `own` >= 0: the value is itself an index of variable `own`
+    auto move = [&](const Bound &b, int own) {
+        Bound r = b;
+        for (int u = 0; u < S.d; ++u) r.c -= b.coef[u] * off[u];
+        if (own >= 0) r.c += off[own];
+        return r;
+    };
+    for (int v = 0; v < S.d; ++v) {
+        Bound c;
+        for (int u = 0; u < MAXD; ++u) c.coef[u] = 0;
+        c.c = S.first[v] + off[v];
+        A.lo[v].push_back(c);
+        c.c = S.last[v] + off[v];
+        A.hi[v].push_back(c);
+        for (auto &b : S.lo[v]) A.lo[v].push_back(move(b, v));
+        for (auto &b : S.hi[v]) A.hi[v].push_back(move(b, v));
+    }
+    A.empty = S.empty;
+    A.red_sort = S.red_sort;
+    for (auto &t : S.red) {
+        RedTerm q;
+        for (int v = 0; v < MAXD; ++v) q.map[v] = v < S.d ? move(t.map[v], v) : t.map[v];
+        for (auto &c : t.cond) q.cond.push_back(move(c, -1));
+        // the conditions of S were only ever read inside its own box
+        for (int v = 0; v < S.d; ++v) {
+            Bound in;
+            for (int u = 0; u < MAXD; ++u) in.coef[u] = 0;
+            in.coef[v] = 1;
+            in.c = -off[v];
+            q.cond.push_back(in);                                  // x_v - off_v >= 0
+            in.coef[v] = -1;
+            in.c = off[v] + S.dims[v] - 1;
+            q.cond.push_back(in);                                  // off_v + dims_v - 1 - x_v >= 0
+        }
+        A.red.push_back(q);
+    }
+    return finish(A);
+}
+
 // the generated source compiled for gfx950 (no GPU needed); on failure D.error holds the compiler's log
 st_status compile_source(Desc &D, std::vector<char> *code)
 {
@@ -1248,10 +1324,11 @@ st_status module_for(Desc &D, Desc::Loaded &out)
     const char *names[6] = {"st_gen_list", "st_gen_thp", "st_gen_expand", "st_gen_gather", "st_gen_moment",
                             "st_gen_moment_reduce"};
     L.fn[4] = L.fn[5] = L.fn[6] = L.fn[7] = L.fn[8] = nullptr;
-    for (int q = 0; q < 9; ++q) {
+    for (int q = 0; q < 10; ++q) {
         if ((q == 4 || q == 5) && D.ntiles == 0) continue;      // moment kernels: equal extents only
         if ((q == 6 || q == 7) && D.d != 3) continue;           // MTTKRP: order 3 only
-        const char *name = q == 6 ? "st_gen_mttkrp" : q == 7 ? "st_gen_mttkrp_combine" : q == 8 ? "st_gen_sum_last" : names[q];
+        const char *name = q == 6 ? "st_gen_mttkrp" : q == 7 ? "st_gen_mttkrp_combine" : q == 8 ? "st_gen_sum_last"
+                         : q == 9 ? "st_gen_expand_onto" : names[q];
         if (hipModuleGetFunction(&L.fn[q], L.mod, name) != hipSuccess) {
             (void)hipModuleUnload(L.mod);
             D.error = std::string("generated kernel missing: ") + name;
@@ -1542,6 +1619,36 @@ st_status st_desc_power(const st_desc *v, int k, st_desc **out)
     const st_status rc = infer_power(*V, k, *A);
     *out = reinterpret_cast<st_desc *>(A);
     return rc;
+}
+
+st_status st_desc_direct_sum(const st_desc *m, const st_desc *v, st_desc **out_m, st_desc **out_v)
+{
+    if (!m || !v || !out_m || !out_v) return ST_ERR_NULL;
+    *out_m = *out_v = nullptr;
+    const Desc *M = reinterpret_cast<const Desc *>(m), *V = reinterpret_cast<const Desc *>(v);
+    if (M->source.empty() || V->source.empty() || M->d != V->d) return ST_ERR_SHAPE;
+    i64 dims[MAXD] = {0, 0, 0, 0}, zero[MAXD] = {0, 0, 0, 0};
+    for (int q = 0; q < M->d; ++q) dims[q] = M->dims[q] + V->dims[q];
+    Desc *A = new Desc();
+    st_status rc = place(*M, zero, dims, *A);
+    *out_m = reinterpret_cast<st_desc *>(A);      // kept on failure too: st_desc_error tells why
+    if (rc != ST_OK) return rc;
+    Desc *B = new Desc();
+    rc = place(*V, M->dims, dims, *B);
+    *out_v = reinterpret_cast<st_desc *>(B);
+    return rc;
+}
+
+st_status st_desc_expand_onto(st_desc *desc, const void *table, const float *Tc, float *T, void *stream)
+{
+    if (!desc || !table || !Tc || !T) return ST_ERR_NULL;
+    Desc *D = reinterpret_cast<Desc *>(desc);
+    if (D->source.empty()) return ST_ERR_SHAPE;
+    if (!aligned16(table) || !aligned16(Tc) || !aligned16(T)) return ST_ERR_ALIGN;
+    const int64_t total = D->prefixes * D->dims[D->d - 1];
+    if (overlap(T, (size_t)total * 4, Tc, (size_t)D->count * 4)) return ST_ERR_SHAPE;
+    void *args[] = {&table, &Tc, &T};
+    return launch_generated(*D, 9, (unsigned)((total + 255) / 256), args, (hipStream_t)stream);
 }
 
 st_status st_desc_gather(st_desc *desc, const void *table, const float *Tc, const int32_t *idx, int64_t count,

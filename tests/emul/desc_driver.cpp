@@ -7,6 +7,7 @@
 //   writes list.i32 [count*order], thp.f32 [count], expand.f32 [box] (expansion of bc.f32), moment.f32 [count],
 //   sum_last.f32 [nruns] (every run of bc.f32 summed)
 //   when dir holds gather.i32 ([g][order] dense positions; gather_scale.f32 [g] optional): gather.f32 [g]
+//   when dir holds onto.f32 [box]: expand_onto.f32 [box], bc.f32 laid over it (only the elements the structure holds)
 //   when dir holds mk_r.i32 (order 3): mttkrp.f32 [dim0][R] from mk_c.f32 [dim1][R] and mk_d.f32 [dim2][R]
 #include <hip/hip_runtime.h>
 // LDS of the generated moment kernels: the dynamic chunk buffer is a global here, static arrays keep their
@@ -83,6 +84,12 @@ int main(int argc, char **argv)
                                   (long long)g, (int)order, 0, scale.empty() ? (const float *)nullptr : scale.data(),
                                   addend.empty() ? (const float *)nullptr : addend.data(), out.data());
         wr(dir + "/gather.f32", out);
+    }
+    if (FILE *f = fopen((dir + "/onto.f32").c_str(), "rb")) {
+        fclose(f);
+        std::vector<float> onto = rd<float>(dir + "/onto.f32", box);
+        hipLaunchKernelGGL(st_gen_expand_onto, dim3((unsigned)((box + 255) / 256)), dim3(256), 0, 0, tab.data(), bc.data(), onto.data());
+        wr(dir + "/expand_onto.f32", onto);
     }
 #if ST_D == 3
     // the generated MTTKRP, launched with one thread per workgroup (its sums over the threads of a workgroup need a

@@ -279,7 +279,7 @@ PRODUCTS = {
 }
 
 
-def _run_generated(d, workdir, dims, Tc, gather_idx=None, scale=None, addend=None):
+def _run_generated(d, workdir, dims, Tc, gather_idx=None, scale=None, addend=None, onto=None):
     """Compile the generated source of descriptor d against the host stand-in and run the driver in workdir."""
     os.makedirs(workdir, exist_ok=True)
     src = os.path.join(workdir, "generated.hip")
@@ -299,6 +299,8 @@ def _run_generated(d, workdir, dims, Tc, gather_idx=None, scale=None, addend=Non
             np.asarray(scale, dtype=np.float32).tofile(os.path.join(workdir, "gather_scale.f32"))
         if addend is not None:
             np.asarray(addend, dtype=np.float32).tofile(os.path.join(workdir, "gather_addend.f32"))
+    if onto is not None:
+        np.ascontiguousarray(onto, dtype=np.float32).tofile(os.path.join(workdir, "onto.f32"))
     r = subprocess.run([exe, workdir, str(d.count), str(box), str(len(dims)), str(d.runs), str(dims[-1])],
                        capture_output=True, text=True, timeout=300)
     assert r.returncode == 0 and "rc=0" in r.stdout, r.stderr[-3000:]
@@ -587,3 +589,95 @@ def test_constant_range_rule_written_as_text(oracle, tmp_path):
         st.Descriptor("T(i,j): (i=1)*(j=2)", dims, "(1<=i<4)*(2<=j<5) -> (1,2)")
     assert e.value.status == 2 and "disjoint" in str(e.value)
     d.close()
+
+
+# ------------------------------------------------------------------ direct sum: a unique set that is a sum of two nests
+_rows_n = lambda n: (lambda i, j: (0, j) if 1 <= i < n else None)
+# name -> ((text, dims, redundancy, params, predicate, unique_of) of M, the same of V, nest lines of V's part or None)
+DIRECT_SUMS = {
+    "upper_sym": (("U(i,j): (0<=i<=j<n)", (4, 4), None, dict(n=4), lambda i, j: i <= j, None),
+                  ("S(i,j): (0<=i<=j<n)", (5, 5), "sort", dict(n=5), lambda i, j: i <= j, _swap),
+                  ["for (i = 4; i <= 8; ++i)", "  for (j = i; j <= 8; ++j)"]),
+    # different offsets on the two indices, written-out terms on both sides (class S; identical rows)
+    "sym_rows": (("S(i,j): (0<=i<=j<n)", (3, 3), SYM_RED, dict(n=3), lambda i, j: i <= j, _swap),
+                 ("M(i,j): (i=0)*(0<=j<m)", (4, 6), "(1<=i<n) -> (0,j)", dict(n=4, m=6), lambda i, j: i == 0, _rows_n(4)),
+                 ["for (i = 3; i <= 3; ++i)", "  for (j = 3; j <= 8; ++j)"]),
+    "vectors": (("v(i): (2<=i<n)", (9,), None, dict(n=6), lambda i: 2 <= i < 6, None),
+                ("w(i): (1<=i<=3)", (5,), None, dict(), lambda i: 1 <= i <= 3, None),
+                ["for (i = 10; i <= 12; ++i)"]),
+    "band3_diag3": (("B(i,j,l): (0<=i<n)*(i-w<=j<=i+w)*(0<=l<m)", (5, 5, 2), None, dict(n=5, w=1, m=2),
+                     lambda i, j, l: abs(i - j) <= 1, None),
+                    ("D(i,j,l): (0<=i<n)*(i=j)*(0<=l<m)", (4, 4, 3), None, dict(n=4, m=3), lambda i, j, l: i == j, None),
+                    ["for (i = 5; i <= 8; ++i)", "  for (j = i; j <= i; ++j)", "    for (l = 2; l <= 4; ++l)"]),
+    "sym3_lower": (("T(i,j,k): (0<=i<=j<n)*(j<=k<n)", (3, 3, 3), "sort", dict(n=3), lambda i, j, k: i <= j <= k, _sorted),
+                   ("T(i,j,k): (0<=i<=j<n)*(j<=k<n)", (4, 4, 4), "sort", dict(n=4), lambda i, j, k: i <= j <= k, _sorted),
+                   None),
+    "empty_upper": (("E(i,j): (0<=i<n)*(j<i)*(j>i)", (3, 3), None, dict(n=3), lambda i, j: False, None),
+                    ("U(i,j): (0<=i<=j<n)", (4, 4), None, dict(n=4), lambda i, j: i <= j, None), None),
+}
+
+
+@pytest.mark.parametrize("name", sorted(DIRECT_SUMS))
+def test_direct_sum_inference(oracle, tmp_path, name):
+    """T := M (+) V ("Redundancy Map Inference", direct-sum rule): the two summands of T_U and T_R come back as two
+    descriptors over the box of T.  Each is checked against the operand's predicate moved by hand (brute force over
+    the box), its packed order must be the operand's, and the reconstruction -- the first part expanded, the second
+    laid over it, both generated kernels run on the CPU -- must equal the dense direct sum of the two reconstructed
+    operands bit for bit."""
+    if CLANG is None:
+        pytest.skip("no clang++ for the host build")
+    (mt, mdims, mred, mpar, mpred, muniq), (vt, vdims, vred, vpar, vpred, vuniq), nest = DIRECT_SUMS[name]
+    dm, dv = st.Descriptor(mt, mdims, mred, **mpar), st.Descriptor(vt, vdims, vred, **vpar)
+    pm, pv = dm.direct_sum(dv)
+    dims = tuple(a + b for a, b in zip(mdims, vdims))
+    assert pm.dims == dims and pv.dims == dims
+    assert pm.count == dm.count and pv.count == dv.count
+    order = len(dims)
+    in_m = lambda *x: all(x[q] < mdims[q] for q in range(order)) and mpred(*x)
+    in_v = lambda *x: all(x[q] >= mdims[q] for q in range(order)) and vpred(*[x[q] - mdims[q] for q in range(order)])
+    lm, lv = oracle.struct_enumerate(dims, in_m), oracle.struct_enumerate(dims, in_v)
+    assert lm.shape[0] == dm.count and lv.shape[0] == dv.count
+    # the packed order of each part is the operand's: the operand's own listing, moved
+    assert np.array_equal(lm, oracle.struct_enumerate(mdims, mpred))
+    assert np.array_equal(lv, oracle.struct_enumerate(vdims, vpred) + np.asarray(mdims, dtype=np.int32))
+    if nest is not None:
+        assert pv.nest.splitlines()[:len(nest)] == nest
+    Mc, Vc = W.uniform(811, max(dm.count, 1))[: dm.count], W.uniform(812, max(dv.count, 1))[: dv.count]
+    dense = oracle.direct_sum(oracle.struct_expand(Mc, mdims, mpred, muniq), oracle.struct_expand(Vc, vdims, vpred, vuniq))
+    _run_generated(pm, str(tmp_path / "m"), dims, Mc)
+    got = np.fromfile(str(tmp_path / "m" / "list.i32"), dtype=np.int32).reshape(-1, order)
+    assert np.array_equal(got, lm)
+    first = np.fromfile(str(tmp_path / "m" / "expand.f32"), dtype=np.float32).reshape(dims)
+    assert np.array_equal(first, oracle.direct_sum(oracle.struct_expand(Mc, mdims, mpred, muniq),
+                                                   np.zeros(vdims, dtype=np.float32)))
+    _run_generated(pv, str(tmp_path / "v"), dims, Vc, onto=first)
+    got = np.fromfile(str(tmp_path / "v" / "list.i32"), dtype=np.int32).reshape(-1, order)
+    assert np.array_equal(got, lv)
+    both = np.fromfile(str(tmp_path / "v" / "expand_onto.f32"), dtype=np.float32).reshape(dims)
+    assert np.array_equal(both.view(np.uint32), dense.view(np.uint32))
+    # laid over a marker instead: only the elements of V's part change
+    marker = np.full(dims, -3.0, dtype=np.float32)
+    _run_generated(pv, str(tmp_path / "k"), dims, Vc, onto=marker)
+    kept = np.fromfile(str(tmp_path / "k" / "expand_onto.f32"), dtype=np.float32).reshape(dims)
+    vd = oracle.direct_sum(np.zeros(mdims, dtype=np.float32), np.ones(vdims, dtype=np.float32)) > 0
+    held = oracle.direct_sum(np.zeros(mdims, dtype=np.float32),
+                             oracle.struct_expand(np.ones(max(dv.count, 1), dtype=np.float32)[: dv.count], vdims, vpred, vuniq)) > 0
+    assert np.array_equal(kept[~held], marker[~held]) and np.array_equal(kept[held], dense[held]) and not (held & ~vd).any()
+    for d in (dm, dv, pm, pv):
+        d.close()
+
+
+def test_direct_sum_limits():
+    """Operands of different orders are refused; a 'sort' map cannot be moved by different amounts on its indices."""
+    a = st.Descriptor("v(i): (0<=i<n)", (4,), None, n=4)
+    b = st.Descriptor("U(i,j): (0<=i<=j<n)", (4, 4), None, n=4)
+    with pytest.raises(ValueError):
+        a.direct_sum(b)
+    m = st.Descriptor("G(i,j): (0<=i<n)*(0<=j<m)", (3, 5), None, n=3, m=5)
+    s = st.Descriptor("S(i,j): (0<=i<=j<n)", (4, 4), "sort", n=4)
+    with pytest.raises(st.StructTensorError) as e:
+        m.direct_sum(s)
+    assert e.value.status == 6 and "same offset" in str(e.value)
+    # the other way round the symmetric operand stays in place and the general one moves: fine
+    ps, pg = s.direct_sum(m)
+    assert ps.count == 10 and pg.count == 15 and pg.nest.splitlines()[0] == "for (i = 4; i <= 6; ++i)"

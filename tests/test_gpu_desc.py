@@ -448,3 +448,59 @@ def test_ttm_output_structure_is_projection_times_range(st, oracle):
     assert float(np.abs(dense - ref).max()) <= 1e-4 * float(np.abs(ref).max())
     for d in (a, b, k):
         d.close()
+
+
+from test_desc import DIRECT_SUMS
+
+
+@pytest.mark.parametrize("name", sorted(DIRECT_SUMS))
+def test_direct_sum_of_structured_operands(st, oracle, name):
+    """T := M (+) V on the GPU: the two parts list the operands' unique sets moved into the box of T, and the first
+    part expanded with the second laid over it is the dense direct sum of the two reconstructed operands, bit for bit."""
+    say("descriptor direct sum", name)
+    import torch
+    (mt, mdims, mred, mpar, mpred, muniq), (vt, vdims, vred, vpar, vpred, vuniq), _ = DIRECT_SUMS[name]
+    dm, dv = st.Descriptor(mt, mdims, mred, **mpar), st.Descriptor(vt, vdims, vred, **vpar)
+    pm, pv = dm.direct_sum(dv)
+    off = np.asarray(mdims, dtype=np.int32)
+    assert np.array_equal(pm.list().cpu().numpy(), oracle.struct_enumerate(mdims, mpred))
+    assert np.array_equal(pv.list().cpu().numpy(), oracle.struct_enumerate(vdims, vpred) + off)
+    # one packed array for T: M_C followed by V_C (the second part starts at a 16-byte boundary of its own copy here)
+    Mc, Vc = W.uniform(811, max(dm.count, 4)), W.uniform(812, max(dv.count, 4))
+    T = pm.expand(dev(Mc))
+    pv.expand_onto(dev(Vc), T)
+    dense = oracle.direct_sum(oracle.struct_expand(Mc[: dm.count], mdims, mpred, muniq),
+                              oracle.struct_expand(Vc[: dv.count], vdims, vpred, vuniq))
+    assert np.array_equal(T.cpu().numpy().view(np.uint32), dense.view(np.uint32))
+    # a part is an ordinary descriptor: the Hadamard product with a dense operand on V's part alone
+    Cd = W.uniform(813, int(np.prod(dense.shape))).reshape(dense.shape)
+    if dv.count:
+        got = pv.thp(dev(Vc), dev(Cd)).cpu().numpy()
+        lv = pv.list().cpu().numpy().astype(np.int64)
+        assert np.array_equal(got, Vc[: dv.count] * Cd[tuple(lv[:, q] for q in range(lv.shape[1]))])
+    for d in (dm, dv, pm, pv):
+        d.close()
+
+
+def test_direct_sum_of_large_blocks(st, oracle):
+    """A symmetric 300 x 300 block and an upper-triangular 212 x 212 block: 512 x 512 in all, checked through the
+    block property of the dense definition (the oracle's element-by-element loop is too slow here)."""
+    say("descriptor direct sum, 300 + 212")
+    import torch
+    ds = st.Descriptor("S(i,j): (0<=i<=j<n)", (300, 300), "sort", n=300)
+    du = st.Descriptor("U(i,j): (0<=i<=j<n)", (212, 212), None, n=212)
+    ps, pu = ds.direct_sum(du)
+    Sc, Uc = W.uniform(821, ds.count), W.uniform(822, du.count)
+    T = ps.expand(dev(Sc))
+    pu.expand_onto(dev(Uc), T)
+    T = T.cpu().numpy()
+    S = np.zeros((300, 300), dtype=np.float32)
+    iu = np.triu_indices(300)
+    S[iu] = Sc
+    S.T[iu] = Sc
+    U = np.zeros((212, 212), dtype=np.float32)
+    U[np.triu_indices(212)] = Uc
+    assert np.array_equal(T[:300, :300], S) and np.array_equal(T[300:, 300:], U)
+    assert not T[:300, 300:].any() and not T[300:, :300].any()
+    for d in (ds, du, ps, pu):
+        d.close()
