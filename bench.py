@@ -338,10 +338,10 @@ def main():
         del copies
 
     # matrix-core floor of the single-precision kernels: 23 MFMAs 16x16x4 per block from registers, alone and with
-    # the 13 cross-lane multiplies per block that the third-moment kernel needs for its pair products (on this
+    # the 9 cross-lane multiplies per block that the third-moment kernel needs for its pair products (on this
     # chip the fp32 MFMA and the vector ALU do not overlap, so the second figure is that kernel's ceiling)
     msink = torch.empty(256 * 512, **f32)
-    for valu, tag in ((0, "mfma_f32_registers_only_tflops"), (13, "mfma_f32_with_13_valu_per_23_mfma_tflops")):
+    for valu, tag in ((0, "mfma_f32_registers_only_tflops"), (9, "mfma_f32_with_9_valu_per_23_mfma_tflops")):
         fl = [0]
         def f(valu=valu):
             fl[0] = st.probe_mfma_f32(valu, 4000, msink)
@@ -375,7 +375,7 @@ def main():
                     unit="TFLOP/s", frac=round(achieved / MFMA_FP32_PEAK_TFLOPS, 4),
                     frac_kernel_trace=kernels[dom]["frac_kernel_trace"], traffic=kernels[dom]["traffic"],
                     measured_ceiling=dict(mfma_only=floors["mfma_f32_registers_only_tflops"],
-                                          with_pair_products=floors["mfma_f32_with_13_valu_per_23_mfma_tflops"],
+                                          with_pair_products=floors["mfma_f32_with_9_valu_per_23_mfma_tflops"],
                                           unit="TFLOP/s (matrix-core flops of the probe; the kernel's padded tiles do "
                                                "47104/45760 of its unique flops on the matrix cores)"),
                     timing="median of %d event pairs around the call (main kernel + its partial-sum kernel); "

@@ -501,13 +501,14 @@ st_status st_probe_empty(int grid, int block, void *stream);
 st_status st_probe_stream(const void *src, size_t bytes, int grid, int block, float *sink, void *stream);
 
 /* The matrix-core floor of the single-precision kernels: 256 workgroups of 512
- * threads (two waves per SIMD) repeat `iters` times a block of `valu` (0 or 13:
- * ST_ERR_SHAPE otherwise) cross-lane vector multiplies followed by 23
+ * threads (two waves per SIMD) repeat `iters` times a block of `valu` (0, 9 or
+ * 13: ST_ERR_SHAPE otherwise) cross-lane vector multiplies followed by 23
  * independent 16x16x4 single-precision MFMAs on register operands, i.e.
- * 256 * 8 * iters * 23 * 2048 flops on the matrix cores.  13 multiplies per 23
- * MFMAs is the instruction mix of the third-moment kernel (one pair product
- * per distinct column pair of a K-step).  `sink` is a DEVICE buffer of
- * 256 * 512 floats, overwritten. */
+ * 256 * 8 * iters * 23 * 2048 flops on the matrix cores.  9 multiplies per 23
+ * MFMAs is the instruction mix of the third-moment kernel on its busiest
+ * SIMDs (every pair product formed once per K-step and workgroup); 13 is what
+ * it was before the tiles were dealt by product.  `sink` is a DEVICE buffer
+ * of 256 * 512 floats, overwritten. */
 st_status st_probe_mfma_f32(int valu, int iters, float *sink, void *stream);
 
 #ifdef __cplusplus

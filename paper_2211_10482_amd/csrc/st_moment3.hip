@@ -10,9 +10,12 @@
 // four groups of 16, group g = {4m+g}; one 16-byte load per lane then delivers
 // the A operand of all four groups at once (lane = (m, sample slot)).  An
 // unordered index triple is classified by the groups it touches:
-//   * three different groups a<b<c : rows = group a, columns = (fixed element
-//     of b) x (16 elements of c).  P = xa[c] * broadcast_m(xa[b]) is ONE VALU
-//     multiply with a DPP row broadcast.  4 * 16 tiles, all outputs unique.
+//   * three different groups: columns = (fixed element m of group b) x (16 elements
+//     of group c), rows = a group outside {b, c}.  P = xa[c] * broadcast_m(xa[b]) is
+//     ONE VALU multiply with a DPP row broadcast, and it serves BOTH row groups
+//     outside {b, c}: the column pairs (0,1) carry the rows of groups 2 and 3, the
+//     column pairs (2,3) those of groups 0 and 1.  2 * 16 products, 4 * 16 tiles, all
+//     outputs unique.
 //   * a pair inside one group g, third index anywhere (group r): columns = the
 //     16 pairs (m, m-d mod 16) of g at cyclic distance d = 0..8, rows = group r.
 //     P = xa[g] * rotate_d(xa[g]) is one VALU multiply with a DPP row rotate
@@ -21,6 +24,10 @@
 //     distance: the tiles (g, odd d, r = g) are not needed.  At distance 8 there
 //     are only 8 pairs per group, so two groups share a tile (a lane select
 //     between two products).  4 * (4 * 4 + 4 * 3) + 8 tiles.
+// The tiles are dealt to the eight waves by PRODUCT: all tiles that multiply by the
+// same pair product go to one wave, so every product is formed once per K-step in
+// the whole workgroup (70 vector instructions for the 184 MFMAs; on this chip vector
+// instructions and single-precision MFMAs do not overlap).
 // 184 tiles cover every unordered triple (47,104 accumulators for the 45,760
 // unique entries, against 64^3 = 262,144 dense ones).  A workgroup (8 waves,
 // 23 tiles = 92 accumulator
@@ -96,13 +103,15 @@ template <int M> __device__ __forceinline__ float mul_bcast(float bsrc, float ot
 }
 
 // Tile descriptor shared by the accumulation kernel (compile time) and the
-// reduction kernel (run time).  Tile `local` of wave `w`:
-//   0..13  : pair-in-group tiles of group g = w/2: the 28 tiles (d, r) of the group, d = 0..7, r fastest,
-//            r = g only for even d; wave w takes the half w%2
-//   14     : distance-8 tile of the groups (2(w/4), 2(w/4)+1), row group r = w%4
-//   15,16  : groups (r=0, 1, 2), fixed element m = 2w + 0/1 of group 1
-//   17,18  : groups (r=0, 1, 3), fixed element m = 2w + 0/1 of group 1
-//   19..22 : groups (r, 2, 3), fixed element m = 2w + (l-19)/2 of group 2, r = (l-19)%2
+// reduction kernel (run time).  A unit is the set of tiles that use one product:
+//   E(g, d even) : pairs of group g at distance d = 0, 2, 4, 6, row groups 0..3        (4 tiles, 1 multiply)
+//   O(g, d odd)  : the same at d = 1, 3, 5, 7, row groups other than g                 (3 tiles, 1 multiply)
+//   D(g, g+1)    : distance 8 of the groups (0,1) or (2,3), row groups 0..3            (4 tiles, 2 multiplies + select)
+//   K(b, c; m)   : element m of group b times group c, (b,c) = (0,1) with row groups 2, 3
+//                  or (2,3) with row groups 0, 1                                        (2 tiles, 1 multiply)
+// 16 + 16 + 2 + 32 units.  Every wave holds 23 tiles: waves 0..3 two E, three O, three K (8 vector
+// instructions per K-step); waves 4, 5 two E, one O, one D, four K (10); waves 6, 7 two E, one O, six K (9).
+// Waves w and w+4 share a SIMD: 18, 18, 17, 17 vector instructions per SIMD and K-step.
 struct TileDesc {
     int kind;   // 0: pair inside group gb at distance d; 1: (element m of gb) x (group gc);
                 // 2: pairs at distance 8, columns 0..7 of group gb, columns 8..15 of group gc
@@ -112,16 +121,29 @@ struct TileDesc {
 };
 __host__ __device__ constexpr TileDesc tile_desc(int w, int local)
 {
-    if (local < 14) {
-        const int g = w / 2, u = 14 * (w % 2) + local, dd = u / 7, v = u % 7;
-        if (v < 4) return TileDesc{0, v, g, 0, 2 * dd};
-        return TileDesc{0, (v - 4) + ((v - 4) >= g ? 1 : 0), g, 0, 2 * dd + 1};
+    // pair-in-group units at an even distance (four tiles, r = 0..3): every wave takes two
+    if (local < 8) {
+        const int eu = 2 * w + local / 4;
+        return TileDesc{0, local % 4, eu / 4, 0, 2 * (eu % 4)};
     }
-    if (local == 14) return TileDesc{2, w % 4, 2 * (w / 4), 2 * (w / 4) + 1, 8};
-    const int l = local - 15;
-    if (l < 2) return TileDesc{1, 0, 1, 2, 2 * w + l};
-    if (l < 4) return TileDesc{1, 0, 1, 3, 2 * w + (l - 2)};
-    return TileDesc{1, (l - 4) % 2, 2, 3, 2 * w + (l - 4) / 2};
+    int l = local - 8;
+    // at an odd distance (three tiles, r != g): waves 0..3 take three units, waves 4..7 one
+    const int no = w < 4 ? 3 : 1, o0 = w < 4 ? 3 * w : 8 + w;
+    if (l < 3 * no) {
+        const int ou = o0 + l / 3, g = ou / 4, v = l % 3;
+        return TileDesc{0, v + (v >= g ? 1 : 0), g, 0, 2 * (ou % 4) + 1};
+    }
+    l -= 3 * no;
+    // distance 8 (four tiles, r = 0..3): waves 4 and 5
+    if (w == 4 || w == 5) {
+        if (l < 4) return TileDesc{2, l, 2 * (w - 4), 2 * (w - 4) + 1, 8};
+        l -= 4;
+    }
+    // broadcast units (two tiles): three for waves 0..3, four for waves 4 and 5, six for waves 6 and 7
+    const int k0 = w < 4 ? 3 * w : w == 4 ? 12 : w == 5 ? 16 : w == 6 ? 20 : 26;
+    const int ku = k0 + l / 2;
+    if (ku < 16) return TileDesc{1, 2 + l % 2, 0, 1, ku};
+    return TileDesc{1, l % 2, 2, 3, ku - 16};
 }
 // first tile of the wave that multiplies by the same pair product
 __host__ __device__ constexpr int m3_product_of(int w, int local)
@@ -133,6 +155,30 @@ __host__ __device__ constexpr int m3_product_of(int w, int local)
     }
     return local;
 }
+
+// every pair product is formed by exactly one wave: 66 products (16 + 16 + 2 + 32 units) in 70 vector instructions
+__host__ __device__ constexpr int m3_products_formed()
+{
+    int formed = 0;
+    for (int w = 0; w < M3_WAVES; ++w)
+        for (int t = 0; t < M3_TPW; ++t)
+            if (m3_product_of(w, t) == t) ++formed;
+    return formed;
+}
+__host__ __device__ constexpr bool m3_product_in_one_wave()
+{
+    for (int w = 0; w < M3_WAVES; ++w)
+        for (int t = 0; t < M3_TPW; ++t) {
+            const TileDesc a = tile_desc(w, t);
+            for (int w2 = w + 1; w2 < M3_WAVES; ++w2)
+                for (int u = 0; u < M3_TPW; ++u) {
+                    const TileDesc b = tile_desc(w2, u);
+                    if (a.kind == b.kind && a.gb == b.gb && a.gc == b.gc && a.d == b.d) return false;
+                }
+        }
+    return true;
+}
+static_assert(m3_products_formed() == 66 && m3_product_in_one_wave(), "tiles are dealt to the waves by product");
 
 #ifndef ST_M3_CH
 #define ST_M3_CH 64

@@ -104,8 +104,9 @@ __attribute__((visibility("default"))) st_status st_probe_stream(const void *src
 __attribute__((visibility("default"))) st_status st_probe_mfma_f32(int valu, int iters, float *sink, void *stream)
 {
     if (!sink) return ST_ERR_NULL;
-    if (iters < 1 || (valu != 0 && valu != 13)) return ST_ERR_SHAPE;
+    if (iters < 1 || (valu != 0 && valu != 9 && valu != 13)) return ST_ERR_SHAPE;
     if (valu == 0) hipLaunchKernelGGL(probe_mfma_kernel<0>, dim3(256), dim3(512), 0, (hipStream_t)stream, sink, iters);
+    else if (valu == 9) hipLaunchKernelGGL(probe_mfma_kernel<9>, dim3(256), dim3(512), 0, (hipStream_t)stream, sink, iters);
     else hipLaunchKernelGGL(probe_mfma_kernel<13>, dim3(256), dim3(512), 0, (hipStream_t)stream, sink, iters);
     return launch_status();
 }

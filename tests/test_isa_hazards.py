@@ -56,5 +56,5 @@ def test_dpp_operand_of_the_inline_multiply_is_not_freshly_written(tmp_path):
                 continue
             dst = _registers(prev.split(None, 1)[1].split(",")[0].strip())
             assert not (dst & src), "vector-ALU write of the DPP operand too close:\n  %s\n  %s" % (prev, line)
-    # eight per-wave code streams, four K-steps each, six broadcast products per step, two template instances
-    assert found >= 8 * 4 * 6, "the inline multiply was not found in the compiled kernel (%d)" % found
+    # 32 broadcast products per K-step over the eight per-wave code streams, four K-steps each, two template instances
+    assert found >= 32 * 4, "the inline multiply was not found in the compiled kernel (%d)" % found
