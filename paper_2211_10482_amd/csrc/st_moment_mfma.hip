@@ -5,7 +5,8 @@
 // padded with zeros).  A SET holds 16 values per sample: a pair set (ga, gb, d) the products
 // (position m of group ga) * (position m-d mod 16 of group gb) -- in-group sets ga = gb,
 // d = 0..8 (d = 8 names every pair twice), cross sets ga < gb, d = 0..15 -- and a single set (g)
-// the 16 values of group g themselves (written as a product with a plane of ones).  A 16 x 16
+// the 16 values of group g themselves (in the table a product with a plane of ones; the third-moment
+// instance of the kernel, whose row sets are all single, reads the values and skips the multiply).  A 16 x 16
 // MFMA tile contracts a row set with a column set over the samples:
 //     acc(m, m') += sum_s rowset(s, m) * colset(s, m').
 // Fourth moment, Sc(i,j,k,l) = sum_s (x_i x_j)(x_k x_l): pair sets x pair sets.  Every 4-multiset
@@ -31,7 +32,7 @@
 // [position], so that a wave reads either operand of a product, rotated or not, as 64
 // consecutive floats.  The sets are run-time data (a table built on the host per moment and G,
 // copied into the workspace): one code stream for all waves; per product two LDS reads and one
-// multiply.  Slice partials -> reduce kernel: keeps the positions above, adds the slices in
+// multiply (a single row set: one read).  Slice partials -> reduce kernel: keeps the positions above, adds the slices in
 // ascending order, sorts the indices and scatters through the closed-form rank.  No atomics.
 #include <cstring>
 #include <mutex>
@@ -279,7 +280,7 @@ __device__ __forceinline__ void mm_flush(const f32x4 (&acc)[MM_TPB], float *dst,
 }
 
 // STEPS K-steps (4 samples each) per staged chunk; V4: rows are read with 16-byte loads (n % 4 == 0)
-template <int STEPS, bool V4>
+template <int STEPS, bool V4, bool SINGLE>       // SINGLE: the row sets are single sets (third moment): no product, one read
 __global__ __launch_bounds__(MM_THREADS) void moment_mfma_kernel(const float *__restrict__ X, int64_t N, u32 n, u32 G,
                                                                  u32 kinds, int64_t slice,
                                                                  const int *__restrict__ table, float *__restrict__ ws)
@@ -339,7 +340,10 @@ __global__ __launch_bounds__(MM_THREADS) void moment_mfma_kernel(const float *__
         const float *base = lds + cb * chunk_f;
         float a[2][MM_SPECS], b[2][MM_SPECS];
 #pragma unroll
-        for (int u = 0; u < MM_SPECS; ++u) { a[0][u] = base[oa[u]]; b[0][u] = base[ob[u]]; }
+        for (int u = 0; u < MM_SPECS; ++u) {
+            a[0][u] = base[oa[u]];
+            if (!(SINGLE && u < MM_ROWS)) b[0][u] = base[ob[u]];
+        }
 #pragma unroll
         for (int st = 0; st < STEPS; ++st) {
             // The 22 operands of the next step are read under this step's MFMAs in three batches (8, 7, 7), one
@@ -351,14 +355,14 @@ __global__ __launch_bounds__(MM_THREADS) void moment_mfma_kernel(const float *__
 #pragma unroll
                 for (int q = q0; q < q1; ++q) {
                     if (q < MM_SPECS) a[nxt][q] = base[(st + 1) * 64 + oa[q]];
-                    else b[nxt][q - MM_SPECS] = base[(st + 1) * 64 + ob[q - MM_SPECS]];
+                    else if (!(SINGLE && q - MM_SPECS < MM_ROWS)) b[nxt][q - MM_SPECS] = base[(st + 1) * 64 + ob[q - MM_SPECS]];
                 }
             };
             if (more) fetch(0, 8);
             __builtin_amdgcn_sched_barrier(0);
             float p[MM_SPECS];
 #pragma unroll
-            for (int u = 0; u < MM_SPECS; ++u) p[u] = a[cur][u] * b[cur][u];
+            for (int u = 0; u < MM_SPECS; ++u) p[u] = (SINGLE && u < MM_ROWS) ? a[cur][u] : a[cur][u] * b[cur][u];
 #pragma unroll
             for (int t = 0; t < 8; ++t)
                 acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(p[t / MM_COLS], p[MM_ROWS + t % MM_COLS], acc[t], 0, 0, 0);
@@ -566,23 +570,21 @@ st_status launch_moment_mfma(int order, const float *X, int64_t N, int n, float 
     const size_t lds_bytes = (size_t)2u * (p.G + 1u) * p.steps * 64u * sizeof(float);
     const bool v4 = n % 4 == 0;
     bool ok;
+#define ST_MM_LAUNCH(STEPS, V4, SINGLE)                                                                                 \
+    do {                                                                                                                \
+        ok = allow_dynamic_lds(reinterpret_cast<const void *>(moment_mfma_kernel<STEPS, V4, SINGLE>), 96 * 1024); /* up to 74 KB */ \
+        if (ok) hipLaunchKernelGGL((moment_mfma_kernel<STEPS, V4, SINGLE>), grid, block, lds_bytes, s, X, N, (u32)n, p.G,  \
+                                   p.kinds, p.slice, table, wsf);                                                       \
+    } while (0)
+    const bool single = order == 3;
     if (p.steps == 16u) {
-        if (v4) {
-            ok = allow_dynamic_lds(reinterpret_cast<const void *>(moment_mfma_kernel<16, true>), 96 * 1024);   // up to 74 KB
-            if (ok) hipLaunchKernelGGL((moment_mfma_kernel<16, true>), grid, block, lds_bytes, s, X, N, (u32)n, p.G, p.kinds, p.slice, table, wsf);
-        } else {
-            ok = allow_dynamic_lds(reinterpret_cast<const void *>(moment_mfma_kernel<16, false>), 96 * 1024);   // up to 74 KB
-            if (ok) hipLaunchKernelGGL((moment_mfma_kernel<16, false>), grid, block, lds_bytes, s, X, N, (u32)n, p.G, p.kinds, p.slice, table, wsf);
-        }
+        if (v4) { if (single) ST_MM_LAUNCH(16, true, true); else ST_MM_LAUNCH(16, true, false); }
+        else { if (single) ST_MM_LAUNCH(16, false, true); else ST_MM_LAUNCH(16, false, false); }
     } else {
-        if (v4) {
-            ok = allow_dynamic_lds(reinterpret_cast<const void *>(moment_mfma_kernel<8, true>), 96 * 1024);   // up to 74 KB
-            if (ok) hipLaunchKernelGGL((moment_mfma_kernel<8, true>), grid, block, lds_bytes, s, X, N, (u32)n, p.G, p.kinds, p.slice, table, wsf);
-        } else {
-            ok = allow_dynamic_lds(reinterpret_cast<const void *>(moment_mfma_kernel<8, false>), 96 * 1024);   // up to 74 KB
-            if (ok) hipLaunchKernelGGL((moment_mfma_kernel<8, false>), grid, block, lds_bytes, s, X, N, (u32)n, p.G, p.kinds, p.slice, table, wsf);
-        }
+        if (v4) { if (single) ST_MM_LAUNCH(8, true, true); else ST_MM_LAUNCH(8, true, false); }
+        else { if (single) ST_MM_LAUNCH(8, false, true); else ST_MM_LAUNCH(8, false, false); }
     }
+#undef ST_MM_LAUNCH
     if (!ok || hipGetLastError() != hipSuccess) return ST_ERR_LAUNCH;
     const size_t racc = (size_t)p.blocks * MM_ACC;
     const dim3 rgrid((u32)((racc + 255) / 256));
