@@ -6,7 +6,7 @@
 // by the inner loops, every accumulator a register.
 //   * up to six features all 21 + 56 + 126 unique entries fit ONE lane: every lane of the grid has
 //     its own samples (a wave reads 64 consecutive rows, every byte of them used); the lanes of a
-//     wave, then the four waves of a workgroup, are added in a fixed order at the end;
+//     wave (through LDS), then the four waves of a workgroup, are added in a fixed order at the end;
 //   * seven to sixteen features: the waves of a workgroup take the same 64 samples and different
 //     parts of the nest (second half of this file).
 // Workgroup partials -> reduce kernel (fixed order, no atomics).  Bound by the HBM stream (six
@@ -32,6 +32,8 @@ __global__ __launch_bounds__(256) void covar_small_kernel(const float *__restric
 {
     typedef CsCounts<NP> C;
     __shared__ float red[4][C::ALL];
+    constexpr int CS_PH = NP <= 4 ? 33 : 52;          // accumulators per pass of the lane sum through LDS (at most 64)
+    __shared__ float tr[4][CS_PH * 65];
     const u32 tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
     float acc[C::ALL];
 #pragma unroll
@@ -58,30 +60,44 @@ __global__ __launch_bounds__(256) void covar_small_kernel(const float *__restric
                 }
             }
     }
-    // lanes of the wave (DPP steps, every lane ends with the sum), then the four waves
+    // The 64 lanes of a wave are added through LDS, CS_PH accumulators at a time: every lane writes its values
+    // as column `lane` of a [CS_PH][64] block (rows padded to 65 floats: no bank conflicts either way), lane a
+    // then adds row a in lane order.  A DPP tree per accumulator would be seven vector instructions for each of
+    // the 203, a quarter of everything this kernel issues at two million samples.  Then the four waves.
+    constexpr int PHASES = (C::ALL + CS_PH - 1) / CS_PH;
 #pragma unroll
-    for (int a = 0; a < C::ALL; ++a) {
-        const float v = wave_sum(acc[a]);
-        if (lane == 0u) red[wave][a] = v;
+    for (int ph = 0; ph < PHASES; ++ph) {
+#pragma unroll
+        for (int a = 0; a < CS_PH; ++a)
+            if (ph * CS_PH + a < C::ALL) tr[wave][a * 65 + (int)lane] = acc[ph * CS_PH + a];
+        __syncthreads();
+        if (lane < (u32)CS_PH && ph * CS_PH + (int)lane < C::ALL) {
+            float v = 0.f;
+#pragma unroll 16
+            for (int q = 0; q < 64; ++q) v += tr[wave][lane * 65u + (u32)q];
+            red[wave][ph * CS_PH + (int)lane] = v;
+        }
+        __syncthreads();
     }
-    __syncthreads();
     for (u32 a = tid; a < (u32)C::ALL; a += 256u)
         ws[(size_t)blockIdx.x * C::ALL + a] = (red[0][a] + red[1][a]) + (red[2][a] + red[3][a]);
 }
 
-// 16 accumulators x 16 groups of workgroup partials per block; keeps the entries with every index < n
-// (S1 or S2 may be null: that term is not wanted)
+// 4 accumulators x 64 slices of the workgroup partials per block (at most 8 partials per thread for the 512
+// workgroups of the one-lane kernel, all loads in flight together; slices added in ascending order, y ascending
+// inside a slice); keeps the entries with every index < n (S1 or S2 may be null: that term is not wanted)
 __global__ __launch_bounds__(256) void covar_small_reduce_kernel(const float *__restrict__ ws, u32 G, u32 n, u32 np,
                                                                 float *__restrict__ S1, float *__restrict__ S2,
                                                                 float *__restrict__ S3, int accumulate)
 {
-    __shared__ float part[16][16];
-    const u32 a = threadIdx.x & 15u, g = threadIdx.x >> 4;
+    __shared__ float part[64][4];
+    const u32 a = threadIdx.x & 3u, g = threadIdx.x >> 2;
     const u32 a2 = count_sym2<u32>(np), a3 = count_sym3<u32>(np), a4 = count_sym4<u32>(np), all = a2 + a3 + a4;
-    const u32 t = blockIdx.x * 16u + a;
+    const u32 t = blockIdx.x * 4u + a;
     float s = 0.f;
     if (t < all) {
-        const u32 per = (G + 15u) / 16u, y0 = min(G, g * per), y1 = min(G, y0 + per);
+        const u32 per = (G + 63u) / 64u, y0 = min(G, g * per), y1 = min(G, y0 + per);
+#pragma unroll 8
         for (u32 y = y0; y < y1; ++y) s += ws[(size_t)y * all + t];
     }
     part[g][a] = s;
@@ -89,7 +105,7 @@ __global__ __launch_bounds__(256) void covar_small_reduce_kernel(const float *__
     if (g != 0u || t >= all) return;
     s = 0.f;
 #pragma unroll
-    for (int q = 0; q < 16; ++q) s += part[q][a];
+    for (int q = 0; q < 64; ++q) s += part[q][a];
     u32 i, j, k, l;
     if (t < a2) {
         unrank_sym2<u32>(np, t, i, j);
@@ -353,7 +369,7 @@ st_status launch_covar_small(const float *X, int64_t N, int n, float *S1, float 
         if (rc != ST_OK) return rc;
     }
     const u32 all = cs_all(np);
-    hipLaunchKernelGGL(covar_small_reduce_kernel, dim3((all + 15u) / 16u), dim3(256), 0, s, wsf, G, (u32)n, np, S1, S2,
+    hipLaunchKernelGGL(covar_small_reduce_kernel, dim3((all + 3u) / 4u), dim3(256), 0, s, wsf, G, (u32)n, np, S1, S2,
                        S3, accumulate);
     return launch_status();
 }
