@@ -27,13 +27,15 @@
 // indices give exactly one kept accumulator each).  Tiles are grouped into wave blocks of 3 row
 // sets x 8 column sets = 24 MFMAs fed by 11 products per four samples (fourth moment, n = 64: 175
 // blocks, 4,200 tiles for the 2,994 that the unique entries would fill; the ragged edges weigh
-// less as G grows).  A workgroup of 8 waves owns 8 blocks and streams a slice of the samples
+// less as G grows; a block at the ragged end of a row list runs an instance of the kernel body that issues no
+// MFMAs for the row sets it does not have).  A workgroup of 8 waves owns 8 blocks and streams a slice of the samples
 // through a double-buffered LDS chunk stored as [group][step of 4 samples][sample slot]
 // [position], so that a wave reads either operand of a product, rotated or not, as 64
 // consecutive floats.  The sets are run-time data (a table built on the host per moment and G,
 // copied into the workspace): one code stream for all waves; per product two LDS reads and one
 // multiply (a single row set: one read).  Slice partials -> reduce kernel: keeps the positions above, adds the slices in
 // ascending order, sorts the indices and scatters through the closed-form rank.  No atomics.
+#include <algorithm>
 #include <cstring>
 #include <mutex>
 #include <vector>
@@ -75,6 +77,35 @@ static void mm_add(MMTable &t, const std::vector<int> &rows, const std::vector<i
             ++t.blocks;
         }
 }
+// The blocks in the order the kernel wants them: a block costs as many MFMAs as it has row sets in use, the eight
+// blocks of a workgroup run side by side until the slowest is done, and waves w and w+4 share a SIMD.  So the
+// blocks are sorted by their row sets in use, which makes the workgroups uniform (a workgroup of ragged blocks is
+// short instead of waiting for one full block), and inside a workgroup the k-th largest shares its SIMD with the
+// k-th smallest.  The reduce kernels read a tile's sets from the table and do not care about the order.
+static void mm_arrange(MMTable &t)
+{
+    auto used = [&](size_t b) {
+        int nr = 0;
+        for (int u = 0; u < MM_ROWS; ++u) nr += (t.spec[b * MM_SPECS + u] & (int)MM_VALID) ? 1 : 0;
+        return nr;
+    };
+    const size_t nb = t.blocks;
+    std::vector<size_t> order(nb);
+    for (size_t b = 0; b < nb; ++b) order[b] = b;
+    std::stable_sort(order.begin(), order.end(), [&](size_t x, size_t y) { return used(x) > used(y); });
+    std::vector<int> out(t.spec.size(), 0);
+    for (size_t w0 = 0; w0 < nb; w0 += MM_WAVES) {
+        const size_t cnt = nb - w0 < (size_t)MM_WAVES ? nb - w0 : (size_t)MM_WAVES;
+        for (size_t k = 0; k < cnt; ++k) {
+            // sorted position k of this workgroup -> wave: 0, 1, 2, 3 take the four largest, 7, 6, 5, 4 the rest
+            // (a last workgroup that is not full keeps its blocks in front: the reduce kernels walk `blocks` slots)
+            const size_t wave = cnt < (size_t)MM_WAVES || k < 4 ? k : (size_t)MM_WAVES + 3u - k;
+            const size_t src = order[w0 + k];
+            for (int u = 0; u < MM_SPECS; ++u) out[(w0 + wave) * MM_SPECS + u] = t.spec[src * MM_SPECS + u];
+        }
+    }
+    t.spec.swap(out);
+}
 static MMTable mm_build_table4(int G)
 {
     MMTable t;
@@ -113,6 +144,7 @@ static MMTable mm_build_table4(int G)
     }
     t.kinds = (t.blocks + MM_WAVES - 1) / MM_WAVES;
     t.spec.resize((size_t)t.kinds * MM_WAVES * MM_SPECS, 0);     // empty slots of the last workgroup kind
+    mm_arrange(t);
     return t;
 }
 static MMTable mm_build_table3(int G)
@@ -148,6 +180,7 @@ static MMTable mm_build_table3(int G)
             }
     t.kinds = (t.blocks + MM_WAVES - 1) / MM_WAVES;
     t.spec.resize((size_t)t.kinds * MM_WAVES * MM_SPECS, 0);
+    mm_arrange(t);
     return t;
 }
 // One table per moment and G, built at first use and kept for the life of the process, with a copy in pinned
@@ -256,42 +289,44 @@ __device__ __forceinline__ void mm_store_chunk(const f32x4 (&r)[MM_UNITS], const
     }
 }
 
-// partial (+)= accumulators, six tiles at a time (all 96 values in flight at once would not fit the registers)
+// partial (+)= accumulators, six (or four) tiles at a time (all 96 values in flight at once would not fit the registers)
+template <int NT>                                   // NT: tiles in use (the first NT accumulators)
 __device__ __forceinline__ void mm_flush(const f32x4 (&acc)[MM_TPB], float *dst, bool add)
 {
+    constexpr int STEP = NT % 6 == 0 ? 6 : 4;
     // the 96 addresses are formed here, from immediates, and not ahead of the chunk loop (where they would be
     // kept in registers the loop needs)
     ST_PIN_VGPR(dst);
 #pragma unroll
-    for (int t0 = 0; t0 < MM_TPB; t0 += 6) {
-        float old[6][4];
+    for (int t0 = 0; t0 < NT; t0 += STEP) {
+        float old[STEP][4];
         if (add) {
 #pragma unroll
-            for (int t = 0; t < 6; ++t)
+            for (int t = 0; t < STEP; ++t)
 #pragma unroll
                 for (int v = 0; v < 4; ++v) old[t][v] = dst[((t0 + t) * 4 + v) * 64];
         }
 #pragma unroll
-        for (int t = 0; t < 6; ++t)
+        for (int t = 0; t < STEP; ++t)
 #pragma unroll
             for (int v = 0; v < 4; ++v) dst[((t0 + t) * 4 + v) * 64] = add ? old[t][v] + acc[t0 + t][v] : acc[t0 + t][v];
         __builtin_amdgcn_sched_barrier(0);
     }
 }
 
-// STEPS K-steps (4 samples each) per staged chunk; V4: rows are read with 16-byte loads (n % 4 == 0)
-template <int STEPS, bool V4, bool SINGLE>       // SINGLE: the row sets are single sets (third moment): no product, one read
-__global__ __launch_bounds__(MM_THREADS) void moment_mfma_kernel(const float *__restrict__ X, int64_t N, u32 n, u32 G,
-                                                                 u32 kinds, int64_t slice,
-                                                                 const int *__restrict__ table, float *__restrict__ ws)
+// STEPS K-steps (4 samples each) per staged chunk; V4: rows are read with 16-byte loads (n % 4 == 0); SINGLE: the
+// row sets are single sets (third moment): no product, one read; NR: row sets this wave's block uses (the first NR
+// of its three: a block at the ragged end of a row list issues no MFMAs for the sets it does not have; every
+// instance runs the same chunk loop with the same barriers, so waves of one workgroup may run different ones).
+template <int STEPS, bool V4, bool SINGLE, int NR>
+__device__ __forceinline__ void mm_body(float *lds, const float *__restrict__ X, int64_t N, u32 n, u32 G, u32 kinds,
+                                        int64_t slice, const int *__restrict__ table, float *__restrict__ ws,
+                                        u32 tid, u32 wave, u32 block, u32 sl)
 {
-    extern __shared__ float lds[];                      // two chunks of (G + 1) * STEPS * 64 floats (last plane: ones)
     constexpr int CH = STEPS * 4;
     constexpr int FLUSH = MM_FLUSH_SAMPLES / CH;       // chunks per fp32 accumulation chain
-    const u32 tid = threadIdx.x, lane = tid & 63u;
-    const u32 wave = (u32)__builtin_amdgcn_readfirstlane((int)(tid >> 6));
-    const u32 kind = blockIdx.x % kinds, sl = blockIdx.x / kinds;
-    const u32 block = kind * (u32)MM_WAVES + wave;     // the last slots of the last kind may be empty
+    const u32 lane = tid & 63u;
+    auto used = [](int u) { return u >= MM_ROWS || u < NR; };      // spec u of the block is used by this instance
     const u32 chunk_f = (G + 1u) * (u32)STEPS * 64u;
     const int64_t s_begin = (int64_t)sl * slice, s_end = s_begin + slice < N ? s_begin + slice : N;
 
@@ -341,6 +376,7 @@ __global__ __launch_bounds__(MM_THREADS) void moment_mfma_kernel(const float *__
         float a[2][MM_SPECS], b[2][MM_SPECS];
 #pragma unroll
         for (int u = 0; u < MM_SPECS; ++u) {
+            if (!used(u)) continue;
             a[0][u] = base[oa[u]];
             if (!(SINGLE && u < MM_ROWS)) b[0][u] = base[ob[u]];
         }
@@ -354,6 +390,7 @@ __global__ __launch_bounds__(MM_THREADS) void moment_mfma_kernel(const float *__
             auto fetch = [&](int q0, int q1) {          // operands q of the next step: q < 11 first, else second
 #pragma unroll
                 for (int q = q0; q < q1; ++q) {
+                    if (!used(q < MM_SPECS ? q : q - MM_SPECS)) continue;
                     if (q < MM_SPECS) a[nxt][q] = base[(st + 1) * 64 + oa[q]];
                     else if (!(SINGLE && q - MM_SPECS < MM_ROWS)) b[nxt][q - MM_SPECS] = base[(st + 1) * 64 + ob[q - MM_SPECS]];
                 }
@@ -362,34 +399,60 @@ __global__ __launch_bounds__(MM_THREADS) void moment_mfma_kernel(const float *__
             __builtin_amdgcn_sched_barrier(0);
             float p[MM_SPECS];
 #pragma unroll
-            for (int u = 0; u < MM_SPECS; ++u) p[u] = (SINGLE && u < MM_ROWS) ? a[cur][u] : a[cur][u] * b[cur][u];
+            for (int u = 0; u < MM_SPECS; ++u)
+                if (used(u)) p[u] = (SINGLE && u < MM_ROWS) ? a[cur][u] : a[cur][u] * b[cur][u];
 #pragma unroll
             for (int t = 0; t < 8; ++t)
                 acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(p[t / MM_COLS], p[MM_ROWS + t % MM_COLS], acc[t], 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
             if (more) fetch(8, 15);
             __builtin_amdgcn_sched_barrier(0);
+            if constexpr (NR > 1) {
 #pragma unroll
-            for (int t = 8; t < 16; ++t)
-                acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(p[t / MM_COLS], p[MM_ROWS + t % MM_COLS], acc[t], 0, 0, 0);
+                for (int t = 8; t < 16; ++t)
+                    acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(p[t / MM_COLS], p[MM_ROWS + t % MM_COLS], acc[t], 0, 0, 0);
+            }
             __builtin_amdgcn_sched_barrier(0);
             if (more) fetch(15, 22);
             __builtin_amdgcn_sched_barrier(0);
+            if constexpr (NR > 2) {
 #pragma unroll
-            for (int t = 16; t < MM_TPB; ++t)
-                acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(p[t / MM_COLS], p[MM_ROWS + t % MM_COLS], acc[t], 0, 0, 0);
+                for (int t = 16; t < MM_TPB; ++t)
+                    acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(p[t / MM_COLS], p[MM_ROWS + t % MM_COLS], acc[t], 0, 0, 0);
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
         __syncthreads();
         // Long fp32 accumulation chains lose accuracy (1.2e-4 norm-wise after 180,000 samples): every FLUSH
         // chunks the accumulators are added to the wave's own partial in the workspace and cleared.
         if ((c + 1) % FLUSH == 0 && c + 1 < nchunks) {
-            mm_flush(acc, dst, c + 1 != FLUSH);
+            mm_flush<NR * MM_COLS>(acc, dst, c + 1 != FLUSH);
 #pragma unroll
             for (int t = 0; t < MM_TPB; ++t) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
         }
     }
-    mm_flush(acc, dst, nchunks > FLUSH);
+    mm_flush<NR * MM_COLS>(acc, dst, nchunks > FLUSH);
+}
+
+template <int STEPS, bool V4, bool SINGLE>
+__global__ __launch_bounds__(MM_THREADS) void moment_mfma_kernel(const float *__restrict__ X, int64_t N, u32 n, u32 G,
+                                                                 u32 kinds, int64_t slice,
+                                                                 const int *__restrict__ table, float *__restrict__ ws)
+{
+    extern __shared__ float lds[];                      // two chunks of (G + 1) * STEPS * 64 floats (last plane: ones)
+    const u32 tid = threadIdx.x;
+    const u32 wave = (u32)__builtin_amdgcn_readfirstlane((int)(tid >> 6));
+    const u32 kind = blockIdx.x % kinds, sl = blockIdx.x / kinds;
+    const u32 block = kind * (u32)MM_WAVES + wave;     // the last slots of the last kind may be empty
+    // row sets in use (the valid ones come first); an empty slot runs the one-row instance on sets that the reduce
+    // kernel passes over
+    u32 nr = 0;
+#pragma unroll
+    for (int u = 0; u < MM_ROWS; ++u) nr += ((u32)table[(size_t)block * MM_SPECS + u] & MM_VALID) ? 1u : 0u;
+    nr = (u32)__builtin_amdgcn_readfirstlane((int)nr);
+    if (nr >= 3u) mm_body<STEPS, V4, SINGLE, 3>(lds, X, N, n, G, kinds, slice, table, ws, tid, wave, block, sl);
+    else if (nr == 2u) mm_body<STEPS, V4, SINGLE, 2>(lds, X, N, n, G, kinds, slice, table, ws, tid, wave, block, sl);
+    else mm_body<STEPS, V4, SINGLE, 1>(lds, X, N, n, G, kinds, slice, table, ws, tid, wave, block, sl);
 }
 
 __device__ __forceinline__ u32 mm_cyc(u32 x, u32 y)
