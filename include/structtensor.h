@@ -185,7 +185,9 @@ st_status st_moment3_sym(const float *X, int64_t N, int n, float *Sc, int accumu
  * symmetry).  Arguments as for st_moment3_sym; Sc has n(n+1)/2 entries.  Up to
  * 1024 features the sum runs on the matrix cores; the workspace holds slice
  * partials (about 50 MB; more only for N in the tens of millions at several
- * hundred features: a slice ends after 131,072 samples). */
+ * hundred features: a slice ends after 131,072 samples).  Between 65 and 1024
+ * features N is limited to 2^31 - 1 (ST_ERR_UNSUPPORTED beyond; such an X would
+ * be more than half a terabyte). */
 st_status st_moment2_sym(const float *X, int64_t N, int n, float *Sc, int accumulate,
                          void *ws, size_t ws_bytes, void *stream);
 

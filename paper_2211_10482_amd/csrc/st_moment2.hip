@@ -556,7 +556,10 @@ __host__ __device__ inline void m2w_task(u32 nb, u32 nbb, u32 task, u32 &sa, u32
 template <int MODE>
 __device__ __forceinline__ f32x4 m2w_load(const float *__restrict__ X, int64_t s, int64_t s_end, u32 n, u32 c0, u32 roq)
 {
-    const int64_t rows = s_end - s;                                          // may be <= 0
+    // (32-bit on purpose: the scalar unit has no 64-bit ordered compare, so the same tests on an int64_t are made
+    // by the vector ALU, about fifteen vector instructions per quad that the MFMAs then wait for; the launcher
+    // admits fewer than 2^31 samples)
+    const int rows = (int)(s_end - s);                                       // may be <= 0
     const float *base = X + (rows > 0 ? s : s_end - 1) * (int64_t)n;        // wave-uniform
     const u32 qm = rows >= 4 ? 3u : rows > 0 ? (u32)rows - 1u : 0u;          // last row of the quad that exists
     const u32 ro = min(roq, qm * n);
@@ -587,10 +590,10 @@ __device__ __forceinline__ f32x4 m2w_load(const float *__restrict__ X, int64_t s
 // 0 * inf is not 0).  Columns >= n need no mask at all: they only reach accumulators that the reduce kernel drops.
 __device__ __forceinline__ f32x4 m2w_mask(f32x4 v, int64_t s, int64_t s_end, u32 q)
 {
-    const int64_t rows = s_end - s;
+    const int rows = (int)(s_end - s);
     if (rows < 4) {                                                          // wave-uniform, the end of a slice only
         ST_PIN_VGPR(v);                                                      // a branch, not four selects per quad
-        const bool row_ok = (int64_t)q < rows;
+        const bool row_ok = (int)q < rows;
 #pragma unroll
         for (u32 g = 0; g < 4; ++g) v[g] = row_ok ? v[g] : 0.f;
     }
@@ -804,6 +807,7 @@ size_t moment2_workspace(int64_t N, int n)
     }
     if (n <= 64) return (size_t)m2_groups(N) * M2_ACC * sizeof(float);
     if (m2w_applies(n)) {
+        if (N > 0x7fffffff) return ST_ERR_UNSUPPORTED;        // the kernel counts the rows left in a slice in 32 bits
         const M2WPlan p = m2w_plan(N, n);
         return (size_t)p.S * p.ntasks * M2W_ACC * sizeof(float);
     }
