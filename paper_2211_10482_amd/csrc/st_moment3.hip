@@ -225,6 +225,24 @@ __device__ __forceinline__ void store_chunk(const f32x4 (&r)[M3_LPT], float *__r
     }
 }
 
+// The same two steps for a chunk that lies wholly inside the slice, 64 features: every address is a wave-uniform
+// base plus an offset the lane keeps for the whole kernel, nothing is masked (the general forms above cost about
+// fifty vector instructions per chunk and wave in 64-bit index arithmetic, compares and selects, and on this chip
+// those are not hidden behind the MFMAs).
+__device__ __forceinline__ void load_whole_chunk(f32x4 (&r)[M3_LPT], const float *__restrict__ chunk, u32 tid)
+{
+#pragma unroll
+    for (int k = 0; k < M3_LPT; ++k) {
+        const float4 t = *reinterpret_cast<const float4 *>(chunk + 4u * (tid + (u32)M3_THREADS * k));
+        r[k] = (f32x4){t.x, t.y, t.z, t.w};
+    }
+}
+__device__ __forceinline__ void store_whole_chunk(const f32x4 (&r)[M3_LPT], float *__restrict__ buf, u32 tid)
+{
+#pragma unroll
+    for (int k = 0; k < M3_LPT; ++k) *reinterpret_cast<f32x4 *>(buf + 4u * (tid + (u32)M3_THREADS * k)) = r[k];
+}
+
 template <int W>
 __device__ __forceinline__ void m3_step(f32x4 (&acc)[M3_TPW], const f32x4 &xa, bool upper)
 {
@@ -277,13 +295,20 @@ __device__ __forceinline__ void m3_wave(const float *__restrict__ X, int64_t s_b
 
     // lane (m, q) reads X(s + q, 4m .. 4m+3): component g is the A operand of group g
     const float *mine = &xs[0][0] + lane * 4u;
-    for (int64_t c = 0; c < nchunks; ++c) {
+    // One chunk: the registers hold chunk c+1: park it in the other buffer (its readers finished before the
+    // barrier that ended the previous iteration), put chunk c+2 in flight, then the MFMAs of chunk c.
+    // WHOLE: chunks c+1 and c+2 exist and lie wholly inside the slice (all iterations but the last three): the
+    // staging has no conditions, no masks and no 64-bit index arithmetic per lane.
+    auto chunk = [&](int64_t c, auto whole) {
+        constexpr bool WHOLE = FULL && decltype(whole)::value;
         const u32 cb = (u32)(c & 1);
-        // registers hold chunk c+1: park it in the other buffer (its readers finished
-        // before the barrier that ended the previous iteration), then put chunk c+2
-        // in flight
-        if (c + 1 < nchunks) store_chunk<FULL>(r, xs[cb ^ 1u], s_begin + (c + 1) * M3_CH, s_end, n, tid);
-        if (c + 2 < nchunks) load_chunk<FULL>(r, X, s_begin + (c + 2) * M3_CH, s_end, n, tid);
+        if constexpr (WHOLE) {
+            store_whole_chunk(r, xs[cb ^ 1u], tid);
+            load_whole_chunk(r, X + (s_begin + (c + 2) * M3_CH) * 64, tid);
+        } else {
+            if (c + 1 < nchunks) store_chunk<FULL>(r, xs[cb ^ 1u], s_begin + (c + 1) * M3_CH, s_end, n, tid);
+            if (c + 2 < nchunks) load_chunk<FULL>(r, X, s_begin + (c + 2) * M3_CH, s_end, n, tid);
+        }
         __builtin_amdgcn_sched_barrier(0);
         const float *src = mine + cb * (M3_CH * 64);
         f32x4 xa[4];
@@ -309,7 +334,11 @@ __device__ __forceinline__ void m3_wave(const float *__restrict__ X, int64_t s_b
         }
         __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
-    }
+    };
+    int64_t c = 0;
+    if constexpr (FULL)
+        for (; c + 3 < nchunks; ++c) chunk(c, std::true_type{});
+    for (; c < nchunks; ++c) chunk(c, std::false_type{});
 
     float *dst = part + (size_t)W * M3_TPW * 256 + lane;
 #pragma unroll
