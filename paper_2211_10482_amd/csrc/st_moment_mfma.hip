@@ -37,6 +37,7 @@
 // ascending order, sorts the indices and scatters through the closed-form rank.  No atomics.
 #include <algorithm>
 #include <cstring>
+#include <type_traits>
 #include <mutex>
 #include <vector>
 
@@ -363,14 +364,24 @@ __device__ __forceinline__ void mm_body(float *lds, const float *__restrict__ X,
     if (nchunks > 1) mm_load_chunk<STEPS, V4>(r, stg, X + (s_begin + CH) * (int64_t)n, rows_of(1), n, G, wave, lane);
     __syncthreads();
 
-    for (int64_t c = 0; c < nchunks; ++c) {
+    // One chunk.  WHOLE: chunks c+1 and c+2 exist and are whole (every iteration but the last three of a slice):
+    // their staging is compiled for a full row count and without the tests on c, which leaves no conditional
+    // definitions of the staging registers (they cost a register copy each per chunk) and, for n a multiple of 16,
+    // no per-lane index arithmetic; on this chip none of that would be hidden behind the MFMAs.
+    auto chunk = [&](int64_t c, auto whole) {
+        constexpr bool WHOLE = decltype(whole)::value;
         const u32 cb = (u32)(c & 1);
         // registers hold chunk c+1: park it in the other buffer (its readers finished before the
         // barrier that ended the previous iteration), then put chunk c+2 in flight
-        if (c + 1 < nchunks)
-            mm_store_chunk<STEPS>(r, stg, lds + (cb ^ 1u) * chunk_f, rows_of(c + 1), n, G, wave, lane, padded);
-        if (c + 2 < nchunks)
-            mm_load_chunk<STEPS, V4>(r, stg, X + (s_begin + (c + 2) * CH) * (int64_t)n, rows_of(c + 2), n, G, wave, lane);
+        if constexpr (WHOLE) {
+            mm_store_chunk<STEPS>(r, stg, lds + (cb ^ 1u) * chunk_f, (u32)CH, n, G, wave, lane, padded);
+            mm_load_chunk<STEPS, V4>(r, stg, X + (s_begin + (c + 2) * CH) * (int64_t)n, (u32)CH, n, G, wave, lane);
+        } else {
+            if (c + 1 < nchunks)
+                mm_store_chunk<STEPS>(r, stg, lds + (cb ^ 1u) * chunk_f, rows_of(c + 1), n, G, wave, lane, padded);
+            if (c + 2 < nchunks)
+                mm_load_chunk<STEPS, V4>(r, stg, X + (s_begin + (c + 2) * CH) * (int64_t)n, rows_of(c + 2), n, G, wave, lane);
+        }
         __builtin_amdgcn_sched_barrier(0);
         const float *base = lds + cb * chunk_f;
         float a[2][MM_SPECS], b[2][MM_SPECS];
@@ -430,7 +441,10 @@ __device__ __forceinline__ void mm_body(float *lds, const float *__restrict__ X,
 #pragma unroll
             for (int t = 0; t < MM_TPB; ++t) acc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
         }
-    }
+    };
+    int64_t c = 0;
+    for (; c + 3 < nchunks; ++c) chunk(c, std::true_type{});
+    for (; c < nchunks; ++c) chunk(c, std::false_type{});
     mm_flush<NR * MM_COLS>(acc, dst, nchunks > FLUSH);
 }
 
